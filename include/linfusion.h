@@ -1,0 +1,139 @@
+/*
+ * linfusion.h -- C ABI of the MI355X (gfx950) LinFusion token mixer.
+ *
+ * The operation is the normalized, non-causal generalized linear attention that LinFusion
+ * substitutes for self-attention (Sec. 2.3 normalization, Eq. 5; Sec. 2.4 non-causality,
+ * Prop. 2 and Prop. 3: Y = f'(X) g'(X)^T X with rows normalised to sum to one).  Per
+ * (batch b, head h), with Q, K, V in R^{N x d}, a non-negative elementwise feature map phi
+ * applied to Q and K, and eps >= 0:
+ *
+ *     S     = sum_j phi(k_j)^T v_j          (d x d state, g'(X)^T X of Prop. 2)
+ *     z     = sum_j phi(k_j)                (normalizer state, non-causal Z of Eq. 5)
+ *     out_i = phi(q_i) S / (phi(q_i) . z + eps)
+ *
+ * Every step (feature map, state reduction, combine, apply, normalize) runs in this
+ * library's own HIP kernels.  There is no CPU fallback: on a machine without a gfx950
+ * device every compute entry point returns LINFUSION_ERR_DEVICE.
+ *
+ * Conventions shared by all entry points
+ *   - q, k, v, out: DEVICE pointers to contiguous [B, H, N, d] tensors, d fastest, all of the
+ *     same element type; `out` has the element type of the inputs.  Base pointers must be
+ *     16-byte aligned.  `out` must not overlap k or v; out == q (exact alias) is allowed.
+ *   - The caller owns every buffer and keeps it alive until the work enqueued on `stream`
+ *     has completed.  Calls are asynchronous: they enqueue on `stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream) and return without synchronising.
+ *   - Results are run-to-run bit-identical for identical arguments (fixed-order reductions,
+ *     no floating-point atomics).
+ *   - Return value: LINFUSION_OK or a negative LINFUSION_ERR_* code.  All argument checks
+ *     happen before anything is enqueued.  Nothing is printed, nothing aborts.
+ *   - Supported head widths: d in {8, 16, 24, 32, 40, 48, 56, 64}.
+ */
+#ifndef LINFUSION_H_
+#define LINFUSION_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types of q, k, v, out */
+#define LINFUSION_DTYPE_F32 0
+#define LINFUSION_DTYPE_F16 1
+#define LINFUSION_DTYPE_BF16 2
+
+/* feature maps phi (Sec. 2.3: a non-negative activation on the key / query branches) */
+#define LINFUSION_PHI_ELU_PLUS_ONE 0 /* x > 0 ? x + 1 : exp(x)   (default) */
+#define LINFUSION_PHI_RELU 1         /* max(x, 0)                 (test aid) */
+#define LINFUSION_PHI_IDENTITY 2     /* x; caller guarantees q, k >= 0 (test aid) */
+
+/* flags for linfusion_attn_fwd_ex */
+#define LINFUSION_FLAG_NONE 0u
+#define LINFUSION_FLAG_UNNORMALIZED 1u /* out_i = phi(q_i) S, the un-normalized arm of Tab. 2 */
+#define LINFUSION_FLAG_FORCE_SPLIT 2u  /* always take the three-kernel split-N path */
+#define LINFUSION_FLAG_FORCE_FUSED 4u  /* always take the single-launch small-N path */
+
+#define LINFUSION_OK 0
+#define LINFUSION_ERR_INVALID (-1)     /* NULL pointer, B/H/N/d <= 0, eps < 0 or NaN, bad flags */
+#define LINFUSION_ERR_UNSUPPORTED (-2) /* d, dtype or feature_map outside the supported sets */
+#define LINFUSION_ERR_MISALIGNED (-3)  /* a tensor or workspace pointer is not 16-byte aligned */
+#define LINFUSION_ERR_WORKSPACE (-4)   /* workspace_bytes below linfusion_attn_workspace_bytes() */
+#define LINFUSION_ERR_HIP (-5)         /* a HIP runtime call or kernel launch failed */
+#define LINFUSION_ERR_DEVICE (-6)      /* no HIP device, or the current device is not gfx950 */
+#define LINFUSION_ERR_OVERLAP (-7)     /* out overlaps k or v, or partially overlaps q */
+
+/*
+ * General entry point: the whole hot path (feature map -> split-N state reduction ->
+ * deterministic combine -> apply + normalize) for one [B, H, N, d] problem.
+ *
+ *   dtype            LINFUSION_DTYPE_*; accumulation is fp32 for every dtype.
+ *   feature_map      LINFUSION_PHI_*.
+ *   eps              added once to the denominator phi(q_i).z, after the dot product.
+ *   flags            LINFUSION_FLAG_* (bitwise or).
+ *   workspace        DEVICE scratch of at least linfusion_attn_workspace_bytes(...) bytes,
+ *                    16-byte aligned, owned by the caller, contents undefined before and after.
+ *                    Calls that share a workspace must be ordered on one stream.
+ *   stream           hipStream_t (NULL = default stream).
+ *
+ * Never allocates, never synchronises.
+ */
+int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out,
+                          int B, int H, long long N, int d,
+                          int dtype, int feature_map, float eps, unsigned flags,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Bytes of device scratch linfusion_attn_fwd_ex needs for this shape.  Pure host function of
+ * its arguments (no device query); returns 0 for arguments the forward call would reject.
+ */
+size_t linfusion_attn_workspace_bytes(int B, int H, long long N, int d, int dtype);
+
+/*
+ * Convenience entry points with the signature of the method's token mixer
+ * (q, k, v -> out for phi, eps).  Element type: fp16 for linfusion_attn_fwd and _f16, bf16 for
+ * _bf16, fp32 for _f32.  They use a library-owned scratch buffer per device that is allocated
+ * with hipMalloc on first use (and re-allocated when a later call needs more), so the first
+ * call per device -- and any call that grows the buffer -- synchronises that device.  Calls
+ * on one device must be issued from one thread at a time and ordered on one stream.
+ */
+int linfusion_attn_fwd(const void* q, const void* k, const void* v, void* out,
+                       int B, int H, long long N, int d, int feature_map, float eps, void* stream);
+int linfusion_attn_fwd_f16(const void* q, const void* k, const void* v, void* out,
+                           int B, int H, long long N, int d, int feature_map, float eps, void* stream);
+int linfusion_attn_fwd_bf16(const void* q, const void* k, const void* v, void* out,
+                            int B, int H, long long N, int d, int feature_map, float eps, void* stream);
+int linfusion_attn_fwd_f32(const void* q, const void* k, const void* v, void* out,
+                           int B, int H, long long N, int d, int feature_map, float eps, void* stream);
+
+/*
+ * State-only entry point (the reduction half of Prop. 2; also what an N-sharded deployment
+ * exchanges between devices, Sec. 3.3 "constant communication cost"): writes, per (b, h),
+ * the fp32 state S as [d][d] row-major (row = feature index of phi(K), column = value
+ * channel) followed by z as [d], i.e. state_out is a DEVICE buffer of B*H*(d*d+d) floats.
+ * Same workspace contract as linfusion_attn_fwd_ex.
+ */
+int linfusion_attn_state(const void* k, const void* v, float* state_out,
+                         int B, int H, long long N, int d, int dtype, int feature_map,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Frees the library-owned scratch buffers (synchronises).  Optional; safe to call twice. */
+void linfusion_release(void);
+
+/* Static string for a status code. */
+const char* linfusion_status_string(int status);
+
+/* major * 10000 + minor * 100 + patch */
+int linfusion_version(void);
+
+/*
+ * Introspection for benchmarks and tests (host only, no device work): the launch plan the
+ * forward call will use for this shape.  plan[0] = path (0 = split-N three-kernel path,
+ * 1 = fused single launch), plan[1] = state-reduction workgroups per head, plan[2] = apply
+ * workgroups per head, plan[3] = tokens per tile.  Returns LINFUSION_OK or an error code.
+ */
+int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned flags, int plan[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LINFUSION_H_ */

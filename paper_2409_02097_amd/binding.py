@@ -1,0 +1,166 @@
+"""ctypes binding of include/linfusion.h: same names, argument marshalling only.
+
+Tensors are torch tensors used purely as device-memory handles (`data_ptr()`), and the stream
+is torch's current HIP stream unless one is given.  Every step of the method runs inside the
+shared library; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "liblinfusion.so"
+
+DTYPE_F32, DTYPE_F16, DTYPE_BF16 = 0, 1, 2
+PHI_ELU_PLUS_ONE, PHI_RELU, PHI_IDENTITY = 0, 1, 2
+FLAG_NONE, FLAG_UNNORMALIZED, FLAG_FORCE_SPLIT, FLAG_FORCE_FUSED = 0, 1, 2, 4
+
+_lib = None
+
+
+class LinFusionError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({linfusion_status_string(status)})")
+        self.status = status
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def library() -> ctypes.CDLL:
+    """Loads the built shared library; builds it first if it has never been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(path)
+    vp, i32, i64, f32, u32, sz = (ctypes.c_void_p, ctypes.c_int, ctypes.c_longlong, ctypes.c_float,
+                                  ctypes.c_uint, ctypes.c_size_t)
+    lib.linfusion_attn_fwd_ex.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp]
+    lib.linfusion_attn_fwd_ex.restype = i32
+    lib.linfusion_attn_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
+    lib.linfusion_attn_workspace_bytes.restype = sz
+    for name in ("linfusion_attn_fwd", "linfusion_attn_fwd_f16", "linfusion_attn_fwd_bf16", "linfusion_attn_fwd_f32"):
+        fn = getattr(lib, name)
+        fn.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, f32, vp]
+        fn.restype = i32
+    lib.linfusion_attn_state.argtypes = [vp, vp, vp, i32, i32, i64, i32, i32, i32, vp, sz, vp]
+    lib.linfusion_attn_state.restype = i32
+    lib.linfusion_release.argtypes = []
+    lib.linfusion_release.restype = None
+    lib.linfusion_status_string.argtypes = [i32]
+    lib.linfusion_status_string.restype = ctypes.c_char_p
+    lib.linfusion_version.argtypes = []
+    lib.linfusion_version.restype = i32
+    lib.linfusion_attn_plan.argtypes = [i32, i32, i64, i32, i32, u32, ctypes.POINTER(ctypes.c_int * 4)]
+    lib.linfusion_attn_plan.restype = i32
+    _lib = lib
+    return lib
+
+
+def _dtype_code(t) -> int:
+    import torch
+    return {torch.float32: DTYPE_F32, torch.float16: DTYPE_F16, torch.bfloat16: DTYPE_BF16}[t.dtype]
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _check_layout(*tensors):
+    shape = tensors[0].shape
+    for t in tensors:
+        if t.dim() != 4 or t.shape != shape or not t.is_contiguous() or t.dtype != tensors[0].dtype:
+            raise ValueError("q, k, v, out must be contiguous [B, H, N, d] tensors of one dtype and shape")
+        if not t.is_cuda:
+            raise ValueError("tensors must live in device memory")
+    return shape
+
+
+def linfusion_status_string(status: int) -> str:
+    return library().linfusion_status_string(int(status)).decode()
+
+
+def linfusion_version() -> int:
+    return library().linfusion_version()
+
+
+def linfusion_attn_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int) -> int:
+    return int(library().linfusion_attn_workspace_bytes(B, H, N, d, dtype))
+
+
+def linfusion_attn_plan(B: int, H: int, N: int, d: int, dtype: int, flags: int = 0):
+    arr = (ctypes.c_int * 4)()
+    rc = library().linfusion_attn_plan(B, H, N, d, dtype, flags, ctypes.byref(arr))
+    if rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_plan")
+    return {"path": arr[0], "reduce_wgs_per_head": arr[1], "apply_wgs_per_head": arr[2], "tile_tokens": arr[3]}
+
+
+def linfusion_attn_fwd_ex(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6,
+                          flags: int = FLAG_NONE, workspace=None, stream=None, check: bool = True) -> int:
+    """out <- mixer(q, k, v).  `workspace`: a uint8 device tensor of at least
+    linfusion_attn_workspace_bytes(...) bytes (the caller allocates it)."""
+    B, H, N, d = _check_layout(q, k, v, out)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = library().linfusion_attn_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d,
+                                         _dtype_code(q), feature_map, eps, flags, ws_ptr, ws_bytes,
+                                         _stream_ptr(stream))
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_fwd_ex")
+    return rc
+
+
+def _fwd_owned(name, q, k, v, out, feature_map, eps, stream, check):
+    B, H, N, d = _check_layout(q, k, v, out)
+    rc = getattr(library(), name)(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d,
+                                  feature_map, eps, _stream_ptr(stream))
+    if check and rc != 0:
+        raise LinFusionError(rc, name)
+    return rc
+
+
+def linfusion_attn_fwd(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6, stream=None,
+                       check: bool = True) -> int:
+    return _fwd_owned("linfusion_attn_fwd", q, k, v, out, feature_map, eps, stream, check)
+
+
+def linfusion_attn_fwd_f16(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6, stream=None,
+                           check: bool = True) -> int:
+    return _fwd_owned("linfusion_attn_fwd_f16", q, k, v, out, feature_map, eps, stream, check)
+
+
+def linfusion_attn_fwd_bf16(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6, stream=None,
+                            check: bool = True) -> int:
+    return _fwd_owned("linfusion_attn_fwd_bf16", q, k, v, out, feature_map, eps, stream, check)
+
+
+def linfusion_attn_fwd_f32(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6, stream=None,
+                           check: bool = True) -> int:
+    return _fwd_owned("linfusion_attn_fwd_f32", q, k, v, out, feature_map, eps, stream, check)
+
+
+def linfusion_attn_state(k, v, state_out, feature_map: int = PHI_ELU_PLUS_ONE, workspace=None, stream=None,
+                         check: bool = True) -> int:
+    """state_out <- per head [d*d + d] fp32: S row-major then z."""
+    B, H, N, d = _check_layout(k, v)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = library().linfusion_attn_state(k.data_ptr(), v.data_ptr(), state_out.data_ptr(), B, H, N, d,
+                                        _dtype_code(k), feature_map, ws_ptr, ws_bytes, _stream_ptr(stream))
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_state")
+    return rc
+
+
+def linfusion_release() -> None:
+    library().linfusion_release()

@@ -1,0 +1,145 @@
+// Shared device-side helpers for the gfx950 LinFusion kernels: vector types, 16-bit
+// conversions, the feature map phi (Sec. 2.3: non-negative activation on Q and K), and the
+// shape constants that the state-reduction, combine and apply kernels must agree on.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lf {
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kPhiEluPlusOne = 0;
+constexpr int kPhiRelu = 1;
+constexpr int kPhiIdentity = 2;
+
+struct F16 {};   // tag: IEEE binary16 storage
+struct BF16 {};  // tag: bfloat16 storage
+
+#define LF_DEV __device__ __forceinline__
+#define LF_LDS __attribute__((address_space(3)))
+
+// ---- feature map -------------------------------------------------------------------------
+// elu(x)+1 = x+1 for x > 0, exp(x) otherwise.  exp(x) = 2^(x*log2 e) on the hardware exp2
+// unit; `Precise` adds the rounding error of the product back as a first-order correction
+// (used on the fp32 path, whose tolerance is 1e-5).
+template <int FM, bool Precise = false>
+LF_DEV float phi(float x) {
+  if constexpr (FM == kPhiEluPlusOne) {
+    constexpr float kLog2e = 1.44269504088896340736f;
+    float t = x * kLog2e;
+    float e = __builtin_amdgcn_exp2f(t);
+    if constexpr (Precise) {
+      // t_err = x*log2e - t (exactly, via fma) plus the part of log2e that fp32 drops.
+      float terr = __builtin_fmaf(x, kLog2e, -t) + x * 1.92596299112661746e-8f;
+      e = __builtin_fmaf(e, terr * 0.69314718055994530942f, e);
+    }
+    return x > 0.0f ? x + 1.0f : e;
+  } else if constexpr (FM == kPhiRelu) {
+    return x > 0.0f ? x : 0.0f;   // NaN maps to 0 like fmax(x, 0)
+  } else {
+    return x;
+  }
+}
+
+// ---- 16-bit storage <-> fp32 ----------------------------------------------------------------
+template <typename T> LF_DEV void unpack2(uint32_t w, float& lo, float& hi);
+template <> LF_DEV void unpack2<F16>(uint32_t w, float& lo, float& hi) {
+  f16x2 h = __builtin_bit_cast(f16x2, w);
+  lo = (float)h[0];
+  hi = (float)h[1];
+}
+template <> LF_DEV void unpack2<BF16>(uint32_t w, float& lo, float& hi) {
+  lo = __builtin_bit_cast(float, w << 16);
+  hi = __builtin_bit_cast(float, w & 0xffff0000u);
+}
+
+// round-to-nearest-even pack of two floats into one 32-bit word (element 0 in the low half)
+template <typename T> LF_DEV uint32_t pack2(float lo, float hi);
+template <> LF_DEV uint32_t pack2<F16>(float lo, float hi) {
+  f16x2 h = {(_Float16)lo, (_Float16)hi};
+  return __builtin_bit_cast(uint32_t, h);
+}
+template <> LF_DEV uint32_t pack2<BF16>(float lo, float hi) {
+  bf16x2 h = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, h);
+}
+
+// value of a packed pair after rounding, back in fp32 (for hi/lo operand splitting)
+template <typename T> LF_DEV void pack2_split(float lo, float hi, uint32_t& w_hi, uint32_t& w_lo) {
+  w_hi = pack2<T>(lo, hi);
+  float rl, rh;
+  unpack2<T>(w_hi, rl, rh);
+  w_lo = pack2<T>(lo - rl, hi - rh);
+}
+
+// ---- matrix-core wrappers (operands carried as raw 128-bit words) ---------------------------
+template <typename T> LF_DEV f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c);
+template <> LF_DEV f32x4 mfma_16x16x32<F16>(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <> LF_DEV f32x4 mfma_16x16x32<BF16>(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+template <typename T> LF_DEV f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c);
+template <> LF_DEV f32x16 mfma_32x32x16<F16>(u32x4 a, u32x4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+template <> LF_DEV f32x16 mfma_32x32x16<BF16>(u32x4 a, u32x4 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// LDS transposing read: the 16 lanes of a group each name 8 bytes (4 x 16-bit, lane i = row
+// i/4, columns 4*(i%4)..+3 of a 4 x 16 block); afterwards lane j of the group holds column j
+// of the 4 rows.  Two of them give the 8 contraction-index elements a 16x16x32 operand needs.
+LF_DEV u32x2 lds_read_tr16(const uint16_t* p) {
+  s16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LF_LDS s16x4*)(p));
+  return __builtin_bit_cast(u32x2, r);
+}
+
+// streaming 128-bit global load / store (non-temporal: the tensors are touched once)
+LF_DEV u32x4 ld_stream(const u32x4* p) { return __builtin_nontemporal_load(p); }
+LF_DEV void st_stream(u32x4* p, u32x4 v) { __builtin_nontemporal_store(v, p); }
+LF_DEV void st_stream(u32x2* p, u32x2 v) { __builtin_nontemporal_store(v, p); }
+
+// ---- shape constants of the 16-bit path ---------------------------------------------------
+// State reduction tiles the d x d state in 16 x 16 blocks; apply tiles the output in 32-row
+// blocks with the two normalizer rows (z hi, z lo) appended after each half of the channels.
+template <int D> struct Shape16 {
+  static_assert(D % 8 == 0 && D >= 8 && D <= 64, "head width must be a multiple of 8 up to 64");
+  static constexpr int kChunksPerRow = D / 8;          // 16-byte chunks per token row
+  static constexpr int kMT = (D + 15) / 16;            // 16-wide tiles across d
+  static constexpr int kDP = kMT * 16;
+  static constexpr bool kSpareCol = (D % 16) != 0;     // a free padded column carries the ones
+  // apply: k-steps of 16 channels (lanes 0-31 supply the first 8, lanes 32-63 the second 8)
+  static constexpr int kKS = (kChunksPerRow + 1) / 2;
+  static constexpr int kHalf = D / 2;                  // output channels held by one half-wave
+  static constexpr int kMT2 = (kHalf + 2 + 15) / 16;   // 32-row output tiles incl. normalizer rows
+  static constexpr int kFragsPerSplit = kMT2 * kKS;    // 1 KiB operand fragments per hi/lo level
+};
+
+// header of the packed per-head state consumed by the apply kernel
+struct PackHeader {
+  float c1;      // alpha_z / alpha_S (un-normalized: 1 / alpha_S)
+  float eps_s;   // eps * alpha_z
+  float pad[2];
+};
+
+template <typename T> struct NSplit;                 // operand levels needed to hold an fp32 value
+template <> struct NSplit<F16> { static constexpr int value = 1; };
+template <> struct NSplit<BF16> { static constexpr int value = 2; };
+
+template <typename T> struct OneBits;                // bit pattern of 1.0 in the storage type
+template <> struct OneBits<F16> { static constexpr uint16_t value = 0x3C00; };
+template <> struct OneBits<BF16> { static constexpr uint16_t value = 0x3F80; };
+
+}  // namespace lf

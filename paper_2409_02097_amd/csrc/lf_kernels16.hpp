@@ -1,0 +1,462 @@
+// fp16 / bf16 kernels of the split-N path:
+//   state_reduce16  S_p = sum_{j in chunk} phi(k_j)^T v_j,  z_p = sum phi(k_j)       (Prop. 2: g'(X)^T X)
+//   combine_pack16  S = sum_p S_p, z = sum_p z_p in a fixed order; rescale; pack for apply
+//   apply16         out_i = phi(q_i) S / (phi(q_i).z + eps)                            (Eq. 5 normalizer)
+#pragma once
+#include "lf_common.hpp"
+
+namespace lf {
+
+constexpr int kWavesPerWG = 4;
+constexpr int kThreads = 64 * kWavesPerWG;
+constexpr int kTile = 32;   // tokens per tile, both in the reduction (one 16x16x32 k-step) and in apply
+
+// ==========================================================================================
+// State reduction.  grid = (splits, B*H), block = 256.  Workgroup (split, bh) owns the tiles
+// [split*tiles_per_split, (split+1)*tiles_per_split) of head bh; its four waves take them
+// round-robin and each wave streams on its own: global -> registers (128-bit, coalesced over
+// the contiguous tile) -> phi on K -> wave-private LDS tile -> transposing LDS reads give the
+// token-major operands -> 16x16x32 matrix-core products accumulate S (and z through a column
+// of ones) in fp32.  No workgroup barrier inside the stream loop.
+// Partial written per workgroup: S as [D][D] row-major then z as [D], fp32.
+// ==========================================================================================
+template <int D> struct Reduce16Cfg {
+  using Sh = Shape16<D>;
+  // LDS row stride in 16-bit elements: padded so that the 4 rows x 32 bytes a 16-lane group
+  // reads with one transposing load fall in distinct banks.
+  static constexpr int kRS = Sh::kDP + (Sh::kSpareCol ? 0 : 8);
+  static constexpr int kTileElems = kTile * kRS;
+  static constexpr int kChunks = kTile * Sh::kChunksPerRow;   // 16-byte chunks per tile
+  static constexpr int kNL = (kChunks + 63) / 64;              // loads per lane per tensor
+};
+
+template <typename T, int D>
+constexpr int reduce16_lds_bytes() {
+  // per wave: NSplit tiles of phi(K) + one of V; reused by the cross-wave reduction
+  int tiles = (NSplit<T>::value + 1) * Reduce16Cfg<D>::kTileElems * 2 * kWavesPerWG;
+  int red = (D * D + D) * 4;
+  return tiles > red ? tiles : red;
+}
+
+template <typename T, int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* __restrict__ partials,
+               long long N, int tiles_per_split) {
+  using Sh = Shape16<D>;
+  using Cfg = Reduce16Cfg<D>;
+  constexpr int NS = NSplit<T>::value;
+  constexpr int RS = Cfg::kRS, NL = Cfg::kNL, CPR = Sh::kChunksPerRow, MT = Sh::kMT;
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int split = blockIdx.x;
+  const long long bh = blockIdx.y;
+
+  uint16_t* wbase = reinterpret_cast<uint16_t*>(smem) + wave * (NS + 1) * Cfg::kTileElems;
+  uint16_t* ldsP[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) ldsP[s] = wbase + s * Cfg::kTileElems;
+  uint16_t* ldsV = wbase + NS * Cfg::kTileElems;
+
+  // one-time fill of the wave's tiles: phi(K) pad columns zero; V pad columns zero except the
+  // ones column at index D (when a spare column exists) which makes z fall out of the products
+  for (int i = lane; i < Cfg::kTileElems; i += 64) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) ldsP[s][i] = 0;
+    ldsV[i] = (Sh::kSpareCol && (i % RS) == D) ? OneBits<T>::value : (uint16_t)0;
+  }
+
+  // per-lane constants: which chunks of a tile this lane moves, and where they land in LDS
+  int lds_off[NL];
+#pragma unroll
+  for (int u = 0; u < NL; ++u) {
+    int c = u * 64 + lane;
+    lds_off[u] = (c / CPR) * RS + (c % CPR) * 8;
+  }
+  // transposing-read base: lane j of 16-lane group g reads row 8g + 4r + j/4, columns 4*(j%4)..
+  const int j16 = lane & 15, g4 = lane >> 4;
+  const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
+
+  const long long n_tiles = (N + kTile - 1) / kTile;
+  long long t_begin = (long long)split * tiles_per_split;
+  long long t_end = t_begin + tiles_per_split;
+  if (t_end > n_tiles) t_end = n_tiles;
+
+  const u32x4* Kh = K + bh * N * CPR;
+  const u32x4* Vh = V + bh * N * CPR;
+
+  f32x4 acc[MT][MT];
+  f32x4 accz[MT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    accz[a] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < MT; ++b) acc[a][b] = f32x4{0, 0, 0, 0};
+  }
+  const uint32_t one2 = (uint32_t)OneBits<T>::value * 0x10001u;
+  const u32x4 ones = {one2, one2, one2, one2};
+
+  u32x4 kr[NL], vr[NL];
+  auto issue_loads = [&](long long tile) {
+    // number of valid 16-byte chunks in this tile (ragged last tile of the head)
+    long long rem = (N - tile * kTile) * CPR;
+    int lim = rem < Cfg::kChunks ? (int)rem : Cfg::kChunks;
+    const u32x4* kp = Kh + tile * Cfg::kChunks;
+    const u32x4* vp = Vh + tile * Cfg::kChunks;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      int c = u * 64 + lane;
+      if (c < lim) {
+        kr[u] = ld_stream(kp + c);
+        vr[u] = ld_stream(vp + c);
+      } else {
+        kr[u] = u32x4{0, 0, 0, 0};
+        vr[u] = u32x4{0, 0, 0, 0};
+      }
+    }
+    return lim;
+  };
+
+  long long tile = t_begin + wave;
+  int lim = 0;
+  if (tile < t_end) lim = issue_loads(tile);
+  __builtin_amdgcn_s_waitcnt(0);  // LDS fill done before data writes (same wave, in order anyway)
+
+  while (tile < t_end) {
+    // ---- phi(K) -> 16-bit (hi [, lo]) -> LDS ; V -> LDS --------------------------------------
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      int c = u * 64 + lane;
+      if (c < Cfg::kChunks) {
+        const bool ok = c < lim;
+        u32x4 ph, pl;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1;
+          unpack2<T>(kr[u][w], x0, x1);
+          float p0 = ok ? phi<FM>(x0) : 0.0f;
+          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          if constexpr (NS == 1) {
+            ph[w] = pack2<T>(p0, p1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(p0, p1, h, l);
+            ph[w] = h;
+            pl[w] = l;
+          }
+        }
+        *reinterpret_cast<u32x4*>(ldsP[0] + lds_off[u]) = ph;
+        if constexpr (NS == 2) *reinterpret_cast<u32x4*>(ldsP[1] + lds_off[u]) = pl;
+        *reinterpret_cast<u32x4*>(ldsV + lds_off[u]) = vr[u];
+      }
+    }
+    // ---- prefetch the wave's next tile while this one is multiplied -------------------------
+    const long long next = tile + kWavesPerWG;
+    int next_lim = 0;
+    if (next < t_end) next_lim = issue_loads(next);
+
+    // ---- token-major operands by transposing LDS reads, then the outer products -------------
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    u32x4 bfrag[MT];
+#pragma unroll
+    for (int b = 0; b < MT; ++b) {
+      u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * b);
+      u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * b);
+      bfrag[b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        u32x2 r0 = lds_read_tr16(ldsP[s] + tr_base + 16 * a);
+        u32x2 r1 = lds_read_tr16(ldsP[s] + tr_base + 4 * RS + 16 * a);
+        u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[a][b] = mfma_16x16x32<T>(afrag, bfrag[b], acc[a][b]);
+        if constexpr (!Sh::kSpareCol) accz[a] = mfma_16x16x32<T>(afrag, ones, accz[a]);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    tile = next;
+    lim = next_lim;
+  }
+
+  // ---- fixed-order cross-wave sum in LDS (wave 0, then 1, 2, 3), then one partial per WG -----
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem);   // [D*D] S then [D] z
+  for (int w = 0; w < kWavesPerWG; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = a * 16 + 4 * g4 + i;
+          if (row < D) {
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+              const int col = b * 16 + j16;
+              if (col < D) {
+                float* p = red + row * D + col;
+                *p = (w == 0) ? acc[a][b][i] : *p + acc[a][b][i];
+              } else if (Sh::kSpareCol && col == D) {
+                float* p = red + D * D + row;
+                *p = (w == 0) ? acc[a][b][i] : *p + acc[a][b][i];
+              }
+            }
+            if constexpr (!Sh::kSpareCol) {
+              if (j16 == 0) {
+                float* p = red + D * D + row;
+                *p = (w == 0) ? accz[a][i] : *p + accz[a][i];
+              }
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  float* dst = partials + (bh * gridDim.x + split) * (long long)(D * D + D);
+  for (int i = threadIdx.x; i < D * D + D; i += kThreads) dst[i] = red[i];
+}
+
+// ==========================================================================================
+// Combine + pack.  grid = B*H, block = 512.  Sums the per-workgroup partials of one head in
+// split order (deterministic), optionally writes the fp32 state, and packs S^T and z into the
+// matrix-core operand layout of apply16, rescaled by powers of two so that 16-bit storage
+// neither overflows nor loses small entries:  S' = alpha_S S, z' = alpha_z z.
+//
+// Packed layout per head: PackHeader, then fragments [level][tile T][k-step s][lane][8 x 16-bit].
+// Fragment (T, s), lane l: output row m = l % 32, contraction group kg = l / 32, element j:
+//   feature channel  ch   = (kg * KS + s) * 8 + j           (zero when that chunk is beyond d)
+//   output slot      slot = 16 T + 4 (m / 8) + (m % 4),  half hv = (m / 4) % 2
+//   slot <  d/2   -> S'[ch][hv * d/2 + slot];  slot == d/2 -> z' (hi part);  slot == d/2 + 1 ->
+//   z' (lo part, level 0 only);  else 0.
+// ==========================================================================================
+constexpr int kCombineThreads = 512;
+
+template <int D> constexpr int pack16_bytes(int nsplit) {
+  return (int)sizeof(PackHeader) + nsplit * Shape16<D>::kFragsPerSplit * 64 * 16;
+}
+
+LF_DEV float pow2_scale_for(float mx) {
+  // power of two alpha with alpha * mx in [2^13, 2^14); 1 when mx is zero or not finite
+  if (!(mx > 0.0f) || !(mx < 3.0e38f)) return 1.0f;
+  int e;
+  (void)__builtin_frexpf(mx, &e);     // mx = m * 2^e, m in [0.5, 1)
+  int k = 14 - e;
+  k = k > 100 ? 100 : (k < -100 ? -100 : k);
+  return __builtin_ldexpf(1.0f, k);
+}
+
+template <typename T, int D>
+__global__ void __launch_bounds__(kCombineThreads)
+combine_pack16(const float* __restrict__ partials, int splits, float eps, int unnormalized,
+               unsigned char* __restrict__ packed, float* __restrict__ state_out) {
+  using Sh = Shape16<D>;
+  constexpr int NS = NSplit<T>::value;
+  constexpr int NE = D * D + D;
+  __shared__ float st[NE];
+  __shared__ float redmax[2][kCombineThreads / 64];
+  const long long bh = blockIdx.x;
+  const float* src = partials + bh * splits * (long long)NE;
+
+  float mS = 0.0f, mz = 0.0f;
+  for (int e = threadIdx.x; e < NE; e += kCombineThreads) {
+    float s = 0.0f;
+    int p = 0;
+    for (; p + 4 <= splits; p += 4) {   // four loads in flight, added in split order
+      float a0 = src[(long long)(p + 0) * NE + e], a1 = src[(long long)(p + 1) * NE + e];
+      float a2 = src[(long long)(p + 2) * NE + e], a3 = src[(long long)(p + 3) * NE + e];
+      s = (((s + a0) + a1) + a2) + a3;
+    }
+    for (; p < splits; ++p) s += src[(long long)p * NE + e];
+    st[e] = s;
+    if (state_out) state_out[bh * NE + e] = s;
+    if (e < D * D) mS = fmaxf(mS, fabsf(s)); else mz = fmaxf(mz, fabsf(s));
+  }
+  if (!packed) return;
+  // block-wide maxima
+  for (int o = 32; o > 0; o >>= 1) {
+    mS = fmaxf(mS, __shfl_xor(mS, o));
+    mz = fmaxf(mz, __shfl_xor(mz, o));
+  }
+  if ((threadIdx.x & 63) == 0) { redmax[0][threadIdx.x >> 6] = mS; redmax[1][threadIdx.x >> 6] = mz; }
+  __syncthreads();
+  mS = 0.0f; mz = 0.0f;
+  for (int w = 0; w < kCombineThreads / 64; ++w) { mS = fmaxf(mS, redmax[0][w]); mz = fmaxf(mz, redmax[1][w]); }
+  const float aS = pow2_scale_for(mS);
+  const float az = unnormalized ? 1.0f : pow2_scale_for(mz);
+
+  unsigned char* dstb = packed + bh * (long long)pack16_bytes<D>(NS);
+  if (threadIdx.x == 0) {
+    PackHeader h;
+    h.c1 = az / aS;
+    h.eps_s = unnormalized ? 1.0f : eps * az;
+    h.pad[0] = h.pad[1] = 0.0f;
+    *reinterpret_cast<PackHeader*>(dstb) = h;
+  }
+  uint32_t* frag = reinterpret_cast<uint32_t*>(dstb + sizeof(PackHeader));
+  constexpr int kWordsPerLevel = Sh::kFragsPerSplit * 64 * 4;   // 32-bit words
+  for (int wi = threadIdx.x; wi < kWordsPerLevel; wi += kCombineThreads) {
+    const int jw = wi & 3;            // word within the lane's 8 elements
+    const int l = (wi >> 2) & 63;
+    const int f = wi >> 8;            // fragment index = T * KS + s
+    const int T_ = f / Sh::kKS, s_ = f % Sh::kKS;
+    const int m = l & 31, kg = l >> 5;
+    const int slot = 16 * T_ + 4 * (m >> 3) + (m & 3);
+    const int hv = (m >> 2) & 1;
+    const int chunk = kg * Sh::kKS + s_;
+    float val[2], val_lo[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int ch = chunk * 8 + jw * 2 + q;
+      float x = 0.0f;
+      bool zlo = false;
+      if (chunk < Sh::kChunksPerRow) {
+        if (slot < Sh::kHalf) x = st[ch * D + hv * Sh::kHalf + slot] * aS;
+        else if (slot == Sh::kHalf) x = unnormalized ? 0.0f : st[D * D + ch] * az;
+        else if (slot == Sh::kHalf + 1) { x = unnormalized ? 0.0f : st[D * D + ch] * az; zlo = true; }
+      }
+      // round once to 16 bits; the remainder goes to the lo level (S) or the lo row (z)
+      float r0, r1;
+      uint32_t w = pack2<T>(x, 0.0f);
+      unpack2<T>(w, r0, r1);
+      if (zlo) { val[q] = x - r0; val_lo[q] = 0.0f; }      // lo row of z: remainder of its hi row
+      else { val[q] = x; val_lo[q] = x - r0; }
+      if (slot == Sh::kHalf) val_lo[q] = 0.0f;             // z's remainder lives in its own row
+    }
+    frag[wi] = pack2<T>(val[0], val[1]);
+    if constexpr (NS == 2) frag[kWordsPerLevel + wi] = pack2<T>(val_lo[0], val_lo[1]);
+  }
+}
+
+// ==========================================================================================
+// Apply + normalize.  grid = (wgs_per_head, B*H), block = 256.  Each wave takes 32-token tiles
+// round-robin: a lane owns one token (lane % 32) and one half of the feature channels
+// (lane / 32), loads its part of the Q row with 128-bit loads, applies phi, and feeds it as
+// the B operand of 32x32x16 products against the packed S'^T fragments (A operand), so the
+// accumulator of a lane holds d/2 contiguous output channels of its token plus the two
+// normalizer rows.  out = num * c1 / (den + eps'), rounded to the storage type and written
+// with 128/64-bit stores.  Q is read once, out is written once.
+// ==========================================================================================
+template <typename T, int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+apply16(const u32x4* __restrict__ Q, unsigned char* __restrict__ O, const unsigned char* __restrict__ packed,
+        long long N, int tiles_per_wg) {
+  using Sh = Shape16<D>;
+  constexpr int NS = NSplit<T>::value;
+  constexpr int KS = Sh::kKS, MT2 = Sh::kMT2, CPR = Sh::kChunksPerRow, HALF = Sh::kHalf;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const long long bh = blockIdx.y;
+  const int tok = lane & 31, kg = lane >> 5;
+
+  const unsigned char* pk = packed + bh * (long long)pack16_bytes<D>(NS);
+  const PackHeader hdr = *reinterpret_cast<const PackHeader*>(pk);
+  const u32x4* fragp = reinterpret_cast<const u32x4*>(pk + sizeof(PackHeader));
+  u32x4 A[NS][MT2][KS];
+#pragma unroll
+  for (int lv = 0; lv < NS; ++lv)
+#pragma unroll
+    for (int t = 0; t < MT2; ++t)
+#pragma unroll
+      for (int s = 0; s < KS; ++s) A[lv][t][s] = fragp[((lv * MT2 + t) * KS + s) * 64 + lane];
+
+  const long long n_tiles = (N + kTile - 1) / kTile;
+  long long t_begin = (long long)blockIdx.x * tiles_per_wg;
+  long long t_end = t_begin + tiles_per_wg;
+  if (t_end > n_tiles) t_end = n_tiles;
+
+  const u32x4* Qh = Q + bh * N * CPR;
+  unsigned char* Oh = O + bh * N * (long long)(D * 2);
+
+  u32x4 qr[KS];
+  auto issue_loads = [&](long long tile) {
+    const long long t = tile * kTile + tok;
+    const u32x4* row = Qh + t * CPR + kg * KS;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      if (t < N && kg * KS + s < CPR) qr[s] = ld_stream(row + s);
+      else qr[s] = u32x4{0, 0, 0, 0};
+    }
+  };
+
+  long long tile = t_begin + wave;
+  if (tile < t_end) issue_loads(tile);
+  while (tile < t_end) {
+    // phi(Q) -> 16-bit operand(s)
+    u32x4 Bh[KS], Bl[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const bool ok = kg * KS + s < CPR;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        float x0, x1;
+        unpack2<T>(qr[s][w], x0, x1);
+        float r0 = ok ? phi<FM>(x0) : 0.0f;
+        float r1 = ok ? phi<FM>(x1) : 0.0f;
+        if constexpr (NS == 1) {
+          Bh[s][w] = pack2<T>(r0, r1);
+        } else {
+          uint32_t h, l;
+          pack2_split<T>(r0, r1, h, l);
+          Bh[s][w] = h;
+          Bl[s][w] = l;
+        }
+      }
+    }
+    const long long cur = tile;
+    tile += kWavesPerWG;
+    if (tile < t_end) issue_loads(tile);
+
+    f32x16 acc[MT2];
+#pragma unroll
+    for (int t = 0; t < MT2; ++t) {
+      acc[t] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        acc[t] = mfma_32x32x16<T>(A[0][t][s], Bh[s], acc[t]);
+        if constexpr (NS == 2) {
+          acc[t] = mfma_32x32x16<T>(A[0][t][s], Bl[s], acc[t]);
+          acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);
+        }
+      }
+    }
+    // normalizer: slots HALF (z hi) and HALF+1 (z lo) of this lane's accumulators
+    float scale = hdr.c1;
+    if constexpr (NORM) {
+      const float den = acc[HALF / 16][HALF % 16] + acc[(HALF + 1) / 16][(HALF + 1) % 16] + hdr.eps_s;
+      scale = hdr.c1 * __builtin_amdgcn_rcpf(den);
+    }
+    const long long t = cur * kTile + tok;
+    if (t < N) {
+      unsigned char* orow = Oh + t * (long long)(D * 2) + kg * (HALF * 2);
+      if constexpr ((HALF * 2) % 16 == 0) {
+#pragma unroll
+        for (int c = 0; c < HALF / 8; ++c) {
+          u32x4 w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int s0 = c * 8 + 2 * e;
+            w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
+          }
+          st_stream(reinterpret_cast<u32x4*>(orow) + c, w);
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < HALF / 4; ++c) {
+          u32x2 w;
+#pragma unroll
+          for (int e = 0; e < 2; ++e) {
+            const int s0 = c * 4 + 2 * e;
+            w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
+          }
+          st_stream(reinterpret_cast<u32x2*>(orow) + c, w);
+        }
+      }
+    }
+  }
+}
+
+}  // namespace lf

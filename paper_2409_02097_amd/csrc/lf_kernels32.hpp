@@ -1,0 +1,310 @@
+// fp32 kernels of the split-N path.  fp32 inputs never pass through 16-bit operands: the
+// d x d contractions use the fp32 matrix-core instruction (16x16x4), whose operand layout
+// holds one contraction index per lane, so no transposition is needed anywhere.
+//   state_reduce32  S_p, z_p over a chunk of tokens            (Prop. 2: g'(X)^T X; Eq. 5: Z)
+//   combine_pack32  fixed-order sum of the partials, pack for apply
+//   apply32         out_i = phi(q_i) S / (phi(q_i).z + eps)
+#pragma once
+#include "lf_common.hpp"
+#include "lf_kernels16.hpp"   // kWavesPerWG, kThreads, kCombineThreads
+
+namespace lf {
+
+constexpr int kTile32 = 16;   // tokens per tile: four 16x16x4 k-steps
+
+template <int D> struct Shape32 {
+  static constexpr int kChunks = D / 4;                     // float4 chunks per token row
+  // apply: lane (token = lane % 16, kq = lane / 16) loads the kCS contiguous chunks kq*kCS + cs
+  static constexpr int kCS = (kChunks + 3) / 4;
+  static constexpr int kKSteps = kCS * 4;
+  static constexpr int kQuarter = D / 4;                    // output channels per 16-lane group
+  static constexpr int kMT = (kQuarter + 1 + 3) / 4;        // 16-row output tiles incl. normalizer row
+};
+
+constexpr int pack32_bytes(int d) {
+  int chunks = d / 4, cs = (chunks + 3) / 4, mt = (d / 4 + 1 + 3) / 4;
+  return (int)sizeof(PackHeader) + mt * cs * 4 * 64 * 4;
+}
+
+LF_DEV f32x4 mfma_16x16x4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
+
+// ------------------------------------------------------------------------------------------
+// grid = (splits, B*H), block = 256.  Lane (m = lane % 16, kq = lane / 16) holds channels
+// 4m..4m+3 of token 4u + kq of the tile; element i of its K chunk (after phi) is the A operand
+// and element j of its V chunk the B operand of product (i, j), whose accumulator tile is
+// S[4*row + i][4*col + j].  z is summed on the vector ALU.
+// ------------------------------------------------------------------------------------------
+template <int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* __restrict__ partials,
+               long long N, int tiles_per_split) {
+  constexpr int CH = Shape32<D>::kChunks;
+  constexpr int U = kTile32 / 4;
+  __shared__ float red[D * D + D];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = lane & 15, kq = lane >> 4;
+  const int split = blockIdx.x;
+  const long long bh = blockIdx.y;
+  const bool lane_on = m < CH;
+
+  const long long n_tiles = (N + kTile32 - 1) / kTile32;
+  long long t_begin = (long long)split * tiles_per_split;
+  long long t_end = t_begin + tiles_per_split;
+  if (t_end > n_tiles) t_end = n_tiles;
+  const f32x4* Kh = K + bh * N * CH;
+  const f32x4* Vh = V + bh * N * CH;
+
+  f32x4 acc[4][4];
+  float zacc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0, 0, 0, 0};
+
+  f32x4 kr[U], vr[U];
+  bool okr[U];
+  auto issue_loads = [&](long long tile) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const long long t = tile * kTile32 + 4 * u + kq;
+      okr[u] = lane_on && t < N;
+      if (okr[u]) {
+        kr[u] = __builtin_nontemporal_load(Kh + t * CH + m);
+        vr[u] = __builtin_nontemporal_load(Vh + t * CH + m);
+      } else {
+        kr[u] = f32x4{0, 0, 0, 0};
+        vr[u] = f32x4{0, 0, 0, 0};
+      }
+    }
+  };
+
+  long long tile = t_begin + wave;
+  if (tile < t_end) issue_loads(tile);
+  while (tile < t_end) {
+    f32x4 p[U], vv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) p[u][i] = okr[u] ? phi<FM, true>(kr[u][i]) : 0.0f;
+      vv[u] = vr[u];
+    }
+    tile += kWavesPerWG;
+    if (tile < t_end) issue_loads(tile);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        zacc[i] += p[u][i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = mfma_16x16x4(p[u][i], vv[u][j], acc[i][j]);
+      }
+    }
+  }
+
+  // fixed-order sum: waves 0..3, and inside a wave the four token groups kq = 0..3 for z
+  for (int w = 0; w < kWavesPerWG; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int row = 4 * (4 * kq + r) + i;
+          if (row < D) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              const int col = 4 * m + j;
+              if (col < D) {
+                float* q = red + row * D + col;
+                *q = (w == 0) ? acc[i][j][r] : *q + acc[i][j][r];
+              }
+            }
+          }
+        }
+      for (int s = 0; s < 4; ++s) {
+        if (kq == s && lane_on) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float* q = red + D * D + 4 * m + i;
+            *q = (w == 0 && s == 0) ? zacc[i] : *q + zacc[i];
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      }
+    }
+    __syncthreads();
+  }
+  float* dst = partials + (bh * gridDim.x + split) * (long long)(D * D + D);
+  for (int i = threadIdx.x; i < D * D + D; i += kThreads) dst[i] = red[i];
+}
+
+// ------------------------------------------------------------------------------------------
+// grid = B*H, block = 512.  Packed layout per head: PackHeader, then [tile T][k-step ks][lane]
+// floats.  k-step ks = 4*cs + e; lane l: output row mrow = l % 16, kq = l / 16:
+//   feature channel ch = 4*(kq*CS + cs) + e  (zero when that chunk is beyond d)
+//   slot = 4*T + mrow % 4, group g = mrow / 4:  slot < d/4 -> S[ch][g*d/4 + slot];
+//   slot == d/4 -> z[ch];  else 0.
+// ------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(kCombineThreads)
+combine_pack32(const float* __restrict__ partials, int splits, float eps, int unnormalized,
+               unsigned char* __restrict__ packed, float* __restrict__ state_out) {
+  using Sh = Shape32<D>;
+  constexpr int NE = D * D + D;
+  __shared__ float st[NE];
+  const long long bh = blockIdx.x;
+  const float* src = partials + bh * splits * (long long)NE;
+  for (int e = threadIdx.x; e < NE; e += kCombineThreads) {
+    float s = 0.0f;
+    int p = 0;
+    for (; p + 4 <= splits; p += 4) {
+      float a0 = src[(long long)(p + 0) * NE + e], a1 = src[(long long)(p + 1) * NE + e];
+      float a2 = src[(long long)(p + 2) * NE + e], a3 = src[(long long)(p + 3) * NE + e];
+      s = (((s + a0) + a1) + a2) + a3;
+    }
+    for (; p < splits; ++p) s += src[(long long)p * NE + e];
+    st[e] = s;
+    if (state_out) state_out[bh * NE + e] = s;
+  }
+  if (!packed) return;
+  __syncthreads();
+  unsigned char* dstb = packed + bh * (long long)pack32_bytes(D);
+  if (threadIdx.x == 0) {
+    PackHeader h;
+    h.c1 = 1.0f;
+    h.eps_s = eps;
+    h.pad[0] = h.pad[1] = 0.0f;
+    *reinterpret_cast<PackHeader*>(dstb) = h;
+  }
+  float* frag = reinterpret_cast<float*>(dstb + sizeof(PackHeader));
+  constexpr int kWords = Sh::kMT * Sh::kKSteps * 64;
+  for (int wi = threadIdx.x; wi < kWords; wi += kCombineThreads) {
+    const int l = wi & 63;
+    const int f = wi >> 6;
+    const int T_ = f / Sh::kKSteps, ks = f % Sh::kKSteps;
+    const int cs = ks >> 2, e = ks & 3;
+    const int mrow = l & 15, kq = l >> 4;
+    const int chunk = kq * Sh::kCS + cs;
+    const int slot = 4 * T_ + (mrow & 3), g = mrow >> 2;
+    float x = 0.0f;
+    if (chunk < Sh::kChunks) {
+      const int ch = 4 * chunk + e;
+      if (slot < Sh::kQuarter) x = st[ch * D + g * Sh::kQuarter + slot];
+      else if (slot == Sh::kQuarter && !unnormalized) x = st[D * D + ch];
+    }
+    frag[wi] = x;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// grid = (wgs_per_head, B*H), block = 256.  Lane (token = lane % 16, kq = lane / 16) loads its
+// kCS contiguous float4 chunks of the Q row; element e of chunk cs is the B operand of k-step
+// 4*cs + e against the packed S^T fragment (A operand).  The accumulators of a lane hold d/4
+// contiguous output channels of its token and the normalizer phi(q).z.
+// ------------------------------------------------------------------------------------------
+template <int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const unsigned char* __restrict__ packed,
+        long long N, int tiles_per_wg) {
+  using Sh = Shape32<D>;
+  constexpr int CS = Sh::kCS, KST = Sh::kKSteps, MT = Sh::kMT, CH = Sh::kChunks, QT = Sh::kQuarter;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tok = lane & 15, kq = lane >> 4;
+  const long long bh = blockIdx.y;
+  const unsigned char* pk = packed + bh * (long long)pack32_bytes(D);
+  const PackHeader hdr = *reinterpret_cast<const PackHeader*>(pk);
+  const float* fragp = reinterpret_cast<const float*>(pk + sizeof(PackHeader));
+  float A[MT][KST];
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int ks = 0; ks < KST; ++ks) A[t][ks] = fragp[(t * KST + ks) * 64 + lane];
+
+  const long long n_tiles = (N + kTile32 - 1) / kTile32;
+  long long t_begin = (long long)blockIdx.x * tiles_per_wg;
+  long long t_end = t_begin + tiles_per_wg;
+  if (t_end > n_tiles) t_end = n_tiles;
+  const f32x4* Qh = Q + bh * N * CH;
+  float* Oh = O + bh * N * (long long)D;
+
+  f32x4 qr[CS];
+  auto issue_loads = [&](long long tile) {
+    const long long t = tile * kTile32 + tok;
+#pragma unroll
+    for (int cs = 0; cs < CS; ++cs) {
+      if (t < N && kq * CS + cs < CH) qr[cs] = __builtin_nontemporal_load(Qh + t * CH + kq * CS + cs);
+      else qr[cs] = f32x4{0, 0, 0, 0};
+    }
+  };
+  long long tile = t_begin + wave;
+  if (tile < t_end) issue_loads(tile);
+  while (tile < t_end) {
+    float r[KST];
+#pragma unroll
+    for (int cs = 0; cs < CS; ++cs)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) r[4 * cs + e] = (kq * CS + cs < CH) ? phi<FM, true>(qr[cs][e]) : 0.0f;
+    const long long cur = tile;
+    tile += kWavesPerWG;
+    if (tile < t_end) issue_loads(tile);
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      acc[t] = f32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int ks = 0; ks < KST; ++ks) acc[t] = mfma_16x16x4(A[t][ks], r[ks], acc[t]);
+    }
+    float scale = hdr.c1;
+    if constexpr (NORM) scale = 1.0f / (acc[QT / 4][QT % 4] + hdr.eps_s);
+    const long long t = cur * kTile32 + tok;
+    if (t < N) {
+      float* orow = Oh + t * (long long)D + kq * QT;
+      if constexpr (QT % 4 == 0) {
+#pragma unroll
+        for (int c = 0; c < QT / 4; ++c) {
+          f32x4 w = {acc[c][0] * scale, acc[c][1] * scale, acc[c][2] * scale, acc[c][3] * scale};
+          __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(orow) + c);
+        }
+      } else {
+#pragma unroll
+        for (int c = 0; c < QT / 2; ++c) {
+          const int s0 = 2 * c;
+          f32x2 w = {acc[s0 / 4][s0 % 4] * scale, acc[(s0 + 1) / 4][(s0 + 1) % 4] * scale};
+          __builtin_nontemporal_store(w, reinterpret_cast<f32x2*>(orow) + c);
+        }
+      }
+    }
+  }
+}
+
+template <int D>
+hipError_t run32(const float* q, const float* k, const float* v, float* out, long long BH, long long N, int fm,
+                 float eps, bool unnorm, int splits, int tiles_per_split, int apply_wgs, int tiles_per_wg,
+                 float* partials, unsigned char* packed, float* state_out, hipStream_t st) {
+  const dim3 g1(splits, (unsigned)BH), blk(kThreads);
+  const f32x4* K = (const f32x4*)k;
+  const f32x4* V = (const f32x4*)v;
+  switch (fm) {
+    case 0: state_reduce32<D, 0><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
+    case 1: state_reduce32<D, 1><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
+    default: state_reduce32<D, 2><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
+  }
+  combine_pack32<D><<<dim3((unsigned)BH), dim3(kCombineThreads), 0, st>>>(partials, splits, eps, unnorm ? 1 : 0,
+                                                                          out ? packed : nullptr, state_out);
+  if (out) {
+    const dim3 g2(apply_wgs, (unsigned)BH);
+    const f32x4* Q = (const f32x4*)q;
+#define LF_APPLY32(FM)                                                                   \
+  if (unnorm) apply32<D, FM, false><<<g2, blk, 0, st>>>(Q, out, packed, N, tiles_per_wg); \
+  else apply32<D, FM, true><<<g2, blk, 0, st>>>(Q, out, packed, N, tiles_per_wg);
+    switch (fm) {
+      case 0: LF_APPLY32(0) break;
+      case 1: LF_APPLY32(1) break;
+      default: LF_APPLY32(2) break;
+    }
+#undef LF_APPLY32
+  }
+  return hipGetLastError();
+}
+
+}  // namespace lf

@@ -1,0 +1,62 @@
+"""Tolerance rule for comparing the library with the fp64 oracle (shared by the GPU tests).
+
+The task states "max relative error 2e-3 for fp16/bf16 inputs with fp32 accumulation, 1e-5 for
+fp32 inputs".  Outputs are convex combinations of zero-mean values and cross zero, so an
+element-by-element ratio is ill-posed; the error is measured per (batch, head) slice against
+the slice's largest reference magnitude, and in relative L2 norm.  The tolerance governs the
+arithmetic before the final round-to-nearest cast to the storage type; that cast may move a
+value by half a unit in the last place of the reference, which is added element-wise
+(uniform rounding noise of that size has relative L2 norm 2^-(p-1) / sqrt(12), p = precision).
+
+    |gpu - ref| <= tol * max|ref_slice| + half_ulp_out(ref)          for every element
+    ||gpu - ref||_2 / ||ref||_2 <= tol + 2^-(p-1) / sqrt(12)         for every slice
+"""
+import math
+
+import numpy as np
+
+from oracle import linattn_oracle as orc
+
+TOL = {"f32": 1e-5, "f16": 2e-3, "bf16": 2e-3}
+PREC = {"f32": 24, "f16": 11, "bf16": 8}
+
+
+def to_f64(t):
+    """Library output tensor -> fp64 numpy (exact widening)."""
+    import torch
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+def check_slice(gpu, ref, dtype, what=""):
+    """gpu, ref: [n, d] fp64 arrays of one (b, h) slice (or a sample of its rows)."""
+    tol = TOL[dtype]
+    assert np.all(np.isfinite(ref)), f"{what}: oracle produced non-finite values"
+    assert np.all(np.isfinite(gpu)), f"{what}: library produced non-finite values"
+    scale = np.abs(ref).max()
+    err = np.abs(gpu - ref)
+    bound = tol * scale + orc.half_ulp(ref, dtype)
+    worst = (err - bound).max()
+    assert worst <= 0, (f"{what}: max-norm error {err.max():.3e} vs scale {scale:.3e} "
+                        f"(ratio {err.max() / max(scale, 1e-300):.3e}, tol {tol:g})")
+    nref = math.sqrt(float((ref * ref).sum()))
+    if nref > 0:
+        rel = math.sqrt(float((err * err).sum())) / nref
+        lim = tol + 2.0 ** -(PREC[dtype] - 1) / math.sqrt(12.0)
+        assert rel <= lim, f"{what}: relative L2 error {rel:.3e} > {lim:.3e}"
+        return err.max() / max(scale, 1e-300), rel
+    return err.max() / max(scale, 1e-300), 0.0
+
+
+def check_all(out_t, q_t, k_t, v_t, dtype, feature_map=0, eps=1e-6, normalize=True, what=""):
+    """Full element-by-element comparison over every (b, h) slice.  Returns worst ratios."""
+    from paper_2409_02097_amd.workloads import stored_numpy
+    qs, ks, vs = stored_numpy(q_t), stored_numpy(k_t), stored_numpy(v_t)
+    gpu = to_f64(out_t)
+    B, H = qs.shape[:2]
+    worst = (0.0, 0.0)
+    for b in range(B):
+        for h in range(H):
+            ref = orc.attention_linear_stored(qs[b, h], ks[b, h], vs[b, h], dtype, feature_map, eps, normalize)
+            r = check_slice(gpu[b, h], ref, dtype, f"{what} b={b} h={h}")
+            worst = (max(worst[0], r[0]), max(worst[1], r[1]))
+    return worst
