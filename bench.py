@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the LinFusion token mixer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+A step is one pass of the whole hot path (feature map, split-N state reduction, combine,
+apply + normalize: one linfusion_attn_fwd_ex call) over one batch of seeded synthetic Q/K/V
+that is already resident in HBM.  Prints ONE JSON line: tokens/s for the whole job, the HBM
+roofline of the dominant kernel measured live with HIP events recorded on the launch stream
+between the library's kernels, and the fp64 CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+DEFAULT_WORKLOAD = "sd15_16k_f16"   # 16384x8192 image, SD-v1.5 top level: B=1 H=8 N=2,097,152 d=40 fp16
+
+
+class HipEvents:
+    """hipEvent_t handles created through the HIP runtime directly (ctypes), for per-kernel timing."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.ev = []
+        for _ in range(n):
+            e = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(e))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            self.ev.append(e.value)
+
+    def elapsed_ms(self, a, b):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.ev[a], self.ev[b])
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return ms.value
+
+    def sync(self, i):
+        self.hip.hipEventSynchronize(self.ev[i])
+
+    def close(self):
+        for e in self.ev:
+            self.hip.hipEventDestroy(e)
+        self.ev = []
+
+
+def cpu_baseline(q, k, v, cfg, sample_tokens):
+    """The oracle as it stands, timed on the first `sample_tokens` tokens of head (0, 0)."""
+    import numpy as np
+    from oracle import linattn_oracle as orc
+    from paper_2409_02097_amd import workloads as wl
+    n = min(sample_tokens, cfg["N"])
+    qs = wl.stored_numpy(q[0, 0, :n])
+    ks = wl.stored_numpy(k[0, 0, :n])
+    vs = wl.stored_numpy(v[0, 0, :n])
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    t0 = time.perf_counter()
+    ref = orc.attention_linear_stored(qs, ks, vs, cfg["dtype"], 0, wl.EPS)
+    dt = time.perf_counter() - t0
+    assert np.all(np.isfinite(ref))
+    # the workload's token count is B*N with all H heads per token; the sample is one head
+    tokens_per_s = n / (dt * cfg["H"])
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"fp64 numpy oracle on the first {n} tokens of one (batch, head) slice of the same "
+                      f"tensors ({dt:.1f} s); scaled to all {cfg['H']} heads per token; host has "
+                      f"{os.cpu_count()} logical cores, BLAS threads = {threads}"}, ref
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--profile-steps", type=int, default=10)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1 << 21)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--flags", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the hot path is a single-device kernel "
+              "sequence; sharding over devices is described in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2409_02097_amd as lf
+    from paper_2409_02097_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    cfg = wl.CONFIGS[args.workload]
+    B, H, N, d, dtype = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["dtype"]
+    q, k, v = wl.make_config(args.workload, device="cuda")
+    out = torch.empty_like(q)
+    code = wl.DTYPE_CODE[dtype]
+    ws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
+    plan = lf.linfusion_attn_plan(B, H, N, d, code, args.flags)
+
+    def step():
+        lf.linfusion_attn_fwd_ex(q, k, v, out, lf.PHI_ELU_PLUS_ONE, wl.EPS, args.flags, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = B * N / (dt / args.steps)
+    alg_bytes = wl.algorithmic_bytes(B, H, N, d, dtype)
+
+    # per-kernel durations, HIP events recorded on the launch stream between the kernels
+    evs = HipEvents(4)
+    acc = [0.0, 0.0, 0.0]
+    for _ in range(args.profile_steps):
+        lf.linfusion_attn_fwd_profile(q, k, v, out, lf.PHI_ELU_PLUS_ONE, wl.EPS, args.flags, ws, evs.ev)
+        evs.sync(3)
+        for i in range(3):
+            acc[i] += evs.elapsed_ms(i, i + 1)
+    evs.close()
+    kms = [a / max(args.profile_steps, 1) for a in acc]
+    sfx = {"f16": "16<F16", "bf16": "16<BF16", "f32": "32<"}[dtype]
+    half = alg_bytes / 2      # K+V read by the reduction; Q read + out written by apply
+    kernels = [
+        {"name": f"state_reduce{sfx}", "ms": kms[0], "alg_bytes": half},
+        {"name": "combine_state", "ms": kms[1], "alg_bytes": 0},
+        {"name": f"apply{sfx}", "ms": kms[2], "alg_bytes": half},
+    ]
+    for kk in kernels:
+        kk["gbps"] = kk["alg_bytes"] / (kk["ms"] * 1e-3) / 1e9 if kk["ms"] > 0 else None
+    dom = max((kernels[0], kernels[2]), key=lambda x: x["ms"])
+    roofline = {"bound": "hbm", "kernel": dom["name"], "achieved": dom["gbps"], "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": dom["gbps"] / HBM_PEAK_GBPS, "traffic": None,
+                "avg_launch_ms": dom["ms"], "kernels": kernels}
+
+    result = {
+        "metric": "non-causal linear-attn tokens/s + achieved HBM GB/s (% of peak), 1 GPU",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "B": B, "H": H, "N": N, "d": d, "eps": wl.EPS,
+                   "feature_map": "elu+1", "plan": plan},
+        "hbm_gbps": alg_bytes / (dt / args.steps) / 1e9,
+        "hbm_frac_of_peak": alg_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        base, ref = cpu_baseline(q, k, v, cfg, args.cpu_sample_tokens)
+        result["cpu_baseline"] = base
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -83,6 +83,17 @@ int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Benchmark aid: linfusion_attn_fwd_ex that also records four caller-created hipEvent_t
+ * (passed as void*) on `stream`: events[0] before the state reduction, [1] after it, [2] after
+ * the combine, [3] after apply, so a harness can time each kernel of one call.
+ */
+int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void* out,
+                               int B, int H, long long N, int d,
+                               int dtype, int feature_map, float eps, unsigned flags,
+                               void* workspace, size_t workspace_bytes, void* stream,
+                               void* events[4]);
+
+/*
  * Bytes of device scratch linfusion_attn_fwd_ex needs for this shape.  Pure host function of
  * its arguments (no device query); returns 0 for arguments the forward call would reject.
  */

@@ -43,6 +43,9 @@ def library() -> ctypes.CDLL:
                                   ctypes.c_uint, ctypes.c_size_t)
     lib.linfusion_attn_fwd_ex.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp]
     lib.linfusion_attn_fwd_ex.restype = i32
+    lib.linfusion_attn_fwd_profile.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp,
+                                               ctypes.POINTER(ctypes.c_void_p * 4)]
+    lib.linfusion_attn_fwd_profile.restype = i32
     lib.linfusion_attn_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
     lib.linfusion_attn_workspace_bytes.restype = sz
     for name in ("linfusion_attn_fwd", "linfusion_attn_fwd_f16", "linfusion_attn_fwd_bf16", "linfusion_attn_fwd_f32"):
@@ -117,6 +120,20 @@ def linfusion_attn_fwd_ex(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps
                                          _stream_ptr(stream))
     if check and rc != 0:
         raise LinFusionError(rc, "linfusion_attn_fwd_ex")
+    return rc
+
+
+def linfusion_attn_fwd_profile(q, k, v, out, feature_map, eps, flags, workspace, events, stream=None,
+                               check: bool = True) -> int:
+    """Like linfusion_attn_fwd_ex; `events` = four hipEvent_t handles (ints) recorded around the kernels."""
+    B, H, N, d = _check_layout(q, k, v, out)
+    ev = (ctypes.c_void_p * 4)(*[ctypes.c_void_p(int(e)) for e in events])
+    rc = library().linfusion_attn_fwd_profile(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d,
+                                              _dtype_code(q), feature_map, eps, flags, workspace.data_ptr(),
+                                              workspace.numel() * workspace.element_size(), _stream_ptr(stream),
+                                              ctypes.byref(ev))
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_fwd_profile")
     return rc
 
 

@@ -124,14 +124,6 @@ template <int D> struct Shape16 {
   static constexpr int kKS = (kChunksPerRow + 1) / 2;
   static constexpr int kHalf = D / 2;                  // output channels held by one half-wave
   static constexpr int kMT2 = (kHalf + 2 + 15) / 16;   // 32-row output tiles incl. normalizer rows
-  static constexpr int kFragsPerSplit = kMT2 * kKS;    // 1 KiB operand fragments per hi/lo level
-};
-
-// header of the packed per-head state consumed by the apply kernel
-struct PackHeader {
-  float c1;      // alpha_z / alpha_S (un-normalized: 1 / alpha_S)
-  float eps_s;   // eps * alpha_z
-  float pad[2];
 };
 
 template <typename T> struct NSplit;                 // operand levels needed to hold an fp32 value

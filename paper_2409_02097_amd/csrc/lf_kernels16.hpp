@@ -221,22 +221,39 @@ state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* 
 }
 
 // ==========================================================================================
-// Combine + pack.  grid = B*H, block = 512.  Sums the per-workgroup partials of one head in
-// split order (deterministic), optionally writes the fp32 state, and packs S^T and z into the
-// matrix-core operand layout of apply16, rescaled by powers of two so that 16-bit storage
-// neither overflows nor loses small entries:  S' = alpha_S S, z' = alpha_z z.
-//
-// Packed layout per head: PackHeader, then fragments [level][tile T][k-step s][lane][8 x 16-bit].
-// Fragment (T, s), lane l: output row m = l % 32, contraction group kg = l / 32, element j:
-//   feature channel  ch   = (kg * KS + s) * 8 + j           (zero when that chunk is beyond d)
-//   output slot      slot = 16 T + 4 (m / 8) + (m % 4),  half hv = (m / 4) % 2
-//   slot <  d/2   -> S'[ch][hv * d/2 + slot];  slot == d/2 -> z' (hi part);  slot == d/2 + 1 ->
-//   z' (lo part, level 0 only);  else 0.
+// Combine.  grid = (ceil(NE / 64), B*H), block = 256, NE = d*d + d.  Thread (e, sg) sums element
+// e of the head's partials over the sg-th quarter of the splits in split order; the four
+// quarters are then added in order 0..3.  Fixed order => run-to-run identical.  Output: the
+// fp32 state of the head, S as [d][d] row-major then z as [d].
 // ==========================================================================================
-constexpr int kCombineThreads = 512;
+constexpr int kCombineThreads = 256;
+constexpr int kCombineElems = 64;
 
-template <int D> constexpr int pack16_bytes(int nsplit) {
-  return (int)sizeof(PackHeader) + nsplit * Shape16<D>::kFragsPerSplit * 64 * 16;
+__global__ void __launch_bounds__(kCombineThreads)
+combine_state(const float* __restrict__ partials, int splits, int NE, float* __restrict__ state) {
+  __shared__ float part[4][kCombineElems];
+  const int el = threadIdx.x & 63, sg = threadIdx.x >> 6;
+  const int e = blockIdx.x * kCombineElems + el;
+  const long long bh = blockIdx.y;
+  const int per = (splits + 3) / 4;
+  int p0 = sg * per, p1 = p0 + per;
+  if (p1 > splits) p1 = splits;
+  float s = 0.0f;
+  if (e < NE) {
+    const float* src = partials + (bh * splits) * (long long)NE + e;
+    int p = p0;
+    for (; p + 8 <= p1; p += 8) {   // eight loads in flight, added in split order
+      float a[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a[i] = src[(long long)(p + i) * NE];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += a[i];
+    }
+    for (; p < p1; ++p) s += src[(long long)p * NE];
+  }
+  part[sg][el] = s;
+  __syncthreads();
+  if (sg == 0 && e < NE) state[bh * NE + e] = ((part[0][el] + part[1][el]) + part[2][el]) + part[3][el];
 }
 
 LF_DEV float pow2_scale_for(float mx) {
@@ -249,166 +266,192 @@ LF_DEV float pow2_scale_for(float mx) {
   return __builtin_ldexpf(1.0f, k);
 }
 
-template <typename T, int D>
-__global__ void __launch_bounds__(kCombineThreads)
-combine_pack16(const float* __restrict__ partials, int splits, float eps, int unnormalized,
-               unsigned char* __restrict__ packed, float* __restrict__ state_out) {
+// ==========================================================================================
+// Apply + normalize.  grid = (wgs_per_head, B*H), block = 256, dynamic LDS.
+//
+// Prologue (once per workgroup): the head's fp32 state is staged in LDS, rescaled by powers of
+// two so that 16-bit storage neither overflows nor loses small entries (S' = alpha_S S,
+// z' = alpha_z z), and every lane builds its matrix-core A operands (S'^T and the normalizer
+// rows) in registers.  Fragment (T, s), lane l: output row m = l % 32, contraction group
+// kg = l / 32, element j:
+//   feature channel  ch   = (kg * KS + s) * 8 + j           (zero when that chunk is beyond d)
+//   output slot      slot = 16 T + 4 (m / 8) + (m % 4),  half hv = (m / 4) % 2
+//   slot <  d/2   -> S'[ch][hv * d/2 + slot];  slot == d/2 -> z' rounded to 16 bits;
+//   slot == d/2+1 -> the remainder of z' after that rounding;  else 0.
+// bf16 carries S' as hi + lo fragments (three products per step) to keep ~16 significant bits.
+//
+// Stream loop (per wave, 32-token tiles round-robin, no workgroup barrier): coalesced 128-bit
+// loads of the contiguous tile -> phi -> 16-bit -> wave-private LDS tile -> each lane reads back
+// the 8-channel pieces of its own token (lane % 32) as B operands -> 32x32x16 products: a lane's
+// accumulators hold d/2 contiguous output channels of its token plus the two normalizer rows ->
+// out = num * c1 / (den + eps') -> 16-bit -> LDS tile -> coalesced 128-bit stores.
+// Q is read once, out is written once.
+// ==========================================================================================
+template <int D> struct Apply16Cfg {
   using Sh = Shape16<D>;
-  constexpr int NS = NSplit<T>::value;
-  constexpr int NE = D * D + D;
-  __shared__ float st[NE];
-  __shared__ float redmax[2][kCombineThreads / 64];
-  const long long bh = blockIdx.x;
-  const float* src = partials + bh * splits * (long long)NE;
+  static constexpr int kRowUnits = ((D * 2 / 16) % 2 == 0) ? D * 2 / 16 + 1 : D * 2 / 16;  // odd # of 16 B units
+  static constexpr int kRS = kRowUnits * 8;                        // LDS row stride in 16-bit elements
+  static constexpr int kTileElems = kTile * kRS;
+  static constexpr int kChunks = kTile * Sh::kChunksPerRow;
+  static constexpr int kNL = (kChunks + 63) / 64;
+};
 
-  float mS = 0.0f, mz = 0.0f;
-  for (int e = threadIdx.x; e < NE; e += kCombineThreads) {
-    float s = 0.0f;
-    int p = 0;
-    for (; p + 4 <= splits; p += 4) {   // four loads in flight, added in split order
-      float a0 = src[(long long)(p + 0) * NE + e], a1 = src[(long long)(p + 1) * NE + e];
-      float a2 = src[(long long)(p + 2) * NE + e], a3 = src[(long long)(p + 3) * NE + e];
-      s = (((s + a0) + a1) + a2) + a3;
-    }
-    for (; p < splits; ++p) s += src[(long long)p * NE + e];
-    st[e] = s;
-    if (state_out) state_out[bh * NE + e] = s;
-    if (e < D * D) mS = fmaxf(mS, fabsf(s)); else mz = fmaxf(mz, fabsf(s));
-  }
-  if (!packed) return;
-  // block-wide maxima
-  for (int o = 32; o > 0; o >>= 1) {
-    mS = fmaxf(mS, __shfl_xor(mS, o));
-    mz = fmaxf(mz, __shfl_xor(mz, o));
-  }
-  if ((threadIdx.x & 63) == 0) { redmax[0][threadIdx.x >> 6] = mS; redmax[1][threadIdx.x >> 6] = mz; }
-  __syncthreads();
-  mS = 0.0f; mz = 0.0f;
-  for (int w = 0; w < kCombineThreads / 64; ++w) { mS = fmaxf(mS, redmax[0][w]); mz = fmaxf(mz, redmax[1][w]); }
-  const float aS = pow2_scale_for(mS);
-  const float az = unnormalized ? 1.0f : pow2_scale_for(mz);
-
-  unsigned char* dstb = packed + bh * (long long)pack16_bytes<D>(NS);
-  if (threadIdx.x == 0) {
-    PackHeader h;
-    h.c1 = az / aS;
-    h.eps_s = unnormalized ? 1.0f : eps * az;
-    h.pad[0] = h.pad[1] = 0.0f;
-    *reinterpret_cast<PackHeader*>(dstb) = h;
-  }
-  uint32_t* frag = reinterpret_cast<uint32_t*>(dstb + sizeof(PackHeader));
-  constexpr int kWordsPerLevel = Sh::kFragsPerSplit * 64 * 4;   // 32-bit words
-  for (int wi = threadIdx.x; wi < kWordsPerLevel; wi += kCombineThreads) {
-    const int jw = wi & 3;            // word within the lane's 8 elements
-    const int l = (wi >> 2) & 63;
-    const int f = wi >> 8;            // fragment index = T * KS + s
-    const int T_ = f / Sh::kKS, s_ = f % Sh::kKS;
-    const int m = l & 31, kg = l >> 5;
-    const int slot = 16 * T_ + 4 * (m >> 3) + (m & 3);
-    const int hv = (m >> 2) & 1;
-    const int chunk = kg * Sh::kKS + s_;
-    float val[2], val_lo[2];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int ch = chunk * 8 + jw * 2 + q;
-      float x = 0.0f;
-      bool zlo = false;
-      if (chunk < Sh::kChunksPerRow) {
-        if (slot < Sh::kHalf) x = st[ch * D + hv * Sh::kHalf + slot] * aS;
-        else if (slot == Sh::kHalf) x = unnormalized ? 0.0f : st[D * D + ch] * az;
-        else if (slot == Sh::kHalf + 1) { x = unnormalized ? 0.0f : st[D * D + ch] * az; zlo = true; }
-      }
-      // round once to 16 bits; the remainder goes to the lo level (S) or the lo row (z)
-      float r0, r1;
-      uint32_t w = pack2<T>(x, 0.0f);
-      unpack2<T>(w, r0, r1);
-      if (zlo) { val[q] = x - r0; val_lo[q] = 0.0f; }      // lo row of z: remainder of its hi row
-      else { val[q] = x; val_lo[q] = x - r0; }
-      if (slot == Sh::kHalf) val_lo[q] = 0.0f;             // z's remainder lives in its own row
-    }
-    frag[wi] = pack2<T>(val[0], val[1]);
-    if constexpr (NS == 2) frag[kWordsPerLevel + wi] = pack2<T>(val_lo[0], val_lo[1]);
-  }
+template <typename T, int D>
+constexpr int apply16_lds_bytes() {
+  int tiles = NSplit<T>::value * Apply16Cfg<D>::kTileElems * 2 * kWavesPerWG;
+  int st = (D * D + D) * 4 + 64;
+  return tiles > st ? tiles : st;
 }
 
-// ==========================================================================================
-// Apply + normalize.  grid = (wgs_per_head, B*H), block = 256.  Each wave takes 32-token tiles
-// round-robin: a lane owns one token (lane % 32) and one half of the feature channels
-// (lane / 32), loads its part of the Q row with 128-bit loads, applies phi, and feeds it as
-// the B operand of 32x32x16 products against the packed S'^T fragments (A operand), so the
-// accumulator of a lane holds d/2 contiguous output channels of its token plus the two
-// normalizer rows.  out = num * c1 / (den + eps'), rounded to the storage type and written
-// with 128/64-bit stores.  Q is read once, out is written once.
-// ==========================================================================================
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-apply16(const u32x4* __restrict__ Q, unsigned char* __restrict__ O, const unsigned char* __restrict__ packed,
+apply16(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restrict__ state, float eps,
         long long N, int tiles_per_wg) {
   using Sh = Shape16<D>;
+  using Cfg = Apply16Cfg<D>;
   constexpr int NS = NSplit<T>::value;
   constexpr int KS = Sh::kKS, MT2 = Sh::kMT2, CPR = Sh::kChunksPerRow, HALF = Sh::kHalf;
+  constexpr int RS = Cfg::kRS, NL = Cfg::kNL, NE = D * D + D;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const long long bh = blockIdx.y;
   const int tok = lane & 31, kg = lane >> 5;
 
-  const unsigned char* pk = packed + bh * (long long)pack16_bytes<D>(NS);
-  const PackHeader hdr = *reinterpret_cast<const PackHeader*>(pk);
-  const u32x4* fragp = reinterpret_cast<const u32x4*>(pk + sizeof(PackHeader));
+  // ---- prologue: state -> LDS, maxima, scales, A fragments ---------------------------------
+  float* st = reinterpret_cast<float*>(smem);
+  float* redmax = st + NE;                    // [2][kWavesPerWG]
+  float mS = 0.0f, mz = 0.0f;
+  for (int e = threadIdx.x; e < NE; e += kThreads) {
+    float x = state[bh * NE + e];
+    st[e] = x;
+    if (e < D * D) mS = fmaxf(mS, fabsf(x)); else mz = fmaxf(mz, fabsf(x));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    mS = fmaxf(mS, __shfl_xor(mS, o));
+    mz = fmaxf(mz, __shfl_xor(mz, o));
+  }
+  if (lane == 0) { redmax[wave] = mS; redmax[kWavesPerWG + wave] = mz; }
+  __syncthreads();
+  mS = 0.0f; mz = 0.0f;
+#pragma unroll
+  for (int w = 0; w < kWavesPerWG; ++w) { mS = fmaxf(mS, redmax[w]); mz = fmaxf(mz, redmax[kWavesPerWG + w]); }
+  const float aS = pow2_scale_for(mS);
+  const float az = NORM ? pow2_scale_for(mz) : 1.0f;
+  const float c1 = az / aS;
+  const float eps_s = eps * az;
+
   u32x4 A[NS][MT2][KS];
+  {
+    const int m = lane & 31;
+    const int hv = (m >> 2) & 1;
 #pragma unroll
-  for (int lv = 0; lv < NS; ++lv)
+    for (int t = 0; t < MT2; ++t) {
+      const int slot = 16 * t + 4 * (m >> 3) + (m & 3);
 #pragma unroll
-    for (int t = 0; t < MT2; ++t)
+      for (int s = 0; s < KS; ++s) {
+        const int chunk = kg * KS + s;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) A[lv][t][s] = fragp[((lv * MT2 + t) * KS + s) * 64 + lane];
+        for (int w = 0; w < 4; ++w) {
+          float hi2[2], lo2[2];
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int ch = chunk * 8 + 2 * w + q;
+            float x = 0.0f;
+            bool zrem = false;
+            if (chunk < CPR) {
+              if (slot < HALF) x = st[ch * D + hv * HALF + slot] * aS;
+              else if (NORM && slot == HALF) x = st[D * D + ch] * az;
+              else if (NORM && slot == HALF + 1) { x = st[D * D + ch] * az; zrem = true; }
+            }
+            float r0, r1;
+            unpack2<T>(pack2<T>(x, 0.0f), r0, r1);     // x rounded once to 16 bits
+            hi2[q] = zrem ? x - r0 : x;
+            lo2[q] = (slot < HALF) ? x - r0 : 0.0f;    // S' remainder -> lo fragment (bf16 only)
+          }
+          A[0][t][s][w] = pack2<T>(hi2[0], hi2[1]);
+          if constexpr (NS == 2) A[1][t][s][w] = pack2<T>(lo2[0], lo2[1]);
+        }
+      }
+    }
+  }
+  __syncthreads();   // state in LDS no longer needed: the space becomes the waves' tiles
+
+  // ---- stream loop ---------------------------------------------------------------------------------
+  uint16_t* tileH = reinterpret_cast<uint16_t*>(smem) + wave * NS * Cfg::kTileElems;
+  uint16_t* tileL = tileH + Cfg::kTileElems;   // only touched when NS == 2
+  int lds_off[NL];
+#pragma unroll
+  for (int u = 0; u < NL; ++u) {
+    int c = u * 64 + lane;
+    lds_off[u] = (c / CPR) * RS + (c % CPR) * 8;
+  }
+  const int row_off = tok * RS;
 
   const long long n_tiles = (N + kTile - 1) / kTile;
   long long t_begin = (long long)blockIdx.x * tiles_per_wg;
   long long t_end = t_begin + tiles_per_wg;
   if (t_end > n_tiles) t_end = n_tiles;
-
   const u32x4* Qh = Q + bh * N * CPR;
-  unsigned char* Oh = O + bh * N * (long long)(D * 2);
+  u32x4* Oh = O + bh * N * CPR;
 
-  u32x4 qr[KS];
+  u32x4 qr[NL];
   auto issue_loads = [&](long long tile) {
-    const long long t = tile * kTile + tok;
-    const u32x4* row = Qh + t * CPR + kg * KS;
+    long long rem = (N - tile * kTile) * CPR;
+    int lim = rem < Cfg::kChunks ? (int)rem : Cfg::kChunks;
+    const u32x4* qp = Qh + tile * Cfg::kChunks;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      if (t < N && kg * KS + s < CPR) qr[s] = ld_stream(row + s);
-      else qr[s] = u32x4{0, 0, 0, 0};
+    for (int u = 0; u < NL; ++u) {
+      int c = u * 64 + lane;
+      if (c < lim) qr[u] = ld_stream(qp + c);
+      else qr[u] = u32x4{0, 0, 0, 0};
     }
+    return lim;
   };
 
   long long tile = t_begin + wave;
-  if (tile < t_end) issue_loads(tile);
+  int lim = 0;
+  if (tile < t_end) lim = issue_loads(tile);
   while (tile < t_end) {
-    // phi(Q) -> 16-bit operand(s)
+    // phi(Q) -> 16-bit -> LDS (coalesced layout in, token-per-lane layout out)
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      int c = u * 64 + lane;
+      if (c < Cfg::kChunks) {
+        u32x4 ph, pl;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1;
+          unpack2<T>(qr[u][w], x0, x1);
+          float r0 = phi<FM>(x0), r1 = phi<FM>(x1);
+          if constexpr (NS == 1) {
+            ph[w] = pack2<T>(r0, r1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(r0, r1, h, l);
+            ph[w] = h;
+            pl[w] = l;
+          }
+        }
+        *reinterpret_cast<u32x4*>(tileH + lds_off[u]) = ph;
+        if constexpr (NS == 2) *reinterpret_cast<u32x4*>(tileL + lds_off[u]) = pl;
+      }
+    }
+    const long long cur = tile;
+    const int cur_lim = lim;
+    tile += kWavesPerWG;
+    if (tile < t_end) lim = issue_loads(tile);
+
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     u32x4 Bh[KS], Bl[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       const bool ok = kg * KS + s < CPR;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        float x0, x1;
-        unpack2<T>(qr[s][w], x0, x1);
-        float r0 = ok ? phi<FM>(x0) : 0.0f;
-        float r1 = ok ? phi<FM>(x1) : 0.0f;
-        if constexpr (NS == 1) {
-          Bh[s][w] = pack2<T>(r0, r1);
-        } else {
-          uint32_t h, l;
-          pack2_split<T>(r0, r1, h, l);
-          Bh[s][w] = h;
-          Bl[s][w] = l;
-        }
-      }
+      const int off = row_off + (kg * KS + s) * 8;
+      Bh[s] = ok ? *reinterpret_cast<const u32x4*>(tileH + off) : u32x4{0, 0, 0, 0};
+      if constexpr (NS == 2) Bl[s] = ok ? *reinterpret_cast<const u32x4*>(tileL + off) : u32x4{0, 0, 0, 0};
     }
-    const long long cur = tile;
-    tile += kWavesPerWG;
-    if (tile < t_end) issue_loads(tile);
 
     f32x16 acc[MT2];
 #pragma unroll
@@ -419,43 +462,51 @@ apply16(const u32x4* __restrict__ Q, unsigned char* __restrict__ O, const unsign
         acc[t] = mfma_32x32x16<T>(A[0][t][s], Bh[s], acc[t]);
         if constexpr (NS == 2) {
           acc[t] = mfma_32x32x16<T>(A[0][t][s], Bl[s], acc[t]);
-          acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);
+          if (16 * t < HALF) acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);   // lo rows are zero beyond S'
         }
       }
     }
-    // normalizer: slots HALF (z hi) and HALF+1 (z lo) of this lane's accumulators
-    float scale = hdr.c1;
+    // normalizer: slots HALF (z' rounded) and HALF+1 (its remainder) of this lane's accumulators
+    float scale = c1;
     if constexpr (NORM) {
-      const float den = acc[HALF / 16][HALF % 16] + acc[(HALF + 1) / 16][(HALF + 1) % 16] + hdr.eps_s;
-      scale = hdr.c1 * __builtin_amdgcn_rcpf(den);
+      const float den = acc[HALF / 16][HALF % 16] + acc[(HALF + 1) / 16][(HALF + 1) % 16] + eps_s;
+      scale = c1 * __builtin_amdgcn_rcpf(den);
     }
-    const long long t = cur * kTile + tok;
-    if (t < N) {
-      unsigned char* orow = Oh + t * (long long)(D * 2) + kg * (HALF * 2);
-      if constexpr ((HALF * 2) % 16 == 0) {
+    // this lane's d/2 channels of its token -> 16-bit -> LDS row (rows that hold no token of the
+    // ragged last tile are written too but never stored)
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    uint16_t* orow = tileH + row_off + kg * HALF;
+    if constexpr ((HALF * 2) % 16 == 0) {
 #pragma unroll
-        for (int c = 0; c < HALF / 8; ++c) {
-          u32x4 w;
+      for (int c = 0; c < HALF / 8; ++c) {
+        u32x4 w;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int s0 = c * 8 + 2 * e;
-            w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
-          }
-          st_stream(reinterpret_cast<u32x4*>(orow) + c, w);
+        for (int e = 0; e < 4; ++e) {
+          const int s0 = c * 8 + 2 * e;
+          w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
         }
-      } else {
+        *reinterpret_cast<u32x4*>(orow + c * 8) = w;
+      }
+    } else {
 #pragma unroll
-        for (int c = 0; c < HALF / 4; ++c) {
-          u32x2 w;
+      for (int c = 0; c < HALF / 4; ++c) {
+        u32x2 w;
 #pragma unroll
-          for (int e = 0; e < 2; ++e) {
-            const int s0 = c * 4 + 2 * e;
-            w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
-          }
-          st_stream(reinterpret_cast<u32x2*>(orow) + c, w);
+        for (int e = 0; e < 2; ++e) {
+          const int s0 = c * 4 + 2 * e;
+          w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
         }
+        *reinterpret_cast<u32x2*>(orow + c * 4) = w;
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    u32x4* op = Oh + cur * Cfg::kChunks;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      int c = u * 64 + lane;
+      if (c < cur_lim) st_stream(op + c, *reinterpret_cast<const u32x4*>(tileH + lds_off[u]));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
   }
 }
 

@@ -2,7 +2,7 @@
 // d x d contractions use the fp32 matrix-core instruction (16x16x4), whose operand layout
 // holds one contraction index per lane, so no transposition is needed anywhere.
 //   state_reduce32  S_p, z_p over a chunk of tokens            (Prop. 2: g'(X)^T X; Eq. 5: Z)
-//   combine_pack32  fixed-order sum of the partials, pack for apply
+//   combine_state   (shared with the 16-bit path) fixed-order sum of the partials
 //   apply32         out_i = phi(q_i) S / (phi(q_i).z + eps)
 #pragma once
 #include "lf_common.hpp"
@@ -20,11 +20,6 @@ template <int D> struct Shape32 {
   static constexpr int kQuarter = D / 4;                    // output channels per 16-lane group
   static constexpr int kMT = (kQuarter + 1 + 3) / 4;        // 16-row output tiles incl. normalizer row
 };
-
-constexpr int pack32_bytes(int d) {
-  int chunks = d / 4, cs = (chunks + 3) / 4, mt = (d / 4 + 1 + 3) / 4;
-  return (int)sizeof(PackHeader) + mt * cs * 4 * 64 * 4;
-}
 
 LF_DEV f32x4 mfma_16x16x4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
 
@@ -138,86 +133,45 @@ state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* 
 }
 
 // ------------------------------------------------------------------------------------------
-// grid = B*H, block = 512.  Packed layout per head: PackHeader, then [tile T][k-step ks][lane]
-// floats.  k-step ks = 4*cs + e; lane l: output row mrow = l % 16, kq = l / 16:
+// grid = (wgs_per_head, B*H), block = 256.  Lane (token = lane % 16, kq = lane / 16) loads its
+// kCS contiguous float4 chunks of the Q row; element e of chunk cs is the B operand of k-step
+// 4*cs + e against S^T (A operand), which every lane gathers once from the head's fp32 state:
+// lane l (output row mrow = l % 16, kq = l / 16), tile T, k-step 4*cs + e:
 //   feature channel ch = 4*(kq*CS + cs) + e  (zero when that chunk is beyond d)
 //   slot = 4*T + mrow % 4, group g = mrow / 4:  slot < d/4 -> S[ch][g*d/4 + slot];
 //   slot == d/4 -> z[ch];  else 0.
-// ------------------------------------------------------------------------------------------
-template <int D>
-__global__ void __launch_bounds__(kCombineThreads)
-combine_pack32(const float* __restrict__ partials, int splits, float eps, int unnormalized,
-               unsigned char* __restrict__ packed, float* __restrict__ state_out) {
-  using Sh = Shape32<D>;
-  constexpr int NE = D * D + D;
-  __shared__ float st[NE];
-  const long long bh = blockIdx.x;
-  const float* src = partials + bh * splits * (long long)NE;
-  for (int e = threadIdx.x; e < NE; e += kCombineThreads) {
-    float s = 0.0f;
-    int p = 0;
-    for (; p + 4 <= splits; p += 4) {
-      float a0 = src[(long long)(p + 0) * NE + e], a1 = src[(long long)(p + 1) * NE + e];
-      float a2 = src[(long long)(p + 2) * NE + e], a3 = src[(long long)(p + 3) * NE + e];
-      s = (((s + a0) + a1) + a2) + a3;
-    }
-    for (; p < splits; ++p) s += src[(long long)p * NE + e];
-    st[e] = s;
-    if (state_out) state_out[bh * NE + e] = s;
-  }
-  if (!packed) return;
-  __syncthreads();
-  unsigned char* dstb = packed + bh * (long long)pack32_bytes(D);
-  if (threadIdx.x == 0) {
-    PackHeader h;
-    h.c1 = 1.0f;
-    h.eps_s = eps;
-    h.pad[0] = h.pad[1] = 0.0f;
-    *reinterpret_cast<PackHeader*>(dstb) = h;
-  }
-  float* frag = reinterpret_cast<float*>(dstb + sizeof(PackHeader));
-  constexpr int kWords = Sh::kMT * Sh::kKSteps * 64;
-  for (int wi = threadIdx.x; wi < kWords; wi += kCombineThreads) {
-    const int l = wi & 63;
-    const int f = wi >> 6;
-    const int T_ = f / Sh::kKSteps, ks = f % Sh::kKSteps;
-    const int cs = ks >> 2, e = ks & 3;
-    const int mrow = l & 15, kq = l >> 4;
-    const int chunk = kq * Sh::kCS + cs;
-    const int slot = 4 * T_ + (mrow & 3), g = mrow >> 2;
-    float x = 0.0f;
-    if (chunk < Sh::kChunks) {
-      const int ch = 4 * chunk + e;
-      if (slot < Sh::kQuarter) x = st[ch * D + g * Sh::kQuarter + slot];
-      else if (slot == Sh::kQuarter && !unnormalized) x = st[D * D + ch];
-    }
-    frag[wi] = x;
-  }
-}
-
-// ------------------------------------------------------------------------------------------
-// grid = (wgs_per_head, B*H), block = 256.  Lane (token = lane % 16, kq = lane / 16) loads its
-// kCS contiguous float4 chunks of the Q row; element e of chunk cs is the B operand of k-step
-// 4*cs + e against the packed S^T fragment (A operand).  The accumulators of a lane hold d/4
-// contiguous output channels of its token and the normalizer phi(q).z.
+// The accumulators of a lane hold d/4 contiguous output channels of its token and the
+// normalizer phi(q).z.
 // ------------------------------------------------------------------------------------------
 template <int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const unsigned char* __restrict__ packed,
+apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const float* __restrict__ state, float eps,
         long long N, int tiles_per_wg) {
   using Sh = Shape32<D>;
   constexpr int CS = Sh::kCS, KST = Sh::kKSteps, MT = Sh::kMT, CH = Sh::kChunks, QT = Sh::kQuarter;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int tok = lane & 15, kq = lane >> 4;
   const long long bh = blockIdx.y;
-  const unsigned char* pk = packed + bh * (long long)pack32_bytes(D);
-  const PackHeader hdr = *reinterpret_cast<const PackHeader*>(pk);
-  const float* fragp = reinterpret_cast<const float*>(pk + sizeof(PackHeader));
+  const float* sth = state + bh * (long long)(D * D + D);
   float A[MT][KST];
+  {
+    const int mrow = lane & 15, g = mrow >> 2;
 #pragma unroll
-  for (int t = 0; t < MT; ++t)
+    for (int t = 0; t < MT; ++t) {
+      const int slot = 4 * t + (mrow & 3);
 #pragma unroll
-    for (int ks = 0; ks < KST; ++ks) A[t][ks] = fragp[(t * KST + ks) * 64 + lane];
+      for (int ks = 0; ks < KST; ++ks) {
+        const int chunk = kq * CS + (ks >> 2);
+        const int ch = 4 * chunk + (ks & 3);
+        float x = 0.0f;
+        if (chunk < CH) {
+          if (slot < QT) x = sth[ch * D + g * QT + slot];
+          else if (NORM && slot == QT) x = sth[D * D + ch];
+        }
+        A[t][ks] = x;
+      }
+    }
+  }
 
   const long long n_tiles = (N + kTile32 - 1) / kTile32;
   long long t_begin = (long long)blockIdx.x * tiles_per_wg;
@@ -254,8 +208,8 @@ apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const unsigned char*
 #pragma unroll
       for (int ks = 0; ks < KST; ++ks) acc[t] = mfma_16x16x4(A[t][ks], r[ks], acc[t]);
     }
-    float scale = hdr.c1;
-    if constexpr (NORM) scale = 1.0f / (acc[QT / 4][QT % 4] + hdr.eps_s);
+    float scale = 1.0f;
+    if constexpr (NORM) scale = 1.0f / (acc[QT / 4][QT % 4] + eps);
     const long long t = cur * kTile32 + tok;
     if (t < N) {
       float* orow = Oh + t * (long long)D + kq * QT;
@@ -280,23 +234,27 @@ apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const unsigned char*
 template <int D>
 hipError_t run32(const float* q, const float* k, const float* v, float* out, long long BH, long long N, int fm,
                  float eps, bool unnorm, int splits, int tiles_per_split, int apply_wgs, int tiles_per_wg,
-                 float* partials, unsigned char* packed, float* state_out, hipStream_t st) {
+                 float* partials, float* state, hipStream_t st, hipEvent_t* ev) {
   const dim3 g1(splits, (unsigned)BH), blk(kThreads);
   const f32x4* K = (const f32x4*)k;
   const f32x4* V = (const f32x4*)v;
+  if (ev) (void)hipEventRecord(ev[0], st);
   switch (fm) {
     case 0: state_reduce32<D, 0><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
     case 1: state_reduce32<D, 1><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
     default: state_reduce32<D, 2><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
   }
-  combine_pack32<D><<<dim3((unsigned)BH), dim3(kCombineThreads), 0, st>>>(partials, splits, eps, unnorm ? 1 : 0,
-                                                                          out ? packed : nullptr, state_out);
+  if (ev) (void)hipEventRecord(ev[1], st);
+  constexpr int NE = D * D + D;
+  combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, st>>>(
+      partials, splits, NE, state);
+  if (ev) (void)hipEventRecord(ev[2], st);
   if (out) {
     const dim3 g2(apply_wgs, (unsigned)BH);
     const f32x4* Q = (const f32x4*)q;
 #define LF_APPLY32(FM)                                                                   \
-  if (unnorm) apply32<D, FM, false><<<g2, blk, 0, st>>>(Q, out, packed, N, tiles_per_wg); \
-  else apply32<D, FM, true><<<g2, blk, 0, st>>>(Q, out, packed, N, tiles_per_wg);
+  if (unnorm) apply32<D, FM, false><<<g2, blk, 0, st>>>(Q, out, state, eps, N, tiles_per_wg); \
+  else apply32<D, FM, true><<<g2, blk, 0, st>>>(Q, out, state, eps, N, tiles_per_wg);
     switch (fm) {
       case 0: LF_APPLY32(0) break;
       case 1: LF_APPLY32(1) break;
@@ -304,6 +262,7 @@ hipError_t run32(const float* q, const float* k, const float* v, float* out, lon
     }
 #undef LF_APPLY32
   }
+  if (ev) (void)hipEventRecord(ev[3], st);
   return hipGetLastError();
 }
 

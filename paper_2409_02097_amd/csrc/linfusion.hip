@@ -27,9 +27,8 @@ struct Plan {
   int apply_wgs;        // apply workgroups per head
   int tiles_per_wg;
   long long n_tiles;
-  size_t partial_floats;   // per head-split
-  size_t pack_bytes;       // per head
-  size_t ws_partials, ws_pack, ws_total;
+  size_t state_floats;     // d*d + d: one partial, and one head's state
+  size_t ws_partials, ws_state, ws_total;
 };
 
 int env_int(const char* name, int dflt) {
@@ -40,13 +39,6 @@ int env_int(const char* name, int dflt) {
 }
 
 bool supported_d(int d) { return d >= 8 && d <= 64 && d % 8 == 0; }
-
-int pack_bytes_for(int d, int dtype) {
-  if (dtype == LINFUSION_DTYPE_F32) return lf::pack32_bytes(d);
-  const int ns = dtype == LINFUSION_DTYPE_BF16 ? 2 : 1;
-  const int cpr = d / 8, ks = (cpr + 1) / 2, mt2 = (d / 2 + 2 + 15) / 16;
-  return (int)sizeof(lf::PackHeader) + ns * mt2 * ks * 64 * 16;
-}
 
 int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan* p) {
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
@@ -79,12 +71,11 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   a = (p->n_tiles + tpw - 1) / tpw;
   p->apply_wgs = (int)a;
   p->tiles_per_wg = (int)tpw;
-  p->partial_floats = (size_t)d * d + d;
-  p->pack_bytes = (size_t)pack_bytes_for(d, dtype);
+  p->state_floats = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  p->ws_partials = up((size_t)BH * p->splits * p->partial_floats * sizeof(float));
-  p->ws_pack = up((size_t)BH * p->pack_bytes);
-  p->ws_total = p->ws_partials + p->ws_pack;
+  p->ws_partials = up((size_t)BH * p->splits * p->state_floats * sizeof(float));
+  p->ws_state = up((size_t)BH * p->state_floats * sizeof(float));
+  p->ws_total = p->ws_partials + p->ws_state;
   return LINFUSION_OK;
 }
 
@@ -115,28 +106,33 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
 
 template <typename T, int D>
 int run16(const void* q, const void* k, const void* v, void* out, long long BH, long long N, int fm, float eps,
-          bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st) {
+          bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st, hipEvent_t* ev) {
   using namespace lf;
   float* partials = reinterpret_cast<float*>(ws);
-  unsigned char* packed = ws + p.ws_partials;
+  float* state = state_out ? state_out : reinterpret_cast<float*>(ws + p.ws_partials);
+  constexpr int NE = D * D + D;
   const dim3 g1(p.splits, (unsigned)BH), blk(kThreads);
   const size_t lds = reduce16_lds_bytes<T, D>();
   const u32x4* K = (const u32x4*)k;
   const u32x4* V = (const u32x4*)v;
+  if (ev) (void)hipEventRecord(ev[0], st);
   switch (fm) {
     case 0: state_reduce16<T, D, 0><<<g1, blk, lds, st>>>(K, V, partials, N, p.tiles_per_split); break;
     case 1: state_reduce16<T, D, 1><<<g1, blk, lds, st>>>(K, V, partials, N, p.tiles_per_split); break;
     default: state_reduce16<T, D, 2><<<g1, blk, lds, st>>>(K, V, partials, N, p.tiles_per_split); break;
   }
-  combine_pack16<T, D><<<dim3((unsigned)BH), dim3(kCombineThreads), 0, st>>>(
-      partials, p.splits, eps, unnorm ? 1 : 0, out ? packed : nullptr, state_out);
+  if (ev) (void)hipEventRecord(ev[1], st);
+  combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, st>>>(
+      partials, p.splits, NE, state);
+  if (ev) (void)hipEventRecord(ev[2], st);
   if (out) {
     const dim3 g2(p.apply_wgs, (unsigned)BH);
     const u32x4* Q = (const u32x4*)q;
-    unsigned char* O = (unsigned char*)out;
-#define LF_APPLY(FM)                                                                                   \
-  if (unnorm) apply16<T, D, FM, false><<<g2, blk, 0, st>>>(Q, O, packed, N, p.tiles_per_wg);           \
-  else apply16<T, D, FM, true><<<g2, blk, 0, st>>>(Q, O, packed, N, p.tiles_per_wg);
+    u32x4* O = (u32x4*)out;
+    const size_t lds2 = apply16_lds_bytes<T, D>();
+#define LF_APPLY(FM)                                                                                       \
+  if (unnorm) apply16<T, D, FM, false><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);        \
+  else apply16<T, D, FM, true><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);
     switch (fm) {
       case 0: LF_APPLY(0) break;
       case 1: LF_APPLY(1) break;
@@ -144,14 +140,16 @@ int run16(const void* q, const void* k, const void* v, void* out, long long BH, 
     }
 #undef LF_APPLY
   }
+  if (ev) (void)hipEventRecord(ev[3], st);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
 template <typename T>
 int run16_d(int d, const void* q, const void* k, const void* v, void* out, long long BH, long long N, int fm,
-            float eps, bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st) {
+            float eps, bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st,
+            hipEvent_t* ev) {
   switch (d) {
-#define X(DD) case DD: return run16<T, DD>(q, k, v, out, BH, N, fm, eps, unnorm, p, ws, state_out, st);
+#define X(DD) case DD: return run16<T, DD>(q, k, v, out, BH, N, fm, eps, unnorm, p, ws, state_out, st, ev);
     LF_FOR_D(X)
 #undef X
     default: return LINFUSION_ERR_UNSUPPORTED;
@@ -159,15 +157,16 @@ int run16_d(int d, const void* q, const void* k, const void* v, void* out, long 
 }
 
 int run32_d(int d, const void* q, const void* k, const void* v, void* out, long long BH, long long N, int fm,
-            float eps, bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st) {
+            float eps, bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st,
+            hipEvent_t* ev) {
   float* partials = reinterpret_cast<float*>(ws);
-  unsigned char* packed = ws + p.ws_partials;
+  float* state = state_out ? state_out : reinterpret_cast<float*>(ws + p.ws_partials);
   switch (d) {
 #define X(DD)                                                                                             \
   case DD:                                                                                                \
     return lf::run32<DD>((const float*)q, (const float*)k, (const float*)v, (float*)out, BH, N, fm, eps, \
                          unnorm, p.splits, p.tiles_per_split, p.apply_wgs, p.tiles_per_wg, partials,      \
-                         packed, state_out, st) == hipSuccess                                             \
+                         state, st, ev) == hipSuccess                                             \
                ? LINFUSION_OK                                                                             \
                : LINFUSION_ERR_HIP;
     LF_FOR_D(X)
@@ -226,9 +225,9 @@ int fwd_owned(const void* q, const void* k, const void* v, void* out, int B, int
 
 extern "C" {
 
-int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d,
-                          int dtype, int feature_map, float eps, unsigned flags, void* workspace,
-                          size_t workspace_bytes, void* stream) {
+static int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d,
+                    int dtype, int feature_map, float eps, unsigned flags, void* workspace,
+                    size_t workspace_bytes, void* stream, hipEvent_t* ev) {
   if (!q || !out) return LINFUSION_ERR_INVALID;
   if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
   Plan p;
@@ -252,10 +251,24 @@ int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out
   const long long BH = (long long)B * H;
   unsigned char* ws = (unsigned char*)workspace;
   switch (dtype) {
-    case LINFUSION_DTYPE_F16: return run16_d<lf::F16>(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st);
-    case LINFUSION_DTYPE_BF16: return run16_d<lf::BF16>(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st);
-    default: return run32_d(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st);
+    case LINFUSION_DTYPE_F16: return run16_d<lf::F16>(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st, ev);
+    case LINFUSION_DTYPE_BF16: return run16_d<lf::BF16>(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st, ev);
+    default: return run32_d(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st, ev);
   }
+}
+
+int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d,
+                          int dtype, int feature_map, float eps, unsigned flags, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, flags, workspace, workspace_bytes, stream, nullptr);
+}
+
+int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void* out, int B, int H, long long N,
+                               int d, int dtype, int feature_map, float eps, unsigned flags, void* workspace,
+                               size_t workspace_bytes, void* stream, void* events[4]) {
+  if (!events || !events[0] || !events[1] || !events[2] || !events[3]) return LINFUSION_ERR_INVALID;
+  hipEvent_t ev[4] = {(hipEvent_t)events[0], (hipEvent_t)events[1], (hipEvent_t)events[2], (hipEvent_t)events[3]};
+  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, flags, workspace, workspace_bytes, stream, ev);
 }
 
 size_t linfusion_attn_workspace_bytes(int B, int H, long long N, int d, int dtype) {
@@ -280,9 +293,9 @@ int linfusion_attn_state(const void* k, const void* v, float* state_out, int B, 
   const long long BH = (long long)B * H;
   unsigned char* ws = (unsigned char*)workspace;
   switch (dtype) {
-    case LINFUSION_DTYPE_F16: return run16_d<lf::F16>(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st);
-    case LINFUSION_DTYPE_BF16: return run16_d<lf::BF16>(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st);
-    default: return run32_d(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st);
+    case LINFUSION_DTYPE_F16: return run16_d<lf::F16>(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st, nullptr);
+    case LINFUSION_DTYPE_BF16: return run16_d<lf::BF16>(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st, nullptr);
+    default: return run32_d(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st, nullptr);
   }
 }
 
