@@ -94,6 +94,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=1 << 21)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of one tensor (known size) so that a rocprofv3 --pmc "
+                         "run of this command holds the reference reading for FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the hot path is a single-device kernel "
@@ -119,6 +122,9 @@ def main():
     def step():
         lf.linfusion_attn_fwd_ex(q, k, v, out, lf.PHI_ELU_PLUS_ONE, wl.EPS, args.flags, ws)
 
+    if args.calibrate_copy:
+        out.copy_(q)             # reads and writes B*H*N*d*itemsize bytes exactly once each
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -154,6 +160,15 @@ def main():
     roofline = {"bound": "hbm", "kernel": dom["name"], "achieved": dom["gbps"], "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": dom["gbps"] / HBM_PEAK_GBPS, "traffic": None,
                 "avg_launch_ms": dom["ms"], "kernels": kernels}
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if there is one
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            tr = json.load(f)
+        ent = tr.get("kernels", {}).get(dom["name"].split("<")[0])
+        if ent:
+            roofline["traffic"] = ent["hbm_bytes_per_launch"]
+            roofline["traffic_source"] = f"profiles/{os.path.basename(tpath)}"
 
     result = {
         "metric": "non-causal linear-attn tokens/s + achieved HBM GB/s (% of peak), 1 GPU",

@@ -126,6 +126,31 @@ template <int D> struct Shape16 {
   static constexpr int kMT2 = (kHalf + 2 + 15) / 16;   // 32-row output tiles incl. normalizer rows
 };
 
+// ---- which tiles a wave processes -----------------------------------------------------------
+// The tiles of a head are cut into blocks of `blk` consecutive tiles (blk a multiple of the
+// waves per workgroup); workgroup g of G takes blocks g, g + G, g + 2G, ... and inside a block its
+// waves take tiles round-robin.  blk = ceil(n_tiles / G) gives every workgroup one contiguous
+// chunk; a small blk keeps all workgroups of the chip inside one moving window of memory.
+struct TileIter {
+  long long t, blk_end, blk_first, n_tiles, step;
+  int blk, wave;
+  LF_DEV TileIter(int g, int G, int wave_, int blk_, long long n_tiles_)
+      : n_tiles(n_tiles_), step((long long)G * blk_), blk(blk_), wave(wave_) {
+    blk_first = (long long)g * blk;
+    t = blk_first + wave;
+    blk_end = blk_first + blk < n_tiles ? blk_first + blk : n_tiles;
+  }
+  LF_DEV bool valid() const { return t < n_tiles; }
+  LF_DEV void next() {
+    t += 4;
+    if (t >= blk_end) {
+      blk_first += step;
+      t = blk_first + wave;
+      blk_end = blk_first + blk < n_tiles ? blk_first + blk : n_tiles;
+    }
+  }
+};
+
 template <typename T> struct NSplit;                 // operand levels needed to hold an fp32 value
 template <> struct NSplit<F16> { static constexpr int value = 1; };
 template <> struct NSplit<BF16> { static constexpr int value = 2; };

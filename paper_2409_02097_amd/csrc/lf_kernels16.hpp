@@ -12,8 +12,8 @@ constexpr int kThreads = 64 * kWavesPerWG;
 constexpr int kTile = 32;   // tokens per tile, both in the reduction (one 16x16x32 k-step) and in apply
 
 // ==========================================================================================
-// State reduction.  grid = (splits, B*H), block = 256.  Workgroup (split, bh) owns the tiles
-// [split*tiles_per_split, (split+1)*tiles_per_split) of head bh; its four waves take them
+// State reduction.  grid = (splits, B*H), block = 256.  Workgroup (split, bh) owns blocks of
+// tiles_per_block consecutive tiles of head bh (see TileIter); its four waves take them
 // round-robin and each wave streams on its own: global -> registers (128-bit, coalesced over
 // the contiguous tile) -> phi on K -> wave-private LDS tile -> transposing LDS reads give the
 // token-major operands -> 16x16x32 matrix-core products accumulate S (and z through a column
@@ -41,7 +41,7 @@ constexpr int reduce16_lds_bytes() {
 template <typename T, int D, int FM>
 __global__ void __launch_bounds__(kThreads)
 state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* __restrict__ partials,
-               long long N, int tiles_per_split) {
+               long long N, int tiles_per_block) {
   using Sh = Shape16<D>;
   using Cfg = Reduce16Cfg<D>;
   constexpr int NS = NSplit<T>::value;
@@ -49,7 +49,7 @@ state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* 
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int split = blockIdx.x;
   const long long bh = blockIdx.y;
 
@@ -79,9 +79,7 @@ state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* 
   const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
 
   const long long n_tiles = (N + kTile - 1) / kTile;
-  long long t_begin = (long long)split * tiles_per_split;
-  long long t_end = t_begin + tiles_per_split;
-  if (t_end > n_tiles) t_end = n_tiles;
+  TileIter it(split, gridDim.x, wave, tiles_per_block, n_tiles);
 
   const u32x4* Kh = K + bh * N * CPR;
   const u32x4* Vh = V + bh * N * CPR;
@@ -118,12 +116,10 @@ state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* 
     return lim;
   };
 
-  long long tile = t_begin + wave;
   int lim = 0;
-  if (tile < t_end) lim = issue_loads(tile);
-  __builtin_amdgcn_s_waitcnt(0);  // LDS fill done before data writes (same wave, in order anyway)
+  if (it.valid()) lim = issue_loads(it.t);
 
-  while (tile < t_end) {
+  while (it.valid()) {
     // ---- phi(K) -> 16-bit (hi [, lo]) -> LDS ; V -> LDS --------------------------------------
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
@@ -152,9 +148,9 @@ state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* 
       }
     }
     // ---- prefetch the wave's next tile while this one is multiplied -------------------------
-    const long long next = tile + kWavesPerWG;
+    it.next();
     int next_lim = 0;
-    if (next < t_end) next_lim = issue_loads(next);
+    if (it.valid()) next_lim = issue_loads(it.t);
 
     // ---- token-major operands by transposing LDS reads, then the outer products -------------
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -178,7 +174,6 @@ state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* 
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    tile = next;
     lim = next_lim;
   }
 
@@ -306,7 +301,7 @@ constexpr int apply16_lds_bytes() {
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
 apply16(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restrict__ state, float eps,
-        long long N, int tiles_per_wg) {
+        long long N, int tiles_per_block) {
   using Sh = Shape16<D>;
   using Cfg = Apply16Cfg<D>;
   constexpr int NS = NSplit<T>::value;
@@ -314,7 +309,7 @@ apply16(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restr
   constexpr int RS = Cfg::kRS, NL = Cfg::kNL, NE = D * D + D;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const long long bh = blockIdx.y;
   const int tok = lane & 31, kg = lane >> 5;
 
@@ -390,9 +385,7 @@ apply16(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restr
   const int row_off = tok * RS;
 
   const long long n_tiles = (N + kTile - 1) / kTile;
-  long long t_begin = (long long)blockIdx.x * tiles_per_wg;
-  long long t_end = t_begin + tiles_per_wg;
-  if (t_end > n_tiles) t_end = n_tiles;
+  TileIter it(blockIdx.x, gridDim.x, wave, tiles_per_block, n_tiles);
   const u32x4* Qh = Q + bh * N * CPR;
   u32x4* Oh = O + bh * N * CPR;
 
@@ -410,10 +403,9 @@ apply16(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restr
     return lim;
   };
 
-  long long tile = t_begin + wave;
   int lim = 0;
-  if (tile < t_end) lim = issue_loads(tile);
-  while (tile < t_end) {
+  if (it.valid()) lim = issue_loads(it.t);
+  while (it.valid()) {
     // phi(Q) -> 16-bit -> LDS (coalesced layout in, token-per-lane layout out)
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
@@ -438,10 +430,10 @@ apply16(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restr
         if constexpr (NS == 2) *reinterpret_cast<u32x4*>(tileL + lds_off[u]) = pl;
       }
     }
-    const long long cur = tile;
+    const long long cur = it.t;
     const int cur_lim = lim;
-    tile += kWavesPerWG;
-    if (tile < t_end) lim = issue_loads(tile);
+    it.next();
+    if (it.valid()) lim = issue_loads(it.t);
 
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     u32x4 Bh[KS], Bl[KS];

@@ -12,6 +12,7 @@
 #include <mutex>
 
 #include "lf_kernels16.hpp"
+#include "lf_apply16_dma.hpp"
 #include "lf_kernels32.hpp"
 
 namespace {
@@ -23,9 +24,9 @@ constexpr int kMaxDevices = 16;
 struct Plan {
   int path;             // 0 = split-N three-kernel path, 1 = fused single launch
   int splits;           // state-reduction workgroups per head
-  int tiles_per_split;
+  int tiles_per_split;  // tiles per contiguous block of a reduction workgroup
   int apply_wgs;        // apply workgroups per head
-  int tiles_per_wg;
+  int tiles_per_wg;     // tiles per contiguous block of an apply workgroup
   long long n_tiles;
   size_t state_floats;     // d*d + d: one partial, and one head's state
   size_t ws_partials, ws_state, ws_total;
@@ -36,6 +37,14 @@ int env_int(const char* name, int dflt) {
   if (!s || !*s) return dflt;
   int v = atoi(s);
   return v > 0 ? v : dflt;
+}
+
+// tiles per contiguous block of a workgroup, at most its whole share, rounded up to a multiple of
+// the waves per workgroup; the environment override is a tuning aid
+int block_tiles(int share, const char* env, int dflt) {
+  int b = env_int(env, dflt);
+  if (b > share) b = share;
+  return (b + lf::kWavesPerWG - 1) / lf::kWavesPerWG * lf::kWavesPerWG;
 }
 
 bool supported_d(int d) { return d >= 8 && d <= 64 && d % 8 == 0; }
@@ -53,8 +62,9 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   const int tile = dtype == LINFUSION_DTYPE_F32 ? lf::kTile32 : lf::kTile;
   p->n_tiles = (N + tile - 1) / tile;
   p->path = 0;
-  // state reduction: about four resident workgroups per CU on 256 CUs, at least one tile per wave
-  const int want1 = env_int("LINFUSION_REDUCE_WGS", 1024);
+  // state reduction (read-only stream): two workgroups per CU on 256 CUs measured best -- fewer,
+  // longer streams keep DRAM pages open; at least one tile per wave
+  const int want1 = env_int("LINFUSION_REDUCE_WGS", 512);
   long long s = (want1 + BH - 1) / BH;
   long long max_s = (p->n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;
   if (s > max_s) s = max_s;
@@ -62,15 +72,16 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   long long tps = (p->n_tiles + s - 1) / s;
   s = (p->n_tiles + tps - 1) / tps;
   p->splits = (int)s;
-  p->tiles_per_split = (int)tps;
-  const int want2 = env_int("LINFUSION_APPLY_WGS", 1024);
+  p->tiles_per_split = block_tiles((int)tps, "LINFUSION_REDUCE_BLK", 16);
+  // apply (read + write streams): more, smaller workgroups that sweep memory in one moving window
+  const int want2 = env_int("LINFUSION_APPLY_WGS", 2048);
   long long a = (want2 + BH - 1) / BH;
   if (a > max_s) a = max_s;
   if (a < 1) a = 1;
   long long tpw = (p->n_tiles + a - 1) / a;
   a = (p->n_tiles + tpw - 1) / tpw;
   p->apply_wgs = (int)a;
-  p->tiles_per_wg = (int)tpw;
+  p->tiles_per_wg = block_tiles((int)tpw, "LINFUSION_APPLY_BLK", 8);
   p->state_floats = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   p->ws_partials = up((size_t)BH * p->splits * p->state_floats * sizeof(float));
@@ -129,9 +140,13 @@ int run16(const void* q, const void* k, const void* v, void* out, long long BH, 
     const dim3 g2(p.apply_wgs, (unsigned)BH);
     const u32x4* Q = (const u32x4*)q;
     u32x4* O = (u32x4*)out;
-    const size_t lds2 = apply16_lds_bytes<T, D>();
+    const bool dma = env_int("LINFUSION_APPLY_IMPL", 2) == 2;
+    const size_t lds2 = dma ? apply16_dma_lds_bytes<T, D>() : apply16_lds_bytes<T, D>();
 #define LF_APPLY(FM)                                                                                       \
-  if (unnorm) apply16<T, D, FM, false><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);        \
+  if (dma) {                                                                                               \
+    if (unnorm) apply16_dma<T, D, FM, false><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);  \
+    else apply16_dma<T, D, FM, true><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);          \
+  } else if (unnorm) apply16<T, D, FM, false><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg); \
   else apply16<T, D, FM, true><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);
     switch (fm) {
       case 0: LF_APPLY(0) break;

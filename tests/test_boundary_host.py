@@ -1,0 +1,104 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2409_02097_amd as lf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "linfusion.h")
+
+
+def _declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(linfusion_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    syms = _declared_symbols()
+    for name in ("linfusion_attn_fwd", "linfusion_attn_fwd_ex", "linfusion_attn_workspace_bytes",
+                 "linfusion_attn_state", "linfusion_status_string", "linfusion_version"):
+        assert name in syms
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(lf.library_path()) if os.path.exists(lf.library_path()) else lf.library()
+    for name in _declared_symbols():
+        assert hasattr(lib, name), f"{name} declared in linfusion.h but not exported"
+
+
+def test_version_and_status_strings():
+    assert lf.linfusion_version() >= 100
+    seen = set()
+    for code in range(0, -8, -1):
+        s = lf.linfusion_status_string(code)
+        assert s and s != "unknown status" and s not in seen
+        seen.add(s)
+    assert lf.linfusion_status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes_is_a_pure_function_of_the_shape():
+    a = lf.linfusion_attn_workspace_bytes(1, 8, 2097152, 40, lf.DTYPE_F16)
+    assert a == lf.linfusion_attn_workspace_bytes(1, 8, 2097152, 40, lf.DTYPE_F16) and a > 0
+    plan = lf.linfusion_attn_plan(1, 8, 2097152, 40, lf.DTYPE_F16)
+    need = 8 * (plan["reduce_wgs_per_head"] + 1) * (40 * 40 + 40) * 4
+    assert need <= a <= need + 1024
+    # rejected arguments need no workspace
+    assert lf.linfusion_attn_workspace_bytes(1, 8, 1024, 12, lf.DTYPE_F16) == 0
+    assert lf.linfusion_attn_workspace_bytes(0, 8, 1024, 40, lf.DTYPE_F16) == 0
+    assert lf.linfusion_attn_workspace_bytes(1, 8, 1024, 40, 7) == 0
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 8, 1024, 40, 0), (2, 8, 4096, 40, 1), (2, 5, 9216, 64, 1),
+                                          (2, 10, 16384, 64, 2), (2, 20, 4096, 64, 2), (1, 8, 2097152, 40, 1),
+                                          (1, 1, 1, 8, 1), (1, 1, 31, 64, 0)])
+def test_plan_covers_every_token_tile(B, H, N, d, dtype):
+    plan = lf.linfusion_attn_plan(B, H, N, d, dtype)
+    tile = plan["tile_tokens"]
+    n_tiles = -(-N // tile)
+    assert 1 <= plan["reduce_wgs_per_head"] <= n_tiles
+    assert 1 <= plan["apply_wgs_per_head"] <= n_tiles
+    assert plan["path"] in (0, 1)
+
+
+def _call(q=4096, k=1 << 20, v=2 << 20, out=3 << 20, B=1, H=2, N=64, d=40, dtype=1, fm=0, eps=1e-6, flags=0,
+          ws=8 << 20, ws_bytes=1 << 20):
+    """Raw C call with fake (never dereferenced) device addresses: every check below fails on the host."""
+    return lf.library().linfusion_attn_fwd_ex(q, k, v, out, B, H, N, d, dtype, fm, eps, flags, ws, ws_bytes, None)
+
+
+def test_argument_validation_happens_on_the_host():
+    assert _call(q=None) == -1 and _call(k=None) == -1 and _call(v=None) == -1 and _call(out=None) == -1
+    assert _call(B=0) == -1 and _call(H=-1) == -1 and _call(N=0) == -1 and _call(d=0) == -1
+    assert _call(eps=-1.0) == -1 and _call(eps=float("nan")) == -1 and _call(eps=float("inf")) == -1
+    assert _call(flags=1 << 9) == -1 and _call(flags=2 | 4) == -1
+    assert _call(d=12) == -2 and _call(d=72) == -2 and _call(dtype=3) == -2 and _call(fm=5) == -2
+    assert _call(q=4096 + 8) == -3 and _call(out=(3 << 20) + 2) == -3 and _call(ws=(8 << 20) + 4) == -3
+    assert _call(ws=None) == -4 and _call(ws_bytes=16) == -4
+    assert _call(out=1 << 20) == -7                      # out aliases k
+    assert _call(out=(2 << 20) + 64) == -7               # out overlaps v partially
+    assert _call(q=4096, out=4096 + 160) == -7           # partial overlap with q
+    assert _call(ws=3 << 20) == -7                       # workspace overlaps out
+
+
+def test_valid_call_without_a_gfx950_device_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present; the no-device error path is a CPU-box check")
+    assert _call() == -6
+    assert _call(q=4096, out=4096) == -6                 # exact in-place alias passes validation
+    rc = lf.library().linfusion_attn_fwd(4096, 1 << 20, 2 << 20, 3 << 20, 1, 2, 64, 40, 0, 1e-6, None)
+    assert rc == -6
+    st = lf.library().linfusion_attn_state(1 << 20, 2 << 20, 3 << 20, 1, 2, 64, 40, 1, 0, 8 << 20, 1 << 20, None)
+    assert st == -6
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 1, 8, 8, dtype=torch.float16)
+    with pytest.raises(ValueError):
+        lf.linfusion_attn_fwd_ex(x, x, x, x.clone(), 0, 1e-6, 0, None)
