@@ -87,10 +87,10 @@ def cpu_baseline(q, k, v, cfg, sample_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=25)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
-    ap.add_argument("--profile-steps", type=int, default=10)
+    ap.add_argument("--profile-steps", type=int, default=20)
     ap.add_argument("--cpu-sample-tokens", type=int, default=1 << 21)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
@@ -147,12 +147,13 @@ def main():
             acc[i] += evs.elapsed_ms(i, i + 1)
     evs.close()
     kms = [a / max(args.profile_steps, 1) for a in acc]
-    sfx = {"f16": "16<F16", "bf16": "16<BF16", "f32": "32<"}[dtype]
+    rname, aname = {"f16": ("state_reduce16<F16", "apply16_dma<F16"), "bf16": ("state_reduce16<BF16", "apply16_dma<BF16"),
+                    "f32": ("state_reduce32", "apply32")}[dtype]
     half = alg_bytes / 2      # K+V read by the reduction; Q read + out written by apply
     kernels = [
-        {"name": f"state_reduce{sfx}", "ms": kms[0], "alg_bytes": half},
+        {"name": rname, "ms": kms[0], "alg_bytes": half},
         {"name": "combine_state", "ms": kms[1], "alg_bytes": 0},
-        {"name": f"apply{sfx}", "ms": kms[2], "alg_bytes": half},
+        {"name": aname, "ms": kms[2], "alg_bytes": half},
     ]
     for kk in kernels:
         kk["gbps"] = kk["alg_bytes"] / (kk["ms"] * 1e-3) / 1e9 if kk["ms"] > 0 else None
