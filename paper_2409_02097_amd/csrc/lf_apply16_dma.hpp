@@ -1,8 +1,23 @@
 // Apply + normalize for fp16 / bf16 with asynchronous global->LDS tile loads.
 //   out_i = phi(q_i) S / (phi(q_i).z + eps)                     (Eq. 5 normalizer on Prop. 2's form)
 //
-// grid = (wgs_per_head, B*H), block = 256, dynamic LDS.  Same operand layout and prologue as
-// apply16 (see lf_kernels16.hpp); what differs is how a Q tile reaches the lanes:
+// grid = (wgs_per_head, B*H), block = 256, dynamic LDS.
+//
+// Prologue (once per workgroup): the head's fp32 state is staged in LDS, rescaled by powers of
+// two so that 16-bit storage neither overflows nor loses small entries (S' = alpha_S S,
+// z' = alpha_z z), and every lane builds its matrix-core A operands (S'^T and the normalizer
+// rows) in registers.  Fragment (T, s), lane l: output row m = l % 32, contraction group
+// kg = l / 32, element j:
+//   feature channel  ch   = (kg * KS + s) * 8 + j           (zero when that chunk is beyond d)
+//   output slot      slot = 16 T + 4 (m / 8) + (m % 4),  half hv = (m / 4) % 2
+//   slot <  d/2   -> S'[ch][hv * d/2 + slot];  slot == d/2 -> z' rounded to 16 bits;
+//   slot == d/2+1 -> the remainder of z' after that rounding;  else 0.
+// bf16 carries S' as hi + lo fragments (three products per step) to keep ~16 significant bits.
+// The output is computed transposed (out^T = S'^T phi(Q)^T, 32x32x16 products) so that a lane's
+// accumulators hold d/2 contiguous output channels of its token plus the two normalizer rows:
+// out = num * c1 / (den + eps'), c1 = alpha_z / alpha_S, eps' = eps alpha_z.
+//
+// Stream loop: how a Q tile reaches the lanes:
 //   * each wave owns a ring of kRing LDS slots; a tile (32 tokens, contiguous in memory) is copied
 //     into a slot by `global_load_lds_dwordx4` (lane l of load u deposits 16 bytes at slot + 1024 u
 //     + 16 l), so tiles in flight occupy LDS, not registers, and kRing-1 tiles are always in flight;
@@ -20,7 +35,7 @@
 // unconditionally (partial lane masks, clamped addresses) so that n is a compile-time constant in
 // the steady state; the last kRing-1 tiles of a wave simply wait for everything.
 #pragma once
-#include "lf_kernels16.hpp"
+#include "lf_reduce16.hpp"
 
 namespace lf {
 
@@ -48,28 +63,28 @@ constexpr int apply16_dma_lds_bytes() {
 
 template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
+// `state`: this head's [D*D + D] fp32 state.  `smem`: apply16_dma_lds_bytes<T,D>() bytes of LDS that no
+// thread of the workgroup is still using.  Workgroup `wg` of `nwg` of head `bh`.
 template <typename T, int D, int FM, bool NORM>
-__global__ void __launch_bounds__(kThreads)
-apply16_dma(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restrict__ state, float eps,
-            long long N, int tiles_per_block) {
+LF_DEV void apply16_dma_phase(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* state, float eps,
+                              long long N, int tiles_per_block, int wg, int nwg, long long bh,
+                              unsigned char* smem) {
   using Sh = Shape16<D>;
   using Cfg = ApplyDmaCfg<D>;
   constexpr int NS = NSplit<T>::value;
   constexpr int KS = Sh::kKS, MT2 = Sh::kMT2, CPR = Sh::kChunksPerRow, HALF = Sh::kHalf;
   constexpr int NL = Cfg::kNL, NE = D * D + D, R = Cfg::kRing;
   static_assert(R == 3, "the wait counts below are written for a ring of three slots");
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const long long bh = blockIdx.y;
   const int tok = lane & 31, kg = lane >> 5;
 
-  // ---- prologue: state -> LDS, maxima, power-of-two scales, A fragments (as in apply16) --------
+  // ---- prologue: state -> LDS, maxima, power-of-two scales, A fragments -------------------------
   float* st = reinterpret_cast<float*>(smem);
   float* redmax = st + NE;
   float mS = 0.0f, mz = 0.0f;
   for (int e = threadIdx.x; e < NE; e += kThreads) {
-    float x = state[bh * NE + e];
+    float x = state[e];
     st[e] = x;
     if (e < D * D) mS = fmaxf(mS, fabsf(x)); else mz = fmaxf(mz, fabsf(x));
   }
@@ -138,7 +153,7 @@ apply16_dma(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __r
   const int tsw = Cfg::swz(tok);
 
   const long long n_tiles = (N + kTile - 1) / kTile;
-  TileIter it(blockIdx.x, gridDim.x, wave, tiles_per_block, n_tiles);
+  TileIter it(wg, nwg, wave, tiles_per_block, n_tiles);
   TileIter ahead = it;
   const u32x4* Qh = Q + bh * N * CPR;
   u32x4* Oh = O + bh * N * CPR;
@@ -271,6 +286,16 @@ apply16_dma(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __r
     ahead.next();
     slot = slot + 1 == R ? 0 : slot + 1;
   }
+}
+
+template <typename T, int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+apply16_dma(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restrict__ state, float eps,
+            long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const long long bh = blockIdx.y;
+  apply16_dma_phase<T, D, FM, NORM>(Q, O, state + bh * (D * D + D), eps, N, tiles_per_block, blockIdx.x, gridDim.x,
+                                    bh, smem);
 }
 
 }  // namespace lf

@@ -1,12 +1,12 @@
-// fp32 kernels of the split-N path.  fp32 inputs never pass through 16-bit operands: the
-// d x d contractions use the fp32 matrix-core instruction (16x16x4), whose operand layout
-// holds one contraction index per lane, so no transposition is needed anywhere.
-//   state_reduce32  S_p, z_p over a chunk of tokens            (Prop. 2: g'(X)^T X; Eq. 5: Z)
-//   combine_state   (shared with the 16-bit path) fixed-order sum of the partials
+// fp32 kernels.  fp32 inputs never pass through 16-bit operands: the d x d contractions use the
+// fp32 matrix-core instruction (16x16x4), whose operand layout holds one contraction index per
+// lane, so no transposition and no LDS staging is needed anywhere.
+//   state_reduce32  S_p, z_p over a workgroup's tiles          (Prop. 2: g'(X)^T X; Eq. 5: Z)
+//   combine_state   (lf_reduce16.hpp) fixed-order sum of the partials
 //   apply32         out_i = phi(q_i) S / (phi(q_i).z + eps)
 #pragma once
 #include "lf_common.hpp"
-#include "lf_kernels16.hpp"   // kWavesPerWG, kThreads, kCombineThreads
+#include "lf_reduce16.hpp"   // kWavesPerWG, kThreads, combine_state
 
 namespace lf {
 
@@ -21,31 +21,30 @@ template <int D> struct Shape32 {
   static constexpr int kMT = (kQuarter + 1 + 3) / 4;        // 16-row output tiles incl. normalizer row
 };
 
+template <int D> constexpr int reduce32_lds_bytes() { return (D * D + D) * 4; }
+
 LF_DEV f32x4 mfma_16x16x4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
 
 // ------------------------------------------------------------------------------------------
-// grid = (splits, B*H), block = 256.  Lane (m = lane % 16, kq = lane / 16) holds channels
-// 4m..4m+3 of token 4u + kq of the tile; element i of its K chunk (after phi) is the A operand
-// and element j of its V chunk the B operand of product (i, j), whose accumulator tile is
-// S[4*row + i][4*col + j].  z is summed on the vector ALU.
+// Lane (m = lane % 16, kq = lane / 16) holds channels 4m..4m+3 of token 4u + kq of the tile;
+// element i of its K chunk (after phi) is the A operand and element j of its V chunk the B
+// operand of product (i, j), whose accumulator tile is S[4*row + i][4*col + j].  z is summed
+// on the vector ALU.  `smem`: reduce32_lds_bytes<D>() bytes; `dst`: this workgroup's partial.
 // ------------------------------------------------------------------------------------------
 template <int D, int FM>
-__global__ void __launch_bounds__(kThreads)
-state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* __restrict__ partials,
-               long long N, int tiles_per_split) {
+LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* __restrict__ dst,
+                           long long N, int tiles_per_block, int split, int nsplit, long long bh,
+                           unsigned char* smem) {
   constexpr int CH = Shape32<D>::kChunks;
   constexpr int U = kTile32 / 4;
-  __shared__ float red[D * D + D];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float* red = reinterpret_cast<float*>(smem);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m = lane & 15, kq = lane >> 4;
-  const int split = blockIdx.x;
-  const long long bh = blockIdx.y;
   const bool lane_on = m < CH;
 
   const long long n_tiles = (N + kTile32 - 1) / kTile32;
-  long long t_begin = (long long)split * tiles_per_split;
-  long long t_end = t_begin + tiles_per_split;
-  if (t_end > n_tiles) t_end = n_tiles;
+  TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
   const f32x4* Kh = K + bh * N * CH;
   const f32x4* Vh = V + bh * N * CH;
 
@@ -73,9 +72,8 @@ state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* 
     }
   };
 
-  long long tile = t_begin + wave;
-  if (tile < t_end) issue_loads(tile);
-  while (tile < t_end) {
+  if (it.valid()) issue_loads(it.t);
+  while (it.valid()) {
     f32x4 p[U], vv[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -83,8 +81,8 @@ state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* 
       for (int i = 0; i < 4; ++i) p[u][i] = okr[u] ? phi<FM, true>(kr[u][i]) : 0.0f;
       vv[u] = vr[u];
     }
-    tile += kWavesPerWG;
-    if (tile < t_end) issue_loads(tile);
+    it.next();
+    if (it.valid()) issue_loads(it.t);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
 #pragma unroll
@@ -128,31 +126,39 @@ state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* 
     }
     __syncthreads();
   }
-  float* dst = partials + (bh * gridDim.x + split) * (long long)(D * D + D);
   for (int i = threadIdx.x; i < D * D + D; i += kThreads) dst[i] = red[i];
 }
 
+// grid = (splits, B*H), block = 256
+template <int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* __restrict__ partials,
+               long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const long long bh = blockIdx.y;
+  float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
+  reduce32_phase<D, FM>(K, V, dst, N, tiles_per_block, blockIdx.x, gridDim.x, bh, smem);
+}
+
 // ------------------------------------------------------------------------------------------
-// grid = (wgs_per_head, B*H), block = 256.  Lane (token = lane % 16, kq = lane / 16) loads its
-// kCS contiguous float4 chunks of the Q row; element e of chunk cs is the B operand of k-step
-// 4*cs + e against S^T (A operand), which every lane gathers once from the head's fp32 state:
+// Lane (token = lane % 16, kq = lane / 16) loads its kCS contiguous float4 chunks of the Q row;
+// element e of chunk cs is the B operand of k-step 4*cs + e against S^T (A operand), which every
+// lane gathers once from the head's fp32 state:
 // lane l (output row mrow = l % 16, kq = l / 16), tile T, k-step 4*cs + e:
 //   feature channel ch = 4*(kq*CS + cs) + e  (zero when that chunk is beyond d)
 //   slot = 4*T + mrow % 4, group g = mrow / 4:  slot < d/4 -> S[ch][g*d/4 + slot];
 //   slot == d/4 -> z[ch];  else 0.
 // The accumulators of a lane hold d/4 contiguous output channels of its token and the
-// normalizer phi(q).z.
+// normalizer phi(q).z.  `state`: this head's [D*D + D] floats.
 // ------------------------------------------------------------------------------------------
 template <int D, int FM, bool NORM>
-__global__ void __launch_bounds__(kThreads)
-apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const float* __restrict__ state, float eps,
-        long long N, int tiles_per_wg) {
+LF_DEV void apply32_phase(const f32x4* __restrict__ Q, float* __restrict__ O, const float* state, float eps,
+                          long long N, int tiles_per_block, int wg, int nwg, long long bh) {
   using Sh = Shape32<D>;
   constexpr int CS = Sh::kCS, KST = Sh::kKSteps, MT = Sh::kMT, CH = Sh::kChunks, QT = Sh::kQuarter;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int tok = lane & 15, kq = lane >> 4;
-  const long long bh = blockIdx.y;
-  const float* sth = state + bh * (long long)(D * D + D);
   float A[MT][KST];
   {
     const int mrow = lane & 15, g = mrow >> 2;
@@ -165,8 +171,8 @@ apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const float* __restr
         const int ch = 4 * chunk + (ks & 3);
         float x = 0.0f;
         if (chunk < CH) {
-          if (slot < QT) x = sth[ch * D + g * QT + slot];
-          else if (NORM && slot == QT) x = sth[D * D + ch];
+          if (slot < QT) x = state[ch * D + g * QT + slot];
+          else if (NORM && slot == QT) x = state[D * D + ch];
         }
         A[t][ks] = x;
       }
@@ -174,9 +180,7 @@ apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const float* __restr
   }
 
   const long long n_tiles = (N + kTile32 - 1) / kTile32;
-  long long t_begin = (long long)blockIdx.x * tiles_per_wg;
-  long long t_end = t_begin + tiles_per_wg;
-  if (t_end > n_tiles) t_end = n_tiles;
+  TileIter it(wg, nwg, wave, tiles_per_block, n_tiles);
   const f32x4* Qh = Q + bh * N * CH;
   float* Oh = O + bh * N * (long long)D;
 
@@ -189,17 +193,16 @@ apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const float* __restr
       else qr[cs] = f32x4{0, 0, 0, 0};
     }
   };
-  long long tile = t_begin + wave;
-  if (tile < t_end) issue_loads(tile);
-  while (tile < t_end) {
+  if (it.valid()) issue_loads(it.t);
+  while (it.valid()) {
     float r[KST];
 #pragma unroll
     for (int cs = 0; cs < CS; ++cs)
 #pragma unroll
       for (int e = 0; e < 4; ++e) r[4 * cs + e] = (kq * CS + cs < CH) ? phi<FM, true>(qr[cs][e]) : 0.0f;
-    const long long cur = tile;
-    tile += kWavesPerWG;
-    if (tile < t_end) issue_loads(tile);
+    const long long cur = it.t;
+    it.next();
+    if (it.valid()) issue_loads(it.t);
 
     f32x4 acc[MT];
 #pragma unroll
@@ -231,39 +234,13 @@ apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const float* __restr
   }
 }
 
-template <int D>
-hipError_t run32(const float* q, const float* k, const float* v, float* out, long long BH, long long N, int fm,
-                 float eps, bool unnorm, int splits, int tiles_per_split, int apply_wgs, int tiles_per_wg,
-                 float* partials, float* state, hipStream_t st, hipEvent_t* ev) {
-  const dim3 g1(splits, (unsigned)BH), blk(kThreads);
-  const f32x4* K = (const f32x4*)k;
-  const f32x4* V = (const f32x4*)v;
-  if (ev) (void)hipEventRecord(ev[0], st);
-  switch (fm) {
-    case 0: state_reduce32<D, 0><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
-    case 1: state_reduce32<D, 1><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
-    default: state_reduce32<D, 2><<<g1, blk, 0, st>>>(K, V, partials, N, tiles_per_split); break;
-  }
-  if (ev) (void)hipEventRecord(ev[1], st);
-  constexpr int NE = D * D + D;
-  combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, st>>>(
-      partials, splits, NE, state);
-  if (ev) (void)hipEventRecord(ev[2], st);
-  if (out) {
-    const dim3 g2(apply_wgs, (unsigned)BH);
-    const f32x4* Q = (const f32x4*)q;
-#define LF_APPLY32(FM)                                                                   \
-  if (unnorm) apply32<D, FM, false><<<g2, blk, 0, st>>>(Q, out, state, eps, N, tiles_per_wg); \
-  else apply32<D, FM, true><<<g2, blk, 0, st>>>(Q, out, state, eps, N, tiles_per_wg);
-    switch (fm) {
-      case 0: LF_APPLY32(0) break;
-      case 1: LF_APPLY32(1) break;
-      default: LF_APPLY32(2) break;
-    }
-#undef LF_APPLY32
-  }
-  if (ev) (void)hipEventRecord(ev[3], st);
-  return hipGetLastError();
+// grid = (wgs_per_head, B*H), block = 256
+template <int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const float* __restrict__ state, float eps,
+        long long N, int tiles_per_block) {
+  const long long bh = blockIdx.y;
+  apply32_phase<D, FM, NORM>(Q, O, state + bh * (D * D + D), eps, N, tiles_per_block, blockIdx.x, gridDim.x, bh);
 }
 
 }  // namespace lf

@@ -1,0 +1,280 @@
+// fp16 / bf16 state reduction and the dtype-independent combine of the split-N path:
+//   state_reduce16  S_p = sum_{j in chunk} phi(k_j)^T v_j,  z_p = sum phi(k_j)       (Prop. 2: g'(X)^T X)
+//   combine_state   S = sum_p S_p, z = sum_p z_p in a fixed order                      (Eq. 5: Z, non-causal)
+// The apply + normalize kernel is in lf_apply16_dma.hpp.  Each step is a __device__ "phase" function
+// so that the single-launch kernel (lf_fused.hpp) runs exactly the same code as the separate kernels.
+#pragma once
+#include "lf_common.hpp"
+
+namespace lf {
+
+constexpr int kWavesPerWG = 4;
+constexpr int kThreads = 64 * kWavesPerWG;
+constexpr int kTile = 32;   // tokens per tile, both in the reduction (one 16x16x32 k-step) and in apply
+
+// ==========================================================================================
+// State reduction.  grid = (splits, B*H), block = 256.  Workgroup (split, bh) owns blocks of
+// tiles_per_block consecutive tiles of head bh (see TileIter); its four waves take them
+// round-robin and each wave streams on its own: global -> registers (128-bit, coalesced over
+// the contiguous tile) -> phi on K -> wave-private LDS tile -> transposing LDS reads give the
+// token-major operands -> 16x16x32 matrix-core products accumulate S (and z through a column
+// of ones) in fp32.  No workgroup barrier inside the stream loop.
+// Partial written per workgroup: S as [D][D] row-major then z as [D], fp32.
+// ==========================================================================================
+template <int D> struct Reduce16Cfg {
+  using Sh = Shape16<D>;
+  // LDS row stride in 16-bit elements: padded so that the 4 rows x 32 bytes a 16-lane group
+  // reads with one transposing load fall in distinct banks.
+  static constexpr int kRS = Sh::kDP + (Sh::kSpareCol ? 0 : 8);
+  static constexpr int kTileElems = kTile * kRS;
+  static constexpr int kChunks = kTile * Sh::kChunksPerRow;   // 16-byte chunks per tile
+  static constexpr int kNL = (kChunks + 63) / 64;              // loads per lane per tensor
+};
+
+template <typename T, int D>
+constexpr int reduce16_lds_bytes() {
+  // per wave: NSplit tiles of phi(K) + one of V; reused by the cross-wave reduction
+  int tiles = (NSplit<T>::value + 1) * Reduce16Cfg<D>::kTileElems * 2 * kWavesPerWG;
+  int red = (D * D + D) * 4;
+  return tiles > red ? tiles : red;
+}
+
+// `dst`: where this workgroup's partial goes ([D*D + D] floats).  `smem`: reduce16_lds_bytes<T,D>()
+// bytes of LDS.  Ends with every thread having written its share of `dst` (no trailing barrier).
+template <typename T, int D, int FM>
+LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* __restrict__ dst,
+                           long long N, int tiles_per_block, int split, int nsplit, long long bh,
+                           unsigned char* smem) {
+  using Sh = Shape16<D>;
+  using Cfg = Reduce16Cfg<D>;
+  constexpr int NS = NSplit<T>::value;
+  constexpr int RS = Cfg::kRS, NL = Cfg::kNL, CPR = Sh::kChunksPerRow, MT = Sh::kMT;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+  uint16_t* wbase = reinterpret_cast<uint16_t*>(smem) + wave * (NS + 1) * Cfg::kTileElems;
+  uint16_t* ldsP[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) ldsP[s] = wbase + s * Cfg::kTileElems;
+  uint16_t* ldsV = wbase + NS * Cfg::kTileElems;
+
+  // one-time fill of the wave's tiles: phi(K) pad columns zero; V pad columns zero except the
+  // ones column at index D (when a spare column exists) which makes z fall out of the products
+  for (int i = lane; i < Cfg::kTileElems; i += 64) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) ldsP[s][i] = 0;
+    ldsV[i] = (Sh::kSpareCol && (i % RS) == D) ? OneBits<T>::value : (uint16_t)0;
+  }
+
+  // per-lane constants: which chunks of a tile this lane moves, and where they land in LDS
+  int lds_off[NL];
+#pragma unroll
+  for (int u = 0; u < NL; ++u) {
+    int c = u * 64 + lane;
+    lds_off[u] = (c / CPR) * RS + (c % CPR) * 8;
+  }
+  // transposing-read base: lane j of 16-lane group g reads row 8g + 4r + j/4, columns 4*(j%4)..
+  const int j16 = lane & 15, g4 = lane >> 4;
+  const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
+
+  const long long n_tiles = (N + kTile - 1) / kTile;
+  TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
+
+  const u32x4* Kh = K + bh * N * CPR;
+  const u32x4* Vh = V + bh * N * CPR;
+
+  f32x4 acc[MT][MT];
+  f32x4 accz[MT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    accz[a] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < MT; ++b) acc[a][b] = f32x4{0, 0, 0, 0};
+  }
+  const uint32_t one2 = (uint32_t)OneBits<T>::value * 0x10001u;
+  const u32x4 ones = {one2, one2, one2, one2};
+
+  u32x4 kr[NL], vr[NL];
+  auto issue_loads = [&](long long tile) {
+    // number of valid 16-byte chunks in this tile (ragged last tile of the head)
+    long long rem = (N - tile * kTile) * CPR;
+    int lim = rem < Cfg::kChunks ? (int)rem : Cfg::kChunks;
+    const u32x4* kp = Kh + tile * Cfg::kChunks;
+    const u32x4* vp = Vh + tile * Cfg::kChunks;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      int c = u * 64 + lane;
+      if (c < lim) {
+        kr[u] = ld_stream(kp + c);
+        vr[u] = ld_stream(vp + c);
+      } else {
+        kr[u] = u32x4{0, 0, 0, 0};
+        vr[u] = u32x4{0, 0, 0, 0};
+      }
+    }
+    return lim;
+  };
+
+  int lim = 0;
+  if (it.valid()) lim = issue_loads(it.t);
+
+  while (it.valid()) {
+    // ---- phi(K) -> 16-bit (hi [, lo]) -> LDS ; V -> LDS --------------------------------------
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      int c = u * 64 + lane;
+      if (c < Cfg::kChunks) {
+        const bool ok = c < lim;
+        u32x4 ph, pl;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1;
+          unpack2<T>(kr[u][w], x0, x1);
+          float p0 = ok ? phi<FM>(x0) : 0.0f;
+          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          if constexpr (NS == 1) {
+            ph[w] = pack2<T>(p0, p1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(p0, p1, h, l);
+            ph[w] = h;
+            pl[w] = l;
+          }
+        }
+        *reinterpret_cast<u32x4*>(ldsP[0] + lds_off[u]) = ph;
+        if constexpr (NS == 2) *reinterpret_cast<u32x4*>(ldsP[1] + lds_off[u]) = pl;
+        *reinterpret_cast<u32x4*>(ldsV + lds_off[u]) = vr[u];
+      }
+    }
+    // ---- prefetch the wave's next tile while this one is multiplied -------------------------
+    it.next();
+    int next_lim = 0;
+    if (it.valid()) next_lim = issue_loads(it.t);
+
+    // ---- token-major operands by transposing LDS reads, then the outer products -------------
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    u32x4 bfrag[MT];
+#pragma unroll
+    for (int b = 0; b < MT; ++b) {
+      u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * b);
+      u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * b);
+      bfrag[b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        u32x2 r0 = lds_read_tr16(ldsP[s] + tr_base + 16 * a);
+        u32x2 r1 = lds_read_tr16(ldsP[s] + tr_base + 4 * RS + 16 * a);
+        u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+        for (int b = 0; b < MT; ++b) acc[a][b] = mfma_16x16x32<T>(afrag, bfrag[b], acc[a][b]);
+        if constexpr (!Sh::kSpareCol) accz[a] = mfma_16x16x32<T>(afrag, ones, accz[a]);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    lim = next_lim;
+  }
+
+  // ---- fixed-order cross-wave sum in LDS (wave 0, then 1, 2, 3), then one partial per WG -----
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem);   // [D*D] S then [D] z
+  for (int w = 0; w < kWavesPerWG; ++w) {
+    if (wave == w) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = a * 16 + 4 * g4 + i;
+          if (row < D) {
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+              const int col = b * 16 + j16;
+              if (col < D) {
+                float* p = red + row * D + col;
+                *p = (w == 0) ? acc[a][b][i] : *p + acc[a][b][i];
+              } else if (Sh::kSpareCol && col == D) {
+                float* p = red + D * D + row;
+                *p = (w == 0) ? acc[a][b][i] : *p + acc[a][b][i];
+              }
+            }
+            if constexpr (!Sh::kSpareCol) {
+              if (j16 == 0) {
+                float* p = red + D * D + row;
+                *p = (w == 0) ? accz[a][i] : *p + accz[a][i];
+              }
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int i = threadIdx.x; i < D * D + D; i += kThreads) dst[i] = red[i];
+}
+
+template <typename T, int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* __restrict__ partials,
+               long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const long long bh = blockIdx.y;
+  float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
+  reduce16_phase<T, D, FM>(K, V, dst, N, tiles_per_block, blockIdx.x, gridDim.x, bh, smem);
+}
+
+// ==========================================================================================
+// Combine.  Thread (e, sg) sums element e of the head's partials over the sg-th quarter of the
+// splits in split order; the four quarters are then added in order 0..3.  Fixed order =>
+// run-to-run identical.  Output: the fp32 state of the head, S as [d][d] row-major then z as [d].
+// One call handles the 64 elements [e0, e0 + 64) with 256 threads; `part` is 256 floats of LDS.
+// ==========================================================================================
+constexpr int kCombineThreads = 256;
+constexpr int kCombineElems = 64;
+
+LF_DEV void combine_slice(const float* __restrict__ head_partials, int splits, int NE, int e0,
+                          float* __restrict__ head_state, float* part) {
+  const int el = threadIdx.x & 63, sg = threadIdx.x >> 6;
+  const int e = e0 + el;
+  const int per = (splits + 3) / 4;
+  int p0 = sg * per, p1 = p0 + per;
+  if (p1 > splits) p1 = splits;
+  float s = 0.0f;
+  if (e < NE) {
+    const float* src = head_partials + e;
+    int p = p0;
+    for (; p + 8 <= p1; p += 8) {   // eight loads in flight, added in split order
+      float a[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a[i] = src[(long long)(p + i) * NE];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s += a[i];
+    }
+    for (; p < p1; ++p) s += src[(long long)p * NE];
+  }
+  part[sg * kCombineElems + el] = s;
+  __syncthreads();
+  if (sg == 0 && e < NE)
+    head_state[e] = ((part[el] + part[kCombineElems + el]) + part[2 * kCombineElems + el]) + part[3 * kCombineElems + el];
+}
+
+// grid = (ceil(NE / 64), B*H), block = 256, NE = d*d + d
+__global__ void __launch_bounds__(kCombineThreads)
+combine_state(const float* __restrict__ partials, int splits, int NE, float* __restrict__ state) {
+  __shared__ float part[4 * kCombineElems];
+  const long long bh = blockIdx.y;
+  combine_slice(partials + (bh * splits) * (long long)NE, splits, NE, blockIdx.x * kCombineElems, state + bh * NE, part);
+}
+
+LF_DEV float pow2_scale_for(float mx) {
+  // power of two alpha with alpha * mx in [2^13, 2^14); 1 when mx is zero or not finite
+  if (!(mx > 0.0f) || !(mx < 3.0e38f)) return 1.0f;
+  int e;
+  (void)__builtin_frexpf(mx, &e);     // mx = m * 2^e, m in [0.5, 1)
+  int k = 14 - e;
+  k = k > 100 ? 100 : (k < -100 ? -100 : k);
+  return __builtin_ldexpf(1.0f, k);
+}
+
+}  // namespace lf

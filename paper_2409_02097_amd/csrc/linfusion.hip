@@ -1,6 +1,6 @@
 // Host side of the C ABI declared in include/linfusion.h: argument validation, launch plan,
-// kernel dispatch.  Every arithmetic step of the method runs in the kernels of
-// lf_kernels16.hpp (fp16 / bf16) and lf_kernels32.hpp (fp32).
+// kernel dispatch.  Every arithmetic step of the method runs in the kernels of lf_reduce16.hpp,
+// lf_apply16_dma.hpp (fp16 / bf16), lf_fp32.hpp (fp32) and lf_fused.hpp (single-launch variant).
 #include "../../include/linfusion.h"
 
 #include <hip/hip_runtime.h>
@@ -8,28 +8,30 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
 #include <cmath>
 #include <mutex>
 
-#include "lf_kernels16.hpp"
-#include "lf_apply16_dma.hpp"
-#include "lf_kernels32.hpp"
+#include "lf_fused.hpp"
 
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 200;  // 0.2.0
 constexpr int kMaxDevices = 16;
+constexpr int kNumCU = 256;    // the library targets one chip
 
-// ---- launch plan (pure function of the shape; the library targets one chip: 256 CUs) --------
+// ---- launch plan (pure function of the shape and flags) ----------------------------------------
 struct Plan {
   int path;             // 0 = split-N three-kernel path, 1 = fused single launch
-  int splits;           // state-reduction workgroups per head
-  int tiles_per_split;  // tiles per contiguous block of a reduction workgroup
-  int apply_wgs;        // apply workgroups per head
-  int tiles_per_wg;     // tiles per contiguous block of an apply workgroup
+  int splits;           // split path: state-reduction workgroups per head
+  int blk_reduce;       //   tiles per contiguous block of a reduction workgroup
+  int apply_wgs;        //   apply workgroups per head
+  int blk_apply;        //   tiles per contiguous block of an apply workgroup
+  int fsplits;          // fused path: workgroups per head (0 = the shape cannot use it)
+  int fblk_reduce, fblk_apply;
   long long n_tiles;
-  size_t state_floats;     // d*d + d: one partial, and one head's state
-  size_t ws_partials, ws_state, ws_total;
+  size_t state_floats;  // d*d + d: one partial, and one head's state
+  size_t ws_partials, ws_state, ws_sync, ws_total;
 };
 
 int env_int(const char* name, int dflt) {
@@ -41,13 +43,22 @@ int env_int(const char* name, int dflt) {
 
 // tiles per contiguous block of a workgroup, at most its whole share, rounded up to a multiple of
 // the waves per workgroup; the environment override is a tuning aid
-int block_tiles(int share, const char* env, int dflt) {
-  int b = env_int(env, dflt);
+int block_tiles(long long share, const char* env, int dflt) {
+  long long b = env_int(env, dflt);
   if (b > share) b = share;
-  return (b + lf::kWavesPerWG - 1) / lf::kWavesPerWG * lf::kWavesPerWG;
+  if (b > (1 << 28)) b = 1 << 28;
+  return (int)((b + lf::kWavesPerWG - 1) / lf::kWavesPerWG * lf::kWavesPerWG);
 }
 
 bool supported_d(int d) { return d >= 8 && d <= 64 && d % 8 == 0; }
+
+// Workgroups of the fused kernel that fit one CU at once (registers and LDS of the largest phase);
+// conservative figures, re-checked against the runtime's occupancy query before each fused launch.
+int fused_wgs_per_cu(int d, int dtype) {
+  if (dtype == LINFUSION_DTYPE_F32) return 2;
+  if (dtype == LINFUSION_DTYPE_BF16) return d <= 40 ? 4 : (d <= 48 ? 3 : 2);
+  return d <= 48 ? 4 : 2;
+}
 
 int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan* p) {
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
@@ -61,38 +72,53 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   const long long BH = (long long)B * H;
   const int tile = dtype == LINFUSION_DTYPE_F32 ? lf::kTile32 : lf::kTile;
   p->n_tiles = (N + tile - 1) / tile;
-  p->path = 0;
-  // state reduction (read-only stream): two workgroups per CU on 256 CUs measured best -- fewer,
-  // longer streams keep DRAM pages open; at least one tile per wave
-  const int want1 = env_int("LINFUSION_REDUCE_WGS", 512);
-  long long s = (want1 + BH - 1) / BH;
-  long long max_s = (p->n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;
-  if (s > max_s) s = max_s;
-  if (s < 1) s = 1;
-  long long tps = (p->n_tiles + s - 1) / s;
-  s = (p->n_tiles + tps - 1) / tps;
-  p->splits = (int)s;
-  p->tiles_per_split = block_tiles((int)tps, "LINFUSION_REDUCE_BLK", 16);
+  const long long max_s = (p->n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;   // >= one tile per wave
+  auto per_head = [&](int want_total, long long* share) {
+    long long s = (want_total + BH - 1) / BH;
+    if (s > max_s) s = max_s;
+    if (s < 1) s = 1;
+    long long t = (p->n_tiles + s - 1) / s;
+    *share = t;
+    return (int)((p->n_tiles + t - 1) / t);
+  };
+  long long share = 0;
+  // state reduction (read-only stream): two workgroups per CU measured best -- fewer, longer
+  // streams keep DRAM pages open
+  p->splits = per_head(env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), &share);
+  p->blk_reduce = block_tiles(share, "LINFUSION_REDUCE_BLK", 16);
   // apply (read + write streams): more, smaller workgroups that sweep memory in one moving window
-  const int want2 = env_int("LINFUSION_APPLY_WGS", 2048);
-  long long a = (want2 + BH - 1) / BH;
-  if (a > max_s) a = max_s;
-  if (a < 1) a = 1;
-  long long tpw = (p->n_tiles + a - 1) / a;
-  a = (p->n_tiles + tpw - 1) / tpw;
-  p->apply_wgs = (int)a;
-  p->tiles_per_wg = block_tiles((int)tpw, "LINFUSION_APPLY_BLK", 8);
+  p->apply_wgs = per_head(env_int("LINFUSION_APPLY_WGS", 8 * kNumCU), &share);
+  p->blk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", 8);
+  // fused single launch: every workgroup must be resident at once
+  const long long cap = (long long)fused_wgs_per_cu(d, dtype) * kNumCU;
+  p->fsplits = 0;
+  if (BH <= cap) {
+    p->fsplits = per_head((int)(cap / BH * BH), &share);
+    if ((long long)p->fsplits * BH > cap) p->fsplits = 0;
+    p->fblk_reduce = block_tiles(share, "LINFUSION_REDUCE_BLK", 16);
+    p->fblk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", 8);
+  }
+  const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
+  const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
+  const double fused_max = (double)env_int("LINFUSION_FUSED_MAX_MB", 48) * 1048576.0;
+  p->path = 0;
+  if (p->fsplits > 0 && !(flags & LINFUSION_FLAG_FORCE_SPLIT) &&
+      ((flags & LINFUSION_FLAG_FORCE_FUSED) || bytes <= fused_max))
+    p->path = 1;
   p->state_floats = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  p->ws_partials = up((size_t)BH * p->splits * p->state_floats * sizeof(float));
+  const int smax = p->splits > p->fsplits ? p->splits : p->fsplits;
+  p->ws_partials = up((size_t)BH * smax * p->state_floats * sizeof(float));
   p->ws_state = up((size_t)BH * p->state_floats * sizeof(float));
-  p->ws_total = p->ws_partials + p->ws_state;
+  p->ws_sync = up((size_t)BH * sizeof(lf::HeadSync) + 16);
+  p->ws_total = p->ws_partials + p->ws_state + p->ws_sync;
   return LINFUSION_OK;
 }
 
 // ---- device check (cached per device) ------------------------------------------------------------
 int g_dev_ok[kMaxDevices];   // 0 = unknown, 1 = gfx950, -1 = something else
 std::mutex g_mu;
+std::atomic<unsigned> g_ticket{1};
 
 int check_device() {
   int dev = -1;
@@ -112,82 +138,186 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   return x < y + nb && y < x + na;
 }
 
+unsigned next_ticket() {
+  unsigned t = g_ticket.fetch_add(1, std::memory_order_relaxed);
+  if (t == 0) t = g_ticket.fetch_add(1, std::memory_order_relaxed);
+  return t;
+}
+
+// true when `grid` workgroups of `kernel` (256 threads, `lds` dynamic bytes) are resident at once
+template <typename KernelT>
+bool fits_resident(KernelT kernel, size_t lds, long long grid) {
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, lf::kThreads, lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return (long long)per_cu * kNumCU >= grid;
+}
+
+struct Args {
+  const void *q, *k, *v;
+  void* out;
+  long long BH, N;
+  int fm;
+  float eps;
+  bool unnorm;
+  const Plan* p;
+  unsigned char* ws;
+  float* state_out;
+  hipStream_t st;
+  hipEvent_t* ev;
+};
+
+constexpr unsigned kSpinLimit = 4u << 20;   // polls of ~1 us each before a fused launch gives up
+
 // ---- kernel dispatch ---------------------------------------------------------------------------------
 #define LF_FOR_D(X) X(8) X(16) X(24) X(32) X(40) X(48) X(56) X(64)
 
-template <typename T, int D>
-int run16(const void* q, const void* k, const void* v, void* out, long long BH, long long N, int fm, float eps,
-          bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st, hipEvent_t* ev) {
-  using namespace lf;
-  float* partials = reinterpret_cast<float*>(ws);
-  float* state = state_out ? state_out : reinterpret_cast<float*>(ws + p.ws_partials);
-  constexpr int NE = D * D + D;
-  const dim3 g1(p.splits, (unsigned)BH), blk(kThreads);
-  const size_t lds = reduce16_lds_bytes<T, D>();
-  const u32x4* K = (const u32x4*)k;
-  const u32x4* V = (const u32x4*)v;
-  if (ev) (void)hipEventRecord(ev[0], st);
-  switch (fm) {
-    case 0: state_reduce16<T, D, 0><<<g1, blk, lds, st>>>(K, V, partials, N, p.tiles_per_split); break;
-    case 1: state_reduce16<T, D, 1><<<g1, blk, lds, st>>>(K, V, partials, N, p.tiles_per_split); break;
-    default: state_reduce16<T, D, 2><<<g1, blk, lds, st>>>(K, V, partials, N, p.tiles_per_split); break;
+#define LF_SWITCH_FM_NORM(CALL)                 \
+  switch (a.fm) {                               \
+    case 0: if (a.unnorm) { CALL(0, false) } else { CALL(0, true) } break;  \
+    case 1: if (a.unnorm) { CALL(1, false) } else { CALL(1, true) } break;  \
+    default: if (a.unnorm) { CALL(2, false) } else { CALL(2, true) } break; \
   }
-  if (ev) (void)hipEventRecord(ev[1], st);
-  combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, st>>>(
-      partials, p.splits, NE, state);
-  if (ev) (void)hipEventRecord(ev[2], st);
-  if (out) {
-    const dim3 g2(p.apply_wgs, (unsigned)BH);
-    const u32x4* Q = (const u32x4*)q;
-    u32x4* O = (u32x4*)out;
-    const bool dma = env_int("LINFUSION_APPLY_IMPL", 2) == 2;
-    const size_t lds2 = dma ? apply16_dma_lds_bytes<T, D>() : apply16_lds_bytes<T, D>();
-#define LF_APPLY(FM)                                                                                       \
-  if (dma) {                                                                                               \
-    if (unnorm) apply16_dma<T, D, FM, false><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);  \
-    else apply16_dma<T, D, FM, true><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);          \
-  } else if (unnorm) apply16<T, D, FM, false><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg); \
-  else apply16<T, D, FM, true><<<g2, blk, lds2, st>>>(Q, O, state, eps, N, p.tiles_per_wg);
-    switch (fm) {
-      case 0: LF_APPLY(0) break;
-      case 1: LF_APPLY(1) break;
-      default: LF_APPLY(2) break;
+#define LF_SWITCH_FM(CALL)      \
+  switch (a.fm) {               \
+    case 0: CALL(0) break;      \
+    case 1: CALL(1) break;      \
+    default: CALL(2) break;     \
+  }
+
+template <typename T, int D>
+int run16(const Args& a) {
+  using namespace lf;
+  const Plan& p = *a.p;
+  float* partials = reinterpret_cast<float*>(a.ws);
+  float* state = a.state_out ? a.state_out : reinterpret_cast<float*>(a.ws + p.ws_partials);
+  constexpr int NE = D * D + D;
+  const dim3 blk(kThreads);
+  const u32x4* K = (const u32x4*)a.k;
+  const u32x4* V = (const u32x4*)a.v;
+  const u32x4* Q = (const u32x4*)a.q;
+  u32x4* O = (u32x4*)a.out;
+  hipStream_t st = a.st;
+  if (p.path == 1 && a.out) {
+    HeadSync* sync = reinterpret_cast<HeadSync*>(a.ws + p.ws_partials + p.ws_state);
+    unsigned* err = reinterpret_cast<unsigned*>(sync + a.BH);
+    const dim3 g(p.fsplits, (unsigned)a.BH);
+    const size_t lds = fused16_lds_bytes<T, D>();
+    bool launched = false;
+#define LF_FUSED(FM, NORM)                                                                               \
+  if (fits_resident(fused16<T, D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                        \
+    if (a.ev) (void)hipEventRecord(a.ev[0], st);                                                         \
+    fused16<T, D, FM, NORM><<<g, blk, lds, st>>>(K, V, Q, O, partials, state, sync, err, next_ticket(),  \
+                                                 kSpinLimit, a.eps, a.N, p.fblk_reduce, p.fblk_apply);   \
+    launched = true;                                                                                     \
+  }
+    LF_SWITCH_FM_NORM(LF_FUSED)
+#undef LF_FUSED
+    if (launched) {
+      if (a.ev) { (void)hipEventRecord(a.ev[1], st); (void)hipEventRecord(a.ev[2], st); (void)hipEventRecord(a.ev[3], st); }
+      return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
     }
+  }
+  const dim3 g1(p.splits, (unsigned)a.BH);
+  const size_t lds1 = reduce16_lds_bytes<T, D>();
+  if (a.ev) (void)hipEventRecord(a.ev[0], st);
+#define LF_REDUCE(FM) state_reduce16<T, D, FM><<<g1, blk, lds1, st>>>(K, V, partials, a.N, p.blk_reduce);
+  LF_SWITCH_FM(LF_REDUCE)
+#undef LF_REDUCE
+  if (a.ev) (void)hipEventRecord(a.ev[1], st);
+  combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
+      partials, p.splits, NE, state);
+  if (a.ev) (void)hipEventRecord(a.ev[2], st);
+  if (a.out) {
+    const dim3 g2(p.apply_wgs, (unsigned)a.BH);
+    const size_t lds2 = apply16_dma_lds_bytes<T, D>();
+#define LF_APPLY(FM, NORM) apply16_dma<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, O, state, a.eps, a.N, p.blk_apply);
+    LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
   }
-  if (ev) (void)hipEventRecord(ev[3], st);
+  if (a.ev) (void)hipEventRecord(a.ev[3], st);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
-template <typename T>
-int run16_d(int d, const void* q, const void* k, const void* v, void* out, long long BH, long long N, int fm,
-            float eps, bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st,
-            hipEvent_t* ev) {
-  switch (d) {
-#define X(DD) case DD: return run16<T, DD>(q, k, v, out, BH, N, fm, eps, unnorm, p, ws, state_out, st, ev);
-    LF_FOR_D(X)
-#undef X
-    default: return LINFUSION_ERR_UNSUPPORTED;
+template <int D>
+int run32(const Args& a) {
+  using namespace lf;
+  const Plan& p = *a.p;
+  float* partials = reinterpret_cast<float*>(a.ws);
+  float* state = a.state_out ? a.state_out : reinterpret_cast<float*>(a.ws + p.ws_partials);
+  constexpr int NE = D * D + D;
+  const dim3 blk(kThreads);
+  const f32x4* K = (const f32x4*)a.k;
+  const f32x4* V = (const f32x4*)a.v;
+  const f32x4* Q = (const f32x4*)a.q;
+  float* O = (float*)a.out;
+  hipStream_t st = a.st;
+  constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
+  if (p.path == 1 && a.out) {
+    HeadSync* sync = reinterpret_cast<HeadSync*>(a.ws + p.ws_partials + p.ws_state);
+    unsigned* err = reinterpret_cast<unsigned*>(sync + a.BH);
+    const dim3 g(p.fsplits, (unsigned)a.BH);
+    bool launched = false;
+#define LF_FUSED(FM, NORM)                                                                           \
+  if (fits_resident(fused32<D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                       \
+    if (a.ev) (void)hipEventRecord(a.ev[0], st);                                                     \
+    fused32<D, FM, NORM><<<g, blk, lds, st>>>(K, V, Q, O, partials, state, sync, err, next_ticket(),  \
+                                              kSpinLimit, a.eps, a.N, p.fblk_reduce, p.fblk_apply);  \
+    launched = true;                                                                                 \
   }
+    LF_SWITCH_FM_NORM(LF_FUSED)
+#undef LF_FUSED
+    if (launched) {
+      if (a.ev) { (void)hipEventRecord(a.ev[1], st); (void)hipEventRecord(a.ev[2], st); (void)hipEventRecord(a.ev[3], st); }
+      return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+    }
+  }
+  const dim3 g1(p.splits, (unsigned)a.BH);
+  if (a.ev) (void)hipEventRecord(a.ev[0], st);
+#define LF_REDUCE(FM) state_reduce32<D, FM><<<g1, blk, lds, st>>>(K, V, partials, a.N, p.blk_reduce);
+  LF_SWITCH_FM(LF_REDUCE)
+#undef LF_REDUCE
+  if (a.ev) (void)hipEventRecord(a.ev[1], st);
+  combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
+      partials, p.splits, NE, state);
+  if (a.ev) (void)hipEventRecord(a.ev[2], st);
+  if (a.out) {
+    const dim3 g2(p.apply_wgs, (unsigned)a.BH);
+#define LF_APPLY(FM, NORM) apply32<D, FM, NORM><<<g2, blk, 0, st>>>(Q, O, state, a.eps, a.N, p.blk_apply);
+    LF_SWITCH_FM_NORM(LF_APPLY)
+#undef LF_APPLY
+  }
+  if (a.ev) (void)hipEventRecord(a.ev[3], st);
+  return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
-int run32_d(int d, const void* q, const void* k, const void* v, void* out, long long BH, long long N, int fm,
-            float eps, bool unnorm, const Plan& p, unsigned char* ws, float* state_out, hipStream_t st,
-            hipEvent_t* ev) {
-  float* partials = reinterpret_cast<float*>(ws);
-  float* state = state_out ? state_out : reinterpret_cast<float*>(ws + p.ws_partials);
-  switch (d) {
-#define X(DD)                                                                                             \
-  case DD:                                                                                                \
-    return lf::run32<DD>((const float*)q, (const float*)k, (const float*)v, (float*)out, BH, N, fm, eps, \
-                         unnorm, p.splits, p.tiles_per_split, p.apply_wgs, p.tiles_per_wg, partials,      \
-                         state, st, ev) == hipSuccess                                             \
-               ? LINFUSION_OK                                                                             \
-               : LINFUSION_ERR_HIP;
-    LF_FOR_D(X)
+int dispatch(int d, int dtype, const Args& a) {
+  switch (dtype) {
+    case LINFUSION_DTYPE_F16:
+      switch (d) {
+#define X(DD) case DD: return run16<lf::F16, DD>(a);
+        LF_FOR_D(X)
 #undef X
-    default: return LINFUSION_ERR_UNSUPPORTED;
+      }
+      break;
+    case LINFUSION_DTYPE_BF16:
+      switch (d) {
+#define X(DD) case DD: return run16<lf::BF16, DD>(a);
+        LF_FOR_D(X)
+#undef X
+      }
+      break;
+    default:
+      switch (d) {
+#define X(DD) case DD: return run32<DD>(a);
+        LF_FOR_D(X)
+#undef X
+      }
+      break;
   }
+  return LINFUSION_ERR_UNSUPPORTED;
 }
 
 int validate_common(const void* k, const void* v, int B, int H, long long N, int d, int dtype, int feature_map,
@@ -221,28 +351,9 @@ int owned_workspace(size_t need, void** ws) {
   return LINFUSION_OK;
 }
 
-int fwd_owned(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d, int dtype,
-              int feature_map, float eps, void* stream) {
-  size_t need = linfusion_attn_workspace_bytes(B, H, N, d, dtype);
-  void* ws = nullptr;
-  if (need == 0) {
-    // let the general entry point name the error (nothing is enqueued for invalid arguments)
-    return linfusion_attn_fwd_ex(q, k, v, out, B, H, N, d, dtype, feature_map, eps, 0u, nullptr, 0, stream);
-  }
-  int rc = check_device();
-  if (rc != LINFUSION_OK) return rc;
-  rc = owned_workspace(need, &ws);
-  if (rc != LINFUSION_OK) return rc;
-  return linfusion_attn_fwd_ex(q, k, v, out, B, H, N, d, dtype, feature_map, eps, 0u, ws, g_ws_bytes[0] ? need : need, stream);
-}
-
-}  // namespace
-
-extern "C" {
-
-static int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d,
-                    int dtype, int feature_map, float eps, unsigned flags, void* workspace,
-                    size_t workspace_bytes, void* stream, hipEvent_t* ev) {
+int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d, int dtype,
+             int feature_map, float eps, unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
+             hipEvent_t* ev) {
   if (!q || !out) return LINFUSION_ERR_INVALID;
   if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
   Plan p;
@@ -261,16 +372,27 @@ static int fwd_impl(const void* q, const void* k, const void* v, void* out, int 
     return LINFUSION_ERR_OVERLAP;
   rc = check_device();
   if (rc != LINFUSION_OK) return rc;
-  const bool unnorm = (flags & LINFUSION_FLAG_UNNORMALIZED) != 0;
-  hipStream_t st = (hipStream_t)stream;
-  const long long BH = (long long)B * H;
-  unsigned char* ws = (unsigned char*)workspace;
-  switch (dtype) {
-    case LINFUSION_DTYPE_F16: return run16_d<lf::F16>(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st, ev);
-    case LINFUSION_DTYPE_BF16: return run16_d<lf::BF16>(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st, ev);
-    default: return run32_d(d, q, k, v, out, BH, N, feature_map, eps, unnorm, p, ws, nullptr, st, ev);
-  }
+  Args a{q, k, v, out, (long long)B * H, N, feature_map, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
+         &p, (unsigned char*)workspace, nullptr, (hipStream_t)stream, ev};
+  return dispatch(d, dtype, a);
 }
+
+int fwd_owned(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d, int dtype,
+              int feature_map, float eps, void* stream) {
+  size_t need = linfusion_attn_workspace_bytes(B, H, N, d, dtype);
+  if (need == 0)   // let the general entry point name the error (nothing is enqueued for invalid arguments)
+    return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, 0u, nullptr, 0, stream, nullptr);
+  int rc = check_device();
+  if (rc != LINFUSION_OK) return rc;
+  void* ws = nullptr;
+  rc = owned_workspace(need, &ws);
+  if (rc != LINFUSION_OK) return rc;
+  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, 0u, ws, need, stream, nullptr);
+}
+
+}  // namespace
+
+extern "C" {
 
 int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d,
                           int dtype, int feature_map, float eps, unsigned flags, void* workspace,
@@ -304,14 +426,10 @@ int linfusion_attn_state(const void* k, const void* v, float* state_out, int B, 
   if (workspace_bytes < p.ws_total) return LINFUSION_ERR_WORKSPACE;
   rc = check_device();
   if (rc != LINFUSION_OK) return rc;
-  hipStream_t st = (hipStream_t)stream;
-  const long long BH = (long long)B * H;
-  unsigned char* ws = (unsigned char*)workspace;
-  switch (dtype) {
-    case LINFUSION_DTYPE_F16: return run16_d<lf::F16>(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st, nullptr);
-    case LINFUSION_DTYPE_BF16: return run16_d<lf::BF16>(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st, nullptr);
-    default: return run32_d(d, nullptr, k, v, nullptr, BH, N, feature_map, 0.f, false, p, ws, state_out, st, nullptr);
-  }
+  p.path = 0;
+  Args a{nullptr, k, v, nullptr, (long long)B * H, N, feature_map, 0.0f, false,
+         &p, (unsigned char*)workspace, state_out, (hipStream_t)stream, nullptr};
+  return dispatch(d, dtype, a);
 }
 
 int linfusion_attn_fwd(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d,
@@ -370,8 +488,8 @@ int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned fl
   int rc = make_plan(B, H, N, d, dtype, flags, &p);
   if (rc != LINFUSION_OK) return rc;
   plan[0] = p.path;
-  plan[1] = p.splits;
-  plan[2] = p.apply_wgs;
+  plan[1] = p.path == 1 ? p.fsplits : p.splits;
+  plan[2] = p.path == 1 ? p.fsplits : p.apply_wgs;
   plan[3] = dtype == LINFUSION_DTYPE_F32 ? lf::kTile32 : lf::kTile;
   return LINFUSION_OK;
 }

@@ -35,22 +35,28 @@ SMALL = [
 ]
 
 
+PATHS = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED}
+
+
+@pytest.mark.parametrize("path", list(PATHS))
 @pytest.mark.parametrize("B,H,N,d,dtype", SMALL)
-def test_small_shapes_match_oracle(B, H, N, d, dtype):
-    print(f"case B={B} H={H} N={N} d={d} {dtype}", flush=True)
+def test_small_shapes_match_oracle(B, H, N, d, dtype, path):
+    print(f"case B={B} H={H} N={N} d={d} {dtype} {path}", flush=True)
     q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=50, device="cpu")
-    out = _run(q.cuda(), k.cuda(), v.cuda())
+    assert lf.linfusion_attn_plan(B, H, N, d, wl.DTYPE_CODE[dtype], PATHS[path])["path"] == (path == "fused")
+    out = _run(q.cuda(), k.cuda(), v.cuda(), flags=PATHS[path])
     worst = parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"N={N} d={d} {dtype}")
     print(f"  worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("path", list(PATHS))
 @pytest.mark.parametrize("name", ["sd15_256_f32", "sd15_512_f16", "sd21_768_f16", "sd21_768_f16_peaky",
                                   "sdxl_2048_A_bf16", "sdxl_2048_B_bf16"])
-def test_paper_shaped_configs_match_oracle(name):
-    print(f"config {name}", flush=True)
+def test_paper_shaped_configs_match_oracle(name, path):
+    print(f"config {name} {path}", flush=True)
     c = wl.CONFIGS[name]
     q, k, v = wl.make_config(name, device="cpu")
-    out = _run(q.cuda(), k.cuda(), v.cuda(), 0, wl.EPS)
+    out = _run(q.cuda(), k.cuda(), v.cuda(), 0, wl.EPS, PATHS[path])
     worst = parity.check_all(out, q, k, v, c["dtype"], 0, wl.EPS, True, name)
     print(f"  worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
 
@@ -83,12 +89,30 @@ def test_constant_v_and_large_mean(dtype):
     parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"constant V {dtype}")
 
 
+@pytest.mark.parametrize("path", list(PATHS))
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
-def test_run_to_run_bit_identical(dtype):
+def test_run_to_run_bit_identical(dtype, path):
     q, k, v = wl.make_qkv(2, 3, 5000, 64, dtype, idx=63, device="cuda")
-    a = _run(q, k, v)
-    b = _run(q, k, v)
-    assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    a = _run(q, k, v, flags=PATHS[path])
+    for _ in range(3):
+        b = _run(q, k, v, flags=PATHS[path])
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+def test_fused_calls_back_to_back_share_a_workspace():
+    # the barrier words are never reset: consecutive calls on one workspace must not see stale arrivals
+    q, k, v = wl.make_qkv(2, 4, 3000, 40, "f16", idx=67, device="cuda")
+    ws = torch.empty(lf.linfusion_attn_workspace_bytes(2, 4, 3000, 40, 1), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)            # whatever the caller left there
+    ref = _run(q, k, v, flags=lf.FLAG_FORCE_SPLIT)
+    outs = [torch.empty_like(q) for _ in range(20)]
+    for o in outs:
+        lf.linfusion_attn_fwd_ex(q, k, v, o, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws)
+    torch.cuda.synchronize()
+    for o in outs:
+        assert torch.equal(o.view(torch.uint8), outs[0].view(torch.uint8))
+    parity.check_all(outs[0], q.cpu(), k.cpu(), v.cpu(), "f16", 0, 1e-6, True, "fused back-to-back")
+    assert (outs[0].float() - ref.float()).abs().max().item() < 1e-2
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
