@@ -84,7 +84,7 @@ LF_DEV void apply16_dma_phase(const u32x4* __restrict__ Q, u32x4* __restrict__ O
   float* redmax = st + NE;
   float mS = 0.0f, mz = 0.0f;
   for (int e = threadIdx.x; e < NE; e += kThreads) {
-    float x = state[e];
+    float x = ld_agent(state + e);
     st[e] = x;
     if (e < D * D) mS = fmaxf(mS, fabsf(x)); else mz = fmaxf(mz, fabsf(x));
   }

@@ -111,6 +111,12 @@ LF_DEV u32x4 ld_stream(const u32x4* p) { return __builtin_nontemporal_load(p); }
 LF_DEV void st_stream(u32x4* p, u32x4 v) { __builtin_nontemporal_store(v, p); }
 LF_DEV void st_stream(u32x2* p, u32x2 v) { __builtin_nontemporal_store(v, p); }
 
+// Loads / stores of the small fp32 partial states and states that other workgroups (on other XCDs,
+// each with its own L2) consume inside the same launch: device-scope relaxed atomics, which go
+// through to the device-coherent level instead of staying in the issuing XCD's L2.
+LF_DEV void st_agent(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+LF_DEV float ld_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
 // ---- shape constants of the 16-bit path ---------------------------------------------------
 // State reduction tiles the d x d state in 16 x 16 blocks; apply tiles the output in 32-row
 // blocks with the two normalizer rows (z hi, z lo) appended after each half of the channels.

@@ -126,7 +126,7 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict_
     }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < D * D + D; i += kThreads) dst[i] = red[i];
+  for (int i = threadIdx.x; i < D * D + D; i += kThreads) st_agent(dst + i, red[i]);
 }
 
 // grid = (splits, B*H), block = 256
@@ -171,8 +171,8 @@ LF_DEV void apply32_phase(const f32x4* __restrict__ Q, float* __restrict__ O, co
         const int ch = 4 * chunk + (ks & 3);
         float x = 0.0f;
         if (chunk < CH) {
-          if (slot < QT) x = state[ch * D + g * QT + slot];
-          else if (NORM && slot == QT) x = state[D * D + ch];
+          if (slot < QT) x = ld_agent(state + ch * D + g * QT + slot);
+          else if (NORM && slot == QT) x = ld_agent(state + D * D + ch);
         }
         A[t][ks] = x;
       }

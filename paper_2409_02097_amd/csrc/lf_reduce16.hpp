@@ -211,7 +211,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
     }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < D * D + D; i += kThreads) dst[i] = red[i];
+  for (int i = threadIdx.x; i < D * D + D; i += kThreads) st_agent(dst + i, red[i]);
 }
 
 template <typename T, int D, int FM>
@@ -247,16 +247,17 @@ LF_DEV void combine_slice(const float* __restrict__ head_partials, int splits, i
     for (; p + 8 <= p1; p += 8) {   // eight loads in flight, added in split order
       float a[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) a[i] = src[(long long)(p + i) * NE];
+      for (int i = 0; i < 8; ++i) a[i] = ld_agent(src + (long long)(p + i) * NE);
 #pragma unroll
       for (int i = 0; i < 8; ++i) s += a[i];
     }
-    for (; p < p1; ++p) s += src[(long long)p * NE];
+    for (; p < p1; ++p) s += ld_agent(src + (long long)p * NE);
   }
   part[sg * kCombineElems + el] = s;
   __syncthreads();
   if (sg == 0 && e < NE)
-    head_state[e] = ((part[el] + part[kCombineElems + el]) + part[2 * kCombineElems + el]) + part[3 * kCombineElems + el];
+    st_agent(head_state + e,
+             ((part[el] + part[kCombineElems + el]) + part[2 * kCombineElems + el]) + part[3 * kCombineElems + el]);
 }
 
 // grid = (ceil(NE / 64), B*H), block = 256, NE = d*d + d

@@ -100,17 +100,21 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   }
   const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
   const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
-  const double fused_max = (double)env_int("LINFUSION_FUSED_MAX_MB", 48) * 1048576.0;
+  // Measured on MI355X: below ~64 MB of tensor traffic the three short kernels are as fast as the
+  // single launch with its two in-kernel barriers; between ~64 MB and ~512 MB the single launch wins
+  // (no drain and refill of the chip between phases); above that both are HBM-bound and equal.
+  const double fused_min = (double)env_int("LINFUSION_FUSED_MIN_MB", 64) * 1048576.0;
+  const double fused_max = (double)env_int("LINFUSION_FUSED_MAX_MB", 512) * 1048576.0;
   p->path = 0;
   if (p->fsplits > 0 && !(flags & LINFUSION_FLAG_FORCE_SPLIT) &&
-      ((flags & LINFUSION_FLAG_FORCE_FUSED) || bytes <= fused_max))
+      ((flags & LINFUSION_FLAG_FORCE_FUSED) || (bytes >= fused_min && bytes <= fused_max)))
     p->path = 1;
   p->state_floats = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   const int smax = p->splits > p->fsplits ? p->splits : p->fsplits;
   p->ws_partials = up((size_t)BH * smax * p->state_floats * sizeof(float));
   p->ws_state = up((size_t)BH * p->state_floats * sizeof(float));
-  p->ws_sync = up((size_t)BH * sizeof(lf::HeadSync) + 16);
+  p->ws_sync = up((size_t)BH * 2 * (p->fsplits > 0 ? p->fsplits : 1) * sizeof(unsigned) + 16);
   p->ws_total = p->ws_partials + p->ws_state + p->ws_sync;
   return LINFUSION_OK;
 }
@@ -201,8 +205,8 @@ int run16(const Args& a) {
   u32x4* O = (u32x4*)a.out;
   hipStream_t st = a.st;
   if (p.path == 1 && a.out) {
-    HeadSync* sync = reinterpret_cast<HeadSync*>(a.ws + p.ws_partials + p.ws_state);
-    unsigned* err = reinterpret_cast<unsigned*>(sync + a.BH);
+    unsigned* sync = reinterpret_cast<unsigned*>(a.ws + p.ws_partials + p.ws_state);
+    unsigned* err = sync + a.BH * 2 * p.fsplits;
     const dim3 g(p.fsplits, (unsigned)a.BH);
     const size_t lds = fused16_lds_bytes<T, D>();
     bool launched = false;
@@ -256,8 +260,8 @@ int run32(const Args& a) {
   hipStream_t st = a.st;
   constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
   if (p.path == 1 && a.out) {
-    HeadSync* sync = reinterpret_cast<HeadSync*>(a.ws + p.ws_partials + p.ws_state);
-    unsigned* err = reinterpret_cast<unsigned*>(sync + a.BH);
+    unsigned* sync = reinterpret_cast<unsigned*>(a.ws + p.ws_partials + p.ws_state);
+    unsigned* err = sync + a.BH * 2 * p.fsplits;
     const dim3 g(p.fsplits, (unsigned)a.BH);
     bool launched = false;
 #define LF_FUSED(FM, NORM)                                                                           \
