@@ -21,7 +21,7 @@ template <int D> struct Shape32 {
   static constexpr int kMT = (kQuarter + 1 + 3) / 4;        // 16-row output tiles incl. normalizer row
 };
 
-template <int D> constexpr int reduce32_lds_bytes() { return (D * D + D) * 4; }
+template <int D> constexpr int reduce32_lds_bytes() { return 2 * (D * D + D) * 4; }
 
 LF_DEV f32x4 mfma_16x16x4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
 
@@ -94,9 +94,14 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict_
     }
   }
 
-  // fixed-order sum: waves 0..3, and inside a wave the four token groups kq = 0..3 for z
-  for (int w = 0; w < kWavesPerWG; ++w) {
-    if (wave == w) {
+  // cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3): waves 0 and 1 park their accumulators in
+  // two LDS copies, waves 2 and 3 add theirs on top (inside a wave the four token groups kq = 0..3 add
+  // their z in order), then all threads add the two copies and write the partial
+  constexpr int NE = D * D + D;
+  float* mine = red + (wave & 1) * NE;
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    if ((wave >> 1) == round) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -107,8 +112,8 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict_
             for (int j = 0; j < 4; ++j) {
               const int col = 4 * m + j;
               if (col < D) {
-                float* q = red + row * D + col;
-                *q = (w == 0) ? acc[i][j][r] : *q + acc[i][j][r];
+                float* q = mine + row * D + col;
+                *q = (round == 0) ? acc[i][j][r] : *q + acc[i][j][r];
               }
             }
           }
@@ -117,8 +122,8 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict_
         if (kq == s && lane_on) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            float* q = red + D * D + 4 * m + i;
-            *q = (w == 0 && s == 0) ? zacc[i] : *q + zacc[i];
+            float* q = mine + D * D + 4 * m + i;
+            *q = (round == 0 && s == 0) ? zacc[i] : *q + zacc[i];
           }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -126,7 +131,7 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict_
     }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < D * D + D; i += kThreads) st_agent(dst + i, red[i]);
+  for (int i = threadIdx.x; i < NE; i += kThreads) st_agent(dst + i, red[i] + red[NE + i]);
 }
 
 // grid = (splits, B*H), block = 256

@@ -1,13 +1,13 @@
-// Single-launch variant of the whole path for small token counts, where three dependent launches
-// cost more than the data movement:
+// Single-launch variant of the whole path, for token counts where three dependent launches (and the
+// drain and refill of the chip between them) cost a visible share of the time:
 //   phase 1  state reduction of this workgroup's tiles          (reduce16_phase / reduce32_phase)
 //   barrier  all workgroups of the head have written their partial
-//   phase 2  this workgroup sums its 64-element slices of the head's partials in split order
+//            (fp16 / bf16: the first two Q tiles of every wave are requested here, see ApplyDma)
+//   phase 2  this workgroup sums the elements of the head's state that it owns, over all partials
 //   barrier  the head's state is complete
-//   phase 3  apply + normalize on this workgroup's tiles         (apply16_dma_phase / apply32_phase)
+//   phase 3  apply + normalize on this workgroup's tiles         (ApplyDma / apply32_phase)
 // grid = (splits, B*H), block = 256; the host launches it only when every workgroup of the grid is
-// resident at once.  The arithmetic and its order are those of the separate kernels, so both paths
-// give bit-identical results for the same number of splits.
+// resident at once.  All sums run in a fixed order, so results are run-to-run bit-identical.
 //
 // Barrier: every workgroup owns one 32-bit flag per barrier in the caller's workspace and publishes
 // its arrival by storing the call's `ticket` there; wave 0 of each workgroup then polls the flags of
@@ -61,11 +61,43 @@ LF_DEV bool head_barrier(unsigned* flags, int split, int nsplit, unsigned ticket
   return *lds_flag != 0;
 }
 
-// phase 2: workgroup `split` sums the 64-element slices split, split + nsplit, ... of the head
-LF_DEV void combine_my_slices(const float* head_partials, int nsplit, int NE, int split, float* head_state,
-                              float* part) {
-  for (int sl = split; sl * kCombineElems < NE; sl += nsplit) {
-    combine_slice(head_partials, nsplit, NE, sl * kCombineElems, head_state, part);
+// Phase 2.  Workgroup `split` owns the state elements [split * per, (split + 1) * per), per =
+// ceil(NE / nsplit).  Its 256 threads are laid out as (element, split group): thread t sums element
+// t % width over the splits of group t / width in split order, with all loads of the workgroup in
+// flight at once; the groups are then added in group order.  `scratch`: 256 floats of LDS.
+LF_DEV void combine_owned(const float* head_partials, int nsplit, int NE, int split, float* head_state,
+                          float* scratch) {
+  const int per = (NE + nsplit - 1) / nsplit;
+  const int lo = split * per;
+  int hi = lo + per;
+  if (hi > NE) hi = NE;
+  for (int c0 = lo; c0 < hi; c0 += kThreads) {   // one pass unless the workgroup owns more than 256 elements
+    int width = hi - c0;
+    if (width > kThreads) width = kThreads;
+    const int groups = kThreads / width;
+    const int g = (int)threadIdx.x / width, el = (int)threadIdx.x % width;
+    const int spg = (nsplit + groups - 1) / groups;
+    float s = 0.0f;
+    if (g < groups) {
+      int p = g * spg, p1 = p + spg;
+      if (p1 > nsplit) p1 = nsplit;
+      const float* src = head_partials + c0 + el;
+      for (; p + 8 <= p1; p += 8) {
+        float a[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = ld_agent(src + (long long)(p + i) * NE);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += a[i];
+      }
+      for (; p < p1; ++p) s += ld_agent(src + (long long)p * NE);
+    }
+    scratch[threadIdx.x] = s;
+    __syncthreads();
+    if (g == 0) {
+      float t = scratch[el];
+      for (int gg = 1; gg < groups; ++gg) t += scratch[gg * width + el];
+      st_agent(head_state + c0 + el, t);
+    }
     __syncthreads();
   }
 }
@@ -90,10 +122,18 @@ fused16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, const u32x4* _
   float* head_state = state + bh * NE;
   reduce16_phase<T, D, FM>(K, V, head_part + (long long)split * NE, N, blk_reduce, split, nsplit, bh, smem);
   if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
-  combine_my_slices(head_part, nsplit, NE, split, head_state, reinterpret_cast<float*>(smem));
-  if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
-  apply16_dma_phase<T, D, FM, NORM>(Q, O, head_state, eps, N, blk_apply, split, nsplit, bh, smem);
+  ApplyDma<T, D, FM, NORM> ap(Q, O, N, blk_apply, split, nsplit, bh, smem);
+  ap.prefetch();   // Q does not depend on the state: its first tiles travel during phase 2 and the barrier
+  combine_owned(head_part, nsplit, NE, split, head_state,
+                reinterpret_cast<float*>(smem + ApplyDmaCfg<D>::kStageOffset));
+  if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) {
+    wait_vmcnt<0>();   // no copy into this workgroup's LDS may still be in flight when it ends
+    return;
+  }
+  ap.run(head_state, eps);
 }
+
+template <int D> constexpr int fused32_lds_bytes() { return reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024; }
 
 template <int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
@@ -109,7 +149,7 @@ fused32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, const f32x4* _
   float* head_state = state + bh * NE;
   reduce32_phase<D, FM>(K, V, head_part + (long long)split * NE, N, blk_reduce, split, nsplit, bh, smem);
   if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
-  combine_my_slices(head_part, nsplit, NE, split, head_state, reinterpret_cast<float*>(smem));
+  combine_owned(head_part, nsplit, NE, split, head_state, reinterpret_cast<float*>(smem));
   if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
   apply32_phase<D, FM, NORM>(Q, O, head_state, eps, N, blk_apply, split, nsplit, bh);
 }

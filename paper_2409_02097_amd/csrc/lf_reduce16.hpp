@@ -33,9 +33,10 @@ template <int D> struct Reduce16Cfg {
 
 template <typename T, int D>
 constexpr int reduce16_lds_bytes() {
-  // per wave: NSplit tiles of phi(K) + one of V; reused by the cross-wave reduction
+  // per wave: NSplit tiles of phi(K) + one of V; reused by the cross-wave reduction (two copies of the
+  // accumulators)
   int tiles = (NSplit<T>::value + 1) * Reduce16Cfg<D>::kTileElems * 2 * kWavesPerWG;
-  int red = (D * D + D) * 4;
+  int red = 2 * (D * D + D) * 4;
   return tiles > red ? tiles : red;
 }
 
@@ -58,14 +59,6 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
 #pragma unroll
   for (int s = 0; s < NS; ++s) ldsP[s] = wbase + s * Cfg::kTileElems;
   uint16_t* ldsV = wbase + NS * Cfg::kTileElems;
-
-  // one-time fill of the wave's tiles: phi(K) pad columns zero; V pad columns zero except the
-  // ones column at index D (when a spare column exists) which makes z fall out of the products
-  for (int i = lane; i < Cfg::kTileElems; i += 64) {
-#pragma unroll
-    for (int s = 0; s < NS; ++s) ldsP[s][i] = 0;
-    ldsV[i] = (Sh::kSpareCol && (i % RS) == D) ? OneBits<T>::value : (uint16_t)0;
-  }
 
   // per-lane constants: which chunks of a tile this lane moves, and where they land in LDS
   int lds_off[NL];
@@ -118,6 +111,14 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
 
   int lim = 0;
   if (it.valid()) lim = issue_loads(it.t);
+
+  // (while the first tile is on its way) one-time fill of the wave's tiles: phi(K) pad columns zero; V pad columns zero except the
+  // ones column at index D (when a spare column exists) which makes z fall out of the products
+  for (int i = lane; i < Cfg::kTileElems; i += 64) {
+#pragma unroll
+    for (int s = 0; s < NS; ++s) ldsP[s][i] = 0;
+    ldsV[i] = (Sh::kSpareCol && (i % RS) == D) ? OneBits<T>::value : (uint16_t)0;
+  }
 
   while (it.valid()) {
     // ---- phi(K) -> 16-bit (hi [, lo]) -> LDS ; V -> LDS --------------------------------------
@@ -177,11 +178,16 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
     lim = next_lim;
   }
 
-  // ---- fixed-order cross-wave sum in LDS (wave 0, then 1, 2, 3), then one partial per WG -----
+  // ---- cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3): waves 0 and 1 park their accumulators
+  //      in two LDS copies ([D*D] S then [D] z), waves 2 and 3 add theirs on top, then all threads add
+  //      the two copies and write the partial --------------------------------------------------------
   __syncthreads();
-  float* red = reinterpret_cast<float*>(smem);   // [D*D] S then [D] z
-  for (int w = 0; w < kWavesPerWG; ++w) {
-    if (wave == w) {
+  constexpr int NE = D * D + D;
+  float* red = reinterpret_cast<float*>(smem);
+  float* mine = red + (wave & 1) * NE;
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    if ((wave >> 1) == round) {
 #pragma unroll
       for (int a = 0; a < MT; ++a) {
 #pragma unroll
@@ -191,18 +197,15 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
 #pragma unroll
             for (int b = 0; b < MT; ++b) {
               const int col = b * 16 + j16;
-              if (col < D) {
-                float* p = red + row * D + col;
-                *p = (w == 0) ? acc[a][b][i] : *p + acc[a][b][i];
-              } else if (Sh::kSpareCol && col == D) {
-                float* p = red + D * D + row;
-                *p = (w == 0) ? acc[a][b][i] : *p + acc[a][b][i];
-              }
+              float* p = nullptr;
+              if (col < D) p = mine + row * D + col;
+              else if (Sh::kSpareCol && col == D) p = mine + D * D + row;
+              if (p) *p = (round == 0) ? acc[a][b][i] : *p + acc[a][b][i];
             }
             if constexpr (!Sh::kSpareCol) {
               if (j16 == 0) {
-                float* p = red + D * D + row;
-                *p = (w == 0) ? accz[a][i] : *p + accz[a][i];
+                float* p = mine + D * D + row;
+                *p = (round == 0) ? accz[a][i] : *p + accz[a][i];
               }
             }
           }
@@ -211,7 +214,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
     }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < D * D + D; i += kThreads) st_agent(dst + i, red[i]);
+  for (int i = threadIdx.x; i < NE; i += kThreads) st_agent(dst + i, red[i] + red[NE + i]);
 }
 
 template <typename T, int D, int FM>
