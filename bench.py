@@ -84,6 +84,46 @@ def cpu_baseline(q, k, v, cfg, sample_tokens):
                       f"{os.cpu_count()} logical cores, BLAS threads = {threads}"}, ref
 
 
+def latency_table(steps=200):
+    """Per-call latency of the small and medium workloads (they fit the 256 MB memory-side cache):
+    'hot' = the same buffers back to back, 'cold' = rotating through enough independent buffer sets
+    (> 768 MB in total) that every call streams from HBM.  One JSON line per workload on stderr."""
+    import torch
+    import paper_2409_02097_amd as lf
+    from paper_2409_02097_amd import workloads as wl
+    for name, cfg in wl.CONFIGS.items():
+        if name == DEFAULT_WORKLOAD:
+            continue
+        B, H, N, d, dtype = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["dtype"]
+        code = wl.DTYPE_CODE[dtype]
+        nbytes = wl.algorithmic_bytes(B, H, N, d, dtype)
+        nsets = max(2, int(768e6 // nbytes) + 1)
+        q0, k0, v0 = wl.make_config(name, device="cuda")
+        sets = [(q0, k0, v0, torch.empty_like(q0))] + [
+            (q0.clone(), k0.clone(), v0.clone(), torch.empty_like(q0)) for _ in range(nsets - 1)]
+        ws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
+        row = {"workload": name, "B": B, "H": H, "N": N, "d": d, "dtype": dtype, "algorithmic_bytes": nbytes,
+               "ideal_us_at_8TBps": nbytes / 8e6, "buffer_sets_cold": nsets}
+        for label, flags in (("auto", 0), ("split", lf.FLAG_FORCE_SPLIT), ("fused", lf.FLAG_FORCE_FUSED)):
+            for mode in ("hot", "cold"):
+                use = sets[:1] if mode == "hot" else sets
+                for i in range(10):
+                    q, k, v, o = use[i % len(use)]
+                    lf.linfusion_attn_fwd_ex(q, k, v, o, lf.PHI_ELU_PLUS_ONE, wl.EPS, flags, ws)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for i in range(steps):
+                    q, k, v, o = use[i % len(use)]
+                    lf.linfusion_attn_fwd_ex(q, k, v, o, lf.PHI_ELU_PLUS_ONE, wl.EPS, flags, ws)
+                torch.cuda.synchronize()
+                us = (time.perf_counter() - t0) / steps * 1e6
+                row[f"{label}_{mode}_us"] = round(us, 2)
+                row[f"{label}_{mode}_gbps"] = round(nbytes / us / 1e3, 1)
+            row[f"{label}_path"] = lf.linfusion_attn_plan(B, H, N, d, code, flags)["path"]
+        print(json.dumps(row), file=sys.stderr, flush=True)
+        del sets
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +134,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=1 << 21)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--latency-table", action="store_true",
+                    help="also time the small and medium workloads, hot and cold cache, both launch paths "
+                         "(JSON lines on stderr; the one-line result on stdout is unchanged)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of one tensor (known size) so that a rocprofv3 --pmc "
                          "run of this command holds the reference reading for FETCH_SIZE / WRITE_SIZE")
@@ -185,6 +228,10 @@ def main():
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(q, k, v, cfg, args.cpu_sample_tokens)
         result["cpu_baseline"] = base
+    if args.latency_table:
+        del q, k, v, out
+        torch.cuda.empty_cache()
+        latency_table()
     print(json.dumps(result), flush=True)
 
 
