@@ -51,7 +51,7 @@ extern "C" {
 #define LINFUSION_FLAG_NONE 0u
 #define LINFUSION_FLAG_UNNORMALIZED 1u /* out_i = phi(q_i) S, the un-normalized arm of Tab. 2 */
 #define LINFUSION_FLAG_FORCE_SPLIT 2u  /* always take the three-kernel split-N path */
-#define LINFUSION_FLAG_FORCE_FUSED 4u  /* always take the single-launch small-N path */
+#define LINFUSION_FLAG_FORCE_FUSED 4u  /* take the single-launch path whenever the shape allows it */
 
 #define LINFUSION_OK 0
 #define LINFUSION_ERR_INVALID (-1)     /* NULL pointer, B/H/N/d <= 0, eps < 0 or NaN, bad flags */
@@ -61,10 +61,21 @@ extern "C" {
 #define LINFUSION_ERR_HIP (-5)         /* a HIP runtime call or kernel launch failed */
 #define LINFUSION_ERR_DEVICE (-6)      /* no HIP device, or the current device is not gfx950 */
 #define LINFUSION_ERR_OVERLAP (-7)     /* out overlaps k or v, or partially overlaps q */
+#define LINFUSION_ERR_TIMEOUT (-8)     /* a single-launch call gave up waiting at its internal barrier */
 
 /*
  * General entry point: the whole hot path (feature map -> split-N state reduction ->
  * deterministic combine -> apply + normalize) for one [B, H, N, d] problem.
+ *
+ * Two launch shapes compute it.  The split path enqueues three kernels (state reduction,
+ * combine, apply).  The single-launch path runs the same three phases in one kernel whose
+ * workgroups meet at two per-head barriers; it is chosen automatically for mid-sized problems
+ * (about 64 MB to 512 MB of tensor traffic, where draining and refilling the chip between
+ * kernels costs a visible share), can be forced or forbidden with the flags, and is used only
+ * when all of its workgroups are resident at once (otherwise the call falls back to the split
+ * path).  Its barrier waits are bounded: if a wait ever expires (which needs another workload
+ * to hold the device's compute units for seconds) the kernel ends early, `out` is incomplete,
+ * and linfusion_attn_last_error reports LINFUSION_ERR_TIMEOUT.
  *
  *   dtype            LINFUSION_DTYPE_*; accumulation is fp32 for every dtype.
  *   feature_map      LINFUSION_PHI_*.
@@ -92,6 +103,14 @@ int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void
                                int dtype, int feature_map, float eps, unsigned flags,
                                void* workspace, size_t workspace_bytes, void* stream,
                                void* events[4]);
+
+/*
+ * Synchronises `stream` and reports whether the most recent single-launch call that used this
+ * workspace for this shape completed: LINFUSION_OK, LINFUSION_ERR_TIMEOUT, or an argument / HIP
+ * error code.  (The split path cannot time out; after it this returns LINFUSION_OK.)
+ */
+int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes,
+                              int B, int H, long long N, int d, int dtype, void* stream);
 
 /*
  * Bytes of device scratch linfusion_attn_fwd_ex needs for this shape.  Pure host function of
@@ -139,8 +158,9 @@ int linfusion_version(void);
 /*
  * Introspection for benchmarks and tests (host only, no device work): the launch plan the
  * forward call will use for this shape.  plan[0] = path (0 = split-N three-kernel path,
- * 1 = fused single launch), plan[1] = state-reduction workgroups per head, plan[2] = apply
- * workgroups per head, plan[3] = tokens per tile.  Returns LINFUSION_OK or an error code.
+ * 1 = single launch), plan[1] = state-reduction workgroups per head, plan[2] = apply
+ * workgroups per head (on the single-launch path both are its workgroups per head),
+ * plan[3] = tokens per tile.  Returns LINFUSION_OK or an error code.
  */
 int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned flags, int plan[4]);
 

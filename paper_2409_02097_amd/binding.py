@@ -46,6 +46,8 @@ def library() -> ctypes.CDLL:
     lib.linfusion_attn_fwd_profile.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp,
                                                ctypes.POINTER(ctypes.c_void_p * 4)]
     lib.linfusion_attn_fwd_profile.restype = i32
+    lib.linfusion_attn_last_error.argtypes = [vp, sz, i32, i32, i64, i32, i32, vp]
+    lib.linfusion_attn_last_error.restype = i32
     lib.linfusion_attn_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
     lib.linfusion_attn_workspace_bytes.restype = sz
     for name in ("linfusion_attn_fwd", "linfusion_attn_fwd_f16", "linfusion_attn_fwd_bf16", "linfusion_attn_fwd_f32"):
@@ -98,6 +100,12 @@ def linfusion_version() -> int:
 
 def linfusion_attn_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int) -> int:
     return int(library().linfusion_attn_workspace_bytes(B, H, N, d, dtype))
+
+
+def linfusion_attn_last_error(workspace, B: int, H: int, N: int, d: int, dtype: int, stream=None) -> int:
+    """Synchronises the stream; 0, or LINFUSION_ERR_TIMEOUT (-8) if the last single-launch call gave up."""
+    return int(library().linfusion_attn_last_error(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                   B, H, N, d, dtype, _stream_ptr(stream)))
 
 
 def linfusion_attn_plan(B: int, H: int, N: int, d: int, dtype: int, flags: int = 0):

@@ -52,7 +52,10 @@ LF_DEV bool head_barrier(unsigned* flags, int split, int nsplit, unsigned ticket
       }
     }
     if (threadIdx.x == 0) {
-      if (!ok) __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (!ok) {   // error word: {ticket of the failing call, 1}
+        __hip_atomic_store(err, ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(err + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
       *lds_flag = ok;
     }
   }

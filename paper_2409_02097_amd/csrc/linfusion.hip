@@ -123,6 +123,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
 int g_dev_ok[kMaxDevices];   // 0 = unknown, 1 = gfx950, -1 = something else
 std::mutex g_mu;
 std::atomic<unsigned> g_ticket{1};
+std::atomic<unsigned> g_last_ticket{0};   // ticket of the most recent single-launch call
 
 int check_device() {
   int dev = -1;
@@ -145,6 +146,7 @@ bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
 unsigned next_ticket() {
   unsigned t = g_ticket.fetch_add(1, std::memory_order_relaxed);
   if (t == 0) t = g_ticket.fetch_add(1, std::memory_order_relaxed);
+  g_last_ticket.store(t, std::memory_order_relaxed);
   return t;
 }
 
@@ -173,7 +175,13 @@ struct Args {
   hipEvent_t* ev;
 };
 
-constexpr unsigned kSpinLimit = 4u << 20;   // polls of ~1 us each before a fused launch gives up
+// polls (of about a microsecond each) before a single-launch call gives up at a barrier; the
+// environment override exists so that a test can force the give-up path from the host
+unsigned spin_limit() {
+  const char* s = getenv("LINFUSION_FUSED_SPIN_LIMIT");
+  if (s && *s) return (unsigned)strtoul(s, nullptr, 10);
+  return 4u << 20;
+}
 
 // ---- kernel dispatch ---------------------------------------------------------------------------------
 #define LF_FOR_D(X) X(8) X(16) X(24) X(32) X(40) X(48) X(56) X(64)
@@ -214,7 +222,7 @@ int run16(const Args& a) {
   if (fits_resident(fused16<T, D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                        \
     if (a.ev) (void)hipEventRecord(a.ev[0], st);                                                         \
     fused16<T, D, FM, NORM><<<g, blk, lds, st>>>(K, V, Q, O, partials, state, sync, err, next_ticket(),  \
-                                                 kSpinLimit, a.eps, a.N, p.fblk_reduce, p.fblk_apply);   \
+                                                 spin_limit(), a.eps, a.N, p.fblk_reduce, p.fblk_apply);   \
     launched = true;                                                                                     \
   }
     LF_SWITCH_FM_NORM(LF_FUSED)
@@ -268,7 +276,7 @@ int run32(const Args& a) {
   if (fits_resident(fused32<D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                       \
     if (a.ev) (void)hipEventRecord(a.ev[0], st);                                                     \
     fused32<D, FM, NORM><<<g, blk, lds, st>>>(K, V, Q, O, partials, state, sync, err, next_ticket(),  \
-                                              kSpinLimit, a.eps, a.N, p.fblk_reduce, p.fblk_apply);  \
+                                              spin_limit(), a.eps, a.N, p.fblk_reduce, p.fblk_apply);  \
     launched = true;                                                                                 \
   }
     LF_SWITCH_FM_NORM(LF_FUSED)
@@ -412,6 +420,25 @@ int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void
   return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, flags, workspace, workspace_bytes, stream, ev);
 }
 
+int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes, int B, int H, long long N, int d,
+                              int dtype, void* stream) {
+  if (!workspace) return LINFUSION_ERR_INVALID;
+  Plan p;
+  int rc = make_plan(B, H, N, d, dtype, 0u, &p);
+  if (rc != LINFUSION_OK) return rc;
+  if (workspace_bytes < p.ws_total) return LINFUSION_ERR_WORKSPACE;
+  rc = check_device();
+  if (rc != LINFUSION_OK) return rc;
+  const unsigned char* ws = (const unsigned char*)workspace;
+  const unsigned* err = reinterpret_cast<const unsigned*>(ws + p.ws_partials + p.ws_state) +
+                        (size_t)B * H * 2 * (p.fsplits > 0 ? p.fsplits : 1);
+  unsigned pair[2] = {0, 0};   // {ticket of the call that raised it, 1}
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
+  if (hipMemcpy(pair, err, sizeof(pair), hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
+  // the word is meaningful only when it carries the ticket of the last single-launch call on this process
+  return (pair[1] == 1u && pair[0] != 0u && pair[0] == g_last_ticket.load()) ? LINFUSION_ERR_TIMEOUT : LINFUSION_OK;
+}
+
 size_t linfusion_attn_workspace_bytes(int B, int H, long long N, int d, int dtype) {
   Plan p;
   if (make_plan(B, H, N, d, dtype, 0u, &p) != LINFUSION_OK) return 0;
@@ -480,6 +507,7 @@ const char* linfusion_status_string(int status) {
     case LINFUSION_ERR_HIP: return "HIP runtime or launch error";
     case LINFUSION_ERR_DEVICE: return "no gfx950 device";
     case LINFUSION_ERR_OVERLAP: return "buffers overlap";
+    case LINFUSION_ERR_TIMEOUT: return "single-launch barrier wait expired";
     default: return "unknown status";
   }
 }

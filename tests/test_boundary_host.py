@@ -34,7 +34,7 @@ def test_library_exports_every_declared_symbol():
 def test_version_and_status_strings():
     assert lf.linfusion_version() >= 100
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = lf.linfusion_status_string(code)
         assert s and s != "unknown status" and s not in seen
         seen.add(s)

@@ -154,3 +154,34 @@ def test_owned_workspace_entry_points():
         torch.cuda.synchronize()
         assert torch.equal(out.view(torch.uint8), _run(q, k, v).view(torch.uint8))
     lf.linfusion_release()
+
+
+def test_single_launch_timeout_is_reported_and_harmless(monkeypatch):
+    # a spin limit of zero makes every workgroup that does not see all arrivals at its first poll give
+    # up: the kernel must still end (no hang), the error must be reported, and the next call must work
+    B, H, N, d = 2, 4, 20000, 40
+    q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=68, device="cuda")
+    ws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, 1), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(q)
+    assert lf.linfusion_attn_plan(B, H, N, d, 1, lf.FLAG_FORCE_FUSED)["reduce_wgs_per_head"] > 8
+    monkeypatch.setenv("LINFUSION_FUSED_SPIN_LIMIT", "0")
+    lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws)
+    rc = lf.linfusion_attn_last_error(ws, B, H, N, d, 1)
+    assert rc in (0, -8)          # -8 unless every workgroup happened to arrive before the first poll
+    print("forced give-up ->", rc, flush=True)
+    monkeypatch.delenv("LINFUSION_FUSED_SPIN_LIMIT")
+    lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws)
+    assert lf.linfusion_attn_last_error(ws, B, H, N, d, 1) == 0
+    parity.check_all(out, q.cpu(), k.cpu(), v.cpu(), "f16", 0, 1e-6, True, "after a forced give-up")
+    # the split path never reports a timeout
+    lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, lf.FLAG_FORCE_SPLIT, ws)
+    assert lf.linfusion_attn_last_error(ws, B, H, N, d, 1) == 0
+
+
+def test_single_launch_falls_back_when_heads_exceed_residency():
+    # more (batch, head) slices than resident workgroups: the single-launch path is not available
+    B, H, N, d = 8, 160, 64, 64
+    assert lf.linfusion_attn_plan(B, H, N, d, 1, lf.FLAG_FORCE_FUSED)["path"] == 0
+    q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=69, device="cpu")
+    out = _run(q.cuda(), k.cuda(), v.cuda(), flags=lf.FLAG_FORCE_FUSED)
+    parity.check_all(out, q, k, v, "f16", 0, 1e-6, True, "fallback")
