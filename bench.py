@@ -134,6 +134,9 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=1 << 21)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flags", type=int, default=0)
+    ap.add_argument("--layout", choices=["head_major", "token_major"], default="head_major",
+                    help="memory layout of q, k, v, out: contiguous [B, H, N, d] (the headline workload) or the "
+                         "UNet's [B, N, H*d] handed over as strided views")
     ap.add_argument("--latency-table", action="store_true",
                     help="also time the small and medium workloads, hot and cold cache, both launch paths "
                          "(JSON lines on stderr; the one-line result on stdout is unchanged)")
@@ -157,16 +160,21 @@ def main():
     cfg = wl.CONFIGS[args.workload]
     B, H, N, d, dtype = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["dtype"]
     q, k, v = wl.make_config(args.workload, device="cuda")
-    out = torch.empty_like(q)
+    if args.layout == "token_major":
+        tm = lambda t: t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)   # [B, N, H, d] in memory
+        qd, kd, vd = tm(q), tm(k), tm(v)
+    else:
+        qd, kd, vd = q, k, v
+    out = torch.empty_like(qd)          # keeps the strides of qd
     code = wl.DTYPE_CODE[dtype]
     ws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
     plan = lf.linfusion_attn_plan(B, H, N, d, code, args.flags)
 
     def step():
-        lf.linfusion_attn_fwd_ex(q, k, v, out, lf.PHI_ELU_PLUS_ONE, wl.EPS, args.flags, ws)
+        lf.linfusion_attn_fwd_strided(qd, kd, vd, out, lf.PHI_ELU_PLUS_ONE, wl.EPS, args.flags, ws)
 
     if args.calibrate_copy:
-        out.copy_(q)             # reads and writes B*H*N*d*itemsize bytes exactly once each
+        out.copy_(qd)            # reads and writes B*H*N*d*itemsize bytes exactly once each
         torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
@@ -184,7 +192,7 @@ def main():
     evs = HipEvents(4)
     acc = [0.0, 0.0, 0.0]
     for _ in range(args.profile_steps):
-        lf.linfusion_attn_fwd_profile(q, k, v, out, lf.PHI_ELU_PLUS_ONE, wl.EPS, args.flags, ws, evs.ev)
+        lf.linfusion_attn_fwd_profile(qd, kd, vd, out, lf.PHI_ELU_PLUS_ONE, wl.EPS, args.flags, ws, evs.ev)
         evs.sync(3)
         for i in range(3):
             acc[i] += evs.elapsed_ms(i, i + 1)
@@ -220,7 +228,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": args.workload, "B": B, "H": H, "N": N, "d": d, "eps": wl.EPS,
-                   "feature_map": "elu+1", "plan": plan},
+                   "feature_map": "elu+1", "layout": args.layout, "plan": plan},
         "hbm_gbps": alg_bytes / (dt / args.steps) / 1e9,
         "hbm_frac_of_peak": alg_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "roofline": roofline,
@@ -229,7 +237,7 @@ def main():
         base, ref = cpu_baseline(q, k, v, cfg, args.cpu_sample_tokens)
         result["cpu_baseline"] = base
     if args.latency_table:
-        del q, k, v, out
+        del q, k, v, qd, kd, vd, out
         torch.cuda.empty_cache()
         latency_table()
     print(json.dumps(result), flush=True)

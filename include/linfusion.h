@@ -19,6 +19,7 @@
  *   - q, k, v, out: DEVICE pointers to contiguous [B, H, N, d] tensors, d fastest, all of the
  *     same element type; `out` has the element type of the inputs.  Base pointers must be
  *     16-byte aligned.  `out` must not overlap k or v; out == q (exact alias) is allowed.
+ *     (linfusion_attn_fwd_strided takes other layouts, e.g. the token-major [B, N, H*d].)
  *   - The caller owns every buffer and keeps it alive until the work enqueued on `stream`
  *     has completed.  Calls are asynchronous: they enqueue on `stream` (a hipStream_t passed
  *     as void*; NULL = the default stream) and return without synchronising.
@@ -94,13 +95,46 @@ int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out
                           void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Benchmark aid: linfusion_attn_fwd_ex that also records four caller-created hipEvent_t
+ * linfusion_attn_fwd_ex on tensors that are views into larger buffers, so that the layer around
+ * the mixer needs no permute or copy: the UNet's token-major activations [B, N, H*d] (Sec. 3:
+ * the module replaces self-attention inside each transformer block, whose q/k/v projections emit
+ * that layout), or q, k, v sliced out of one fused projection output.
+ *
+ * Each *_strides array holds HOST values, in ELEMENTS: {batch stride, head stride, token stride}.
+ * The d channels of one token of one head are always contiguous.  q has its own strides, k and v
+ * share one set, out has its own.  Examples for element (b, h, n, c):
+ *     contiguous [B, H, N, d]  : {H*N*d, N*d, d}
+ *     token-major [B, N, H*d]  : {N*H*d, d, H*d}
+ *     k, v inside [B, N, 2, H, d] : {N*2*H*d, d, 2*H*d} with k = base, v = base + H*d
+ * A NULL array means contiguous [B, H, N, d].
+ *
+ * Requirements: every stride is >= 0 and a multiple of 16 bytes (8 elements for the 16-bit types,
+ * 4 for fp32), so that with 16-byte aligned base pointers every token row is 16-byte aligned;
+ * token stride below 2^24 * 16 bytes (else LINFUSION_ERR_INVALID).  Input strides may be 0 (one
+ * k, v shared by all heads, say).  The rows of `out` must not overlap one another
+ * (LINFUSION_ERR_OVERLAP).  Overlap between tensors is judged on the byte range each view spans from
+ * its first to its last element: the range of `out` must be disjoint from those of k and v and
+ * from that of q, except that out == q with identical strides (in place) is allowed.
+ * Everything else is as for linfusion_attn_fwd_ex (same workspace size, same two launch paths).
+ */
+int linfusion_attn_fwd_strided(const void* q, const void* k, const void* v, void* out,
+                               int B, int H, long long N, int d,
+                               int dtype, int feature_map, float eps, unsigned flags,
+                               const long long q_strides[3], const long long kv_strides[3],
+                               const long long out_strides[3],
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Benchmark aid: linfusion_attn_fwd_strided that also records four caller-created hipEvent_t
  * (passed as void*) on `stream`: events[0] before the state reduction, [1] after it, [2] after
- * the combine, [3] after apply, so a harness can time each kernel of one call.
+ * the combine, [3] after apply, so a harness can time each kernel of one call.  The stride
+ * arrays may be NULL (contiguous).
  */
 int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void* out,
                                int B, int H, long long N, int d,
                                int dtype, int feature_map, float eps, unsigned flags,
+                               const long long q_strides[3], const long long kv_strides[3],
+                               const long long out_strides[3],
                                void* workspace, size_t workspace_bytes, void* stream,
                                void* events[4]);
 

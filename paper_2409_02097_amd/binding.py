@@ -43,8 +43,12 @@ def library() -> ctypes.CDLL:
                                   ctypes.c_uint, ctypes.c_size_t)
     lib.linfusion_attn_fwd_ex.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp]
     lib.linfusion_attn_fwd_ex.restype = i32
-    lib.linfusion_attn_fwd_profile.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp,
-                                               ctypes.POINTER(ctypes.c_void_p * 4)]
+    st3 = ctypes.POINTER(ctypes.c_longlong * 3)
+    lib.linfusion_attn_fwd_strided.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, st3, st3, st3,
+                                               vp, sz, vp]
+    lib.linfusion_attn_fwd_strided.restype = i32
+    lib.linfusion_attn_fwd_profile.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, st3, st3, st3,
+                                               vp, sz, vp, ctypes.POINTER(ctypes.c_void_p * 4)]
     lib.linfusion_attn_fwd_profile.restype = i32
     lib.linfusion_attn_last_error.argtypes = [vp, sz, i32, i32, i64, i32, i32, vp]
     lib.linfusion_attn_last_error.restype = i32
@@ -90,6 +94,23 @@ def _check_layout(*tensors):
     return shape
 
 
+def _check_views(q, k, v, out):
+    """[B, H, N, d]-shaped views with any batch / head / token strides and contiguous channels."""
+    shape = q.shape
+    for t in (q, k, v, out):
+        if t.dim() != 4 or t.shape != shape or t.dtype != q.dtype or not t.is_cuda:
+            raise ValueError("q, k, v, out must be [B, H, N, d]-shaped device views of one dtype and shape")
+        if t.shape[3] > 1 and t.stride(3) != 1:
+            raise ValueError("the d channels of a token must be contiguous")
+    if k.stride() != v.stride():
+        raise ValueError("k and v must share their strides")
+    return shape
+
+
+def _strides3(t):
+    return (ctypes.c_longlong * 3)(t.stride(0), t.stride(1), t.stride(2))
+
+
 def linfusion_status_string(status: int) -> str:
     return library().linfusion_status_string(int(status)).decode()
 
@@ -131,13 +152,31 @@ def linfusion_attn_fwd_ex(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps
     return rc
 
 
+def linfusion_attn_fwd_strided(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6,
+                               flags: int = FLAG_NONE, workspace=None, stream=None, check: bool = True) -> int:
+    """out <- mixer(q, k, v) on [B, H, N, d]-shaped VIEWS (e.g. `x.view(B, N, H, d).permute(0, 2, 1, 3)` of a
+    token-major activation): the views' strides are handed to the library, nothing is copied."""
+    B, H, N, d = _check_views(q, k, v, out)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = library().linfusion_attn_fwd_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d,
+                                              _dtype_code(q), feature_map, eps, flags, ctypes.byref(_strides3(q)),
+                                              ctypes.byref(_strides3(k)), ctypes.byref(_strides3(out)), ws_ptr,
+                                              ws_bytes, _stream_ptr(stream))
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_fwd_strided")
+    return rc
+
+
 def linfusion_attn_fwd_profile(q, k, v, out, feature_map, eps, flags, workspace, events, stream=None,
                                check: bool = True) -> int:
-    """Like linfusion_attn_fwd_ex; `events` = four hipEvent_t handles (ints) recorded around the kernels."""
-    B, H, N, d = _check_layout(q, k, v, out)
+    """Like linfusion_attn_fwd_strided; `events` = four hipEvent_t handles (ints) recorded around the kernels."""
+    B, H, N, d = _check_views(q, k, v, out)
     ev = (ctypes.c_void_p * 4)(*[ctypes.c_void_p(int(e)) for e in events])
     rc = library().linfusion_attn_fwd_profile(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d,
-                                              _dtype_code(q), feature_map, eps, flags, workspace.data_ptr(),
+                                              _dtype_code(q), feature_map, eps, flags, ctypes.byref(_strides3(q)),
+                                              ctypes.byref(_strides3(k)), ctypes.byref(_strides3(out)),
+                                              workspace.data_ptr(),
                                               workspace.numel() * workspace.element_size(), _stream_ptr(stream),
                                               ctypes.byref(ev))
     if check and rc != 0:

@@ -69,8 +69,12 @@ constexpr int apply16_dma_lds_bytes() {
 
 template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// One workgroup's apply work on head `bh`: construct, prefetch(), run().
-template <typename T, int D, int FM, bool NORM>
+// One workgroup's apply work: construct, prefetch(), run() -- or, with HG ("one head per wave": the four
+// waves work on four different heads over the same tiles, every wave visiting all of the workgroup's
+// tiles), construct with the wave's own pointers, prefetch(), load_state() once per head of the group,
+// stream().  HG stores are ordinary cached stores: the waves of a group fill neighbouring pieces of
+// the same memory rows, which the cache then writes back whole.
+template <typename T, int D, int FM, bool NORM, bool HG = false>
 struct ApplyDma {
   using Sh = Shape16<D>;
   using Cfg = ApplyDmaCfg<D>;
@@ -83,15 +87,23 @@ struct ApplyDma {
   u32x4* Oh;
   long long N;
   unsigned char* smem;
+  int rs_q, rs_o;
   int lane, wave, tok, kg, row_byte, tsw;
-  int goff[NL];   // LDS position p = 64 u + lane of a slot holds global chunk goff[u] of the tile
+  // LDS position p = 64 u + lane of a slot holds the chunk of token row trow[u] that lies qoff[u]
+  // (in Q) / ooff[u] (in out) vector units after the tile's first row
+  int trow[NL], qoff[NL], ooff[NL];
   TileIter it, ahead;
+  u32x4 A[NSplit<T>::value][Shape16<D>::kMT2][Shape16<D>::kKS];   // this wave's state operands
+  float c1, eps_s;
 
-  LF_DEV ApplyDma(const u32x4* Q, u32x4* O, long long N_, int tiles_per_block, int wg, int nwg, long long bh,
-                  unsigned char* smem_)
-      : Qh(Q + bh * N_ * CPR), Oh(O + bh * N_ * CPR), N(N_), smem(smem_),
+  // `Qh_`, `Oh_`: first token row of this head; `rs_q_`, `rs_o_`: row strides in 16-byte units
+  LF_DEV ApplyDma(const u32x4* Qh_, int rs_q_, u32x4* Oh_, int rs_o_, long long N_, int tiles_per_block, int wg,
+                  int nwg, unsigned char* smem_, bool active = true)
+      : Qh(Qh_), Oh(Oh_), N(N_), smem(smem_), rs_q(rs_q_), rs_o(rs_o_),
         lane(threadIdx.x & 63), wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
-        it(wg, nwg, wave, tiles_per_block, (N_ + kTile - 1) / kTile), ahead(it) {
+        it(wg, nwg, HG ? 0 : wave, tiles_per_block, (HG && !active) ? 0 : (N_ + kTile - 1) / kTile,
+           HG ? 1 : kWavesPerWG),
+        ahead(it) {
     tok = lane & 31;
     kg = lane >> 5;
     row_byte = tok * Cfg::kRowBytes;
@@ -100,7 +112,9 @@ struct ApplyDma {
     for (int u = 0; u < NL; ++u) {
       const int p = u * 64 + lane;
       const int r = p / CPR, pos = p % CPR;
-      goff[u] = r * CPR + (pos ^ Cfg::swz(r));
+      trow[u] = r;
+      qoff[u] = r * rs_q + (pos ^ Cfg::swz(r));
+      ooff[u] = r * rs_o + (pos ^ Cfg::swz(r));
     }
   }
 
@@ -108,15 +122,14 @@ struct ApplyDma {
 
   // copies tile `tile` into ring slot `slot`; always issues exactly NL vector memory instructions
   LF_DEV void issue_copy(long long tile, int slot) {
-    long long rem = (N - tile * kTile) * CPR;
-    const int lim = rem < Cfg::kChunks ? (int)rem : Cfg::kChunks;
-    const u32x4* qp = Qh + tile * Cfg::kChunks;
+    long long rem = N - tile * kTile;
+    const int lim = rem < kTile ? (int)rem : kTile;   // valid token rows
+    const u32x4* qp = Qh + tile * kTile * rs_q;
     unsigned char* sl = slot_ptr(slot);
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
       if (u * 64 + lane < Cfg::kChunks) {          // lanes past the tile would deposit past the slot's rows
-        int c = goff[u];
-        c = c < lim ? c : 0;                       // rows past N re-read chunk 0; their results are never stored
+        const int c = trow[u] < lim ? qoff[u] : 0; // rows past N re-read chunk 0; their results are never stored
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
                                          (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
       }
@@ -134,6 +147,12 @@ struct ApplyDma {
 
   // `state`: this head's [D*D + D] fp32 state.  The staging area (from kStageOffset) must be free.
   LF_DEV void run(const float* state, float eps) {
+    load_state(state, eps, true);
+    stream();
+  }
+
+  // Whole workgroup: stages one head's state in LDS; the waves with `keep` build their operands from it.
+  LF_DEV void load_state(const float* state, float eps, bool keep) {
     // ---- prologue: state -> LDS, maxima, power-of-two scales, A fragments -------------------------
     float* st = reinterpret_cast<float*>(smem + Cfg::kStageOffset);
     float* redmax = st + NE;
@@ -155,11 +174,9 @@ struct ApplyDma {
     for (int w = 0; w < kWavesPerWG; ++w) { mS = fmaxf(mS, redmax[w]); mz = fmaxf(mz, redmax[kWavesPerWG + w]); }
     const float aS = pow2_scale_for(mS);
     const float az = NORM ? pow2_scale_for(mz) : 1.0f;
-    const float c1 = az / aS;
-    const float eps_s = eps * az;
-
-    u32x4 A[NS][MT2][KS];
-    {
+    if (keep) {
+      c1 = az / aS;
+      eps_s = eps * az;
       const int m = lane & 31;
       const int hv = (m >> 2) & 1;
 #pragma unroll
@@ -193,8 +210,9 @@ struct ApplyDma {
       }
     }
     __syncthreads();   // the staged state is dead: the third slot block may be filled from here on
+  }
 
-    // ---- stream loop ---------------------------------------------------------------------------------
+  LF_DEV void stream() {
     int slot = 0;
     int iter = 0;
     while (it.valid()) {
@@ -290,13 +308,15 @@ struct ApplyDma {
 
       // ---- coalesced stores; always NL instructions (lanes without a valid chunk are masked) ------
       {
-        long long rem = (N - tile * kTile) * CPR;
-        const int lim = rem < Cfg::kChunks ? (int)rem : Cfg::kChunks;
-        u32x4* op = Oh + tile * Cfg::kChunks;
+        long long rem = N - tile * kTile;
+        const int lim = rem < kTile ? (int)rem : kTile;
+        u32x4* op = Oh + tile * kTile * rs_o;
 #pragma unroll
         for (int u = 0; u < NL; ++u) {
           const u32x4 w = *reinterpret_cast<const u32x4*>(sl + u * 1024 + lane * 16);
-          if (u * 64 + lane < Cfg::kChunks && goff[u] < lim) st_stream(op + goff[u], w);
+          if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) {
+            if constexpr (HG) op[ooff[u]] = w; else st_stream(op + ooff[u], w);
+          }
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -309,13 +329,35 @@ struct ApplyDma {
 
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-apply16_dma(const u32x4* __restrict__ Q, u32x4* __restrict__ O, const float* __restrict__ state, float eps,
-            long long N, int tiles_per_block) {
+apply16_dma(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo,
+            const float* __restrict__ state, float eps, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const long long bh = blockIdx.y;
-  ApplyDma<T, D, FM, NORM> ap(Q, O, N, tiles_per_block, blockIdx.x, gridDim.x, bh, smem);
+  ApplyDma<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
+                              gridDim.x, smem);
   ap.prefetch();
   ap.run(state + bh * (D * D + D), eps);
+}
+
+// Apply with one head per wave.  grid = (wgs, B * ceil(H / 4)); same head assignment as state_reduce16_hg.
+template <typename T, int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+apply16_dma_hg(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo,
+               const float* __restrict__ state, float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int H = lq.H;
+  const int gpb = (H + kWavesPerWG - 1) / kWavesPerWG;
+  const int b = blockIdx.y / gpb;
+  const int h0 = (blockIdx.y % gpb) * kWavesPerWG;
+  const bool active = h0 + wave < H;
+  const int h = active ? h0 + wave : H - 1;
+  ApplyDma<T, D, FM, NORM, true> ap(Q + (b * lq.batch + h * lq.head), lq.row, O + (b * lo.batch + h * lo.head), lo.row,
+                                    N, tiles_per_block, blockIdx.x, gridDim.x, smem, active);
+  ap.prefetch();
+  for (int w = 0; w < kWavesPerWG && h0 + w < H; ++w)
+    ap.load_state(state + ((long long)b * H + h0 + w) * (D * D + D), eps, wave == w);
+  ap.stream();
 }
 
 }  // namespace lf

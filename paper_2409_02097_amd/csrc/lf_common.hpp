@@ -132,23 +132,37 @@ template <int D> struct Shape16 {
   static constexpr int kMT2 = (kHalf + 2 + 15) / 16;   // 32-row output tiles incl. normalizer rows
 };
 
+// ---- where a (batch, head) slice of a tensor starts and how far apart its token rows are ------
+// All in units of one vector access (16 bytes): [B, H, N, d] contiguous has row = d * s / 16,
+// head = N * row, batch = H * head; the token-major [B, N, H * d] layout of the UNet has
+// row = H * d * s / 16, head = d * s / 16, batch = N * row.  Inside a row the d channels are contiguous.
+struct Layout {
+  long long batch, head;   // strides between batches / heads
+  int row;                 // stride between consecutive tokens of one head
+  int H;                   // heads per batch
+  LF_DEV long long slice(long long bh) const { return (bh / H) * batch + (bh % H) * head; }
+};
+
 // ---- which tiles a wave processes -----------------------------------------------------------
 // The tiles of a head are cut into blocks of `blk` consecutive tiles (blk a multiple of the
 // waves per workgroup); workgroup g of G takes blocks g, g + G, g + 2G, ... and inside a block its
 // waves take tiles round-robin.  blk = ceil(n_tiles / G) gives every workgroup one contiguous
 // chunk; a small blk keeps all workgroups of the chip inside one moving window of memory.
+// `stride` = 4 with `wave_` = the wave's index is that round-robin; `stride` = 1 with `wave_` = 0 makes a
+// wave visit every tile of the workgroup's blocks (used when each wave of a workgroup works on a
+// different head over the same token range).
 struct TileIter {
   long long t, blk_end, blk_first, n_tiles, step;
-  int blk, wave;
-  LF_DEV TileIter(int g, int G, int wave_, int blk_, long long n_tiles_)
-      : n_tiles(n_tiles_), step((long long)G * blk_), blk(blk_), wave(wave_) {
+  int blk, wave, stride;
+  LF_DEV TileIter(int g, int G, int wave_, int blk_, long long n_tiles_, int stride_ = 4)
+      : n_tiles(n_tiles_), step((long long)G * blk_), blk(blk_), wave(wave_), stride(stride_) {
     blk_first = (long long)g * blk;
     t = blk_first + wave;
     blk_end = blk_first + blk < n_tiles ? blk_first + blk : n_tiles;
   }
   LF_DEV bool valid() const { return t < n_tiles; }
   LF_DEV void next() {
-    t += 4;
+    t += stride;
     if (t >= blk_end) {
       blk_first += step;
       t = blk_first + wave;

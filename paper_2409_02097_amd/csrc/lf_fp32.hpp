@@ -29,11 +29,12 @@ LF_DEV f32x4 mfma_16x16x4(float a, float b, f32x4 c) { return __builtin_amdgcn_m
 // Lane (m = lane % 16, kq = lane / 16) holds channels 4m..4m+3 of token 4u + kq of the tile;
 // element i of its K chunk (after phi) is the A operand and element j of its V chunk the B
 // operand of product (i, j), whose accumulator tile is S[4*row + i][4*col + j].  z is summed
-// on the vector ALU.  `smem`: reduce32_lds_bytes<D>() bytes; `dst`: this workgroup's partial.
+// on the vector ALU.  `smem`: reduce32_lds_bytes<D>() bytes; `dst`: this workgroup's partial;
+// `Kh`, `Vh`: first token row of this head; `rs`: row stride in 16-byte units.
 // ------------------------------------------------------------------------------------------
 template <int D, int FM>
-LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* __restrict__ dst,
-                           long long N, int tiles_per_block, int split, int nsplit, long long bh,
+LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict__ Vh, int rs,
+                           float* __restrict__ dst, long long N, int tiles_per_block, int split, int nsplit,
                            unsigned char* smem) {
   constexpr int CH = Shape32<D>::kChunks;
   constexpr int U = kTile32 / 4;
@@ -45,9 +46,6 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict_
 
   const long long n_tiles = (N + kTile32 - 1) / kTile32;
   TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
-  const f32x4* Kh = K + bh * N * CH;
-  const f32x4* Vh = V + bh * N * CH;
-
   f32x4 acc[4][4];
   float zacc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -63,8 +61,8 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict_
       const long long t = tile * kTile32 + 4 * u + kq;
       okr[u] = lane_on && t < N;
       if (okr[u]) {
-        kr[u] = __builtin_nontemporal_load(Kh + t * CH + m);
-        vr[u] = __builtin_nontemporal_load(Vh + t * CH + m);
+        kr[u] = __builtin_nontemporal_load(Kh + t * rs + m);
+        vr[u] = __builtin_nontemporal_load(Vh + t * rs + m);
       } else {
         kr[u] = f32x4{0, 0, 0, 0};
         vr[u] = f32x4{0, 0, 0, 0};
@@ -137,12 +135,13 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ K, const f32x4* __restrict_
 // grid = (splits, B*H), block = 256
 template <int D, int FM>
 __global__ void __launch_bounds__(kThreads)
-state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* __restrict__ partials,
+state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout kv, float* __restrict__ partials,
                long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const long long bh = blockIdx.y;
   float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
-  reduce32_phase<D, FM>(K, V, dst, N, tiles_per_block, blockIdx.x, gridDim.x, bh, smem);
+  const long long off = kv.slice(bh);
+  reduce32_phase<D, FM>(K + off, V + off, kv.row, dst, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -154,11 +153,12 @@ state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, float* 
 //   slot = 4*T + mrow % 4, group g = mrow / 4:  slot < d/4 -> S[ch][g*d/4 + slot];
 //   slot == d/4 -> z[ch];  else 0.
 // The accumulators of a lane hold d/4 contiguous output channels of its token and the
-// normalizer phi(q).z.  `state`: this head's [D*D + D] floats.
+// normalizer phi(q).z.  `state`: this head's [D*D + D] floats; `Qh`, `Oh4`: first token row of this head;
+// `rs_q`, `rs_o`: row strides in 16-byte units.
 // ------------------------------------------------------------------------------------------
 template <int D, int FM, bool NORM>
-LF_DEV void apply32_phase(const f32x4* __restrict__ Q, float* __restrict__ O, const float* state, float eps,
-                          long long N, int tiles_per_block, int wg, int nwg, long long bh) {
+LF_DEV void apply32_phase(const f32x4* __restrict__ Qh, int rs_q, f32x4* __restrict__ Oh4, int rs_o,
+                          const float* state, float eps, long long N, int tiles_per_block, int wg, int nwg) {
   using Sh = Shape32<D>;
   constexpr int CS = Sh::kCS, KST = Sh::kKSteps, MT = Sh::kMT, CH = Sh::kChunks, QT = Sh::kQuarter;
   const int lane = threadIdx.x & 63;
@@ -186,15 +186,13 @@ LF_DEV void apply32_phase(const f32x4* __restrict__ Q, float* __restrict__ O, co
 
   const long long n_tiles = (N + kTile32 - 1) / kTile32;
   TileIter it(wg, nwg, wave, tiles_per_block, n_tiles);
-  const f32x4* Qh = Q + bh * N * CH;
-  float* Oh = O + bh * N * (long long)D;
 
   f32x4 qr[CS];
   auto issue_loads = [&](long long tile) {
     const long long t = tile * kTile32 + tok;
 #pragma unroll
     for (int cs = 0; cs < CS; ++cs) {
-      if (t < N && kq * CS + cs < CH) qr[cs] = __builtin_nontemporal_load(Qh + t * CH + kq * CS + cs);
+      if (t < N && kq * CS + cs < CH) qr[cs] = __builtin_nontemporal_load(Qh + t * rs_q + kq * CS + cs);
       else qr[cs] = f32x4{0, 0, 0, 0};
     }
   };
@@ -220,7 +218,7 @@ LF_DEV void apply32_phase(const f32x4* __restrict__ Q, float* __restrict__ O, co
     if constexpr (NORM) scale = 1.0f / (acc[QT / 4][QT % 4] + eps);
     const long long t = cur * kTile32 + tok;
     if (t < N) {
-      float* orow = Oh + t * (long long)D + kq * QT;
+      float* orow = reinterpret_cast<float*>(Oh4 + t * rs_o) + kq * QT;
       if constexpr (QT % 4 == 0) {
 #pragma unroll
         for (int c = 0; c < QT / 4; ++c) {
@@ -242,10 +240,11 @@ LF_DEV void apply32_phase(const f32x4* __restrict__ Q, float* __restrict__ O, co
 // grid = (wgs_per_head, B*H), block = 256
 template <int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-apply32(const f32x4* __restrict__ Q, float* __restrict__ O, const float* __restrict__ state, float eps,
-        long long N, int tiles_per_block) {
+apply32(const f32x4* __restrict__ Q, Layout lq, f32x4* __restrict__ O, Layout lo, const float* __restrict__ state,
+        float eps, long long N, int tiles_per_block) {
   const long long bh = blockIdx.y;
-  apply32_phase<D, FM, NORM>(Q, O, state + bh * (D * D + D), eps, N, tiles_per_block, blockIdx.x, gridDim.x, bh);
+  apply32_phase<D, FM, NORM>(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, state + bh * (D * D + D), eps, N,
+                             tiles_per_block, blockIdx.x, gridDim.x);
 }
 
 }  // namespace lf

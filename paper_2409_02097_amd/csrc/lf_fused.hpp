@@ -113,8 +113,8 @@ constexpr int fused16_lds_bytes() {
 
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-fused16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, const u32x4* __restrict__ Q,
-        u32x4* __restrict__ O, float* partials, float* state, unsigned* flags, unsigned* err, unsigned ticket,
+fused16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, const u32x4* __restrict__ Q,
+        Layout lq, u32x4* __restrict__ O, Layout lo, float* partials, float* state, unsigned* flags, unsigned* err, unsigned ticket,
         unsigned spin_limit, float eps, long long N, int blk_reduce, int blk_apply) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int flag;
@@ -123,9 +123,11 @@ fused16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, const u32x4* _
   const long long bh = blockIdx.y;
   float* head_part = partials + bh * nsplit * (long long)NE;
   float* head_state = state + bh * NE;
-  reduce16_phase<T, D, FM>(K, V, head_part + (long long)split * NE, N, blk_reduce, split, nsplit, bh, smem);
+  const long long okv = lkv.slice(bh);
+  reduce16_phase<T, D, FM>(K + okv, V + okv, lkv.row, head_part + (long long)split * NE, N, blk_reduce, split, nsplit,
+                           smem);
   if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
-  ApplyDma<T, D, FM, NORM> ap(Q, O, N, blk_apply, split, nsplit, bh, smem);
+  ApplyDma<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, blk_apply, split, nsplit, smem);
   ap.prefetch();   // Q does not depend on the state: its first tiles travel during phase 2 and the barrier
   combine_owned(head_part, nsplit, NE, split, head_state,
                 reinterpret_cast<float*>(smem + ApplyDmaCfg<D>::kStageOffset));
@@ -140,8 +142,8 @@ template <int D> constexpr int fused32_lds_bytes() { return reduce32_lds_bytes<D
 
 template <int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-fused32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, const f32x4* __restrict__ Q,
-        float* __restrict__ O, float* partials, float* state, unsigned* flags, unsigned* err, unsigned ticket,
+fused32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout lkv, const f32x4* __restrict__ Q,
+        Layout lq, f32x4* __restrict__ O, Layout lo, float* partials, float* state, unsigned* flags, unsigned* err, unsigned ticket,
         unsigned spin_limit, float eps, long long N, int blk_reduce, int blk_apply) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int flag;
@@ -150,11 +152,13 @@ fused32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, const f32x4* _
   const long long bh = blockIdx.y;
   float* head_part = partials + bh * nsplit * (long long)NE;
   float* head_state = state + bh * NE;
-  reduce32_phase<D, FM>(K, V, head_part + (long long)split * NE, N, blk_reduce, split, nsplit, bh, smem);
+  const long long okv = lkv.slice(bh);
+  reduce32_phase<D, FM>(K + okv, V + okv, lkv.row, head_part + (long long)split * NE, N, blk_reduce, split, nsplit, smem);
   if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
   combine_owned(head_part, nsplit, NE, split, head_state, reinterpret_cast<float*>(smem));
   if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
-  apply32_phase<D, FM, NORM>(Q, O, head_state, eps, N, blk_apply, split, nsplit, bh);
+  apply32_phase<D, FM, NORM>(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, head_state, eps, N, blk_apply, split,
+                             nsplit);
 }
 
 }  // namespace lf

@@ -42,10 +42,15 @@ constexpr int reduce16_lds_bytes() {
 
 // `dst`: where this workgroup's partial goes ([D*D + D] floats).  `smem`: reduce16_lds_bytes<T,D>()
 // bytes of LDS.  Ends with every thread having written its share of `dst` (no trailing barrier).
-template <typename T, int D, int FM>
-LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* __restrict__ dst,
-                           long long N, int tiles_per_block, int split, int nsplit, long long bh,
-                           unsigned char* smem) {
+// `Kh`, `Vh`: first token row of this head; `rs`: row stride in 16-byte units.
+// HG ("one head per wave"): the four waves of the workgroup work on four different heads over the same
+// tiles -- `Kh`, `Vh`, `dst` are then the calling wave's own (wave-uniform) and each wave writes its own
+// partial; a wave with `active` false (no head left for it) does nothing.  When the heads of a token lie
+// next to each other in memory, the workgroup as a whole then touches whole contiguous row pieces.
+template <typename T, int D, int FM, bool HG = false>
+LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict__ Vh, int rs,
+                           float* __restrict__ dst, long long N, int tiles_per_block, int split, int nsplit,
+                           unsigned char* smem, bool active = true) {
   using Sh = Shape16<D>;
   using Cfg = Reduce16Cfg<D>;
   constexpr int NS = NSplit<T>::value;
@@ -60,22 +65,22 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
   for (int s = 0; s < NS; ++s) ldsP[s] = wbase + s * Cfg::kTileElems;
   uint16_t* ldsV = wbase + NS * Cfg::kTileElems;
 
-  // per-lane constants: which chunks of a tile this lane moves, and where they land in LDS
-  int lds_off[NL];
+  // per-lane constants: which chunks of a tile this lane moves (token row, offset from the tile's
+  // first row in memory), and where they land in LDS
+  int lds_off[NL], trow[NL], goff[NL];
 #pragma unroll
   for (int u = 0; u < NL; ++u) {
     int c = u * 64 + lane;
-    lds_off[u] = (c / CPR) * RS + (c % CPR) * 8;
+    trow[u] = c / CPR;
+    goff[u] = trow[u] * rs + c % CPR;
+    lds_off[u] = trow[u] * RS + (c % CPR) * 8;
   }
   // transposing-read base: lane j of 16-lane group g reads row 8g + 4r + j/4, columns 4*(j%4)..
   const int j16 = lane & 15, g4 = lane >> 4;
   const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
 
   const long long n_tiles = (N + kTile - 1) / kTile;
-  TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
-
-  const u32x4* Kh = K + bh * N * CPR;
-  const u32x4* Vh = V + bh * N * CPR;
+  TileIter it(split, nsplit, HG ? 0 : wave, tiles_per_block, (HG && !active) ? 0 : n_tiles, HG ? 1 : kWavesPerWG);
 
   f32x4 acc[MT][MT];
   f32x4 accz[MT];
@@ -90,17 +95,16 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
 
   u32x4 kr[NL], vr[NL];
   auto issue_loads = [&](long long tile) {
-    // number of valid 16-byte chunks in this tile (ragged last tile of the head)
-    long long rem = (N - tile * kTile) * CPR;
-    int lim = rem < Cfg::kChunks ? (int)rem : Cfg::kChunks;
-    const u32x4* kp = Kh + tile * Cfg::kChunks;
-    const u32x4* vp = Vh + tile * Cfg::kChunks;
+    // number of valid token rows in this tile (ragged last tile of the head)
+    long long rem = N - tile * kTile;
+    int lim = rem < kTile ? (int)rem : kTile;
+    const u32x4* kp = Kh + tile * kTile * rs;
+    const u32x4* vp = Vh + tile * kTile * rs;
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
-      int c = u * 64 + lane;
-      if (c < lim) {
-        kr[u] = ld_stream(kp + c);
-        vr[u] = ld_stream(vp + c);
+      if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) {
+        kr[u] = ld_stream(kp + goff[u]);
+        vr[u] = ld_stream(vp + goff[u]);
       } else {
         kr[u] = u32x4{0, 0, 0, 0};
         vr[u] = u32x4{0, 0, 0, 0};
@@ -126,7 +130,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
     for (int u = 0; u < NL; ++u) {
       int c = u * 64 + lane;
       if (c < Cfg::kChunks) {
-        const bool ok = c < lim;
+        const bool ok = trow[u] < lim;
         u32x4 ph, pl;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -178,6 +182,31 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
     lim = next_lim;
   }
 
+  if constexpr (HG) {
+    // each wave owns a whole partial: straight from the accumulator layout (lane: rows 4 (l / 16) + i,
+    // column l % 16 of each 16 x 16 block) to memory
+    if (!active) return;
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = a * 16 + 4 * g4 + i;
+        if (row < D) {
+#pragma unroll
+          for (int b = 0; b < MT; ++b) {
+            const int col = b * 16 + j16;
+            if (col < D) st_agent(dst + row * D + col, acc[a][b][i]);
+            else if (Sh::kSpareCol && col == D) st_agent(dst + D * D + row, acc[a][b][i]);
+          }
+          if constexpr (!Sh::kSpareCol) {
+            if (j16 == 0) st_agent(dst + D * D + row, accz[a][i]);
+          }
+        }
+      }
+    }
+    return;
+  }
+
   // ---- cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3): waves 0 and 1 park their accumulators
   //      in two LDS copies ([D*D] S then [D] z), waves 2 and 3 add theirs on top, then all threads add
   //      the two copies and write the partial --------------------------------------------------------
@@ -219,12 +248,33 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ K, const u32x4* __restrict_
 
 template <typename T, int D, int FM>
 __global__ void __launch_bounds__(kThreads)
-state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, float* __restrict__ partials,
+state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, float* __restrict__ partials,
                long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const long long bh = blockIdx.y;
   float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
-  reduce16_phase<T, D, FM>(K, V, dst, N, tiles_per_block, blockIdx.x, gridDim.x, bh, smem);
+  const long long off = kv.slice(bh);
+  reduce16_phase<T, D, FM>(K + off, V + off, kv.row, dst, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+}
+
+// The same reduction with one head per wave.  grid = (splits, B * ceil(H / 4)): workgroup (split, g) takes
+// heads 4 (g % ceil(H/4)) + wave of batch g / ceil(H/4).  Partials keep the layout [B*H][splits][d*d + d].
+template <typename T, int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+state_reduce16_hg(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, float* __restrict__ partials,
+                  long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int gpb = (kv.H + kWavesPerWG - 1) / kWavesPerWG;
+  const int b = blockIdx.y / gpb;
+  int h = (blockIdx.y % gpb) * kWavesPerWG + wave;
+  const bool active = h < kv.H;
+  if (!active) h = kv.H - 1;
+  const long long bh = (long long)b * kv.H + h;
+  float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
+  const long long off = b * kv.batch + h * kv.head;
+  reduce16_phase<T, D, FM, true>(K + off, V + off, kv.row, dst, N, tiles_per_block, blockIdx.x, gridDim.x, smem,
+                                 active);
 }
 
 // ==========================================================================================

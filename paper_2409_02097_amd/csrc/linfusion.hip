@@ -16,7 +16,7 @@
 
 namespace {
 
-constexpr int kVersion = 200;  // 0.2.0
+constexpr int kVersion = 300;  // 0.3.0
 constexpr int kMaxDevices = 16;
 constexpr int kNumCU = 256;    // the library targets one chip
 
@@ -29,6 +29,8 @@ struct Plan {
   int blk_apply;        //   tiles per contiguous block of an apply workgroup
   int fsplits;          // fused path: workgroups per head (0 = the shape cannot use it)
   int fblk_reduce, fblk_apply;
+  // one-head-per-wave kernels (heads adjacent in memory): workgroups per group of four heads
+  int groups, gsplits, gblk_reduce, gapply_wgs, gblk_apply;
   long long n_tiles;
   size_t state_floats;  // d*d + d: one partial, and one head's state
   size_t ws_partials, ws_state, ws_sync, ws_total;
@@ -98,6 +100,22 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     p->fblk_reduce = block_tiles(share, "LINFUSION_REDUCE_BLK", 16);
     p->fblk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", 8);
   }
+  // one head per wave: a workgroup covers four heads, every wave walks all of its tiles
+  p->groups = B * ((H + lf::kWavesPerWG - 1) / lf::kWavesPerWG);
+  {
+    auto per_group = [&](int want_total, long long* sh) {
+      long long s = (want_total + p->groups - 1) / p->groups;
+      if (s > p->n_tiles) s = p->n_tiles;
+      if (s < 1) s = 1;
+      long long t = (p->n_tiles + s - 1) / s;
+      *sh = t;
+      return (int)((p->n_tiles + t - 1) / t);
+    };
+    p->gsplits = per_group(env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * kNumCU), &share);
+    p->gblk_reduce = block_tiles(share, "LINFUSION_GROUP_REDUCE_BLK", 8);
+    p->gapply_wgs = per_group(env_int("LINFUSION_GROUP_APPLY_WGS", 8 * kNumCU), &share);
+    p->gblk_apply = block_tiles(share, "LINFUSION_GROUP_APPLY_BLK", 4);
+  }
   const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
   const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
   // Measured on MI355X: below ~64 MB of tensor traffic the three short kernels are as fast as the
@@ -111,7 +129,8 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     p->path = 1;
   p->state_floats = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  const int smax = p->splits > p->fsplits ? p->splits : p->fsplits;
+  int smax = p->splits > p->fsplits ? p->splits : p->fsplits;
+  if (dtype != LINFUSION_DTYPE_F32 && p->gsplits > smax) smax = p->gsplits;
   p->ws_partials = up((size_t)BH * smax * p->state_floats * sizeof(float));
   p->ws_state = up((size_t)BH * p->state_floats * sizeof(float));
   p->ws_sync = up((size_t)BH * 2 * (p->fsplits > 0 ? p->fsplits : 1) * sizeof(unsigned) + 16);
@@ -173,6 +192,8 @@ struct Args {
   float* state_out;
   hipStream_t st;
   hipEvent_t* ev;
+  lf::Layout lq, lkv, lo;
+  bool group_reduce, group_apply;   // use the one-head-per-wave kernels
 };
 
 // polls (of about a microsecond each) before a single-launch call gives up at a barrier; the
@@ -212,7 +233,7 @@ int run16(const Args& a) {
   const u32x4* Q = (const u32x4*)a.q;
   u32x4* O = (u32x4*)a.out;
   hipStream_t st = a.st;
-  if (p.path == 1 && a.out) {
+  if (p.path == 1 && a.out && !(a.group_reduce || a.group_apply)) {
     unsigned* sync = reinterpret_cast<unsigned*>(a.ws + p.ws_partials + p.ws_state);
     unsigned* err = sync + a.BH * 2 * p.fsplits;
     const dim3 g(p.fsplits, (unsigned)a.BH);
@@ -221,8 +242,9 @@ int run16(const Args& a) {
 #define LF_FUSED(FM, NORM)                                                                               \
   if (fits_resident(fused16<T, D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                        \
     if (a.ev) (void)hipEventRecord(a.ev[0], st);                                                         \
-    fused16<T, D, FM, NORM><<<g, blk, lds, st>>>(K, V, Q, O, partials, state, sync, err, next_ticket(),  \
-                                                 spin_limit(), a.eps, a.N, p.fblk_reduce, p.fblk_apply);   \
+    fused16<T, D, FM, NORM><<<g, blk, lds, st>>>(K, V, a.lkv, Q, a.lq, O, a.lo, partials, state, sync, err,  \
+                                                 next_ticket(), spin_limit(), a.eps, a.N, p.fblk_reduce,     \
+                                                 p.fblk_apply);                                              \
     launched = true;                                                                                     \
   }
     LF_SWITCH_FM_NORM(LF_FUSED)
@@ -232,22 +254,38 @@ int run16(const Args& a) {
       return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
     }
   }
-  const dim3 g1(p.splits, (unsigned)a.BH);
   const size_t lds1 = reduce16_lds_bytes<T, D>();
   if (a.ev) (void)hipEventRecord(a.ev[0], st);
-#define LF_REDUCE(FM) state_reduce16<T, D, FM><<<g1, blk, lds1, st>>>(K, V, partials, a.N, p.blk_reduce);
-  LF_SWITCH_FM(LF_REDUCE)
+  if (a.group_reduce) {
+    const dim3 g1(p.gsplits, (unsigned)p.groups);
+#define LF_REDUCE(FM) state_reduce16_hg<T, D, FM><<<g1, blk, lds1, st>>>(K, V, a.lkv, partials, a.N, p.gblk_reduce);
+    LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
+  } else {
+    const dim3 g1(p.splits, (unsigned)a.BH);
+#define LF_REDUCE(FM) state_reduce16<T, D, FM><<<g1, blk, lds1, st>>>(K, V, a.lkv, partials, a.N, p.blk_reduce);
+    LF_SWITCH_FM(LF_REDUCE)
+#undef LF_REDUCE
+  }
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
   combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
-      partials, p.splits, NE, state);
+      partials, a.group_reduce ? p.gsplits : p.splits, NE, state);
   if (a.ev) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
-    const dim3 g2(p.apply_wgs, (unsigned)a.BH);
     const size_t lds2 = apply16_dma_lds_bytes<T, D>();
-#define LF_APPLY(FM, NORM) apply16_dma<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, O, state, a.eps, a.N, p.blk_apply);
-    LF_SWITCH_FM_NORM(LF_APPLY)
+    if (a.group_apply) {
+      const dim3 g2(p.gapply_wgs, (unsigned)p.groups);
+#define LF_APPLY(FM, NORM) \
+  apply16_dma_hg<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, state, a.eps, a.N, p.gblk_apply);
+      LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
+    } else {
+      const dim3 g2(p.apply_wgs, (unsigned)a.BH);
+#define LF_APPLY(FM, NORM) \
+  apply16_dma<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, state, a.eps, a.N, p.blk_apply);
+      LF_SWITCH_FM_NORM(LF_APPLY)
+#undef LF_APPLY
+    }
   }
   if (a.ev) (void)hipEventRecord(a.ev[3], st);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
@@ -264,7 +302,7 @@ int run32(const Args& a) {
   const f32x4* K = (const f32x4*)a.k;
   const f32x4* V = (const f32x4*)a.v;
   const f32x4* Q = (const f32x4*)a.q;
-  float* O = (float*)a.out;
+  f32x4* O = (f32x4*)a.out;
   hipStream_t st = a.st;
   constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
   if (p.path == 1 && a.out) {
@@ -275,8 +313,9 @@ int run32(const Args& a) {
 #define LF_FUSED(FM, NORM)                                                                           \
   if (fits_resident(fused32<D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                       \
     if (a.ev) (void)hipEventRecord(a.ev[0], st);                                                     \
-    fused32<D, FM, NORM><<<g, blk, lds, st>>>(K, V, Q, O, partials, state, sync, err, next_ticket(),  \
-                                              spin_limit(), a.eps, a.N, p.fblk_reduce, p.fblk_apply);  \
+    fused32<D, FM, NORM><<<g, blk, lds, st>>>(K, V, a.lkv, Q, a.lq, O, a.lo, partials, state, sync, err, \
+                                              next_ticket(), spin_limit(), a.eps, a.N, p.fblk_reduce,   \
+                                              p.fblk_apply);                                            \
     launched = true;                                                                                 \
   }
     LF_SWITCH_FM_NORM(LF_FUSED)
@@ -288,7 +327,7 @@ int run32(const Args& a) {
   }
   const dim3 g1(p.splits, (unsigned)a.BH);
   if (a.ev) (void)hipEventRecord(a.ev[0], st);
-#define LF_REDUCE(FM) state_reduce32<D, FM><<<g1, blk, lds, st>>>(K, V, partials, a.N, p.blk_reduce);
+#define LF_REDUCE(FM) state_reduce32<D, FM><<<g1, blk, lds, st>>>(K, V, a.lkv, partials, a.N, p.blk_reduce);
   LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
@@ -297,7 +336,7 @@ int run32(const Args& a) {
   if (a.ev) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
     const dim3 g2(p.apply_wgs, (unsigned)a.BH);
-#define LF_APPLY(FM, NORM) apply32<D, FM, NORM><<<g2, blk, 0, st>>>(Q, O, state, a.eps, a.N, p.blk_apply);
+#define LF_APPLY(FM, NORM) apply32<D, FM, NORM><<<g2, blk, 0, st>>>(Q, a.lq, O, a.lo, state, a.eps, a.N, p.blk_apply);
     LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
   }
@@ -363,9 +402,54 @@ int owned_workspace(size_t need, void** ws) {
   return LINFUSION_OK;
 }
 
+// ---- tensor layouts ------------------------------------------------------------------------------
+// Strides in elements between batches, heads and tokens; the d channels of a token are contiguous.
+struct Strides { long long b, h, n; };
+
+Strides contiguous_strides(int H, long long N, int d) { return Strides{(long long)H * N * d, N * d, (long long)d}; }
+
+// bytes from the first to one past the last element the layout touches
+size_t span_bytes(const Strides& s, int B, int H, long long N, int d, size_t esz) {
+  return (size_t)((B - 1) * s.b + (H - 1) * s.h + (N - 1) * s.n + d) * esz;
+}
+
+// LINFUSION_OK when the kernels can address the layout: non-negative strides that keep every token row
+// 16-byte aligned and within the index widths the kernels use.  `written`: additionally no two
+// (batch, head, token) rows may share memory -- checked by ordering the dimensions by stride and
+// requiring each stride to clear the span of the smaller ones.
+int check_strides(const Strides& s, int B, int H, long long N, int d, size_t esz, bool written) {
+  const long long vec = (long long)(16 / esz);
+  if (s.b < 0 || s.h < 0 || s.n < 0) return LINFUSION_ERR_INVALID;
+  if (s.b % vec || s.h % vec || s.n % vec) return LINFUSION_ERR_MISALIGNED;
+  if (s.n / vec >= (1LL << 24)) return LINFUSION_ERR_INVALID;           // 32 rows * stride stays in int
+  const long double span = (long double)(B - 1) * s.b + (long double)(H - 1) * s.h + (long double)(N - 1) * s.n + d;
+  if (span * esz >= (long double)(1LL << 46)) return LINFUSION_ERR_INVALID;
+  if (written) {
+    struct Dim { long long extent, stride; } dims[4] = {{d, 1}, {N, s.n}, {H, s.h}, {B, s.b}};
+    int n = 0;
+    for (int i = 0; i < 4; ++i)
+      if (dims[i].extent > 1) dims[n++] = dims[i];
+    for (int i = 1; i < n; ++i)            // insertion sort by stride
+      for (int j = i; j > 0 && dims[j].stride < dims[j - 1].stride; --j) { Dim t = dims[j]; dims[j] = dims[j - 1]; dims[j - 1] = t; }
+    long long reach = 1;                   // elements spanned by the dimensions seen so far
+    for (int i = 0; i < n; ++i) {
+      if (dims[i].stride < reach) return LINFUSION_ERR_OVERLAP;
+      reach = (dims[i].extent - 1) * dims[i].stride + reach;
+    }
+  }
+  return LINFUSION_OK;
+}
+
+lf::Layout device_layout(const Strides& s, int H, size_t esz) {
+  const long long vec = (long long)(16 / esz);
+  return lf::Layout{s.b / vec, s.h / vec, (int)(s.n / vec), H};
+}
+
+// `sq`, `skv`, `so`: strides of q, of k and v, and of out; null = contiguous [B, H, N, d]
 int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d, int dtype,
              int feature_map, float eps, unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
-             hipEvent_t* ev) {
+             hipEvent_t* ev, const long long* sq = nullptr, const long long* skv = nullptr,
+             const long long* so = nullptr) {
   if (!q || !out) return LINFUSION_ERR_INVALID;
   if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
   Plan p;
@@ -373,19 +457,39 @@ int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int 
   if (rc != LINFUSION_OK) return rc;
   if (((uintptr_t)q | (uintptr_t)out) & 15) return LINFUSION_ERR_MISALIGNED;
   const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
-  const size_t tbytes = (size_t)B * H * (size_t)N * d * esz;
-  if (overlaps(out, tbytes, k, tbytes) || overlaps(out, tbytes, v, tbytes)) return LINFUSION_ERR_OVERLAP;
-  if (out != q && overlaps(out, tbytes, q, tbytes)) return LINFUSION_ERR_OVERLAP;
+  const Strides dense = contiguous_strides(H, N, d);
+  const Strides lq = sq ? Strides{sq[0], sq[1], sq[2]} : dense;
+  const Strides lkv = skv ? Strides{skv[0], skv[1], skv[2]} : dense;
+  const Strides lo = so ? Strides{so[0], so[1], so[2]} : dense;
+  if ((rc = check_strides(lq, B, H, N, d, esz, false)) != LINFUSION_OK) return rc;
+  if ((rc = check_strides(lkv, B, H, N, d, esz, false)) != LINFUSION_OK) return rc;
+  if ((rc = check_strides(lo, B, H, N, d, esz, true)) != LINFUSION_OK) return rc;
+  const size_t nq = span_bytes(lq, B, H, N, d, esz), nkv = span_bytes(lkv, B, H, N, d, esz);
+  const size_t no = span_bytes(lo, B, H, N, d, esz);
+  if (overlaps(out, no, k, nkv) || overlaps(out, no, v, nkv)) return LINFUSION_ERR_OVERLAP;
+  // in place on q: every tile is read before the same wave writes it, provided both views coincide
+  const bool same_view = out == q && lq.b == lo.b && lq.h == lo.h && lq.n == lo.n;
+  if (!same_view && overlaps(out, no, q, nq)) return LINFUSION_ERR_OVERLAP;
   if (!workspace) return LINFUSION_ERR_WORKSPACE;
   if ((uintptr_t)workspace & 15) return LINFUSION_ERR_MISALIGNED;
   if (workspace_bytes < p.ws_total) return LINFUSION_ERR_WORKSPACE;
-  if (overlaps(workspace, p.ws_total, out, tbytes) || overlaps(workspace, p.ws_total, q, tbytes) ||
-      overlaps(workspace, p.ws_total, k, tbytes) || overlaps(workspace, p.ws_total, v, tbytes))
+  if (overlaps(workspace, p.ws_total, out, no) || overlaps(workspace, p.ws_total, q, nq) ||
+      overlaps(workspace, p.ws_total, k, nkv) || overlaps(workspace, p.ws_total, v, nkv))
     return LINFUSION_ERR_OVERLAP;
   rc = check_device();
   if (rc != LINFUSION_OK) return rc;
+  // One head per wave pays where the heads of a token are neighbours in memory and a head's row is not
+  // a whole number of 128-byte lines: four waves side by side then cover contiguous row pieces that
+  // single heads would touch as scattered fragments.  (Not used by the single-launch kernel, so a
+  // forced single launch keeps the one-head-per-workgroup mapping.)
+  auto heads_adjacent = [&](const Strides& s) { return H > 1 && s.h == d && s.n > d; };
+  const bool frag = dtype != LINFUSION_DTYPE_F32 && (d * esz) % 128 != 0 && !(flags & LINFUSION_FLAG_FORCE_FUSED);
+  int group_mode = env_int("LINFUSION_HEAD_GROUPS", 1);   // 2 = off (tuning aid)
+  const bool group_reduce = frag && group_mode == 1 && heads_adjacent(lkv);
+  const bool group_apply = frag && group_mode == 1 && (heads_adjacent(lo) || heads_adjacent(lq));
   Args a{q, k, v, out, (long long)B * H, N, feature_map, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
-         &p, (unsigned char*)workspace, nullptr, (hipStream_t)stream, ev};
+         &p, (unsigned char*)workspace, nullptr, (hipStream_t)stream, ev,
+         device_layout(lq, H, esz), device_layout(lkv, H, esz), device_layout(lo, H, esz), group_reduce, group_apply};
   return dispatch(d, dtype, a);
 }
 
@@ -412,12 +516,24 @@ int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out
   return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, flags, workspace, workspace_bytes, stream, nullptr);
 }
 
+int linfusion_attn_fwd_strided(const void* q, const void* k, const void* v, void* out, int B, int H, long long N,
+                               int d, int dtype, int feature_map, float eps, unsigned flags,
+                               const long long q_strides[3], const long long kv_strides[3],
+                               const long long out_strides[3], void* workspace, size_t workspace_bytes,
+                               void* stream) {
+  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, flags, workspace, workspace_bytes, stream, nullptr,
+                  q_strides, kv_strides, out_strides);
+}
+
 int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void* out, int B, int H, long long N,
-                               int d, int dtype, int feature_map, float eps, unsigned flags, void* workspace,
-                               size_t workspace_bytes, void* stream, void* events[4]) {
+                               int d, int dtype, int feature_map, float eps, unsigned flags,
+                               const long long q_strides[3], const long long kv_strides[3],
+                               const long long out_strides[3], void* workspace, size_t workspace_bytes,
+                               void* stream, void* events[4]) {
   if (!events || !events[0] || !events[1] || !events[2] || !events[3]) return LINFUSION_ERR_INVALID;
   hipEvent_t ev[4] = {(hipEvent_t)events[0], (hipEvent_t)events[1], (hipEvent_t)events[2], (hipEvent_t)events[3]};
-  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, flags, workspace, workspace_bytes, stream, ev);
+  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, flags, workspace, workspace_bytes, stream, ev,
+                  q_strides, kv_strides, out_strides);
 }
 
 int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes, int B, int H, long long N, int d,
@@ -458,8 +574,10 @@ int linfusion_attn_state(const void* k, const void* v, float* state_out, int B, 
   rc = check_device();
   if (rc != LINFUSION_OK) return rc;
   p.path = 0;
+  const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
+  const lf::Layout dense = device_layout(contiguous_strides(H, N, d), H, esz);
   Args a{nullptr, k, v, nullptr, (long long)B * H, N, feature_map, 0.0f, false,
-         &p, (unsigned char*)workspace, state_out, (hipStream_t)stream, nullptr};
+         &p, (unsigned char*)workspace, state_out, (hipStream_t)stream, nullptr, dense, dense, dense, false, false};
   return dispatch(d, dtype, a);
 }
 

@@ -20,7 +20,8 @@ def _declared_symbols():
 
 def test_header_declares_the_expected_entry_points():
     syms = _declared_symbols()
-    for name in ("linfusion_attn_fwd", "linfusion_attn_fwd_ex", "linfusion_attn_workspace_bytes",
+    for name in ("linfusion_attn_fwd", "linfusion_attn_fwd_ex", "linfusion_attn_fwd_strided",
+                 "linfusion_attn_workspace_bytes",
                  "linfusion_attn_state", "linfusion_status_string", "linfusion_version"):
         assert name in syms
 
@@ -83,6 +84,39 @@ def test_argument_validation_happens_on_the_host():
     assert _call(out=(2 << 20) + 64) == -7               # out overlaps v partially
     assert _call(q=4096, out=4096 + 160) == -7           # partial overlap with q
     assert _call(ws=3 << 20) == -7                       # workspace overlaps out
+
+
+def _strided(sq=None, skv=None, so=None, q=4096, k=1 << 20, v=2 << 20, out=3 << 20, B=2, H=4, N=64, d=40, dtype=1,
+             ws=64 << 20, ws_bytes=1 << 20):
+    arr = lambda s: None if s is None else ctypes.byref((ctypes.c_longlong * 3)(*s))
+    return lf.library().linfusion_attn_fwd_strided(q, k, v, out, B, H, N, d, dtype, 0, 1e-6, 0, arr(sq), arr(skv),
+                                                   arr(so), ws, ws_bytes, None)
+
+
+def test_stride_validation_happens_on_the_host():
+    import torch
+    ok = -6 if not torch.cuda.is_available() else None      # valid arguments reach the device check
+    dense = (4 * 64 * 40, 64 * 40, 40)
+    token_major = (64 * 4 * 40, 40, 4 * 40)
+    if ok is not None:
+        assert _strided() == ok and _strided(dense, dense, dense) == ok
+        assert _strided(token_major, token_major, token_major) == ok
+        assert _strided(dense, (64 * 40, 0, 40), dense) == ok            # k, v shared by all heads
+        assert _strided(token_major, token_major, token_major, q=4096, out=4096, k=8 << 20, v=16 << 20) == ok
+    assert _strided(so=(4 * 64 * 40, 64 * 40, -40)) == -1                # negative stride
+    assert _strided(sq=(4 * 64 * 40, 64 * 40, 44)) == -3                 # rows not 16-byte aligned
+    assert _strided(so=(4 * 64 * 40 + 4, 64 * 40, 40)) == -3
+    assert _strided(sq=dense, skv=dense, so=(4 * 64 * 40, 64 * 40, 40), dtype=0, d=40) in (-6, 0, ok)
+    assert _strided(sq=(0, 0, 4), dtype=1) == -3                         # 4 fp16 elements = 8 bytes
+    assert _strided(sq=(0, 0, 4), dtype=0, ws_bytes=4 << 20) in (-6, ok) # 4 fp32 elements = 16 bytes
+    assert _strided(so=(4 * 64 * 40, 64 * 40, 32)) == -7                 # output rows overlap each other
+    assert _strided(so=(4 * 64 * 40, 40, 40)) == -7                      # heads on top of tokens
+    assert _strided(so=(0, 64 * 40, 40)) == -7                           # batches on top of each other
+    assert _strided(so=(4 * 64 * 40, 64 * 40, 40), sq=token_major, q=4096, out=4096) == -7   # alias, other view
+    assert _strided(sq=(1 << 46, 64 * 40, 40)) == -1                     # span beyond the addressable range
+    assert _strided(sq=(4 * 64 * 40, 64 * 40, 8 << 24)) == -1            # token stride too large
+    # the span of a strided k reaches into out although the dense extents would not
+    assert _strided(skv=(64 * 4 * 80, 80, 4 * 80), k=(3 << 20) - 4 * 64 * 80 * 2 * 2 + 4096) == -7
 
 
 def test_valid_call_without_a_gfx950_device_fails_loudly():

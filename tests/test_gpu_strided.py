@@ -1,0 +1,144 @@
+"""GPU parity of linfusion_attn_fwd_strided: views into token-major, fused-projection and padded
+buffers against the fp64 oracle, and bit-for-bit against the contiguous entry point (the layout
+changes addresses only, not the arithmetic or its order)."""
+import pytest
+import torch
+
+import paper_2409_02097_amd as lf
+from paper_2409_02097_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+PATHS = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED}
+SENTINEL = 12345.0
+
+
+def _ws(B, H, N, d, dtype, dev):
+    return torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, wl.DTYPE_CODE[dtype]), dtype=torch.uint8, device=dev)
+
+
+def _contiguous(q, k, v, flags):
+    B, H, N, d = q.shape
+    out = torch.full_like(q, float("nan"))
+    lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, flags, _ws(B, H, N, d, _dt(q), q.device))
+    torch.cuda.synchronize()
+    return out
+
+
+def _dt(t):
+    return {torch.float32: "f32", torch.float16: "f16", torch.bfloat16: "bf16"}[t.dtype]
+
+
+SHAPES = [
+    (2, 3, 33, 40, "f16"), (1, 8, 1000, 40, "f16"), (2, 2, 4099, 64, "f16"), (1, 3, 515, 24, "f16"),
+    (1, 2, 300, 32, "f16"), (1, 5, 77, 8, "f16"), (2, 5, 1000, 40, "f16"), (1, 1, 100, 40, "f16"),
+    (1, 9, 2500, 56, "f16"), (3, 6, 130, 16, "f16"),
+    (2, 2, 33, 40, "bf16"), (1, 3, 4099, 64, "bf16"), (1, 2, 300, 48, "bf16"), (2, 7, 900, 40, "bf16"),
+    (1, 2, 17, 64, "f32"), (2, 2, 1000, 40, "f32"), (1, 3, 2051, 56, "f32"),
+]
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("B,H,N,d,dtype", SHAPES)
+def test_token_major_views_match_oracle_and_the_contiguous_call(B, H, N, d, dtype, path):
+    print(f"token-major B={B} H={H} N={N} d={d} {dtype} {path}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=60, device="cpu")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda()          # [B, N, H, d] in memory
+    qt, kt, vt = tm(q), tm(k), tm(v)
+    ot = torch.full_like(qt, float("nan"))
+    view = lambda t: t.permute(0, 2, 1, 3)                            # [B, H, N, d]-shaped view
+    lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(ot), 0, 1e-6, PATHS[path],
+                                  _ws(B, H, N, d, dtype, qt.device))
+    torch.cuda.synchronize()
+    out = view(ot).contiguous()
+    parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"token-major N={N} d={d} {dtype}")
+    # Same kernels, other addresses => same bits as the contiguous call.  The exception: 16-bit rows that
+    # are not whole 128-byte lines go through the one-head-per-wave kernels on the split path, which add
+    # the tiles of a head in another order; those must still be run-to-run identical.
+    regrouped = path == "split" and dtype != "f32" and (d * 2) % 128 != 0 and H > 1
+    if regrouped:
+        ot2 = torch.full_like(qt, float("nan"))
+        lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(ot2), 0, 1e-6, PATHS[path],
+                                      _ws(B, H, N, d, dtype, qt.device))
+        torch.cuda.synchronize()
+        assert torch.equal(ot.view(torch.uint8), ot2.view(torch.uint8))
+    else:
+        ref = _contiguous(q.cuda(), k.cuda(), v.cuda(), PATHS[path])
+        assert torch.equal(out.view(torch.uint8), ref.view(torch.uint8))
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_q_k_v_sliced_from_one_fused_projection_buffer(dtype, path):
+    B, H, N, d = 2, 4, 777, 40
+    print(f"fused projection buffer {dtype} {path}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=61, device="cpu")
+    buf = torch.stack([t.permute(0, 2, 1, 3) for t in (q, k, v)], dim=2).contiguous().cuda()   # [B, N, 3, H, d]
+    views = [buf[:, :, i].permute(0, 2, 1, 3) for i in range(3)]
+    ot = torch.full((B, N, H, d), float("nan"), dtype=q.dtype, device="cuda")
+    lf.linfusion_attn_fwd_strided(views[0], views[1], views[2], ot.permute(0, 2, 1, 3), 0, 1e-6, PATHS[path],
+                                  _ws(B, H, N, d, dtype, buf.device))
+    torch.cuda.synchronize()
+    parity.check_all(ot.permute(0, 2, 1, 3).contiguous(), q, k, v, dtype, 0, 1e-6, True, f"fused buffer {dtype}")
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("dtype,d", [("f16", 40), ("bf16", 64), ("f32", 24)])
+def test_padded_rows_leave_the_padding_untouched(dtype, d, path):
+    B, H, N, pad = 1, 3, 1001, 16
+    print(f"padded rows {dtype} d={d} {path}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=62, device="cpu")
+
+    def padded(t, fill):
+        big = torch.full((B, H, N, d + pad), fill, dtype=t.dtype)
+        big[..., :d] = t
+        return big.cuda()
+    qp, kp, vp = padded(q, float("nan")), padded(k, float("nan")), padded(v, float("nan"))
+    op = torch.full((B, H, N, d + pad), SENTINEL, dtype=q.dtype, device="cuda")
+    lf.linfusion_attn_fwd_strided(qp[..., :d], kp[..., :d], vp[..., :d], op[..., :d], 0, 1e-6, PATHS[path],
+                                  _ws(B, H, N, d, dtype, qp.device))
+    torch.cuda.synchronize()
+    assert bool((op[..., d:] == SENTINEL).all()), "bytes between output rows were written"
+    parity.check_all(op[..., :d].contiguous(), q, k, v, dtype, 0, 1e-6, True, f"padded {dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_one_k_v_shared_by_all_heads_through_a_zero_head_stride(dtype):
+    B, H, N, d = 2, 4, 500, 40
+    q, k1, v1 = wl.make_qkv(B, H, N, d, dtype, idx=63, device="cpu")
+    k1, v1 = k1[:, :1].contiguous(), v1[:, :1].contiguous()
+    qd, kd, vd = q.cuda(), k1.cuda(), v1.cuda()
+    out = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_strided(qd, kd.expand(B, H, N, d), vd.expand(B, H, N, d), out, 0, 1e-6, 0,
+                                  _ws(B, H, N, d, dtype, qd.device))
+    torch.cuda.synchronize()
+    parity.check_all(out, q, k1.expand(B, H, N, d).contiguous(), v1.expand(B, H, N, d).contiguous(), dtype, 0, 1e-6,
+                     True, f"shared kv {dtype}")
+
+
+def test_in_place_on_a_token_major_q():
+    B, H, N, d, dtype = 1, 8, 2000, 40, "f16"
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=64, device="cpu")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda()
+    qt, kt, vt = tm(q), tm(k), tm(v)
+    view = lambda t: t.permute(0, 2, 1, 3)
+    lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(qt), 0, 1e-6, 0, _ws(B, H, N, d, dtype, qt.device))
+    torch.cuda.synchronize()
+    parity.check_all(view(qt).contiguous(), q, k, v, dtype, 0, 1e-6, True, "in place, token-major")
+
+
+def test_sd_sized_token_major_layer():
+    """B=2, H=8, N=4096, d=40 fp16 in the UNet's own [B, N, H*d] layout, default path choice."""
+    name = "sd15_512_f16"
+    c = wl.CONFIGS[name]
+    q, k, v = wl.make_config(name, device="cpu")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda()
+    qt, kt, vt = tm(q), tm(k), tm(v)
+    ot = torch.full_like(qt, float("nan"))
+    view = lambda t: t.permute(0, 2, 1, 3)
+    B, H, N, d = q.shape
+    lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(ot), 0, wl.EPS, 0,
+                                  _ws(B, H, N, d, c["dtype"], qt.device))
+    torch.cuda.synchronize()
+    parity.check_all(view(ot).contiguous(), q, k, v, c["dtype"], 0, wl.EPS, True, name + " token-major")
