@@ -60,35 +60,55 @@ template <int D> struct ApplyDmaCfg {
   static __device__ __forceinline__ int swz(int row) { return (row >> kSwzShift) & kSwzMask; }
 };
 
+// `waves`: waves per workgroup (4, or 8 for the row-piece kernel on groups of eight heads)
 template <typename T, int D>
-constexpr int apply16_dma_lds_bytes() {
-  int ring = ApplyDmaCfg<D>::kRing * ApplyDmaCfg<D>::kSlotBytes * kWavesPerWG;
-  int st = ApplyDmaCfg<D>::kStageOffset + ApplyDmaCfg<D>::kStageBytes;
+constexpr int apply16_dma_lds_bytes(int waves = kWavesPerWG) {
+  int ring = ApplyDmaCfg<D>::kRing * ApplyDmaCfg<D>::kSlotBytes * waves;
+  int st = (ApplyDmaCfg<D>::kRing - 1) * ApplyDmaCfg<D>::kSlotBytes * waves + ApplyDmaCfg<D>::kStageBytes;
   return ring > st ? ring : st;
 }
 
 template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// One workgroup's apply work: construct, prefetch(), run() -- or, with HG ("one head per wave": the four
-// waves work on four different heads over the same tiles, every wave visiting all of the workgroup's
-// tiles), construct with the wave's own pointers, prefetch(), load_state() once per head of the group,
-// stream().  HG stores are ordinary cached stores: the waves of a group fill neighbouring pieces of
-// the same memory rows, which the cache then writes back whole.
-template <typename T, int D, int FM, bool NORM, bool HG = false>
+// One workgroup's apply work on one head: construct, prefetch(), run().
+//
+// ROWS_W = W > 0 (4 or 8; for layouts in which the W heads h0..h0+W-1 of a token are neighbours in memory,
+// so that a token row of the group is one contiguous piece of W d elements): a workgroup of W waves works
+// on the W heads at once, wave w computing head h0 + w, and all waves walk the same tiles.  A ring slot
+// then spans the waves' regions and holds a tile of whole row pieces: wave w copies in (and later stores)
+// token rows (32 / W) w .. + 32 / W - 1 of the tile, all heads of them -- contiguous W d-element pieces
+// instead of W scattered d-element ones -- and two workgroup barriers per tile separate "pieces have
+// landed" -> "each wave reads and overwrites its head's columns" -> "pieces leave".  Inside a row piece
+// the 16-byte chunks are rotated by a row-dependent amount (both ways) so that the token-per-lane
+// accesses to one head's columns are bank-conflict free.  Use: construct with the group's pointers,
+// prefetch(), load_state() once per head (`keep` on the wave that owns it), stream().
+template <typename T, int D, int FM, bool NORM, int ROWS_W = 0>
 struct ApplyDma {
+  static constexpr bool ROWS = ROWS_W > 0;
+  static constexpr int W = ROWS ? ROWS_W : kWavesPerWG;   // waves per workgroup
+  static constexpr int NT = 64 * W;
   using Sh = Shape16<D>;
   using Cfg = ApplyDmaCfg<D>;
   static constexpr int NS = NSplit<T>::value;
   static constexpr int KS = Sh::kKS, MT2 = Sh::kMT2, CPR = Sh::kChunksPerRow, HALF = Sh::kHalf;
   static constexpr int NL = Cfg::kNL, NE = D * D + D, R = Cfg::kRing;
   static_assert(R == 3, "the wait counts below are written for a ring of three slots");
+  // ROWS: chunks per row piece, and the rotation that spreads 16 consecutive tokens over the 16
+  // sixteen-byte bank groups: row r is rotated by (r * G >> 4) % G chunks, G = gcd(PC, 16)
+  static constexpr int PC = W * CPR;
+  static constexpr int G = (PC % 16 == 0) ? 16 : ((PC % 8 == 0) ? 8 : 4);
+  static constexpr int RPR = kTile / W;   // token rows per wave region
+  static_assert(!ROWS || (PC % 4 == 0 && RPR * G >= 16 && kTile % W == 0), "rotation classes must fit a region");
+  static constexpr int kStageOffset = (R - 1) * W * Cfg::kSlotBytes;
+  static __device__ __forceinline__ int rot(int r) { return ((r * G) >> 4) & (G - 1); }
 
   const u32x4* Qh;
   u32x4* Oh;
   long long N;
   unsigned char* smem;
   int rs_q, rs_o;
-  int lane, wave, tok, kg, row_byte, tsw;
+  int lane, wave, tok, kg, row_byte, tsw;   // ROWS: row_byte = byte offset of the token's piece in a slot block,
+                                            //       tsw = first chunk of this wave's head + the row's rotation
   // LDS position p = 64 u + lane of a slot holds the chunk of token row trow[u] that lies qoff[u]
   // (in Q) / ooff[u] (in out) vector units after the tile's first row
   int trow[NL], qoff[NL], ooff[NL];
@@ -98,27 +118,52 @@ struct ApplyDma {
 
   // `Qh_`, `Oh_`: first token row of this head; `rs_q_`, `rs_o_`: row strides in 16-byte units
   LF_DEV ApplyDma(const u32x4* Qh_, int rs_q_, u32x4* Oh_, int rs_o_, long long N_, int tiles_per_block, int wg,
-                  int nwg, unsigned char* smem_, bool active = true)
+                  int nwg, unsigned char* smem_)
       : Qh(Qh_), Oh(Oh_), N(N_), smem(smem_), rs_q(rs_q_), rs_o(rs_o_),
         lane(threadIdx.x & 63), wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
-        it(wg, nwg, HG ? 0 : wave, tiles_per_block, (HG && !active) ? 0 : (N_ + kTile - 1) / kTile,
-           HG ? 1 : kWavesPerWG),
+        it(wg, nwg, ROWS ? 0 : wave, tiles_per_block, (N_ + kTile - 1) / kTile, ROWS ? 1 : kWavesPerWG),
         ahead(it) {
     tok = lane & 31;
     kg = lane >> 5;
-    row_byte = tok * Cfg::kRowBytes;
-    tsw = Cfg::swz(tok);
+    if constexpr (ROWS) {
+      row_byte = (tok / RPR) * Cfg::kSlotBytes + (tok % RPR) * PC * 16;
+      tsw = wave * CPR + rot(tok);
 #pragma unroll
-    for (int u = 0; u < NL; ++u) {
-      const int p = u * 64 + lane;
-      const int r = p / CPR, pos = p % CPR;
-      trow[u] = r;
-      qoff[u] = r * rs_q + (pos ^ Cfg::swz(r));
-      ooff[u] = r * rs_o + (pos ^ Cfg::swz(r));
+      for (int u = 0; u < NL; ++u) {
+        const int P = wave * Cfg::kChunks + u * 64 + lane;   // position in the tile of row pieces
+        const int r = P / PC;
+        int c = P % PC - rot(r);
+        if (c < 0) c += PC;
+        trow[u] = r;
+        qoff[u] = r * rs_q + c;
+        ooff[u] = r * rs_o + c;
+      }
+    } else {
+      row_byte = tok * Cfg::kRowBytes;
+      tsw = Cfg::swz(tok);
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        const int p = u * 64 + lane;
+        const int r = p / CPR, pos = p % CPR;
+        trow[u] = r;
+        qoff[u] = r * rs_q + (pos ^ Cfg::swz(r));
+        ooff[u] = r * rs_o + (pos ^ Cfg::swz(r));
+      }
     }
   }
 
-  LF_DEV unsigned char* slot_ptr(int slot) const { return smem + (slot * kWavesPerWG + wave) * Cfg::kSlotBytes; }
+  // this wave's region of ring slot `slot`: what it copies in and stores from
+  LF_DEV unsigned char* slot_ptr(int slot) const { return smem + (slot * W + wave) * Cfg::kSlotBytes; }
+  // where this lane finds (and overwrites) 16-byte chunk `chunk` of its token's head row in slot `slot`
+  LF_DEV unsigned char* chunk_ptr(int slot, int chunk) const {
+    if constexpr (ROWS) {
+      int x = tsw + chunk;
+      if (x >= PC) x -= PC;
+      return smem + slot * W * Cfg::kSlotBytes + row_byte + (x << 4);
+    } else {
+      return slot_ptr(slot) + row_byte + ((chunk ^ tsw) << 4);
+    }
+  }
 
   // copies tile `tile` into ring slot `slot`; always issues exactly NL vector memory instructions
   LF_DEV void issue_copy(long long tile, int slot) {
@@ -154,10 +199,10 @@ struct ApplyDma {
   // Whole workgroup: stages one head's state in LDS; the waves with `keep` build their operands from it.
   LF_DEV void load_state(const float* state, float eps, bool keep) {
     // ---- prologue: state -> LDS, maxima, power-of-two scales, A fragments -------------------------
-    float* st = reinterpret_cast<float*>(smem + Cfg::kStageOffset);
+    float* st = reinterpret_cast<float*>(smem + kStageOffset);
     float* redmax = st + NE;
     float mS = 0.0f, mz = 0.0f;
-    for (int e = threadIdx.x; e < NE; e += kThreads) {
+    for (int e = threadIdx.x; e < NE; e += NT) {
       float x = ld_agent(state + e);
       st[e] = x;
       if (e < D * D) mS = fmaxf(mS, fabsf(x)); else mz = fmaxf(mz, fabsf(x));
@@ -167,11 +212,11 @@ struct ApplyDma {
       mS = fmaxf(mS, __shfl_xor(mS, o));
       mz = fmaxf(mz, __shfl_xor(mz, o));
     }
-    if (lane == 0) { redmax[wave] = mS; redmax[kWavesPerWG + wave] = mz; }
+    if (lane == 0) { redmax[wave] = mS; redmax[W + wave] = mz; }
     __syncthreads();
     mS = 0.0f; mz = 0.0f;
 #pragma unroll
-    for (int w = 0; w < kWavesPerWG; ++w) { mS = fmaxf(mS, redmax[w]); mz = fmaxf(mz, redmax[kWavesPerWG + w]); }
+    for (int w = 0; w < W; ++w) { mS = fmaxf(mS, redmax[w]); mz = fmaxf(mz, redmax[W + w]); }
     const float aS = pow2_scale_for(mS);
     const float az = NORM ? pow2_scale_for(mz) : 1.0f;
     if (keep) {
@@ -212,7 +257,9 @@ struct ApplyDma {
     __syncthreads();   // the staged state is dead: the third slot block may be filled from here on
   }
 
+  // Per-head mode: each wave streams on its own.
   LF_DEV void stream() {
+    if constexpr (ROWS) { stream_rows(); return; }
     int slot = 0;
     int iter = 0;
     while (it.valid()) {
@@ -230,133 +277,173 @@ struct ApplyDma {
         wait_vmcnt<0>();
       }
       iter = iter < 2 ? iter + 1 : 2;
-      unsigned char* sl = slot_ptr(slot);
-
-      // ---- this lane's token row -> phi -> 16-bit B operands ----------------------------------------
-      u32x4 Bh[KS], Bl[KS];
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        const int chunk = kg * KS + s;
-        const bool ok = chunk < CPR;
-        u32x4 raw = u32x4{0, 0, 0, 0};
-        if (ok) raw = *reinterpret_cast<const u32x4*>(sl + row_byte + ((chunk ^ tsw) << 4));
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          float x0, x1;
-          unpack2<T>(raw[w], x0, x1);
-          float r0 = ok ? phi<FM>(x0) : 0.0f;
-          float r1 = ok ? phi<FM>(x1) : 0.0f;
-          if constexpr (NS == 1) {
-            Bh[s][w] = pack2<T>(r0, r1);
-          } else {
-            uint32_t h, l;
-            pack2_split<T>(r0, r1, h, l);
-            Bh[s][w] = h;
-            Bl[s][w] = l;
-          }
-        }
-      }
-
-      f32x16 acc[MT2];
-#pragma unroll
-      for (int t = 0; t < MT2; ++t) {
-        acc[t] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          acc[t] = mfma_32x32x16<T>(A[0][t][s], Bh[s], acc[t]);
-          if constexpr (NS == 2) {
-            acc[t] = mfma_32x32x16<T>(A[0][t][s], Bl[s], acc[t]);
-            if (16 * t < HALF) acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);   // lo rows are zero beyond S'
-          }
-        }
-      }
-      // normalizer: slots HALF (z' rounded) and HALF+1 (its remainder) of this lane's accumulators
-      float scale = c1;
-      if constexpr (NORM) {
-        const float den = acc[HALF / 16][HALF % 16] + acc[(HALF + 1) / 16][(HALF + 1) % 16] + eps_s;
-        scale = c1 * __builtin_amdgcn_rcpf(den);
-      }
-
-      // ---- d/2 channels of this lane's token -> 16-bit -> back into the slot -------------------------
+      compute_tile(slot);
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      if constexpr (HALF % 8 == 0) {
-#pragma unroll
-        for (int c = 0; c < HALF / 8; ++c) {
-          u32x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int s0 = c * 8 + 2 * e;
-            w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
-          }
-          const int chunk = kg * (HALF / 8) + c;
-          *reinterpret_cast<u32x4*>(sl + row_byte + ((chunk ^ tsw) << 4)) = w;
-        }
-      } else {
-        static_assert(HALF % 8 == 0 || Cfg::kSwzMask == 0, "64-bit row pieces need an unswizzled row");
-#pragma unroll
-        for (int c = 0; c < HALF / 4; ++c) {
-          u32x2 w;
-#pragma unroll
-          for (int e = 0; e < 2; ++e) {
-            const int s0 = c * 4 + 2 * e;
-            w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
-          }
-          *reinterpret_cast<u32x2*>(sl + row_byte + kg * (HALF * 2) + c * 8) = w;
-        }
-      }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-
-      // ---- coalesced stores; always NL instructions (lanes without a valid chunk are masked) ------
-      {
-        long long rem = N - tile * kTile;
-        const int lim = rem < kTile ? (int)rem : kTile;
-        u32x4* op = Oh + tile * kTile * rs_o;
-#pragma unroll
-        for (int u = 0; u < NL; ++u) {
-          const u32x4 w = *reinterpret_cast<const u32x4*>(sl + u * 1024 + lane * 16);
-          if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) {
-            if constexpr (HG) op[ooff[u]] = w; else st_stream(op + ooff[u], w);
-          }
-        }
-      }
+      store_tile(tile, slot);
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       it.next();
       ahead.next();
       slot = slot + 1 == R ? 0 : slot + 1;
     }
   }
+
+  // Row-piece mode: the waves move in step, one workgroup barrier per tile.  Iteration j: store tile
+  // j-1 (complete since the last barrier), copy tile j+2 into the slot that frees, compute tile j,
+  // wait for this wave's rows of tile j+1, barrier ("tile j computed by all, tile j+1 landed for all").
+  // Issue order per wave:  C0 C1 [state] | C2 K0 w | S0 C3 K1 w | S1 C4 K2 w | ...  so after tile j+1's
+  // copies come S(j-1) and C(j+2), where they exist.
+  LF_DEV void stream_rows() {
+    {   // this wave's rows of the first tile: only the second tile's copies were issued after them
+      TileIter second = it;
+      second.next();
+      if (second.valid()) wait_vmcnt<NL>();
+      else wait_vmcnt<0>();
+    }
+    __syncthreads();
+    int slot = 0, prev_slot = 0;
+    long long prev_tile = -1;
+    while (it.valid()) {
+      const long long tile = it.t;
+      const bool have_prev = prev_tile >= 0;
+      if (have_prev) store_tile(prev_tile, prev_slot);
+      const bool copied = ahead.valid();
+      if (copied) issue_copy(ahead.t, have_prev ? prev_slot : R - 1);
+      compute_tile(slot);
+      it.next();
+      ahead.next();
+      if (it.valid()) {
+        if (have_prev && copied) wait_vmcnt<2 * NL>();
+        else if (have_prev || copied) wait_vmcnt<NL>();
+        else wait_vmcnt<0>();
+      }
+      __syncthreads();
+      prev_tile = tile;
+      prev_slot = slot;
+      slot = slot + 1 == R ? 0 : slot + 1;
+    }
+    if (prev_tile >= 0) store_tile(prev_tile, prev_slot);
+  }
+
+  // B operands of this lane's token from ring slot `slot`, products with the state operands, normalizer,
+  // and the finished channels back into the same places of the slot
+  LF_DEV void compute_tile(int slot) {
+    // ---- this lane's token row -> phi -> 16-bit B operands ----------------------------------------
+    u32x4 Bh[KS], Bl[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int chunk = kg * KS + s;
+      const bool ok = chunk < CPR;
+      u32x4 raw = u32x4{0, 0, 0, 0};
+      if (ok) raw = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, chunk));
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        float x0, x1;
+        unpack2<T>(raw[w], x0, x1);
+        float r0 = ok ? phi<FM>(x0) : 0.0f;
+        float r1 = ok ? phi<FM>(x1) : 0.0f;
+        if constexpr (NS == 1) {
+          Bh[s][w] = pack2<T>(r0, r1);
+        } else {
+          uint32_t h, l;
+          pack2_split<T>(r0, r1, h, l);
+          Bh[s][w] = h;
+          Bl[s][w] = l;
+        }
+      }
+    }
+
+    f32x16 acc[MT2];
+#pragma unroll
+    for (int t = 0; t < MT2; ++t) {
+      acc[t] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        acc[t] = mfma_32x32x16<T>(A[0][t][s], Bh[s], acc[t]);
+        if constexpr (NS == 2) {
+          acc[t] = mfma_32x32x16<T>(A[0][t][s], Bl[s], acc[t]);
+          if (16 * t < HALF) acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);   // lo rows are zero beyond S'
+        }
+      }
+    }
+    // normalizer: slots HALF (z' rounded) and HALF+1 (its remainder) of this lane's accumulators
+    float scale = c1;
+    if constexpr (NORM) {
+      const float den = acc[HALF / 16][HALF % 16] + acc[(HALF + 1) / 16][(HALF + 1) % 16] + eps_s;
+      scale = c1 * __builtin_amdgcn_rcpf(den);
+    }
+
+    // ---- d/2 channels of this lane's token -> 16-bit -> back into the slot -------------------------
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    if constexpr (HALF % 8 == 0) {
+#pragma unroll
+      for (int c = 0; c < HALF / 8; ++c) {
+        u32x4 w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int s0 = c * 8 + 2 * e;
+          w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
+        }
+        const int chunk = kg * (HALF / 8) + c;
+        *reinterpret_cast<u32x4*>(chunk_ptr(slot, chunk)) = w;
+      }
+    } else {
+      static_assert(HALF % 8 == 0 || Cfg::kSwzMask == 0, "64-bit pieces assume whole chunks stay together");
+#pragma unroll
+      for (int c = 0; c < HALF / 4; ++c) {
+        u32x2 w;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int s0 = c * 4 + 2 * e;
+          w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
+        }
+        const int byte = kg * (HALF * 2) + c * 8;   // offset inside the head's row
+        *reinterpret_cast<u32x2*>(chunk_ptr(slot, byte >> 4) + (byte & 15)) = w;
+      }
+    }
+  }
+
+  // coalesced stores of a finished tile; always NL instructions (lanes without a valid chunk are masked)
+  LF_DEV void store_tile(long long tile, int slot) {
+    const unsigned char* sl = slot_ptr(slot);
+    long long rem = N - tile * kTile;
+    const int lim = rem < kTile ? (int)rem : kTile;
+    u32x4* op = Oh + tile * kTile * rs_o;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(sl + u * 1024 + lane * 16);
+      if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) st_stream(op + ooff[u], w);
+    }
+  }
 };
 
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-apply16_dma(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo,
+apply16_dma(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, HeadSubset hs,
             const float* __restrict__ state, float eps, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const long long bh = blockIdx.y;
+  const long long bh = hs.bh(blockIdx.y, lq.H);
   ApplyDma<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
                               gridDim.x, smem);
   ap.prefetch();
   ap.run(state + bh * (D * D + D), eps);
 }
 
-// Apply with one head per wave.  grid = (wgs, B * ceil(H / 4)); same head assignment as state_reduce16_hg.
-template <typename T, int D, int FM, bool NORM>
-__global__ void __launch_bounds__(kThreads)
-apply16_dma_hg(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo,
-               const float* __restrict__ state, float eps, long long N, int tiles_per_block) {
+// Apply on groups of W (4 or 8) neighbouring heads (see ROWS_W above).  grid = (wgs, B * groups_per_batch),
+// block = 64 W: workgroup (x, y) takes heads W (y % gpb) .. + W - 1 of batch y / gpb.  Heads beyond the last
+// whole group are left to apply16_dma.
+template <typename T, int D, int FM, bool NORM, int W>
+__global__ void __launch_bounds__(64 * W)
+apply16_rows(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, int groups_per_batch,
+             const float* __restrict__ state, float eps, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int H = lq.H;
-  const int gpb = (H + kWavesPerWG - 1) / kWavesPerWG;
-  const int b = blockIdx.y / gpb;
-  const int h0 = (blockIdx.y % gpb) * kWavesPerWG;
-  const bool active = h0 + wave < H;
-  const int h = active ? h0 + wave : H - 1;
-  ApplyDma<T, D, FM, NORM, true> ap(Q + (b * lq.batch + h * lq.head), lq.row, O + (b * lo.batch + h * lo.head), lo.row,
-                                    N, tiles_per_block, blockIdx.x, gridDim.x, smem, active);
+  const long long b = blockIdx.y / groups_per_batch;
+  const long long h0 = (long long)(blockIdx.y % groups_per_batch) * W;
+  ApplyDma<T, D, FM, NORM, W> ap(Q + (b * lq.batch + h0 * lq.head), lq.row, O + (b * lo.batch + h0 * lo.head), lo.row,
+                                 N, tiles_per_block, blockIdx.x, gridDim.x, smem);
   ap.prefetch();
-  for (int w = 0; w < kWavesPerWG && h0 + w < H; ++w)
-    ap.load_state(state + ((long long)b * H + h0 + w) * (D * D + D), eps, wave == w);
+  for (int w = 0; w < W; ++w)
+    ap.load_state(state + (b * lq.H + h0 + w) * (D * D + D), eps, wave == w);
   ap.stream();
 }
 

@@ -143,6 +143,13 @@ struct Layout {
   LF_DEV long long slice(long long bh) const { return (bh / H) * batch + (bh % H) * head; }
 };
 
+// Heads [first, first + count) of every batch: grid row y of a per-head kernel works on
+// head first + y % count of batch y / count.  {0, H} = all heads.
+struct HeadSubset {
+  int first, count;
+  LF_DEV long long bh(int y, int H) const { return (long long)(y / count) * H + first + y % count; }
+};
+
 // ---- which tiles a wave processes -----------------------------------------------------------
 // The tiles of a head are cut into blocks of `blk` consecutive tiles (blk a multiple of the
 // waves per workgroup); workgroup g of G takes blocks g, g + G, g + 2G, ... and inside a block its

@@ -43,14 +43,10 @@ constexpr int reduce16_lds_bytes() {
 // `dst`: where this workgroup's partial goes ([D*D + D] floats).  `smem`: reduce16_lds_bytes<T,D>()
 // bytes of LDS.  Ends with every thread having written its share of `dst` (no trailing barrier).
 // `Kh`, `Vh`: first token row of this head; `rs`: row stride in 16-byte units.
-// HG ("one head per wave"): the four waves of the workgroup work on four different heads over the same
-// tiles -- `Kh`, `Vh`, `dst` are then the calling wave's own (wave-uniform) and each wave writes its own
-// partial; a wave with `active` false (no head left for it) does nothing.  When the heads of a token lie
-// next to each other in memory, the workgroup as a whole then touches whole contiguous row pieces.
-template <typename T, int D, int FM, bool HG = false>
+template <typename T, int D, int FM>
 LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict__ Vh, int rs,
                            float* __restrict__ dst, long long N, int tiles_per_block, int split, int nsplit,
-                           unsigned char* smem, bool active = true) {
+                           unsigned char* smem) {
   using Sh = Shape16<D>;
   using Cfg = Reduce16Cfg<D>;
   constexpr int NS = NSplit<T>::value;
@@ -80,7 +76,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
   const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
 
   const long long n_tiles = (N + kTile - 1) / kTile;
-  TileIter it(split, nsplit, HG ? 0 : wave, tiles_per_block, (HG && !active) ? 0 : n_tiles, HG ? 1 : kWavesPerWG);
+  TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
 
   f32x4 acc[MT][MT];
   f32x4 accz[MT];
@@ -182,31 +178,6 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
     lim = next_lim;
   }
 
-  if constexpr (HG) {
-    // each wave owns a whole partial: straight from the accumulator layout (lane: rows 4 (l / 16) + i,
-    // column l % 16 of each 16 x 16 block) to memory
-    if (!active) return;
-#pragma unroll
-    for (int a = 0; a < MT; ++a) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int row = a * 16 + 4 * g4 + i;
-        if (row < D) {
-#pragma unroll
-          for (int b = 0; b < MT; ++b) {
-            const int col = b * 16 + j16;
-            if (col < D) st_agent(dst + row * D + col, acc[a][b][i]);
-            else if (Sh::kSpareCol && col == D) st_agent(dst + D * D + row, acc[a][b][i]);
-          }
-          if constexpr (!Sh::kSpareCol) {
-            if (j16 == 0) st_agent(dst + D * D + row, accz[a][i]);
-          }
-        }
-      }
-    }
-    return;
-  }
-
   // ---- cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3): waves 0 and 1 park their accumulators
   //      in two LDS copies ([D*D] S then [D] z), waves 2 and 3 add theirs on top, then all threads add
   //      the two copies and write the partial --------------------------------------------------------
@@ -248,33 +219,202 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
 
 template <typename T, int D, int FM>
 __global__ void __launch_bounds__(kThreads)
-state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, float* __restrict__ partials,
-               long long N, int tiles_per_block) {
+state_reduce16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, HeadSubset hs,
+               float* __restrict__ partials, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const long long bh = blockIdx.y;
+  const long long bh = hs.bh(blockIdx.y, kv.H);
   float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
   const long long off = kv.slice(bh);
   reduce16_phase<T, D, FM>(K + off, V + off, kv.row, dst, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
 }
 
-// The same reduction with one head per wave.  grid = (splits, B * ceil(H / 4)): workgroup (split, g) takes
-// heads 4 (g % ceil(H/4)) + wave of batch g / ceil(H/4).  Partials keep the layout [B*H][splits][d*d + d].
-template <typename T, int D, int FM>
-__global__ void __launch_bounds__(kThreads)
-state_reduce16_hg(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, float* __restrict__ partials,
-                  long long N, int tiles_per_block) {
+// ==========================================================================================
+// State reduction on groups of W (4 or 8) heads that are neighbours in memory (a token row of the group
+// is one contiguous piece of W d elements, as in the token-major [B, N, H*d] layout).
+// grid = (splits, B * groups_per_batch), block = 64 W: workgroup (x, y) takes heads W (y % gpb) .. + W-1
+// of batch y / gpb; heads beyond the last whole group are left to state_reduce16.
+// All threads fetch each tile as whole row pieces (coalesced over W d elements instead of W scattered
+// d-element rows), apply phi to the K pieces and scatter the chunks into per-head LDS tiles; after a
+// workgroup barrier wave w multiplies head w's tiles exactly as state_reduce16 does and keeps that
+// head's accumulators, so a partial is one wave's sum over all the workgroup's tiles.  The LDS tiles
+// are double-buffered where two sets fit in 64 KiB (one barrier per tile), else single (two).
+// ==========================================================================================
+template <typename T, int D, int W> struct ReduceRowsCfg {
+  using Sh = Shape16<D>;
+  using RC = Reduce16Cfg<D>;
+  static constexpr int kNS = NSplit<T>::value;
+  static constexpr int kThreadsW = 64 * W;
+  static constexpr int kPiece = W * Sh::kChunksPerRow;      // 16-byte chunks per row piece
+  static constexpr int kChunks = kTile * kPiece;                       // chunks per tile of row pieces
+  static constexpr int kNL = (kChunks + kThreadsW - 1) / kThreadsW;      // loads per thread per tensor
+  static constexpr int kHeadElems = (kNS + 1) * RC::kTileElems;        // phi(K) level tiles, then the V tile
+  static constexpr int kBufElems = W * kHeadElems;
+  static constexpr bool kDouble = 2 * kBufElems * 2 <= 65536;
+  static constexpr int kLdsBytes = (kDouble ? 2 : 1) * kBufElems * 2;
+};
+
+template <typename T, int D, int FM, int W>
+__global__ void __launch_bounds__(64 * W)
+state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, int groups_per_batch,
+                    float* __restrict__ partials, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int gpb = (kv.H + kWavesPerWG - 1) / kWavesPerWG;
-  const int b = blockIdx.y / gpb;
-  int h = (blockIdx.y % gpb) * kWavesPerWG + wave;
-  const bool active = h < kv.H;
-  if (!active) h = kv.H - 1;
-  const long long bh = (long long)b * kv.H + h;
-  float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
-  const long long off = b * kv.batch + h * kv.head;
-  reduce16_phase<T, D, FM, true>(K + off, V + off, kv.row, dst, N, tiles_per_block, blockIdx.x, gridDim.x, smem,
-                                 active);
+  using Sh = Shape16<D>;
+  using RC = Reduce16Cfg<D>;
+  using Cfg = ReduceRowsCfg<T, D, W>;
+  constexpr int NT = Cfg::kThreadsW;
+  constexpr int NS = Cfg::kNS, RS = RC::kRS, NL = Cfg::kNL, CPR = Sh::kChunksPerRow, MT = Sh::kMT;
+  constexpr int PC = Cfg::kPiece, TE = RC::kTileElems;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long b = blockIdx.y / groups_per_batch;
+  const long long h0 = (long long)(blockIdx.y % groups_per_batch) * W;
+  const u32x4* Kg = K + (b * kv.batch + h0 * kv.head);
+  const u32x4* Vg = V + (b * kv.batch + h0 * kv.head);
+  const int rs = kv.row;
+  uint16_t* lds = reinterpret_cast<uint16_t*>(smem);
+
+  // per-thread constants: chunk p = 64 W u + tid of a tile is chunk p % PC of token row p / PC; it
+  // belongs to head (p % PC) / CPR and lands in that head's LDS tiles
+  int goff[NL], loff[NL], trow[NL];
+#pragma unroll
+  for (int u = 0; u < NL; ++u) {
+    const int p = u * NT + tid;
+    const int r = p / PC, c = p % PC;
+    const bool in = p < Cfg::kChunks;
+    trow[u] = in ? r : kTile;              // kTile: never below the row limit
+    goff[u] = r * rs + c;
+    loff[u] = in ? (c / CPR) * Cfg::kHeadElems + r * RS + (c % CPR) * 8 : 0;
+  }
+  const int j16 = lane & 15, g4 = lane >> 4;
+  const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
+
+  const long long n_tiles = (N + kTile - 1) / kTile;
+  TileIter it(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);   // every wave walks every tile
+
+  f32x4 acc[MT][MT];
+  f32x4 accz[MT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    accz[a] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int bb = 0; bb < MT; ++bb) acc[a][bb] = f32x4{0, 0, 0, 0};
+  }
+  const uint32_t one2 = (uint32_t)OneBits<T>::value * 0x10001u;
+  const u32x4 ones = {one2, one2, one2, one2};
+
+  u32x4 kr[NL], vr[NL];
+  auto issue_loads = [&](long long tile) {
+    long long rem = N - tile * kTile;
+    int lim = rem < kTile ? (int)rem : kTile;
+    const u32x4* kp = Kg + tile * kTile * rs;
+    const u32x4* vp = Vg + tile * kTile * rs;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      if (trow[u] < lim) {
+        kr[u] = ld_stream(kp + goff[u]);
+        vr[u] = ld_stream(vp + goff[u]);
+      } else {
+        kr[u] = u32x4{0, 0, 0, 0};
+        vr[u] = u32x4{0, 0, 0, 0};
+      }
+    }
+    return lim;
+  };
+
+  int lim = 0;
+  if (it.valid()) lim = issue_loads(it.t);
+
+  // one-time fill: pad columns zero, ones column (index D, where a spare column exists) in the V tiles
+  for (int i = tid; i < (Cfg::kDouble ? 2 : 1) * Cfg::kBufElems; i += NT) {
+    const int tile_idx = i / TE, within = i % TE;
+    const bool is_v = tile_idx % (NS + 1) == NS;
+    lds[i] = (is_v && Sh::kSpareCol && within % RS == D) ? OneBits<T>::value : (uint16_t)0;
+  }
+  __syncthreads();
+
+  int buf = 0;
+  while (it.valid()) {
+    uint16_t* bufp = lds + buf * Cfg::kBufElems;
+    // ---- phi(K) -> 16-bit (hi [, lo]) -> the owning head's tiles ; V likewise ------------------
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      if (u * NT + tid < Cfg::kChunks) {
+        const bool ok = trow[u] < lim;
+        u32x4 ph, pl;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1;
+          unpack2<T>(kr[u][w], x0, x1);
+          float p0 = ok ? phi<FM>(x0) : 0.0f;
+          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          if constexpr (NS == 1) {
+            ph[w] = pack2<T>(p0, p1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(p0, p1, h, l);
+            ph[w] = h;
+            pl[w] = l;
+          }
+        }
+        *reinterpret_cast<u32x4*>(bufp + loff[u]) = ph;
+        if constexpr (NS == 2) *reinterpret_cast<u32x4*>(bufp + TE + loff[u]) = pl;
+        *reinterpret_cast<u32x4*>(bufp + NS * TE + loff[u]) = vr[u];
+      }
+    }
+    it.next();
+    int next_lim = 0;
+    if (it.valid()) next_lim = issue_loads(it.t);
+    __syncthreads();   // the tile is complete in LDS
+
+    // ---- wave w: head w's outer products ----------------------------------------------------
+    const uint16_t* hp = bufp + wave * Cfg::kHeadElems;
+    const uint16_t* ldsV = hp + NS * TE;
+    u32x4 bfrag[MT];
+#pragma unroll
+    for (int bb = 0; bb < MT; ++bb) {
+      u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * bb);
+      u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * bb);
+      bfrag[bb] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        u32x2 r0 = lds_read_tr16(hp + s * TE + tr_base + 16 * a);
+        u32x2 r1 = lds_read_tr16(hp + s * TE + tr_base + 4 * RS + 16 * a);
+        u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+        for (int bb = 0; bb < MT; ++bb) acc[a][bb] = mfma_16x16x32<T>(afrag, bfrag[bb], acc[a][bb]);
+        if constexpr (!Sh::kSpareCol) accz[a] = mfma_16x16x32<T>(afrag, ones, accz[a]);
+      }
+    }
+    if constexpr (Cfg::kDouble) buf ^= 1;
+    else __syncthreads();   // single buffer: everyone is done reading before the next tile is written
+    lim = next_lim;
+  }
+
+  // ---- each wave owns a whole partial: straight from the accumulator layout (lane: rows 4 (l / 16) + i,
+  //      column l % 16 of each 16 x 16 block) to memory ----------------------------------------------
+  float* dst = partials + (((b * kv.H + h0 + wave) * gridDim.x) + blockIdx.x) * (long long)(D * D + D);
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = a * 16 + 4 * g4 + i;
+      if (row < D) {
+#pragma unroll
+        for (int bb = 0; bb < MT; ++bb) {
+          const int col = bb * 16 + j16;
+          if (col < D) st_agent(dst + row * D + col, acc[a][bb][i]);
+          else if (Sh::kSpareCol && col == D) st_agent(dst + D * D + row, acc[a][bb][i]);
+        }
+        if constexpr (!Sh::kSpareCol) {
+          if (j16 == 0) st_agent(dst + D * D + row, accz[a][i]);
+        }
+      }
+    }
+  }
 }
 
 // ==========================================================================================

@@ -29,8 +29,9 @@ struct Plan {
   int blk_apply;        //   tiles per contiguous block of an apply workgroup
   int fsplits;          // fused path: workgroups per head (0 = the shape cannot use it)
   int fblk_reduce, fblk_apply;
-  // one-head-per-wave kernels (heads adjacent in memory): workgroups per group of four heads
-  int groups, gsplits, gblk_reduce, gapply_wgs, gblk_apply;
+  // row-piece kernels (heads adjacent in memory): whole groups of gwaves (8 if H % 8 == 0, else 4)
+  // heads, one wave per head; workgroups per group
+  int gwaves, groups, gsplits, gblk_reduce, gapply_wgs, gblk_apply;
   long long n_tiles;
   size_t state_floats;  // d*d + d: one partial, and one head's state
   size_t ws_partials, ws_state, ws_sync, ws_total;
@@ -45,11 +46,11 @@ int env_int(const char* name, int dflt) {
 
 // tiles per contiguous block of a workgroup, at most its whole share, rounded up to a multiple of
 // the waves per workgroup; the environment override is a tuning aid
-int block_tiles(long long share, const char* env, int dflt) {
+int block_tiles(long long share, const char* env, int dflt, int multiple = lf::kWavesPerWG) {
   long long b = env_int(env, dflt);
   if (b > share) b = share;
   if (b > (1 << 28)) b = 1 << 28;
-  return (int)((b + lf::kWavesPerWG - 1) / lf::kWavesPerWG * lf::kWavesPerWG);
+  return (int)((b + multiple - 1) / multiple * multiple);
 }
 
 bool supported_d(int d) { return d >= 8 && d <= 64 && d % 8 == 0; }
@@ -100,9 +101,10 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     p->fblk_reduce = block_tiles(share, "LINFUSION_REDUCE_BLK", 16);
     p->fblk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", 8);
   }
-  // one head per wave: a workgroup covers four heads, every wave walks all of its tiles
-  p->groups = B * ((H + lf::kWavesPerWG - 1) / lf::kWavesPerWG);
-  {
+  // row-piece kernels: a workgroup covers a whole group of four heads, every wave walks all of its tiles
+  p->gwaves = (H % 8 == 0 && env_int("LINFUSION_GROUP_WAVES", 8) == 8) ? 8 : 4;
+  p->groups = B * (H / p->gwaves);
+  if (p->groups > 0) {
     auto per_group = [&](int want_total, long long* sh) {
       long long s = (want_total + p->groups - 1) / p->groups;
       if (s > p->n_tiles) s = p->n_tiles;
@@ -111,10 +113,17 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
       *sh = t;
       return (int)((p->n_tiles + t - 1) / t);
     };
-    p->gsplits = per_group(env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * kNumCU), &share);
-    p->gblk_reduce = block_tiles(share, "LINFUSION_GROUP_REDUCE_BLK", 8);
-    p->gapply_wgs = per_group(env_int("LINFUSION_GROUP_APPLY_WGS", 8 * kNumCU), &share);
-    p->gblk_apply = block_tiles(share, "LINFUSION_GROUP_APPLY_BLK", 4);
+    // (the defaults are in 256-thread units: a workgroup of eight waves counts twice)
+    const int unit = p->gwaves / lf::kWavesPerWG;
+    p->gsplits = per_group(env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * kNumCU) / unit, &share);
+    p->gblk_reduce = block_tiles(share, "LINFUSION_GROUP_REDUCE_BLK", 2, 1);
+    p->gapply_wgs = per_group(env_int("LINFUSION_GROUP_APPLY_WGS", 2 * kNumCU) / unit, &share);
+    // measured best: one workgroup of eight waves (two of four) per CU, tiles dealt out one at a time so
+    // that the whole chip sweeps one narrow window of memory
+    p->gblk_apply = block_tiles(share, "LINFUSION_GROUP_APPLY_BLK", p->gwaves == 8 ? 1 : 2, 1);
+  } else {
+    p->gsplits = p->gapply_wgs = 0;
+    p->gblk_reduce = p->gblk_apply = lf::kWavesPerWG;
   }
   const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
   const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
@@ -178,6 +187,18 @@ bool fits_resident(KernelT kernel, size_t lds, long long grid) {
     return false;
   }
   return (long long)per_cu * kNumCU >= grid;
+}
+
+// Workgroups may use up to 160 KiB of LDS on this device; above 64 KiB the kernel has to be told once.
+template <typename KernelT>
+bool allow_lds(KernelT kernel, int bytes) {
+  if (bytes <= 65536) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
 }
 
 struct Args {
@@ -256,14 +277,33 @@ int run16(const Args& a) {
   }
   const size_t lds1 = reduce16_lds_bytes<T, D>();
   if (a.ev) (void)hipEventRecord(a.ev[0], st);
+  const int H = a.lkv.H, B = (int)(a.BH / H);
+  const int gpb = H / p.gwaves, rest = H % p.gwaves;   // whole groups of heads, heads left over
+  const HeadSubset all{0, H}, tail{H - rest, rest > 0 ? rest : 1};
   if (a.group_reduce) {
     const dim3 g1(p.gsplits, (unsigned)p.groups);
-#define LF_REDUCE(FM) state_reduce16_hg<T, D, FM><<<g1, blk, lds1, st>>>(K, V, a.lkv, partials, a.N, p.gblk_reduce);
+#define LF_REDUCE_W(FM, WW)                                                                              \
+  {                                                                                                      \
+    constexpr int ldsr = ReduceRowsCfg<T, D, WW>::kLdsBytes;                                             \
+    if (!allow_lds(state_reduce16_rows<T, D, FM, WW>, ldsr)) return LINFUSION_ERR_HIP;                   \
+    state_reduce16_rows<T, D, FM, WW><<<g1, dim3(64 * WW), ldsr, st>>>(K, V, a.lkv, gpb, partials, a.N,  \
+                                                                       p.gblk_reduce);                   \
+  }
+#define LF_REDUCE(FM) if (p.gwaves == 8) LF_REDUCE_W(FM, 8) else LF_REDUCE_W(FM, 4)
     LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
+#undef LF_REDUCE_W
+    if (rest > 0) {   // same number of partials per head, so that one combine serves all heads
+      const dim3 g1t(p.gsplits, (unsigned)(B * rest));
+#define LF_REDUCE(FM) \
+  state_reduce16<T, D, FM><<<g1t, blk, lds1, st>>>(K, V, a.lkv, tail, partials, a.N, p.blk_reduce);
+      LF_SWITCH_FM(LF_REDUCE)
+#undef LF_REDUCE
+    }
   } else {
     const dim3 g1(p.splits, (unsigned)a.BH);
-#define LF_REDUCE(FM) state_reduce16<T, D, FM><<<g1, blk, lds1, st>>>(K, V, a.lkv, partials, a.N, p.blk_reduce);
+#define LF_REDUCE(FM) \
+  state_reduce16<T, D, FM><<<g1, blk, lds1, st>>>(K, V, a.lkv, all, partials, a.N, p.blk_reduce);
     LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
   }
@@ -275,14 +315,28 @@ int run16(const Args& a) {
     const size_t lds2 = apply16_dma_lds_bytes<T, D>();
     if (a.group_apply) {
       const dim3 g2(p.gapply_wgs, (unsigned)p.groups);
-#define LF_APPLY(FM, NORM) \
-  apply16_dma_hg<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, state, a.eps, a.N, p.gblk_apply);
+#define LF_APPLY_W(FM, NORM, WW)                                                                          \
+  {                                                                                                       \
+    constexpr int ldsa = apply16_dma_lds_bytes<T, D>(WW);                                                 \
+    if (!allow_lds(apply16_rows<T, D, FM, NORM, WW>, ldsa)) return LINFUSION_ERR_HIP;                     \
+    apply16_rows<T, D, FM, NORM, WW><<<g2, dim3(64 * WW), ldsa, st>>>(Q, a.lq, O, a.lo, gpb, state, a.eps, \
+                                                                      a.N, p.gblk_apply);                 \
+  }
+#define LF_APPLY(FM, NORM) if (p.gwaves == 8) LF_APPLY_W(FM, NORM, 8) else LF_APPLY_W(FM, NORM, 4)
       LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
+#undef LF_APPLY_W
+      if (rest > 0) {
+        const dim3 g2t(p.apply_wgs, (unsigned)(B * rest));
+#define LF_APPLY(FM, NORM) \
+  apply16_dma<T, D, FM, NORM><<<g2t, blk, lds2, st>>>(Q, a.lq, O, a.lo, tail, state, a.eps, a.N, p.blk_apply);
+        LF_SWITCH_FM_NORM(LF_APPLY)
+#undef LF_APPLY
+      }
     } else {
       const dim3 g2(p.apply_wgs, (unsigned)a.BH);
 #define LF_APPLY(FM, NORM) \
-  apply16_dma<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, state, a.eps, a.N, p.blk_apply);
+  apply16_dma<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, state, a.eps, a.N, p.blk_apply);
       LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
     }
@@ -478,15 +532,15 @@ int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int 
     return LINFUSION_ERR_OVERLAP;
   rc = check_device();
   if (rc != LINFUSION_OK) return rc;
-  // One head per wave pays where the heads of a token are neighbours in memory and a head's row is not
-  // a whole number of 128-byte lines: four waves side by side then cover contiguous row pieces that
+  // The row-piece kernels pay where the heads of a token are neighbours in memory and a head's row is
+  // not a whole number of 128-byte lines: a group of four heads is then moved as contiguous pieces that
   // single heads would touch as scattered fragments.  (Not used by the single-launch kernel, so a
   // forced single launch keeps the one-head-per-workgroup mapping.)
-  auto heads_adjacent = [&](const Strides& s) { return H > 1 && s.h == d && s.n > d; };
+  auto heads_adjacent = [&](const Strides& s) { return p.groups > 0 && s.h == d && s.n > d; };
   const bool frag = dtype != LINFUSION_DTYPE_F32 && (d * esz) % 128 != 0 && !(flags & LINFUSION_FLAG_FORCE_FUSED);
   int group_mode = env_int("LINFUSION_HEAD_GROUPS", 1);   // 2 = off (tuning aid)
   const bool group_reduce = frag && group_mode == 1 && heads_adjacent(lkv);
-  const bool group_apply = frag && group_mode == 1 && (heads_adjacent(lo) || heads_adjacent(lq));
+  const bool group_apply = frag && group_mode == 1 && heads_adjacent(lo) && heads_adjacent(lq);
   Args a{q, k, v, out, (long long)B * H, N, feature_map, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
          &p, (unsigned char*)workspace, nullptr, (hipStream_t)stream, ev,
          device_layout(lq, H, esz), device_layout(lkv, H, esz), device_layout(lo, H, esz), group_reduce, group_apply};

@@ -47,7 +47,8 @@ def test_workspace_bytes_is_a_pure_function_of_the_shape():
     assert a == lf.linfusion_attn_workspace_bytes(1, 8, 2097152, 40, lf.DTYPE_F16) and a > 0
     plan = lf.linfusion_attn_plan(1, 8, 2097152, 40, lf.DTYPE_F16)
     need = 8 * (plan["reduce_wgs_per_head"] + 1) * (40 * 40 + 40) * 4
-    assert need <= a <= 2 * need + 4096      # room for the single-launch path's larger split count
+    # room for the launch shapes with more partials per head (single launch, grouped heads of strided layouts)
+    assert need <= a <= 8 * need
     # rejected arguments need no workspace
     assert lf.linfusion_attn_workspace_bytes(1, 8, 1024, 12, lf.DTYPE_F16) == 0
     assert lf.linfusion_attn_workspace_bytes(0, 8, 1024, 40, lf.DTYPE_F16) == 0

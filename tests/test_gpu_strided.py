@@ -33,8 +33,10 @@ def _dt(t):
 SHAPES = [
     (2, 3, 33, 40, "f16"), (1, 8, 1000, 40, "f16"), (2, 2, 4099, 64, "f16"), (1, 3, 515, 24, "f16"),
     (1, 2, 300, 32, "f16"), (1, 5, 77, 8, "f16"), (2, 5, 1000, 40, "f16"), (1, 1, 100, 40, "f16"),
-    (1, 9, 2500, 56, "f16"), (3, 6, 130, 16, "f16"),
+    (1, 9, 2500, 56, "f16"), (3, 6, 130, 16, "f16"), (1, 8, 777, 56, "f16"), (1, 12, 600, 40, "f16"),
+    (2, 8, 95, 8, "f16"), (1, 16, 1030, 48, "f16"), (1, 8, 400, 32, "f16"),
     (2, 2, 33, 40, "bf16"), (1, 3, 4099, 64, "bf16"), (1, 2, 300, 48, "bf16"), (2, 7, 900, 40, "bf16"),
+    (2, 16, 300, 24, "bf16"), (1, 8, 2100, 40, "bf16"), (1, 8, 260, 56, "bf16"),
     (1, 2, 17, 64, "f32"), (2, 2, 1000, 40, "f32"), (1, 3, 2051, 56, "f32"),
 ]
 
