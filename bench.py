@@ -217,7 +217,8 @@ def main():
                 "unit": "GB/s", "frac": dom["gbps"] / HBM_PEAK_GBPS, "traffic": None,
                 "avg_launch_ms": dom["ms"], "kernels": kernels}
     # HBM bytes per launch from the committed rocprofv3 --pmc summary of this workload, if there is one
-    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
+    tname = args.workload + ("_token_major" if args.layout == "token_major" else "")
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{tname}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             tr = json.load(f)

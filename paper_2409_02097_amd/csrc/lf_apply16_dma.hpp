@@ -112,6 +112,9 @@ struct ApplyDma {
   // LDS position p = 64 u + lane of a slot holds the chunk of token row trow[u] that lies qoff[u]
   // (in Q) / ooff[u] (in out) vector units after the tile's first row
   int trow[NL], qoff[NL], ooff[NL];
+  // ROWS: stores go out in memory order (whole 128-byte lines per instruction); lane (u, l) then fetches its
+  // chunk from byte soff[u] of the wave's slot region
+  int soff[ROWS ? NL : 1];
   TileIter it, ahead;
   u32x4 A[NSplit<T>::value][Shape16<D>::kMT2][Shape16<D>::kKS];   // this wave's state operands
   float c1, eps_s;
@@ -136,7 +139,11 @@ struct ApplyDma {
         if (c < 0) c += PC;
         trow[u] = r;
         qoff[u] = r * rs_q + c;
-        ooff[u] = r * rs_o + c;
+        const int cs = P % PC;               // store side: this lane takes chunk cs of row r ...
+        int pos = cs + rot(r);               // ... which sits at this rotated position of the row piece
+        if (pos >= PC) pos -= PC;
+        ooff[u] = r * rs_o + cs;
+        soff[u] = ((r % RPR) * PC + pos) * 16;
       }
     } else {
       row_byte = tok * Cfg::kRowBytes;
@@ -410,7 +417,9 @@ struct ApplyDma {
     u32x4* op = Oh + tile * kTile * rs_o;
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
-      const u32x4 w = *reinterpret_cast<const u32x4*>(sl + u * 1024 + lane * 16);
+      int from = u * 1024 + lane * 16;
+      if constexpr (ROWS) from = soff[u];
+      const u32x4 w = *reinterpret_cast<const u32x4*>(sl + from);
       if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) st_stream(op + ooff[u], w);
     }
   }
