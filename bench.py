@@ -200,7 +200,10 @@ def main():
     kms = [a / max(args.profile_steps, 1) for a in acc]
     rname, aname = {"f16": ("state_reduce16<F16", "apply16_dma<F16"), "bf16": ("state_reduce16<BF16", "apply16_dma<BF16"),
                     "f32": ("state_reduce32", "apply32")}[dtype]
-    if args.layout == "token_major" and dtype != "f32" and (d * 2) % 128 != 0 and H >= 4:
+    if d > 64:
+        rname = rname.replace("state_reduce16<", "state_reduce16_wide<")
+        aname = aname.replace("apply16_dma<", "apply16_wide<")
+    elif args.layout == "token_major" and dtype != "f32" and (d * 2) % 128 != 0 and H >= 4:
         # heads adjacent in memory and rows that are not whole 128-byte lines: the row-piece kernels run
         rname = rname.replace("state_reduce16<", "state_reduce16_rows<")
         aname = aname.replace("apply16_dma<", "apply16_rows<")

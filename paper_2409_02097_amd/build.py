@@ -11,11 +11,12 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "linfusion.hip")
+SRCS = [os.path.join(HERE, "csrc", "linfusion.hip"), os.path.join(HERE, "csrc", "linfusion_wide.hip")]
 LIB = os.path.join(HERE, "liblinfusion.so")
+OBJ_DIR = os.path.join(HERE, "_build")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",
 ]
@@ -28,17 +29,37 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found: the library is built with ROCm's hipcc for gfx950")
 
 
-def build(verbose: bool = False, extra: list[str] | None = None) -> str:
-    cmd = [hipcc_path(), *HIPCC_FLAGS, *(extra or []), "-I", os.path.join(ROOT, "include"), SRC, "-o", LIB + ".tmp"]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, capture_output=True, text=True)
+def _filtered(stderr: str) -> str:
     noise = "is not a recognized feature for this target"
-    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    return "\n".join(l for l in stderr.splitlines() if noise not in l)
+
+
+def build(verbose: bool = False, extra: list[str] | None = None) -> str:
+    """Compiles the translation units side by side, then links them into the shared library."""
+    hipcc = hipcc_path()
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    procs = []
+    for src in SRCS:
+        obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+        cmd = [hipcc, *HIPCC_FLAGS, *(extra or []), "-I", os.path.join(ROOT, "include"), "-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)))
+    objs = []
+    for obj, pr in procs:
+        _, err = pr.communicate()
+        err = _filtered(err)
+        if pr.returncode != 0:
+            raise RuntimeError(f"hipcc failed ({pr.returncode}):\n{err}")
+        if verbose and err.strip():
+            print(err, flush=True)
+        objs.append(obj)
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB + ".tmp"]
+    if verbose:
+        print(" ".join(link), flush=True)
+    res = subprocess.run(link, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError(f"hipcc failed ({res.returncode}):\n{err}")
-    if verbose and err.strip():
-        print(err, flush=True)
+        raise RuntimeError(f"link failed ({res.returncode}):\n{_filtered(res.stderr)}")
     os.replace(LIB + ".tmp", LIB)
     return LIB
 

@@ -453,7 +453,9 @@ LF_DEV void combine_slice(const float* __restrict__ head_partials, int splits, i
              ((part[el] + part[kCombineElems + el]) + part[2 * kCombineElems + el]) + part[3 * kCombineElems + el]);
 }
 
-// grid = (ceil(NE / 64), B*H), block = 256, NE = d*d + d
+// grid = (ceil(NE / 64), B*H), block = 256, NE = d*d + d.  (A template only so that the two translation
+// units of the library may both hold it.)
+template <int kUnused>
 __global__ void __launch_bounds__(kCombineThreads)
 combine_state(const float* __restrict__ partials, int splits, int NE, float* __restrict__ state) {
   __shared__ float part[4 * kCombineElems];

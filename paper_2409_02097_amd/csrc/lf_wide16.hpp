@@ -1,0 +1,470 @@
+// fp16 / bf16 kernels for head widths above 64 (d a multiple of 16 up to 160: the deeper levels of the
+// SD-v1.5 UNet have d = 80 and d = 160).  Same mathematics as the narrow kernels (Prop. 2's g'(X)^T X state,
+// Eq. 5's normalizer), other work split: the d x d fp32 state no longer fits one wave's accumulators, so
+// the four waves of a workgroup share every 32-token tile and split the state between them --
+//   state_reduce16_wide  by columns (value channels): wave w accumulates the 16-column blocks b = w mod 4;
+//   apply16_wide         by output channels: wave w produces channels [w d/4, (w+1) d/4) of every token.
+// Both move tiles as whole workgroups (coalesced over full token rows) and synchronise with workgroup
+// barriers; both address memory through Layout, so every layout of the strided entry point works.
+#pragma once
+#include "lf_apply16_dma.hpp"
+
+namespace lf {
+
+template <int D> struct ShapeWide {
+  static_assert(D % 16 == 0 && D > 64 && D <= 160, "wide kernels: head width a multiple of 16 in (64, 160]");
+  static constexpr int kCPR = D / 8;                  // 16-byte chunks per token row
+  static constexpr int kMT = D / 16;                  // 16-wide blocks across d
+  static constexpr int kRS = D + 8;                   // LDS row stride of the reduction tiles (bank spread)
+  static constexpr int kTileElems = kTile * kRS;
+  static constexpr int kChunks = kTile * kCPR;        // chunks per tile
+  static constexpr int kNLR = (kChunks + kThreads - 1) / kThreads;   // reduction: loads per thread per tensor
+  static constexpr int kNBW = (kMT + kWavesPerWG - 1) / kWavesPerWG; // column blocks per wave (at most)
+  // apply
+  static constexpr int kDQ = D / kWavesPerWG;         // output channels per wave
+  static constexpr int kHalf = kDQ / 2;               // ... per half-wave
+  static constexpr int kMT2 = (kHalf + 2 + 15) / 16;  // 32-row output tiles incl. the two normalizer rows
+  static constexpr int kKS = D / 16;                  // contraction steps of 16 channels
+  static constexpr int kRPR = kTile / kWavesPerWG;    // token rows per wave region
+  static constexpr int kRegionChunks = kRPR * kCPR;
+  static constexpr int kNLA = (kRegionChunks + 63) / 64;   // apply: copies / stores per wave per tile
+  static constexpr int kRegionBytes = kNLA * 1024;
+  static constexpr int kRing = 3;
+  static constexpr int kSlotBytes = kWavesPerWG * kRegionBytes;
+  static constexpr int kStageOffset = (kRing - 1) * kSlotBytes;   // 16 rows of S during the prologue
+  static_assert(16 * D * 4 <= kSlotBytes, "a 16-row block of the state must fit one slot");
+  // rotation of the chunks inside a token row that makes token-per-lane accesses bank-conflict free
+  static constexpr int kG = (kCPR % 16 == 0) ? 16 : ((kCPR % 8 == 0) ? 8 : ((kCPR % 4 == 0) ? 4 : 2));
+  static_assert(kCPR % 2 == 0 && kRPR * kG >= 16, "rotation classes must fit a region");
+  static __device__ __forceinline__ int rot(int r) { return ((r * kG) >> 4) & (kG - 1); }
+};
+
+template <typename T, int D>
+constexpr int reduce16_wide_lds_bytes() {
+  return 2 * (NSplit<T>::value + 1) * ShapeWide<D>::kTileElems * 2;   // double-buffered phi(K) levels + V
+}
+template <int D>
+constexpr int apply16_wide_lds_bytes() { return ShapeWide<D>::kRing * ShapeWide<D>::kSlotBytes; }
+
+// ==========================================================================================
+// State reduction.  grid = (splits, heads), block = 256.  Workgroup x walks blocks of tiles_per_block
+// consecutive tiles (x, x + splits, ...; every wave visits every tile).  Per tile: all threads load K and V
+// rows (coalesced), apply phi to K, write 16-bit operands into the LDS tiles of the current buffer; barrier;
+// every wave reads all phi(K) operand blocks (transposing LDS reads) and the V blocks of its own columns
+// and accumulates S[:, its columns]; z rows a = w mod 4 through a ones operand.  Two LDS buffers: the next
+// tile is written while slower waves still multiply the previous one, one barrier per tile.
+// Partial: S as [D][D] row-major then z, fp32; each wave writes its own columns.
+// ==========================================================================================
+template <typename T, int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, HeadSubset hs,
+                    float* __restrict__ partials, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using Sw = ShapeWide<D>;
+  constexpr int NS = NSplit<T>::value, RS = Sw::kRS, NL = Sw::kNLR, CPR = Sw::kCPR, MT = Sw::kMT, NBW = Sw::kNBW;
+  constexpr int TE = Sw::kTileElems, BUF = (NS + 1) * TE;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long bh = hs.bh(blockIdx.y, kv.H);
+  const long long off = kv.slice(bh);
+  const u32x4* Kh = K + off;
+  const u32x4* Vh = V + off;
+  const int rs = kv.row;
+  uint16_t* lds = reinterpret_cast<uint16_t*>(smem);
+
+  int goff[NL], loff[NL], trow[NL];
+#pragma unroll
+  for (int u = 0; u < NL; ++u) {
+    const int p = u * kThreads + tid;
+    const int r = p / CPR, c = p % CPR;
+    const bool in = p < Sw::kChunks;
+    trow[u] = in ? r : kTile;              // kTile: never below the row limit
+    goff[u] = r * rs + c;
+    loff[u] = in ? r * RS + c * 8 : 0;
+  }
+  const int j16 = lane & 15, g4 = lane >> 4;
+  const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
+
+  const long long n_tiles = (N + kTile - 1) / kTile;
+  TileIter it(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);
+
+  f32x4 acc[MT][NBW];
+  f32x4 accz[NBW];
+#pragma unroll
+  for (int i = 0; i < NBW; ++i) {
+    accz[i] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int a = 0; a < MT; ++a) acc[a][i] = f32x4{0, 0, 0, 0};
+  }
+  const uint32_t one2 = (uint32_t)OneBits<T>::value * 0x10001u;
+  const u32x4 ones = {one2, one2, one2, one2};
+
+  u32x4 kr[NL], vr[NL];
+  auto issue_loads = [&](long long tile) {
+    long long rem = N - tile * kTile;
+    int lim = rem < kTile ? (int)rem : kTile;
+    const u32x4* kp = Kh + tile * kTile * rs;
+    const u32x4* vp = Vh + tile * kTile * rs;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      if (trow[u] < lim) {
+        kr[u] = ld_stream(kp + goff[u]);
+        vr[u] = ld_stream(vp + goff[u]);
+      } else {
+        kr[u] = u32x4{0, 0, 0, 0};
+        vr[u] = u32x4{0, 0, 0, 0};
+      }
+    }
+    return lim;
+  };
+
+  int lim = 0;
+  if (it.valid()) lim = issue_loads(it.t);
+  for (int i = tid; i < 2 * BUF; i += kThreads) lds[i] = 0;   // pad columns stay zero
+  __syncthreads();
+
+  int buf = 0;
+  while (it.valid()) {
+    uint16_t* bufp = lds + buf * BUF;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      if (u * kThreads + tid < Sw::kChunks) {
+        const bool ok = trow[u] < lim;
+        u32x4 ph, pl;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1;
+          unpack2<T>(kr[u][w], x0, x1);
+          float p0 = ok ? phi<FM>(x0) : 0.0f;
+          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          if constexpr (NS == 1) {
+            ph[w] = pack2<T>(p0, p1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(p0, p1, h, l);
+            ph[w] = h;
+            pl[w] = l;
+          }
+        }
+        *reinterpret_cast<u32x4*>(bufp + loff[u]) = ph;
+        if constexpr (NS == 2) *reinterpret_cast<u32x4*>(bufp + TE + loff[u]) = pl;
+        *reinterpret_cast<u32x4*>(bufp + NS * TE + loff[u]) = vr[u];
+      }
+    }
+    it.next();
+    int next_lim = 0;
+    if (it.valid()) next_lim = issue_loads(it.t);
+    __syncthreads();   // the tile is complete in this buffer; the other buffer is free to be rewritten
+
+    const uint16_t* ldsV = bufp + NS * TE;
+    u32x4 bfrag[NBW];
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+      const int b = wave + kWavesPerWG * i;
+      bfrag[i] = u32x4{0, 0, 0, 0};
+      if (b < MT) {
+        u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * b);
+        u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * b);
+        bfrag[i] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        u32x2 r0 = lds_read_tr16(bufp + s * TE + tr_base + 16 * a);
+        u32x2 r1 = lds_read_tr16(bufp + s * TE + tr_base + 4 * RS + 16 * a);
+        u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+        for (int i = 0; i < NBW; ++i)
+          if (wave + kWavesPerWG * i < MT) acc[a][i] = mfma_16x16x32<T>(afrag, bfrag[i], acc[a][i]);
+        if (a % kWavesPerWG == wave) accz[a / kWavesPerWG] = mfma_16x16x32<T>(afrag, ones, accz[a / kWavesPerWG]);
+      }
+    }
+    buf ^= 1;
+    lim = next_lim;
+  }
+
+  // ---- each wave writes its columns of the partial (lane: rows 4 (l / 16) + i, column l % 16 of a block) ----
+  float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = a * 16 + 4 * g4 + i;
+#pragma unroll
+      for (int c = 0; c < NBW; ++c) {
+        const int b = wave + kWavesPerWG * c;
+        if (b < MT) st_agent(dst + row * D + b * 16 + j16, acc[a][c][i]);
+      }
+      if (a % kWavesPerWG == wave && j16 == 0) st_agent(dst + D * D + row, accz[a / kWavesPerWG][i]);
+    }
+  }
+}
+
+// ==========================================================================================
+// Apply + normalize.  grid = (wgs, heads), block = 256.  The LDS-DMA ring of apply16_dma with workgroup-wide
+// slots: wave w copies in (and later stores) token rows 8w..8w+7 of a tile, whole rows.  Every wave reads the
+// whole tile as matrix-core B operands (phi applied in registers), then -- after a barrier, since all waves
+// read all channels -- overwrites its own d/4 output channels of every token in place.  Per wave the
+// products are those of apply16_dma for a head whose state has only this wave's d/4 columns (plus the two
+// normalizer rows, which every wave carries).  Pipelined as the row-piece kernel: store tile j-1, copy tile
+// j+2, read tile j, barrier, compute and write back, wait for own rows of tile j+1, barrier.
+// The prologue cannot stage the whole fp32 state in LDS (103 KB at d = 160): a first pass over the state in
+// global memory finds the maxima that fix the power-of-two scales, then the state is staged 16 rows (one
+// contraction step) at a time and each wave builds that step's A operands.
+// ==========================================================================================
+template <typename T, int D, int FM, bool NORM>
+struct ApplyWide {
+  using Sw = ShapeWide<D>;
+  static constexpr int NS = NSplit<T>::value;
+  static constexpr int CPR = Sw::kCPR, KS = Sw::kKS, MT2 = Sw::kMT2, HALF = Sw::kHalf, DQ = Sw::kDQ;
+  static constexpr int NL = Sw::kNLA, NE = D * D + D, R = Sw::kRing, RPR = Sw::kRPR;
+  static_assert(R == 3, "the wait counts below are written for a ring of three slots");
+
+  const u32x4* Qh;
+  u32x4* Oh;
+  long long N;
+  unsigned char* smem;
+  int rs_q, rs_o;
+  int lane, wave, tok, kg, row_byte, trot;
+  int trow[NL], qoff[NL], ooff[NL], soff[NL];
+  TileIter it, ahead;
+  u32x4 A[NS][MT2][KS];
+  float c1, eps_s;
+
+  LF_DEV ApplyWide(const u32x4* Qh_, int rs_q_, u32x4* Oh_, int rs_o_, long long N_, int tiles_per_block, int wg,
+                   int nwg, unsigned char* smem_)
+      : Qh(Qh_), Oh(Oh_), N(N_), smem(smem_), rs_q(rs_q_), rs_o(rs_o_),
+        lane(threadIdx.x & 63), wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
+        it(wg, nwg, 0, tiles_per_block, (N_ + kTile - 1) / kTile, 1), ahead(it) {
+    tok = lane & 31;
+    kg = lane >> 5;
+    row_byte = (tok / RPR) * Sw::kRegionBytes + (tok % RPR) * CPR * 16;
+    trot = Sw::rot(tok);
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const int P = wave * Sw::kRegionChunks + u * 64 + lane;   // position in the tile
+      const int r = P / CPR, pos = P % CPR;
+      int c = pos - Sw::rot(r);                // copy side: position pos of row r receives chunk c
+      if (c < 0) c += CPR;
+      int spos = pos + Sw::rot(r);             // store side: this lane sends chunk pos, found at spos
+      if (spos >= CPR) spos -= CPR;
+      trow[u] = r;
+      qoff[u] = r * rs_q + c;
+      ooff[u] = r * rs_o + pos;
+      soff[u] = ((r % RPR) * CPR + spos) * 16;
+    }
+  }
+
+  LF_DEV unsigned char* region_ptr(int slot) const { return smem + slot * Sw::kSlotBytes + wave * Sw::kRegionBytes; }
+  // where this lane finds 16-byte chunk `chunk` of its token's row in slot `slot`
+  LF_DEV unsigned char* chunk_ptr(int slot, int chunk) const {
+    int x = chunk + trot;
+    if (x >= CPR) x -= CPR;
+    return smem + slot * Sw::kSlotBytes + row_byte + (x << 4);
+  }
+
+  // always issues exactly NL vector memory instructions
+  LF_DEV void issue_copy(long long tile, int slot) {
+    long long rem = N - tile * kTile;
+    const int lim = rem < kTile ? (int)rem : kTile;
+    const u32x4* qp = Qh + tile * kTile * rs_q;
+    unsigned char* sl = region_ptr(slot);
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      if (u * 64 + lane < Sw::kRegionChunks) {
+        const int c = trow[u] < lim ? qoff[u] : 0;   // rows past N re-read chunk 0; never stored
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
+                                         (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
+      }
+    }
+  }
+
+  LF_DEV void prefetch() {
+    if (ahead.valid()) issue_copy(ahead.t, 0);
+    ahead.next();
+    if (ahead.valid()) issue_copy(ahead.t, 1);
+    ahead.next();
+  }
+
+  // `state`: this head's [D*D + D] fp32 state; `zst`, `redmax`: D + 16 and 8 floats of LDS outside the ring
+  LF_DEV void load_state(const float* state, float eps, float* zst, float* redmax) {
+    float mS = 0.0f, mz = 0.0f;
+    for (int e = threadIdx.x; e < NE; e += kThreads) {
+      const float x = ld_agent(state + e);
+      if (e < D * D) mS = fmaxf(mS, fabsf(x));
+      else { mz = fmaxf(mz, fabsf(x)); zst[e - D * D] = x; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      mS = fmaxf(mS, __shfl_xor(mS, o));
+      mz = fmaxf(mz, __shfl_xor(mz, o));
+    }
+    if (lane == 0) { redmax[wave] = mS; redmax[kWavesPerWG + wave] = mz; }
+    __syncthreads();
+    mS = 0.0f; mz = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerWG; ++w) { mS = fmaxf(mS, redmax[w]); mz = fmaxf(mz, redmax[kWavesPerWG + w]); }
+    const float aS = pow2_scale_for(mS);
+    const float az = NORM ? pow2_scale_for(mz) : 1.0f;
+    c1 = az / aS;
+    eps_s = eps * az;
+
+    float* st = reinterpret_cast<float*>(smem + Sw::kStageOffset);
+    const int m = lane & 31;
+    const int hv = (m >> 2) & 1;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      for (int e = threadIdx.x; e < 16 * D; e += kThreads) st[e] = ld_agent(state + s * 16 * D + e);
+      __syncthreads();
+#pragma unroll
+      for (int t = 0; t < MT2; ++t) {
+        const int slot = 16 * t + 4 * (m >> 3) + (m & 3);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float hi2[2], lo2[2];
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int chl = 8 * kg + 2 * w + q;      // row inside the staged 16-row block
+            float x = 0.0f;
+            bool zrem = false;
+            if (slot < HALF) x = st[chl * D + wave * DQ + hv * HALF + slot] * aS;
+            else if (NORM && slot == HALF) x = zst[s * 16 + chl] * az;
+            else if (NORM && slot == HALF + 1) { x = zst[s * 16 + chl] * az; zrem = true; }
+            float r0, r1;
+            unpack2<T>(pack2<T>(x, 0.0f), r0, r1);   // x rounded once to 16 bits
+            hi2[q] = zrem ? x - r0 : x;
+            lo2[q] = (slot < HALF) ? x - r0 : 0.0f;
+          }
+          A[0][t][s][w] = pack2<T>(hi2[0], hi2[1]);
+          if constexpr (NS == 2) A[1][t][s][w] = pack2<T>(lo2[0], lo2[1]);
+        }
+      }
+      __syncthreads();
+    }
+  }
+
+  LF_DEV void store_tile(long long tile, int slot) {
+    const unsigned char* sl = region_ptr(slot);
+    long long rem = N - tile * kTile;
+    const int lim = rem < kTile ? (int)rem : kTile;
+    u32x4* op = Oh + tile * kTile * rs_o;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(sl + soff[u]);
+      if (u * 64 + lane < Sw::kRegionChunks && trow[u] < lim) st_stream(op + ooff[u], w);
+    }
+  }
+
+  // Issue order per wave:  C0 C1 [state] | C2 K0 w | S0 C3 K1 w | S1 C4 K2 w | ...  : after tile j+1's copies
+  // come S(j-1) and C(j+2), where they exist.
+  LF_DEV void stream() {
+    {
+      TileIter second = it;
+      second.next();
+      if (second.valid()) wait_vmcnt<NL>();
+      else wait_vmcnt<0>();
+    }
+    __syncthreads();
+    int slot = 0, prev_slot = 0;
+    long long prev_tile = -1;
+    while (it.valid()) {
+      const long long tile = it.t;
+      const bool have_prev = prev_tile >= 0;
+      if (have_prev) store_tile(prev_tile, prev_slot);
+      const bool copied = ahead.valid();
+      if (copied) issue_copy(ahead.t, have_prev ? prev_slot : R - 1);
+
+      // ---- the whole row of this lane's token -> phi -> 16-bit B operands ---------------------------
+      u32x4 Bh[KS], Bl[NS == 2 ? KS : 1];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, 2 * s + kg));
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1;
+          unpack2<T>(raw[w], x0, x1);
+          const float r0 = phi<FM>(x0), r1 = phi<FM>(x1);
+          if constexpr (NS == 1) {
+            Bh[s][w] = pack2<T>(r0, r1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(r0, r1, h, l);
+            Bh[s][w] = h;
+            Bl[s][w] = l;
+          }
+        }
+      }
+      __syncthreads();   // every wave holds its operands: the tile may be overwritten
+
+      f32x16 acc[MT2];
+#pragma unroll
+      for (int t = 0; t < MT2; ++t) {
+        acc[t] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          acc[t] = mfma_32x32x16<T>(A[0][t][s], Bh[s], acc[t]);
+          if constexpr (NS == 2) {
+            acc[t] = mfma_32x32x16<T>(A[0][t][s], Bl[s], acc[t]);
+            if (16 * t < HALF) acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);
+          }
+        }
+      }
+      float scale = c1;
+      if constexpr (NORM) {
+        const float den = acc[HALF / 16][HALF % 16] + acc[(HALF + 1) / 16][(HALF + 1) % 16] + eps_s;
+        scale = c1 * __builtin_amdgcn_rcpf(den);
+      }
+      // ---- this lane's d/8 channels (wave quarter, half kg) -> 16 bits -> back into the row, in pieces
+      //      that stay inside one 16-byte chunk -----------------------------------------------------------
+      constexpr int PB = (HALF % 8 == 0) ? 16 : ((HALF % 4 == 0) ? 8 : 4);   // piece bytes
+      const int byte0 = (wave * DQ + kg * HALF) * 2;
+#pragma unroll
+      for (int c = 0; c < HALF * 2 / PB; ++c) {
+        uint32_t w[PB / 4];
+#pragma unroll
+        for (int e = 0; e < PB / 4; ++e) {
+          const int s0 = c * (PB / 2) + 2 * e;
+          w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
+        }
+        const int byte = byte0 + c * PB;
+        unsigned char* p = chunk_ptr(slot, byte >> 4) + (byte & 15);
+        if constexpr (PB == 16) *reinterpret_cast<u32x4*>(p) = u32x4{w[0], w[1], w[2], w[3]};
+        else if constexpr (PB == 8) *reinterpret_cast<u32x2*>(p) = u32x2{w[0], w[1]};
+        else *reinterpret_cast<uint32_t*>(p) = w[0];
+      }
+
+      it.next();
+      ahead.next();
+      if (it.valid()) {
+        if (have_prev && copied) wait_vmcnt<2 * NL>();
+        else if (have_prev || copied) wait_vmcnt<NL>();
+        else wait_vmcnt<0>();
+      }
+      __syncthreads();   // tile j is finished by all waves; tile j+1 has landed for all
+      prev_tile = tile;
+      prev_slot = slot;
+      slot = slot + 1 == R ? 0 : slot + 1;
+    }
+    if (prev_tile >= 0) store_tile(prev_tile, prev_slot);
+  }
+};
+
+template <typename T, int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+apply16_wide(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, HeadSubset hs,
+             const float* __restrict__ state, float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ float zst[D + 16];
+  __shared__ float redmax[2 * kWavesPerWG];
+  const long long bh = hs.bh(blockIdx.y, lq.H);
+  ApplyWide<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
+                               gridDim.x, smem);
+  ap.prefetch();
+  ap.load_state(state + bh * (D * D + D), eps, zst, redmax);
+  ap.stream();
+}
+
+}  // namespace lf

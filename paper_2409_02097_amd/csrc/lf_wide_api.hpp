@@ -1,0 +1,30 @@
+// Host-side interface between the two translation units of the library: linfusion.hip (boundary, planning,
+// head widths up to 64) and linfusion_wide.hip (the kernels for head widths above 64).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "lf_common.hpp"
+
+namespace lfw {
+
+struct WideArgs {
+  const void *q, *k, *v;
+  void* out;                  // null: stop after the combine (state only)
+  int B, H;
+  long long N;
+  int d, dtype, fm;           // dtype: LINFUSION_DTYPE_F16 or _BF16
+  float eps;
+  bool unnorm;
+  lf::Layout lq, lkv, lo;
+  float *partials, *state;    // [B*H][splits][d*d + d] and [B*H][d*d + d], fp32
+  int splits, blk_reduce, apply_wgs, blk_apply;
+  hipStream_t st;
+  hipEvent_t* ev;             // null, or four events: before reduce, after it, after combine, after apply
+};
+
+// head widths the wide kernels are built for
+bool wide_supported(int d);
+// enqueues state reduction, combine and (if out) apply; returns LINFUSION_OK or a LINFUSION_ERR_* code
+int run_wide(const WideArgs& a);
+
+}  // namespace lfw

@@ -13,6 +13,7 @@
 #include <mutex>
 
 #include "lf_fused.hpp"
+#include "lf_wide_api.hpp"
 
 namespace {
 
@@ -53,7 +54,11 @@ int block_tiles(long long share, const char* env, int dflt, int multiple = lf::k
   return (int)((b + multiple - 1) / multiple * multiple);
 }
 
-bool supported_d(int d) { return d >= 8 && d <= 64 && d % 8 == 0; }
+// head widths up to 64 in steps of 8 for every dtype; above that the 16-bit wide kernels' widths
+bool supported_d(int d, int dtype) {
+  if (d >= 8 && d <= 64 && d % 8 == 0) return true;
+  return dtype != LINFUSION_DTYPE_F32 && lfw::wide_supported(d);
+}
 
 // Workgroups of the fused kernel that fit one CU at once (registers and LDS of the largest phase);
 // conservative figures, re-checked against the runtime's occupancy query before each fused launch.
@@ -70,11 +75,38 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     return LINFUSION_ERR_INVALID;
   if ((flags & LINFUSION_FLAG_FORCE_SPLIT) && (flags & LINFUSION_FLAG_FORCE_FUSED)) return LINFUSION_ERR_INVALID;
   if (dtype < 0 || dtype > 2) return LINFUSION_ERR_UNSUPPORTED;
-  if (!supported_d(d)) return LINFUSION_ERR_UNSUPPORTED;
+  if (!supported_d(d, dtype)) return LINFUSION_ERR_UNSUPPORTED;
   if (N > (1LL << 40) / d) return LINFUSION_ERR_INVALID;
   const long long BH = (long long)B * H;
   const int tile = dtype == LINFUSION_DTYPE_F32 ? lf::kTile32 : lf::kTile;
   p->n_tiles = (N + tile - 1) / tile;
+  if (d > 64) {
+    // wide kernels: every wave of a workgroup visits every tile of its blocks; three-kernel path only
+    auto per_head = [&](int want_total, int blk_dflt, const char* env_blk, int* blk) {
+      long long s = (want_total + BH - 1) / BH;
+      if (s > p->n_tiles) s = p->n_tiles;
+      if (s < 1) s = 1;
+      const long long t = (p->n_tiles + s - 1) / s;
+      *blk = block_tiles(t, env_blk, blk_dflt, 1);
+      return (int)((p->n_tiles + t - 1) / t);
+    };
+    p->splits = per_head(env_int("LINFUSION_WIDE_REDUCE_WGS", 2 * kNumCU), 4, "LINFUSION_WIDE_REDUCE_BLK", &p->blk_reduce);
+    p->apply_wgs = per_head(env_int("LINFUSION_WIDE_APPLY_WGS", 2 * kNumCU), 1, "LINFUSION_WIDE_APPLY_BLK", &p->blk_apply);
+    p->fsplits = 0;
+    p->fblk_reduce = p->fblk_apply = 1;
+    p->gwaves = lf::kWavesPerWG;
+    p->groups = p->gsplits = p->gapply_wgs = 0;
+    p->gblk_reduce = p->gblk_apply = 1;
+    p->path = 0;
+    if (flags & LINFUSION_FLAG_FORCE_FUSED) return LINFUSION_ERR_UNSUPPORTED;
+    p->state_floats = (size_t)d * d + d;
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    p->ws_partials = up((size_t)BH * p->splits * p->state_floats * sizeof(float));
+    p->ws_state = up((size_t)BH * p->state_floats * sizeof(float));
+    p->ws_sync = up(2 * sizeof(unsigned) + 16);
+    p->ws_total = p->ws_partials + p->ws_state + p->ws_sync;
+    return LINFUSION_OK;
+  }
   const long long max_s = (p->n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;   // >= one tile per wave
   auto per_head = [&](int want_total, long long* share) {
     long long s = (want_total + BH - 1) / BH;
@@ -308,7 +340,7 @@ int run16(const Args& a) {
 #undef LF_REDUCE
   }
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
-  combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
+  combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
       partials, a.group_reduce ? p.gsplits : p.splits, NE, state);
   if (a.ev) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
@@ -385,7 +417,7 @@ int run32(const Args& a) {
   LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
-  combine_state<<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
+  combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
       partials, p.splits, NE, state);
   if (a.ev) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
@@ -399,6 +431,14 @@ int run32(const Args& a) {
 }
 
 int dispatch(int d, int dtype, const Args& a) {
+  if (d > 64) {
+    const Plan& p = *a.p;
+    lfw::WideArgs w{a.q, a.k, a.v, a.out, (int)(a.BH / a.lkv.H), a.lkv.H, a.N, d, dtype, a.fm, a.eps, a.unnorm,
+                    a.lq, a.lkv, a.lo, reinterpret_cast<float*>(a.ws),
+                    a.state_out ? a.state_out : reinterpret_cast<float*>(a.ws + p.ws_partials),
+                    p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, a.st, a.ev};
+    return lfw::run_wide(w);
+  }
   switch (dtype) {
     case LINFUSION_DTYPE_F16:
       switch (d) {

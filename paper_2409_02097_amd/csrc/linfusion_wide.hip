@@ -1,0 +1,96 @@
+// Second translation unit of the library: launches of the kernels for head widths above 64
+// (lf_wide16.hpp).  Kept apart from linfusion.hip so that the two compile side by side.
+#include "../../include/linfusion.h"
+
+#include "lf_wide16.hpp"
+#include "lf_wide_api.hpp"
+
+namespace lfw {
+
+namespace {
+
+template <typename KernelT>
+bool allow_lds(KernelT kernel, int bytes) {
+  if (bytes <= 65536) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
+
+template <typename T, int D>
+int run(const WideArgs& a) {
+  using namespace lf;
+  constexpr int NE = D * D + D;
+  const long long BH = (long long)a.B * a.H;
+  const dim3 blk(kThreads);
+  const u32x4* K = (const u32x4*)a.k;
+  const u32x4* V = (const u32x4*)a.v;
+  const u32x4* Q = (const u32x4*)a.q;
+  u32x4* O = (u32x4*)a.out;
+  const HeadSubset all{0, a.H};
+  hipStream_t st = a.st;
+  constexpr int lds1 = reduce16_wide_lds_bytes<T, D>();
+  const dim3 g1(a.splits, (unsigned)BH);
+  if (a.ev) (void)hipEventRecord(a.ev[0], st);
+#define LFW_REDUCE(FM)                                                                       \
+  {                                                                                          \
+    if (!allow_lds(state_reduce16_wide<T, D, FM>, lds1)) return LINFUSION_ERR_HIP;           \
+    state_reduce16_wide<T, D, FM><<<g1, blk, lds1, st>>>(K, V, a.lkv, all, a.partials, a.N, a.blk_reduce); \
+  }
+  switch (a.fm) {
+    case 0: LFW_REDUCE(0) break;
+    case 1: LFW_REDUCE(1) break;
+    default: LFW_REDUCE(2) break;
+  }
+#undef LFW_REDUCE
+  if (a.ev) (void)hipEventRecord(a.ev[1], st);
+  combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, st>>>(
+      a.partials, a.splits, NE, a.state);
+  if (a.ev) (void)hipEventRecord(a.ev[2], st);
+  if (a.out) {
+    constexpr int lds2 = apply16_wide_lds_bytes<D>();
+    const dim3 g2(a.apply_wgs, (unsigned)BH);
+#define LFW_APPLY(FM, NORM)                                                                   \
+  {                                                                                           \
+    if (!allow_lds(apply16_wide<T, D, FM, NORM>, lds2)) return LINFUSION_ERR_HIP;             \
+    apply16_wide<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.state, a.eps, a.N, a.blk_apply); \
+  }
+    switch (a.fm) {
+      case 0: if (a.unnorm) LFW_APPLY(0, false) else LFW_APPLY(0, true) break;
+      case 1: if (a.unnorm) LFW_APPLY(1, false) else LFW_APPLY(1, true) break;
+      default: if (a.unnorm) LFW_APPLY(2, false) else LFW_APPLY(2, true) break;
+    }
+#undef LFW_APPLY
+  }
+  if (a.ev) (void)hipEventRecord(a.ev[3], st);
+  return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+}
+
+}  // namespace
+
+#define LFW_FOR_D(X) X(80) X(160)
+
+bool wide_supported(int d) {
+  switch (d) {
+#define X(DD) case DD:
+    LFW_FOR_D(X)
+#undef X
+    return true;
+  }
+  return false;
+}
+
+int run_wide(const WideArgs& a) {
+  switch (a.d) {
+#define X(DD) \
+  case DD: return a.dtype == LINFUSION_DTYPE_F16 ? run<lf::F16, DD>(a) : run<lf::BF16, DD>(a);
+    LFW_FOR_D(X)
+#undef X
+  }
+  return LINFUSION_ERR_UNSUPPORTED;
+}
+
+}  // namespace lfw

@@ -22,6 +22,13 @@ CONFIGS = {
     "sdxl_2048_A_bf16": dict(idx=4, B=2, H=10, N=128 * 128, d=64, dtype="bf16", k_scale=1.0),
     "sdxl_2048_B_bf16": dict(idx=5, B=2, H=20, N=64 * 64, d=64, dtype="bf16", k_scale=1.0),
     "sd15_16k_f16": dict(idx=6, B=1, H=8, N=2048 * 1024, d=40, dtype="f16", k_scale=1.0),
+    # the deeper levels of the SD-v1.5 UNet (640 and 1280 channels over 8 heads): at 512 px, and at the
+    # 16K-image resolution of the headline workload (tokens / 4 and / 16)
+    "sd15_512_d80_f16": dict(idx=7, B=2, H=8, N=32 * 32, d=80, dtype="f16", k_scale=1.0),
+    "sd15_512_d160_f16": dict(idx=8, B=2, H=8, N=16 * 16, d=160, dtype="f16", k_scale=1.0),
+    "sd15_16k_d80_f16": dict(idx=9, B=1, H=8, N=1024 * 512, d=80, dtype="f16", k_scale=1.0),
+    "sd15_16k_d160_f16": dict(idx=10, B=1, H=8, N=512 * 256, d=160, dtype="f16", k_scale=1.0),
+    "sd15_16k_d160_bf16": dict(idx=10, B=1, H=8, N=512 * 256, d=160, dtype="bf16", k_scale=1.0),
 }
 EPS = 1e-6
 

@@ -1,0 +1,97 @@
+"""GPU parity for head widths above 64 (the d = 80 and d = 160 levels of the SD-v1.5 UNet): the wide
+kernels against the fp64 oracle, element by element."""
+import pytest
+import torch
+
+import paper_2409_02097_amd as lf
+from paper_2409_02097_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _ws(B, H, N, d, dtype, dev="cuda"):
+    return torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, wl.DTYPE_CODE[dtype]), dtype=torch.uint8, device=dev)
+
+
+SHAPES = [
+    # (B, H, N, d, dtype): SD-v1.5 at 512 px has (2, 8, 1024, 80) and (2, 8, 256 / 64, 160)
+    (2, 8, 1024, 80, "f16"), (2, 8, 256, 160, "f16"), (2, 8, 64, 160, "f16"),
+    (1, 2, 1, 80, "f16"), (1, 3, 33, 160, "f16"), (1, 2, 31, 80, "f16"), (1, 1, 4099, 160, "f16"),
+    (1, 2, 2051, 80, "f16"), (1, 2, 1, 160, "bf16"), (1, 2, 1000, 80, "bf16"), (2, 2, 515, 160, "bf16"),
+    (1, 8, 1024, 80, "bf16"), (1, 1, 97, 160, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", SHAPES)
+def test_wide_heads_match_oracle(B, H, N, d, dtype):
+    print(f"wide B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=70, device="cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    out = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, 1e-6, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    worst = parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"wide N={N} d={d} {dtype}")
+    print(f"  worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
+    out2 = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out2, 0, 1e-6, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.uint8), out2.view(torch.uint8)), "not run-to-run identical"
+
+
+@pytest.mark.parametrize("d,dtype", [(80, "f16"), (160, "f16"), (80, "bf16"), (160, "bf16")])
+def test_wide_heads_token_major_and_in_place(d, dtype):
+    B, H, N = 2, 4, 700
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=71, device="cpu")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda()
+    qt, kt, vt = tm(q), tm(k), tm(v)
+    view = lambda t: t.permute(0, 2, 1, 3)
+    ot = torch.full_like(qt, float("nan"))
+    lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(ot), 0, 1e-6, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    parity.check_all(view(ot).contiguous(), q, k, v, dtype, 0, 1e-6, True, f"wide token-major d={d} {dtype}")
+    lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(qt), 0, 1e-6, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(qt.view(torch.uint8), ot.view(torch.uint8)), "in place differs from out of place"
+
+
+@pytest.mark.parametrize("d", [80, 160])
+@pytest.mark.parametrize("fm,normalize", [(1, True), (2, True), (0, False)])
+def test_wide_heads_other_feature_maps_and_unnormalized(d, fm, normalize):
+    B, H, N, dtype = 1, 2, 300, "f16"
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=72, device="cpu")
+    if fm == 2:
+        q, k = q.abs(), k.abs()
+    if not normalize:
+        v = v * 0.01          # keeps the un-normalized sums inside fp16's range
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    out = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out, fm, 1e-6, 0 if normalize else lf.FLAG_UNNORMALIZED, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    parity.check_all(out, q, k, v, dtype, fm, 1e-6, normalize, f"wide d={d} fm={fm} norm={normalize}")
+
+
+def test_wide_state_entry_matches_oracle():
+    import numpy as np
+    from oracle import linattn_oracle as orc
+    B, H, N, d, dtype = 1, 2, 777, 160, "f16"
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=73, device="cpu")
+    st = torch.full((B, H, d * d + d), float("nan"), dtype=torch.float32, device="cuda")
+    lf.linfusion_attn_state(k.cuda(), v.cuda(), st, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    ks, vs = wl.stored_numpy(k), wl.stored_numpy(v)
+    for h in range(H):
+        S, z = orc.state(orc.widen(ks[0, h], dtype), orc.widen(vs[0, h], dtype))
+        got = st[0, h].double().cpu().numpy()
+        scale = np.abs(S).max()
+        assert np.abs(got[:d * d].reshape(d, d) - S).max() <= 2e-3 * scale
+        assert np.abs(got[d * d:] - z).max() <= 2e-3 * np.abs(z).max()
+
+
+def test_wide_heads_reject_fp32_and_forced_single_launch():
+    x = torch.zeros(1, 1, 64, 80, dtype=torch.float32, device="cuda")
+    assert lf.linfusion_attn_workspace_bytes(1, 1, 64, 80, lf.DTYPE_F32) == 0
+    h = torch.zeros(1, 1, 64, 80, dtype=torch.float16, device="cuda")
+    ws = _ws(1, 1, 64, 80, "f16")
+    assert lf.linfusion_attn_fwd_ex(h, h, h, torch.empty_like(h), 0, 1e-6, lf.FLAG_FORCE_FUSED, ws, check=False) == -2
+    assert lf.linfusion_attn_fwd_ex(x, x, x, torch.empty_like(x), 0, 1e-6, 0, ws, check=False) == -2
