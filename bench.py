@@ -157,7 +157,7 @@ def main():
         print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
-    cfg = wl.CONFIGS[args.workload]
+    cfg = wl.config(args.workload)
     B, H, N, d, dtype = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["dtype"]
     q, k, v = wl.make_config(args.workload, device="cuda")
     if args.layout == "token_major":
@@ -200,7 +200,7 @@ def main():
     kms = [a / max(args.profile_steps, 1) for a in acc]
     rname, aname = {"f16": ("state_reduce16<F16", "apply16_dma<F16"), "bf16": ("state_reduce16<BF16", "apply16_dma<BF16"),
                     "f32": ("state_reduce32", "apply32")}[dtype]
-    if d > 64:
+    if d > 80:
         rname = rname.replace("state_reduce16<", "state_reduce16_wide<")
         aname = aname.replace("apply16_dma<", "apply16_wide<")
     elif args.layout == "token_major" and dtype != "f32" and (d * 2) % 128 != 0 and H >= 4:

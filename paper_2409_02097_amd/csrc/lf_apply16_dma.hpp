@@ -68,6 +68,15 @@ constexpr int apply16_dma_lds_bytes(int waves = kWavesPerWG) {
   return ring > st ? ring : st;
 }
 
+// The state of one head as the apply lanes' matrix-core A operands (see the header comment), written once
+// per head by pack_state16 for the kernels whose workgroups would otherwise rebuild it for several heads:
+// {c1, alpha_z} then frag[level][t][s][lane], 16 bytes each.
+template <typename T, int D> struct Pack16 {
+  static constexpr int kHeaderBytes = 256;
+  static constexpr int kFrags = NSplit<T>::value * Shape16<D>::kMT2 * Shape16<D>::kKS;   // per lane
+  static constexpr int kHeadBytes = kHeaderBytes + kFrags * 64 * 16;
+};
+
 template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
 // One workgroup's apply work on one head: construct, prefetch(), run().
@@ -81,7 +90,7 @@ template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :
 // landed" -> "each wave reads and overwrites its head's columns" -> "pieces leave".  Inside a row piece
 // the 16-byte chunks are rotated by a row-dependent amount (both ways) so that the token-per-lane
 // accesses to one head's columns are bank-conflict free.  Use: construct with the group's pointers,
-// prefetch(), load_state() once per head (`keep` on the wave that owns it), stream().
+// prefetch(), load_packed() with the wave's own head (operands prepared by pack_state16), stream().
 template <typename T, int D, int FM, bool NORM, int ROWS_W = 0>
 struct ApplyDma {
   static constexpr bool ROWS = ROWS_W > 0;
@@ -117,7 +126,7 @@ struct ApplyDma {
   int soff[ROWS ? NL : 1];
   TileIter it, ahead;
   u32x4 A[NSplit<T>::value][Shape16<D>::kMT2][Shape16<D>::kKS];   // this wave's state operands
-  float c1, eps_s;
+  float c1, eps_s, c1_az;   // c1_az: alpha_z, kept for save_packed
 
   // `Qh_`, `Oh_`: first token row of this head; `rs_q_`, `rs_o_`: row strides in 16-byte units
   LF_DEV ApplyDma(const u32x4* Qh_, int rs_q_, u32x4* Oh_, int rs_o_, long long N_, int tiles_per_block, int wg,
@@ -198,21 +207,63 @@ struct ApplyDma {
   }
 
   // `state`: this head's [D*D + D] fp32 state.  The staging area (from kStageOffset) must be free.
+  // COHERENT: the state was written by other workgroups of the same launch (single-launch kernel) and
+  // must be read past this XCD's L2; otherwise an earlier kernel wrote it and plain wide loads do.
+  template <bool COHERENT = false>
   LF_DEV void run(const float* state, float eps) {
-    load_state(state, eps, true);
+    load_state<COHERENT>(state, eps, true);
     stream();
   }
 
+  // This wave's operands from what pack_state16 wrote for its head.
+  LF_DEV void load_packed(const unsigned char* packed, float eps) {
+    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + Pack16<T, D>::kHeaderBytes);
+#pragma unroll
+    for (int l = 0; l < NS; ++l)
+#pragma unroll
+      for (int t = 0; t < MT2; ++t)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) A[l][t][s] = frag[((l * MT2 + t) * KS + s) * 64 + lane];
+    const float* scales = reinterpret_cast<const float*>(packed);
+    c1 = scales[0];
+    eps_s = eps * scales[1];
+  }
+
+  // Writes this wave's operands where load_packed finds them (`out`: one head's Pack16 record).
+  LF_DEV void save_packed(unsigned char* out, bool header) const {
+    u32x4* frag = reinterpret_cast<u32x4*>(out + Pack16<T, D>::kHeaderBytes);
+#pragma unroll
+    for (int l = 0; l < NS; ++l)
+#pragma unroll
+      for (int t = 0; t < MT2; ++t)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) frag[((l * MT2 + t) * KS + s) * 64 + lane] = A[l][t][s];
+    if (header && lane == 0) {
+      float* scales = reinterpret_cast<float*>(out);
+      scales[0] = c1;
+      scales[1] = c1_az;
+    }
+  }
+
   // Whole workgroup: stages one head's state in LDS; the waves with `keep` build their operands from it.
+  template <bool COHERENT = false>
   LF_DEV void load_state(const float* state, float eps, bool keep) {
     // ---- prologue: state -> LDS, maxima, power-of-two scales, A fragments -------------------------
     float* st = reinterpret_cast<float*>(smem + kStageOffset);
     float* redmax = st + NE;
     float mS = 0.0f, mz = 0.0f;
-    for (int e = threadIdx.x; e < NE; e += NT) {
-      float x = ld_agent(state + e);
-      st[e] = x;
-      if (e < D * D) mS = fmaxf(mS, fabsf(x)); else mz = fmaxf(mz, fabsf(x));
+    static_assert(NE % 4 == 0 && (D * D) % 4 == 0, "the state is moved four floats at a time");
+    for (int e = threadIdx.x; e < NE / 4; e += NT) {
+      f32x4 x;
+      if constexpr (COHERENT) {
+        x = f32x4{ld_agent(state + 4 * e), ld_agent(state + 4 * e + 1), ld_agent(state + 4 * e + 2),
+                  ld_agent(state + 4 * e + 3)};
+      } else {
+        x = reinterpret_cast<const f32x4*>(state)[e];
+      }
+      reinterpret_cast<f32x4*>(st)[e] = x;
+      const float m4 = fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3])));
+      if (e < D * D / 4) mS = fmaxf(mS, m4); else mz = fmaxf(mz, m4);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -229,6 +280,7 @@ struct ApplyDma {
     if (keep) {
       c1 = az / aS;
       eps_s = eps * az;
+      c1_az = az;
       const int m = lane & 31;
       const int hv = (m >> 2) & 1;
 #pragma unroll
@@ -443,7 +495,7 @@ apply16_dma(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layou
 template <typename T, int D, int FM, bool NORM, int W>
 __global__ void __launch_bounds__(64 * W)
 apply16_rows(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, int groups_per_batch,
-             const float* __restrict__ state, float eps, long long N, int tiles_per_block) {
+             const unsigned char* __restrict__ packed, float eps, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const long long b = blockIdx.y / groups_per_batch;
@@ -451,9 +503,20 @@ apply16_rows(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layo
   ApplyDma<T, D, FM, NORM, W> ap(Q + (b * lq.batch + h0 * lq.head), lq.row, O + (b * lo.batch + h0 * lo.head), lo.row,
                                  N, tiles_per_block, blockIdx.x, gridDim.x, smem);
   ap.prefetch();
-  for (int w = 0; w < W; ++w)
-    ap.load_state(state + (b * lq.H + h0 + w) * (D * D + D), eps, wave == w);
+  ap.load_packed(packed + (b * lq.H + h0 + wave) * Pack16<T, D>::kHeadBytes, eps);
   ap.stream();
+}
+
+// Operand-ready state for apply16_rows.  grid = (B*H), block = 256: the workgroup builds the head's operands
+// with the per-head kernel's own prologue (one wave's registers hold them all) and wave 0 writes them out.
+template <typename T, int D, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+pack_state16(const float* __restrict__ state, unsigned char* __restrict__ packed) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const long long bh = blockIdx.x;
+  ApplyDma<T, D, 0, NORM> ap(nullptr, 0, nullptr, 0, 0, kWavesPerWG, 0, 1, smem);
+  ap.load_state(state + bh * (D * D + D), 0.0f, ap.wave == 0);
+  if (ap.wave == 0) ap.save_packed(packed + bh * Pack16<T, D>::kHeadBytes, true);
 }
 
 }  // namespace lf

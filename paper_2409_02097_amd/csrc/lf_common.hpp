@@ -121,7 +121,7 @@ LF_DEV float ld_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_REL
 // State reduction tiles the d x d state in 16 x 16 blocks; apply tiles the output in 32-row
 // blocks with the two normalizer rows (z hi, z lo) appended after each half of the channels.
 template <int D> struct Shape16 {
-  static_assert(D % 8 == 0 && D >= 8 && D <= 64, "head width must be a multiple of 8 up to 64");
+  static_assert(D % 8 == 0 && D >= 8 && D <= 80, "head width must be a multiple of 8 up to 80");
   static constexpr int kChunksPerRow = D / 8;          // 16-byte chunks per token row
   static constexpr int kMT = (D + 15) / 16;            // 16-wide tiles across d
   static constexpr int kDP = kMT * 16;

@@ -135,7 +135,7 @@ fused16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, co
     wait_vmcnt<0>();   // no copy into this workgroup's LDS may still be in flight when it ends
     return;
   }
-  ap.run(head_state, eps);
+  ap.template run<true>(head_state, eps);
 }
 
 template <int D> constexpr int fused32_lds_bytes() { return reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024; }

@@ -31,8 +31,6 @@ template <int D> struct ShapeWide {
   static constexpr int kRegionBytes = kNLA * 1024;
   static constexpr int kRing = 3;
   static constexpr int kSlotBytes = kWavesPerWG * kRegionBytes;
-  static constexpr int kStageOffset = (kRing - 1) * kSlotBytes;   // 16 rows of S during the prologue
-  static_assert(16 * D * 4 <= kSlotBytes, "a 16-row block of the state must fit one slot");
   // rotation of the chunks inside a token row that makes token-per-lane accesses bank-conflict free
   static constexpr int kG = (kCPR % 16 == 0) ? 16 : ((kCPR % 8 == 0) ? 8 : ((kCPR % 4 == 0) ? 4 : 2));
   static_assert(kCPR % 2 == 0 && kRPR * kG >= 16, "rotation classes must fit a region");
@@ -43,8 +41,11 @@ template <typename T, int D>
 constexpr int reduce16_wide_lds_bytes() {
   return 2 * (NSplit<T>::value + 1) * ShapeWide<D>::kTileElems * 2;   // double-buffered phi(K) levels + V
 }
-template <int D>
-constexpr int apply16_wide_lds_bytes() { return ShapeWide<D>::kRing * ShapeWide<D>::kSlotBytes; }
+// ring of tiles, plus (bf16) one slot-sized buffer for the low halves of phi(Q) of the current tile
+template <typename T, int D>
+constexpr int apply16_wide_lds_bytes() {
+  return (ShapeWide<D>::kRing + (NSplit<T>::value == 2 ? 1 : 0)) * ShapeWide<D>::kSlotBytes;
+}
 
 // ==========================================================================================
 // State reduction.  grid = (splits, heads), block = 256.  Workgroup x walks blocks of tiles_per_block
@@ -204,16 +205,107 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
 }
 
 // ==========================================================================================
+// Operand-ready state.  The apply kernel multiplies by S'^T = alpha_S S^T (and the normalizer rows
+// alpha_z z) as 16-bit matrix-core A operands; building them from the fp32 state costs a pass over d*d + d
+// floats, far too much to repeat in every apply workgroup at these widths.  pack_state_wide does it once
+// per head: grid = (d / 16, heads), block = 256.  Every workgroup finds the maxima (power-of-two scales so
+// that 16-bit storage neither overflows nor loses small entries), workgroup s then writes the operands of
+// contraction step s for all four apply waves, in the order the apply lanes load them:
+//   header  {c1 = alpha_z / alpha_S, alpha_z}, then  frag[level][wave][t][s][lane] (16 bytes each)
+// Operand (wave w, tile t, step s), lane l: m = l % 32, kg = l / 32, element j:
+//   contraction channel ch = 16 s + 8 kg + j;  slot = 16 t + 4 (m / 8) + m % 4,  half hv = (m / 4) % 2
+//   slot <  d/8   -> S'[ch][w d/4 + hv d/8 + slot];   slot == d/8 -> z'[ch] rounded to 16 bits;
+//   slot == d/8+1 -> the remainder of z'[ch] after that rounding;  else 0.
+// Level 1 (bf16 only) holds the remainders of the S' entries after rounding (hi + lo operands).
+// ==========================================================================================
+template <typename T, int D> struct PackWide {
+  using Sw = ShapeWide<D>;
+  static constexpr int kHeaderBytes = 256;
+  static constexpr int kFrags = NSplit<T>::value * kWavesPerWG * Sw::kMT2 * Sw::kKS;   // per lane
+  static constexpr int kHeadBytes = kHeaderBytes + kFrags * 64 * 16;
+};
+
+template <typename T, int D>
+__global__ void __launch_bounds__(kThreads)
+pack_state_wide(const float* __restrict__ state, unsigned char* __restrict__ packed, int normalize) {
+  using Sw = ShapeWide<D>;
+  constexpr int NS = NSplit<T>::value, KS = Sw::kKS, MT2 = Sw::kMT2, HALF = Sw::kHalf, DQ = Sw::kDQ, NE = D * D + D;
+  __shared__ float redmax[2 * kWavesPerWG];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int s = blockIdx.x;
+  const long long bh = blockIdx.y;
+  const float* st = state + bh * NE;
+  unsigned char* out = packed + bh * PackWide<T, D>::kHeadBytes;
+
+  float mS = 0.0f, mz = 0.0f;
+  const f32x4* st4 = reinterpret_cast<const f32x4*>(st);
+  for (int e = tid; e < NE / 4; e += kThreads) {     // D*D and D are multiples of 4
+    const f32x4 x = st4[e];
+    const float m = fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3])));
+    if (e < D * D / 4) mS = fmaxf(mS, m); else mz = fmaxf(mz, m);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    mS = fmaxf(mS, __shfl_xor(mS, o));
+    mz = fmaxf(mz, __shfl_xor(mz, o));
+  }
+  if (lane == 0) { redmax[wave] = mS; redmax[kWavesPerWG + wave] = mz; }
+  __syncthreads();
+  mS = 0.0f; mz = 0.0f;
+#pragma unroll
+  for (int w = 0; w < kWavesPerWG; ++w) { mS = fmaxf(mS, redmax[w]); mz = fmaxf(mz, redmax[kWavesPerWG + w]); }
+  const float aS = pow2_scale_for(mS);
+  const float az = normalize ? pow2_scale_for(mz) : 1.0f;
+  if (s == 0 && tid == 0) {
+    float* scales = reinterpret_cast<float*>(out);
+    scales[0] = az / aS;
+    scales[1] = az;
+  }
+
+  u32x4* frag = reinterpret_cast<u32x4*>(out + PackWide<T, D>::kHeaderBytes);
+  const int m = lane & 31, kg = lane >> 5;
+  const int hv = (m >> 2) & 1;
+#pragma unroll
+  for (int t = 0; t < MT2; ++t) {
+    const int slot = 16 * t + 4 * (m >> 3) + (m & 3);
+    u32x4 hi4, lo4;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      float hi2[2], lo2[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int ch = 16 * s + 8 * kg + 2 * w + q;
+        float x = 0.0f;
+        bool zrem = false;
+        if (slot < HALF) x = st[ch * D + wave * DQ + hv * HALF + slot] * aS;
+        else if (normalize && slot == HALF) x = st[D * D + ch] * az;
+        else if (normalize && slot == HALF + 1) { x = st[D * D + ch] * az; zrem = true; }
+        float r0, r1;
+        unpack2<T>(pack2<T>(x, 0.0f), r0, r1);   // x rounded once to 16 bits
+        hi2[q] = zrem ? x - r0 : x;
+        lo2[q] = (slot < HALF) ? x - r0 : 0.0f;
+      }
+      hi4[w] = pack2<T>(hi2[0], hi2[1]);
+      lo4[w] = pack2<T>(lo2[0], lo2[1]);
+    }
+    frag[(((0 * kWavesPerWG + wave) * MT2 + t) * KS + s) * 64 + lane] = hi4;
+    if constexpr (NS == 2) frag[(((1 * kWavesPerWG + wave) * MT2 + t) * KS + s) * 64 + lane] = lo4;
+  }
+}
+
+// ==========================================================================================
 // Apply + normalize.  grid = (wgs, heads), block = 256.  The LDS-DMA ring of apply16_dma with workgroup-wide
-// slots: wave w copies in (and later stores) token rows 8w..8w+7 of a tile, whole rows.  Every wave reads the
-// whole tile as matrix-core B operands (phi applied in registers), then -- after a barrier, since all waves
-// read all channels -- overwrites its own d/4 output channels of every token in place.  Per wave the
+// slots: wave w copies in (and later stores) token rows 8w..8w+7 of a tile, whole rows, and applies phi to
+// them in place once they have landed (each element once per workgroup; bf16 keeps the low halves of the
+// hi + lo operands in a buffer of their own).  Every wave then reads the whole tile as matrix-core B
+// operands and -- after a barrier, since all waves read all channels -- overwrites its own d/4 output
+// channels of every token in place.  Per wave the
 // products are those of apply16_dma for a head whose state has only this wave's d/4 columns (plus the two
 // normalizer rows, which every wave carries).  Pipelined as the row-piece kernel: store tile j-1, copy tile
-// j+2, read tile j, barrier, compute and write back, wait for own rows of tile j+1, barrier.
-// The prologue cannot stage the whole fp32 state in LDS (103 KB at d = 160): a first pass over the state in
-// global memory finds the maxima that fix the power-of-two scales, then the state is staged 16 rows (one
-// contraction step) at a time and each wave builds that step's A operands.
+// j+2, read tile j, barrier, compute and write back, wait for own rows of tile j+1 and apply phi to them,
+// barrier.
+// The state arrives operand-ready from pack_state_wide: the prologue is a handful of coalesced loads.
 // ==========================================================================================
 template <typename T, int D, int FM, bool NORM>
 struct ApplyWide {
@@ -289,60 +381,46 @@ struct ApplyWide {
     ahead.next();
   }
 
-  // `state`: this head's [D*D + D] fp32 state; `zst`, `redmax`: D + 16 and 8 floats of LDS outside the ring
-  LF_DEV void load_state(const float* state, float eps, float* zst, float* redmax) {
-    float mS = 0.0f, mz = 0.0f;
-    for (int e = threadIdx.x; e < NE; e += kThreads) {
-      const float x = ld_agent(state + e);
-      if (e < D * D) mS = fmaxf(mS, fabsf(x));
-      else { mz = fmaxf(mz, fabsf(x)); zst[e - D * D] = x; }
-    }
+  // `packed`: this head's operands as pack_state_wide wrote them
+  LF_DEV void load_packed(const unsigned char* packed, float eps) {
+    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + PackWide<T, D>::kHeaderBytes);
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      mS = fmaxf(mS, __shfl_xor(mS, o));
-      mz = fmaxf(mz, __shfl_xor(mz, o));
-    }
-    if (lane == 0) { redmax[wave] = mS; redmax[kWavesPerWG + wave] = mz; }
-    __syncthreads();
-    mS = 0.0f; mz = 0.0f;
+    for (int l = 0; l < NS; ++l)
 #pragma unroll
-    for (int w = 0; w < kWavesPerWG; ++w) { mS = fmaxf(mS, redmax[w]); mz = fmaxf(mz, redmax[kWavesPerWG + w]); }
-    const float aS = pow2_scale_for(mS);
-    const float az = NORM ? pow2_scale_for(mz) : 1.0f;
-    c1 = az / aS;
-    eps_s = eps * az;
+      for (int t = 0; t < MT2; ++t)
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+          A[l][t][s] = frag[(((l * kWavesPerWG + wave) * MT2 + t) * KS + s) * 64 + lane];
+    const float* scales = reinterpret_cast<const float*>(packed);
+    c1 = scales[0];
+    eps_s = eps * scales[1];
+  }
 
-    float* st = reinterpret_cast<float*>(smem + Sw::kStageOffset);
-    const int m = lane & 31;
-    const int hv = (m >> 2) & 1;
+  // phi on this wave's rows of ring slot `slot` (they have landed), in place; bf16: low halves to the LO buffer
+  LF_DEV void phi_pass(int slot) {
+    unsigned char* sl = region_ptr(slot);
+    unsigned char* lo = smem + R * Sw::kSlotBytes + wave * Sw::kRegionBytes;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      for (int e = threadIdx.x; e < 16 * D; e += kThreads) st[e] = ld_agent(state + s * 16 * D + e);
-      __syncthreads();
+    for (int u = 0; u < NL; ++u) {
+      const int at = u * 1024 + lane * 16;
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(sl + at);
+      u32x4 h4, l4;
 #pragma unroll
-      for (int t = 0; t < MT2; ++t) {
-        const int slot = 16 * t + 4 * (m >> 3) + (m & 3);
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          float hi2[2], lo2[2];
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            const int chl = 8 * kg + 2 * w + q;      // row inside the staged 16-row block
-            float x = 0.0f;
-            bool zrem = false;
-            if (slot < HALF) x = st[chl * D + wave * DQ + hv * HALF + slot] * aS;
-            else if (NORM && slot == HALF) x = zst[s * 16 + chl] * az;
-            else if (NORM && slot == HALF + 1) { x = zst[s * 16 + chl] * az; zrem = true; }
-            float r0, r1;
-            unpack2<T>(pack2<T>(x, 0.0f), r0, r1);   // x rounded once to 16 bits
-            hi2[q] = zrem ? x - r0 : x;
-            lo2[q] = (slot < HALF) ? x - r0 : 0.0f;
-          }
-          A[0][t][s][w] = pack2<T>(hi2[0], hi2[1]);
-          if constexpr (NS == 2) A[1][t][s][w] = pack2<T>(lo2[0], lo2[1]);
+      for (int w = 0; w < 4; ++w) {
+        float x0, x1;
+        unpack2<T>(raw[w], x0, x1);
+        const float r0 = phi<FM>(x0), r1 = phi<FM>(x1);
+        if constexpr (NS == 1) {
+          h4[w] = pack2<T>(r0, r1);
+        } else {
+          uint32_t h, l;
+          pack2_split<T>(r0, r1, h, l);
+          h4[w] = h;
+          l4[w] = l;
         }
       }
-      __syncthreads();
+      *reinterpret_cast<u32x4*>(sl + at) = h4;
+      if constexpr (NS == 2) *reinterpret_cast<u32x4*>(lo + at) = l4;
     }
   }
 
@@ -367,6 +445,7 @@ struct ApplyWide {
       if (second.valid()) wait_vmcnt<NL>();
       else wait_vmcnt<0>();
     }
+    if (it.valid()) phi_pass(0);
     __syncthreads();
     int slot = 0, prev_slot = 0;
     long long prev_tile = -1;
@@ -377,27 +456,15 @@ struct ApplyWide {
       const bool copied = ahead.valid();
       if (copied) issue_copy(ahead.t, have_prev ? prev_slot : R - 1);
 
-      // ---- the whole row of this lane's token -> phi -> 16-bit B operands ---------------------------
+      // ---- phi(q) of this lane's token, all channels: the B operands ---------------------------------
       u32x4 Bh[KS], Bl[NS == 2 ? KS : 1];
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        const u32x4 raw = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, 2 * s + kg));
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          float x0, x1;
-          unpack2<T>(raw[w], x0, x1);
-          const float r0 = phi<FM>(x0), r1 = phi<FM>(x1);
-          if constexpr (NS == 1) {
-            Bh[s][w] = pack2<T>(r0, r1);
-          } else {
-            uint32_t h, l;
-            pack2_split<T>(r0, r1, h, l);
-            Bh[s][w] = h;
-            Bl[s][w] = l;
-          }
-        }
+        const unsigned char* p = chunk_ptr(slot, 2 * s + kg);
+        Bh[s] = *reinterpret_cast<const u32x4*>(p);
+        if constexpr (NS == 2) Bl[s] = *reinterpret_cast<const u32x4*>(p + (R - slot) * Sw::kSlotBytes);
       }
-      __syncthreads();   // every wave holds its operands: the tile may be overwritten
+      __syncthreads();   // every wave holds its operands: the tile (and the LO buffer) may be overwritten
 
       f32x16 acc[MT2];
 #pragma unroll
@@ -442,8 +509,9 @@ struct ApplyWide {
         if (have_prev && copied) wait_vmcnt<2 * NL>();
         else if (have_prev || copied) wait_vmcnt<NL>();
         else wait_vmcnt<0>();
+        phi_pass(slot + 1 == R ? 0 : slot + 1);
       }
-      __syncthreads();   // tile j is finished by all waves; tile j+1 has landed for all
+      __syncthreads();   // tile j is finished by all waves; tile j+1 has landed and carries phi for all
       prev_tile = tile;
       prev_slot = slot;
       slot = slot + 1 == R ? 0 : slot + 1;
@@ -455,15 +523,13 @@ struct ApplyWide {
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
 apply16_wide(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, HeadSubset hs,
-             const float* __restrict__ state, float eps, long long N, int tiles_per_block) {
+             const unsigned char* __restrict__ packed, float eps, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ float zst[D + 16];
-  __shared__ float redmax[2 * kWavesPerWG];
   const long long bh = hs.bh(blockIdx.y, lq.H);
   ApplyWide<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
                                gridDim.x, smem);
   ap.prefetch();
-  ap.load_state(state + bh * (D * D + D), eps, zst, redmax);
+  ap.load_packed(packed + bh * PackWide<T, D>::kHeadBytes, eps);
   ap.stream();
 }
 

@@ -17,6 +17,7 @@ struct WideArgs {
   bool unnorm;
   lf::Layout lq, lkv, lo;
   float *partials, *state;    // [B*H][splits][d*d + d] and [B*H][d*d + d], fp32
+  unsigned char* packed;      // wide_packed_bytes(d, dtype) per head: the state as apply operands
   int splits, blk_reduce, apply_wgs, blk_apply;
   hipStream_t st;
   hipEvent_t* ev;             // null, or four events: before reduce, after it, after combine, after apply
@@ -24,7 +25,9 @@ struct WideArgs {
 
 // head widths the wide kernels are built for
 bool wide_supported(int d);
-// enqueues state reduction, combine and (if out) apply; returns LINFUSION_OK or a LINFUSION_ERR_* code
+// bytes per head of the operand-ready state between the pack and apply kernels (0 if unsupported)
+size_t wide_packed_bytes(int d, int dtype);
+// enqueues state reduction, combine and (if out) pack and apply; returns LINFUSION_OK or a LINFUSION_ERR_* code
 int run_wide(const WideArgs& a);
 
 }  // namespace lfw

@@ -35,7 +35,7 @@ struct Plan {
   int gwaves, groups, gsplits, gblk_reduce, gapply_wgs, gblk_apply;
   long long n_tiles;
   size_t state_floats;  // d*d + d: one partial, and one head's state
-  size_t ws_partials, ws_state, ws_sync, ws_total;
+  size_t ws_partials, ws_state, ws_sync, ws_pack, ws_total;   // ws_pack: operand-ready state (row-piece apply)
 };
 
 int env_int(const char* name, int dflt) {
@@ -54,16 +54,19 @@ int block_tiles(long long share, const char* env, int dflt, int multiple = lf::k
   return (int)((b + multiple - 1) / multiple * multiple);
 }
 
-// head widths up to 64 in steps of 8 for every dtype; above that the 16-bit wide kernels' widths
+// head widths up to 64 in steps of 8 for every dtype; for the 16-bit types also 80 (same kernels) and the
+// wide kernels' widths
+bool is_wide(int d) { return d > 80; }
 bool supported_d(int d, int dtype) {
   if (d >= 8 && d <= 64 && d % 8 == 0) return true;
-  return dtype != LINFUSION_DTYPE_F32 && lfw::wide_supported(d);
+  return dtype != LINFUSION_DTYPE_F32 && (d == 80 || lfw::wide_supported(d));
 }
 
 // Workgroups of the fused kernel that fit one CU at once (registers and LDS of the largest phase);
 // conservative figures, re-checked against the runtime's occupancy query before each fused launch.
 int fused_wgs_per_cu(int d, int dtype) {
   if (dtype == LINFUSION_DTYPE_F32) return 2;
+  if (d > 64) return 1;
   if (dtype == LINFUSION_DTYPE_BF16) return d <= 40 ? 4 : (d <= 48 ? 3 : 2);
   return d <= 48 ? 4 : 2;
 }
@@ -80,7 +83,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   const long long BH = (long long)B * H;
   const int tile = dtype == LINFUSION_DTYPE_F32 ? lf::kTile32 : lf::kTile;
   p->n_tiles = (N + tile - 1) / tile;
-  if (d > 64) {
+  if (is_wide(d)) {
     // wide kernels: every wave of a workgroup visits every tile of its blocks; three-kernel path only
     auto per_head = [&](int want_total, int blk_dflt, const char* env_blk, int* blk) {
       long long s = (want_total + BH - 1) / BH;
@@ -103,7 +106,9 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     p->ws_partials = up((size_t)BH * p->splits * p->state_floats * sizeof(float));
     p->ws_state = up((size_t)BH * p->state_floats * sizeof(float));
-    p->ws_sync = up(2 * sizeof(unsigned) + 16);
+    // in place of the single-launch flags: the state as apply operands
+    p->ws_sync = up((size_t)BH * lfw::wide_packed_bytes(d, dtype));
+    p->ws_pack = 0;
     p->ws_total = p->ws_partials + p->ws_state + p->ws_sync;
     return LINFUSION_OK;
   }
@@ -134,7 +139,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     p->fblk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", 8);
   }
   // row-piece kernels: a workgroup covers a whole group of four heads, every wave walks all of its tiles
-  p->gwaves = (H % 8 == 0 && env_int("LINFUSION_GROUP_WAVES", 8) == 8) ? 8 : 4;
+  p->gwaves = (H % 8 == 0 && d <= 64 && env_int("LINFUSION_GROUP_WAVES", 8) == 8) ? 8 : 4;   // d = 80: registers
   p->groups = B * (H / p->gwaves);
   if (p->groups > 0) {
     auto per_group = [&](int want_total, long long* sh) {
@@ -175,7 +180,13 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   p->ws_partials = up((size_t)BH * smax * p->state_floats * sizeof(float));
   p->ws_state = up((size_t)BH * p->state_floats * sizeof(float));
   p->ws_sync = up((size_t)BH * 2 * (p->fsplits > 0 ? p->fsplits : 1) * sizeof(unsigned) + 16);
-  p->ws_total = p->ws_partials + p->ws_state + p->ws_sync;
+  p->ws_pack = 0;
+  if (dtype != LINFUSION_DTYPE_F32 && p->groups > 0) {
+    const size_t ns = dtype == LINFUSION_DTYPE_BF16 ? 2 : 1;
+    const size_t frags = ns * (size_t)((d / 2 + 2 + 15) / 16) * (size_t)((d / 8 + 1) / 2);   // Pack16<T, D>::kFrags
+    p->ws_pack = up((size_t)BH * (256 + frags * 1024));
+  }
+  p->ws_total = p->ws_partials + p->ws_state + p->ws_sync + p->ws_pack;
   return LINFUSION_OK;
 }
 
@@ -293,7 +304,8 @@ int run16(const Args& a) {
     const size_t lds = fused16_lds_bytes<T, D>();
     bool launched = false;
 #define LF_FUSED(FM, NORM)                                                                               \
-  if (fits_resident(fused16<T, D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                        \
+  if (allow_lds(fused16<T, D, FM, NORM>, (int)lds) &&                                                    \
+      fits_resident(fused16<T, D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                        \
     if (a.ev) (void)hipEventRecord(a.ev[0], st);                                                         \
     fused16<T, D, FM, NORM><<<g, blk, lds, st>>>(K, V, a.lkv, Q, a.lq, O, a.lo, partials, state, sync, err,  \
                                                  next_ticket(), spin_limit(), a.eps, a.N, p.fblk_reduce,     \
@@ -321,20 +333,25 @@ int run16(const Args& a) {
     state_reduce16_rows<T, D, FM, WW><<<g1, dim3(64 * WW), ldsr, st>>>(K, V, a.lkv, gpb, partials, a.N,  \
                                                                        p.gblk_reduce);                   \
   }
-#define LF_REDUCE(FM) if (p.gwaves == 8) LF_REDUCE_W(FM, 8) else LF_REDUCE_W(FM, 4)
+#define LF_REDUCE(FM)                                   \
+  if constexpr (D <= 64) {                              \
+    if (p.gwaves == 8) LF_REDUCE_W(FM, 8) else LF_REDUCE_W(FM, 4) \
+  } else LF_REDUCE_W(FM, 4)
     LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
 #undef LF_REDUCE_W
     if (rest > 0) {   // same number of partials per head, so that one combine serves all heads
       const dim3 g1t(p.gsplits, (unsigned)(B * rest));
-#define LF_REDUCE(FM) \
+#define LF_REDUCE(FM)                                                                    \
+  if (!allow_lds(state_reduce16<T, D, FM>, (int)lds1)) return LINFUSION_ERR_HIP;         \
   state_reduce16<T, D, FM><<<g1t, blk, lds1, st>>>(K, V, a.lkv, tail, partials, a.N, p.blk_reduce);
       LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
     }
   } else {
     const dim3 g1(p.splits, (unsigned)a.BH);
-#define LF_REDUCE(FM) \
+#define LF_REDUCE(FM)                                                                    \
+  if (!allow_lds(state_reduce16<T, D, FM>, (int)lds1)) return LINFUSION_ERR_HIP;         \
   state_reduce16<T, D, FM><<<g1, blk, lds1, st>>>(K, V, a.lkv, all, partials, a.N, p.blk_reduce);
     LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
@@ -347,27 +364,39 @@ int run16(const Args& a) {
     const size_t lds2 = apply16_dma_lds_bytes<T, D>();
     if (a.group_apply) {
       const dim3 g2(p.gapply_wgs, (unsigned)p.groups);
+      unsigned char* packed = a.ws + p.ws_partials + p.ws_state + p.ws_sync;
+      static_assert(Pack16<T, D>::kFrags == NSplit<T>::value * ((D / 2 + 2 + 15) / 16) * ((D / 8 + 1) / 2),
+                    "the workspace size formula must match the packed layout");
+      if (!allow_lds(pack_state16<T, D, true>, (int)lds2) || !allow_lds(pack_state16<T, D, false>, (int)lds2))
+        return LINFUSION_ERR_HIP;
+      if (a.unnorm) pack_state16<T, D, false><<<dim3((unsigned)a.BH), blk, lds2, st>>>(state, packed);
+      else pack_state16<T, D, true><<<dim3((unsigned)a.BH), blk, lds2, st>>>(state, packed);
 #define LF_APPLY_W(FM, NORM, WW)                                                                          \
   {                                                                                                       \
     constexpr int ldsa = apply16_dma_lds_bytes<T, D>(WW);                                                 \
     if (!allow_lds(apply16_rows<T, D, FM, NORM, WW>, ldsa)) return LINFUSION_ERR_HIP;                     \
-    apply16_rows<T, D, FM, NORM, WW><<<g2, dim3(64 * WW), ldsa, st>>>(Q, a.lq, O, a.lo, gpb, state, a.eps, \
+    apply16_rows<T, D, FM, NORM, WW><<<g2, dim3(64 * WW), ldsa, st>>>(Q, a.lq, O, a.lo, gpb, packed, a.eps, \
                                                                       a.N, p.gblk_apply);                 \
   }
-#define LF_APPLY(FM, NORM) if (p.gwaves == 8) LF_APPLY_W(FM, NORM, 8) else LF_APPLY_W(FM, NORM, 4)
+#define LF_APPLY(FM, NORM)                                          \
+  if constexpr (D <= 64) {                                          \
+    if (p.gwaves == 8) LF_APPLY_W(FM, NORM, 8) else LF_APPLY_W(FM, NORM, 4) \
+  } else LF_APPLY_W(FM, NORM, 4)
       LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
 #undef LF_APPLY_W
       if (rest > 0) {
         const dim3 g2t(p.apply_wgs, (unsigned)(B * rest));
-#define LF_APPLY(FM, NORM) \
+#define LF_APPLY(FM, NORM)                                                               \
+  if (!allow_lds(apply16_dma<T, D, FM, NORM>, (int)lds2)) return LINFUSION_ERR_HIP;      \
   apply16_dma<T, D, FM, NORM><<<g2t, blk, lds2, st>>>(Q, a.lq, O, a.lo, tail, state, a.eps, a.N, p.blk_apply);
         LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
       }
     } else {
       const dim3 g2(p.apply_wgs, (unsigned)a.BH);
-#define LF_APPLY(FM, NORM) \
+#define LF_APPLY(FM, NORM)                                                               \
+  if (!allow_lds(apply16_dma<T, D, FM, NORM>, (int)lds2)) return LINFUSION_ERR_HIP;      \
   apply16_dma<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, state, a.eps, a.N, p.blk_apply);
       LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
@@ -431,26 +460,26 @@ int run32(const Args& a) {
 }
 
 int dispatch(int d, int dtype, const Args& a) {
-  if (d > 64) {
+  if (is_wide(d)) {
     const Plan& p = *a.p;
     lfw::WideArgs w{a.q, a.k, a.v, a.out, (int)(a.BH / a.lkv.H), a.lkv.H, a.N, d, dtype, a.fm, a.eps, a.unnorm,
                     a.lq, a.lkv, a.lo, reinterpret_cast<float*>(a.ws),
                     a.state_out ? a.state_out : reinterpret_cast<float*>(a.ws + p.ws_partials),
-                    p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, a.st, a.ev};
+                    a.ws + p.ws_partials + p.ws_state, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, a.st, a.ev};
     return lfw::run_wide(w);
   }
   switch (dtype) {
     case LINFUSION_DTYPE_F16:
       switch (d) {
 #define X(DD) case DD: return run16<lf::F16, DD>(a);
-        LF_FOR_D(X)
+        LF_FOR_D(X) X(80)
 #undef X
       }
       break;
     case LINFUSION_DTYPE_BF16:
       switch (d) {
 #define X(DD) case DD: return run16<lf::BF16, DD>(a);
-        LF_FOR_D(X)
+        LF_FOR_D(X) X(80)
 #undef X
       }
       break;
@@ -577,10 +606,16 @@ int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int 
   // single heads would touch as scattered fragments.  (Not used by the single-launch kernel, so a
   // forced single launch keeps the one-head-per-workgroup mapping.)
   auto heads_adjacent = [&](const Strides& s) { return p.groups > 0 && s.h == d && s.n > d; };
-  const bool frag = dtype != LINFUSION_DTYPE_F32 && (d * esz) % 128 != 0 && !(flags & LINFUSION_FLAG_FORCE_FUSED);
-  int group_mode = env_int("LINFUSION_HEAD_GROUPS", 1);   // 2 = off (tuning aid)
-  const bool group_reduce = frag && group_mode == 1 && heads_adjacent(lkv);
-  const bool group_apply = frag && group_mode == 1 && heads_adjacent(lo) && heads_adjacent(lq);
+  // Measured (token-major, d = 40): from about 40 MB of tensor traffic up the row-piece kernels match the
+  // contiguous layout's speed and the per-head kernels fall behind (2x at 170 MB, 3x at 2.7 GB); below
+  // about 20 MB the per-head kernels' shorter start wins.
+  const double tensor_bytes = 4.0 * (double)B * H * (double)N * d * (double)esz;
+  const bool big = tensor_bytes >= (double)env_int("LINFUSION_GROUP_MIN_MB", 24) * 1048576.0;
+  const int group_mode = env_int("LINFUSION_HEAD_GROUPS", 1);   // 1 = by size, 2 = never, 3 = whenever possible
+  const bool frag = (group_mode == 3 || (group_mode == 1 && big)) && dtype != LINFUSION_DTYPE_F32 &&
+                    (d * esz) % 128 != 0 && !(flags & LINFUSION_FLAG_FORCE_FUSED);
+  const bool group_reduce = frag && heads_adjacent(lkv);
+  const bool group_apply = frag && heads_adjacent(lo) && heads_adjacent(lq);
   Args a{q, k, v, out, (long long)B * H, N, feature_map, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
          &p, (unsigned char*)workspace, nullptr, (hipStream_t)stream, ev,
          device_layout(lq, H, esz), device_layout(lkv, H, esz), device_layout(lo, H, esz), group_reduce, group_apply};
@@ -639,11 +674,12 @@ int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes, int
   if (workspace_bytes < p.ws_total) return LINFUSION_ERR_WORKSPACE;
   rc = check_device();
   if (rc != LINFUSION_OK) return rc;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
+  if (p.fsplits == 0) return LINFUSION_OK;   // no single-launch path for this shape: nothing can time out
   const unsigned char* ws = (const unsigned char*)workspace;
   const unsigned* err = reinterpret_cast<const unsigned*>(ws + p.ws_partials + p.ws_state) +
                         (size_t)B * H * 2 * (p.fsplits > 0 ? p.fsplits : 1);
   unsigned pair[2] = {0, 0};   // {ticket of the call that raised it, 1}
-  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
   if (hipMemcpy(pair, err, sizeof(pair), hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
   // the word is meaningful only when it carries the ticket of the last single-launch call on this process
   return (pair[1] == 1u && pair[0] != 0u && pair[0] == g_last_ticket.load()) ? LINFUSION_ERR_TIMEOUT : LINFUSION_OK;

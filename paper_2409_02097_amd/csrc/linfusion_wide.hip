@@ -51,12 +51,13 @@ int run(const WideArgs& a) {
       a.partials, a.splits, NE, a.state);
   if (a.ev) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
-    constexpr int lds2 = apply16_wide_lds_bytes<D>();
+    pack_state_wide<T, D><<<dim3(ShapeWide<D>::kKS, (unsigned)BH), blk, 0, st>>>(a.state, a.packed, a.unnorm ? 0 : 1);
+    constexpr int lds2 = apply16_wide_lds_bytes<T, D>();
     const dim3 g2(a.apply_wgs, (unsigned)BH);
 #define LFW_APPLY(FM, NORM)                                                                   \
   {                                                                                           \
     if (!allow_lds(apply16_wide<T, D, FM, NORM>, lds2)) return LINFUSION_ERR_HIP;             \
-    apply16_wide<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.state, a.eps, a.N, a.blk_apply); \
+    apply16_wide<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, a.N, a.blk_apply); \
   }
     switch (a.fm) {
       case 0: if (a.unnorm) LFW_APPLY(0, false) else LFW_APPLY(0, true) break;
@@ -71,7 +72,7 @@ int run(const WideArgs& a) {
 
 }  // namespace
 
-#define LFW_FOR_D(X) X(80) X(160)
+#define LFW_FOR_D(X) X(160)
 
 bool wide_supported(int d) {
   switch (d) {
@@ -81,6 +82,16 @@ bool wide_supported(int d) {
     return true;
   }
   return false;
+}
+
+size_t wide_packed_bytes(int d, int dtype) {
+  switch (d) {
+#define X(DD) \
+  case DD: return dtype == LINFUSION_DTYPE_F16 ? lf::PackWide<lf::F16, DD>::kHeadBytes : lf::PackWide<lf::BF16, DD>::kHeadBytes;
+    LFW_FOR_D(X)
+#undef X
+  }
+  return 0;
 }
 
 int run_wide(const WideArgs& a) {

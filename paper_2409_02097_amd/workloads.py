@@ -32,6 +32,19 @@ CONFIGS = {
 }
 EPS = 1e-6
 
+
+def config(name: str) -> dict:
+    """A named workload, or an ad-hoc one written as "B=2,H=8,N=16384,d=40,dtype=f16"."""
+    if name in CONFIGS:
+        return CONFIGS[name]
+    c = dict(idx=99, k_scale=1.0)
+    for item in name.split(","):
+        key, val = item.split("=")
+        c[key] = val if key == "dtype" else int(val)
+    if not {"B", "H", "N", "d", "dtype"} <= set(c):
+        raise KeyError(f"unknown workload {name!r}")
+    return c
+
 TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 DTYPE_CODE = {"f32": 0, "f16": 1, "bf16": 2}
 ITEMSIZE = {"f32": 4, "f16": 2, "bf16": 2}
@@ -56,7 +69,7 @@ def make_qkv(B, H, N, d, dtype, idx=0, k_scale=1.0, device="cpu", seed_offset=0)
 
 
 def make_config(name: str, device="cpu"):
-    c = CONFIGS[name]
+    c = config(name)
     return make_qkv(c["B"], c["H"], c["N"], c["d"], c["dtype"], c["idx"], c["k_scale"], device)
 
 

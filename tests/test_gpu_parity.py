@@ -29,7 +29,8 @@ SMALL = [
     (1, 2, 1000, 40, "f16"), (2, 2, 4099, 64, "f16"), (1, 3, 777, 8, "f16"), (1, 1, 130, 16, "f16"),
     (1, 2, 515, 24, "f16"), (1, 2, 300, 32, "f16"), (1, 2, 300, 48, "f16"), (1, 1, 300, 56, "f16"),
     (1, 2, 1, 64, "bf16"), (2, 2, 33, 40, "bf16"), (1, 2, 1000, 64, "bf16"), (1, 3, 4099, 40, "bf16"),
-    (1, 2, 300, 24, "bf16"), (1, 1, 200, 48, "bf16"),
+    (1, 2, 300, 24, "bf16"), (1, 1, 200, 48, "bf16"), (1, 2, 1029, 80, "bf16"), (1, 2, 1, 80, "bf16"),
+    (2, 3, 1500, 80, "f16"), (1, 1, 33, 80, "f16"),
     (1, 2, 1, 40, "f32"), (1, 2, 17, 64, "f32"), (2, 2, 1000, 40, "f32"), (1, 3, 2051, 64, "f32"),
     (1, 2, 100, 8, "f32"), (1, 2, 100, 24, "f32"), (1, 1, 100, 56, "f32"), (1, 1, 333, 32, "f32"),
 ]

@@ -14,6 +14,13 @@ PATHS = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED}
 SENTINEL = 12345.0
 
 
+@pytest.fixture(autouse=True)
+def _row_piece_kernels_at_every_size(monkeypatch):
+    """By default the library keeps the per-head kernels below ~24 MB of tensor traffic; these tests want the
+    row-piece kernels wherever the layout allows them (the library reads the variable at every call)."""
+    monkeypatch.setenv("LINFUSION_HEAD_GROUPS", "3")
+
+
 def _ws(B, H, N, d, dtype, dev):
     return torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, wl.DTYPE_CODE[dtype]), dtype=torch.uint8, device=dev)
 
@@ -34,9 +41,11 @@ SHAPES = [
     (2, 3, 33, 40, "f16"), (1, 8, 1000, 40, "f16"), (2, 2, 4099, 64, "f16"), (1, 3, 515, 24, "f16"),
     (1, 2, 300, 32, "f16"), (1, 5, 77, 8, "f16"), (2, 5, 1000, 40, "f16"), (1, 1, 100, 40, "f16"),
     (1, 9, 2500, 56, "f16"), (3, 6, 130, 16, "f16"), (1, 8, 777, 56, "f16"), (1, 12, 600, 40, "f16"),
-    (2, 8, 95, 8, "f16"), (1, 16, 1030, 48, "f16"), (1, 8, 400, 32, "f16"),
+    (2, 8, 95, 8, "f16"), (1, 16, 1030, 48, "f16"), (1, 8, 400, 32, "f16"), (1, 8, 500, 80, "f16"),
+    (2, 5, 300, 80, "f16"),
     (2, 2, 33, 40, "bf16"), (1, 3, 4099, 64, "bf16"), (1, 2, 300, 48, "bf16"), (2, 7, 900, 40, "bf16"),
     (2, 16, 300, 24, "bf16"), (1, 8, 2100, 40, "bf16"), (1, 8, 260, 56, "bf16"),
+    (1, 8, 333, 80, "bf16"),
     (1, 2, 17, 64, "f32"), (2, 2, 1000, 40, "f32"), (1, 3, 2051, 56, "f32"),
 ]
 
@@ -130,10 +139,12 @@ def test_in_place_on_a_token_major_q():
     parity.check_all(view(qt).contiguous(), q, k, v, dtype, 0, 1e-6, True, "in place, token-major")
 
 
-def test_sd_sized_token_major_layer():
-    """B=2, H=8, N=4096, d=40 fp16 in the UNet's own [B, N, H*d] layout, default path choice."""
-    name = "sd15_512_f16"
-    c = wl.CONFIGS[name]
+@pytest.mark.parametrize("name", ["sd15_512_f16", "B=2,H=8,N=16384,d=40,dtype=f16"])
+def test_sd_sized_token_major_layer(name, monkeypatch):
+    """SD-v1.5 layers at 512 px and 1024 px in the UNet's own [B, N, H*d] layout, default choice of kernels
+    (per-head below the size threshold, row-piece above)."""
+    monkeypatch.delenv("LINFUSION_HEAD_GROUPS")
+    c = wl.config(name)
     q, k, v = wl.make_config(name, device="cpu")
     tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda()
     qt, kt, vt = tm(q), tm(k), tm(v)

@@ -89,9 +89,10 @@ def test_wide_state_entry_matches_oracle():
 
 
 def test_wide_heads_reject_fp32_and_forced_single_launch():
-    x = torch.zeros(1, 1, 64, 80, dtype=torch.float32, device="cuda")
+    x = torch.zeros(1, 1, 64, 160, dtype=torch.float32, device="cuda")
+    assert lf.linfusion_attn_workspace_bytes(1, 1, 64, 160, lf.DTYPE_F32) == 0
     assert lf.linfusion_attn_workspace_bytes(1, 1, 64, 80, lf.DTYPE_F32) == 0
-    h = torch.zeros(1, 1, 64, 80, dtype=torch.float16, device="cuda")
-    ws = _ws(1, 1, 64, 80, "f16")
+    h = torch.zeros(1, 1, 64, 160, dtype=torch.float16, device="cuda")
+    ws = _ws(1, 1, 64, 160, "f16")
     assert lf.linfusion_attn_fwd_ex(h, h, h, torch.empty_like(h), 0, 1e-6, lf.FLAG_FORCE_FUSED, ws, check=False) == -2
     assert lf.linfusion_attn_fwd_ex(x, x, x, torch.empty_like(x), 0, 1e-6, 0, ws, check=False) == -2
