@@ -20,17 +20,22 @@ template <int D> struct ShapeWide {
   static constexpr int kChunks = kTile * kCPR;        // chunks per tile
   static constexpr int kNLR = (kChunks + kThreads - 1) / kThreads;   // reduction: loads per thread per tensor
   static constexpr int kNBW = (kMT + kWavesPerWG - 1) / kWavesPerWG; // column blocks per wave (at most)
-  // apply
-  static constexpr int kDQ = D / kWavesPerWG;         // output channels per wave
+};
+
+// apply: W waves per workgroup (4 or 8), wave w produces output channels [w d/W, (w+1) d/W)
+template <int D, int W> struct ApplyWideShape {
+  static_assert(kTile % W == 0 && D % (4 * W) == 0, "output channels split evenly, two per 32-bit word per half-wave");
+  static constexpr int kCPR = D / 8;                  // 16-byte chunks per token row
+  static constexpr int kDQ = D / W;                   // output channels per wave
   static constexpr int kHalf = kDQ / 2;               // ... per half-wave
   static constexpr int kMT2 = (kHalf + 2 + 15) / 16;  // 32-row output tiles incl. the two normalizer rows
   static constexpr int kKS = D / 16;                  // contraction steps of 16 channels
-  static constexpr int kRPR = kTile / kWavesPerWG;    // token rows per wave region
+  static constexpr int kRPR = kTile / W;              // token rows per wave region
   static constexpr int kRegionChunks = kRPR * kCPR;
-  static constexpr int kNLA = (kRegionChunks + 63) / 64;   // apply: copies / stores per wave per tile
+  static constexpr int kNLA = (kRegionChunks + 63) / 64;   // copies / stores per wave per tile
   static constexpr int kRegionBytes = kNLA * 1024;
   static constexpr int kRing = 3;
-  static constexpr int kSlotBytes = kWavesPerWG * kRegionBytes;
+  static constexpr int kSlotBytes = W * kRegionBytes;
   // rotation of the chunks inside a token row that makes token-per-lane accesses bank-conflict free
   static constexpr int kG = (kCPR % 16 == 0) ? 16 : ((kCPR % 8 == 0) ? 8 : ((kCPR % 4 == 0) ? 4 : 2));
   static_assert(kCPR % 2 == 0 && kRPR * kG >= 16, "rotation classes must fit a region");
@@ -42,9 +47,9 @@ constexpr int reduce16_wide_lds_bytes() {
   return 2 * (NSplit<T>::value + 1) * ShapeWide<D>::kTileElems * 2;   // double-buffered phi(K) levels + V
 }
 // ring of tiles, plus (bf16) one slot-sized buffer for the low halves of phi(Q) of the current tile
-template <typename T, int D>
+template <typename T, int D, int W>
 constexpr int apply16_wide_lds_bytes() {
-  return (ShapeWide<D>::kRing + (NSplit<T>::value == 2 ? 1 : 0)) * ShapeWide<D>::kSlotBytes;
+  return (ApplyWideShape<D, W>::kRing + (NSplit<T>::value == 2 ? 1 : 0)) * ApplyWideShape<D, W>::kSlotBytes;
 }
 
 // ==========================================================================================
@@ -57,7 +62,7 @@ constexpr int apply16_wide_lds_bytes() {
 // Partial: S as [D][D] row-major then z, fp32; each wave writes its own columns.
 // ==========================================================================================
 template <typename T, int D, int FM>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, 2)   // two workgroups per CU: one multiplies while the other loads
 state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, HeadSubset hs,
                     float* __restrict__ partials, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -208,35 +213,36 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
 // Operand-ready state.  The apply kernel multiplies by S'^T = alpha_S S^T (and the normalizer rows
 // alpha_z z) as 16-bit matrix-core A operands; building them from the fp32 state costs a pass over d*d + d
 // floats, far too much to repeat in every apply workgroup at these widths.  pack_state_wide does it once
-// per head: grid = (d / 16, heads), block = 256.  Every workgroup finds the maxima (power-of-two scales so
+// per head: grid = (d / 16, heads), block = 64 W (W = the apply kernel's waves).  Every workgroup finds the maxima (power-of-two scales so
 // that 16-bit storage neither overflows nor loses small entries), workgroup s then writes the operands of
-// contraction step s for all four apply waves, in the order the apply lanes load them:
+// contraction step s for all W apply waves, in the order the apply lanes load them:
 //   header  {c1 = alpha_z / alpha_S, alpha_z}, then  frag[level][wave][t][s][lane] (16 bytes each)
 // Operand (wave w, tile t, step s), lane l: m = l % 32, kg = l / 32, element j:
 //   contraction channel ch = 16 s + 8 kg + j;  slot = 16 t + 4 (m / 8) + m % 4,  half hv = (m / 4) % 2
-//   slot <  d/8   -> S'[ch][w d/4 + hv d/8 + slot];   slot == d/8 -> z'[ch] rounded to 16 bits;
-//   slot == d/8+1 -> the remainder of z'[ch] after that rounding;  else 0.
+//   h = d / (2 W):  slot < h -> S'[ch][w d/W + hv h + slot];   slot == h -> z'[ch] rounded to 16 bits;
+//   slot == h+1 -> the remainder of z'[ch] after that rounding;  else 0.
 // Level 1 (bf16 only) holds the remainders of the S' entries after rounding (hi + lo operands).
 // ==========================================================================================
-template <typename T, int D> struct PackWide {
-  using Sw = ShapeWide<D>;
+template <typename T, int D, int W> struct PackWide {
+  using Sw = ApplyWideShape<D, W>;
   static constexpr int kHeaderBytes = 256;
-  static constexpr int kFrags = NSplit<T>::value * kWavesPerWG * Sw::kMT2 * Sw::kKS;   // per lane
+  static constexpr int kFrags = NSplit<T>::value * W * Sw::kMT2 * Sw::kKS;   // per lane
   static constexpr int kHeadBytes = kHeaderBytes + kFrags * 64 * 16;
 };
 
-template <typename T, int D>
-__global__ void __launch_bounds__(kThreads)
+template <typename T, int D, int W>
+__global__ void __launch_bounds__(64 * W)
 pack_state_wide(const float* __restrict__ state, unsigned char* __restrict__ packed, int normalize) {
-  using Sw = ShapeWide<D>;
+  using Sw = ApplyWideShape<D, W>;
   constexpr int NS = NSplit<T>::value, KS = Sw::kKS, MT2 = Sw::kMT2, HALF = Sw::kHalf, DQ = Sw::kDQ, NE = D * D + D;
+  constexpr int kThreads = 64 * W, kWavesPerWG = W;   // this kernel's own workgroup shape
   __shared__ float redmax[2 * kWavesPerWG];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int s = blockIdx.x;
   const long long bh = blockIdx.y;
   const float* st = state + bh * NE;
-  unsigned char* out = packed + bh * PackWide<T, D>::kHeadBytes;
+  unsigned char* out = packed + bh * PackWide<T, D, W>::kHeadBytes;
 
   float mS = 0.0f, mz = 0.0f;
   const f32x4* st4 = reinterpret_cast<const f32x4*>(st);
@@ -263,7 +269,7 @@ pack_state_wide(const float* __restrict__ state, unsigned char* __restrict__ pac
     scales[1] = az;
   }
 
-  u32x4* frag = reinterpret_cast<u32x4*>(out + PackWide<T, D>::kHeaderBytes);
+  u32x4* frag = reinterpret_cast<u32x4*>(out + PackWide<T, D, W>::kHeaderBytes);
   const int m = lane & 31, kg = lane >> 5;
   const int hv = (m >> 2) & 1;
 #pragma unroll
@@ -295,21 +301,22 @@ pack_state_wide(const float* __restrict__ state, unsigned char* __restrict__ pac
 }
 
 // ==========================================================================================
-// Apply + normalize.  grid = (wgs, heads), block = 256.  The LDS-DMA ring of apply16_dma with workgroup-wide
-// slots: wave w copies in (and later stores) token rows 8w..8w+7 of a tile, whole rows, and applies phi to
+// Apply + normalize.  grid = (wgs, heads), block = 64 W (W = 4 or 8 waves).  The LDS-DMA ring of apply16_dma with workgroup-wide
+// slots: wave w copies in (and later stores) token rows (32/W) w .. of a tile, whole rows, and applies phi to
 // them in place once they have landed (each element once per workgroup; bf16 keeps the low halves of the
 // hi + lo operands in a buffer of their own).  Every wave then reads the whole tile as matrix-core B
-// operands and -- after a barrier, since all waves read all channels -- overwrites its own d/4 output
+// operands and -- after a barrier, since all waves read all channels -- overwrites its own d/W output
 // channels of every token in place.  Per wave the
-// products are those of apply16_dma for a head whose state has only this wave's d/4 columns (plus the two
+// products are those of apply16_dma for a head whose state has only this wave's d/W columns (plus the two
 // normalizer rows, which every wave carries).  Pipelined as the row-piece kernel: store tile j-1, copy tile
 // j+2, read tile j, barrier, compute and write back, wait for own rows of tile j+1 and apply phi to them,
 // barrier.
 // The state arrives operand-ready from pack_state_wide: the prologue is a handful of coalesced loads.
 // ==========================================================================================
-template <typename T, int D, int FM, bool NORM>
+template <typename T, int D, int FM, bool NORM, int W>
 struct ApplyWide {
-  using Sw = ShapeWide<D>;
+  using Sw = ApplyWideShape<D, W>;
+  static constexpr int kWavesPerWG = W;   // this kernel's own workgroup shape
   static constexpr int NS = NSplit<T>::value;
   static constexpr int CPR = Sw::kCPR, KS = Sw::kKS, MT2 = Sw::kMT2, HALF = Sw::kHalf, DQ = Sw::kDQ;
   static constexpr int NL = Sw::kNLA, NE = D * D + D, R = Sw::kRing, RPR = Sw::kRPR;
@@ -383,7 +390,7 @@ struct ApplyWide {
 
   // `packed`: this head's operands as pack_state_wide wrote them
   LF_DEV void load_packed(const unsigned char* packed, float eps) {
-    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + PackWide<T, D>::kHeaderBytes);
+    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + PackWide<T, D, W>::kHeaderBytes);
 #pragma unroll
     for (int l = 0; l < NS; ++l)
 #pragma unroll
@@ -520,16 +527,16 @@ struct ApplyWide {
   }
 };
 
-template <typename T, int D, int FM, bool NORM>
-__global__ void __launch_bounds__(kThreads)
+template <typename T, int D, int FM, bool NORM, int W>
+__global__ void __launch_bounds__(64 * W)
 apply16_wide(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, HeadSubset hs,
              const unsigned char* __restrict__ packed, float eps, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const long long bh = hs.bh(blockIdx.y, lq.H);
-  ApplyWide<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
+  ApplyWide<T, D, FM, NORM, W> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
                                gridDim.x, smem);
   ap.prefetch();
-  ap.load_packed(packed + bh * PackWide<T, D>::kHeadBytes, eps);
+  ap.load_packed(packed + bh * PackWide<T, D, W>::kHeadBytes, eps);
   ap.stream();
 }
 

@@ -19,6 +19,7 @@ struct WideArgs {
   float *partials, *state;    // [B*H][splits][d*d + d] and [B*H][d*d + d], fp32
   unsigned char* packed;      // wide_packed_bytes(d, dtype) per head: the state as apply operands
   int splits, blk_reduce, apply_wgs, blk_apply;
+  int apply_waves;            // waves per apply workgroup: 4 or 8
   hipStream_t st;
   hipEvent_t* ev;             // null, or four events: before reduce, after it, after combine, after apply
 };

@@ -465,7 +465,8 @@ int dispatch(int d, int dtype, const Args& a) {
     lfw::WideArgs w{a.q, a.k, a.v, a.out, (int)(a.BH / a.lkv.H), a.lkv.H, a.N, d, dtype, a.fm, a.eps, a.unnorm,
                     a.lq, a.lkv, a.lo, reinterpret_cast<float*>(a.ws),
                     a.state_out ? a.state_out : reinterpret_cast<float*>(a.ws + p.ws_partials),
-                    a.ws + p.ws_partials + p.ws_state, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, a.st, a.ev};
+                    a.ws + p.ws_partials + p.ws_state, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply,
+                    env_int("LINFUSION_WIDE_APPLY_WAVES", dtype == LINFUSION_DTYPE_BF16 ? 8 : 4) == 8 ? 8 : 4, a.st, a.ev};
     return lfw::run_wide(w);
   }
   switch (dtype) {

@@ -51,20 +51,25 @@ int run(const WideArgs& a) {
       a.partials, a.splits, NE, a.state);
   if (a.ev) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
-    pack_state_wide<T, D><<<dim3(ShapeWide<D>::kKS, (unsigned)BH), blk, 0, st>>>(a.state, a.packed, a.unnorm ? 0 : 1);
-    constexpr int lds2 = apply16_wide_lds_bytes<T, D>();
     const dim3 g2(a.apply_wgs, (unsigned)BH);
-#define LFW_APPLY(FM, NORM)                                                                   \
-  {                                                                                           \
-    if (!allow_lds(apply16_wide<T, D, FM, NORM>, lds2)) return LINFUSION_ERR_HIP;             \
-    apply16_wide<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, a.N, a.blk_apply); \
+#define LFW_APPLY_W(FM, NORM, WW)                                                                            \
+  {                                                                                                          \
+    constexpr int lds2 = apply16_wide_lds_bytes<T, D, WW>();                                                 \
+    if (!allow_lds(apply16_wide<T, D, FM, NORM, WW>, lds2)) return LINFUSION_ERR_HIP;                        \
+    pack_state_wide<T, D, WW><<<dim3(ApplyWideShape<D, WW>::kKS, (unsigned)BH), dim3(64 * WW), 0, st>>>(     \
+        a.state, a.packed, NORM ? 1 : 0);                                                                    \
+    apply16_wide<T, D, FM, NORM, WW><<<g2, dim3(64 * WW), lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, \
+                                                                      a.N, a.blk_apply);                     \
   }
+#define LFW_APPLY(FM, NORM) \
+  if (a.apply_waves == 8) LFW_APPLY_W(FM, NORM, 8) else LFW_APPLY_W(FM, NORM, 4)
     switch (a.fm) {
-      case 0: if (a.unnorm) LFW_APPLY(0, false) else LFW_APPLY(0, true) break;
-      case 1: if (a.unnorm) LFW_APPLY(1, false) else LFW_APPLY(1, true) break;
-      default: if (a.unnorm) LFW_APPLY(2, false) else LFW_APPLY(2, true) break;
+      case 0: if (a.unnorm) { LFW_APPLY(0, false) } else { LFW_APPLY(0, true) } break;
+      case 1: if (a.unnorm) { LFW_APPLY(1, false) } else { LFW_APPLY(1, true) } break;
+      default: if (a.unnorm) { LFW_APPLY(2, false) } else { LFW_APPLY(2, true) } break;
     }
 #undef LFW_APPLY
+#undef LFW_APPLY_W
   }
   if (a.ev) (void)hipEventRecord(a.ev[3], st);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
@@ -73,6 +78,13 @@ int run(const WideArgs& a) {
 }  // namespace
 
 #define LFW_FOR_D(X) X(160)
+
+// room for either workgroup shape of the apply kernel
+template <typename T, int D>
+constexpr size_t pack_bytes() {
+  return lf::PackWide<T, D, 4>::kHeadBytes > lf::PackWide<T, D, 8>::kHeadBytes ? lf::PackWide<T, D, 4>::kHeadBytes
+                                                                               : lf::PackWide<T, D, 8>::kHeadBytes;
+}
 
 bool wide_supported(int d) {
   switch (d) {
@@ -87,7 +99,7 @@ bool wide_supported(int d) {
 size_t wide_packed_bytes(int d, int dtype) {
   switch (d) {
 #define X(DD) \
-  case DD: return dtype == LINFUSION_DTYPE_F16 ? lf::PackWide<lf::F16, DD>::kHeadBytes : lf::PackWide<lf::BF16, DD>::kHeadBytes;
+  case DD: return dtype == LINFUSION_DTYPE_F16 ? pack_bytes<lf::F16, DD>() : pack_bytes<lf::BF16, DD>();
     LFW_FOR_D(X)
 #undef X
   }
