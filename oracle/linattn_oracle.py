@@ -35,6 +35,12 @@ equal to one, row-stochastic weights, Prop. 1 (constant V), joint K/V permutatio
 token-tiling invariance, the Kronecker identity from the proof of Prop. 2, affine
 equivariance, the d = 1 weighted mean, all-equal K = plain mean, IDENTITY phi = two library
 GEMMs, and a mutant check showing that planted mistakes are caught.
+Backward pass (needed by the distillation of Sec. 3.4, Eq. 8; the paper gives no formula, so the
+definition is the derivative of the forward definition): `attention_backward_quadratic` differentiates
+the quadratic form with the n x n weights written out, `attention_backward_linear` is the same gradient
+reordered through the d x d states (S, z, dS, dz) and is what large-N parity tests call.  Pins
+(tests/test_oracle_backward.py): central differences of `attention_quadratic`, agreement of the two
+forms, dV column sums, orthogonality of d phi(q) to phi(q) at eps = 0, linearity in the upstream gradient.
 Unpinned: that elu(x)+1 is the activation the authors trained with (their figure naming it
 is not in the text available to this build) -- "parity unpinned" for that choice only.
 """
@@ -185,6 +191,83 @@ def attention_linear_stored(q, k, v, dtype: str, feature_map: int = ELU_PLUS_ONE
     """Same, on stored tensors: the oracle sees exactly the quantised inputs the GPU sees."""
     return attention_linear(widen(q, dtype), widen(k, dtype), widen(v, dtype),
                             feature_map, eps, normalize)
+
+
+# ----------------------------------------------------------------------------------------
+# Backward pass: gradients of a scalar loss L with respect to q, k, v, given g = dL/d out.
+# ----------------------------------------------------------------------------------------
+def phi_prime(x, feature_map: int = ELU_PLUS_ONE) -> np.ndarray:
+    """d phi / dx, elementwise (one-sided value 1 at x = 0 for elu+1, 0 for relu)."""
+    x = np.asarray(x, dtype=np.float64)
+    if feature_map == ELU_PLUS_ONE:
+        return np.where(x > 0.0, 1.0, np.exp(np.minimum(x, 0.0)))
+    if feature_map == RELU:
+        return np.where(x > 0.0, 1.0, 0.0)
+    if feature_map == IDENTITY:
+        return np.ones_like(x)
+    raise ValueError(f"unknown feature_map {feature_map!r}")
+
+
+def attention_backward_quadratic(q, k, v, g, feature_map: int = ELU_PLUS_ONE, eps: float = 0.0,
+                                 normalize: bool = True):
+    """Derivative of the quadratic form, one head, with the n x n matrices written out.
+    out_i = sum_j w_ij v_j,  w_ij = a_ij / den_i,  a_ij = r_i . p_j,  den_i = sum_j a_ij + eps:
+        dv_j  = sum_i w_ij g_i
+        da_ij = (g_i . v_j - g_i . out_i) / den_i          (normalized; g_i . v_j otherwise)
+        dr_i  = sum_j da_ij p_j ,  dp_j = sum_i da_ij r_i ,  dq = dr * phi'(q) ,  dk = dp * phi'(k)
+    Returns (dq, dk, dv).  O(N^2 d): small N only."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    r = phi(q, feature_map)
+    p = phi(k, feature_map)
+    a = r @ p.T                                   # [n_q, n_k]
+    gv = g @ v.T                                  # g_i . v_j
+    if normalize:
+        den = a.sum(axis=1) + eps
+        w = a / den[:, None]
+        out = w @ v
+        da = (gv - (g * out).sum(axis=1)[:, None]) / den[:, None]
+    else:
+        w = a
+        da = gv
+    dv = w.T @ g
+    dr = da @ p
+    dp = da.T @ r
+    return dr * phi_prime(q, feature_map), dp * phi_prime(k, feature_map), dv
+
+
+def attention_backward_linear(q, k, v, g, feature_map: int = ELU_PLUS_ONE, eps: float = 0.0,
+                              normalize: bool = True):
+    """The same gradient with every sum over tokens taken through a d x d (or d) state:
+        S = P^T V, z = P^T 1;  den = R z + eps;  out = R S / den
+        gn_i = g_i / den_i ;  e_i = -(g_i . out_i) / den_i        (gn = g, e = 0 if not normalized)
+        dS = R^T gn ,  dz = R^T e
+        dr = gn S^T + e z^T ;  dp = V dS^T + 1 dz^T ;  dv = P dS
+    One head; O(N d^2)."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    r = phi(q, feature_map)
+    p = phi(k, feature_map)
+    S = p.T @ v
+    z = p.sum(axis=0)
+    if normalize:
+        den = r @ z + eps
+        out = (r @ S) / den[:, None]
+        gn = g / den[:, None]
+        e = -(g * out).sum(axis=1) / den
+    else:
+        gn = g
+        e = np.zeros(q.shape[0], dtype=np.float64)
+    dS = r.T @ gn
+    dz = r.T @ e
+    dr = gn @ S.T + e[:, None] * z[None, :]
+    dp = v @ dS.T + dz[None, :]
+    dv = p @ dS
+    return dr * phi_prime(q, feature_map), dp * phi_prime(k, feature_map), dv
 
 
 # ----------------------------------------------------------------------------------------
