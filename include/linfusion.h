@@ -141,6 +141,37 @@ int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void
                                void* events[4]);
 
 /*
+ * Backward pass of the mixer: gradients of a scalar loss with respect to q, k and v, given
+ * dout = d loss / d out.  (Training by distillation, Sec. 3.4, Eq. 8, differentiates through every
+ * LinFusion module; the paper gives no formula, so the operation is defined as the derivative of the
+ * forward definition above.)  With P = phi(K), R = phi(Q), S = P^T V, z = P^T 1, den_i = r_i . z + eps:
+ *
+ *     u_i = S dout_i ,  go_i = (r_i . u_i) / den_i            (= dout_i . out_i)
+ *     dq_i = ((u_i - go_i z) / den_i) * phi'(q_i)
+ *     dS = sum_i r_i^T (dout_i / den_i) ,  dz = -sum_i r_i go_i / den_i
+ *     dk_j = (dS v_j + dz) * phi'(k_j) ,   dv_j = dS^T p_j
+ *
+ * (LINFUSION_FLAG_UNNORMALIZED: den = 1, go = 0.)  phi' at 0 is the one-sided value 1 for elu+1 and 0
+ * for relu.  The forward output is not an input: dout . out is recomputed in fp32.
+ *
+ *   q, k, v, dout   DEVICE pointers, contiguous [B, H, N, d], fp16 or bf16 (LINFUSION_DTYPE_F32 ->
+ *                   LINFUSION_ERR_UNSUPPORTED), d in {8, ..., 64 step 8, 80}.
+ *   dq, dk, dv      DEVICE pointers, same shape and type; must not overlap any input or each other.
+ *   flags           LINFUSION_FLAG_NONE or LINFUSION_FLAG_UNNORMALIZED (anything else -> ERR_INVALID).
+ *   workspace       DEVICE scratch of at least linfusion_attn_bwd_workspace_bytes(...) bytes, 16-byte
+ *                   aligned, caller-owned, contents undefined before and after.
+ * Enqueues six kernels on `stream`; never allocates, never synchronises.  Results are run-to-run identical.
+ */
+int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* dout,
+                       void* dq, void* dk, void* dv,
+                       int B, int H, long long N, int d,
+                       int dtype, int feature_map, float eps, unsigned flags,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of device scratch linfusion_attn_bwd needs; pure host function; 0 for rejected arguments. */
+size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int dtype);
+
+/*
  * Synchronises `stream` and reports whether the most recent single-launch call that used this
  * workspace for this shape completed: LINFUSION_OK, LINFUSION_ERR_TIMEOUT, or an argument / HIP
  * error code.  (The split path cannot time out; after it this returns LINFUSION_OK.)

@@ -1,0 +1,633 @@
+// Backward pass of the token mixer for fp16 / bf16, head widths up to 80 (training by distillation, Sec. 3.4,
+// Eq. 8, needs it; the paper gives no formula -- these are the derivatives of Eq. 5 on Prop. 2's form).
+// With P = phi(K), R = phi(Q), S = P^T V, z = P^T 1, den = R z + eps, out = R S / den and g = dL/d out:
+//     u_i  = S g_i                      (d-vector per token)
+//     go_i = (r_i . u_i) / den_i        (= g_i . out_i, recomputed in fp32 instead of read back in 16 bits)
+//     dr_i = (u_i - go_i z) / den_i ,   dq = dr * phi'(q)
+//     e_i  = -go_i / den_i ,            dS = R^T (g / den) ,  dz = R^T e
+//     dp_j = dS v_j + dz ,              dk = dp * phi'(k) ,   dv_j = dS^T p_j
+// (un-normalized: den = 1, go = e = 0).  Five launches:
+//     state_reduce16 + combine_state    S, z                         (the forward kernels)
+//     bwd_q16                           reads Q, g: writes dQ and per token {1 / den_i, e_i}
+//     bwd_state16 + combine_state       reads Q, g and those scalars: dS, dz
+//     bwd_kv16                          reads K, V: writes dK, dV
+// The two apply-shaped kernels use the LDS-DMA ring of apply16_dma with two tensors per slot; the
+// reduction is state_reduce16 with phi(Q) in the place of phi(K), g / den in the place of V and e_i in the
+// place of the ones column.  Contiguous [B, H, N, d] tensors only.
+#pragma once
+#include "lf_apply16_dma.hpp"
+
+namespace lf {
+
+template <int FM>
+LF_DEV float phi_prime_from(float x, float phi_x) {   // d phi / dx given x and phi(x)
+  if constexpr (FM == kPhiEluPlusOne) return x > 0.0f ? 1.0f : phi_x;
+  else if constexpr (FM == kPhiRelu) return x > 0.0f ? 1.0f : 0.0f;
+  else return 1.0f;
+}
+
+template <int D> struct BwdCfg {
+  using Sh = Shape16<D>;
+  using AC = ApplyDmaCfg<D>;
+  static constexpr int kNL = AC::kNL;
+  static constexpr int kTileBytes = AC::kSlotBytes;              // one tensor's tile (whole 1 KiB deposits)
+  static constexpr int kSlotBytes = 2 * kTileBytes;              // two tensors per ring slot
+  static constexpr int kRing = 3;
+  static constexpr int kStageOffset = (kRing - 1) * kWavesPerWG * kSlotBytes;
+  static constexpr int kStageBytes = (D * D + D) * 4 + 64;
+  static constexpr int kMTB = (Sh::kHalf + 15) / 16;            // 32-row output tiles (no normalizer rows)
+  static constexpr int lds_bytes() {
+    int ring = kRing * kWavesPerWG * kSlotBytes, st = kStageOffset + kStageBytes;
+    return ring > st ? ring : st;
+  }
+};
+
+// ---- two-tensor LDS-DMA ring, one wave per tile (see apply16_dma for the mechanism) -----------------
+template <typename T, int D>
+struct Ring2 {
+  using Sh = Shape16<D>;
+  using AC = ApplyDmaCfg<D>;
+  using BC = BwdCfg<D>;
+  static constexpr int NS = NSplit<T>::value;
+  static constexpr int KS = Sh::kKS, CPR = Sh::kChunksPerRow, HALF = Sh::kHalf, MTB = BC::kMTB;
+  static constexpr int NL = BC::kNL, NE = D * D + D, R = BC::kRing, TB = BC::kTileBytes;
+  static_assert(R == 3, "the wait counts are written for a ring of three slots");
+
+  const u32x4 *Xh, *Yh;
+  long long N;
+  unsigned char* smem;
+  int lane, wave, tok, kg, row_byte, tsw;
+  int trow[NL], goff[NL];
+  TileIter it, ahead;
+
+  LF_DEV Ring2(const u32x4* Xh_, const u32x4* Yh_, long long N_, int tiles_per_block, int wg, int nwg,
+               unsigned char* smem_)
+      : Xh(Xh_), Yh(Yh_), N(N_), smem(smem_), lane(threadIdx.x & 63),
+        wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
+        it(wg, nwg, wave, tiles_per_block, (N_ + kTile - 1) / kTile), ahead(it) {
+    tok = lane & 31;
+    kg = lane >> 5;
+    row_byte = tok * AC::kRowBytes;
+    tsw = AC::swz(tok);
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const int p = u * 64 + lane;
+      const int r = p / CPR, pos = p % CPR;
+      trow[u] = r;
+      goff[u] = r * CPR + (pos ^ AC::swz(r));
+    }
+  }
+
+  LF_DEV unsigned char* tile_ptr(int slot, int which) const {
+    return smem + (slot * kWavesPerWG + wave) * BC::kSlotBytes + which * TB;
+  }
+  LF_DEV unsigned char* chunk_ptr(int slot, int which, int chunk) const {
+    return tile_ptr(slot, which) + row_byte + ((chunk ^ tsw) << 4);
+  }
+  // pointer to byte `byte` of this lane's token row (pieces never straddle a 16-byte chunk)
+  LF_DEV unsigned char* byte_ptr(int slot, int which, int byte) const {
+    return chunk_ptr(slot, which, byte >> 4) + (byte & 15);
+  }
+
+  // copies tile `tile` of both tensors into ring slot `slot`: always 2 NL vector memory instructions
+  LF_DEV void issue_copy(long long tile, int slot) {
+    long long rem = N - tile * kTile;
+    const int lim = rem < kTile ? (int)rem : kTile;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+      const u32x4* gp = (which ? Yh : Xh) + tile * AC::kChunks;
+      unsigned char* sl = tile_ptr(slot, which);
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        if (u * 64 + lane < AC::kChunks) {
+          const int c = trow[u] < lim ? goff[u] : 0;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gp + c),
+                                           (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
+        }
+      }
+    }
+  }
+  LF_DEV void prefetch() {
+    if (ahead.valid()) issue_copy(ahead.t, 0);
+    ahead.next();
+    if (ahead.valid()) issue_copy(ahead.t, 1);
+    ahead.next();
+  }
+  // coalesced stores of tile part `which` of slot `slot` to head tensor `Oh`: always NL instructions
+  LF_DEV void store_tile(long long tile, int slot, int which, u32x4* Oh) {
+    const unsigned char* sl = tile_ptr(slot, which);
+    long long rem = N - tile * kTile;
+    const int lim = rem < kTile ? (int)rem : kTile;
+    u32x4* op = Oh + tile * AC::kChunks;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const u32x4 w = *reinterpret_cast<const u32x4*>(sl + u * 1024 + lane * 16);
+      if (u * 64 + lane < AC::kChunks && trow[u] < lim) st_stream(op + goff[u], w);
+    }
+  }
+  // waits until the copies of the tile that is about to be used have landed; `iter` = tiles done so far
+  // (0, 1, 2 = two or more), `more` = a copy was issued this iteration, SN = store instructions per tile
+  template <int SN>
+  LF_DEV void wait_tile(int iter, bool more) {
+    if (!more) { wait_vmcnt<0>(); return; }
+    if (iter == 0) wait_vmcnt<4 * NL>();
+    else if (iter == 1) wait_vmcnt<4 * NL + SN>();
+    else wait_vmcnt<4 * NL + 2 * SN>();
+  }
+
+  // Stages one head's fp32 state ([D*D] matrix then [D] vector) in LDS and returns the power-of-two scale
+  // for the matrix.  The staging area starts at the third slot block (free before the stream loop).
+  LF_DEV float stage_state(const float* state) {
+    float* st = reinterpret_cast<float*>(smem + BC::kStageOffset);
+    float* redmax = st + NE;
+    float mS = 0.0f;
+    for (int e = threadIdx.x; e < NE / 4; e += kThreads) {
+      const f32x4 x = reinterpret_cast<const f32x4*>(state)[e];
+      reinterpret_cast<f32x4*>(st)[e] = x;
+      if (e < D * D / 4) mS = fmaxf(mS, fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3]))));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mS = fmaxf(mS, __shfl_xor(mS, o));
+    if (lane == 0) redmax[wave] = mS;
+    __syncthreads();
+    mS = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerWG; ++w) mS = fmaxf(mS, redmax[w]);
+    return pow2_scale_for(mS);
+  }
+  // A operands of the staged matrix M scaled by aS, for products  out[o] = sum_c M'[.][.] b[c]  over the
+  // contraction index c = input channel of the B operand and o = this lane-half's output channels:
+  //   TRANSPOSED = false: element M[o][c]   (out = M b);   TRANSPOSED = true: element M[c][o]  (out = M^T b)
+  template <bool TRANSPOSED>
+  LF_DEV void build_A(float aS, u32x4 (&A)[NS][MTB][KS]) const {
+    const float* st = reinterpret_cast<const float*>(smem + BC::kStageOffset);
+    const int m = lane & 31;
+    const int hv = (m >> 2) & 1;
+#pragma unroll
+    for (int t = 0; t < MTB; ++t) {
+      const int slot = 16 * t + 4 * (m >> 3) + (m & 3);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const int chunk = kg * KS + s;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float hi2[2], lo2[2];
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int c = chunk * 8 + 2 * w + q;
+            const int o = hv * HALF + slot;
+            float x = 0.0f;
+            if (chunk < CPR && slot < HALF) x = (TRANSPOSED ? st[c * D + o] : st[o * D + c]) * aS;
+            float r0, r1;
+            unpack2<T>(pack2<T>(x, 0.0f), r0, r1);
+            hi2[q] = x;
+            lo2[q] = x - r0;
+          }
+          A[0][t][s][w] = pack2<T>(hi2[0], hi2[1]);
+          if constexpr (NS == 2) A[1][t][s][w] = pack2<T>(lo2[0], lo2[1]);
+        }
+      }
+    }
+  }
+  // the staged vector at this lane-half's output channels
+  LF_DEV void load_vec(float (&v)[HALF]) const {
+    const float* st = reinterpret_cast<const float*>(smem + BC::kStageOffset) + D * D;
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) v[i] = st[kg * HALF + i];
+  }
+  // this lane's HALF channels (lane-half kg) of its token's row in tile part `which`, widened to fp32
+  LF_DEV void read_half_row(int slot, int which, float (&x)[HALF]) const {
+    constexpr int PB = (HALF % 8 == 0) ? 16 : 8;   // piece bytes (HALF is a multiple of 4)
+#pragma unroll
+    for (int c = 0; c < HALF * 2 / PB; ++c) {
+      const unsigned char* p = byte_ptr(slot, which, kg * HALF * 2 + c * PB);
+      uint32_t w[PB / 4];
+      if constexpr (PB == 16) {
+        const u32x4 t = *reinterpret_cast<const u32x4*>(p);
+        w[0] = t[0]; w[1] = t[1]; w[2] = t[2]; w[3] = t[3];
+      } else {
+        const u32x2 t = *reinterpret_cast<const u32x2*>(p);
+        w[0] = t[0]; w[1] = t[1];
+      }
+#pragma unroll
+      for (int e = 0; e < PB / 4; ++e) unpack2<T>(w[e], x[c * (PB / 2) + 2 * e], x[c * (PB / 2) + 2 * e + 1]);
+    }
+  }
+  LF_DEV void write_half_row(int slot, int which, const float (&x)[HALF]) const {
+    constexpr int PB = (HALF % 8 == 0) ? 16 : 8;
+#pragma unroll
+    for (int c = 0; c < HALF * 2 / PB; ++c) {
+      unsigned char* p = byte_ptr(slot, which, kg * HALF * 2 + c * PB);
+      uint32_t w[PB / 4];
+#pragma unroll
+      for (int e = 0; e < PB / 4; ++e) w[e] = pack2<T>(x[c * (PB / 2) + 2 * e], x[c * (PB / 2) + 2 * e + 1]);
+      if constexpr (PB == 16) *reinterpret_cast<u32x4*>(p) = u32x4{w[0], w[1], w[2], w[3]};
+      else *reinterpret_cast<u32x2*>(p) = u32x2{w[0], w[1]};
+    }
+  }
+  // B operands: this lane's input chunks of its token's row, raw 16-bit values
+  LF_DEV void read_B_raw(int slot, int which, u32x4 (&B)[KS]) const {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int chunk = kg * KS + s;
+      B[s] = u32x4{0, 0, 0, 0};
+      if (chunk < CPR) B[s] = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, which, chunk));
+    }
+  }
+  // acc[t] = sum_s A[.][t][s] * B[s]   (b_lo: low halves of a split B operand, or null)
+  LF_DEV void products(const u32x4 (&A)[NS][MTB][KS], const u32x4 (&Bh)[KS], const u32x4* Bl, f32x16 (&acc)[MTB]) const {
+#pragma unroll
+    for (int t = 0; t < MTB; ++t) {
+      acc[t] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        acc[t] = mfma_32x32x16<T>(A[0][t][s], Bh[s], acc[t]);
+        if constexpr (NS == 2) {
+          acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);
+          if (Bl) acc[t] = mfma_32x32x16<T>(A[0][t][s], Bl[s], acc[t]);
+        }
+      }
+    }
+  }
+};
+
+// ==========================================================================================
+// bwd_q16: dQ and the per-token scalars.  grid = (wgs, B*H), block = 256, dynamic LDS BwdCfg<D>::lds_bytes().
+// `scal`: [B*H][N] pairs {1 / den_i, e_i} (written only when NORM).
+// ==========================================================================================
+template <typename T, int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+bwd_q16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __restrict__ dQ,
+        const float* __restrict__ state, f32x2* __restrict__ scal, float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using RG = Ring2<T, D>;
+  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
+  constexpr int SN = NL + (NORM ? 1 : 0);
+  const long long bh = blockIdx.y;
+  const long long hoff = bh * N * CPR;
+  RG rg(Q + hoff, G + hoff, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  u32x4* dQh = dQ + hoff;
+  f32x2* sh = scal + bh * N;
+  rg.prefetch();
+
+  const float aS = rg.stage_state(state + bh * (D * D + D));
+  u32x4 A[NS][MTB][KS];
+  rg.template build_A<false>(aS, A);       // u = S g
+  float zo[HALF];
+  rg.load_vec(zo);
+  const float inv_aS = 1.0f / aS;
+  __syncthreads();                          // the staged state is dead
+
+  int slot = 0, iter = 0;
+  while (rg.it.valid()) {
+    const long long tile = rg.it.t;
+    int aslot = slot + (R - 1);
+    if (aslot >= R) aslot -= R;
+    const bool more = rg.ahead.valid();
+    if (more) rg.issue_copy(rg.ahead.t, aslot);
+    rg.template wait_tile<SN>(iter, more);
+    iter = iter < 2 ? iter + 1 : 2;
+
+    u32x4 Bg[KS];
+    rg.read_B_raw(slot, 1, Bg);
+    f32x16 acc[MTB];
+    rg.products(A, Bg, nullptr, acc);
+    float x[HALF];
+    rg.read_half_row(slot, 0, x);             // q at this lane's output channels
+    float denp = 0.0f, rup = 0.0f;
+    float dr[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const float r = phi<FM>(x[i]);
+      const float u = acc[i / 16][i % 16] * inv_aS;
+      denp = __builtin_fmaf(r, zo[i], denp);
+      rup = __builtin_fmaf(r, u, rup);
+      dr[i] = u;
+      x[i] = phi_prime_from<FM>(x[i], r);     // x now holds phi'(q)
+    }
+    if constexpr (NORM) {
+      const float den = denp + __shfl_xor(denp, 32) + eps;
+      const float ru = rup + __shfl_xor(rup, 32);
+      const float invden = 1.0f / den;
+      const float go = ru * invden;
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) dr[i] = (dr[i] - go * zo[i]) * invden * x[i];
+      long long rem = N - tile * kTile;
+      const int lim = rem < kTile ? (int)rem : kTile;
+      if (rg.kg == 0 && rg.tok < lim) sh[tile * kTile + rg.tok] = f32x2{invden, -go * invden};
+    } else {
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) dr[i] *= x[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.write_half_row(slot, 0, dr);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.store_tile(tile, slot, 0, dQh);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.it.next();
+    rg.ahead.next();
+    slot = slot + 1 == R ? 0 : slot + 1;
+  }
+}
+
+// ==========================================================================================
+// bwd_kv16: dK and dV.  grid = (wgs, B*H), block = 256.  `dstate`: [B*H][D*D + D], dS row-major then dz.
+// ==========================================================================================
+template <typename T, int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+bwd_kv16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, u32x4* __restrict__ dK, u32x4* __restrict__ dV,
+         const float* __restrict__ dstate, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using RG = Ring2<T, D>;
+  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
+  constexpr int SN = 2 * NL;
+  const long long bh = blockIdx.y;
+  const long long hoff = bh * N * CPR;
+  RG rg(K + hoff, V + hoff, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  u32x4* dKh = dK + hoff;
+  u32x4* dVh = dV + hoff;
+  rg.prefetch();
+
+  const float aS = rg.stage_state(dstate + bh * (D * D + D));
+  u32x4 A1[NS][MTB][KS], A2[NS][MTB][KS];
+  rg.template build_A<true>(aS, A1);        // dv = dS^T p
+  rg.template build_A<false>(aS, A2);       // dp = dS v (+ dz)
+  float dzo[HALF];
+  rg.load_vec(dzo);
+  const float inv_aS = 1.0f / aS;
+  __syncthreads();
+
+  int slot = 0, iter = 0;
+  while (rg.it.valid()) {
+    const long long tile = rg.it.t;
+    int aslot = slot + (R - 1);
+    if (aslot >= R) aslot -= R;
+    const bool more = rg.ahead.valid();
+    if (more) rg.issue_copy(rg.ahead.t, aslot);
+    rg.template wait_tile<SN>(iter, more);
+    iter = iter < 2 ? iter + 1 : 2;
+
+    // phi(k) of this lane's input chunks -> B operands (hi [, lo]); v raw
+    u32x4 Bp[KS], Bpl[NS == 2 ? KS : 1], Bv[KS];
+    rg.read_B_raw(slot, 0, Bp);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const bool ok = rg.kg * KS + s < CPR;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        float x0, x1;
+        unpack2<T>(Bp[s][w], x0, x1);
+        const float r0 = ok ? phi<FM>(x0) : 0.0f, r1 = ok ? phi<FM>(x1) : 0.0f;
+        if constexpr (NS == 1) {
+          Bp[s][w] = pack2<T>(r0, r1);
+        } else {
+          uint32_t h, l;
+          pack2_split<T>(r0, r1, h, l);
+          Bp[s][w] = h;
+          Bpl[s][w] = l;
+        }
+      }
+    }
+    rg.read_B_raw(slot, 1, Bv);
+    f32x16 acc1[MTB], acc2[MTB];
+    rg.products(A1, Bp, NS == 2 ? Bpl : nullptr, acc1);
+    rg.products(A2, Bv, nullptr, acc2);
+    float x[HALF], o[HALF];
+    rg.read_half_row(slot, 0, x);             // k at this lane's output channels
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const float pk = phi<FM>(x[i]);
+      x[i] = (acc2[i / 16][i % 16] * inv_aS + dzo[i]) * phi_prime_from<FM>(x[i], pk);   // dk
+      o[i] = acc1[i / 16][i % 16] * inv_aS;                                              // dv
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.write_half_row(slot, 0, x);
+    rg.write_half_row(slot, 1, o);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.store_tile(tile, slot, 0, dKh);
+    rg.store_tile(tile, slot, 1, dVh);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.it.next();
+    rg.ahead.next();
+    slot = slot + 1 == R ? 0 : slot + 1;
+  }
+}
+
+// ==========================================================================================
+// bwd_state16: dS = sum_i phi(q_i)^T (g_i / den_i),  dz = sum_i phi(q_i) e_i, as split-N partials (then
+// combine_state).  grid = (splits, B*H), block = 256.  state_reduce16's stream with the B tile built from
+// g and the scalars; the tile carries one extra 16-column block whose first column holds e_i.
+// `state`: the forward state (only z is read, for the scale beta below).
+// Partial: dS as [D][D] row-major (row = feature index of phi(q), column = channel of g), then dz.
+// ==========================================================================================
+template <int D> struct BwdReduceCfg {
+  using Sh = Shape16<D>;
+  static constexpr int kRS = Sh::kDP + 24;                       // one more 16-column block, 8 columns of padding
+  static constexpr int kTileElems = kTile * kRS;
+  static constexpr int kChunks = kTile * Sh::kChunksPerRow;
+  static constexpr int kNL = (kChunks + 63) / 64;
+};
+template <typename T, int D>
+constexpr int bwd_state_lds_bytes() {
+  int tiles = 2 * NSplit<T>::value * BwdReduceCfg<D>::kTileElems * 2 * kWavesPerWG;
+  int red = 2 * (D * D + D) * 4;
+  return tiles > red ? tiles : red;
+}
+
+template <typename T, int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+bwd_state16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, const f32x2* __restrict__ scal,
+            const float* __restrict__ state, float* __restrict__ partials, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using Sh = Shape16<D>;
+  using Cfg = BwdReduceCfg<D>;
+  constexpr int NS = NSplit<T>::value;
+  constexpr int RS = Cfg::kRS, NL = Cfg::kNL, CPR = Sh::kChunksPerRow, MT = Sh::kMT, TE = Cfg::kTileElems;
+  constexpr int NE = D * D + D;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const long long bh = blockIdx.y;
+  const u32x4* Qh = Q + bh * N * CPR;
+  const u32x4* Gh = G + bh * N * CPR;
+  const f32x2* sh = scal + bh * N;
+  float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)NE;
+
+  // g / den and e are of the order 1 / (N d): far below the fp16 normal range for large N.  Both are
+  // carried times beta, a power of two near the typical denominator (sum of z, as phi(q) is of order one),
+  // and the partial is divided by beta again (exactly) at the end.
+  float beta = 1.0f, inv_beta = 1.0f;
+  if constexpr (NORM) {
+    const float* z = state + bh * NE + D * D;
+    float zs = 0.0f;
+    for (int i = lane; i < D; i += 64) zs += z[i];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) zs += __shfl_xor(zs, o);
+    if (zs > 0.0f && zs < 3.0e38f) {
+      int ex;
+      (void)__builtin_frexpf(zs, &ex);
+      ex = ex > 100 ? 100 : (ex < -100 ? -100 : ex);
+      beta = __builtin_ldexpf(1.0f, ex);
+      inv_beta = __builtin_ldexpf(1.0f, -ex);
+    }
+  }
+
+  // per wave: NS tiles of phi(Q) then NS tiles of g / den (with the e column)
+  uint16_t* wbase = reinterpret_cast<uint16_t*>(smem) + wave * 2 * NS * TE;
+  int lds_off[NL], trow[NL], goff[NL];
+#pragma unroll
+  for (int u = 0; u < NL; ++u) {
+    const int c = u * 64 + lane;
+    trow[u] = c / CPR;
+    goff[u] = c;
+    lds_off[u] = trow[u] * RS + (c % CPR) * 8;
+  }
+  const int j16 = lane & 15, g4 = lane >> 4;
+  const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
+
+  TileIter it(blockIdx.x, gridDim.x, wave, tiles_per_block, (N + kTile - 1) / kTile);
+
+  f32x4 acc[MT][MT + 1];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int b = 0; b <= MT; ++b) acc[a][b] = f32x4{0, 0, 0, 0};
+
+  u32x4 qr[NL], gr[NL];
+  f32x2 sc[NL];
+  auto issue_loads = [&](long long tile) {
+    long long rem = N - tile * kTile;
+    int lim = rem < kTile ? (int)rem : kTile;
+    const u32x4* qp = Qh + tile * Cfg::kChunks;
+    const u32x4* gp = Gh + tile * Cfg::kChunks;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      qr[u] = u32x4{0, 0, 0, 0};
+      gr[u] = u32x4{0, 0, 0, 0};
+      sc[u] = f32x2{1.0f, 0.0f};
+      if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) {
+        qr[u] = ld_stream(qp + goff[u]);
+        gr[u] = ld_stream(gp + goff[u]);
+        if constexpr (NORM) {
+          sc[u] = sh[tile * kTile + trow[u]];
+          sc[u][0] *= beta;
+          sc[u][1] *= beta;
+        }
+      }
+    }
+    return lim;
+  };
+
+  int lim = 0;
+  if (it.valid()) lim = issue_loads(it.t);
+  for (int i = lane; i < 2 * NS * TE; i += 64) wbase[i] = 0;   // pad columns and the unused part of the extra block
+
+  while (it.valid()) {
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const int c = u * 64 + lane;
+      if (c < Cfg::kChunks) {
+        const bool ok = trow[u] < lim;
+        u32x4 ph, pl, gh, gl;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1, g0, g1;
+          unpack2<T>(qr[u][w], x0, x1);
+          unpack2<T>(gr[u][w], g0, g1);
+          const float p0 = ok ? phi<FM>(x0) : 0.0f, p1 = ok ? phi<FM>(x1) : 0.0f;
+          g0 *= sc[u][0];
+          g1 *= sc[u][0];
+          if constexpr (NS == 1) {
+            ph[w] = pack2<T>(p0, p1);
+            gh[w] = pack2<T>(g0, g1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(p0, p1, h, l);
+            ph[w] = h; pl[w] = l;
+            pack2_split<T>(g0, g1, h, l);
+            gh[w] = h; gl[w] = l;
+          }
+        }
+        *reinterpret_cast<u32x4*>(wbase + lds_off[u]) = ph;
+        *reinterpret_cast<u32x4*>(wbase + NS * TE + lds_off[u]) = gh;
+        if constexpr (NS == 2) {
+          *reinterpret_cast<u32x4*>(wbase + TE + lds_off[u]) = pl;
+          *reinterpret_cast<u32x4*>(wbase + 3 * TE + lds_off[u]) = gl;
+        }
+        if (NORM && c % CPR == 0) {   // this lane holds the first chunk of its row: it also writes e_i
+          const float e = ok ? sc[u][1] : 0.0f;
+          if constexpr (NS == 1) {
+            wbase[NS * TE + trow[u] * RS + Sh::kDP] = (uint16_t)pack2<T>(e, 0.0f);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(e, 0.0f, h, l);
+            wbase[2 * TE + trow[u] * RS + Sh::kDP] = (uint16_t)h;
+            wbase[3 * TE + trow[u] * RS + Sh::kDP] = (uint16_t)l;
+          }
+        }
+      }
+    }
+    it.next();
+    int next_lim = 0;
+    if (it.valid()) next_lim = issue_loads(it.t);
+
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    u32x4 bfrag[NS][MT + 1];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int b = 0; b <= MT; ++b) {
+        const uint16_t* base = wbase + (NS + s) * TE;
+        u32x2 r0 = lds_read_tr16(base + tr_base + 16 * b);
+        u32x2 r1 = lds_read_tr16(base + tr_base + 4 * RS + 16 * b);
+        bfrag[s][b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+      }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        u32x2 r0 = lds_read_tr16(wbase + s * TE + tr_base + 16 * a);
+        u32x2 r1 = lds_read_tr16(wbase + s * TE + tr_base + 4 * RS + 16 * a);
+        const u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+        for (int b = 0; b <= MT; ++b) {
+          acc[a][b] = mfma_16x16x32<T>(afrag, bfrag[0][b], acc[a][b]);              // hi * hi, lo * hi
+          if (NS == 2 && s == 0) acc[a][b] = mfma_16x16x32<T>(afrag, bfrag[NS - 1][b], acc[a][b]);   // hi * lo
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    lim = next_lim;
+  }
+
+  // ---- cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3), as in state_reduce16 ----------------
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem);
+  float* mine = red + (wave & 1) * NE;
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    if ((wave >> 1) == round) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = a * 16 + 4 * g4 + i;
+          if (row < D) {
+#pragma unroll
+            for (int b = 0; b <= MT; ++b) {
+              const int col = b * 16 + j16;
+              float* p = nullptr;
+              if (b < MT && col < D) p = mine + row * D + col;
+              else if (b == MT && j16 == 0) p = mine + D * D + row;
+              if (p) *p = (round == 0) ? acc[a][b][i] : *p + acc[a][b][i];
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  for (int i = threadIdx.x; i < NE; i += kThreads) dst[i] = (red[i] + red[NE + i]) * inv_beta;
+}
+
+}  // namespace lf

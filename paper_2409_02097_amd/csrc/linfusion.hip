@@ -13,6 +13,7 @@
 #include <mutex>
 
 #include "lf_fused.hpp"
+#include "lf_host_api.hpp"
 #include "lf_wide_api.hpp"
 
 namespace {
@@ -637,6 +638,11 @@ int fwd_owned(const void* q, const void* k, const void* v, void* out, int B, int
 }
 
 }  // namespace
+
+namespace lfh {
+int check_device() { return ::check_device(); }
+int env_int(const char* name, int dflt) { return ::env_int(name, dflt); }
+}  // namespace lfh
 
 extern "C" {
 

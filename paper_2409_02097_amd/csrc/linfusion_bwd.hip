@@ -1,0 +1,186 @@
+// Third translation unit of the library: the backward pass (lf_backward16.hpp) and its entry points.
+#include "../../include/linfusion.h"
+
+#include <stdint.h>
+
+#include <cmath>
+
+#include "lf_backward16.hpp"
+#include "lf_host_api.hpp"
+
+namespace {
+
+constexpr int kNumCU = 256;
+
+struct BwdPlan {
+  int splits, blk_reduce, apply_wgs, blk_apply;
+  size_t ne, ws_partials, ws_state, ws_scal, ws_total;
+};
+
+bool bwd_supported_d(int d) { return (d >= 8 && d <= 64 && d % 8 == 0) || d == 80; }
+
+int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
+  if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
+  if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;
+  if (dtype != LINFUSION_DTYPE_F16 && dtype != LINFUSION_DTYPE_BF16) return LINFUSION_ERR_UNSUPPORTED;
+  if (!bwd_supported_d(d)) return LINFUSION_ERR_UNSUPPORTED;
+  if (N > (1LL << 40) / d) return LINFUSION_ERR_INVALID;
+  const long long BH = (long long)B * H;
+  const long long n_tiles = (N + lf::kTile - 1) / lf::kTile;
+  const long long max_s = (n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;
+  auto per_head = [&](int want_total, int blk_dflt, int* blk) {
+    long long s = (want_total + BH - 1) / BH;
+    if (s > max_s) s = max_s;
+    if (s < 1) s = 1;
+    long long t = (n_tiles + s - 1) / s;
+    long long b = blk_dflt < t ? blk_dflt : t;
+    *blk = (int)((b + lf::kWavesPerWG - 1) / lf::kWavesPerWG * lf::kWavesPerWG);
+    return (int)((n_tiles + t - 1) / t);
+  };
+  p->splits = per_head(lfh::env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_REDUCE_BLK", 16),
+                       &p->blk_reduce);
+  p->apply_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY_WGS", 4 * kNumCU), lfh::env_int("LINFUSION_BWD_APPLY_BLK", 8),
+                          &p->blk_apply);
+  p->ne = (size_t)d * d + d;
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  p->ws_partials = up((size_t)BH * p->splits * p->ne * sizeof(float));
+  p->ws_state = up((size_t)BH * p->ne * sizeof(float));
+  p->ws_scal = up((size_t)BH * (size_t)N * 2 * sizeof(float));
+  p->ws_total = p->ws_partials + 2 * p->ws_state + p->ws_scal;
+  return LINFUSION_OK;
+}
+
+template <typename KernelT>
+bool allow_lds(KernelT kernel, int bytes) {
+  if (bytes <= 65536) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
+
+struct BwdArgs {
+  const void *q, *k, *v, *g;
+  void *dq, *dk, *dv;
+  int B, H;
+  long long N;
+  float eps;
+  bool unnorm;
+  const BwdPlan* p;
+  unsigned char* ws;
+  hipStream_t st;
+};
+
+template <typename T, int D, int FM, bool NORM>
+int run_bwd(const BwdArgs& a) {
+  using namespace lf;
+  const BwdPlan& p = *a.p;
+  constexpr int NE = D * D + D;
+  const long long BH = (long long)a.B * a.H;
+  float* partials = reinterpret_cast<float*>(a.ws);
+  float* stateS = reinterpret_cast<float*>(a.ws + p.ws_partials);
+  float* stateD = reinterpret_cast<float*>(a.ws + p.ws_partials + p.ws_state);
+  f32x2* scal = reinterpret_cast<f32x2*>(a.ws + p.ws_partials + 2 * p.ws_state);
+  const u32x4* Q = (const u32x4*)a.q;
+  const u32x4* K = (const u32x4*)a.k;
+  const u32x4* V = (const u32x4*)a.v;
+  const u32x4* G = (const u32x4*)a.g;
+  const dim3 blk(kThreads);
+  hipStream_t st = a.st;
+  const Layout dense{(long long)a.H * a.N * (D / 8), a.N * (D / 8), D / 8, a.H};
+  const HeadSubset all{0, a.H};
+  const dim3 gr(p.splits, (unsigned)BH), ga(p.apply_wgs, (unsigned)BH);
+  const dim3 gc((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH);
+
+  constexpr int lds_r = reduce16_lds_bytes<T, D>();
+  constexpr int lds_a = BwdCfg<D>::lds_bytes();
+  constexpr int lds_s = bwd_state_lds_bytes<T, D>();
+  if (!allow_lds(state_reduce16<T, D, FM>, lds_r) || !allow_lds(bwd_q16<T, D, FM, NORM>, lds_a) ||
+      !allow_lds(bwd_state16<T, D, FM, NORM>, lds_s) || !allow_lds(bwd_kv16<T, D, FM>, lds_a))
+    return LINFUSION_ERR_HIP;
+
+  state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, dense, all, partials, a.N, p.blk_reduce);
+  combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateS);
+  bwd_q16<T, D, FM, NORM><<<ga, blk, lds_a, st>>>(Q, G, (u32x4*)a.dq, stateS, scal, a.eps, a.N, p.blk_apply);
+  bwd_state16<T, D, FM, NORM><<<gr, blk, lds_s, st>>>(Q, G, scal, stateS, partials, a.N, p.blk_reduce);
+  combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateD);
+  bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, (u32x4*)a.dk, (u32x4*)a.dv, stateD, a.N, p.blk_apply);
+  return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+}
+
+template <typename T, int D>
+int run_bwd_fm(int fm, const BwdArgs& a) {
+  switch (fm) {
+    case 0: return a.unnorm ? run_bwd<T, D, 0, false>(a) : run_bwd<T, D, 0, true>(a);
+    case 1: return a.unnorm ? run_bwd<T, D, 1, false>(a) : run_bwd<T, D, 1, true>(a);
+    default: return a.unnorm ? run_bwd<T, D, 2, false>(a) : run_bwd<T, D, 2, true>(a);
+  }
+}
+
+#define LFB_FOR_D(X) X(8) X(16) X(24) X(32) X(40) X(48) X(56) X(64) X(80)
+
+int dispatch_bwd(int d, int dtype, int fm, const BwdArgs& a) {
+  switch (d) {
+#define X(DD) \
+  case DD: return dtype == LINFUSION_DTYPE_F16 ? run_bwd_fm<lf::F16, DD>(fm, a) : run_bwd_fm<lf::BF16, DD>(fm, a);
+    LFB_FOR_D(X)
+#undef X
+  }
+  return LINFUSION_ERR_UNSUPPORTED;
+}
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int dtype) {
+  BwdPlan p;
+  if (make_bwd_plan(B, H, N, d, dtype, &p) != LINFUSION_OK) return 0;
+  return p.ws_total;
+}
+
+int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk, void* dv,
+                       int B, int H, long long N, int d, int dtype, int feature_map, float eps, unsigned flags,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !dout || !dq || !dk || !dv) return LINFUSION_ERR_INVALID;
+  if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
+  if (flags & ~LINFUSION_FLAG_UNNORMALIZED) return LINFUSION_ERR_INVALID;
+  BwdPlan p;
+  int rc = make_bwd_plan(B, H, N, d, dtype, &p);
+  if (rc != LINFUSION_OK) return rc;
+  if (feature_map < 0 || feature_map > 2) return LINFUSION_ERR_UNSUPPORTED;
+  const void* ins[4] = {q, k, v, dout};
+  void* outs[3] = {dq, dk, dv};
+  for (const void* x : ins)
+    if ((uintptr_t)x & 15) return LINFUSION_ERR_MISALIGNED;
+  for (void* x : outs)
+    if ((uintptr_t)x & 15) return LINFUSION_ERR_MISALIGNED;
+  const size_t tbytes = (size_t)B * H * (size_t)N * d * 2;
+  for (int i = 0; i < 3; ++i) {
+    for (const void* x : ins)
+      if (overlaps(outs[i], tbytes, x, tbytes)) return LINFUSION_ERR_OVERLAP;
+    for (int j = i + 1; j < 3; ++j)
+      if (overlaps(outs[i], tbytes, outs[j], tbytes)) return LINFUSION_ERR_OVERLAP;
+  }
+  if (!workspace) return LINFUSION_ERR_WORKSPACE;
+  if ((uintptr_t)workspace & 15) return LINFUSION_ERR_MISALIGNED;
+  if (workspace_bytes < p.ws_total) return LINFUSION_ERR_WORKSPACE;
+  for (const void* x : ins)
+    if (overlaps(workspace, p.ws_total, x, tbytes)) return LINFUSION_ERR_OVERLAP;
+  for (void* x : outs)
+    if (overlaps(workspace, p.ws_total, x, tbytes)) return LINFUSION_ERR_OVERLAP;
+  rc = lfh::check_device();
+  if (rc != LINFUSION_OK) return rc;
+  BwdArgs a{q, k, v, dout, dq, dk, dv, B, H, N, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
+            &p, (unsigned char*)workspace, (hipStream_t)stream};
+  return dispatch_bwd(d, dtype, feature_map, a);
+}
+
+}  // extern "C"

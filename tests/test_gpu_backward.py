@@ -1,0 +1,128 @@
+"""GPU parity of the backward pass (linfusion_attn_bwd) against the fp64 oracle's gradients."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_02097_amd as lf
+from oracle import linattn_oracle as orc
+from paper_2409_02097_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(q, k, v, g, fm=0, eps=1e-6, flags=0):
+    B, H, N, d = q.shape
+    code = wl.DTYPE_CODE[{torch.float16: "f16", torch.bfloat16: "bf16"}[q.dtype]]
+    ws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    outs = [torch.full_like(q, float("nan")).cuda() for _ in range(3)]
+    lf.linfusion_attn_bwd(q.cuda(), k.cuda(), v.cuda(), g.cuda(), *outs, fm, eps, flags, ws)
+    torch.cuda.synchronize()
+    return outs
+
+
+def _term_scales(q, k, v, g, fm, eps, normalize):
+    """Largest magnitude, per gradient, of the sums of absolute terms that the gradient is made of:
+        dq: (|g / den| |S|^T + |e| |z|) phi'(q),  dk: (|v| |dS|^T + |dz|) phi'(k),  dv: |p| |dS|.
+    Gradients cancel (with one token dq is exactly zero: the output does not depend on q), so an error
+    bound has to be relative to what is summed, not to what is left; these are the classical |A| |B| bounds."""
+    r, p = orc.phi(q, fm), orc.phi(k, fm)
+    S, z = orc.state(k, v, fm)
+    if normalize:
+        den = r @ z + eps
+        gn = g / den[:, None]
+        e = -(g * ((r @ S) / den[:, None])).sum(axis=1) / den
+    else:
+        gn, e = g, np.zeros(q.shape[0])
+    dS, dz = r.T @ gn, r.T @ e
+    sq = (np.abs(gn) @ np.abs(S).T + np.abs(e)[:, None] * np.abs(z)[None, :]) * np.abs(orc.phi_prime(q, fm))
+    sk = (np.abs(v) @ np.abs(dS).T + np.abs(dz)[None, :]) * np.abs(orc.phi_prime(k, fm))
+    sv = np.abs(p) @ np.abs(dS)
+    return sq.max(), sk.max(), sv.max()
+
+
+def _check(outs, q, k, v, g, dtype, fm, eps, normalize, what):
+    """|gpu - ref| <= tol * (largest sum of absolute terms in the slice) + half an ulp of the output type."""
+    qs, ks, vs, gs = (wl.stored_numpy(t) for t in (q, k, v, g))
+    B, H = qs.shape[:2]
+    tol = parity.TOL[dtype]
+    worst = 0.0
+    for b in range(B):
+        for h in range(H):
+            w = [orc.widen(x[b, h], dtype) for x in (qs, ks, vs, gs)]
+            ref = orc.attention_backward_linear(*w, fm, eps, normalize)
+            scales = _term_scales(*w, fm, eps, normalize)
+            for got, want, scale, name in zip(outs, ref, scales, ("dq", "dk", "dv")):
+                gpu = parity.to_f64(got[b, h])
+                assert np.all(np.isfinite(gpu)), f"{what} {name} b={b} h={h}: non-finite values"
+                err = np.abs(gpu - want)
+                bound = tol * scale + orc.half_ulp(want, dtype)
+                assert (err - bound).max() <= 0, (f"{what} {name} b={b} h={h}: error {err.max():.3e} vs term scale "
+                                                  f"{scale:.3e} (ratio {err.max() / scale:.3e}, tol {tol:g})")
+                worst = max(worst, float((err / scale).max()))
+    return worst
+
+
+SHAPES = [
+    (1, 2, 1, 40, "f16"), (1, 1, 31, 64, "f16"), (2, 3, 33, 40, "f16"), (1, 2, 1000, 40, "f16"),
+    (2, 2, 4099, 64, "f16"), (1, 3, 777, 8, "f16"), (1, 1, 130, 16, "f16"), (1, 2, 515, 24, "f16"),
+    (1, 2, 300, 32, "f16"), (1, 2, 300, 48, "f16"), (1, 1, 300, 56, "f16"), (1, 2, 700, 80, "f16"),
+    (1, 2, 1, 64, "bf16"), (2, 2, 33, 40, "bf16"), (1, 2, 1000, 64, "bf16"), (1, 3, 4099, 40, "bf16"),
+    (1, 2, 300, 24, "bf16"), (1, 1, 200, 48, "bf16"), (1, 2, 600, 80, "bf16"), (2, 8, 4096, 40, "f16"),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", SHAPES)
+def test_backward_matches_oracle(B, H, N, d, dtype):
+    print(f"bwd B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=80, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 80777, dtype, "cpu")
+    outs = _run(q, k, v, g)
+    worst = _check(outs, q, k, v, g, dtype, 0, 1e-6, True, f"bwd N={N} d={d} {dtype}")
+    print(f"  worst max-norm ratio {worst:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("fm,normalize", [(1, True), (2, True), (0, False), (1, False)])
+def test_backward_other_feature_maps_and_unnormalized(dtype, fm, normalize):
+    B, H, N, d = 1, 2, 500, 40
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=81, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 81777, dtype, "cpu")
+    if fm == 2:
+        q, k = q.abs(), k.abs()
+    if not normalize:
+        v, g = v * 0.05, g * 0.05      # keeps the un-normalized sums inside fp16's range
+    outs = _run(q, k, v, g, fm, 1e-6, 0 if normalize else lf.FLAG_UNNORMALIZED)
+    _check(outs, q, k, v, g, dtype, fm, 1e-6, normalize, f"bwd fm={fm} norm={normalize} {dtype}")
+
+
+def test_backward_is_run_to_run_identical_and_leaves_inputs_alone():
+    B, H, N, d, dtype = 1, 3, 2100, 40, "f16"
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=82, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 82777, dtype, "cpu")
+    qd, kd, vd, gd = q.cuda(), k.cuda(), v.cuda(), g.cuda()
+    ws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, 1), dtype=torch.uint8, device="cuda")
+    a = [torch.empty_like(qd) for _ in range(3)]
+    b = [torch.empty_like(qd) for _ in range(3)]
+    lf.linfusion_attn_bwd(qd, kd, vd, gd, *a, 0, 1e-6, 0, ws)
+    lf.linfusion_attn_bwd(qd, kd, vd, gd, *b, 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8))
+    for dev, host in ((qd, q), (kd, k), (vd, v), (gd, g)):
+        assert torch.equal(dev.cpu().view(torch.uint8), host.view(torch.uint8))
+
+
+def test_backward_argument_checks():
+    x = torch.zeros(1, 1, 64, 40, dtype=torch.float16, device="cuda")
+    outs = [torch.empty_like(x) for _ in range(3)]
+    ws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(1, 1, 64, 40, 1), dtype=torch.uint8, device="cuda")
+    assert lf.linfusion_attn_bwd(x, x, x, x, x, outs[1], outs[2], 0, 1e-6, 0, ws, check=False) == -7   # dq aliases q
+    assert lf.linfusion_attn_bwd(x, x, x, x, outs[0], outs[0], outs[2], 0, 1e-6, 0, ws, check=False) == -7
+    assert lf.linfusion_attn_bwd(x, x, x, x, *outs, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws, check=False) == -1
+    assert lf.linfusion_attn_bwd(x, x, x, x, *outs, 0, 1e-6, 0, ws[:64], check=False) == -4
+    f = torch.zeros(1, 1, 64, 40, dtype=torch.float32, device="cuda")
+    fo = [torch.empty_like(f) for _ in range(3)]
+    assert lf.linfusion_attn_bwd(f, f, f, f, *fo, 0, 1e-6, 0, ws, check=False) == -2
+    assert lf.linfusion_attn_bwd_workspace_bytes(1, 1, 64, 40, 0) == 0
