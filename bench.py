@@ -137,6 +137,9 @@ def main():
     ap.add_argument("--layout", choices=["head_major", "token_major"], default="head_major",
                     help="memory layout of q, k, v, out: contiguous [B, H, N, d] (the headline workload) or the "
                          "UNet's [B, N, H*d] handed over as strided views")
+    ap.add_argument("--backward", action="store_true",
+                    help="also time linfusion_attn_bwd on the same workload (fp16 / bf16 only); reported in an extra "
+                         "`backward` object of the result line")
     ap.add_argument("--latency-table", action="store_true",
                     help="also time the small and medium workloads, hot and cold cache, both launch paths "
                          "(JSON lines on stderr; the one-line result on stdout is unchanged)")
@@ -241,6 +244,30 @@ def main():
         "hbm_frac_of_peak": alg_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS,
         "roofline": roofline,
     }
+    if args.backward:
+        # gradient tensors resident in HBM; minimal traffic = q, k, v, dout read + dq, dk, dv written (7 tensors);
+        # the kernels read q and dout twice and k, v twice (11 tensor passes plus 8 bytes per token-head)
+        g = torch.randn_like(q)
+        grads = [torch.empty_like(q) for _ in range(3)]
+        bws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
+
+        def bstep():
+            lf.linfusion_attn_bwd(q, k, v, g, *grads, lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, bws)
+        for _ in range(max(args.warmup // 2, 2)):
+            bstep()
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        bsteps = max(args.steps // 2, 1)
+        for _ in range(bsteps):
+            bstep()
+        torch.cuda.synchronize()
+        bdt = (time.perf_counter() - tb) / bsteps
+        tensor_bytes = alg_bytes / 4
+        result["backward"] = {"ms_per_step": bdt * 1e3, "tokens_per_s": B * N / bdt,
+                              "min_traffic_gbps": 7 * tensor_bytes / bdt / 1e9,
+                              "kernel_traffic_gbps": (11 * tensor_bytes + 8.0 * B * H * N * 2) / bdt / 1e9,
+                              "frac_of_peak_kernel_traffic": (11 * tensor_bytes + 16.0 * B * H * N) / bdt / 1e9 / HBM_PEAK_GBPS}
+        del g, grads, bws
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(q, k, v, cfg, args.cpu_sample_tokens)
         result["cpu_baseline"] = base

@@ -14,6 +14,7 @@ constexpr int kNumCU = 256;
 
 struct BwdPlan {
   int splits, blk_reduce, apply_wgs, blk_apply;
+  int gsplits, gblk_reduce;   // the state-gradient reduction's own launch shape
   size_t ne, ws_partials, ws_state, ws_scal, ws_total;
 };
 
@@ -39,11 +40,13 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   };
   p->splits = per_head(lfh::env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_REDUCE_BLK", 16),
                        &p->blk_reduce);
+  p->gsplits = per_head(lfh::env_int("LINFUSION_BWD_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_BWD_REDUCE_BLK", 16),
+                        &p->gblk_reduce);
   p->apply_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY_WGS", 4 * kNumCU), lfh::env_int("LINFUSION_BWD_APPLY_BLK", 8),
                           &p->blk_apply);
   p->ne = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  p->ws_partials = up((size_t)BH * p->splits * p->ne * sizeof(float));
+  p->ws_partials = up((size_t)BH * (p->splits > p->gsplits ? p->splits : p->gsplits) * p->ne * sizeof(float));
   p->ws_state = up((size_t)BH * p->ne * sizeof(float));
   p->ws_scal = up((size_t)BH * (size_t)N * 2 * sizeof(float));
   p->ws_total = p->ws_partials + 2 * p->ws_state + p->ws_scal;
@@ -104,8 +107,9 @@ int run_bwd(const BwdArgs& a) {
   state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, dense, all, partials, a.N, p.blk_reduce);
   combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateS);
   bwd_q16<T, D, FM, NORM><<<ga, blk, lds_a, st>>>(Q, G, (u32x4*)a.dq, stateS, scal, a.eps, a.N, p.blk_apply);
-  bwd_state16<T, D, FM, NORM><<<gr, blk, lds_s, st>>>(Q, G, scal, stateS, partials, a.N, p.blk_reduce);
-  combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateD);
+  bwd_state16<T, D, FM, NORM><<<dim3(p.gsplits, (unsigned)BH), blk, lds_s, st>>>(Q, G, scal, stateS, partials, a.N,
+                                                                                  p.gblk_reduce);
+  combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.gsplits, NE, stateD);
   bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, (u32x4*)a.dk, (u32x4*)a.dv, stateD, a.N, p.blk_apply);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }

@@ -65,3 +65,96 @@ def test_16k_image_workload_sampled_rows():
         got = parity.to_f64(out[0, h].index_select(0, idx))
         r = parity.check_slice(got, ref, dtype, f"{name} head {h} sampled rows")
         print(f"  sampled rows: max-norm ratio {r[0]:.2e}, rel L2 {r[1]:.2e}", flush=True)
+
+
+def _stream_head(t, h, step=1 << 19):
+    """One head of a [1, H, N, d] device tensor, widened to fp64, in slices that bound host memory."""
+    N = t.shape[2]
+    for s0 in range(0, N, step):
+        yield s0, orc.widen(wl.stored_numpy(t[0, h, s0:s0 + step]), "f16")
+
+
+def test_16k_image_workload_token_major_sampled_rows():
+    """The same workload handed over in the UNet's [B, N, H*d] layout (row-piece kernels, groups of 8 heads)."""
+    name = "sd15_16k_f16"
+    c = wl.CONFIGS[name]
+    B, H, N, d, dtype = c["B"], c["H"], c["N"], c["d"], c["dtype"]
+    q, k, v = wl.make_config(name, device="cuda")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous()
+    qt, kt, vt = tm(q), tm(k), tm(v)
+    ot = torch.empty_like(qt)
+    view = lambda t: t.permute(0, 2, 1, 3)
+    ws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, 1), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(ot), lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(ot).all())
+    del qt, kt, vt
+    rng = np.random.default_rng(20240903)
+    edges = [0, 31, 32, 255, 256, N // 2 - 1, N // 2, N - 33, N - 32, N - 1]
+    for h in (1, 6):
+        print(f"token-major head {h}: oracle state over {N} tokens", flush=True)
+        S, z = np.zeros((d, d)), np.zeros(d)
+        for (s0, ks), (_, vs) in zip(_stream_head(k, h), _stream_head(v, h)):
+            S_c, z_c = orc.state(ks, vs)
+            S += S_c
+            z += z_c
+        rows = np.unique(np.concatenate([np.array(edges), rng.integers(0, N, size=4096)]))
+        idx = torch.from_numpy(rows).cuda()
+        ref = orc.apply_state(orc.widen(wl.stored_numpy(q[0, h].index_select(0, idx)), dtype), S, z, orc.ELU_PLUS_ONE, wl.EPS)
+        got = parity.to_f64(ot[0, :, h].index_select(0, idx))
+        r = parity.check_slice(got, ref, dtype, f"{name} token-major head {h} sampled rows")
+        print(f"  sampled rows: max-norm ratio {r[0]:.2e}, rel L2 {r[1]:.2e}", flush=True)
+
+
+def test_16k_image_workload_backward_sampled_rows():
+    """Gradients at the benchmark size: the oracle streams one head through its state form (S, z, then dS, dz
+    over all 2,097,152 tokens) and evaluates sampled rows of dq, dk and dv."""
+    name = "sd15_16k_f16"
+    c = wl.CONFIGS[name]
+    B, H, N, d, dtype = c["B"], c["H"], c["N"], c["d"], c["dtype"]
+    q, k, v = wl.make_config(name, device="cuda")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 99777, dtype, "cuda")
+    dq, dk, dv = (torch.empty_like(q) for _ in range(3))
+    ws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, 1), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_bwd(q, k, v, g, dq, dk, dv, lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, ws)
+    torch.cuda.synchronize()
+    for t in (dq, dk, dv):
+        assert bool(torch.isfinite(t).all())
+    rng = np.random.default_rng(20240904)
+    edges = [0, 31, 32, N // 2, N - 32, N - 1]
+    h = 5
+    print(f"backward head {h}: oracle states over {N} tokens", flush=True)
+    S, z = np.zeros((d, d)), np.zeros(d)
+    for (s0, ks), (_, vs) in zip(_stream_head(k, h), _stream_head(v, h)):
+        S_c, z_c = orc.state(ks, vs)
+        S += S_c
+        z += z_c
+    dS, dz = np.zeros((d, d)), np.zeros(d)
+    a_gn, a_e = 0.0, 0.0
+    for (s0, qs), (_, gs) in zip(_stream_head(q, h), _stream_head(g, h)):
+        r = orc.phi(qs)
+        den = r @ z + wl.EPS
+        gn = gs / den[:, None]
+        e = -(gs * ((r @ S) / den[:, None])).sum(axis=1) / den
+        dS += r.T @ gn
+        dz += r.T @ e
+    rows = np.unique(np.concatenate([np.array(edges), rng.integers(0, N, size=2048)]))
+    idx = torch.from_numpy(rows).cuda()
+    sel = lambda t: orc.widen(wl.stored_numpy(t[0, h].index_select(0, idx)), dtype)
+    qs, ks, vs, gs = sel(q), sel(k), sel(v), sel(g)
+    r, p = orc.phi(qs), orc.phi(ks)
+    den = r @ z + wl.EPS
+    gn = gs / den[:, None]
+    e = -(gs * ((r @ S) / den[:, None])).sum(axis=1) / den
+    ref = {"dq": (gn @ S.T + e[:, None] * z[None, :]) * orc.phi_prime(qs),
+           "dk": (vs @ dS.T + dz[None, :]) * orc.phi_prime(ks),
+           "dv": p @ dS}
+    scale = {"dq": ((np.abs(gn) @ np.abs(S).T + np.abs(e)[:, None] * np.abs(z)[None, :]) * orc.phi_prime(qs)).max(),
+             "dk": ((np.abs(vs) @ np.abs(dS).T + np.abs(dz)[None, :]) * orc.phi_prime(ks)).max(),
+             "dv": (np.abs(p) @ np.abs(dS)).max()}
+    for name_, t in (("dq", dq), ("dk", dk), ("dv", dv)):
+        got = parity.to_f64(t[0, h].index_select(0, idx))
+        err = np.abs(got - ref[name_])
+        bound = parity.TOL[dtype] * scale[name_] + orc.half_ulp(ref[name_], dtype)
+        assert (err - bound).max() <= 0, f"{name_}: error {err.max():.3e} vs term scale {scale[name_]:.3e}"
+        print(f"  {name_}: error / term scale {err.max() / scale[name_]:.2e}", flush=True)
