@@ -149,7 +149,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the hot path is a single-device kernel "
-              "sequence; sharding over devices is described in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "sequence and every box has one GPU; no multi-GPU figure exists). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
