@@ -40,7 +40,7 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   };
   p->splits = per_head(lfh::env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_REDUCE_BLK", 16),
                        &p->blk_reduce);
-  p->gsplits = per_head(lfh::env_int("LINFUSION_BWD_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_BWD_REDUCE_BLK", 16),
+  p->gsplits = per_head(lfh::env_int("LINFUSION_BWD_REDUCE_WGS", 8 * kNumCU), lfh::env_int("LINFUSION_BWD_REDUCE_BLK", 16),
                         &p->gblk_reduce);
   p->apply_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY_WGS", 4 * kNumCU), lfh::env_int("LINFUSION_BWD_APPLY_BLK", 8),
                           &p->blk_apply);
