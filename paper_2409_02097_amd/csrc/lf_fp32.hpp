@@ -145,27 +145,108 @@ state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout 
 }
 
 // ------------------------------------------------------------------------------------------
-// Lane (token = lane % 16, kq = lane / 16) loads its kCS contiguous float4 chunks of the Q row;
-// element e of chunk cs is the B operand of k-step 4*cs + e against S^T (A operand), which every
-// lane gathers once from the head's fp32 state:
-// lane l (output row mrow = l % 16, kq = l / 16), tile T, k-step 4*cs + e:
+// Apply + normalize, fp32.  out^T = S^T phi(Q)^T with 16x16x4 products: the A operands (one value per lane
+// and k-step) are gathered once from the head's fp32 state:
+//   lane l (output row mrow = l % 16, kq = l / 16), tile T, k-step 4*cs + e:
 //   feature channel ch = 4*(kq*CS + cs) + e  (zero when that chunk is beyond d)
 //   slot = 4*T + mrow % 4, group g = mrow / 4:  slot < d/4 -> S[ch][g*d/4 + slot];
 //   slot == d/4 -> z[ch];  else 0.
-// The accumulators of a lane hold d/4 contiguous output channels of its token and the
-// normalizer phi(q).z.  `state`: this head's [D*D + D] floats; `Qh`, `Oh4`: first token row of this head;
-// `rs_q`, `rs_o`: row strides in 16-byte units.
+// The accumulators of a lane (token = l % 16, quarter kq) hold d/4 contiguous output channels of its
+// token and the normalizer phi(q).z.
+// Q tiles (16 tokens, contiguous rows) travel as in apply16_dma: each wave owns a ring of three LDS slots
+// filled by asynchronous global->LDS copies two tiles ahead, lanes read their own token's chunks from the
+// slot, write their channels back into it, and the tile leaves with coalesced stores in memory order.
+// The 16-byte chunks of a row are rotated by a row-dependent amount so that the token-per-lane accesses
+// are bank-conflict free for every d (row r by (r * G / 16) mod G chunks, G = gcd(d / 4, 16)).
 // ------------------------------------------------------------------------------------------
+template <int D> struct Apply32Cfg {
+  static constexpr int kCH = D / 4;
+  static constexpr int kChunks = kTile32 * kCH;      // 16-byte chunks per tile
+  static constexpr int kNL = (kChunks + 63) / 64;
+  static constexpr int kSlotBytes = kNL * 1024;
+  static constexpr int kRing = 3;
+  static constexpr int kG = (kCH % 16 == 0) ? 16 : ((kCH % 8 == 0) ? 8 : ((kCH % 4 == 0) ? 4 : 2));
+  static_assert(kCH % 2 == 0, "d is a multiple of 8");
+  static __device__ __forceinline__ int rot(int r) { return ((r * kG) >> 4) & (kG - 1); }
+};
+template <int D> constexpr int apply32_lds_bytes() { return Apply32Cfg<D>::kRing * kWavesPerWG * Apply32Cfg<D>::kSlotBytes; }
+
+template <int N> LF_DEV void wait_vmcnt32() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
 template <int D, int FM, bool NORM>
-LF_DEV void apply32_phase(const f32x4* __restrict__ Qh, int rs_q, f32x4* __restrict__ Oh4, int rs_o,
-                          const float* state, float eps, long long N, int tiles_per_block, int wg, int nwg) {
+struct Apply32Dma {
   using Sh = Shape32<D>;
-  constexpr int CS = Sh::kCS, KST = Sh::kKSteps, MT = Sh::kMT, CH = Sh::kChunks, QT = Sh::kQuarter;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int tok = lane & 15, kq = lane >> 4;
+  using Cfg = Apply32Cfg<D>;
+  static constexpr int CS = Sh::kCS, KST = Sh::kKSteps, MT = Sh::kMT, CH = Sh::kChunks, QT = Sh::kQuarter;
+  static constexpr int NL = Cfg::kNL, R = Cfg::kRing;
+  static_assert(R == 3, "the wait counts below are written for a ring of three slots");
+
+  const f32x4* Qh;
+  f32x4* Oh;
+  long long N;
+  unsigned char* smem;
+  int rs_q, rs_o;
+  int lane, wave, tok, kq, row_byte, trot;
+  int trow[NL], qoff[NL], ooff[NL], soff[NL];
+  TileIter it, ahead;
   float A[MT][KST];
-  {
+
+  LF_DEV Apply32Dma(const f32x4* Qh_, int rs_q_, f32x4* Oh_, int rs_o_, long long N_, int tiles_per_block, int wg,
+                    int nwg, unsigned char* smem_)
+      : Qh(Qh_), Oh(Oh_), N(N_), smem(smem_), rs_q(rs_q_), rs_o(rs_o_), lane(threadIdx.x & 63),
+        wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
+        it(wg, nwg, wave, tiles_per_block, (N_ + kTile32 - 1) / kTile32), ahead(it) {
+    tok = lane & 15;
+    kq = lane >> 4;
+    row_byte = tok * CH * 16;
+    trot = Cfg::rot(tok);
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const int P = u * 64 + lane;
+      const int r = P / CH, pos = P % CH;
+      int c = pos - Cfg::rot(r);                 // copy side: position pos of row r receives chunk c
+      if (c < 0) c += CH;
+      int spos = pos + Cfg::rot(r);              // store side: this lane sends chunk pos, found at spos
+      if (spos >= CH) spos -= CH;
+      trow[u] = r;
+      qoff[u] = r * rs_q + c;
+      ooff[u] = r * rs_o + pos;
+      soff[u] = (r * CH + spos) * 16;
+    }
+  }
+
+  LF_DEV unsigned char* slot_ptr(int slot) const { return smem + (slot * kWavesPerWG + wave) * Cfg::kSlotBytes; }
+  LF_DEV unsigned char* chunk_ptr(int slot, int chunk) const {
+    int x = chunk + trot;
+    if (x >= CH) x -= CH;
+    return slot_ptr(slot) + row_byte + (x << 4);
+  }
+
+  // always issues exactly NL vector memory instructions
+  LF_DEV void issue_copy(long long tile, int slot) {
+    long long rem = N - tile * kTile32;
+    const int lim = rem < kTile32 ? (int)rem : kTile32;
+    const f32x4* qp = Qh + tile * kTile32 * rs_q;
+    unsigned char* sl = slot_ptr(slot);
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      if (u * 64 + lane < Cfg::kChunks) {
+        const int c = trow[u] < lim ? qoff[u] : 0;   // rows past N re-read chunk 0; never stored
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
+                                         (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
+      }
+    }
+  }
+  LF_DEV void prefetch() {
+    if (ahead.valid()) issue_copy(ahead.t, 0);
+    ahead.next();
+    if (ahead.valid()) issue_copy(ahead.t, 1);
+    ahead.next();
+  }
+
+  // COHERENT: the state was written by other workgroups of the same launch (single-launch kernel)
+  template <bool COHERENT>
+  LF_DEV void load_state(const float* state) {
     const int mrow = lane & 15, g = mrow >> 2;
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
@@ -176,75 +257,101 @@ LF_DEV void apply32_phase(const f32x4* __restrict__ Qh, int rs_q, f32x4* __restr
         const int ch = 4 * chunk + (ks & 3);
         float x = 0.0f;
         if (chunk < CH) {
-          if (slot < QT) x = ld_agent(state + ch * D + g * QT + slot);
-          else if (NORM && slot == QT) x = ld_agent(state + D * D + ch);
+          const float* p = nullptr;
+          if (slot < QT) p = state + ch * D + g * QT + slot;
+          else if (NORM && slot == QT) p = state + D * D + ch;
+          if (p) x = COHERENT ? ld_agent(p) : *p;
         }
         A[t][ks] = x;
       }
     }
   }
 
-  const long long n_tiles = (N + kTile32 - 1) / kTile32;
-  TileIter it(wg, nwg, wave, tiles_per_block, n_tiles);
-
-  f32x4 qr[CS];
-  auto issue_loads = [&](long long tile) {
-    const long long t = tile * kTile32 + tok;
-#pragma unroll
-    for (int cs = 0; cs < CS; ++cs) {
-      if (t < N && kq * CS + cs < CH) qr[cs] = __builtin_nontemporal_load(Qh + t * rs_q + kq * CS + cs);
-      else qr[cs] = f32x4{0, 0, 0, 0};
-    }
-  };
-  if (it.valid()) issue_loads(it.t);
-  while (it.valid()) {
-    float r[KST];
-#pragma unroll
-    for (int cs = 0; cs < CS; ++cs)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) r[4 * cs + e] = (kq * CS + cs < CH) ? phi<FM, true>(qr[cs][e]) : 0.0f;
-    const long long cur = it.t;
-    it.next();
-    if (it.valid()) issue_loads(it.t);
-
-    f32x4 acc[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t) {
-      acc[t] = f32x4{0, 0, 0, 0};
-#pragma unroll
-      for (int ks = 0; ks < KST; ++ks) acc[t] = mfma_16x16x4(A[t][ks], r[ks], acc[t]);
-    }
-    float scale = 1.0f;
-    if constexpr (NORM) scale = 1.0f / (acc[QT / 4][QT % 4] + eps);
-    const long long t = cur * kTile32 + tok;
-    if (t < N) {
-      float* orow = reinterpret_cast<float*>(Oh4 + t * rs_o) + kq * QT;
-      if constexpr (QT % 4 == 0) {
-#pragma unroll
-        for (int c = 0; c < QT / 4; ++c) {
-          f32x4 w = {acc[c][0] * scale, acc[c][1] * scale, acc[c][2] * scale, acc[c][3] * scale};
-          __builtin_nontemporal_store(w, reinterpret_cast<f32x4*>(orow) + c);
-        }
+  LF_DEV void stream(float eps) {
+    int slot = 0, iter = 0;
+    while (it.valid()) {
+      const long long tile = it.t;
+      int aslot = slot + (R - 1);
+      if (aslot >= R) aslot -= R;
+      if (ahead.valid()) {
+        issue_copy(ahead.t, aslot);
+        // issue order  C0 C1 | C2 W0 S0 | C3 W1 S1 | ... : after tile j's copies come C(j+1), C(j+2), S(j-2), S(j-1)
+        if (iter == 0) wait_vmcnt32<2 * NL>();
+        else if (iter == 1) wait_vmcnt32<3 * NL>();
+        else wait_vmcnt32<4 * NL>();
       } else {
+        wait_vmcnt32<0>();
+      }
+      iter = iter < 2 ? iter + 1 : 2;
+
+      float r[KST];
 #pragma unroll
-        for (int c = 0; c < QT / 2; ++c) {
-          const int s0 = 2 * c;
-          f32x2 w = {acc[s0 / 4][s0 % 4] * scale, acc[(s0 + 1) / 4][(s0 + 1) % 4] * scale};
-          __builtin_nontemporal_store(w, reinterpret_cast<f32x2*>(orow) + c);
+      for (int cs = 0; cs < CS; ++cs) {
+        const int chunk = kq * CS + cs;
+        f32x4 raw = f32x4{0, 0, 0, 0};
+        if (chunk < CH) raw = *reinterpret_cast<const f32x4*>(chunk_ptr(slot, chunk));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[4 * cs + e] = (chunk < CH) ? phi<FM, true>(raw[e]) : 0.0f;
+      }
+      f32x4 acc[MT];
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        acc[t] = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks) acc[t] = mfma_16x16x4(A[t][ks], r[ks], acc[t]);
+      }
+      float scale = 1.0f;
+      if constexpr (NORM) scale = 1.0f / (acc[QT / 4][QT % 4] + eps);
+
+      // ---- d/4 channels of this lane's token back into the slot, in pieces inside one chunk ----------
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      constexpr int PB = (QT % 4 == 0) ? 16 : 8;
+#pragma unroll
+      for (int c = 0; c < QT * 4 / PB; ++c) {
+        const int byte = kq * QT * 4 + c * PB;
+        unsigned char* p = chunk_ptr(slot, byte >> 4) + (byte & 15);
+        const int s0 = c * (PB / 4);
+        if constexpr (PB == 16) {
+          *reinterpret_cast<f32x4*>(p) = f32x4{acc[s0 / 4][s0 % 4] * scale, acc[(s0 + 1) / 4][(s0 + 1) % 4] * scale,
+                                               acc[(s0 + 2) / 4][(s0 + 2) % 4] * scale, acc[(s0 + 3) / 4][(s0 + 3) % 4] * scale};
+        } else {
+          *reinterpret_cast<f32x2*>(p) = f32x2{acc[s0 / 4][s0 % 4] * scale, acc[(s0 + 1) / 4][(s0 + 1) % 4] * scale};
         }
       }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+
+      // ---- coalesced stores in memory order; always NL instructions ------------------------------------
+      {
+        const unsigned char* sl = slot_ptr(slot);
+        long long rem = N - tile * kTile32;
+        const int lim = rem < kTile32 ? (int)rem : kTile32;
+        f32x4* op = Oh + tile * kTile32 * rs_o;
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+          const f32x4 w = *reinterpret_cast<const f32x4*>(sl + soff[u]);
+          if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) __builtin_nontemporal_store(w, op + ooff[u]);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      it.next();
+      ahead.next();
+      slot = slot + 1 == R ? 0 : slot + 1;
     }
   }
-}
+};
 
-// grid = (wgs_per_head, B*H), block = 256
+// grid = (wgs_per_head, B*H), block = 256, dynamic LDS apply32_lds_bytes<D>()
 template <int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
 apply32(const f32x4* __restrict__ Q, Layout lq, f32x4* __restrict__ O, Layout lo, const float* __restrict__ state,
         float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const long long bh = blockIdx.y;
-  apply32_phase<D, FM, NORM>(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, state + bh * (D * D + D), eps, N,
-                             tiles_per_block, blockIdx.x, gridDim.x);
+  Apply32Dma<D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
+                             gridDim.x, smem);
+  ap.prefetch();
+  ap.template load_state<false>(state + bh * (D * D + D));
+  ap.stream(eps);
 }
 
 }  // namespace lf

@@ -138,7 +138,9 @@ fused16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, co
   ap.template run<true>(head_state, eps);
 }
 
-template <int D> constexpr int fused32_lds_bytes() { return reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024; }
+template <int D> constexpr int fused32_lds_bytes() {
+  return reduce32_lds_bytes<D>() > apply32_lds_bytes<D>() ? reduce32_lds_bytes<D>() : apply32_lds_bytes<D>();
+}
 
 template <int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
@@ -157,8 +159,10 @@ fused32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout lkv, co
   if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
   combine_owned(head_part, nsplit, NE, split, head_state, reinterpret_cast<float*>(smem));
   if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
-  apply32_phase<D, FM, NORM>(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, head_state, eps, N, blk_apply, split,
-                             nsplit);
+  Apply32Dma<D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, blk_apply, split, nsplit, smem);
+  ap.prefetch();   // the combine's scratch in LDS is dead after the barrier
+  ap.template load_state<true>(head_state);
+  ap.stream(eps);
 }
 
 }  // namespace lf

@@ -421,15 +421,17 @@ int run32(const Args& a) {
   f32x4* O = (f32x4*)a.out;
   hipStream_t st = a.st;
   constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
+  constexpr size_t ldsf = fused32_lds_bytes<D>();
+  constexpr size_t ldsa = apply32_lds_bytes<D>();
   if (p.path == 1 && a.out) {
     unsigned* sync = reinterpret_cast<unsigned*>(a.ws + p.ws_partials + p.ws_state);
     unsigned* err = sync + a.BH * 2 * p.fsplits;
     const dim3 g(p.fsplits, (unsigned)a.BH);
     bool launched = false;
 #define LF_FUSED(FM, NORM)                                                                           \
-  if (fits_resident(fused32<D, FM, NORM>, lds, (long long)p.fsplits * a.BH)) {                       \
+  if (fits_resident(fused32<D, FM, NORM>, ldsf, (long long)p.fsplits * a.BH)) {                       \
     if (a.ev) (void)hipEventRecord(a.ev[0], st);                                                     \
-    fused32<D, FM, NORM><<<g, blk, lds, st>>>(K, V, a.lkv, Q, a.lq, O, a.lo, partials, state, sync, err, \
+    fused32<D, FM, NORM><<<g, blk, ldsf, st>>>(K, V, a.lkv, Q, a.lq, O, a.lo, partials, state, sync, err, \
                                               next_ticket(), spin_limit(), a.eps, a.N, p.fblk_reduce,   \
                                               p.fblk_apply);                                            \
     launched = true;                                                                                 \
@@ -452,7 +454,7 @@ int run32(const Args& a) {
   if (a.ev) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
     const dim3 g2(p.apply_wgs, (unsigned)a.BH);
-#define LF_APPLY(FM, NORM) apply32<D, FM, NORM><<<g2, blk, 0, st>>>(Q, a.lq, O, a.lo, state, a.eps, a.N, p.blk_apply);
+#define LF_APPLY(FM, NORM) apply32<D, FM, NORM><<<g2, blk, ldsa, st>>>(Q, a.lq, O, a.lo, state, a.eps, a.N, p.blk_apply);
     LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
   }
