@@ -28,8 +28,9 @@
  *   - Return value: LINFUSION_OK or a negative LINFUSION_ERR_* code.  All argument checks
  *     happen before anything is enqueued.  Nothing is printed, nothing aborts.
  *   - Supported head widths: d in {8, 16, 24, 32, 40, 48, 56, 64} for every dtype; for fp16 and bf16 also
- *     d = 80 and d = 160 (the deeper levels of the SD-v1.5 UNet: 640 and 1280 channels over 8 heads).
- *     d = 160 runs on the three-kernel path only (LINFUSION_FLAG_FORCE_FUSED -> LINFUSION_ERR_UNSUPPORTED).
+ *     d = 80 and d = 160 (the deeper levels of the SD-v1.5 UNet: 640 and 1280 channels over 8 heads) and
+ *     d = 96, 128.  Widths above 80 run on the three-kernel path only (LINFUSION_FLAG_FORCE_FUSED ->
+ *     LINFUSION_ERR_UNSUPPORTED).
  */
 #ifndef LINFUSION_H_
 #define LINFUSION_H_

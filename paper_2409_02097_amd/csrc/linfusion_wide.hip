@@ -77,7 +77,7 @@ int run(const WideArgs& a) {
 
 }  // namespace
 
-#define LFW_FOR_D(X) X(160)
+#define LFW_FOR_D(X) X(96) X(128) X(160)
 
 // room for either workgroup shape of the apply kernel
 template <typename T, int D>

@@ -79,7 +79,7 @@ def test_argument_validation_happens_on_the_host():
     assert _call(eps=-1.0) == -1 and _call(eps=float("nan")) == -1 and _call(eps=float("inf")) == -1
     assert _call(flags=1 << 9) == -1 and _call(flags=2 | 4) == -1
     assert _call(d=12) == -2 and _call(d=72) == -2 and _call(dtype=3) == -2 and _call(fm=5) == -2
-    assert _call(d=80, dtype=0) == -2 and _call(d=160, dtype=0) == -2 and _call(d=168) == -2   # wide heads: 16-bit only
+    assert _call(d=80, dtype=0) == -2 and _call(d=160, dtype=0) == -2 and _call(d=168) == -2 and _call(d=112) == -2   # wide heads: 16-bit only
     assert _call(d=160, flags=4, ws_bytes=64 << 20) == -2                                         # no single launch there
     assert _call(q=4096 + 8) == -3 and _call(out=(3 << 20) + 2) == -3 and _call(ws=(8 << 20) + 4) == -3
     assert _call(ws=None) == -4 and _call(ws_bytes=16) == -4

@@ -20,6 +20,8 @@ SHAPES = [
     (1, 2, 1, 80, "f16"), (1, 3, 33, 160, "f16"), (1, 2, 31, 80, "f16"), (1, 1, 4099, 160, "f16"),
     (1, 2, 2051, 80, "f16"), (1, 2, 1, 160, "bf16"), (1, 2, 1000, 80, "bf16"), (2, 2, 515, 160, "bf16"),
     (1, 8, 1024, 80, "bf16"), (1, 1, 97, 160, "bf16"),
+    (1, 2, 700, 96, "f16"), (1, 2, 1, 96, "bf16"), (2, 2, 333, 128, "f16"), (1, 3, 1030, 128, "bf16"),
+    (1, 2, 65, 96, "bf16"),
 ]
 
 
@@ -39,7 +41,7 @@ def test_wide_heads_match_oracle(B, H, N, d, dtype):
     assert torch.equal(out.view(torch.uint8), out2.view(torch.uint8)), "not run-to-run identical"
 
 
-@pytest.mark.parametrize("d,dtype", [(80, "f16"), (160, "f16"), (80, "bf16"), (160, "bf16")])
+@pytest.mark.parametrize("d,dtype", [(80, "f16"), (160, "f16"), (80, "bf16"), (160, "bf16"), (96, "f16"), (128, "bf16")])
 def test_wide_heads_token_major_and_in_place(d, dtype):
     B, H, N = 2, 4, 700
     q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=71, device="cpu")
