@@ -155,15 +155,19 @@ int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void
  * (LINFUSION_FLAG_UNNORMALIZED: den = 1, go = 0.)  phi' at 0 is the one-sided value 1 for elu+1 and 0
  * for relu.  The forward output is not an input: dout . out is recomputed in fp32.
  *
+ *   state           NULL, or a DEVICE pointer to the fp32 forward state of these q, k, v ([B*H][d*d + d]: S
+ *                   row-major then z, as linfusion_attn_state writes it and as a forward call leaves it in
+ *                   its workspace at linfusion_attn_workspace_state_offset(...)): saves the pass over k, v.
+ *                   16-byte aligned; must not overlap dq, dk, dv or `workspace`.
  *   q, k, v, dout   DEVICE pointers, contiguous [B, H, N, d], fp16 or bf16 (LINFUSION_DTYPE_F32 ->
  *                   LINFUSION_ERR_UNSUPPORTED), d in {8, ..., 64 step 8, 80}.
  *   dq, dk, dv      DEVICE pointers, same shape and type; must not overlap any input or each other.
  *   flags           LINFUSION_FLAG_NONE or LINFUSION_FLAG_UNNORMALIZED (anything else -> ERR_INVALID).
  *   workspace       DEVICE scratch of at least linfusion_attn_bwd_workspace_bytes(...) bytes, 16-byte
  *                   aligned, caller-owned, contents undefined before and after.
- * Enqueues six kernels on `stream`; never allocates, never synchronises.  Results are run-to-run identical.
+ * Enqueues six kernels (four when `state` is given) on `stream`; never allocates, never synchronises.  Results are run-to-run identical.
  */
-int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* dout,
+int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* dout, const float* state,
                        void* dq, void* dk, void* dv,
                        int B, int H, long long N, int d,
                        int dtype, int feature_map, float eps, unsigned flags,
@@ -179,6 +183,13 @@ size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int 
  */
 int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes,
                               int B, int H, long long N, int d, int dtype, void* stream);
+
+/*
+ * Byte offset, inside the workspace of linfusion_attn_fwd_ex / _fwd_strided, at which a completed forward
+ * call of this shape has left the head states ([B*H][d*d + d] fp32, S row-major then z).  A later call
+ * with the same workspace overwrites them.  Pure host function; 0 for rejected arguments.
+ */
+size_t linfusion_attn_workspace_state_offset(int B, int H, long long N, int d, int dtype);
 
 /*
  * Bytes of device scratch linfusion_attn_fwd_ex needs for this shape.  Pure host function of

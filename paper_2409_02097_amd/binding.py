@@ -50,8 +50,10 @@ def library() -> ctypes.CDLL:
     lib.linfusion_attn_fwd_profile.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, st3, st3, st3,
                                                vp, sz, vp, ctypes.POINTER(ctypes.c_void_p * 4)]
     lib.linfusion_attn_fwd_profile.restype = i32
-    lib.linfusion_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp]
+    lib.linfusion_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp]
     lib.linfusion_attn_bwd.restype = i32
+    lib.linfusion_attn_workspace_state_offset.argtypes = [i32, i32, i64, i32, i32]
+    lib.linfusion_attn_workspace_state_offset.restype = sz
     lib.linfusion_attn_bwd_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
     lib.linfusion_attn_bwd_workspace_bytes.restype = sz
     lib.linfusion_attn_last_error.argtypes = [vp, sz, i32, i32, i64, i32, i32, vp]
@@ -131,13 +133,19 @@ def linfusion_attn_bwd_workspace_bytes(B: int, H: int, N: int, d: int, dtype: in
     return int(library().linfusion_attn_bwd_workspace_bytes(B, H, N, d, dtype))
 
 
+def linfusion_attn_workspace_state_offset(B: int, H: int, N: int, d: int, dtype: int) -> int:
+    return int(library().linfusion_attn_workspace_state_offset(B, H, N, d, dtype))
+
+
 def linfusion_attn_bwd(q, k, v, dout, dq, dk, dv, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6,
-                       flags: int = FLAG_NONE, workspace=None, stream=None, check: bool = True) -> int:
-    """dq, dk, dv <- gradients of the mixer for upstream gradient dout (contiguous [B, H, N, d] tensors)."""
+                       flags: int = FLAG_NONE, workspace=None, stream=None, check: bool = True, state=None) -> int:
+    """dq, dk, dv <- gradients of the mixer for upstream gradient dout (contiguous [B, H, N, d] tensors).
+    `state`: optional fp32 device tensor holding the forward state of q, k, v."""
     B, H, N, d = _check_layout(q, k, v, dout, dq, dk, dv)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    rc = library().linfusion_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(), dq.data_ptr(),
+    rc = library().linfusion_attn_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(),
+                                      state.data_ptr() if state is not None else None, dq.data_ptr(),
                                       dk.data_ptr(), dv.data_ptr(), B, H, N, d, _dtype_code(q), feature_map, eps,
                                       flags, ws_ptr, ws_bytes, _stream_ptr(stream))
     if check and rc != 0:

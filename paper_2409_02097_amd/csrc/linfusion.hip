@@ -694,6 +694,12 @@ int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes, int
   return (pair[1] == 1u && pair[0] != 0u && pair[0] == g_last_ticket.load()) ? LINFUSION_ERR_TIMEOUT : LINFUSION_OK;
 }
 
+size_t linfusion_attn_workspace_state_offset(int B, int H, long long N, int d, int dtype) {
+  Plan p;
+  if (make_plan(B, H, N, d, dtype, 0u, &p) != LINFUSION_OK) return 0;
+  return p.ws_partials;
+}
+
 size_t linfusion_attn_workspace_bytes(int B, int H, long long N, int d, int dtype) {
   Plan p;
   if (make_plan(B, H, N, d, dtype, 0u, &p) != LINFUSION_OK) return 0;

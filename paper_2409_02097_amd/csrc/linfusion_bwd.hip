@@ -65,6 +65,7 @@ bool allow_lds(KernelT kernel, int bytes) {
 }
 
 struct BwdArgs {
+  const float* saved_state;   // the forward state of the same q, k, v, or null: recompute it from k, v
   const void *q, *k, *v, *g;
   void *dq, *dk, *dv;
   int B, H;
@@ -104,8 +105,12 @@ int run_bwd(const BwdArgs& a) {
       !allow_lds(bwd_state16<T, D, FM, NORM>, lds_s) || !allow_lds(bwd_kv16<T, D, FM>, lds_a))
     return LINFUSION_ERR_HIP;
 
-  state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, dense, all, partials, a.N, p.blk_reduce);
-  combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateS);
+  if (a.saved_state) {
+    stateS = const_cast<float*>(a.saved_state);   // only read below
+  } else {
+    state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, dense, all, partials, a.N, p.blk_reduce);
+    combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateS);
+  }
   bwd_q16<T, D, FM, NORM><<<ga, blk, lds_a, st>>>(Q, G, (u32x4*)a.dq, stateS, scal, a.eps, a.N, p.blk_apply);
   bwd_state16<T, D, FM, NORM><<<dim3(p.gsplits, (unsigned)BH), blk, lds_s, st>>>(Q, G, scal, stateS, partials, a.N,
                                                                                   p.gblk_reduce);
@@ -150,9 +155,9 @@ size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int 
   return p.ws_total;
 }
 
-int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* dout, void* dq, void* dk, void* dv,
-                       int B, int H, long long N, int d, int dtype, int feature_map, float eps, unsigned flags,
-                       void* workspace, size_t workspace_bytes, void* stream) {
+int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* dout, const float* state, void* dq,
+                       void* dk, void* dv, int B, int H, long long N, int d, int dtype, int feature_map, float eps,
+                       unsigned flags, void* workspace, size_t workspace_bytes, void* stream) {
   if (!q || !k || !v || !dout || !dq || !dk || !dv) return LINFUSION_ERR_INVALID;
   if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
   if (flags & ~LINFUSION_FLAG_UNNORMALIZED) return LINFUSION_ERR_INVALID;
@@ -176,13 +181,20 @@ int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* 
   if (!workspace) return LINFUSION_ERR_WORKSPACE;
   if ((uintptr_t)workspace & 15) return LINFUSION_ERR_MISALIGNED;
   if (workspace_bytes < p.ws_total) return LINFUSION_ERR_WORKSPACE;
+  if (state) {
+    const size_t sbytes = (size_t)B * H * p.ne * sizeof(float);
+    if ((uintptr_t)state & 15) return LINFUSION_ERR_MISALIGNED;
+    if (overlaps(workspace, p.ws_total, state, sbytes)) return LINFUSION_ERR_OVERLAP;
+    for (void* x : outs)
+      if (overlaps(x, tbytes, state, sbytes)) return LINFUSION_ERR_OVERLAP;
+  }
   for (const void* x : ins)
     if (overlaps(workspace, p.ws_total, x, tbytes)) return LINFUSION_ERR_OVERLAP;
   for (void* x : outs)
     if (overlaps(workspace, p.ws_total, x, tbytes)) return LINFUSION_ERR_OVERLAP;
   rc = lfh::check_device();
   if (rc != LINFUSION_OK) return rc;
-  BwdArgs a{q, k, v, dout, dq, dk, dv, B, H, N, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
+  BwdArgs a{state, q, k, v, dout, dq, dk, dv, B, H, N, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
             &p, (unsigned char*)workspace, (hipStream_t)stream};
   return dispatch_bwd(d, dtype, feature_map, a);
 }

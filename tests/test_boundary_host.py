@@ -125,15 +125,17 @@ def test_stride_validation_happens_on_the_host():
 def test_backward_argument_validation_happens_on_the_host():
     lib = lf.library()
 
-    def call(q=4096, k=1 << 20, v=2 << 20, g=3 << 20, dq=4 << 20, dk=5 << 20, dv=6 << 20, d=40, dtype=1, fm=0, eps=1e-6,
+    def call(state=None, q=4096, k=1 << 20, v=2 << 20, g=3 << 20, dq=4 << 20, dk=5 << 20, dv=6 << 20, d=40, dtype=1, fm=0, eps=1e-6,
              flags=0, ws=64 << 20, ws_bytes=8 << 20):
-        return lib.linfusion_attn_bwd(q, k, v, g, dq, dk, dv, 1, 2, 64, d, dtype, fm, eps, flags, ws, ws_bytes, None)
+        return lib.linfusion_attn_bwd(q, k, v, g, state, dq, dk, dv, 1, 2, 64, d, dtype, fm, eps, flags, ws, ws_bytes, None)
     assert call(g=None) == -1 and call(dk=None) == -1 and call(eps=-1.0) == -1 and call(flags=2) == -1
     assert call(dtype=0) == -2 and call(d=160) == -2 and call(d=12) == -2 and call(fm=3) == -2
     assert call(dq=(4 << 20) + 8) == -3 and call(ws=(64 << 20) + 4) == -3
     assert call(ws=None) == -4 and call(ws_bytes=64) == -4
     assert call(dq=4096) == -7 and call(dk=4 << 20) == -7 and call(dv=(2 << 20) + 256) == -7 and call(ws=6 << 20) == -7
+    assert call(state=(7 << 20) + 4) == -3 and call(state=4 << 20) == -7 and call(state=64 << 20) == -7
     assert lf.linfusion_attn_bwd_workspace_bytes(1, 2, 64, 40, 1) > 0
+    assert 0 < lf.linfusion_attn_workspace_state_offset(1, 2, 64, 40, 1) < lf.linfusion_attn_workspace_bytes(1, 2, 64, 40, 1)
     assert lf.linfusion_attn_bwd_workspace_bytes(1, 2, 64, 40, 0) == 0
 
 

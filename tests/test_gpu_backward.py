@@ -114,6 +114,29 @@ def test_backward_is_run_to_run_identical_and_leaves_inputs_alone():
         assert torch.equal(dev.cpu().view(torch.uint8), host.view(torch.uint8))
 
 
+@pytest.mark.parametrize("path", [lf.FLAG_FORCE_SPLIT, lf.FLAG_FORCE_FUSED])
+def test_backward_with_the_state_a_forward_call_left_in_its_workspace(path):
+    B, H, N, d, dtype = 2, 3, 1500, 40, "f16"
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=83, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 83777, dtype, "cpu")
+    qd, kd, vd, gd = q.cuda(), k.cuda(), v.cuda(), g.cuda()
+    fws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, 1), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(qd)
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, 1e-6, path, fws)
+    off = lf.linfusion_attn_workspace_state_offset(B, H, N, d, 1)
+    state = fws[off:off + B * H * (d * d + d) * 4].view(torch.float32)
+    ws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, 1), dtype=torch.uint8, device="cuda")
+    a = [torch.full_like(qd, float("nan")) for _ in range(3)]
+    b = [torch.full_like(qd, float("nan")) for _ in range(3)]
+    lf.linfusion_attn_bwd(qd, kd, vd, gd, *a, 0, 1e-6, 0, ws, state=state)
+    lf.linfusion_attn_bwd(qd, kd, vd, gd, *b, 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    _check(a, q, k, v, g, dtype, 0, 1e-6, True, "bwd with saved state")
+    if path == lf.FLAG_FORCE_SPLIT:       # same kernels produced the state: the gradients are identical
+        for x, y in zip(a, b):
+            assert torch.equal(x.view(torch.uint8), y.view(torch.uint8))
+
+
 def test_backward_argument_checks():
     x = torch.zeros(1, 1, 64, 40, dtype=torch.float16, device="cuda")
     outs = [torch.empty_like(x) for _ in range(3)]
