@@ -186,3 +186,40 @@ def test_single_launch_falls_back_when_heads_exceed_residency():
     q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=69, device="cpu")
     out = _run(q.cuda(), k.cuda(), v.cuda(), flags=lf.FLAG_FORCE_FUSED)
     parity.check_all(out, q, k, v, "f16", 0, 1e-6, True, "fallback")
+
+
+@pytest.mark.parametrize("path", list(PATHS))
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("case", ["zeros", "large_positive", "large_negative", "tiny"])
+def test_extreme_values_match_oracle(dtype, case, path):
+    """Inputs at the edges of the feature map: phi(0) = 1 everywhere; q, k = 30 (state entries ~ N * 31 * |v|,
+    beyond fp16 without the power-of-two rescaling); q, k = -20 (phi ~ 2e-9 is below fp16's range, and eps
+    takes over the denominator); q, k, v ~ 1e-3."""
+    B, H, N, d = 1, 2, 777, 40
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=66, device="cpu")
+    if case == "zeros":
+        q, k, v = torch.zeros_like(q), torch.zeros_like(k), torch.zeros_like(v)
+    elif case == "large_positive":
+        q, k = q * 0.5 + 30.0, k * 0.5 + 30.0
+    elif case == "large_negative":
+        q, k = q * 0.5 - 20.0, k * 0.5 - 20.0
+    else:
+        q, k, v = q * 1e-3, k * 1e-3, v * 1e-3
+    out = _run(q.cuda(), k.cuda(), v.cuda(), flags=PATHS[path])
+    parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"{case} {dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_a_nan_stays_inside_its_head(dtype):
+    B, H, N, d = 1, 3, 500, 40
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=67, device="cpu")
+    k[0, 1, 123, 7] = float("nan")
+    out = _run(q.cuda(), k.cuda(), v.cuda())
+    assert bool(torch.isnan(out[0, 1]).all()), "the poisoned head must not produce numbers"
+    clean = torch.isfinite(out[0, 0]).all() and torch.isfinite(out[0, 2]).all()
+    assert bool(clean), "other heads must be unaffected"
+    k[0, 1, 123, 7] = 0.0
+    for h in (0, 2):
+        ref = __import__("oracle.linattn_oracle", fromlist=["x"]).attention_linear_stored(
+            wl.stored_numpy(q)[0, h], wl.stored_numpy(k)[0, h], wl.stored_numpy(v)[0, h], dtype, 0, 1e-6, True)
+        parity.check_slice(parity.to_f64(out[0, h]), ref, dtype, f"head {h} next to a NaN head")
