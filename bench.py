@@ -246,7 +246,8 @@ def main():
     }
     if args.backward:
         # gradient tensors resident in HBM; minimal traffic = q, k, v, dout read + dq, dk, dv written (7 tensors);
-        # the kernels read q and dout twice and k, v twice (11 tensor passes plus 8 bytes per token-head)
+        # the kernels read k, v twice (9 tensor passes); bf16 and d > 48 also read q and dout twice (11 passes
+        # plus 16 bytes per token-head of scalars written and read)
         g = torch.randn_like(q)
         grads = [torch.empty_like(q) for _ in range(3)]
         bws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
@@ -263,10 +264,12 @@ def main():
         torch.cuda.synchronize()
         bdt = (time.perf_counter() - tb) / bsteps
         tensor_bytes = alg_bytes / 4
+        merged = dtype == "f16" and d <= 48
+        kbytes = 9 * tensor_bytes if merged else 11 * tensor_bytes + 16.0 * B * H * N
         result["backward"] = {"ms_per_step": bdt * 1e3, "tokens_per_s": B * N / bdt,
                               "min_traffic_gbps": 7 * tensor_bytes / bdt / 1e9,
-                              "kernel_traffic_gbps": (11 * tensor_bytes + 8.0 * B * H * N * 2) / bdt / 1e9,
-                              "frac_of_peak_kernel_traffic": (11 * tensor_bytes + 16.0 * B * H * N) / bdt / 1e9 / HBM_PEAK_GBPS}
+                              "kernel_traffic_gbps": kbytes / bdt / 1e9,
+                              "frac_of_peak_kernel_traffic": kbytes / bdt / 1e9 / HBM_PEAK_GBPS}
         del g, grads, bws
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(q, k, v, cfg, args.cpu_sample_tokens)

@@ -6,7 +6,7 @@
 //     dr_i = (u_i - go_i z) / den_i ,   dq = dr * phi'(q)
 //     e_i  = -go_i / den_i ,            dS = R^T (g / den) ,  dz = R^T e
 //     dp_j = dS v_j + dz ,              dk = dp * phi'(k) ,   dv_j = dS^T p_j
-// (un-normalized: den = 1, go = e = 0).  Five launches:
+// (un-normalized: den = 1, go = e = 0).  Launches (fp16 with d <= 48 merges the second and third: bwd_qs16):
 //     state_reduce16 + combine_state    S, z                         (the forward kernels)
 //     bwd_q16                           reads Q, g: writes dQ and per token {1 / den_i, e_i}
 //     bwd_state16 + combine_state       reads Q, g and those scalars: dS, dz
@@ -87,6 +87,14 @@ struct Ring2 {
   // pointer to byte `byte` of this lane's token row (pieces never straddle a 16-byte chunk)
   LF_DEV unsigned char* byte_ptr(int slot, int which, int byte) const {
     return chunk_ptr(slot, which, byte >> 4) + (byte & 15);
+  }
+
+  // address of the four 16-bit elements (row, col .. col + 3) of tile part `which`, col a multiple of 4: what
+  // one lane names in a transposing LDS read
+  LF_DEV const uint16_t* tr_ptr(int slot, int which, int row, int col) const {
+    const int chunk = col >> 3;
+    return reinterpret_cast<const uint16_t*>(tile_ptr(slot, which) + row * AC::kRowBytes +
+                                             ((chunk ^ AC::swz(row)) << 4) + (col & 7) * 2);
   }
 
   // copies tile `tile` of both tensors into ring slot `slot`: always 2 NL vector memory instructions
@@ -328,6 +336,191 @@ bwd_q16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __restr
     rg.ahead.next();
     slot = slot + 1 == R ? 0 : slot + 1;
   }
+}
+
+// ==========================================================================================
+// bwd_qs16 (fp16): bwd_q16 and bwd_state16 in one pass over Q and g.  After a tile's dq is known, the wave
+// overwrites the Q tile in its LDS slot with phi(q) and the g tile with g beta / den (16-bit), keeps
+// e_i beta in a 32-entry column, and accumulates dS += phi(q)^T (g beta / den), dz += phi(q)^T (e beta) with
+// transposing LDS reads exactly as the reductions do; then dq takes the Q tile's place and leaves.
+// At the end the four waves' accumulators are summed in a fixed order and written (divided by beta) as
+// this workgroup's partial: [B*H][gridDim.x][D*D + D], for combine_state.  No per-token scalars in memory,
+// two tensor passes fewer.  LDS: BwdCfg<D>::lds_bytes() + 256.
+// ==========================================================================================
+template <typename T, int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+bwd_qs16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __restrict__ dQ,
+         const float* __restrict__ state, float* __restrict__ partials, float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using RG = Ring2<T, D>;
+  using Sh = Shape16<D>;
+  static_assert(NSplit<T>::value == 1, "single-level operands only (fp16)");
+  constexpr int NS = 1, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
+  constexpr int MT = Sh::kMT, NE = D * D + D;
+  const long long bh = blockIdx.y;
+  const long long hoff = bh * N * CPR;
+  RG rg(Q + hoff, G + hoff, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  u32x4* dQh = dQ + hoff;
+  uint16_t* ecol = reinterpret_cast<uint16_t*>(smem + BwdCfg<D>::lds_bytes()) + rg.wave * 32;
+  rg.prefetch();
+
+  const float aS = rg.stage_state(state + bh * NE);
+  u32x4 A[NS][MTB][KS];
+  rg.template build_A<false>(aS, A);
+  float zo[HALF];
+  rg.load_vec(zo);
+  const float inv_aS = 1.0f / aS;
+  float beta = 1.0f, inv_beta = 1.0f;
+  if constexpr (NORM) {   // power of two near the typical denominator (see bwd_state16)
+    const float* z = reinterpret_cast<const float*>(smem + BwdCfg<D>::kStageOffset) + D * D;
+    float zs = 0.0f;
+    for (int i = 0; i < D; ++i) zs += z[i];
+    if (zs > 0.0f && zs < 3.0e38f) {
+      int ex;
+      (void)__builtin_frexpf(zs, &ex);
+      ex = ex > 100 ? 100 : (ex < -100 ? -100 : ex);
+      beta = __builtin_ldexpf(1.0f, ex);
+      inv_beta = __builtin_ldexpf(1.0f, -ex);
+    }
+  }
+  __syncthreads();
+
+  f32x4 accS[MT][MT], accZ[MT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    accZ[a] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < MT; ++b) accS[a][b] = f32x4{0, 0, 0, 0};
+  }
+  const int j16 = rg.lane & 15, g4 = rg.lane >> 4;
+  const int tr_row = 8 * g4 + (j16 >> 2), tr_col = 4 * (j16 & 3);
+
+  int slot = 0, iter = 0;
+  while (rg.it.valid()) {
+    const long long tile = rg.it.t;
+    int aslot = slot + (R - 1);
+    if (aslot >= R) aslot -= R;
+    const bool more = rg.ahead.valid();
+    if (more) rg.issue_copy(rg.ahead.t, aslot);
+    rg.template wait_tile<NL>(iter, more);
+    iter = iter < 2 ? iter + 1 : 2;
+    long long rem = N - tile * kTile;
+    const bool ok = rg.tok < (rem < kTile ? (int)rem : kTile);
+
+    u32x4 Bg[KS];
+    rg.read_B_raw(slot, 1, Bg);
+    f32x16 acc[MTB];
+    rg.products(A, Bg, nullptr, acc);
+    float x[HALF], dr[HALF], rr[HALF];
+    rg.read_half_row(slot, 0, x);
+    float denp = 0.0f, rup = 0.0f;
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const float r = phi<FM>(x[i]);
+      const float u = acc[i / 16][i % 16] * inv_aS;
+      denp = __builtin_fmaf(r, zo[i], denp);
+      rup = __builtin_fmaf(r, u, rup);
+      dr[i] = u;
+      rr[i] = ok ? r : 0.0f;
+      x[i] = phi_prime_from<FM>(x[i], r);
+    }
+    float gsc = ok ? 1.0f : 0.0f, e = 0.0f;
+    if constexpr (NORM) {
+      const float den = denp + __shfl_xor(denp, 32) + eps;
+      const float ru = rup + __shfl_xor(rup, 32);
+      const float invden = 1.0f / den;
+      const float go = ru * invden;
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) dr[i] = (dr[i] - go * zo[i]) * invden * x[i];
+      gsc = ok ? invden * beta : 0.0f;
+      e = ok ? -go * invden * beta : 0.0f;
+    } else {
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) dr[i] *= x[i];
+    }
+    // ---- phi(q), g beta / den and e beta take the tiles' places --------------------------------------
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.write_half_row(slot, 0, rr);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int chunk = rg.kg * KS + s;
+      if (chunk < CPR) {
+        u32x4 w;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          float g0, g1;
+          unpack2<T>(Bg[s][c], g0, g1);
+          w[c] = pack2<T>(g0 * gsc, g1 * gsc);
+        }
+        *reinterpret_cast<u32x4*>(rg.chunk_ptr(slot, 1, chunk)) = w;
+      }
+    }
+    if (rg.kg == 0) ecol[rg.tok] = (uint16_t)pack2<T>(e, 0.0f);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    // ---- dS, dz: token-major operands by transposing reads --------------------------------------------
+    {
+      u32x4 bfrag[MT], bfe = u32x4{0, 0, 0, 0};
+      if (j16 == 0) bfe = *reinterpret_cast<const u32x4*>(ecol + 8 * g4);
+#pragma unroll
+      for (int b = 0; b < MT; ++b) {
+        const u32x2 r0 = lds_read_tr16(rg.tr_ptr(slot, 1, tr_row, 16 * b + tr_col));
+        const u32x2 r1 = lds_read_tr16(rg.tr_ptr(slot, 1, tr_row + 4, 16 * b + tr_col));
+        bfrag[b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+      }
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        const u32x2 r0 = lds_read_tr16(rg.tr_ptr(slot, 0, tr_row, 16 * a + tr_col));
+        const u32x2 r1 = lds_read_tr16(rg.tr_ptr(slot, 0, tr_row + 4, 16 * a + tr_col));
+        const u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+        for (int b = 0; b < MT; ++b) accS[a][b] = mfma_16x16x32<T>(afrag, bfrag[b], accS[a][b]);
+        accZ[a] = mfma_16x16x32<T>(afrag, bfe, accZ[a]);
+      }
+    }
+    // ---- dq takes the Q tile's place and leaves -----------------------------------------------------------
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.write_half_row(slot, 0, dr);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.store_tile(tile, slot, 0, dQh);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.it.next();
+    rg.ahead.next();
+    slot = slot + 1 == R ? 0 : slot + 1;
+  }
+
+  // ---- cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3), then the partial ---------------------------
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem);
+  float* mine = red + (rg.wave & 1) * NE;
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    if ((rg.wave >> 1) == round) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = a * 16 + 4 * g4 + i;
+          if (row < D) {
+#pragma unroll
+            for (int b = 0; b < MT; ++b) {
+              const int col = b * 16 + j16;
+              if (col < D) {
+                float* p = mine + row * D + col;
+                *p = (round == 0) ? accS[a][b][i] : *p + accS[a][b][i];
+              }
+            }
+            if (j16 == 0) {
+              float* p = mine + D * D + row;
+              *p = (round == 0) ? accZ[a][i] : *p + accZ[a][i];
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)NE;
+  for (int i = threadIdx.x; i < NE; i += kThreads) dst[i] = (red[i] + red[NE + i]) * inv_beta;
 }
 
 // ==========================================================================================

@@ -46,7 +46,9 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
                           &p->blk_apply);
   p->ne = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  p->ws_partials = up((size_t)BH * (p->splits > p->gsplits ? p->splits : p->gsplits) * p->ne * sizeof(float));
+  int most = p->splits > p->gsplits ? p->splits : p->gsplits;
+  if (p->apply_wgs > most) most = p->apply_wgs;   // the merged dQ + state-gradient kernel writes one partial each
+  p->ws_partials = up((size_t)BH * most * p->ne * sizeof(float));
   p->ws_state = up((size_t)BH * p->ne * sizeof(float));
   p->ws_scal = up((size_t)BH * (size_t)N * 2 * sizeof(float));
   p->ws_total = p->ws_partials + 2 * p->ws_state + p->ws_scal;
@@ -110,6 +112,18 @@ int run_bwd(const BwdArgs& a) {
   } else {
     state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, dense, all, partials, a.N, p.blk_reduce);
     combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateS);
+  }
+  // fp16 up to d = 48: dQ and the state gradient in one pass over Q and dout (registers allow it there)
+  constexpr bool kMerged = NSplit<T>::value == 1 && D <= 48;
+  if constexpr (kMerged) {
+    if (lfh::env_int("LINFUSION_BWD_MERGED", 1) == 1) {
+      if (!allow_lds(bwd_qs16<T, D, FM, NORM>, lds_a + 256)) return LINFUSION_ERR_HIP;
+      bwd_qs16<T, D, FM, NORM><<<ga, blk, lds_a + 256, st>>>(Q, G, (u32x4*)a.dq, stateS, partials, a.eps, a.N,
+                                                             p.blk_apply);
+      combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.apply_wgs, NE, stateD);
+      bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, (u32x4*)a.dk, (u32x4*)a.dv, stateD, a.N, p.blk_apply);
+      return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+    }
   }
   bwd_q16<T, D, FM, NORM><<<ga, blk, lds_a, st>>>(Q, G, (u32x4*)a.dq, stateS, scal, a.eps, a.N, p.blk_apply);
   bwd_state16<T, D, FM, NORM><<<dim3(p.gsplits, (unsigned)BH), blk, lds_s, st>>>(Q, G, scal, stateS, partials, a.N,

@@ -83,6 +83,17 @@ def test_backward_matches_oracle(B, H, N, d, dtype):
     print(f"  worst max-norm ratio {worst:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 1000, 40), (2, 2, 333, 16), (1, 1, 4099, 48)])
+def test_backward_separate_kernels_for_fp16_small_widths(B, H, N, d, monkeypatch):
+    """fp16 with d <= 48 normally takes the merged dQ + state-gradient kernel; the separate kernels (what bf16
+    and wider heads use) must give the same gradients to tolerance."""
+    monkeypatch.setenv("LINFUSION_BWD_MERGED", "2")
+    q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=84, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 84777, "f16", "cpu")
+    outs = _run(q, k, v, g)
+    _check(outs, q, k, v, g, "f16", 0, 1e-6, True, f"bwd separate kernels N={N} d={d}")
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("fm,normalize", [(1, True), (2, True), (0, False), (1, False)])
 def test_backward_other_feature_maps_and_unnormalized(dtype, fm, normalize):
