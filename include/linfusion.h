@@ -64,7 +64,7 @@ extern "C" {
 #define LINFUSION_ERR_WORKSPACE (-4)   /* workspace_bytes below linfusion_attn_workspace_bytes() */
 #define LINFUSION_ERR_HIP (-5)         /* a HIP runtime call or kernel launch failed */
 #define LINFUSION_ERR_DEVICE (-6)      /* no HIP device, or the current device is not gfx950 */
-#define LINFUSION_ERR_OVERLAP (-7)     /* out overlaps k or v, or partially overlaps q */
+#define LINFUSION_ERR_OVERLAP (-7)     /* an output overlaps an input it must not, another output, or the workspace */
 #define LINFUSION_ERR_TIMEOUT (-8)     /* a single-launch call gave up waiting at its internal barrier */
 
 /*
@@ -119,6 +119,11 @@ int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out
  * its first to its last element: the range of `out` must be disjoint from those of k and v and
  * from that of q, except that out == q with identical strides (in place) is allowed.
  * Everything else is as for linfusion_attn_fwd_ex (same workspace size, same two launch paths).
+ * Speed: 16-bit tensors whose heads are neighbours in memory (head stride == d) and whose head rows are
+ * not whole 128-byte lines (d = 40, say) are moved in groups of 4 or 8 heads as whole contiguous row
+ * pieces once the problem is large enough for that to pay (about 24 MB of tensor traffic); they then
+ * run as fast as the contiguous layout.  Results there may differ from the contiguous call's in the
+ * last bits (another summation order); they stay run-to-run identical.
  */
 int linfusion_attn_fwd_strided(const void* q, const void* k, const void* v, void* out,
                                int B, int H, long long N, int d,
