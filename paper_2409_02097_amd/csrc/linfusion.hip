@@ -87,7 +87,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   if (is_wide(d)) {
     // wide kernels: every wave of a workgroup visits every tile of its blocks; three-kernel path only
     auto per_head = [&](int want_total, int blk_dflt, const char* env_blk, int* blk) {
-      long long s = (want_total + BH - 1) / BH;
+      long long s = want_total / BH;   // rounded down: one workgroup too many costs a whole extra round
       if (s > p->n_tiles) s = p->n_tiles;
       if (s < 1) s = 1;
       const long long t = (p->n_tiles + s - 1) / s;
@@ -115,7 +115,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   }
   const long long max_s = (p->n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;   // >= one tile per wave
   auto per_head = [&](int want_total, long long* share) {
-    long long s = (want_total + BH - 1) / BH;
+    long long s = want_total / BH;   // rounded down: one workgroup too many costs a whole extra round
     if (s > max_s) s = max_s;
     if (s < 1) s = 1;
     long long t = (p->n_tiles + s - 1) / s;
@@ -144,7 +144,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   p->groups = B * (H / p->gwaves);
   if (p->groups > 0) {
     auto per_group = [&](int want_total, long long* sh) {
-      long long s = (want_total + p->groups - 1) / p->groups;
+      long long s = want_total / p->groups;
       if (s > p->n_tiles) s = p->n_tiles;
       if (s < 1) s = 1;
       long long t = (p->n_tiles + s - 1) / s;

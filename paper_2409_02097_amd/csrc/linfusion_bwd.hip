@@ -30,7 +30,7 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   const long long n_tiles = (N + lf::kTile - 1) / lf::kTile;
   const long long max_s = (n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;
   auto per_head = [&](int want_total, int blk_dflt, int* blk) {
-    long long s = (want_total + BH - 1) / BH;
+    long long s = want_total / BH;   // rounded down: one workgroup too many costs a whole extra round
     if (s > max_s) s = max_s;
     if (s < 1) s = 1;
     long long t = (n_tiles + s - 1) / s;
