@@ -90,7 +90,9 @@ extern "C" {
  *                    Calls that share a workspace must be ordered on one stream.
  *   stream           hipStream_t (NULL = default stream).
  *
- * Never allocates, never synchronises.
+ * Never allocates, never synchronises; may be recorded into a HIP graph (while `stream` is being
+ * captured the split path is taken whatever the flags say: the single launch's barrier tickets are
+ * per call and must not be replayed).
  */
 int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out,
                           int B, int H, long long N, int d,

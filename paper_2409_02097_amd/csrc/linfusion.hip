@@ -245,6 +245,17 @@ bool allow_lds(KernelT kernel, int bytes) {
   return true;
 }
 
+// The single-launch kernel's barriers compare flags against a ticket that is new for every call; a captured
+// launch would replay an old ticket (its flags already match), so under stream capture the three-kernel path runs.
+bool capturing(hipStream_t st) {
+  hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &status) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return status != hipStreamCaptureStatusNone;
+}
+
 struct Args {
   const void *q, *k, *v;
   void* out;
@@ -298,7 +309,7 @@ int run16(const Args& a) {
   const u32x4* Q = (const u32x4*)a.q;
   u32x4* O = (u32x4*)a.out;
   hipStream_t st = a.st;
-  if (p.path == 1 && a.out && !(a.group_reduce || a.group_apply)) {
+  if (p.path == 1 && a.out && !(a.group_reduce || a.group_apply) && !capturing(a.st)) {
     unsigned* sync = reinterpret_cast<unsigned*>(a.ws + p.ws_partials + p.ws_state);
     unsigned* err = sync + a.BH * 2 * p.fsplits;
     const dim3 g(p.fsplits, (unsigned)a.BH);
@@ -423,7 +434,7 @@ int run32(const Args& a) {
   constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
   constexpr size_t ldsf = fused32_lds_bytes<D>();
   constexpr size_t ldsa = apply32_lds_bytes<D>();
-  if (p.path == 1 && a.out) {
+  if (p.path == 1 && a.out && !capturing(a.st)) {
     unsigned* sync = reinterpret_cast<unsigned*>(a.ws + p.ws_partials + p.ws_state);
     unsigned* err = sync + a.BH * 2 * p.fsplits;
     const dim3 g(p.fsplits, (unsigned)a.BH);

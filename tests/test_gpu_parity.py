@@ -223,3 +223,36 @@ def test_a_nan_stays_inside_its_head(dtype):
         ref = __import__("oracle.linattn_oracle", fromlist=["x"]).attention_linear_stored(
             wl.stored_numpy(q)[0, h], wl.stored_numpy(k)[0, h], wl.stored_numpy(v)[0, h], dtype, 0, 1e-6, True)
         parity.check_slice(parity.to_f64(out[0, h]), ref, dtype, f"head {h} next to a NaN head")
+
+
+def test_forward_recorded_into_a_graph_replays_correctly():
+    """A mid-sized problem (the single launch would be chosen eagerly) captured once and replayed with new
+    inputs in the same buffers, with eager calls and synchronisations in between: every replay must give
+    what an eager call on the same inputs gives."""
+    B, H, N, d, dtype = 2, 10, 16384, 64, "bf16"          # 84 MB of tensor traffic: inside the single-launch window
+    code = wl.DTYPE_CODE[dtype]
+    assert lf.linfusion_attn_plan(B, H, N, d, code)["path"] == 1
+    q, k, v = (t.cuda() for t in wl.make_qkv(B, H, N, d, dtype, idx=68, device="cpu"))
+    out = torch.zeros_like(q)
+    ws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                          # warm-up outside the capture
+        lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, 0, ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, 0, ws, stream=torch.cuda.current_stream())
+    for rep in range(3):
+        nq, nk, nv = (t.cuda() for t in wl.make_qkv(B, H, N, d, dtype, idx=68, device="cpu", seed_offset=rep + 1))
+        q.copy_(nq); k.copy_(nk); v.copy_(nv)
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = torch.empty_like(nq)
+        ews = torch.empty_like(ws)
+        lf.linfusion_attn_fwd_ex(nq, nk, nv, eager, 0, 1e-6, lf.FLAG_FORCE_SPLIT, ews)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.uint8), eager.view(torch.uint8)), f"replay {rep} differs from the eager call"
+    worst = parity.check_all(out[:, :2], q[:, :2].cpu(), k[:, :2].cpu(), v[:, :2].cpu(), dtype, 0, 1e-6, True, "graph replay")
