@@ -73,9 +73,10 @@ extern "C" {
  *
  * Two launch shapes compute it.  The split path enqueues three kernels (state reduction,
  * combine, apply).  The single-launch path runs the same three phases in one kernel whose
- * workgroups meet at two per-head barriers; it is chosen automatically for mid-sized problems
- * (about 64 MB to 512 MB of tensor traffic, where draining and refilling the chip between
- * kernels costs a visible share), can be forced or forbidden with the flags, and is used only
+ * workgroups meet at two per-head barriers; it is chosen automatically where it measured
+ * faster (16-bit heads of 56 or 64 channels with about 128 MB to 1 GB of tensor traffic, where
+ * draining and refilling the chip between kernels costs a visible share), can be forced or
+ * forbidden with the flags, and is used only
  * when all of its workgroups are resident at once (otherwise the call falls back to the split
  * path).  Its barrier waits are bounded: if a wait ever expires (which needs another workload
  * to hold the device's compute units for seconds) the kernel ends early, `out` is incomplete,

@@ -72,6 +72,13 @@ int fused_wgs_per_cu(int d, int dtype) {
   return d <= 48 ? 4 : 2;
 }
 
+// Workgroups of the per-head apply kernel that one CU holds at once (registers and LDS).
+int apply_wgs_per_cu(int d, int dtype) {
+  if (dtype == LINFUSION_DTYPE_F32) return 2;
+  if (d > 64) return 2;
+  return fused_wgs_per_cu(d, dtype);
+}
+
 int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan* p) {
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
   if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;   // grid.y limit
@@ -127,8 +134,14 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   // streams keep DRAM pages open
   p->splits = per_head(env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), &share);
   p->blk_reduce = block_tiles(share, "LINFUSION_REDUCE_BLK", 16);
-  // apply (read + write streams): more, smaller workgroups that sweep memory in one moving window
-  p->apply_wgs = per_head(env_int("LINFUSION_APPLY_WGS", 8 * kNumCU), &share);
+  // apply (read + write streams): more, smaller workgroups that sweep memory in one moving window.
+  // Up to a few hundred MB of tensor traffic one resident round measured best (a second, partly filled
+  // round costs more than its finer balance gains); beyond that eight workgroups per CU.
+  const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
+  const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
+  const bool one_round = bytes < (double)env_int("LINFUSION_APPLY_ONE_ROUND_MB", 768) * 1048576.0;
+  const int apply_dflt = (one_round ? apply_wgs_per_cu(d, dtype) : 8) * kNumCU;
+  p->apply_wgs = per_head(env_int("LINFUSION_APPLY_WGS", apply_dflt), &share);
   p->blk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", 8);
   // fused single launch: every workgroup must be resident at once
   const long long cap = (long long)fused_wgs_per_cu(d, dtype) * kNumCU;
@@ -163,16 +176,15 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     p->gsplits = p->gapply_wgs = 0;
     p->gblk_reduce = p->gblk_apply = lf::kWavesPerWG;
   }
-  const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
-  const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
-  // Measured on MI355X: below ~64 MB of tensor traffic the three short kernels are as fast as the
-  // single launch with its two in-kernel barriers; between ~64 MB and ~512 MB the single launch wins
-  // (no drain and refill of the chip between phases); above that both are HBM-bound and equal.
-  const double fused_min = (double)env_int("LINFUSION_FUSED_MIN_MB", 64) * 1048576.0;
-  const double fused_max = (double)env_int("LINFUSION_FUSED_MAX_MB", 512) * 1048576.0;
+  // Measured on MI355X: with the apply launch sized to one resident round the three short kernels match
+  // or beat the single launch (two in-kernel barriers) nearly everywhere; the single launch still wins
+  // by 4-7 % for 16-bit heads of 56 and 64 channels between ~128 MB and ~1 GB of tensor traffic (no
+  // drain and refill of the chip between phases), so only there it is chosen unasked.
+  const double fused_min = (double)env_int("LINFUSION_FUSED_MIN_MB", 128) * 1048576.0;
+  const double fused_max = (double)env_int("LINFUSION_FUSED_MAX_MB", 1024) * 1048576.0;
+  const bool fused_pays = dtype != LINFUSION_DTYPE_F32 && d > 48 && d <= 64 && bytes >= fused_min && bytes <= fused_max;
   p->path = 0;
-  if (p->fsplits > 0 && !(flags & LINFUSION_FLAG_FORCE_SPLIT) &&
-      ((flags & LINFUSION_FLAG_FORCE_FUSED) || (bytes >= fused_min && bytes <= fused_max)))
+  if (p->fsplits > 0 && !(flags & LINFUSION_FLAG_FORCE_SPLIT) && ((flags & LINFUSION_FLAG_FORCE_FUSED) || fused_pays))
     p->path = 1;
   p->state_floats = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };

@@ -229,7 +229,7 @@ def test_forward_recorded_into_a_graph_replays_correctly():
     """A mid-sized problem (the single launch would be chosen eagerly) captured once and replayed with new
     inputs in the same buffers, with eager calls and synchronisations in between: every replay must give
     what an eager call on the same inputs gives."""
-    B, H, N, d, dtype = 2, 10, 16384, 64, "bf16"          # 84 MB of tensor traffic: inside the single-launch window
+    B, H, N, d, dtype = 2, 10, 16384, 64, "bf16"          # 168 MB of tensor traffic, d = 64: inside the single-launch window
     code = wl.DTYPE_CODE[dtype]
     assert lf.linfusion_attn_plan(B, H, N, d, code)["path"] == 1
     q, k, v = (t.cuda() for t in wl.make_qkv(B, H, N, d, dtype, idx=68, device="cpu"))
