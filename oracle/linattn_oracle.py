@@ -41,6 +41,16 @@ the quadratic form with the n x n weights written out, `attention_backward_linea
 reordered through the d x d states (S, z, dS, dz) and is what large-N parity tests call.  Pins
 (tests/test_oracle_backward.py): central differences of `attention_quadratic`, agreement of the two
 forms, dV column sums, orthogonality of d phi(q) to phi(q) at eps = 0, linearity in the upstream gradient.
+Upstream of the mixer (Sec. 4.1, implementation details): f' and g' are two-branch MLPs, a plain
+linear branch plus one Linear-LayerNorm-LeakyReLU block, the two results added; the linear branch starts
+from the softmax layer's W_Q / W_K and the other branch starts at zero.  `mlp_branch_sum` is that sum given
+the two Linear outputs, `module_mixer` feeds it to the mixer over all heads of a token-major tensor.
+Readings where the text names no value: LayerNorm over the whole channel axis C = H d of a token (the MLP
+acts before the split into heads), biased variance, ln_eps = 1e-5 inside the square root, affine gamma and
+beta per channel (gamma = beta = 0 is the zero start), LeakyReLU slope 0.01.  Pins
+(tests/test_oracle_mlp.py): a library layer norm + leaky ReLU, zero mean / unit variance rows, invariance
+to shifting and scaling the LayerNorm input, the zero start reducing the module to the plain mixer,
+a hand-worked row, mutants.
 Unpinned: that elu(x)+1 is the activation the authors trained with (their figure naming it
 is not in the text available to this build) -- "parity unpinned" for that choice only.
 """
@@ -191,6 +201,49 @@ def attention_linear_stored(q, k, v, dtype: str, feature_map: int = ELU_PLUS_ONE
     """Same, on stored tensors: the oracle sees exactly the quantised inputs the GPU sees."""
     return attention_linear(widen(q, dtype), widen(k, dtype), widen(v, dtype),
                             feature_map, eps, normalize)
+
+
+# ----------------------------------------------------------------------------------------
+# The two-branch MLPs f', g' in front of the mixer (Sec. 4.1): what they add after their Linears.
+# ----------------------------------------------------------------------------------------
+def layer_norm_rows(t, gamma, beta, ln_eps: float = 1e-5) -> np.ndarray:
+    """LayerNorm over the last axis (all C channels of a token): (t - mean) / sqrt(var + ln_eps),
+    var the mean squared deviation, then the per-channel affine gamma, beta."""
+    t = np.asarray(t, dtype=np.float64)
+    mean = t.mean(axis=-1, keepdims=True)
+    dev = t - mean
+    var = (dev * dev).mean(axis=-1, keepdims=True)
+    return dev / np.sqrt(var + ln_eps) * np.asarray(gamma, dtype=np.float64) + np.asarray(beta, dtype=np.float64)
+
+
+def leaky_relu(x, slope: float = 0.01) -> np.ndarray:
+    x = np.asarray(x, dtype=np.float64)
+    return np.where(x >= 0.0, x, slope * x)
+
+
+def mlp_branch_sum(a, t, gamma, beta, ln_eps: float = 1e-5, slope: float = 0.01) -> np.ndarray:
+    """Output of f' (or g') for tokens whose linear-branch result is `a` [..., C] and whose second
+    branch's Linear result is `t` [..., C]:  a + LeakyReLU(LayerNorm(t))."""
+    return np.asarray(a, dtype=np.float64) + leaky_relu(layer_norm_rows(t, gamma, beta, ln_eps), slope)
+
+
+def module_mixer(a_q, t_q, a_k, t_k, v, gamma_q, beta_q, gamma_k, beta_k, H: int,
+                 feature_map: int = ELU_PLUS_ONE, eps: float = 0.0, normalize: bool = True,
+                 ln_eps: float = 1e-5, slope: float = 0.01) -> np.ndarray:
+    """Token-major tensors [B, N, C], C = H d, head h owning channels h d .. (h + 1) d - 1:
+    q = f'(X), k = g'(X) from their branch results, then the mixer per (batch, head).  Returns [B, N, C]."""
+    q = mlp_branch_sum(a_q, t_q, gamma_q, beta_q, ln_eps, slope)
+    k = mlp_branch_sum(a_k, t_k, gamma_k, beta_k, ln_eps, slope)
+    v = np.asarray(v, dtype=np.float64)
+    B, N, C = q.shape
+    d = C // H
+    out = np.empty_like(v)
+    for b in range(B):
+        for h in range(H):
+            c = slice(h * d, (h + 1) * d)
+            S, z = state(k[b, :, c], v[b, :, c], feature_map)
+            out[b, :, c] = apply_state(q[b, :, c], S, z, feature_map, eps, normalize)
+    return out
 
 
 # ----------------------------------------------------------------------------------------
