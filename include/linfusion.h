@@ -185,6 +185,48 @@ int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* 
 size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int dtype);
 
 /*
+ * The mixer fed directly by the two-branch MLPs f' and g' that produce its queries and keys (Sec. 4.1,
+ * implementation details: a linear branch, started from the softmax layer's W_Q / W_K, plus one
+ * Linear-LayerNorm-LeakyReLU block, started at zero, the two results added; Prop. 2 names the functions):
+ *
+ *     q_i = a_q,i + LeakyReLU(gamma_q * (t_q,i - mean_i) / sqrt(var_i + ln_eps) + beta_q)      (k likewise)
+ *     out = mixer(q, k, v)                          as linfusion_attn_fwd_ex, per head, Eq. 5 / Prop. 2
+ *
+ * a_* is the result of the linear branch and t_* the result of the second branch's Linear for the same
+ * tokens (both GEMMs are the caller's); mean_i and var_i (mean squared deviation) run over all C = H*d
+ * channels of token i.  q and k are formed inside the state-reduction and apply kernels and never exist in
+ * memory: the call reads five tensors and writes one.
+ *
+ *   a_q, t_q, a_k, t_k, v   DEVICE pointers, token-major contiguous [B, N, H*d] (head h owns channels
+ *                           h*d .. h*d+d-1 of a token), fp16 or bf16, 16-byte aligned.
+ *   out                     DEVICE pointer, same layout and type; must not overlap any input.
+ *   gamma_*, beta_*         DEVICE pointers to H*d fp32 values each (the LayerNorms' affine).
+ *   H, d                    H = 8 with d in {8, ..., 48 step 8}, or H = 4 with d in {8, ..., 64 step 8, 80}
+ *                           (a workgroup must hold whole token rows); LINFUSION_DTYPE_F32 and every
+ *                           other shape -> LINFUSION_ERR_UNSUPPORTED.
+ *   eps                     as linfusion_attn_fwd_ex.  ln_eps > 0 (finite), slope finite: the LayerNorm's
+ *                           epsilon (inside the square root) and the LeakyReLU's negative slope; the paper
+ *                           names neither, the common defaults are 1e-5 and 0.01.
+ *   flags                   LINFUSION_FLAG_NONE or LINFUSION_FLAG_UNNORMALIZED (anything else -> ERR_INVALID).
+ *   workspace               DEVICE scratch of at least linfusion_attn_mlp_workspace_bytes(...) bytes,
+ *                           16-byte aligned, caller-owned, contents undefined before and after.
+ *   events                  NULL, or four hipEvent_t created by the caller (passed as void*), recorded on
+ *                           `stream` before the state reduction, after it, after combine + operand
+ *                           packing, and after apply.
+ * Enqueues four kernels on `stream`; never allocates, never synchronises; run-to-run identical results.
+ * Errors as linfusion_attn_fwd_ex (first failing check wins; nothing is enqueued on an error).
+ */
+int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, const void* t_k, const void* v,
+                           void* out,
+                           const float* gamma_q, const float* beta_q, const float* gamma_k, const float* beta_k,
+                           int B, int H, long long N, int d,
+                           int dtype, int feature_map, float eps, float ln_eps, float slope, unsigned flags,
+                           void* workspace, size_t workspace_bytes, void* stream, void* events[4]);
+
+/* Bytes of device scratch linfusion_attn_fwd_mlp needs; pure host function; 0 for rejected arguments. */
+size_t linfusion_attn_mlp_workspace_bytes(int B, int H, long long N, int d, int dtype);
+
+/*
  * Synchronises `stream` and reports whether the most recent single-launch call that used this
  * workspace for this shape completed: LINFUSION_OK, LINFUSION_ERR_TIMEOUT, or an argument / HIP
  * error code.  (The split path cannot time out; after it this returns LINFUSION_OK.)

@@ -56,6 +56,11 @@ def library() -> ctypes.CDLL:
     lib.linfusion_attn_workspace_state_offset.restype = sz
     lib.linfusion_attn_bwd_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
     lib.linfusion_attn_bwd_workspace_bytes.restype = sz
+    lib.linfusion_attn_fwd_mlp.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32,
+                                           f32, f32, u32, vp, sz, vp, ctypes.POINTER(ctypes.c_void_p * 4)]
+    lib.linfusion_attn_fwd_mlp.restype = i32
+    lib.linfusion_attn_mlp_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
+    lib.linfusion_attn_mlp_workspace_bytes.restype = sz
     lib.linfusion_attn_last_error.argtypes = [vp, sz, i32, i32, i64, i32, i32, vp]
     lib.linfusion_attn_last_error.restype = i32
     lib.linfusion_attn_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
@@ -150,6 +155,40 @@ def linfusion_attn_bwd(q, k, v, dout, dq, dk, dv, feature_map: int = PHI_ELU_PLU
                                       flags, ws_ptr, ws_bytes, _stream_ptr(stream))
     if check and rc != 0:
         raise LinFusionError(rc, "linfusion_attn_bwd")
+    return rc
+
+
+def linfusion_attn_mlp_workspace_bytes(B: int, H: int, N: int, d: int, dtype: int) -> int:
+    return int(library().linfusion_attn_mlp_workspace_bytes(B, H, N, d, dtype))
+
+
+def linfusion_attn_fwd_mlp(a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, H: int,
+                           feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6, ln_eps: float = 1e-5,
+                           slope: float = 0.01, flags: int = FLAG_NONE, workspace=None, stream=None,
+                           events=None, check: bool = True) -> int:
+    """out <- mixer(a_q + LeakyReLU(LayerNorm(t_q)), a_k + LeakyReLU(LayerNorm(t_k)), v) on token-major
+    contiguous [B, N, H*d] tensors; gamma_*, beta_*: fp32 device vectors of H*d values.
+    `events`: optional ctypes array of four hipEvent_t handles (c_void_p * 4)."""
+    import torch
+    ts = (a_q, t_q, a_k, t_k, v, out)
+    if any(t.dim() != 3 or not t.is_contiguous() or t.shape != a_q.shape or t.dtype != a_q.dtype
+           or t.device != a_q.device for t in ts):
+        raise ValueError("a_q, t_q, a_k, t_k, v, out must be contiguous [B, N, H*d] tensors of one dtype and device")
+    B, N, C = a_q.shape
+    if C % H:
+        raise ValueError("the channel count must be a multiple of H")
+    for g in (gamma_q, beta_q, gamma_k, beta_k):
+        if g.dtype != torch.float32 or g.numel() != C or not g.is_contiguous() or g.device != a_q.device:
+            raise ValueError("gamma / beta must be contiguous fp32 vectors of H*d values on the tensors' device")
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = library().linfusion_attn_fwd_mlp(a_q.data_ptr(), t_q.data_ptr(), a_k.data_ptr(), t_k.data_ptr(), v.data_ptr(),
+                                          out.data_ptr(), gamma_q.data_ptr(), beta_q.data_ptr(), gamma_k.data_ptr(),
+                                          beta_k.data_ptr(), B, H, N, C // H, _dtype_code(a_q), feature_map, eps,
+                                          ln_eps, slope, flags, ws_ptr, ws_bytes, _stream_ptr(stream),
+                                          ctypes.byref(events) if events is not None else None)
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_fwd_mlp")
     return rc
 
 

@@ -91,9 +91,17 @@ template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :
 // the 16-byte chunks are rotated by a row-dependent amount (both ways) so that the token-per-lane
 // accesses to one head's columns are bank-conflict free.  Use: construct with the group's pointers,
 // prefetch(), load_packed() with the wave's own head (operands prepared by pack_state16), stream().
-template <typename T, int D, int FM, bool NORM, int ROWS_W = 0>
+//
+// MLP (row-piece mode with the workgroup covering whole token rows, C = W D channels): the query is not read
+// but formed per element as  a + LeakyReLU(LayerNorm_C(t)),  the sum of the two branches of f' (Sec. 4.1), from
+// the branch results `a` (through the ring at offset 0) and `t` (through a second ring behind it).  The row
+// statistics come from the tile in LDS: every lane reduces the channels it holds of its token (mean and
+// centred sum of squares, exact in two passes over registers), the 2 W pieces per token meet in LDS and are
+// merged with the pairwise-variance formula -- one more workgroup barrier per tile, no extra memory pass.
+template <typename T, int D, int FM, bool NORM, int ROWS_W = 0, bool MLP = false>
 struct ApplyDma {
   static constexpr bool ROWS = ROWS_W > 0;
+  static_assert(!MLP || ROWS, "the two-branch input needs whole token rows in one workgroup");
   static constexpr int W = ROWS ? ROWS_W : kWavesPerWG;   // waves per workgroup
   static constexpr int NT = 64 * W;
   using Sh = Shape16<D>;
@@ -109,6 +117,9 @@ struct ApplyDma {
   static constexpr int RPR = kTile / W;   // token rows per wave region
   static_assert(!ROWS || (PC % 4 == 0 && RPR * G >= 16 && kTile % W == 0), "rotation classes must fit a region");
   static constexpr int kStageOffset = (R - 1) * W * Cfg::kSlotBytes;
+  static constexpr int NLC = MLP ? 2 * NL : NL;                  // copy instructions per tile
+  static constexpr int kTOffset = R * W * Cfg::kSlotBytes;        // MLP: ring of the LayerNorm branch's tiles
+  static constexpr int kPartOffset = 2 * R * W * Cfg::kSlotBytes; // MLP: (mean, M2) per (wave, half, token)
   static __device__ __forceinline__ int rot(int r) { return ((r * G) >> 4) & (G - 1); }
 
   const u32x4* Qh;
@@ -127,6 +138,10 @@ struct ApplyDma {
   TileIter it, ahead;
   u32x4 A[NSplit<T>::value][Shape16<D>::kMT2][Shape16<D>::kKS];   // this wave's state operands
   float c1, eps_s, c1_az;   // c1_az: alpha_z, kept for save_packed
+  // MLP: the LayerNorm branch's tensor, the affine of this lane's channels, and the two scalars
+  const u32x4* Th;
+  float gam[MLP ? Shape16<D>::kKS * 8 : 1], bet[MLP ? Shape16<D>::kKS * 8 : 1];
+  float ln_eps, slope;
 
   // `Qh_`, `Oh_`: first token row of this head; `rs_q_`, `rs_o_`: row strides in 16-byte units
   LF_DEV ApplyDma(const u32x4* Qh_, int rs_q_, u32x4* Oh_, int rs_o_, long long N_, int tiles_per_block, int wg,
@@ -168,6 +183,24 @@ struct ApplyDma {
     }
   }
 
+  // MLP: `Th_` addresses the LayerNorm branch like Qh the linear one (same row stride); gamma, beta: the
+  // affine of the group's W D channels.  Call before prefetch().
+  LF_DEV void set_mlp(const u32x4* Th_, const float* gamma, const float* beta, float ln_eps_, float slope_) {
+    Th = Th_;
+    ln_eps = ln_eps_;
+    slope = slope_;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int chunk = kg * KS + s;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int ch = wave * D + chunk * 8 + e;
+        gam[s * 8 + e] = chunk < CPR ? gamma[ch] : 0.0f;
+        bet[s * 8 + e] = chunk < CPR ? beta[ch] : 0.0f;
+      }
+    }
+  }
+
   // this wave's region of ring slot `slot`: what it copies in and stores from
   LF_DEV unsigned char* slot_ptr(int slot) const { return smem + (slot * W + wave) * Cfg::kSlotBytes; }
   // where this lane finds (and overwrites) 16-byte chunk `chunk` of its token's head row in slot `slot`
@@ -181,7 +214,7 @@ struct ApplyDma {
     }
   }
 
-  // copies tile `tile` into ring slot `slot`; always issues exactly NL vector memory instructions
+  // copies tile `tile` into ring slot `slot`; always issues exactly NLC vector memory instructions
   LF_DEV void issue_copy(long long tile, int slot) {
     long long rem = N - tile * kTile;
     const int lim = rem < kTile ? (int)rem : kTile;   // valid token rows
@@ -193,6 +226,17 @@ struct ApplyDma {
         const int c = trow[u] < lim ? qoff[u] : 0; // rows past N re-read chunk 0; their results are never stored
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
                                          (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
+      }
+    }
+    if constexpr (MLP) {
+      const u32x4* tp = Th + tile * kTile * rs_q;
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        if (u * 64 + lane < Cfg::kChunks) {
+          const int c = trow[u] < lim ? qoff[u] : 0;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tp + c),
+                                           (LF_LDS void*)(sl + kTOffset + u * 1024), 16, 0, 2 /* nt */);
+        }
       }
     }
   }
@@ -355,7 +399,7 @@ struct ApplyDma {
     {   // this wave's rows of the first tile: only the second tile's copies were issued after them
       TileIter second = it;
       second.next();
-      if (second.valid()) wait_vmcnt<NL>();
+      if (second.valid()) wait_vmcnt<NLC>();
       else wait_vmcnt<0>();
     }
     __syncthreads();
@@ -371,8 +415,9 @@ struct ApplyDma {
       it.next();
       ahead.next();
       if (it.valid()) {
-        if (have_prev && copied) wait_vmcnt<2 * NL>();
-        else if (have_prev || copied) wait_vmcnt<NL>();
+        if (have_prev && copied) wait_vmcnt<NL + NLC>();
+        else if (copied) wait_vmcnt<NLC>();
+        else if (have_prev) wait_vmcnt<NL>();
         else wait_vmcnt<0>();
       }
       __syncthreads();
@@ -388,6 +433,53 @@ struct ApplyDma {
   LF_DEV void compute_tile(int slot) {
     // ---- this lane's token row -> phi -> 16-bit B operands ----------------------------------------
     u32x4 Bh[KS], Bl[KS];
+    float tv[MLP ? KS * 8 : 1];
+    float mu = 0.0f, rstd = 0.0f;
+    if constexpr (MLP) {
+      // ---- LayerNorm statistics of this lane's token over all W D channels -------------------------
+      const int mine = CPR - kg * KS < KS ? (CPR - kg * KS > 0 ? CPR - kg * KS : 0) : KS;   // valid chunks here
+      float sum = 0.0f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const bool ok = kg * KS + s < CPR;
+        u32x4 raw = u32x4{0, 0, 0, 0};
+        if (ok) raw = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, kg * KS + s) + kTOffset);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          unpack2<T>(raw[w], tv[s * 8 + 2 * w], tv[s * 8 + 2 * w + 1]);
+          sum += tv[s * 8 + 2 * w] + tv[s * 8 + 2 * w + 1];
+        }
+      }
+      const float mean_l = mine > 0 ? sum / (float)(8 * mine) : 0.0f;
+      float m2_l = 0.0f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        if (kg * KS + s < CPR) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float dv = tv[s * 8 + e] - mean_l;
+            m2_l = __builtin_fmaf(dv, dv, m2_l);
+          }
+        }
+      }
+      f32x2* part = reinterpret_cast<f32x2*>(smem + kPartOffset);
+      part[(wave * 2 + kg) * kTile + tok] = f32x2{mean_l, m2_l};
+      __syncthreads();
+      constexpr int n0 = 8 * (CPR < KS ? CPR : KS), n1 = 8 * (CPR - KS > 0 ? CPR - KS : 0);
+      f32x2 pp[2 * W];
+#pragma unroll
+      for (int i = 0; i < 2 * W; ++i) pp[i] = part[i * kTile + tok];
+#pragma unroll
+      for (int i = 0; i < 2 * W; ++i) mu += (float)((i & 1) ? n1 : n0) * pp[i][0];
+      mu *= 1.0f / (float)(W * D);
+      float m2 = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 2 * W; ++i) {
+        const float dm = pp[i][0] - mu;
+        m2 += pp[i][1] + (float)((i & 1) ? n1 : n0) * dm * dm;
+      }
+      rstd = __builtin_amdgcn_rsqf(m2 * (1.0f / (float)(W * D)) + ln_eps);
+    }
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       const int chunk = kg * KS + s;
@@ -398,6 +490,12 @@ struct ApplyDma {
       for (int w = 0; w < 4; ++w) {
         float x0, x1;
         unpack2<T>(raw[w], x0, x1);
+        if constexpr (MLP) {
+          float y0 = __builtin_fmaf(gam[s * 8 + 2 * w] * rstd, tv[s * 8 + 2 * w] - mu, bet[s * 8 + 2 * w]);
+          float y1 = __builtin_fmaf(gam[s * 8 + 2 * w + 1] * rstd, tv[s * 8 + 2 * w + 1] - mu, bet[s * 8 + 2 * w + 1]);
+          x0 += y0 >= 0.0f ? y0 : slope * y0;
+          x1 += y1 >= 0.0f ? y1 : slope * y1;
+        }
         float r0 = ok ? phi<FM>(x0) : 0.0f;
         float r1 = ok ? phi<FM>(x1) : 0.0f;
         if constexpr (NS == 1) {

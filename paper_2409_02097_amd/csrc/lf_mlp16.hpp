@@ -1,0 +1,278 @@
+// The mixer fed straight from the two-branch MLPs f', g' of Sec. 4.1 (fp16 / bf16, token-major rows):
+//   q = a_q + LeakyReLU(LayerNorm_C(t_q)),   k = a_k + LeakyReLU(LayerNorm_C(t_k)),   C = H d,
+// where a_* is the result of the linear branch and t_* the result of the second branch's Linear.  The sum,
+// the LayerNorm over all channels of a token and the activation happen inside the state-reduction and the
+// apply kernels, on tiles that are in registers / LDS anyway, so q and k never exist in memory: per token
+// the kernels read a_k, t_k, v and a_q, t_q and write out -- six tensor passes where forming q and k first
+// costs ten.  Both kernels are the row-piece kernels (lf_reduce16.hpp, lf_apply16_dma.hpp) with the
+// workgroup covering whole token rows (H = W heads, one wave per head), which is what lets the LayerNorm
+// statistics be found without a pass of their own.
+#pragma once
+#include "lf_apply16_dma.hpp"
+
+namespace lf {
+
+template <typename T, int D, int W> struct ReduceMlpCfg {
+  using Base = ReduceRowsCfg<T, D, W>;
+  static constexpr int kPartOffset = Base::kLdsBytes;                     // (mean, M2) of every 8-channel chunk
+  static constexpr int kPartBytes = kTile * Base::kPiece * 8;
+  static constexpr int kRowOffset = kPartOffset + kPartBytes;             // (mean, rstd) of every token row
+  static constexpr int kLdsBytes = kRowOffset + kTile * 8;
+  static constexpr int kTPR = Base::kThreadsW / kTile;                    // threads that reduce one row
+  static_assert(kTPR == 8 || kTPR == 16, "a row's partials are reduced inside one wave by shuffles");
+};
+
+// State reduction from the branch results of g'.  grid = (splits, B), block = 64 W, H = W heads.
+// Per tile: chunk statistics of t (registers, two passes) -> LDS -> barrier -> row statistics by kTPR threads per
+// row -> LDS -> barrier -> k = a + LeakyReLU(gamma (t - mean) rstd + beta), phi(k) and v into the heads' LDS tiles
+// -> barrier -> each wave its head's matrix-core products.  `row`: token stride in 16-byte units (= W D / 8 for
+// dense rows); a_k, t_k and v share it.
+template <typename T, int D, int FM, int W>
+__global__ void __launch_bounds__(64 * W)
+state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, const u32x4* __restrict__ V,
+                   long long batch_stride, int row, const float* __restrict__ gamma, const float* __restrict__ beta,
+                   float ln_eps, float slope, float* __restrict__ partials, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using Sh = Shape16<D>;
+  using RC = Reduce16Cfg<D>;
+  using Cfg = ReduceRowsCfg<T, D, W>;
+  using MC = ReduceMlpCfg<T, D, W>;
+  constexpr int NT = Cfg::kThreadsW;
+  constexpr int NS = Cfg::kNS, RS = RC::kRS, NL = Cfg::kNL, CPR = Sh::kChunksPerRow, MT = Sh::kMT;
+  constexpr int PC = Cfg::kPiece, TE = RC::kTileElems, TPR = MC::kTPR;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long long b = blockIdx.y;
+  const u32x4* Ag = Ak + b * batch_stride;
+  const u32x4* Tg = Tk + b * batch_stride;
+  const u32x4* Vg = V + b * batch_stride;
+  uint16_t* lds = reinterpret_cast<uint16_t*>(smem);
+  f32x2* part = reinterpret_cast<f32x2*>(smem + MC::kPartOffset);
+  f32x2* rowstat = reinterpret_cast<f32x2*>(smem + MC::kRowOffset);
+
+  // chunk p = NT u + tid of a tile is chunk p % PC of token row p / PC (head (p % PC) / CPR)
+  int goff[NL], loff[NL], trow[NL], pidx[NL];
+  float gam[NL][8], bet[NL][8];
+#pragma unroll
+  for (int u = 0; u < NL; ++u) {
+    const int p = u * NT + tid;
+    const int r = p / PC, c = p % PC;
+    const bool in = p < Cfg::kChunks;
+    trow[u] = in ? r : kTile;
+    goff[u] = r * row + c;
+    loff[u] = in ? (c / CPR) * Cfg::kHeadElems + r * RS + (c % CPR) * 8 : 0;
+    pidx[u] = in ? p : 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      gam[u][e] = gamma[c * 8 + e];
+      bet[u][e] = beta[c * 8 + e];
+    }
+  }
+  const int j16 = lane & 15, g4 = lane >> 4;
+  const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
+  const int srow = tid / TPR, ssub = tid % TPR;
+
+  const long long n_tiles = (N + kTile - 1) / kTile;
+  TileIter it(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);   // every wave walks every tile
+
+  f32x4 acc[MT][MT];
+  f32x4 accz[MT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    accz[a] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int bb = 0; bb < MT; ++bb) acc[a][bb] = f32x4{0, 0, 0, 0};
+  }
+  const uint32_t one2 = (uint32_t)OneBits<T>::value * 0x10001u;
+  const u32x4 ones = {one2, one2, one2, one2};
+
+  u32x4 ar[NL], tr[NL], vr[NL];
+  auto issue_loads = [&](long long tile) {
+    long long rem = N - tile * kTile;
+    int lim = rem < kTile ? (int)rem : kTile;
+    const long long base = tile * kTile * row;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      if (trow[u] < lim) {
+        ar[u] = ld_stream(Ag + base + goff[u]);
+        tr[u] = ld_stream(Tg + base + goff[u]);
+        vr[u] = ld_stream(Vg + base + goff[u]);
+      } else {
+        ar[u] = u32x4{0, 0, 0, 0};
+        tr[u] = u32x4{0, 0, 0, 0};
+        vr[u] = u32x4{0, 0, 0, 0};
+      }
+    }
+    return lim;
+  };
+
+  int lim = 0;
+  if (it.valid()) lim = issue_loads(it.t);
+
+  // one-time fill: pad columns zero, ones column (index D, where a spare column exists) in the V tiles
+  for (int i = tid; i < (Cfg::kDouble ? 2 : 1) * Cfg::kBufElems; i += NT) {
+    const int tile_idx = i / TE, within = i % TE;
+    const bool is_v = tile_idx % (NS + 1) == NS;
+    lds[i] = (is_v && Sh::kSpareCol && within % RS == D) ? OneBits<T>::value : (uint16_t)0;
+  }
+  __syncthreads();
+
+  int buf = 0;
+  while (it.valid()) {
+    uint16_t* bufp = lds + buf * Cfg::kBufElems;
+    // ---- LayerNorm statistics, level 1: mean and centred sum of squares of every 8-channel chunk ----
+    float tvals[NL][8];
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      float sum = 0.0f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        unpack2<T>(tr[u][w], tvals[u][2 * w], tvals[u][2 * w + 1]);
+        sum += tvals[u][2 * w] + tvals[u][2 * w + 1];
+      }
+      const float mean = sum * 0.125f;
+      float m2 = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float dv = tvals[u][e] - mean;
+        m2 = __builtin_fmaf(dv, dv, m2);
+      }
+      if (u * NT + tid < Cfg::kChunks) part[pidx[u]] = f32x2{mean, m2};
+    }
+    __syncthreads();
+    // ---- level 2: TPR threads per token row merge its PC chunks (all of 8 channels) -------------------
+    {
+      f32x2 mine[(PC + TPR - 1) / TPR];
+      float s1 = 0.0f;
+#pragma unroll
+      for (int i = 0; i < (PC + TPR - 1) / TPR; ++i) {
+        const int c = ssub + i * TPR;
+        mine[i] = c < PC ? part[srow * PC + c] : f32x2{0.0f, 0.0f};
+        s1 += mine[i][0];
+      }
+#pragma unroll
+      for (int o = TPR / 2; o > 0; o >>= 1) s1 += __shfl_xor(s1, o);
+      const float mu = s1 * (1.0f / (float)PC);
+      float m2 = 0.0f;
+#pragma unroll
+      for (int i = 0; i < (PC + TPR - 1) / TPR; ++i) {
+        if (ssub + i * TPR < PC) {
+          const float dm = mine[i][0] - mu;
+          m2 += mine[i][1] + 8.0f * dm * dm;
+        }
+      }
+#pragma unroll
+      for (int o = TPR / 2; o > 0; o >>= 1) m2 += __shfl_xor(m2, o);
+      if (ssub == 0) rowstat[srow] = f32x2{mu, __builtin_amdgcn_rsqf(m2 * (1.0f / (float)(8 * PC)) + ln_eps)};
+    }
+    __syncthreads();
+    // ---- k = a + LeakyReLU(LayerNorm(t)) -> phi -> 16-bit (hi [, lo]) -> the owning head's tiles ; V ----
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      if (u * NT + tid < Cfg::kChunks) {
+        const bool ok = trow[u] < lim;
+        const f32x2 rsd = rowstat[ok ? trow[u] : 0];
+        u32x4 ph, pl;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1;
+          unpack2<T>(ar[u][w], x0, x1);
+          const float y0 = __builtin_fmaf(gam[u][2 * w] * rsd[1], tvals[u][2 * w] - rsd[0], bet[u][2 * w]);
+          const float y1 = __builtin_fmaf(gam[u][2 * w + 1] * rsd[1], tvals[u][2 * w + 1] - rsd[0], bet[u][2 * w + 1]);
+          x0 += y0 >= 0.0f ? y0 : slope * y0;
+          x1 += y1 >= 0.0f ? y1 : slope * y1;
+          float p0 = ok ? phi<FM>(x0) : 0.0f;
+          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          if constexpr (NS == 1) {
+            ph[w] = pack2<T>(p0, p1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(p0, p1, h, l);
+            ph[w] = h;
+            pl[w] = l;
+          }
+        }
+        *reinterpret_cast<u32x4*>(bufp + loff[u]) = ph;
+        if constexpr (NS == 2) *reinterpret_cast<u32x4*>(bufp + TE + loff[u]) = pl;
+        *reinterpret_cast<u32x4*>(bufp + NS * TE + loff[u]) = vr[u];
+      }
+    }
+    it.next();
+    int next_lim = 0;
+    if (it.valid()) next_lim = issue_loads(it.t);
+    __syncthreads();   // the tile is complete in LDS
+
+    // ---- wave w: head w's outer products ----------------------------------------------------
+    const uint16_t* hp = bufp + wave * Cfg::kHeadElems;
+    const uint16_t* ldsV = hp + NS * TE;
+    u32x4 bfrag[MT];
+#pragma unroll
+    for (int bb = 0; bb < MT; ++bb) {
+      u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * bb);
+      u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * bb);
+      bfrag[bb] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        u32x2 r0 = lds_read_tr16(hp + s * TE + tr_base + 16 * a);
+        u32x2 r1 = lds_read_tr16(hp + s * TE + tr_base + 4 * RS + 16 * a);
+        u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+        for (int bb = 0; bb < MT; ++bb) acc[a][bb] = mfma_16x16x32<T>(afrag, bfrag[bb], acc[a][bb]);
+        if constexpr (!Sh::kSpareCol) accz[a] = mfma_16x16x32<T>(afrag, ones, accz[a]);
+      }
+    }
+    if constexpr (Cfg::kDouble) buf ^= 1;
+    lim = next_lim;
+  }
+
+  // ---- each wave owns a whole partial (lane: rows 4 (l / 16) + i, column l % 16 of each 16 x 16 block) ----
+  float* dst = partials + (((b * W + wave) * gridDim.x) + blockIdx.x) * (long long)(D * D + D);
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = a * 16 + 4 * g4 + i;
+      if (r < D) {
+#pragma unroll
+        for (int bb = 0; bb < MT; ++bb) {
+          const int col = bb * 16 + j16;
+          if (col < D) dst[r * D + col] = acc[a][bb][i];
+          else if (Sh::kSpareCol && col == D) dst[D * D + r] = acc[a][bb][i];
+        }
+        if constexpr (!Sh::kSpareCol) {
+          if (j16 == 0) dst[D * D + r] = accz[a][i];
+        }
+      }
+    }
+  }
+}
+
+template <typename T, int D>
+constexpr int apply16_mlp_lds_bytes(int waves) {
+  return 2 * ApplyDmaCfg<D>::kRing * ApplyDmaCfg<D>::kSlotBytes * waves + waves * 2 * kTile * 8;
+}
+
+// Apply from the branch results of f'.  grid = (wgs, B), block = 64 W, H = W heads; `packed`: the heads'
+// operand-ready states (pack_state16).  a_q and t_q share the token stride `row_q`; out has `row_o`.
+template <typename T, int D, int FM, bool NORM, int W>
+__global__ void __launch_bounds__(64 * W)
+apply16_mlp(const u32x4* __restrict__ Aq, const u32x4* __restrict__ Tq, long long batch_q, int row_q,
+            u32x4* __restrict__ O, long long batch_o, int row_o, const float* __restrict__ gamma,
+            const float* __restrict__ beta, float ln_eps, float slope, const unsigned char* __restrict__ packed,
+            float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const long long b = blockIdx.y;
+  ApplyDma<T, D, FM, NORM, W, true> ap(Aq + b * batch_q, row_q, O + b * batch_o, row_o, N, tiles_per_block, blockIdx.x,
+                                       gridDim.x, smem);
+  ap.set_mlp(Tq + b * batch_q, gamma, beta, ln_eps, slope);
+  ap.prefetch();
+  ap.load_packed(packed + (b * W + wave) * Pack16<T, D>::kHeadBytes, eps);
+  ap.stream();
+}
+
+}  // namespace lf

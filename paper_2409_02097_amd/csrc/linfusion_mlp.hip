@@ -1,0 +1,219 @@
+// Fourth translation unit of the library: the mixer fed from the two-branch MLPs f', g' (lf_mlp16.hpp).
+#include "../../include/linfusion.h"
+
+#include <stdint.h>
+
+#include <cmath>
+
+#include "lf_host_api.hpp"
+#include "lf_mlp16.hpp"
+
+namespace {
+
+constexpr int kNumCU = 256;
+
+struct MlpPlan {
+  int W;                          // heads = waves per workgroup
+  int splits, blk_reduce;         // state reduction: workgroups per batch, tiles per block
+  int apply_wgs, blk_apply;
+  size_t ne, ws_partials, ws_state, ws_pack, ws_total;
+};
+
+// Which shapes have kernels: the workgroup must cover whole token rows (H = W in {4, 8}) and both rings of
+// the apply kernel must fit the 160 KiB of LDS (eight heads: d <= 48; four heads: d <= 80).
+bool mlp_supported(int H, int d) {
+  if (d < 8 || d % 8 != 0) return false;
+  if (H == 8) return d <= 48;
+  if (H == 4) return d <= 64 || d == 80;
+  return false;
+}
+
+size_t pack_bytes(int d, int dtype) {
+  const size_t ns = dtype == LINFUSION_DTYPE_BF16 ? 2 : 1;
+  const size_t frags = ns * (size_t)((d / 2 + 2 + 15) / 16) * (size_t)((d / 8 + 1) / 2);   // Pack16<T, D>::kFrags
+  return 256 + frags * 1024;
+}
+
+int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
+  if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
+  if (B > 65535) return LINFUSION_ERR_INVALID;   // grid.y limit
+  if (dtype != LINFUSION_DTYPE_F16 && dtype != LINFUSION_DTYPE_BF16) return LINFUSION_ERR_UNSUPPORTED;
+  if (!mlp_supported(H, d)) return LINFUSION_ERR_UNSUPPORTED;
+  if (N > (1LL << 40) / ((long long)H * d)) return LINFUSION_ERR_INVALID;
+  p->W = H;
+  const long long n_tiles = (N + lf::kTile - 1) / lf::kTile;
+  auto per_batch = [&](int want_total, int blk_dflt, int* blk) {
+    long long s = want_total / B;
+    if (s > n_tiles) s = n_tiles;
+    if (s < 1) s = 1;
+    long long t = (n_tiles + s - 1) / s;
+    *blk = (int)(blk_dflt < t ? blk_dflt : t);
+    return (int)((n_tiles + t - 1) / t);
+  };
+  // (defaults in 256-thread units, as for the row-piece kernels: a workgroup of eight waves counts twice)
+  const int unit = H / lf::kWavesPerWG;
+  p->splits = per_batch(lfh::env_int("LINFUSION_MLP_REDUCE_WGS", 2 * kNumCU) / unit,
+                        lfh::env_int("LINFUSION_MLP_REDUCE_BLK", 2), &p->blk_reduce);
+  p->apply_wgs = per_batch(lfh::env_int("LINFUSION_MLP_APPLY_WGS", 2 * kNumCU) / unit,
+                           lfh::env_int("LINFUSION_MLP_APPLY_BLK", H == 8 ? 1 : 2), &p->blk_apply);
+  p->ne = (size_t)d * d + d;
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  p->ws_partials = up((size_t)B * H * p->splits * p->ne * sizeof(float));
+  p->ws_state = up((size_t)B * H * p->ne * sizeof(float));
+  p->ws_pack = up((size_t)B * H * pack_bytes(d, dtype));
+  p->ws_total = p->ws_partials + p->ws_state + p->ws_pack;
+  return LINFUSION_OK;
+}
+
+template <typename KernelT>
+bool allow_lds(KernelT kernel, int bytes) {
+  if (bytes <= 65536) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
+
+struct MlpArgs {
+  const void *a_q, *t_q, *a_k, *t_k, *v;
+  void* out;
+  const float *gamma_q, *beta_q, *gamma_k, *beta_k;
+  int B;
+  long long N;
+  int fm;
+  float eps, ln_eps, slope;
+  bool unnorm;
+  const MlpPlan* p;
+  unsigned char* ws;
+  hipStream_t st;
+  hipEvent_t* ev;
+};
+
+template <typename T, int D, int W, int FM, bool NORM>
+int run_mlp(const MlpArgs& a) {
+  using namespace lf;
+  const MlpPlan& p = *a.p;
+  constexpr int NE = D * D + D;
+  static_assert(W * D % 8 == 0, "rows are whole 16-byte chunks");
+  const int row = W * D / 8;                               // token stride in 16-byte units
+  const long long batch = a.N * row;
+  float* partials = reinterpret_cast<float*>(a.ws);
+  float* state = reinterpret_cast<float*>(a.ws + p.ws_partials);
+  unsigned char* packed = a.ws + p.ws_partials + p.ws_state;
+  hipStream_t st = a.st;
+  constexpr int lds_r = ReduceMlpCfg<T, D, W>::kLdsBytes;
+  constexpr int lds_p = apply16_dma_lds_bytes<T, D>();
+  constexpr int lds_a = apply16_mlp_lds_bytes<T, D>(W);
+  static_assert(lds_r <= 160 * 1024 && lds_a <= 160 * 1024, "workgroup LDS limit of the device");
+  static_assert(Pack16<T, D>::kFrags == NSplit<T>::value * ((D / 2 + 2 + 15) / 16) * ((D / 8 + 1) / 2),
+                "the workspace size formula must match the packed layout");
+  if (!allow_lds(state_reduce16_mlp<T, D, FM, W>, lds_r) || !allow_lds(pack_state16<T, D, NORM>, lds_p) ||
+      !allow_lds(apply16_mlp<T, D, FM, NORM, W>, lds_a))
+    return LINFUSION_ERR_HIP;
+  if (a.ev) (void)hipEventRecord(a.ev[0], st);
+  state_reduce16_mlp<T, D, FM, W><<<dim3(p.splits, (unsigned)a.B), dim3(64 * W), lds_r, st>>>(
+      (const u32x4*)a.a_k, (const u32x4*)a.t_k, (const u32x4*)a.v, batch, row, a.gamma_k, a.beta_k, a.ln_eps, a.slope,
+      partials, a.N, p.blk_reduce);
+  if (a.ev) (void)hipEventRecord(a.ev[1], st);
+  combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)(a.B * W)), dim3(kCombineThreads), 0, st>>>(
+      partials, p.splits, NE, state);
+  pack_state16<T, D, NORM><<<dim3((unsigned)(a.B * W)), dim3(kThreads), lds_p, st>>>(state, packed);
+  if (a.ev) (void)hipEventRecord(a.ev[2], st);
+  apply16_mlp<T, D, FM, NORM, W><<<dim3(p.apply_wgs, (unsigned)a.B), dim3(64 * W), lds_a, st>>>(
+      (const u32x4*)a.a_q, (const u32x4*)a.t_q, batch, row, (u32x4*)a.out, batch, row, a.gamma_q, a.beta_q, a.ln_eps,
+      a.slope, packed, a.eps, a.N, p.blk_apply);
+  if (a.ev) (void)hipEventRecord(a.ev[3], st);
+  return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+}
+
+template <typename T, int D, int W>
+int run_mlp_fm(const MlpArgs& a) {
+  switch (a.fm) {
+    case 0: return a.unnorm ? run_mlp<T, D, W, 0, false>(a) : run_mlp<T, D, W, 0, true>(a);
+    case 1: return a.unnorm ? run_mlp<T, D, W, 1, false>(a) : run_mlp<T, D, W, 1, true>(a);
+    default: return a.unnorm ? run_mlp<T, D, W, 2, false>(a) : run_mlp<T, D, W, 2, true>(a);
+  }
+}
+
+template <int D, int W>
+int run_mlp_dtype(int dtype, const MlpArgs& a) {
+  return dtype == LINFUSION_DTYPE_F16 ? run_mlp_fm<lf::F16, D, W>(a) : run_mlp_fm<lf::BF16, D, W>(a);
+}
+
+int dispatch_mlp(int H, int d, int dtype, const MlpArgs& a) {
+  if (H == 8) {
+    switch (d) {
+#define X(DD) case DD: return run_mlp_dtype<DD, 8>(dtype, a);
+      X(8) X(16) X(24) X(32) X(40) X(48)
+#undef X
+    }
+  } else if (H == 4) {
+    switch (d) {
+#define X(DD) case DD: return run_mlp_dtype<DD, 4>(dtype, a);
+      X(8) X(16) X(24) X(32) X(40) X(48) X(56) X(64) X(80)
+#undef X
+    }
+  }
+  return LINFUSION_ERR_UNSUPPORTED;
+}
+
+bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t linfusion_attn_mlp_workspace_bytes(int B, int H, long long N, int d, int dtype) {
+  MlpPlan p;
+  if (make_mlp_plan(B, H, N, d, dtype, &p) != LINFUSION_OK) return 0;
+  return p.ws_total;
+}
+
+int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, const void* t_k, const void* v, void* out,
+                           const float* gamma_q, const float* beta_q, const float* gamma_k, const float* beta_k, int B,
+                           int H, long long N, int d, int dtype, int feature_map, float eps, float ln_eps, float slope,
+                           unsigned flags, void* workspace, size_t workspace_bytes, void* stream, void* events[4]) {
+  if (!a_q || !t_q || !a_k || !t_k || !v || !out || !gamma_q || !beta_q || !gamma_k || !beta_k)
+    return LINFUSION_ERR_INVALID;
+  if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
+  if (!(ln_eps > 0.0f) || std::isinf(ln_eps)) return LINFUSION_ERR_INVALID;
+  if (!std::isfinite(slope)) return LINFUSION_ERR_INVALID;
+  if (flags & ~LINFUSION_FLAG_UNNORMALIZED) return LINFUSION_ERR_INVALID;
+  MlpPlan p;
+  int rc = make_mlp_plan(B, H, N, d, dtype, &p);
+  if (rc != LINFUSION_OK) return rc;
+  if (feature_map < 0 || feature_map > 2) return LINFUSION_ERR_UNSUPPORTED;
+  const void* ins[5] = {a_q, t_q, a_k, t_k, v};
+  for (const void* x : ins)
+    if ((uintptr_t)x & 15) return LINFUSION_ERR_MISALIGNED;
+  if ((uintptr_t)out & 15) return LINFUSION_ERR_MISALIGNED;
+  const float* vecs[4] = {gamma_q, beta_q, gamma_k, beta_k};
+  for (const float* x : vecs)
+    if ((uintptr_t)x & 3) return LINFUSION_ERR_MISALIGNED;
+  const size_t tbytes = (size_t)B * H * (size_t)N * d * 2, vbytes = (size_t)H * d * sizeof(float);
+  for (const void* x : ins)
+    if (overlaps(out, tbytes, x, tbytes)) return LINFUSION_ERR_OVERLAP;
+  for (const float* x : vecs)
+    if (overlaps(out, tbytes, x, vbytes)) return LINFUSION_ERR_OVERLAP;
+  if (!workspace) return LINFUSION_ERR_WORKSPACE;
+  if ((uintptr_t)workspace & 15) return LINFUSION_ERR_MISALIGNED;
+  if (workspace_bytes < p.ws_total) return LINFUSION_ERR_WORKSPACE;
+  for (const void* x : ins)
+    if (overlaps(workspace, p.ws_total, x, tbytes)) return LINFUSION_ERR_OVERLAP;
+  for (const float* x : vecs)
+    if (overlaps(workspace, p.ws_total, x, vbytes)) return LINFUSION_ERR_OVERLAP;
+  if (overlaps(workspace, p.ws_total, out, tbytes)) return LINFUSION_ERR_OVERLAP;
+  rc = lfh::check_device();
+  if (rc != LINFUSION_OK) return rc;
+  MlpArgs a{a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, B, N, feature_map, eps, ln_eps, slope,
+            (flags & LINFUSION_FLAG_UNNORMALIZED) != 0, &p, (unsigned char*)workspace, (hipStream_t)stream,
+            reinterpret_cast<hipEvent_t*>(events)};
+  return dispatch_mlp(H, d, dtype, a);
+}
+
+}  // extern "C"

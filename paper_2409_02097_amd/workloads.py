@@ -68,6 +68,27 @@ def make_qkv(B, H, N, d, dtype, idx=0, k_scale=1.0, device="cpu", seed_offset=0)
     return q, k, v
 
 
+def make_mlp_inputs(B, H, N, d, dtype, idx=0, device="cpu", zero_start=False):
+    """Stand-ins for what the two-branch MLPs in front of the mixer hand over, token-major [B, N, H*d]:
+    a_q, a_k (linear-branch results) and v ~ N(0, 1); t_q, t_k (results of the second branch's Linear)
+    ~ N(0.5, 1.5^2) so that the LayerNorm has a mean and a scale to remove; per-channel affine
+    gamma ~ N(1, 0.25^2), beta ~ N(0, 0.5^2) in fp32 (both zero with `zero_start`: the state the paper
+    initialises the second branch to).  Returns (a_q, t_q, a_k, t_k, v, gamma_q, beta_q, gamma_k, beta_k)."""
+    base = BASE_SEED + 1000 * idx + 500
+    C = H * d
+    a_q = draw((B, N, C), base + 0, dtype, device)
+    a_k = draw((B, N, C), base + 1, dtype, device)
+    v = draw((B, N, C), base + 2, dtype, device)
+    t_q = (draw((B, N, C), base + 3, "f32", device, scale=1.5) + 0.5).to(TORCH_DTYPE[dtype])
+    t_k = (draw((B, N, C), base + 4, "f32", device, scale=1.5) + 0.5).to(TORCH_DTYPE[dtype])
+    if zero_start:
+        vecs = [torch.zeros(C, dtype=torch.float32, device=device) for _ in range(4)]
+    else:
+        vecs = [draw((C,), base + 5, "f32", device, scale=0.25) + 1.0, draw((C,), base + 6, "f32", device, scale=0.5),
+                draw((C,), base + 7, "f32", device, scale=0.25) + 1.0, draw((C,), base + 8, "f32", device, scale=0.5)]
+    return (a_q, t_q, a_k, t_k, v, *vecs)
+
+
 def make_config(name: str, device="cpu"):
     c = config(name)
     return make_qkv(c["B"], c["H"], c["N"], c["d"], c["dtype"], c["idx"], c["k_scale"], device)

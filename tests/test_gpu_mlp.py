@@ -1,0 +1,148 @@
+"""GPU parity of linfusion_attn_fwd_mlp (the mixer fed by the two-branch MLPs f', g' of Sec. 4.1) against the
+fp64 oracle's module_mixer on the same stored inputs, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_02097_amd as lf
+from oracle import linattn_oracle as orc
+from paper_2409_02097_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+LN_EPS, SLOPE = 1e-5, 0.01
+
+
+def _ws(B, H, N, d, dtype):
+    n = lf.linfusion_attn_mlp_workspace_bytes(B, H, N, d, wl.DTYPE_CODE[dtype])
+    assert n > 0
+    return torch.empty(n, dtype=torch.uint8, device="cuda")
+
+
+def _run(ins, H, fm=0, eps=1e-6, flags=0, ln_eps=LN_EPS, slope=SLOPE):
+    dev = [t.cuda() for t in ins]
+    B, N, C = dev[0].shape
+    dtype = {torch.float16: "f16", torch.bfloat16: "bf16"}[dev[0].dtype]
+    out = torch.full_like(dev[0], float("nan"))
+    lf.linfusion_attn_fwd_mlp(*dev[:5], out, *dev[5:], H, fm, eps, ln_eps, slope, flags, _ws(B, H, N, C // H, dtype))
+    torch.cuda.synchronize()
+    return out
+
+
+def _oracle(ins, H, dtype, fm=0, eps=1e-6, normalize=True, ln_eps=LN_EPS, slope=SLOPE):
+    a_q, t_q, a_k, t_k, v = (orc.widen(wl.stored_numpy(t), dtype) for t in ins[:5])
+    gq, bq, gk, bk = (t.numpy().astype(np.float64) for t in ins[5:])
+    return orc.module_mixer(a_q, t_q, a_k, t_k, v, gq, bq, gk, bk, H, fm, eps, normalize, ln_eps, slope)
+
+
+def _check(out, ref, H, dtype, what):
+    gpu = parity.to_f64(out)
+    B, N, C = ref.shape
+    d = C // H
+    worst = (0.0, 0.0)
+    for b in range(B):
+        for h in range(H):
+            c = slice(h * d, (h + 1) * d)
+            r = parity.check_slice(gpu[b, :, c], ref[b, :, c], dtype, f"{what} b={b} h={h}")
+            worst = (max(worst[0], r[0]), max(worst[1], r[1]))
+    return worst
+
+
+SHAPES = [
+    # eight heads (whole rows of the SD-v1.5 first level: 8 x 40 = 320 channels)
+    (1, 8, 1, 40, "f16"), (2, 8, 33, 40, "f16"), (1, 8, 1000, 40, "f16"), (2, 8, 4099, 40, "f16"),
+    (3, 8, 31, 8, "f16"), (1, 8, 515, 16, "f16"), (1, 8, 300, 24, "f16"), (2, 8, 260, 32, "f16"),
+    (1, 8, 777, 48, "f16"),
+    (1, 8, 33, 40, "bf16"), (2, 8, 1000, 40, "bf16"), (1, 8, 2100, 48, "bf16"), (1, 8, 130, 8, "bf16"),
+    (1, 8, 95, 32, "bf16"),
+    # four heads
+    (1, 4, 1, 64, "f16"), (2, 4, 1000, 64, "f16"), (1, 4, 333, 80, "f16"), (2, 4, 77, 40, "f16"),
+    (1, 4, 600, 56, "f16"), (1, 4, 100, 8, "f16"), (1, 4, 2051, 16, "f16"),
+    (1, 4, 500, 80, "bf16"), (2, 4, 300, 64, "bf16"), (1, 4, 1030, 24, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", SHAPES)
+def test_matches_oracle(B, H, N, d, dtype):
+    print(f"mlp B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=80)
+    out = _run(ins, H)
+    _check(out, _oracle(ins, H, dtype), H, dtype, f"mlp {B}x{H}x{N}x{d} {dtype}")
+
+
+@pytest.mark.parametrize("fm", [0, 1, 2])
+@pytest.mark.parametrize("unnorm", [False, True])
+@pytest.mark.parametrize("H,d,dtype", [(8, 40, "f16"), (4, 64, "bf16")])
+def test_feature_maps_and_unnormalized(H, d, dtype, fm, unnorm):
+    print(f"mlp fm={fm} unnorm={unnorm} H={H} d={d} {dtype}", flush=True)
+    B, N = 2, 700
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=81))
+    if fm != 0:   # identity / relu: keep the denominators away from zero
+        ins[0] = (ins[0].float().abs() + 0.5).to(ins[0].dtype)
+        ins[2] = (ins[2].float().abs() + 0.5).to(ins[2].dtype)
+    out = _run(ins, H, fm=fm, flags=lf.FLAG_UNNORMALIZED if unnorm else 0)
+    _check(out, _oracle(ins, H, dtype, fm=fm, normalize=not unnorm), H, dtype, f"fm={fm} unnorm={unnorm}")
+
+
+@pytest.mark.parametrize("H,d,dtype", [(8, 40, "f16"), (8, 48, "bf16"), (4, 80, "f16")])
+def test_zero_start_is_the_plain_mixer(H, d, dtype):
+    """Sec. 4.1: with the second branch at its initial value zero, q and k are the linear-branch results."""
+    B, N = 2, 1500
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=82, zero_start=True)
+    out = _run(ins, H)
+    heads = lambda t: t.cuda().view(B, N, H, d).permute(0, 2, 1, 3)          # strided [B, H, N, d] views
+    plain = torch.empty(B, N, H, d, dtype=out.dtype, device="cuda")
+    ws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, wl.DTYPE_CODE[dtype]), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_fwd_strided(heads(ins[0]), heads(ins[2]), heads(ins[4]), plain.permute(0, 2, 1, 3), 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    ref = parity.to_f64(plain.view(B, N, H * d))
+    _check(out, _oracle(ins, H, dtype), H, dtype, "zero start vs oracle")
+    # two correct roundings of the same values: they differ by at most one unit in the last place
+    diff = np.abs(parity.to_f64(out) - ref)
+    assert (diff <= 2.0 * orc.half_ulp(ref, dtype) + 2e-3 * np.abs(ref).max()).all()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_layer_norm_input_far_from_zero_mean(dtype):
+    """Rows whose mean is many standard deviations away from zero: the variance must come from centred sums."""
+    B, H, N, d = 1, 8, 500, 40
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=83))
+    for i in (1, 3):
+        ins[i] = (ins[i].float() * 0.5 + 40.0).to(ins[i].dtype)
+    out = _run(ins, H)
+    _check(out, _oracle(ins, H, dtype), H, dtype, "offset LayerNorm input")
+
+
+def test_layer_norm_epsilon_and_slope_are_honoured():
+    B, H, N, d, dtype = 1, 8, 200, 40, "f16"
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=84))
+    for i in (1, 3):
+        ins[i] = (ins[i].float() * 0.01).to(ins[i].dtype)        # variance ~ 2e-4: ln_eps = 1e-3 matters
+    out = _run(ins, H, ln_eps=1e-3, slope=0.2)
+    _check(out, _oracle(ins, H, dtype, ln_eps=1e-3, slope=0.2), H, dtype, "ln_eps, slope")
+    other = _oracle(ins, H, dtype)                                # the defaults give something else
+    assert np.abs(other - parity.to_f64(out)).max() > 1e-2
+
+
+def test_run_to_run_identical():
+    ins = wl.make_mlp_inputs(2, 8, 3000, 40, "f16", idx=85)
+    a, b = _run(ins, 8), _run(ins, 8)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_rejected_arguments():
+    code = wl.DTYPE_CODE
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 64, code["f16"]) == 0      # eight heads: d <= 48
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 5, 100, 40, code["f16"]) == 0      # rows must fit a workgroup
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 40, code["f32"]) == 0
+    ins = [t.cuda() for t in wl.make_mlp_inputs(1, 8, 64, 40, "f16", idx=86)]
+    out = torch.empty_like(ins[0])
+    ws = _ws(1, 8, 64, 40, "f16")
+    call = lambda *a, **k: lf.linfusion_attn_fwd_mlp(*a, check=False, **k)
+    assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 0.0, 0.01, 0, ws) == -1           # ln_eps must be positive
+    assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 1e-5, float("nan"), 0, ws) == -1
+    assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 1e-5, 0.01, lf.FLAG_FORCE_FUSED, ws) == -1
+    assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 1e-5, 0.01, 0, ws[:1024]) == -4   # workspace too small
+    assert call(*ins[:5], ins[0], *ins[5:], 8, 0, 1e-6, 1e-5, 0.01, 0, ws) == -7       # out aliases an input
+    assert call(*ins[:5], out, *ins[5:], 8, 7, 1e-6, 1e-5, 0.01, 0, ws) == -2          # unknown feature map
