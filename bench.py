@@ -146,6 +146,10 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="also time linfusion_attn_bwd on the same workload (fp16 / bf16 only); reported in an extra "
                          "`backward` object of the result line")
+    ap.add_argument("--mlp", action="store_true",
+                    help="also time linfusion_attn_fwd_mlp (the mixer fed by the two-branch MLPs' results, token-major) "
+                         "on the same shape, next to the unfused route (q and k formed by torch ops, then the "
+                         "strided mixer); reported in an extra `mlp` object of the result line")
     ap.add_argument("--latency-table", action="store_true",
                     help="also time the small and medium workloads, hot and cold cache, both launch paths "
                          "(JSON lines on stderr; the one-line result on stdout is unchanged)")
@@ -277,6 +281,64 @@ def main():
                               "kernel_traffic_gbps": kbytes / bdt / 1e9,
                               "frac_of_peak_kernel_traffic": kbytes / bdt / 1e9 / HBM_PEAK_GBPS}
         del g, grads, bws
+    if args.mlp:
+        # algorithmic traffic: a_k, t_k, v read by the reduction; a_q, t_q read and out written by apply
+        ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=cfg["idx"], device="cuda")
+        mout = torch.empty_like(ins[0])
+        mws = torch.empty(lf.linfusion_attn_mlp_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
+
+        def mstep(events=None):
+            lf.linfusion_attn_fwd_mlp(*ins[:5], mout, *ins[5:], H, lf.PHI_ELU_PLUS_ONE, wl.EPS, 1e-5, 0.01, 0, mws,
+                                      events=events)
+        for _ in range(max(args.warmup // 2, 2)):
+            mstep()
+        torch.cuda.synchronize()
+        tm0 = time.perf_counter()
+        msteps = max(args.steps // 2, 1)
+        for _ in range(msteps):
+            mstep()
+        torch.cuda.synchronize()
+        mdt = (time.perf_counter() - tm0) / msteps
+        mev = HipEvents(4)
+        macc = [0.0, 0.0, 0.0]
+        for _ in range(args.profile_steps):
+            mstep(mev.ev)
+            mev.sync(3)
+            for i in range(3):
+                macc[i] += mev.elapsed_ms(i, i + 1)
+        mev.close()
+        mk = [a / max(args.profile_steps, 1) for a in macc]
+        tensor_bytes = alg_bytes / 4
+
+        def unfused():
+            F = torch.nn.functional
+            C = H * d
+            qq = ins[0] + F.leaky_relu(F.layer_norm(ins[1], (C,), ins[5].to(ins[1].dtype), ins[6].to(ins[1].dtype), 1e-5), 0.01)
+            kk = ins[2] + F.leaky_relu(F.layer_norm(ins[3], (C,), ins[7].to(ins[3].dtype), ins[8].to(ins[3].dtype), 1e-5), 0.01)
+            hv = lambda t: t.view(B, N, H, d).permute(0, 2, 1, 3)
+            lf.linfusion_attn_fwd_strided(hv(qq), hv(kk), hv(ins[4]), hv(mout), lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, ws)
+        for _ in range(3):
+            unfused()
+        torch.cuda.synchronize()
+        tu0 = time.perf_counter()
+        usteps = max(args.steps // 4, 1)
+        for _ in range(usteps):
+            unfused()
+        torch.cuda.synchronize()
+        udt = (time.perf_counter() - tu0) / usteps
+        result["mlp"] = {
+            "ms_per_step": mdt * 1e3, "tokens_per_s": B * N / mdt, "alg_bytes": 6 * tensor_bytes,
+            "hbm_gbps": 6 * tensor_bytes / mdt / 1e9, "hbm_frac_of_peak": 6 * tensor_bytes / mdt / 1e9 / HBM_PEAK_GBPS,
+            "kernels": [
+                {"name": "state_reduce16_mlp", "ms": mk[0], "alg_bytes": 3 * tensor_bytes,
+                 "gbps": 3 * tensor_bytes / (mk[0] * 1e-3) / 1e9 if mk[0] > 0 else None},
+                {"name": "combine_state + pack_state16", "ms": mk[1], "alg_bytes": 0, "gbps": 0.0},
+                {"name": "apply16_mlp", "ms": mk[2], "alg_bytes": 3 * tensor_bytes,
+                 "gbps": 3 * tensor_bytes / (mk[2] * 1e-3) / 1e9 if mk[2] > 0 else None}],
+            "unfused_ms_per_step": udt * 1e3,
+            "unfused": "q, k formed by torch layer_norm + leaky_relu + add (16-bit), then linfusion_attn_fwd_strided",
+        }
+        del ins, mout, mws
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(q, k, v, cfg, args.cpu_sample_tokens)
         result["cpu_baseline"] = base

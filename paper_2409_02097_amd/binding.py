@@ -168,7 +168,7 @@ def linfusion_attn_fwd_mlp(a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k,
                            events=None, check: bool = True) -> int:
     """out <- mixer(a_q + LeakyReLU(LayerNorm(t_q)), a_k + LeakyReLU(LayerNorm(t_k)), v) on token-major
     contiguous [B, N, H*d] tensors; gamma_*, beta_*: fp32 device vectors of H*d values.
-    `events`: optional ctypes array of four hipEvent_t handles (c_void_p * 4)."""
+    `events`: optional list of four hipEvent_t handles (ints) recorded around the kernels."""
     import torch
     ts = (a_q, t_q, a_k, t_k, v, out)
     if any(t.dim() != 3 or not t.is_contiguous() or t.shape != a_q.shape or t.dtype != a_q.dtype
@@ -186,7 +186,8 @@ def linfusion_attn_fwd_mlp(a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k,
                                           out.data_ptr(), gamma_q.data_ptr(), beta_q.data_ptr(), gamma_k.data_ptr(),
                                           beta_k.data_ptr(), B, H, N, C // H, _dtype_code(a_q), feature_map, eps,
                                           ln_eps, slope, flags, ws_ptr, ws_bytes, _stream_ptr(stream),
-                                          ctypes.byref(events) if events is not None else None)
+                                          ctypes.byref((ctypes.c_void_p * 4)(*[ctypes.c_void_p(int(e)) for e in events]))
+                                          if events is not None else None)
     if check and rc != 0:
         raise LinFusionError(rc, "linfusion_attn_fwd_mlp")
     return rc

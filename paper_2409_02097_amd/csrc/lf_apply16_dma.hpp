@@ -402,7 +402,7 @@ struct ApplyDma {
       if (second.valid()) wait_vmcnt<NLC>();
       else wait_vmcnt<0>();
     }
-    __syncthreads();
+    lds_barrier();
     int slot = 0, prev_slot = 0;
     long long prev_tile = -1;
     while (it.valid()) {
@@ -420,7 +420,7 @@ struct ApplyDma {
         else if (have_prev) wait_vmcnt<NL>();
         else wait_vmcnt<0>();
       }
-      __syncthreads();
+      lds_barrier();
       prev_tile = tile;
       prev_slot = slot;
       slot = slot + 1 == R ? 0 : slot + 1;
@@ -464,7 +464,7 @@ struct ApplyDma {
       }
       f32x2* part = reinterpret_cast<f32x2*>(smem + kPartOffset);
       part[(wave * 2 + kg) * kTile + tok] = f32x2{mean_l, m2_l};
-      __syncthreads();
+      lds_barrier();
       constexpr int n0 = 8 * (CPR < KS ? CPR : KS), n1 = 8 * (CPR - KS > 0 ? CPR - KS : 0);
       f32x2 pp[2 * W];
 #pragma unroll

@@ -106,6 +106,11 @@ LF_DEV u32x2 lds_read_tr16(const uint16_t* p) {
   return __builtin_bit_cast(u32x2, r);
 }
 
+// Workgroup barrier that orders LDS traffic only: the wave's LDS operations are complete before it arrives,
+// while its outstanding global loads, stores and LDS copies stay in flight (before __syncthreads() the
+// compiler drains every memory counter, which would expose the latency of loads issued just before it).
+LF_DEV void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // streaming 128-bit global load / store (non-temporal: the tensors are touched once)
 LF_DEV u32x4 ld_stream(const u32x4* p) { return __builtin_nontemporal_load(p); }
 LF_DEV void st_stream(u32x4* p, u32x4 v) { __builtin_nontemporal_store(v, p); }

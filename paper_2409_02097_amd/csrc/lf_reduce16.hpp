@@ -365,7 +365,7 @@ state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
     it.next();
     int next_lim = 0;
     if (it.valid()) next_lim = issue_loads(it.t);
-    __syncthreads();   // the tile is complete in LDS
+    lds_barrier();   // the tile is complete in LDS
 
     // ---- wave w: head w's outer products ----------------------------------------------------
     const uint16_t* hp = bufp + wave * Cfg::kHeadElems;
@@ -390,7 +390,7 @@ state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
       }
     }
     if constexpr (Cfg::kDouble) buf ^= 1;
-    else __syncthreads();   // single buffer: everyone is done reading before the next tile is written
+    else lds_barrier();   // single buffer: everyone is done reading before the next tile is written
     lim = next_lim;
   }
 

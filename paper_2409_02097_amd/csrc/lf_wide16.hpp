@@ -161,7 +161,7 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
     it.next();
     int next_lim = 0;
     if (it.valid()) next_lim = issue_loads(it.t);
-    __syncthreads();   // the tile is complete in this buffer; the other buffer is free to be rewritten
+    lds_barrier();   // the tile is complete in this buffer; the other buffer is free to be rewritten
 
     const uint16_t* ldsV = bufp + NS * TE;
     u32x4 bfrag[NBW];
@@ -471,7 +471,7 @@ struct ApplyWide {
         Bh[s] = *reinterpret_cast<const u32x4*>(p);
         if constexpr (NS == 2) Bl[s] = *reinterpret_cast<const u32x4*>(p + (R - slot) * Sw::kSlotBytes);
       }
-      __syncthreads();   // every wave holds its operands: the tile (and the LO buffer) may be overwritten
+      lds_barrier();   // every wave holds its operands: the tile (and the LO buffer) may be overwritten
 
       f32x16 acc[MT2];
 #pragma unroll
@@ -518,7 +518,7 @@ struct ApplyWide {
         else wait_vmcnt<0>();
         phi_pass(slot + 1 == R ? 0 : slot + 1);
       }
-      __syncthreads();   // tile j is finished by all waves; tile j+1 has landed and carries phi for all
+      lds_barrier();   // tile j is finished by all waves; tile j+1 has landed and carries phi for all
       prev_tile = tile;
       prev_slot = slot;
       slot = slot + 1 == R ? 0 : slot + 1;
