@@ -204,7 +204,7 @@ size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int 
  *   H, d                    H = 8 with d in {8, ..., 48 step 8}, or H = 4 with d in {8, ..., 64 step 8, 80}
  *                           (a workgroup must hold whole token rows); LINFUSION_DTYPE_F32 and every
  *                           other shape -> LINFUSION_ERR_UNSUPPORTED.
- *   eps                     as linfusion_attn_fwd_ex.  ln_eps > 0 (finite), slope finite: the LayerNorm's
+ *   eps                     as linfusion_attn_fwd_ex.  ln_eps > 0 (finite), 0 <= slope <= 1: the LayerNorm's
  *                           epsilon (inside the square root) and the LeakyReLU's negative slope; the paper
  *                           names neither, the common defaults are 1e-5 and 0.01.
  *   flags                   LINFUSION_FLAG_NONE or LINFUSION_FLAG_UNNORMALIZED (anything else -> ERR_INVALID).

@@ -436,49 +436,66 @@ struct ApplyDma {
     float tv[MLP ? KS * 8 : 1];
     float mu = 0.0f, rstd = 0.0f;
     if constexpr (MLP) {
-      // ---- LayerNorm statistics of this lane's token over all W D channels -------------------------
-      const int mine = CPR - kg * KS < KS ? (CPR - kg * KS > 0 ? CPR - kg * KS : 0) : KS;   // valid chunks here
-      float sum = 0.0f;
+      // ---- LayerNorm statistics of this lane's token over all W D channels: sums of (t - pivot) and of its
+      //      square, the pivot being the token's channel 0 (the same for all lanes of the token, so the
+      //      pieces simply add; deviations are small next to a large common offset, so nothing cancels) ----
+      const uint16_t pv16 = *reinterpret_cast<const uint16_t*>(smem + slot * W * Cfg::kSlotBytes + kTOffset +
+                                                               row_byte + (rot(tok) << 4));
+      float pivot, pivot_unused;
+      unpack2<T>((uint32_t)pv16, pivot, pivot_unused);
+      float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         const bool ok = kg * KS + s < CPR;
         u32x4 raw = u32x4{0, 0, 0, 0};
         if (ok) raw = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, kg * KS + s) + kTOffset);
+        if constexpr (NS == 1) {
+          // fp16: for the two sums the difference is taken in packed half precision (its rounding is relative
+          // to the deviation and averages out) and accumulated by the mixed-precision dot product
+          const f16x2 np = __builtin_bit_cast(f16x2, (uint32_t)(pv16 ^ 0x8000u) * 0x10001u);
+          const f16x2 one = __builtin_bit_cast(f16x2, 0x3C003C00u);
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          unpack2<T>(raw[w], tv[s * 8 + 2 * w], tv[s * 8 + 2 * w + 1]);
-          sum += tv[s * 8 + 2 * w] + tv[s * 8 + 2 * w + 1];
-        }
-      }
-      const float mean_l = mine > 0 ? sum / (float)(8 * mine) : 0.0f;
-      float m2_l = 0.0f;
+          for (int w = 0; w < 4; ++w) {
+            const uint32_t word = raw[w];   // (by value: a bit cast applied to the vector element itself reads element 0)
+            const f16x2 tt = __builtin_bit_cast(f16x2, word);
+            const f16x2 dd = tt + np;                      // feeds the statistics only
+            tv[s * 8 + 2 * w] = (float)tt[0] - pivot;
+            tv[s * 8 + 2 * w + 1] = (float)tt[1] - pivot;
+            if (ok) {
+              s1 = __builtin_amdgcn_fdot2(dd, one, s1, false);
+              s2 = __builtin_amdgcn_fdot2(dd, dd, s2, false);
+            }
+          }
+        } else {
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        if (kg * KS + s < CPR) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const float dv = tv[s * 8 + e] - mean_l;
-            m2_l = __builtin_fmaf(dv, dv, m2_l);
+          for (int w = 0; w < 4; ++w) {
+            float t0, t1;
+            unpack2<T>(raw[w], t0, t1);
+            t0 -= pivot;
+            t1 -= pivot;
+            tv[s * 8 + 2 * w] = t0;
+            tv[s * 8 + 2 * w + 1] = t1;
+            if (ok) {
+              s1 += t0 + t1;
+              s2 = __builtin_fmaf(t0, t0, __builtin_fmaf(t1, t1, s2));
+            }
           }
         }
       }
       f32x2* part = reinterpret_cast<f32x2*>(smem + kPartOffset);
-      part[(wave * 2 + kg) * kTile + tok] = f32x2{mean_l, m2_l};
+      part[(wave * 2 + kg) * kTile + tok] = f32x2{s1, s2};
       lds_barrier();
-      constexpr int n0 = 8 * (CPR < KS ? CPR : KS), n1 = 8 * (CPR - KS > 0 ? CPR - KS : 0);
-      f32x2 pp[2 * W];
-#pragma unroll
-      for (int i = 0; i < 2 * W; ++i) pp[i] = part[i * kTile + tok];
-#pragma unroll
-      for (int i = 0; i < 2 * W; ++i) mu += (float)((i & 1) ? n1 : n0) * pp[i][0];
-      mu *= 1.0f / (float)(W * D);
-      float m2 = 0.0f;
+      s1 = 0.0f;
+      s2 = 0.0f;
 #pragma unroll
       for (int i = 0; i < 2 * W; ++i) {
-        const float dm = pp[i][0] - mu;
-        m2 += pp[i][1] + (float)((i & 1) ? n1 : n0) * dm * dm;
+        const f32x2 pp = part[i * kTile + tok];
+        s1 += pp[0];
+        s2 += pp[1];
       }
-      rstd = __builtin_amdgcn_rsqf(m2 * (1.0f / (float)(W * D)) + ln_eps);
+      mu = s1 * (1.0f / (float)(W * D));                       // mean of t - pivot, which is what tv holds
+      const float var = fmaxf(__builtin_fmaf(-mu, mu, s2 * (1.0f / (float)(W * D))), 0.0f);
+      rstd = __builtin_amdgcn_rsqf(var + ln_eps);
     }
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -493,8 +510,8 @@ struct ApplyDma {
         if constexpr (MLP) {
           float y0 = __builtin_fmaf(gam[s * 8 + 2 * w] * rstd, tv[s * 8 + 2 * w] - mu, bet[s * 8 + 2 * w]);
           float y1 = __builtin_fmaf(gam[s * 8 + 2 * w + 1] * rstd, tv[s * 8 + 2 * w + 1] - mu, bet[s * 8 + 2 * w + 1]);
-          x0 += y0 >= 0.0f ? y0 : slope * y0;
-          x1 += y1 >= 0.0f ? y1 : slope * y1;
+          x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
+          x1 += fmaxf(y1, slope * y1);
         }
         float r0 = ok ? phi<FM>(x0) : 0.0f;
         float r1 = ok ? phi<FM>(x1) : 0.0f;

@@ -17,8 +17,7 @@ template <typename T, int D, int W> struct ReduceMlpCfg {
   static constexpr int kPartOffset = Base::kLdsBytes;                     // (mean, M2) of every 8-channel chunk
   static constexpr int kPartBytes = kTile * Base::kPiece * 8;
   static constexpr int kRowOffset = kPartOffset + kPartBytes;             // (mean, rstd) of every token row
-  static constexpr int kAffineOffset = kRowOffset + kTile * 8;             // gamma[C] then beta[C], fp32
-  static constexpr int kLdsBytes = kAffineOffset + 2 * W * D * 4;
+  static constexpr int kLdsBytes = kRowOffset + kTile * 8;
   static constexpr int kTPR = Base::kThreadsW / kTile;                    // threads that reduce one row
   static_assert(kTPR == 8 || kTPR == 16, "a row's partials are reduced inside one wave by shuffles");
 };
@@ -53,12 +52,8 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
   f32x2* rowstat = reinterpret_cast<f32x2*>(smem + MC::kRowOffset);
 
   // chunk p = NT u + tid of a tile is chunk p % PC of token row p / PC (head (p % PC) / CPR)
-  int goff[NL], loff[NL], trow[NL], pidx[NL], coff[NL];
-  float* affine = reinterpret_cast<float*>(smem + MC::kAffineOffset);
-  for (int i = tid; i < W * D; i += NT) {
-    affine[i] = gamma[i];
-    affine[W * D + i] = beta[i];
-  }
+  int goff[NL], loff[NL], trow[NL], pidx[NL];
+  float gam[NL][8], bet[NL][8];   // (one workgroup per CU either way: registers are not what limits residency)
 #pragma unroll
   for (int u = 0; u < NL; ++u) {
     const int p = u * NT + tid;
@@ -68,7 +63,11 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
     goff[u] = r * row + c;
     loff[u] = in ? (c / CPR) * Cfg::kHeadElems + r * RS + (c % CPR) * 8 : 0;
     pidx[u] = in ? p : 0;
-    coff[u] = c * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      gam[u][e] = gamma[c * 8 + e];
+      bet[u][e] = beta[c * 8 + e];
+    }
   }
   const int j16 = lane & 15, g4 = lane >> 4;
   const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
@@ -125,19 +124,41 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
     // ---- LayerNorm statistics, level 1: mean and centred sum of squares of every 8-channel chunk ----
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
-      float tv[8];
-      float sum = 0.0f;
+      float mean, m2;
+      if constexpr (NS == 1) {
+        // fp16: sums of (t - pivot) and its square, pivot = the chunk's first value, the difference in packed
+        // half precision and the sums by the mixed-precision dot product (no cancellation: the deviations
+        // inside a chunk are small next to a large common offset)
+        const uint32_t p16 = tr[u][0] & 0xffffu;
+        const f16x2 np = __builtin_bit_cast(f16x2, (p16 ^ 0x8000u) * 0x10001u);
+        const f16x2 one = __builtin_bit_cast(f16x2, 0x3C003C00u);
+        float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        unpack2<T>(tr[u][w], tv[2 * w], tv[2 * w + 1]);
-        sum += tv[2 * w] + tv[2 * w + 1];
-      }
-      const float mean = sum * 0.125f;
-      float m2 = 0.0f;
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t word = tr[u][w];   // (by value: a bit cast applied to the vector element itself reads element 0)
+          const f16x2 dd = __builtin_bit_cast(f16x2, word) + np;
+          s1 = __builtin_amdgcn_fdot2(dd, one, s1, false);
+          s2 = __builtin_amdgcn_fdot2(dd, dd, s2, false);
+        }
+        float pivot, unused;
+        unpack2<T>(p16, pivot, unused);
+        mean = __builtin_fmaf(s1, 0.125f, pivot);
+        m2 = fmaxf(__builtin_fmaf(-0.125f * s1, s1, s2), 0.0f);
+      } else {
+        float tv[8];
+        float sum = 0.0f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float dv = tv[e] - mean;
-        m2 = __builtin_fmaf(dv, dv, m2);
+        for (int w = 0; w < 4; ++w) {
+          unpack2<T>(tr[u][w], tv[2 * w], tv[2 * w + 1]);
+          sum += tv[2 * w] + tv[2 * w + 1];
+        }
+        mean = sum * 0.125f;
+        m2 = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float dv = tv[e] - mean;
+          m2 = __builtin_fmaf(dv, dv, m2);
+        }
       }
       if (u * NT + tid < Cfg::kChunks) part[pidx[u]] = f32x2{mean, m2};
     }
@@ -174,21 +195,16 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
       if (u * NT + tid < Cfg::kChunks) {
         const bool ok = trow[u] < lim;
         const f32x2 rsd = rowstat[ok ? trow[u] : 0];
-        const f32x4* gp = reinterpret_cast<const f32x4*>(affine + coff[u]);
-        const f32x4* bp = reinterpret_cast<const f32x4*>(affine + W * D + coff[u]);
-        const f32x4 g0 = gp[0], g1 = gp[1], b0 = bp[0], b1 = bp[1];
-        const float gam[8] = {g0[0], g0[1], g0[2], g0[3], g1[0], g1[1], g1[2], g1[3]};
-        const float bet[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
         u32x4 ph, pl;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           float x0, x1, t0, t1;
           unpack2<T>(ar[u][w], x0, x1);
           unpack2<T>(tr[u][w], t0, t1);
-          const float y0 = __builtin_fmaf(gam[2 * w] * rsd[1], t0 - rsd[0], bet[2 * w]);
-          const float y1 = __builtin_fmaf(gam[2 * w + 1] * rsd[1], t1 - rsd[0], bet[2 * w + 1]);
-          x0 += y0 >= 0.0f ? y0 : slope * y0;
-          x1 += y1 >= 0.0f ? y1 : slope * y1;
+          const float y0 = __builtin_fmaf(gam[u][2 * w] * rsd[1], t0 - rsd[0], bet[u][2 * w]);
+          const float y1 = __builtin_fmaf(gam[u][2 * w + 1] * rsd[1], t1 - rsd[0], bet[u][2 * w + 1]);
+          x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
+          x1 += fmaxf(y1, slope * y1);
           float p0 = ok ? phi<FM>(x0) : 0.0f;
           float p1 = ok ? phi<FM>(x1) : 0.0f;
           if constexpr (NS == 1) {

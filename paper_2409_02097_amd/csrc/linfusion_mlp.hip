@@ -182,7 +182,7 @@ int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, co
     return LINFUSION_ERR_INVALID;
   if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
   if (!(ln_eps > 0.0f) || std::isinf(ln_eps)) return LINFUSION_ERR_INVALID;
-  if (!std::isfinite(slope)) return LINFUSION_ERR_INVALID;
+  if (!(slope >= 0.0f && slope <= 1.0f)) return LINFUSION_ERR_INVALID;
   if (flags & ~LINFUSION_FLAG_UNNORMALIZED) return LINFUSION_ERR_INVALID;
   MlpPlan p;
   int rc = make_mlp_plan(B, H, N, d, dtype, &p);

@@ -142,6 +142,7 @@ def test_rejected_arguments():
     call = lambda *a, **k: lf.linfusion_attn_fwd_mlp(*a, check=False, **k)
     assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 0.0, 0.01, 0, ws) == -1           # ln_eps must be positive
     assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 1e-5, float("nan"), 0, ws) == -1
+    assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 1e-5, 1.5, 0, ws) == -1           # slope must lie in [0, 1]
     assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 1e-5, 0.01, lf.FLAG_FORCE_FUSED, ws) == -1
     assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 1e-5, 0.01, 0, ws[:1024]) == -4   # workspace too small
     assert call(*ins[:5], ins[0], *ins[5:], 8, 0, 1e-6, 1e-5, 0.01, 0, ws) == -7       # out aliases an input
