@@ -158,3 +158,52 @@ def test_16k_image_workload_backward_sampled_rows():
         bound = parity.TOL[dtype] * scale[name_] + orc.half_ulp(ref[name_], dtype)
         assert (err - bound).max() <= 0, f"{name_}: error {err.max():.3e} vs term scale {scale[name_]:.3e}"
         print(f"  {name_}: error / term scale {err.max() / scale[name_]:.2e}", flush=True)
+
+
+def test_16k_image_workload_mlp_fed_sampled_rows():
+    """linfusion_attn_fwd_mlp at the benchmark shape: the oracle forms k = g'(X) for all 2,097,152 tokens in
+    slices (LayerNorm over the 320 channels of a token), accumulates the exact fp64 state of a subset of heads,
+    and evaluates sampled output rows; finiteness and the range of V are checked over every element."""
+    name = "sd15_16k_f16"
+    c = wl.CONFIGS[name]
+    B, H, N, d, dtype = c["B"], c["H"], c["N"], c["d"], c["dtype"]
+    C = H * d
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=c["idx"], device="cuda")
+    a_q, t_q, a_k, t_k, v = ins[:5]
+    gq, bq, gk, bk = (t.cpu().numpy().astype(np.float64) for t in ins[5:])
+    out = torch.empty_like(a_q)
+    ws = torch.empty(lf.linfusion_attn_mlp_workspace_bytes(B, H, N, d, wl.DTYPE_CODE[dtype]), dtype=torch.uint8,
+                     device="cuda")
+    lf.linfusion_attn_fwd_mlp(a_q, t_q, a_k, t_k, v, out, *ins[5:], H, lf.PHI_ELU_PLUS_ONE, wl.EPS, 1e-5, 0.01, 0, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    vmin = v.amin(dim=1, keepdim=True).float()
+    vmax = v.amax(dim=1, keepdim=True).float()
+    assert bool((out.float() >= vmin - 1e-3).all()) and bool((out.float() <= vmax + 1e-3).all())
+
+    heads = (0, 5, 7)
+    S = {h: np.zeros((d, d)) for h in heads}
+    z = {h: np.zeros(d) for h in heads}
+    step = 1 << 18
+    for s0 in range(0, N, step):
+        if s0 % (1 << 20) == 0:
+            print(f"oracle keys: tokens {s0} ..", flush=True)
+        sl = slice(s0, s0 + step)
+        k = orc.mlp_branch_sum(orc.widen(wl.stored_numpy(a_k[0, sl]), dtype), orc.widen(wl.stored_numpy(t_k[0, sl]), dtype),
+                               gk, bk, 1e-5, 0.01)
+        vs = orc.widen(wl.stored_numpy(v[0, sl]), dtype)
+        for h in heads:
+            S_c, z_c = orc.state(k[:, h * d:(h + 1) * d], vs[:, h * d:(h + 1) * d])
+            S[h] += S_c
+            z[h] += z_c
+    rng = np.random.default_rng(20240903)
+    edges = [0, 31, 32, 255, 256, N // 2 - 1, N // 2, N - 33, N - 32, N - 1]
+    rows = np.unique(np.concatenate([np.array(edges), rng.integers(0, N, size=4096)]))
+    idx = torch.from_numpy(rows).cuda()
+    q = orc.mlp_branch_sum(orc.widen(wl.stored_numpy(a_q[0].index_select(0, idx)), dtype),
+                           orc.widen(wl.stored_numpy(t_q[0].index_select(0, idx)), dtype), gq, bq, 1e-5, 0.01)
+    got = parity.to_f64(out[0].index_select(0, idx))
+    for h in heads:
+        ref = orc.apply_state(q[:, h * d:(h + 1) * d], S[h], z[h], orc.ELU_PLUS_ONE, wl.EPS)
+        r = parity.check_slice(got[:, h * d:(h + 1) * d], ref, dtype, f"{name} mlp-fed head {h} sampled rows")
+        print(f"  head {h} sampled rows: max-norm ratio {r[0]:.2e}, rel L2 {r[1]:.2e}", flush=True)
