@@ -38,12 +38,15 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
     *blk = (int)((b + lf::kWavesPerWG - 1) / lf::kWavesPerWG * lf::kWavesPerWG);
     return (int)((n_tiles + t - 1) / t);
   };
+  // Launch sizes measured on MI355X: up to a few hundred MB of tensor traffic two workgroups per CU (one resident
+  // round) are best for the gradient kernels too; at GB sizes four (dQ, dK/dV) and eight (state gradient) per CU.
+  const bool mid = 4.0 * (double)BH * (double)N * d * 2.0 < (double)lfh::env_int("LINFUSION_APPLY_ONE_ROUND_MB", 768) * 1048576.0;
   p->splits = per_head(lfh::env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_REDUCE_BLK", 16),
                        &p->blk_reduce);
-  p->gsplits = per_head(lfh::env_int("LINFUSION_BWD_REDUCE_WGS", 8 * kNumCU), lfh::env_int("LINFUSION_BWD_REDUCE_BLK", 16),
-                        &p->gblk_reduce);
-  p->apply_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY_WGS", 4 * kNumCU), lfh::env_int("LINFUSION_BWD_APPLY_BLK", 8),
-                          &p->blk_apply);
+  p->gsplits = per_head(lfh::env_int("LINFUSION_BWD_REDUCE_WGS", (mid ? 2 : 8) * kNumCU),
+                        lfh::env_int("LINFUSION_BWD_REDUCE_BLK", 16), &p->gblk_reduce);
+  p->apply_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY_WGS", (mid ? 2 : 4) * kNumCU),
+                          lfh::env_int("LINFUSION_BWD_APPLY_BLK", 8), &p->blk_apply);
   p->ne = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   int most = p->splits > p->gsplits ? p->splits : p->gsplits;
