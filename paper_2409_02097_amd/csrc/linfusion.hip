@@ -18,7 +18,7 @@
 
 namespace {
 
-constexpr int kVersion = 300;  // 0.3.0
+constexpr int kVersion = 500;  // 0.5.0
 constexpr int kMaxDevices = 16;
 constexpr int kNumCU = 256;    // the library targets one chip
 
