@@ -227,6 +227,34 @@ int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, co
 size_t linfusion_attn_mlp_workspace_bytes(int B, int H, long long N, int d, int dtype);
 
 /*
+ * The mixer with a feature width d_qk of q and k different from the value width d_v (Prop. 3: with
+ * vector-valued attention weights f' and g' map to d' * r channels while the values keep theirs; the
+ * computational form is that of Prop. 2 with a d_qk x d_v state):
+ *
+ *     S = sum_j phi(k_j)^T v_j  (d_qk x d_v),  z = sum_j phi(k_j)  (d_qk),
+ *     out_i = phi(q_i) S / (phi(q_i) . z + eps)                      (d_v)
+ *
+ *   q, k            DEVICE pointers, contiguous [B, H, N, d_qk]; v, out: contiguous [B, H, N, d_v]; fp16 or
+ *                   bf16 (LINFUSION_DTYPE_F32 -> LINFUSION_ERR_UNSUPPORTED); 16-byte aligned; out must not
+ *                   overlap an input.
+ *   d_qk, d_v       d_v in {40, 64}, d_qk in {16, 32, 40, 64, 80}, d_qk != d_v (equal widths are
+ *                   linfusion_attn_fwd_ex's); anything else -> LINFUSION_ERR_UNSUPPORTED.
+ *   flags           LINFUSION_FLAG_NONE or LINFUSION_FLAG_UNNORMALIZED (anything else -> ERR_INVALID).
+ *   workspace       DEVICE scratch of at least linfusion_attn_qv_workspace_bytes(...) bytes, 16-byte
+ *                   aligned, caller-owned, contents undefined before and after.
+ *   events          NULL, or four hipEvent_t created by the caller (passed as void*), recorded on `stream`
+ *                   before the state reduction, after it, after the combine, and after apply.
+ * Enqueues three kernels on `stream`; never allocates, never synchronises; run-to-run identical results.
+ */
+int linfusion_attn_fwd_qv(const void* q, const void* k, const void* v, void* out,
+                          int B, int H, long long N, int d_qk, int d_v,
+                          int dtype, int feature_map, float eps, unsigned flags,
+                          void* workspace, size_t workspace_bytes, void* stream, void* events[4]);
+
+/* Bytes of device scratch linfusion_attn_fwd_qv needs; pure host function; 0 for rejected arguments. */
+size_t linfusion_attn_qv_workspace_bytes(int B, int H, long long N, int d_qk, int d_v, int dtype);
+
+/*
  * Synchronises `stream` and reports whether the most recent single-launch call that used this
  * workspace for this shape completed: LINFUSION_OK, LINFUSION_ERR_TIMEOUT, or an argument / HIP
  * error code.  (The split path cannot time out; after it this returns LINFUSION_OK.)

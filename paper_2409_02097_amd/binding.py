@@ -61,6 +61,11 @@ def library() -> ctypes.CDLL:
     lib.linfusion_attn_fwd_mlp.restype = i32
     lib.linfusion_attn_mlp_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
     lib.linfusion_attn_mlp_workspace_bytes.restype = sz
+    lib.linfusion_attn_fwd_qv.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, i32, f32, u32, vp, sz, vp,
+                                          ctypes.POINTER(ctypes.c_void_p * 4)]
+    lib.linfusion_attn_fwd_qv.restype = i32
+    lib.linfusion_attn_qv_workspace_bytes.argtypes = [i32, i32, i64, i32, i32, i32]
+    lib.linfusion_attn_qv_workspace_bytes.restype = sz
     lib.linfusion_attn_last_error.argtypes = [vp, sz, i32, i32, i64, i32, i32, vp]
     lib.linfusion_attn_last_error.restype = i32
     lib.linfusion_attn_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
@@ -155,6 +160,30 @@ def linfusion_attn_bwd(q, k, v, dout, dq, dk, dv, feature_map: int = PHI_ELU_PLU
                                       flags, ws_ptr, ws_bytes, _stream_ptr(stream))
     if check and rc != 0:
         raise LinFusionError(rc, "linfusion_attn_bwd")
+    return rc
+
+
+def linfusion_attn_qv_workspace_bytes(B: int, H: int, N: int, d_qk: int, d_v: int, dtype: int) -> int:
+    return int(library().linfusion_attn_qv_workspace_bytes(B, H, N, d_qk, d_v, dtype))
+
+
+def linfusion_attn_fwd_qv(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6, flags: int = FLAG_NONE,
+                          workspace=None, stream=None, events=None, check: bool = True) -> int:
+    """out <- mixer(q, k, v) with q, k contiguous [B, H, N, d_qk] and v, out contiguous [B, H, N, d_v], d_qk != d_v."""
+    if q.shape != k.shape or v.shape != out.shape or q.shape[:3] != v.shape[:3] or q.dim() != 4:
+        raise ValueError("q, k: [B, H, N, d_qk]; v, out: [B, H, N, d_v]")
+    if any(not t.is_contiguous() or t.dtype != q.dtype or t.device != q.device for t in (q, k, v, out)):
+        raise ValueError("q, k, v, out must be contiguous tensors of one dtype on one device")
+    B, H, N, dk = q.shape
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = library().linfusion_attn_fwd_qv(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, dk,
+                                         v.shape[3], _dtype_code(q), feature_map, eps, flags, ws_ptr, ws_bytes,
+                                         _stream_ptr(stream),
+                                         ctypes.byref((ctypes.c_void_p * 4)(*[ctypes.c_void_p(int(e)) for e in events]))
+                                         if events is not None else None)
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_fwd_qv")
     return rc
 
 

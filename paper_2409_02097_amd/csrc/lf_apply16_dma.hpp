@@ -44,27 +44,36 @@
 
 namespace lf {
 
-template <int D> struct ApplyDmaCfg {
+// D: width of the query rows that come in; DV: width of the value / output rows that leave (Prop. 3 allows a
+// feature width other than the value width; DV = D everywhere else).
+template <int D, int DV = D> struct ApplyDmaCfg {
   using Sh = Shape16<D>;
   static constexpr int kCPR = Sh::kChunksPerRow;
   static constexpr int kRowBytes = D * 2;
   static constexpr int kChunks = kTile * kCPR;
   static constexpr int kNL = (kChunks + 63) / 64;
-  static constexpr int kSlotBytes = kNL * 1024;          // whole 1 KiB deposits; >= the tile's bytes
+  static constexpr int kCPRO = DV / 8;                   // the same four for the tile that is stored
+  static constexpr int kRowBytesO = DV * 2;
+  static constexpr int kChunksO = kTile * kCPRO;
+  static constexpr int kNLO = (kChunksO + 63) / 64;
+  static constexpr int kSlotBytes = (kNL > kNLO ? kNL : kNLO) * 1024;   // whole 1 KiB deposits; >= either tile's bytes
   static constexpr int kRing = 3;
   static constexpr int kStageOffset = (kRing - 1) * kWavesPerWG * kSlotBytes;
-  static constexpr int kStageBytes = (D * D + D) * 4 + 64;
+  static constexpr int kStageBytes = (D * DV + D) * 4 + 64;
   // XOR swizzle of the chunk position with the row index where rows are 64 or 128 bytes
   static constexpr int kSwzMask = (kCPR == 8) ? 7 : (kCPR == 4 ? 3 : 0);
   static constexpr int kSwzShift = (kCPR == 4) ? 2 : 0;
   static __device__ __forceinline__ int swz(int row) { return (row >> kSwzShift) & kSwzMask; }
+  static constexpr int kSwzMaskO = (kCPRO == 8) ? 7 : (kCPRO == 4 ? 3 : 0);
+  static constexpr int kSwzShiftO = (kCPRO == 4) ? 2 : 0;
+  static __device__ __forceinline__ int swzo(int row) { return (row >> kSwzShiftO) & kSwzMaskO; }
 };
 
 // `waves`: waves per workgroup (4, or 8 for the row-piece kernel on groups of eight heads)
-template <typename T, int D>
+template <typename T, int D, int DV = D>
 constexpr int apply16_dma_lds_bytes(int waves = kWavesPerWG) {
-  int ring = ApplyDmaCfg<D>::kRing * ApplyDmaCfg<D>::kSlotBytes * waves;
-  int st = (ApplyDmaCfg<D>::kRing - 1) * ApplyDmaCfg<D>::kSlotBytes * waves + ApplyDmaCfg<D>::kStageBytes;
+  int ring = ApplyDmaCfg<D, DV>::kRing * ApplyDmaCfg<D, DV>::kSlotBytes * waves;
+  int st = (ApplyDmaCfg<D, DV>::kRing - 1) * ApplyDmaCfg<D, DV>::kSlotBytes * waves + ApplyDmaCfg<D, DV>::kStageBytes;
   return ring > st ? ring : st;
 }
 
@@ -98,17 +107,19 @@ template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :
 // statistics come from the tile in LDS: every lane reduces the channels it holds of its token (mean and
 // centred sum of squares, exact in two passes over registers), the 2 W pieces per token meet in LDS and are
 // merged with the pairwise-variance formula -- one more workgroup barrier per tile, no extra memory pass.
-template <typename T, int D, int FM, bool NORM, int ROWS_W = 0, bool MLP = false>
+template <typename T, int D, int FM, bool NORM, int ROWS_W = 0, bool MLP = false, int DV = D>
 struct ApplyDma {
   static constexpr bool ROWS = ROWS_W > 0;
   static_assert(!MLP || ROWS, "the two-branch input needs whole token rows in one workgroup");
+  static_assert(DV == D || !ROWS, "unequal query and value widths run on the per-head kernel only");
   static constexpr int W = ROWS ? ROWS_W : kWavesPerWG;   // waves per workgroup
   static constexpr int NT = 64 * W;
   using Sh = Shape16<D>;
-  using Cfg = ApplyDmaCfg<D>;
+  using Cfg = ApplyDmaCfg<D, DV>;
   static constexpr int NS = NSplit<T>::value;
-  static constexpr int KS = Sh::kKS, MT2 = Sh::kMT2, CPR = Sh::kChunksPerRow, HALF = Sh::kHalf;
-  static constexpr int NL = Cfg::kNL, NE = D * D + D, R = Cfg::kRing;
+  // k-steps and chunks follow the query width D, output tiles and channels per half-wave the value width DV
+  static constexpr int KS = Sh::kKS, MT2 = Shape16<DV>::kMT2, CPR = Sh::kChunksPerRow, HALF = Shape16<DV>::kHalf;
+  static constexpr int NL = Cfg::kNL, NLO = Cfg::kNLO, NE = D * DV + D, R = Cfg::kRing;
   static_assert(R == 3, "the wait counts below are written for a ring of three slots");
   // ROWS: chunks per row piece, and the rotation that spreads 16 consecutive tokens over the 16
   // sixteen-byte bank groups: row r is rotated by (r * G >> 4) % G chunks, G = gcd(PC, 16)
@@ -129,14 +140,15 @@ struct ApplyDma {
   int rs_q, rs_o;
   int lane, wave, tok, kg, row_byte, tsw;   // ROWS: row_byte = byte offset of the token's piece in a slot block,
                                             //       tsw = first chunk of this wave's head + the row's rotation
+  int row_byte_o, tsw_o;                    // the same two for the row that leaves (differ when DV != D)
   // LDS position p = 64 u + lane of a slot holds the chunk of token row trow[u] that lies qoff[u]
   // (in Q) / ooff[u] (in out) vector units after the tile's first row
-  int trow[NL], qoff[NL], ooff[NL];
+  int trow[NL], qoff[NL], ooff[NLO], trow_o[NLO];
   // ROWS: stores go out in memory order (whole 128-byte lines per instruction); lane (u, l) then fetches its
   // chunk from byte soff[u] of the wave's slot region
   int soff[ROWS ? NL : 1];
   TileIter it, ahead;
-  u32x4 A[NSplit<T>::value][Shape16<D>::kMT2][Shape16<D>::kKS];   // this wave's state operands
+  u32x4 A[NSplit<T>::value][Shape16<DV>::kMT2][Shape16<D>::kKS];   // this wave's state operands
   float c1, eps_s, c1_az;   // c1_az: alpha_z, kept for save_packed
   // MLP: the LayerNorm branch's tensor, the affine of this lane's channels, and the two scalars
   const u32x4* Th;
@@ -167,18 +179,29 @@ struct ApplyDma {
         int pos = cs + rot(r);               // ... which sits at this rotated position of the row piece
         if (pos >= PC) pos -= PC;
         ooff[u] = r * rs_o + cs;
+        trow_o[u] = r;
         soff[u] = ((r % RPR) * PC + pos) * 16;
       }
+      row_byte_o = row_byte;
+      tsw_o = tsw;
     } else {
       row_byte = tok * Cfg::kRowBytes;
       tsw = Cfg::swz(tok);
+      row_byte_o = tok * Cfg::kRowBytesO;
+      tsw_o = Cfg::swzo(tok);
 #pragma unroll
       for (int u = 0; u < NL; ++u) {
         const int p = u * 64 + lane;
         const int r = p / CPR, pos = p % CPR;
         trow[u] = r;
         qoff[u] = r * rs_q + (pos ^ Cfg::swz(r));
-        ooff[u] = r * rs_o + (pos ^ Cfg::swz(r));
+      }
+#pragma unroll
+      for (int u = 0; u < NLO; ++u) {
+        const int p = u * 64 + lane;
+        const int r = p / Cfg::kCPRO, pos = p % Cfg::kCPRO;
+        trow_o[u] = r;
+        ooff[u] = r * rs_o + (pos ^ Cfg::swzo(r));
       }
     }
   }
@@ -212,6 +235,11 @@ struct ApplyDma {
     } else {
       return slot_ptr(slot) + row_byte + ((chunk ^ tsw) << 4);
     }
+  }
+  // the same for the row that leaves (the finished tile takes the place of the tile that came in)
+  LF_DEV unsigned char* out_chunk_ptr(int slot, int chunk) const {
+    if constexpr (DV == D) return chunk_ptr(slot, chunk);
+    else return slot_ptr(slot) + row_byte_o + ((chunk ^ tsw_o) << 4);
   }
 
   // copies tile `tile` into ring slot `slot`; always issues exactly NLC vector memory instructions
@@ -296,7 +324,7 @@ struct ApplyDma {
     float* st = reinterpret_cast<float*>(smem + kStageOffset);
     float* redmax = st + NE;
     float mS = 0.0f, mz = 0.0f;
-    static_assert(NE % 4 == 0 && (D * D) % 4 == 0, "the state is moved four floats at a time");
+    static_assert(NE % 4 == 0 && (D * DV) % 4 == 0, "the state is moved four floats at a time");
     for (int e = threadIdx.x; e < NE / 4; e += NT) {
       f32x4 x;
       if constexpr (COHERENT) {
@@ -307,7 +335,7 @@ struct ApplyDma {
       }
       reinterpret_cast<f32x4*>(st)[e] = x;
       const float m4 = fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3])));
-      if (e < D * D / 4) mS = fmaxf(mS, m4); else mz = fmaxf(mz, m4);
+      if (e < D * DV / 4) mS = fmaxf(mS, m4); else mz = fmaxf(mz, m4);
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -342,9 +370,9 @@ struct ApplyDma {
               float x = 0.0f;
               bool zrem = false;
               if (chunk < CPR) {
-                if (slot < HALF) x = st[ch * D + hv * HALF + slot] * aS;
-                else if (NORM && slot == HALF) x = st[D * D + ch] * az;
-                else if (NORM && slot == HALF + 1) { x = st[D * D + ch] * az; zrem = true; }
+                if (slot < HALF) x = st[ch * DV + hv * HALF + slot] * aS;
+                else if (NORM && slot == HALF) x = st[D * DV + ch] * az;
+                else if (NORM && slot == HALF + 1) { x = st[D * DV + ch] * az; zrem = true; }
               }
               float r0, r1;
               unpack2<T>(pack2<T>(x, 0.0f), r0, r1);   // x rounded once to 16 bits
@@ -371,11 +399,11 @@ struct ApplyDma {
       if (aslot >= R) aslot -= R;
       if (ahead.valid()) {
         issue_copy(ahead.t, aslot);
-        // issue order is  C0 C1 | C2 W0 S0 | C3 W1 S1 | C4 W2 S2 | ...  (C copies, W wait, S stores, NL
-        // instructions each): after tile j's copies come C(j+1), C(j+2) and the stores S(j-2), S(j-1)
+        // issue order is  C0 C1 | C2 W0 S0 | C3 W1 S1 | C4 W2 S2 | ...  (C copies of NL, S stores of NLO
+        // instructions, W wait): after tile j's copies come C(j+1), C(j+2) and the stores S(j-2), S(j-1)
         if (iter == 0) wait_vmcnt<2 * NL>();
-        else if (iter == 1) wait_vmcnt<3 * NL>();
-        else wait_vmcnt<4 * NL>();
+        else if (iter == 1) wait_vmcnt<2 * NL + NLO>();
+        else wait_vmcnt<2 * NL + 2 * NLO>();
       } else {
         wait_vmcnt<0>();
       }
@@ -558,10 +586,10 @@ struct ApplyDma {
           w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
         }
         const int chunk = kg * (HALF / 8) + c;
-        *reinterpret_cast<u32x4*>(chunk_ptr(slot, chunk)) = w;
+        *reinterpret_cast<u32x4*>(out_chunk_ptr(slot, chunk)) = w;
       }
     } else {
-      static_assert(HALF % 8 == 0 || Cfg::kSwzMask == 0, "64-bit pieces assume whole chunks stay together");
+      static_assert(HALF % 8 == 0 || Cfg::kSwzMaskO == 0, "64-bit pieces assume whole chunks stay together");
 #pragma unroll
       for (int c = 0; c < HALF / 4; ++c) {
         u32x2 w;
@@ -571,23 +599,23 @@ struct ApplyDma {
           w[e] = pack2<T>(acc[s0 / 16][s0 % 16] * scale, acc[(s0 + 1) / 16][(s0 + 1) % 16] * scale);
         }
         const int byte = kg * (HALF * 2) + c * 8;   // offset inside the head's row
-        *reinterpret_cast<u32x2*>(chunk_ptr(slot, byte >> 4) + (byte & 15)) = w;
+        *reinterpret_cast<u32x2*>(out_chunk_ptr(slot, byte >> 4) + (byte & 15)) = w;
       }
     }
   }
 
-  // coalesced stores of a finished tile; always NL instructions (lanes without a valid chunk are masked)
+  // coalesced stores of a finished tile; always NLO instructions (lanes without a valid chunk are masked)
   LF_DEV void store_tile(long long tile, int slot) {
     const unsigned char* sl = slot_ptr(slot);
     long long rem = N - tile * kTile;
     const int lim = rem < kTile ? (int)rem : kTile;
     u32x4* op = Oh + tile * kTile * rs_o;
 #pragma unroll
-    for (int u = 0; u < NL; ++u) {
+    for (int u = 0; u < NLO; ++u) {
       int from = u * 1024 + lane * 16;
       if constexpr (ROWS) from = soff[u];
       const u32x4 w = *reinterpret_cast<const u32x4*>(sl + from);
-      if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) st_stream(op + ooff[u], w);
+      if (u * 64 + lane < Cfg::kChunksO && trow_o[u] < lim) st_stream(op + ooff[u], w);
     }
   }
 };

@@ -68,6 +68,13 @@ def make_qkv(B, H, N, d, dtype, idx=0, k_scale=1.0, device="cpu", seed_offset=0)
     return q, k, v
 
 
+def make_qkv_widths(B, H, N, d_qk, d_v, dtype, idx=0, device="cpu"):
+    """q, k ~ N(0, 1) of width d_qk and v ~ N(0, 1) of width d_v (feature width other than the value width)."""
+    base = BASE_SEED + 1000 * idx + 700
+    return (draw((B, H, N, d_qk), base + 0, dtype, device), draw((B, H, N, d_qk), base + 1, dtype, device),
+            draw((B, H, N, d_v), base + 2, dtype, device))
+
+
 def make_mlp_inputs(B, H, N, d, dtype, idx=0, device="cpu", zero_start=False):
     """Stand-ins for what the two-branch MLPs in front of the mixer hand over, token-major [B, N, H*d]:
     a_q, a_k (linear-branch results) and v ~ N(0, 1); t_q, t_k (results of the second branch's Linear)

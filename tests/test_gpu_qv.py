@@ -1,0 +1,84 @@
+"""GPU parity of linfusion_attn_fwd_qv (feature width of q, k other than the value width, Prop. 3) against the
+fp64 oracle on the same stored inputs, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_02097_amd as lf
+from oracle import linattn_oracle as orc
+from paper_2409_02097_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+PAIRS = [(16, 40), (32, 40), (64, 40), (80, 40), (16, 64), (32, 64), (40, 64), (80, 64)]
+
+
+def _run(q, k, v, fm=0, eps=1e-6, flags=0):
+    B, H, N, dk = q.shape
+    dv = v.shape[3]
+    dtype = {torch.float16: "f16", torch.bfloat16: "bf16"}[q.dtype]
+    n = lf.linfusion_attn_qv_workspace_bytes(B, H, N, dk, dv, wl.DTYPE_CODE[dtype])
+    assert n > 0
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    out = torch.full(v.shape, float("nan"), dtype=v.dtype, device="cuda")
+    lf.linfusion_attn_fwd_qv(q.cuda(), k.cuda(), v.cuda(), out, fm, eps, flags, ws)
+    torch.cuda.synchronize()
+    return out
+
+
+def _check(out, q, k, v, dtype, fm=0, eps=1e-6, normalize=True, what=""):
+    gpu = parity.to_f64(out)
+    qs, ks, vs = (wl.stored_numpy(t) for t in (q, k, v))
+    B, H = qs.shape[:2]
+    for b in range(B):
+        for h in range(H):
+            ref = orc.attention_linear_stored(qs[b, h], ks[b, h], vs[b, h], dtype, fm, eps, normalize)
+            parity.check_slice(gpu[b, h], ref, dtype, f"{what} b={b} h={h}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("dk,dv", PAIRS)
+@pytest.mark.parametrize("B,H,N", [(1, 2, 1), (2, 3, 33), (1, 2, 1000), (1, 5, 4099)])
+def test_matches_oracle(B, H, N, dk, dv, dtype):
+    print(f"qv B={B} H={H} N={N} d_qk={dk} d_v={dv} {dtype}", flush=True)
+    q, k, v = wl.make_qkv_widths(B, H, N, dk, dv, dtype, idx=90)
+    _check(_run(q, k, v), q, k, v, dtype, what=f"qv {dk}x{dv} {dtype} N={N}")
+
+
+@pytest.mark.parametrize("fm", [1, 2])
+@pytest.mark.parametrize("unnorm", [False, True])
+@pytest.mark.parametrize("dk,dv,dtype", [(80, 40, "f16"), (32, 64, "bf16")])
+def test_feature_maps_and_unnormalized(dk, dv, dtype, fm, unnorm):
+    B, H, N = 2, 2, 700
+    q, k, v = wl.make_qkv_widths(B, H, N, dk, dv, dtype, idx=91)
+    q, k = (q.float().abs() + 0.5).to(q.dtype), (k.float().abs() + 0.5).to(k.dtype)   # denominators away from zero
+    out = _run(q, k, v, fm=fm, flags=lf.FLAG_UNNORMALIZED if unnorm else 0)
+    _check(out, q, k, v, dtype, fm=fm, normalize=not unnorm, what=f"fm={fm} unnorm={unnorm}")
+    q, k, v = wl.make_qkv_widths(B, H, N, dk, dv, dtype, idx=92)
+    out = _run(q, k, v, fm=0, flags=lf.FLAG_UNNORMALIZED if unnorm else 0)
+    _check(out, q, k, v, dtype, fm=0, normalize=not unnorm, what=f"elu+1 unnorm={unnorm}")
+
+
+def test_large_and_run_to_run_identical():
+    B, H, N, dk, dv, dtype = 1, 8, 70001, 80, 40, "f16"
+    q, k, v = wl.make_qkv_widths(B, H, N, dk, dv, dtype, idx=93)
+    a, b = _run(q, k, v), _run(q, k, v)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    _check(a, q, k, v, dtype, what="large")
+
+
+def test_rejected_arguments():
+    code = wl.DTYPE_CODE
+    assert lf.linfusion_attn_qv_workspace_bytes(1, 2, 100, 40, 40, code["f16"]) == 0      # equal widths: the plain entry
+    assert lf.linfusion_attn_qv_workspace_bytes(1, 2, 100, 24, 40, code["f16"]) == 0
+    assert lf.linfusion_attn_qv_workspace_bytes(1, 2, 100, 80, 40, code["f32"]) == 0
+    q, k, v = (t.cuda() for t in wl.make_qkv_widths(1, 2, 64, 80, 40, "f16", idx=94))
+    out = torch.empty_like(v)
+    ws = torch.empty(lf.linfusion_attn_qv_workspace_bytes(1, 2, 64, 80, 40, 1), dtype=torch.uint8, device="cuda")
+    call = lambda *a, **kw: lf.linfusion_attn_fwd_qv(*a, check=False, **kw)
+    assert call(q, k, v, out, 0, -1.0, 0, ws) == -1
+    assert call(q, k, v, out, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws) == -1
+    assert call(q, k, v, out, 0, 1e-6, 0, ws[:64]) == -4
+    assert call(q, k, v, v, 0, 1e-6, 0, ws) == -7
+    assert call(q, k, v, out, 5, 1e-6, 0, ws) == -2
