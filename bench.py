@@ -150,6 +150,9 @@ def main():
                     help="also time linfusion_attn_fwd_mlp (the mixer fed by the two-branch MLPs' results, token-major) "
                          "on the same shape, next to the unfused route (q and k formed by torch ops, then the "
                          "strided mixer); reported in an extra `mlp` object of the result line")
+    ap.add_argument("--d-qk", type=int, default=0,
+                    help="also time linfusion_attn_fwd_qv with this feature width of q and k (the workload's d stays "
+                         "the value width); reported in an extra `qv` object of the result line")
     ap.add_argument("--latency-table", action="store_true",
                     help="also time the small and medium workloads, hot and cold cache, both launch paths "
                          "(JSON lines on stderr; the one-line result on stdout is unchanged)")
@@ -339,6 +342,39 @@ def main():
             "unfused": "q, k formed by torch layer_norm + leaky_relu + add (16-bit), then linfusion_attn_fwd_strided",
         }
         del ins, mout, mws
+    if args.d_qk:
+        dk = args.d_qk
+        qq, kk, vv = wl.make_qkv_widths(B, H, N, dk, d, dtype, idx=cfg["idx"], device="cuda")
+        qout = torch.empty_like(vv)
+        qws = torch.empty(lf.linfusion_attn_qv_workspace_bytes(B, H, N, dk, d, code), dtype=torch.uint8, device="cuda")
+        for _ in range(max(args.warmup // 2, 2)):
+            lf.linfusion_attn_fwd_qv(qq, kk, vv, qout, lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, qws)
+        torch.cuda.synchronize()
+        tq0 = time.perf_counter()
+        qsteps = max(args.steps // 2, 1)
+        for _ in range(qsteps):
+            lf.linfusion_attn_fwd_qv(qq, kk, vv, qout, lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, qws)
+        torch.cuda.synchronize()
+        qdt = (time.perf_counter() - tq0) / qsteps
+        qev = HipEvents(4)
+        qacc = [0.0, 0.0, 0.0]
+        for _ in range(args.profile_steps):
+            lf.linfusion_attn_fwd_qv(qq, kk, vv, qout, lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, qws, events=qev.ev)
+            qev.sync(3)
+            for i in range(3):
+                qacc[i] += qev.elapsed_ms(i, i + 1)
+        qev.close()
+        qk = [a / max(args.profile_steps, 1) for a in qacc]
+        per_elem = B * H * N * wl.ITEMSIZE[dtype]
+        rb, ab = (dk + d) * per_elem, (dk + d) * per_elem      # k + v read; q read + out written
+        result["qv"] = {
+            "d_qk": dk, "d_v": d, "ms_per_step": qdt * 1e3, "tokens_per_s": B * N / qdt, "alg_bytes": rb + ab,
+            "hbm_gbps": (rb + ab) / qdt / 1e9, "hbm_frac_of_peak": (rb + ab) / qdt / 1e9 / HBM_PEAK_GBPS,
+            "kernels": [
+                {"name": "state_reduce16_qv", "ms": qk[0], "alg_bytes": rb, "gbps": rb / (qk[0] * 1e-3) / 1e9 if qk[0] > 0 else None},
+                {"name": "combine_state", "ms": qk[1], "alg_bytes": 0, "gbps": 0.0},
+                {"name": "apply16_qv", "ms": qk[2], "alg_bytes": ab, "gbps": ab / (qk[2] * 1e-3) / 1e9 if qk[2] > 0 else None}]}
+        del qq, kk, vv, qout, qws
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(q, k, v, cfg, args.cpu_sample_tokens)
         result["cpu_baseline"] = base
