@@ -17,9 +17,13 @@ template <typename T, int D, int W> struct ReduceMlpCfg {
   static constexpr int kPartOffset = Base::kLdsBytes;                     // (mean, M2) of every 8-channel chunk
   static constexpr int kPartBytes = kTile * Base::kPiece * 8;
   static constexpr int kRowOffset = kPartOffset + kPartBytes;             // (mean, rstd) of every token row
-  static constexpr int kLdsBytes = kRowOffset + kTile * 8;
+  static constexpr int kAffineOffset = kRowOffset + kTile * 8;             // gamma[C] then beta[C], fp32
+  static constexpr int kLdsBytes = kAffineOffset + 2 * W * D * 4;
   static constexpr int kTPR = Base::kThreadsW / kTile;                    // threads that reduce one row
   static_assert(kTPR == 8 || kTPR == 16, "a row's partials are reduced inside one wave by shuffles");
+  // fp16 up to d = 40 fits 128 registers, so two 8-wave workgroups share a CU and cover each other's barrier
+  // waits (0.85 -> 0.67 ms at 2 M tokens); the other shapes would spill and keep one workgroup
+  static constexpr int kWavesPerSimd = (W == 8 && NSplit<T>::value == 1 && D <= 40) ? 4 : W / 4;
 };
 
 // State reduction from the branch results of g'.  grid = (splits, B), block = 64 W, H = W heads.
@@ -28,7 +32,7 @@ template <typename T, int D, int W> struct ReduceMlpCfg {
 // -> barrier -> each wave its head's matrix-core products.  `row`: token stride in 16-byte units (= W D / 8 for
 // dense rows); a_k, t_k and v share it.
 template <typename T, int D, int FM, int W>
-__global__ void __launch_bounds__(64 * W)
+__global__ void __launch_bounds__(64 * W, (ReduceMlpCfg<T, D, W>::kWavesPerSimd))
 state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, const u32x4* __restrict__ V,
                    long long batch_stride, int row, const float* __restrict__ gamma, const float* __restrict__ beta,
                    float ln_eps, float slope, float* __restrict__ partials, long long N, int tiles_per_block) {
@@ -52,22 +56,20 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
   f32x2* rowstat = reinterpret_cast<f32x2*>(smem + MC::kRowOffset);
 
   // chunk p = NT u + tid of a tile is chunk p % PC of token row p / PC (head (p % PC) / CPR)
-  int goff[NL], loff[NL], trow[NL], pidx[NL];
-  float gam[NL][8], bet[NL][8];   // (one workgroup per CU either way: registers are not what limits residency)
+  int loff[NL], trow[NL], coff[NL];   // (the global offset of a chunk is rebuilt from row and column: registers)
+  float* affine = reinterpret_cast<float*>(smem + MC::kAffineOffset);
+  for (int i = tid; i < W * D; i += NT) {
+    affine[i] = gamma[i];
+    affine[W * D + i] = beta[i];
+  }
 #pragma unroll
   for (int u = 0; u < NL; ++u) {
     const int p = u * NT + tid;
     const int r = p / PC, c = p % PC;
     const bool in = p < Cfg::kChunks;
     trow[u] = in ? r : kTile;
-    goff[u] = r * row + c;
     loff[u] = in ? (c / CPR) * Cfg::kHeadElems + r * RS + (c % CPR) * 8 : 0;
-    pidx[u] = in ? p : 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      gam[u][e] = gamma[c * 8 + e];
-      bet[u][e] = beta[c * 8 + e];
-    }
+    coff[u] = c * 8;
   }
   const int j16 = lane & 15, g4 = lane >> 4;
   const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
@@ -95,9 +97,10 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
       if (trow[u] < lim) {
-        ar[u] = ld_stream(Ag + base + goff[u]);
-        tr[u] = ld_stream(Tg + base + goff[u]);
-        vr[u] = ld_stream(Vg + base + goff[u]);
+        const long long at = base + trow[u] * row + (coff[u] >> 3);
+        ar[u] = ld_stream(Ag + at);
+        tr[u] = ld_stream(Tg + at);
+        vr[u] = ld_stream(Vg + at);
       } else {
         ar[u] = u32x4{0, 0, 0, 0};
         tr[u] = u32x4{0, 0, 0, 0};
@@ -160,7 +163,7 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
           m2 = __builtin_fmaf(dv, dv, m2);
         }
       }
-      if (u * NT + tid < Cfg::kChunks) part[pidx[u]] = f32x2{mean, m2};
+      if (u * NT + tid < Cfg::kChunks) part[u * NT + tid] = f32x2{mean, m2};
     }
     lds_barrier();
     // ---- level 2: TPR threads per token row merge its PC chunks (all of 8 channels) -------------------
@@ -201,8 +204,10 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
           float x0, x1, t0, t1;
           unpack2<T>(ar[u][w], x0, x1);
           unpack2<T>(tr[u][w], t0, t1);
-          const float y0 = __builtin_fmaf(gam[u][2 * w] * rsd[1], t0 - rsd[0], bet[u][2 * w]);
-          const float y1 = __builtin_fmaf(gam[u][2 * w + 1] * rsd[1], t1 - rsd[0], bet[u][2 * w + 1]);
+          const f32x2 gg = *reinterpret_cast<const f32x2*>(affine + coff[u] + 2 * w);
+          const f32x2 bb = *reinterpret_cast<const f32x2*>(affine + W * D + coff[u] + 2 * w);
+          const float y0 = __builtin_fmaf(gg[0] * rsd[1], t0 - rsd[0], bb[0]);
+          const float y1 = __builtin_fmaf(gg[1] * rsd[1], t1 - rsd[0], bb[1]);
           x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
           x1 += fmaxf(y1, slope * y1);
           float p0 = ok ? phi<FM>(x0) : 0.0f;
