@@ -138,7 +138,8 @@ int linfusion_attn_fwd_strided(const void* q, const void* k, const void* v, void
 /*
  * Benchmark aid: linfusion_attn_fwd_strided that also records four caller-created hipEvent_t
  * (passed as void*) on `stream`: events[0] before the state reduction, [1] after it, [2] after
- * the combine, [3] after apply, so a harness can time each kernel of one call.  The stride
+ * the combine (and the packing of the states into apply operands, where the row-piece kernels run),
+ * [3] after apply, so a harness can time each kernel of one call.  The stride
  * arrays may be NULL (contiguous).
  */
 int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void* out,

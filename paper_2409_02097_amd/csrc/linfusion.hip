@@ -383,7 +383,7 @@ int run16(const Args& a) {
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
   combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
       partials, a.group_reduce ? p.gsplits : p.splits, NE, state);
-  if (a.ev) (void)hipEventRecord(a.ev[2], st);
+  if (a.ev && !(a.out && a.group_apply)) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
     const size_t lds2 = apply16_dma_lds_bytes<T, D>();
     if (a.group_apply) {
@@ -395,6 +395,7 @@ int run16(const Args& a) {
         return LINFUSION_ERR_HIP;
       if (a.unnorm) pack_state16<T, D, false><<<dim3((unsigned)a.BH), blk, lds2, st>>>(state, packed);
       else pack_state16<T, D, true><<<dim3((unsigned)a.BH), blk, lds2, st>>>(state, packed);
+      if (a.ev) (void)hipEventRecord(a.ev[2], st);   // the operand packing counts with the combine
 #define LF_APPLY_W(FM, NORM, WW)                                                                          \
   {                                                                                                       \
     constexpr int ldsa = apply16_dma_lds_bytes<T, D>(WW);                                                 \

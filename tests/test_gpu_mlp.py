@@ -147,3 +147,33 @@ def test_rejected_arguments():
     assert call(*ins[:5], out, *ins[5:], 8, 0, 1e-6, 1e-5, 0.01, 0, ws[:1024]) == -4   # workspace too small
     assert call(*ins[:5], ins[0], *ins[5:], 8, 0, 1e-6, 1e-5, 0.01, 0, ws) == -7       # out aliases an input
     assert call(*ins[:5], out, *ins[5:], 8, 7, 1e-6, 1e-5, 0.01, 0, ws) == -2          # unknown feature map
+
+
+def test_recorded_into_a_graph_replays_correctly():
+    """The MLP-fed call enqueues kernels only, so it can be captured; every replay (new inputs in the same buffers,
+    eager work in between) must equal the eager result bit for bit."""
+    B, H, N, d, dtype = 1, 8, 2000, 40, "f16"
+    dev = [t.cuda() for t in wl.make_mlp_inputs(B, H, N, d, dtype, idx=87)]
+    out = torch.zeros_like(dev[0])
+    ws = _ws(B, H, N, d, dtype)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lf.linfusion_attn_fwd_mlp(*dev[:5], out, *dev[5:], H, 0, 1e-6, LN_EPS, SLOPE, 0, ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lf.linfusion_attn_fwd_mlp(*dev[:5], out, *dev[5:], H, 0, 1e-6, LN_EPS, SLOPE, 0, ws,
+                                  stream=torch.cuda.current_stream())
+    for rep in range(3):
+        fresh = [t.cuda() for t in wl.make_mlp_inputs(B, H, N, d, dtype, idx=88 + rep)]
+        for dst, src in zip(dev, fresh):
+            dst.copy_(src)
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eager = torch.empty_like(out)
+        lf.linfusion_attn_fwd_mlp(*dev[:5], eager, *dev[5:], H, 0, 1e-6, LN_EPS, SLOPE, 0, _ws(B, H, N, d, dtype))
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
