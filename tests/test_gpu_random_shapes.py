@@ -62,3 +62,65 @@ def test_random_case_matches_oracle(seed, monkeypatch):
     lf.linfusion_attn_fwd_strided(qv, kv, vv, ov, fm, 1e-6, path, ws)
     torch.cuda.synchronize()
     parity.check_all(ov.contiguous(), q, k, v, dtype, fm, 1e-6, True, f"seed {seed}")
+
+
+NS_RAGGED = [1, 2, 31, 32, 33, 63, 64, 65, 100, 255, 257, 513, 1000, 2049, 3000]
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_mlp_fed_case_matches_oracle(seed):
+    """linfusion_attn_fwd_mlp on random supported shapes (eight heads up to d = 48, four heads up to d = 80)."""
+    from oracle import linattn_oracle as orc
+    rng = np.random.default_rng(5000 + seed)
+    dtype = ["f16", "bf16"][int(rng.integers(0, 2))]
+    H = int(rng.choice([4, 8]))
+    d = int(rng.choice([8, 16, 24, 32, 40, 48] if H == 8 else [8, 16, 24, 32, 40, 48, 56, 64, 80]))
+    B, N = int(rng.integers(1, 4)), int(rng.choice(NS_RAGGED))
+    fm, unnorm = int(rng.choice([0, 0, 1])), bool(rng.integers(0, 2))
+    slope, ln_eps = float(rng.choice([0.0, 0.01, 0.2, 1.0])), float(rng.choice([1e-6, 1e-5, 1e-3]))
+    print(f"seed {seed}: mlp {dtype} H={H} d={d} B={B} N={N} fm={fm} unnorm={unnorm} slope={slope} ln_eps={ln_eps}", flush=True)
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=400 + seed))
+    if fm != 0:
+        ins[0] = (ins[0].float().abs() + 1.5).to(ins[0].dtype)      # relu: keep q, k positive after the branch sum
+        ins[2] = (ins[2].float().abs() + 1.5).to(ins[2].dtype)
+        ins[6] = ins[6].abs()
+        ins[8] = ins[8].abs()
+    dev = [t.cuda() for t in ins]
+    out = torch.full_like(dev[0], float("nan"))
+    ws = torch.empty(lf.linfusion_attn_mlp_workspace_bytes(B, H, N, d, wl.DTYPE_CODE[dtype]), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_fwd_mlp(*dev[:5], out, *dev[5:], H, fm, 1e-6, ln_eps, slope, lf.FLAG_UNNORMALIZED if unnorm else 0, ws)
+    torch.cuda.synchronize()
+    wide = [orc.widen(wl.stored_numpy(t), dtype) for t in ins[:5]]
+    vecs = [t.numpy().astype(np.float64) for t in ins[5:]]
+    ref = orc.module_mixer(*wide, *vecs, H, fm, 1e-6, not unnorm, ln_eps, slope)
+    got = parity.to_f64(out)
+    for b in range(B):
+        for h in range(H):
+            c = slice(h * d, (h + 1) * d)
+            parity.check_slice(got[b, :, c], ref[b, :, c], dtype, f"seed {seed} b={b} h={h}")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_unequal_width_case_matches_oracle(seed):
+    """linfusion_attn_fwd_qv on random supported width pairs."""
+    from oracle import linattn_oracle as orc
+    rng = np.random.default_rng(6000 + seed)
+    dtype = ["f16", "bf16"][int(rng.integers(0, 2))]
+    dv = int(rng.choice([40, 64]))
+    dk = int(rng.choice([x for x in (16, 32, 40, 64, 80) if x != dv]))
+    B, H, N = int(rng.integers(1, 3)), int(rng.integers(1, 10)), int(rng.choice(NS_RAGGED))
+    fm, unnorm = int(rng.choice([0, 0, 1])), bool(rng.integers(0, 2))
+    print(f"seed {seed}: qv {dtype} d_qk={dk} d_v={dv} B={B} H={H} N={N} fm={fm} unnorm={unnorm}", flush=True)
+    q, k, v = wl.make_qkv_widths(B, H, N, dk, dv, dtype, idx=500 + seed)
+    if fm != 0:
+        q, k = (q.float().abs() + 0.5).to(q.dtype), (k.float().abs() + 0.5).to(k.dtype)
+    out = torch.full(v.shape, float("nan"), dtype=v.dtype, device="cuda")
+    ws = torch.empty(lf.linfusion_attn_qv_workspace_bytes(B, H, N, dk, dv, wl.DTYPE_CODE[dtype]), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_fwd_qv(q.cuda(), k.cuda(), v.cuda(), out, fm, 1e-6, lf.FLAG_UNNORMALIZED if unnorm else 0, ws)
+    torch.cuda.synchronize()
+    got = parity.to_f64(out)
+    qs, ks, vs = (wl.stored_numpy(t) for t in (q, k, v))
+    for b in range(B):
+        for h in range(H):
+            ref = orc.attention_linear_stored(qs[b, h], ks[b, h], vs[b, h], dtype, fm, 1e-6, not unnorm)
+            parity.check_slice(got[b, h], ref, dtype, f"seed {seed} b={b} h={h}")
