@@ -182,6 +182,25 @@ int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* 
                        int dtype, int feature_map, float eps, unsigned flags,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * linfusion_attn_bwd on strided views: q; k and v (one layout); dout; dq; dk and dv (one layout) are each
+ * addressed by element strides {batch, head, token} with contiguous channels, as in
+ * linfusion_attn_fwd_strided (a NULL stride array = contiguous [B, H, N, d]).  Rows must be 16-byte aligned;
+ * dq and dk / dv rows must be disjoint, and the byte span of every output must be disjoint from the spans of
+ * the inputs, of the other outputs and of the workspace (so three gradients interleaved in one buffer are not
+ * accepted).  Same arithmetic and order as the contiguous call: dense strides give bit-identical results.
+ * The kernels work per head, so layouts in which a head's token row is not a whole number of 128-byte lines
+ * (token-major with d = 40 or 80) run at a fraction of the contiguous speed; d = 64 token-major does not.
+ */
+int linfusion_attn_bwd_strided(const void* q, const void* k, const void* v, const void* dout, const float* state,
+                               void* dq, void* dk, void* dv,
+                               int B, int H, long long N, int d,
+                               int dtype, int feature_map, float eps, unsigned flags,
+                               const long long q_strides[3], const long long kv_strides[3],
+                               const long long dout_strides[3], const long long dq_strides[3],
+                               const long long dkv_strides[3],
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of device scratch linfusion_attn_bwd needs; pure host function; 0 for rejected arguments. */
 size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int dtype);
 

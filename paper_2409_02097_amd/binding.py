@@ -52,6 +52,9 @@ def library() -> ctypes.CDLL:
     lib.linfusion_attn_fwd_profile.restype = i32
     lib.linfusion_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp, sz, vp]
     lib.linfusion_attn_bwd.restype = i32
+    lib.linfusion_attn_bwd_strided.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32,
+                                               st3, st3, st3, st3, st3, vp, sz, vp]
+    lib.linfusion_attn_bwd_strided.restype = i32
     lib.linfusion_attn_workspace_state_offset.argtypes = [i32, i32, i64, i32, i32]
     lib.linfusion_attn_workspace_state_offset.restype = sz
     lib.linfusion_attn_bwd_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
@@ -219,6 +222,30 @@ def linfusion_attn_fwd_mlp(a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k,
                                           if events is not None else None)
     if check and rc != 0:
         raise LinFusionError(rc, "linfusion_attn_fwd_mlp")
+    return rc
+
+
+def linfusion_attn_bwd_strided(q, k, v, dout, dq, dk, dv, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6,
+                               flags: int = FLAG_NONE, workspace=None, stream=None, check: bool = True,
+                               state=None) -> int:
+    """linfusion_attn_bwd on [B, H, N, d] views with contiguous channels; k and v must share their strides, and
+    so must dk and dv."""
+    B, H, N, d = _check_views(q, k, v, dout)
+    for t in (dq, dk, dv):
+        if t.dim() != 4 or t.shape != q.shape or t.dtype != q.dtype or not t.is_cuda or (d > 1 and t.stride(3) != 1):
+            raise ValueError("dq, dk, dv must be [B, H, N, d]-shaped device views like q with contiguous channels")
+    if dk.stride() != dv.stride():
+        raise ValueError("dk and dv must share their strides")
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = library().linfusion_attn_bwd_strided(q.data_ptr(), k.data_ptr(), v.data_ptr(), dout.data_ptr(),
+                                              state.data_ptr() if state is not None else None, dq.data_ptr(),
+                                              dk.data_ptr(), dv.data_ptr(), B, H, N, d, _dtype_code(q), feature_map,
+                                              eps, flags, ctypes.byref(_strides3(q)), ctypes.byref(_strides3(k)),
+                                              ctypes.byref(_strides3(dout)), ctypes.byref(_strides3(dq)),
+                                              ctypes.byref(_strides3(dk)), ws_ptr, ws_bytes, _stream_ptr(stream))
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_bwd_strided")
     return rc
 
 

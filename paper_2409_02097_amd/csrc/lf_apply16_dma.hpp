@@ -173,7 +173,7 @@ struct ApplyDma {
         const int r = P / PC;
         int c = P % PC - rot(r);
         if (c < 0) c += PC;
-        trow[u] = r;
+        trow[u] = (u * 64 + lane < Cfg::kChunks) ? r : kTile;   // lanes past the region: never a valid row
         qoff[u] = r * rs_q + c;
         const int cs = P % PC;               // store side: this lane takes chunk cs of row r ...
         int pos = cs + rot(r);               // ... which sits at this rotated position of the row piece
@@ -249,22 +249,22 @@ struct ApplyDma {
     const u32x4* qp = Qh + tile * kTile * rs_q;
     unsigned char* sl = slot_ptr(slot);
 #pragma unroll
+    // Every lane issues every copy (no lane mask: a masked copy is a branch to the compiler, which may then
+    // duplicate or merge the masked instructions and change the number the wave issues -- the wait counts
+    // below are in instructions).  Lanes past the tile's chunks re-read a valid chunk and deposit it in the
+    // slot's padding (slots are whole 1 KiB deposits); rows past N re-read chunk 0 and are never stored.
     for (int u = 0; u < NL; ++u) {
-      if (u * 64 + lane < Cfg::kChunks) {          // lanes past the tile would deposit past the slot's rows
-        const int c = trow[u] < lim ? qoff[u] : 0; // rows past N re-read chunk 0; their results are never stored
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
-                                         (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
-      }
+      const int c = trow[u] < lim ? qoff[u] : 0;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
+                                       (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
     }
     if constexpr (MLP) {
       const u32x4* tp = Th + tile * kTile * rs_q;
 #pragma unroll
       for (int u = 0; u < NL; ++u) {
-        if (u * 64 + lane < Cfg::kChunks) {
-          const int c = trow[u] < lim ? qoff[u] : 0;
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tp + c),
-                                           (LF_LDS void*)(sl + kTOffset + u * 1024), 16, 0, 2 /* nt */);
-        }
+        const int c = trow[u] < lim ? qoff[u] : 0;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tp + c),
+                                         (LF_LDS void*)(sl + kTOffset + u * 1024), 16, 0, 2 /* nt */);
       }
     }
   }

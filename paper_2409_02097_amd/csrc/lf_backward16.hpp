@@ -54,15 +54,16 @@ struct Ring2 {
   static_assert(R == 3, "the wait counts are written for a ring of three slots");
 
   const u32x4 *Xh, *Yh;
+  int rsx, rsy;   // token strides of the two tensors, in 16-byte units (CPR when the rows are dense)
   long long N;
   unsigned char* smem;
   int lane, wave, tok, kg, row_byte, tsw;
-  int trow[NL], goff[NL];
+  int trow[NL], gpos[NL];   // LDS position 64 u + lane holds chunk gpos[u] of token row trow[u]
   TileIter it, ahead;
 
-  LF_DEV Ring2(const u32x4* Xh_, const u32x4* Yh_, long long N_, int tiles_per_block, int wg, int nwg,
-               unsigned char* smem_)
-      : Xh(Xh_), Yh(Yh_), N(N_), smem(smem_), lane(threadIdx.x & 63),
+  LF_DEV Ring2(const u32x4* Xh_, int rsx_, const u32x4* Yh_, int rsy_, long long N_, int tiles_per_block, int wg,
+               int nwg, unsigned char* smem_)
+      : Xh(Xh_), Yh(Yh_), rsx(rsx_), rsy(rsy_), N(N_), smem(smem_), lane(threadIdx.x & 63),
         wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
         it(wg, nwg, wave, tiles_per_block, (N_ + kTile - 1) / kTile), ahead(it) {
     tok = lane & 31;
@@ -74,7 +75,7 @@ struct Ring2 {
       const int p = u * 64 + lane;
       const int r = p / CPR, pos = p % CPR;
       trow[u] = r;
-      goff[u] = r * CPR + (pos ^ AC::swz(r));
+      gpos[u] = pos ^ AC::swz(r);
     }
   }
 
@@ -103,15 +104,14 @@ struct Ring2 {
     const int lim = rem < kTile ? (int)rem : kTile;
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
-      const u32x4* gp = (which ? Yh : Xh) + tile * AC::kChunks;
+      const int rs = which ? rsy : rsx;
+      const u32x4* gp = (which ? Yh : Xh) + tile * kTile * rs;
       unsigned char* sl = tile_ptr(slot, which);
 #pragma unroll
-      for (int u = 0; u < NL; ++u) {
-        if (u * 64 + lane < AC::kChunks) {
-          const int c = trow[u] < lim ? goff[u] : 0;
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gp + c),
-                                           (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
-        }
+      for (int u = 0; u < NL; ++u) {   // every lane issues every copy; lanes past the tile deposit chunk 0 in the padding
+        const int c = trow[u] < lim ? trow[u] * rs + gpos[u] : 0;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gp + c),
+                                         (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
       }
     }
   }
@@ -121,16 +121,17 @@ struct Ring2 {
     if (ahead.valid()) issue_copy(ahead.t, 1);
     ahead.next();
   }
-  // coalesced stores of tile part `which` of slot `slot` to head tensor `Oh`: always NL instructions
-  LF_DEV void store_tile(long long tile, int slot, int which, u32x4* Oh) {
+  // coalesced stores of tile part `which` of slot `slot` to head tensor `Oh` (token stride `rso`): always NL
+  // instructions
+  LF_DEV void store_tile(long long tile, int slot, int which, u32x4* Oh, int rso) {
     const unsigned char* sl = tile_ptr(slot, which);
     long long rem = N - tile * kTile;
     const int lim = rem < kTile ? (int)rem : kTile;
-    u32x4* op = Oh + tile * AC::kChunks;
+    u32x4* op = Oh + tile * kTile * rso;
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
       const u32x4 w = *reinterpret_cast<const u32x4*>(sl + u * 1024 + lane * 16);
-      if (u * 64 + lane < AC::kChunks && trow[u] < lim) st_stream(op + goff[u], w);
+      if (u * 64 + lane < AC::kChunks && trow[u] < lim) st_stream(op + trow[u] * rso + gpos[u], w);
     }
   }
   // waits until the copies of the tile that is about to be used have landed; `iter` = tiles done so far
@@ -265,16 +266,16 @@ struct Ring2 {
 // ==========================================================================================
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-bwd_q16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __restrict__ dQ,
-        const float* __restrict__ state, f32x2* __restrict__ scal, float eps, long long N, int tiles_per_block) {
+bwd_q16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Layout lg, u32x4* __restrict__ dQ,
+        Layout ldq, const float* __restrict__ state, f32x2* __restrict__ scal, float eps, long long N,
+        int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   using RG = Ring2<T, D>;
-  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
+  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R;
   constexpr int SN = NL + (NORM ? 1 : 0);
   const long long bh = blockIdx.y;
-  const long long hoff = bh * N * CPR;
-  RG rg(Q + hoff, G + hoff, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
-  u32x4* dQh = dQ + hoff;
+  RG rg(Q + lq.slice(bh), lq.row, G + lg.slice(bh), lg.row, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  u32x4* dQh = dQ + ldq.slice(bh);
   f32x2* sh = scal + bh * N;
   rg.prefetch();
 
@@ -330,7 +331,7 @@ bwd_q16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __restr
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     rg.write_half_row(slot, 0, dr);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    rg.store_tile(tile, slot, 0, dQh);
+    rg.store_tile(tile, slot, 0, dQh, ldq.row);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     rg.it.next();
     rg.ahead.next();
@@ -349,8 +350,9 @@ bwd_q16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __restr
 // ==========================================================================================
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-bwd_qs16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __restrict__ dQ,
-         const float* __restrict__ state, float* __restrict__ partials, float eps, long long N, int tiles_per_block) {
+bwd_qs16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Layout lg, u32x4* __restrict__ dQ,
+         Layout ldq, const float* __restrict__ state, float* __restrict__ partials, float eps, long long N,
+         int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   using RG = Ring2<T, D>;
   using Sh = Shape16<D>;
@@ -358,9 +360,8 @@ bwd_qs16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __rest
   constexpr int NS = 1, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
   constexpr int MT = Sh::kMT, NE = D * D + D;
   const long long bh = blockIdx.y;
-  const long long hoff = bh * N * CPR;
-  RG rg(Q + hoff, G + hoff, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
-  u32x4* dQh = dQ + hoff;
+  RG rg(Q + lq.slice(bh), lq.row, G + lg.slice(bh), lg.row, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  u32x4* dQh = dQ + ldq.slice(bh);
   uint16_t* ecol = reinterpret_cast<uint16_t*>(smem + BwdCfg<D>::lds_bytes()) + rg.wave * 32;
   rg.prefetch();
 
@@ -481,7 +482,7 @@ bwd_qs16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __rest
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     rg.write_half_row(slot, 0, dr);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    rg.store_tile(tile, slot, 0, dQh);
+    rg.store_tile(tile, slot, 0, dQh, ldq.row);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     rg.it.next();
     rg.ahead.next();
@@ -528,17 +529,16 @@ bwd_qs16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, u32x4* __rest
 // ==========================================================================================
 template <typename T, int D, int FM>
 __global__ void __launch_bounds__(kThreads)
-bwd_kv16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, u32x4* __restrict__ dK, u32x4* __restrict__ dV,
-         const float* __restrict__ dstate, long long N, int tiles_per_block) {
+bwd_kv16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, u32x4* __restrict__ dK,
+         u32x4* __restrict__ dV, Layout ldkv, const float* __restrict__ dstate, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   using RG = Ring2<T, D>;
   constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
   constexpr int SN = 2 * NL;
   const long long bh = blockIdx.y;
-  const long long hoff = bh * N * CPR;
-  RG rg(K + hoff, V + hoff, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
-  u32x4* dKh = dK + hoff;
-  u32x4* dVh = dV + hoff;
+  RG rg(K + lkv.slice(bh), lkv.row, V + lkv.slice(bh), lkv.row, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  u32x4* dKh = dK + ldkv.slice(bh);
+  u32x4* dVh = dV + ldkv.slice(bh);
   rg.prefetch();
 
   const float aS = rg.stage_state(dstate + bh * (D * D + D));
@@ -597,8 +597,8 @@ bwd_kv16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, u32x4* __rest
     rg.write_half_row(slot, 0, x);
     rg.write_half_row(slot, 1, o);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    rg.store_tile(tile, slot, 0, dKh);
-    rg.store_tile(tile, slot, 1, dVh);
+    rg.store_tile(tile, slot, 0, dKh, ldkv.row);
+    rg.store_tile(tile, slot, 1, dVh, ldkv.row);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     rg.it.next();
     rg.ahead.next();
@@ -629,8 +629,9 @@ constexpr int bwd_state_lds_bytes() {
 
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
-bwd_state16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, const f32x2* __restrict__ scal,
-            const float* __restrict__ state, float* __restrict__ partials, long long N, int tiles_per_block) {
+bwd_state16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Layout lg,
+            const f32x2* __restrict__ scal, const float* __restrict__ state, float* __restrict__ partials, long long N,
+            int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   using Sh = Shape16<D>;
   using Cfg = BwdReduceCfg<D>;
@@ -641,8 +642,8 @@ bwd_state16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, const f32x
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const long long bh = blockIdx.y;
-  const u32x4* Qh = Q + bh * N * CPR;
-  const u32x4* Gh = G + bh * N * CPR;
+  const u32x4* Qh = Q + lq.slice(bh);
+  const u32x4* Gh = G + lg.slice(bh);
   const f32x2* sh = scal + bh * N;
   float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)NE;
 
@@ -672,7 +673,7 @@ bwd_state16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, const f32x
   for (int u = 0; u < NL; ++u) {
     const int c = u * 64 + lane;
     trow[u] = c / CPR;
-    goff[u] = c;
+    goff[u] = c % CPR;
     lds_off[u] = trow[u] * RS + (c % CPR) * 8;
   }
   const int j16 = lane & 15, g4 = lane >> 4;
@@ -691,16 +692,16 @@ bwd_state16(const u32x4* __restrict__ Q, const u32x4* __restrict__ G, const f32x
   auto issue_loads = [&](long long tile) {
     long long rem = N - tile * kTile;
     int lim = rem < kTile ? (int)rem : kTile;
-    const u32x4* qp = Qh + tile * Cfg::kChunks;
-    const u32x4* gp = Gh + tile * Cfg::kChunks;
+    const u32x4* qp = Qh + tile * kTile * lq.row;
+    const u32x4* gp = Gh + tile * kTile * lg.row;
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
       qr[u] = u32x4{0, 0, 0, 0};
       gr[u] = u32x4{0, 0, 0, 0};
       sc[u] = f32x2{1.0f, 0.0f};
       if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) {
-        qr[u] = ld_stream(qp + goff[u]);
-        gr[u] = ld_stream(gp + goff[u]);
+        qr[u] = ld_stream(qp + trow[u] * lq.row + goff[u]);
+        gr[u] = ld_stream(gp + trow[u] * lg.row + goff[u]);
         if constexpr (NORM) {
           sc[u] = sh[tile * kTile + trow[u]];
           sc[u][0] *= beta;

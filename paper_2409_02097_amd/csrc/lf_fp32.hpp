@@ -230,11 +230,10 @@ struct Apply32Dma {
     unsigned char* sl = slot_ptr(slot);
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
-      if (u * 64 + lane < Cfg::kChunks) {
-        const int c = trow[u] < lim ? qoff[u] : 0;   // rows past N re-read chunk 0; never stored
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
-                                         (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
-      }
+      // every lane issues every copy (see ApplyDma::issue_copy); lanes past the tile deposit chunk 0 in the padding
+      const int c = trow[u] < lim ? qoff[u] : 0;   // rows past N re-read chunk 0; never stored
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
+                                       (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
     }
   }
   LF_DEV void prefetch() {

@@ -1,5 +1,6 @@
 // Small host-side helpers that linfusion.hip shares with the library's other translation units.
 #pragma once
+#include <stddef.h>
 
 namespace lfh {
 
@@ -7,5 +8,12 @@ namespace lfh {
 int check_device();
 // positive integer from the environment, `dflt` when unset or not positive (tuning aids)
 int env_int(const char* name, int dflt);
+
+// Element strides {batch, head, token} of a [B, H, N, d] view with contiguous channels (null = dense).
+// check_strides: LINFUSION_OK when the kernels can address the view (non-negative, token rows 16-byte aligned,
+// index widths); `written` additionally requires that no two rows share memory.  span_bytes: bytes from the
+// first to one past the last element the view touches.
+int check_strides(const long long s[3], int B, int H, long long N, int d, size_t esz, bool written);
+size_t span_bytes(const long long s[3], int B, int H, long long N, int d, size_t esz);
 
 }  // namespace lfh

@@ -350,7 +350,7 @@ struct ApplyWide {
       if (c < 0) c += CPR;
       int spos = pos + Sw::rot(r);             // store side: this lane sends chunk pos, found at spos
       if (spos >= CPR) spos -= CPR;
-      trow[u] = r;
+      trow[u] = (u * 64 + lane < Sw::kRegionChunks) ? r : kTile;   // lanes past the region: never a valid row
       qoff[u] = r * rs_q + c;
       ooff[u] = r * rs_o + pos;
       soff[u] = ((r % RPR) * CPR + spos) * 16;
@@ -373,11 +373,11 @@ struct ApplyWide {
     unsigned char* sl = region_ptr(slot);
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
-      if (u * 64 + lane < Sw::kRegionChunks) {
-        const int c = trow[u] < lim ? qoff[u] : 0;   // rows past N re-read chunk 0; never stored
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
-                                         (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
-      }
+      // every lane issues every copy (see ApplyDma::issue_copy); lanes past the region's chunks deposit a valid
+      // chunk in the region's padding
+      const int c = trow[u] < lim ? qoff[u] : 0;   // rows past N re-read chunk 0; never stored
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
+                                       (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
     }
   }
 

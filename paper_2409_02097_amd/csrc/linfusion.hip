@@ -668,6 +668,12 @@ int fwd_owned(const void* q, const void* k, const void* v, void* out, int B, int
 namespace lfh {
 int check_device() { return ::check_device(); }
 int env_int(const char* name, int dflt) { return ::env_int(name, dflt); }
+int check_strides(const long long s[3], int B, int H, long long N, int d, size_t esz, bool written) {
+  return ::check_strides(Strides{s[0], s[1], s[2]}, B, H, N, d, esz, written);
+}
+size_t span_bytes(const long long s[3], int B, int H, long long N, int d, size_t esz) {
+  return ::span_bytes(Strides{s[0], s[1], s[2]}, B, H, N, d, esz);
+}
 }  // namespace lfh
 
 extern "C" {

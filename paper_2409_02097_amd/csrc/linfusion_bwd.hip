@@ -80,6 +80,7 @@ struct BwdArgs {
   const BwdPlan* p;
   unsigned char* ws;
   hipStream_t st;
+  lf::Layout lq, lkv, lg, ldq, ldkv;   // q; k and v; dout; dq; dk and dv
 };
 
 template <typename T, int D, int FM, bool NORM>
@@ -98,7 +99,6 @@ int run_bwd(const BwdArgs& a) {
   const u32x4* G = (const u32x4*)a.g;
   const dim3 blk(kThreads);
   hipStream_t st = a.st;
-  const Layout dense{(long long)a.H * a.N * (D / 8), a.N * (D / 8), D / 8, a.H};
   const HeadSubset all{0, a.H};
   const dim3 gr(p.splits, (unsigned)BH), ga(p.apply_wgs, (unsigned)BH);
   const dim3 gc((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH);
@@ -113,7 +113,7 @@ int run_bwd(const BwdArgs& a) {
   if (a.saved_state) {
     stateS = const_cast<float*>(a.saved_state);   // only read below
   } else {
-    state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, dense, all, partials, a.N, p.blk_reduce);
+    state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, a.lkv, all, partials, a.N, p.blk_reduce);
     combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateS);
   }
   // fp16 up to d = 48: dQ and the state gradient in one pass over Q and dout (registers allow it there)
@@ -121,18 +121,20 @@ int run_bwd(const BwdArgs& a) {
   if constexpr (kMerged) {
     if (lfh::env_int("LINFUSION_BWD_MERGED", 1) == 1) {
       if (!allow_lds(bwd_qs16<T, D, FM, NORM>, lds_a + 256)) return LINFUSION_ERR_HIP;
-      bwd_qs16<T, D, FM, NORM><<<ga, blk, lds_a + 256, st>>>(Q, G, (u32x4*)a.dq, stateS, partials, a.eps, a.N,
-                                                             p.blk_apply);
+      bwd_qs16<T, D, FM, NORM><<<ga, blk, lds_a + 256, st>>>(Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, partials,
+                                                             a.eps, a.N, p.blk_apply);
       combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.apply_wgs, NE, stateD);
-      bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, (u32x4*)a.dk, (u32x4*)a.dv, stateD, a.N, p.blk_apply);
+      bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N,
+                                                 p.blk_apply);
       return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
     }
   }
-  bwd_q16<T, D, FM, NORM><<<ga, blk, lds_a, st>>>(Q, G, (u32x4*)a.dq, stateS, scal, a.eps, a.N, p.blk_apply);
-  bwd_state16<T, D, FM, NORM><<<dim3(p.gsplits, (unsigned)BH), blk, lds_s, st>>>(Q, G, scal, stateS, partials, a.N,
-                                                                                  p.gblk_reduce);
+  bwd_q16<T, D, FM, NORM><<<ga, blk, lds_a, st>>>(Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, scal, a.eps, a.N,
+                                                  p.blk_apply);
+  bwd_state16<T, D, FM, NORM><<<dim3(p.gsplits, (unsigned)BH), blk, lds_s, st>>>(Q, a.lq, G, a.lg, scal, stateS,
+                                                                                  partials, a.N, p.gblk_reduce);
   combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.gsplits, NE, stateD);
-  bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, (u32x4*)a.dk, (u32x4*)a.dv, stateD, a.N, p.blk_apply);
+  bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N, p.blk_apply);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
@@ -172,9 +174,11 @@ size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int 
   return p.ws_total;
 }
 
-int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* dout, const float* state, void* dq,
-                       void* dk, void* dv, int B, int H, long long N, int d, int dtype, int feature_map, float eps,
-                       unsigned flags, void* workspace, size_t workspace_bytes, void* stream) {
+// strides: q; k and v; dout; dq; dk and dv -- element strides {batch, head, token}, null = contiguous [B, H, N, d]
+static int bwd_impl(const void* q, const void* k, const void* v, const void* dout, const float* state, void* dq,
+                    void* dk, void* dv, int B, int H, long long N, int d, int dtype, int feature_map, float eps,
+                    unsigned flags, const long long* const strides[5], void* workspace, size_t workspace_bytes,
+                    void* stream) {
   if (!q || !k || !v || !dout || !dq || !dk || !dv) return LINFUSION_ERR_INVALID;
   if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
   if (flags & ~LINFUSION_FLAG_UNNORMALIZED) return LINFUSION_ERR_INVALID;
@@ -188,12 +192,21 @@ int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* 
     if ((uintptr_t)x & 15) return LINFUSION_ERR_MISALIGNED;
   for (void* x : outs)
     if ((uintptr_t)x & 15) return LINFUSION_ERR_MISALIGNED;
-  const size_t tbytes = (size_t)B * H * (size_t)N * d * 2;
+  const long long dense[3] = {(long long)H * N * d, N * d, (long long)d};
+  const long long* st5[5];
+  for (int i = 0; i < 5; ++i) st5[i] = (strides && strides[i]) ? strides[i] : dense;
+  for (int i = 0; i < 5; ++i)
+    if ((rc = lfh::check_strides(st5[i], B, H, N, d, 2, i >= 3)) != LINFUSION_OK) return rc;
+  // spans of q, k, v, dout and of dq, dk, dv
+  const size_t in_span[4] = {lfh::span_bytes(st5[0], B, H, N, d, 2), lfh::span_bytes(st5[1], B, H, N, d, 2),
+                             lfh::span_bytes(st5[1], B, H, N, d, 2), lfh::span_bytes(st5[2], B, H, N, d, 2)};
+  const size_t out_span[3] = {lfh::span_bytes(st5[3], B, H, N, d, 2), lfh::span_bytes(st5[4], B, H, N, d, 2),
+                              lfh::span_bytes(st5[4], B, H, N, d, 2)};
   for (int i = 0; i < 3; ++i) {
-    for (const void* x : ins)
-      if (overlaps(outs[i], tbytes, x, tbytes)) return LINFUSION_ERR_OVERLAP;
+    for (int j = 0; j < 4; ++j)
+      if (overlaps(outs[i], out_span[i], ins[j], in_span[j])) return LINFUSION_ERR_OVERLAP;
     for (int j = i + 1; j < 3; ++j)
-      if (overlaps(outs[i], tbytes, outs[j], tbytes)) return LINFUSION_ERR_OVERLAP;
+      if (overlaps(outs[i], out_span[i], outs[j], out_span[j])) return LINFUSION_ERR_OVERLAP;
   }
   if (!workspace) return LINFUSION_ERR_WORKSPACE;
   if ((uintptr_t)workspace & 15) return LINFUSION_ERR_MISALIGNED;
@@ -202,18 +215,38 @@ int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* 
     const size_t sbytes = (size_t)B * H * p.ne * sizeof(float);
     if ((uintptr_t)state & 15) return LINFUSION_ERR_MISALIGNED;
     if (overlaps(workspace, p.ws_total, state, sbytes)) return LINFUSION_ERR_OVERLAP;
-    for (void* x : outs)
-      if (overlaps(x, tbytes, state, sbytes)) return LINFUSION_ERR_OVERLAP;
+    for (int i = 0; i < 3; ++i)
+      if (overlaps(outs[i], out_span[i], state, sbytes)) return LINFUSION_ERR_OVERLAP;
   }
-  for (const void* x : ins)
-    if (overlaps(workspace, p.ws_total, x, tbytes)) return LINFUSION_ERR_OVERLAP;
-  for (void* x : outs)
-    if (overlaps(workspace, p.ws_total, x, tbytes)) return LINFUSION_ERR_OVERLAP;
+  for (int j = 0; j < 4; ++j)
+    if (overlaps(workspace, p.ws_total, ins[j], in_span[j])) return LINFUSION_ERR_OVERLAP;
+  for (int i = 0; i < 3; ++i)
+    if (overlaps(workspace, p.ws_total, outs[i], out_span[i])) return LINFUSION_ERR_OVERLAP;
   rc = lfh::check_device();
   if (rc != LINFUSION_OK) return rc;
+  auto lay = [&](const long long* s) { return lf::Layout{s[0] / 8, s[1] / 8, (int)(s[2] / 8), H}; };   // 16-byte units
   BwdArgs a{state, q, k, v, dout, dq, dk, dv, B, H, N, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
-            &p, (unsigned char*)workspace, (hipStream_t)stream};
+            &p, (unsigned char*)workspace, (hipStream_t)stream,
+            lay(st5[0]), lay(st5[1]), lay(st5[2]), lay(st5[3]), lay(st5[4])};
   return dispatch_bwd(d, dtype, feature_map, a);
+}
+
+int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* dout, const float* state, void* dq,
+                       void* dk, void* dv, int B, int H, long long N, int d, int dtype, int feature_map, float eps,
+                       unsigned flags, void* workspace, size_t workspace_bytes, void* stream) {
+  return bwd_impl(q, k, v, dout, state, dq, dk, dv, B, H, N, d, dtype, feature_map, eps, flags, nullptr, workspace,
+                  workspace_bytes, stream);
+}
+
+int linfusion_attn_bwd_strided(const void* q, const void* k, const void* v, const void* dout, const float* state,
+                               void* dq, void* dk, void* dv, int B, int H, long long N, int d, int dtype,
+                               int feature_map, float eps, unsigned flags, const long long q_strides[3],
+                               const long long kv_strides[3], const long long dout_strides[3],
+                               const long long dq_strides[3], const long long dkv_strides[3], void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  const long long* const strides[5] = {q_strides, kv_strides, dout_strides, dq_strides, dkv_strides};
+  return bwd_impl(q, k, v, dout, state, dq, dk, dv, B, H, N, d, dtype, feature_map, eps, flags, strides, workspace,
+                  workspace_bytes, stream);
 }
 
 }  // extern "C"

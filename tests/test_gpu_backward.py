@@ -160,3 +160,65 @@ def test_backward_argument_checks():
     fo = [torch.empty_like(f) for _ in range(3)]
     assert lf.linfusion_attn_bwd(f, f, f, f, *fo, 0, 1e-6, 0, ws, check=False) == -2
     assert lf.linfusion_attn_bwd_workspace_bytes(1, 1, 64, 40, 0) == 0
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", [(2, 3, 33, 40, "f16"), (1, 8, 1000, 40, "f16"), (2, 5, 700, 64, "bf16"),
+                                            (1, 4, 515, 80, "f16"), (1, 2, 300, 24, "bf16"), (1, 10, 2049, 64, "f16")])
+def test_backward_on_token_major_views(B, H, N, d, dtype):
+    """All seven tensors in the UNet's [B, N, H*d] layout, handed over as strided [B, H, N, d] views: the oracle's
+    gradients, and bit for bit what the contiguous entry point gives on the same values."""
+    print(f"bwd token-major B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=70, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 70707, dtype, "cpu")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)   # [B, N, H, d] in memory
+    views = [tm(t) for t in (q, k, v, g)]
+    outs = [torch.full((B, N, H, d), float("nan"), dtype=q.dtype, device="cuda").permute(0, 2, 1, 3) for _ in range(3)]
+    code = wl.DTYPE_CODE[dtype]
+    ws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_bwd_strided(*views, *outs, 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    dense = _run(q, k, v, g)
+    for got, want in zip(outs, dense):
+        assert torch.equal(got.contiguous().view(torch.int16), want.view(torch.int16))
+    _check([o.contiguous() for o in outs], q, k, v, g, dtype, 0, 1e-6, True, "token-major")
+
+
+def test_backward_on_padded_and_mixed_layouts():
+    """q and dout padded to a longer row, k and v token-major, gradients written into padded rows whose padding
+    must stay untouched."""
+    B, H, N, d, dtype, pad = 1, 3, 450, 40, "f16", 24
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=71, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 71717, dtype, "cpu")
+
+    def padded(t, fill=float("nan")):
+        big = torch.full((B, H, N, d + pad), fill, dtype=t.dtype)
+        big[..., :d] = t
+        return big.cuda()
+    qb, gb = padded(q), padded(g)
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)
+    bigs = [torch.full((B, H, N, d + pad), 7.0, dtype=q.dtype, device="cuda") for _ in range(3)]
+    outs = [b[..., :d] for b in bigs]
+    ws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, 1), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_bwd_strided(qb[..., :d], tm(k), tm(v), gb[..., :d], *outs, 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    for b in bigs:
+        assert bool((b[..., d:] == 7.0).all()), "padding of a gradient row was written"
+    dense = _run(q, k, v, g)
+    for got, want in zip(outs, dense):
+        assert torch.equal(got.contiguous().view(torch.int16), want.view(torch.int16))
+
+
+def test_backward_strided_argument_checks():
+    B, H, N, d = 1, 2, 64, 40
+    q, k, v = (t.cuda() for t in wl.make_qkv(B, H, N, d, "f16", idx=72, device="cpu"))
+    g = torch.randn_like(q)
+    outs = [torch.empty_like(q) for _ in range(3)]
+    ws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, 1), dtype=torch.uint8, device="cuda")
+    call = lambda *a: lf.linfusion_attn_bwd_strided(*a, 0, 1e-6, 0, ws, check=False)
+    fused = torch.empty(B, N, 3, H, d, dtype=q.dtype, device="cuda")           # three gradients interleaved
+    inter = [fused[:, :, i].permute(0, 2, 1, 3) for i in range(3)]
+    assert call(q, k, v, g, *inter) == -7                                      # spans overlap: not accepted
+    bcast = torch.empty(B, 1, N, d, dtype=q.dtype, device="cuda").expand(B, H, N, d)
+    assert call(q, k, v, g, bcast, outs[1], outs[2]) == -7                     # a written view with stride 0
+    odd = torch.empty(B, H, N, d + 4, dtype=q.dtype, device="cuda")[..., :d]   # rows not 16-byte aligned
+    assert call(odd, k, v, g, *outs) == -3
