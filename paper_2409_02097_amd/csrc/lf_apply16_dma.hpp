@@ -249,10 +249,11 @@ struct ApplyDma {
     const u32x4* qp = Qh + tile * kTile * rs_q;
     unsigned char* sl = slot_ptr(slot);
 #pragma unroll
-    // Every lane issues every copy (no lane mask: a masked copy is a branch to the compiler, which may then
-    // duplicate or merge the masked instructions and change the number the wave issues -- the wait counts
-    // below are in instructions).  Lanes past the tile's chunks re-read a valid chunk and deposit it in the
-    // slot's padding (slots are whole 1 KiB deposits); rows past N re-read chunk 0 and are never stored.
+    // Every lane issues every copy, as straight-line code.  (A lane-masked copy is a branch to the compiler,
+    // which may sink two masked copies into one instruction whose scalar LDS base then depends on the lane --
+    // wrong deposits -- and which changes the number of instructions a wave issues, on which the wait counts
+    // below rely.)  Lanes past the tile's chunks re-read chunk 0 and deposit it in the slot's padding (slots
+    // are whole 1 KiB deposits); rows past N re-read chunk 0 and are never stored.
     for (int u = 0; u < NL; ++u) {
       const int c = trow[u] < lim ? qoff[u] : 0;
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
