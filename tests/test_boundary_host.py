@@ -156,3 +156,68 @@ def test_binding_refuses_cpu_tensors():
     x = torch.zeros(1, 1, 8, 8, dtype=torch.float16)
     with pytest.raises(ValueError):
         lf.linfusion_attn_fwd_ex(x, x, x, x.clone(), 0, 1e-6, 0, None)
+
+
+def _mlp(B=1, H=8, N=64, d=40, dtype=1, fm=0, eps=1e-6, ln_eps=1e-5, slope=0.01, flags=0, out=5 << 20, ws=64 << 20,
+         ws_bytes=4 << 20, a_q=1 << 20, gamma_q=48 << 20):
+    """Raw C call of linfusion_attn_fwd_mlp with fake device addresses (never dereferenced)."""
+    return lf.library().linfusion_attn_fwd_mlp(a_q, 2 << 20, 3 << 20, 4 << 20, 6 << 20, out, gamma_q, 49 << 20, 50 << 20,
+                                               51 << 20, B, H, N, d, dtype, fm, eps, ln_eps, slope, flags, ws, ws_bytes,
+                                               None, None)
+
+
+def test_mlp_fed_entry_validates_on_the_host():
+    import torch
+    ok = -6 if not torch.cuda.is_available() else None
+    if ok is not None:
+        assert _mlp() == ok and _mlp(H=4, d=80) == ok and _mlp(dtype=2, d=48) == ok
+    assert _mlp(a_q=None) == -1 and _mlp(gamma_q=None) == -1 and _mlp(out=None) == -1
+    assert _mlp(ln_eps=0.0) == -1 and _mlp(ln_eps=float("inf")) == -1 and _mlp(slope=-0.1) == -1 and _mlp(slope=2.0) == -1
+    assert _mlp(eps=-1.0) == -1 and _mlp(flags=2) == -1 and _mlp(B=0) == -1
+    assert _mlp(H=8, d=64) == -2 and _mlp(H=5) == -2 and _mlp(H=16) == -2 and _mlp(dtype=0) == -2 and _mlp(fm=9) == -2
+    assert _mlp(a_q=(1 << 20) + 8) == -3 and _mlp(gamma_q=(48 << 20) + 2) == -3
+    assert _mlp(ws=None) == -4 and _mlp(ws_bytes=1024) == -4
+    assert _mlp(out=1 << 20) == -7 and _mlp(ws=5 << 20) == -7
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 2097152, 40, 1) > 0
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 64, 56, 1) == 0
+
+
+def _qv(B=1, H=2, N=64, dk=80, dv=40, dtype=1, fm=0, eps=1e-6, flags=0, q=1 << 20, out=4 << 20, ws=64 << 20,
+        ws_bytes=4 << 20):
+    return lf.library().linfusion_attn_fwd_qv(q, 2 << 20, 3 << 20, out, B, H, N, dk, dv, dtype, fm, eps, flags, ws,
+                                              ws_bytes, None, None)
+
+
+def test_unequal_width_entry_validates_on_the_host():
+    import torch
+    ok = -6 if not torch.cuda.is_available() else None
+    if ok is not None:
+        assert _qv() == ok and _qv(dk=16, dv=64, dtype=2) == ok
+    assert _qv(q=None) == -1 and _qv(out=None) == -1 and _qv(N=0) == -1 and _qv(eps=float("nan")) == -1
+    assert _qv(flags=4) == -1
+    assert _qv(dk=40, dv=40) == -2 and _qv(dk=24) == -2 and _qv(dv=48) == -2 and _qv(dtype=0) == -2 and _qv(fm=3) == -2
+    assert _qv(q=(1 << 20) + 4) == -3
+    assert _qv(ws=None) == -4 and _qv(ws_bytes=64) == -4
+    assert _qv(out=3 << 20) == -7 and _qv(ws=4 << 20) == -7
+    # q and k are d_qk wide: an out placed right behind v's span but inside q's is caught with the right widths
+    assert _qv(q=1 << 20, out=(1 << 20) + 64 * 2 * 80 * 2 - 16) == -7
+    assert lf.linfusion_attn_qv_workspace_bytes(2, 8, 4096, 80, 40, 1) > 0
+
+
+def _bwds(strides=(None,) * 5, B=1, H=2, N=64, d=40, dq=5 << 20, dk=6 << 20, dv=7 << 20, ws=64 << 20, ws_bytes=4 << 20):
+    arr = lambda s: None if s is None else ctypes.byref((ctypes.c_longlong * 3)(*s))
+    return lf.library().linfusion_attn_bwd_strided(1 << 20, 2 << 20, 3 << 20, 4 << 20, None, dq, dk, dv, B, H, N, d, 1, 0,
+                                                   1e-6, 0, *[arr(s) for s in strides], ws, ws_bytes, None)
+
+
+def test_strided_backward_validates_on_the_host():
+    import torch
+    ok = -6 if not torch.cuda.is_available() else None
+    dense, tm = (2 * 64 * 40, 64 * 40, 40), (64 * 2 * 40, 40, 2 * 40)
+    if ok is not None:
+        assert _bwds() == ok and _bwds((tm,) * 5) == ok and _bwds((dense, tm, dense, tm, dense)) == ok
+    assert _bwds((dense, dense, dense, (2 * 64 * 40, 64 * 40, 44), dense)) == -3        # dq rows not 16-byte aligned
+    assert _bwds((dense, dense, dense, (2 * 64 * 40, 0, 40), dense)) == -7              # dq heads on top of each other
+    assert _bwds((dense, (2 * 64 * 40, 0, 40), dense, dense, dense)) in (-6, ok)        # inputs may repeat
+    assert _bwds(dk=5 << 20) == -7 and _bwds(dq=1 << 20) == -7 and _bwds(ws=7 << 20) == -7
+    assert _bwds(ws_bytes=128) == -4
