@@ -1,6 +1,8 @@
 // Small host-side helpers that linfusion.hip shares with the library's other translation units.
 #pragma once
+#include <hip/hip_runtime.h>
 #include <stddef.h>
+#include <stdint.h>
 
 namespace lfh {
 
@@ -15,5 +17,23 @@ int env_int(const char* name, int dflt);
 // first to one past the last element the view touches.
 int check_strides(const long long s[3], int B, int H, long long N, int d, size_t esz, bool written);
 size_t span_bytes(const long long s[3], int B, int H, long long N, int d, size_t esz);
+
+// true when the byte ranges [a, a + na) and [b, b + nb) share a byte
+inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+// Workgroups may use up to 160 KiB of LDS on this device; above 64 KiB the kernel has to be told (per kernel; cheap).
+template <typename KernelT>
+inline bool allow_lds(KernelT kernel, int bytes) {
+  if (bytes <= 65536) return true;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
+      hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
 
 }  // namespace lfh

@@ -222,10 +222,7 @@ int check_device() {
   return g_dev_ok[dev] == 1 ? LINFUSION_OK : LINFUSION_ERR_DEVICE;
 }
 
-bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
-  uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
-  return x < y + nb && y < x + na;
-}
+using lfh::overlaps;
 
 unsigned next_ticket() {
   unsigned t = g_ticket.fetch_add(1, std::memory_order_relaxed);
@@ -245,17 +242,7 @@ bool fits_resident(KernelT kernel, size_t lds, long long grid) {
   return (long long)per_cu * kNumCU >= grid;
 }
 
-// Workgroups may use up to 160 KiB of LDS on this device; above 64 KiB the kernel has to be told once.
-template <typename KernelT>
-bool allow_lds(KernelT kernel, int bytes) {
-  if (bytes <= 65536) return true;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
-      hipSuccess) {
-    (void)hipGetLastError();
-    return false;
-  }
-  return true;
-}
+using lfh::allow_lds;
 
 // The single-launch kernel's barriers compare flags against a ticket that is new for every call; a captured
 // launch would replay an old ticket (its flags already match), so under stream capture the three-kernel path runs.

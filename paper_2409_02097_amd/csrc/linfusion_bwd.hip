@@ -58,16 +58,7 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   return LINFUSION_OK;
 }
 
-template <typename KernelT>
-bool allow_lds(KernelT kernel, int bytes) {
-  if (bytes <= 65536) return true;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
-      hipSuccess) {
-    (void)hipGetLastError();
-    return false;
-  }
-  return true;
-}
+using lfh::allow_lds;
 
 struct BwdArgs {
   const float* saved_state;   // the forward state of the same q, k, v, or null: recompute it from k, v
@@ -159,10 +150,7 @@ int dispatch_bwd(int d, int dtype, int fm, const BwdArgs& a) {
   return LINFUSION_ERR_UNSUPPORTED;
 }
 
-bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
-  uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
-  return x < y + nb && y < x + na;
-}
+using lfh::overlaps;
 
 }  // namespace
 

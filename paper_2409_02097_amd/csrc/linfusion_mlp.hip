@@ -67,16 +67,7 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
   return LINFUSION_OK;
 }
 
-template <typename KernelT>
-bool allow_lds(KernelT kernel, int bytes) {
-  if (bytes <= 65536) return true;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
-      hipSuccess) {
-    (void)hipGetLastError();
-    return false;
-  }
-  return true;
-}
+using lfh::allow_lds;
 
 struct MlpArgs {
   const void *a_q, *t_q, *a_k, *t_k, *v;
@@ -161,10 +152,7 @@ int dispatch_mlp(int H, int d, int dtype, const MlpArgs& a) {
   return LINFUSION_ERR_UNSUPPORTED;
 }
 
-bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
-  uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
-  return x < y + nb && y < x + na;
-}
+using lfh::overlaps;
 
 }  // namespace
 

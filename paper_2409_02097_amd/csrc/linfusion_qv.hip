@@ -57,16 +57,7 @@ int make_qv_plan(int B, int H, long long N, int dk, int dv, int dtype, QvPlan* p
   return LINFUSION_OK;
 }
 
-template <typename KernelT>
-bool allow_lds(KernelT kernel, int bytes) {
-  if (bytes <= 65536) return true;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
-      hipSuccess) {
-    (void)hipGetLastError();
-    return false;
-  }
-  return true;
-}
+using lfh::allow_lds;
 
 struct QvArgs {
   const void *q, *k, *v;
@@ -127,10 +118,7 @@ int dispatch_qv(int dk, int dv, int dtype, const QvArgs& a) {
   return LINFUSION_ERR_UNSUPPORTED;
 }
 
-bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
-  uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
-  return x < y + nb && y < x + na;
-}
+using lfh::overlaps;
 
 }  // namespace
 

@@ -3,22 +3,14 @@
 #include "../../include/linfusion.h"
 
 #include "lf_wide16.hpp"
+#include "lf_host_api.hpp"
 #include "lf_wide_api.hpp"
 
 namespace lfw {
 
 namespace {
 
-template <typename KernelT>
-bool allow_lds(KernelT kernel, int bytes) {
-  if (bytes <= 65536) return true;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes) !=
-      hipSuccess) {
-    (void)hipGetLastError();
-    return false;
-  }
-  return true;
-}
+using lfh::allow_lds;
 
 template <typename T, int D>
 int run(const WideArgs& a) {
