@@ -82,3 +82,44 @@ def test_rejected_arguments():
     assert call(q, k, v, out, 0, 1e-6, 0, ws[:64]) == -4
     assert call(q, k, v, v, 0, 1e-6, 0, ws) == -7
     assert call(q, k, v, out, 5, 1e-6, 0, ws) == -2
+
+
+def test_unequal_widths_and_backward_recorded_into_graphs_replay_correctly():
+    """linfusion_attn_fwd_qv and linfusion_attn_bwd enqueue kernels only: captured once, replayed with new inputs
+    in the same buffers, every replay must equal an eager call bit for bit."""
+    B, H, N, dk, dv, dtype = 1, 4, 1500, 80, 40, "f16"
+    q, k, v = (t.cuda() for t in wl.make_qkv_widths(B, H, N, dk, dv, dtype, idx=95))
+    out = torch.zeros_like(v)
+    ws = torch.empty(lf.linfusion_attn_qv_workspace_bytes(B, H, N, dk, dv, 1), dtype=torch.uint8, device="cuda")
+    q2, k2, v2 = (t.cuda() for t in wl.make_qkv(B, H, N, dv, dtype, idx=96, device="cpu"))
+    g2 = torch.randn_like(q2)
+    grads = [torch.zeros_like(q2) for _ in range(3)]
+    bws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, dv, 1), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                    # warm-up outside the capture
+        lf.linfusion_attn_fwd_qv(q, k, v, out, 0, 1e-6, 0, ws, stream=side)
+        lf.linfusion_attn_bwd(q2, k2, v2, g2, *grads, 0, 1e-6, 0, bws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cur = torch.cuda.current_stream()
+        lf.linfusion_attn_fwd_qv(q, k, v, out, 0, 1e-6, 0, ws, stream=cur)
+        lf.linfusion_attn_bwd(q2, k2, v2, g2, *grads, 0, 1e-6, 0, bws, stream=cur)
+    for rep in range(3):
+        for t in (q, k, v, q2, k2, v2, g2):
+            t.copy_(torch.randn(t.shape, device="cuda").to(t.dtype))
+        out.fill_(float("nan"))
+        for gr in grads:
+            gr.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        e_out = torch.empty_like(out)
+        e_grads = [torch.empty_like(q2) for _ in range(3)]
+        lf.linfusion_attn_fwd_qv(q, k, v, e_out, 0, 1e-6, 0, torch.empty_like(ws))
+        lf.linfusion_attn_bwd(q2, k2, v2, g2, *e_grads, 0, 1e-6, 0, torch.empty_like(bws))
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), e_out.view(torch.int16)), f"forward replay {rep}"
+        for a, b in zip(grads, e_grads):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"backward replay {rep}"
