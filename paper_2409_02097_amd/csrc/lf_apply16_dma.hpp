@@ -462,8 +462,8 @@ struct ApplyDma {
   LF_DEV void compute_tile(int slot) {
     // ---- this lane's token row -> phi -> 16-bit B operands ----------------------------------------
     u32x4 Bh[KS], Bl[KS];
-    float tv[MLP ? KS * 8 : 1];
-    float mu = 0.0f, rstd = 0.0f;
+    u32x4 traw[MLP ? KS : 1];      // MLP: this lane's chunks of t, raw
+    float rstd = 0.0f, cn = 0.0f;   // MLP: LayerNorm(t) = t * rstd + cn
     if constexpr (MLP) {
       // ---- LayerNorm statistics of this lane's token over all W D channels: sums of (t - pivot) and of its
       //      square, the pivot being the token's channel 0 (the same for all lanes of the token, so the
@@ -478,6 +478,7 @@ struct ApplyDma {
         const bool ok = kg * KS + s < CPR;
         u32x4 raw = u32x4{0, 0, 0, 0};
         if (ok) raw = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, kg * KS + s) + kTOffset);
+        traw[s] = raw;
         if constexpr (NS == 1) {
           // fp16: for the two sums the difference is taken in packed half precision (its rounding is relative
           // to the deviation and averages out) and accumulated by the mixed-precision dot product
@@ -486,10 +487,7 @@ struct ApplyDma {
 #pragma unroll
           for (int w = 0; w < 4; ++w) {
             const uint32_t word = raw[w];   // (by value: a bit cast applied to the vector element itself reads element 0)
-            const f16x2 tt = __builtin_bit_cast(f16x2, word);
-            const f16x2 dd = tt + np;                      // feeds the statistics only
-            tv[s * 8 + 2 * w] = (float)tt[0] - pivot;
-            tv[s * 8 + 2 * w + 1] = (float)tt[1] - pivot;
+            const f16x2 dd = __builtin_bit_cast(f16x2, word) + np;   // feeds the statistics only
             if (ok) {
               s1 = __builtin_amdgcn_fdot2(dd, one, s1, false);
               s2 = __builtin_amdgcn_fdot2(dd, dd, s2, false);
@@ -502,8 +500,6 @@ struct ApplyDma {
             unpack2<T>(raw[w], t0, t1);
             t0 -= pivot;
             t1 -= pivot;
-            tv[s * 8 + 2 * w] = t0;
-            tv[s * 8 + 2 * w + 1] = t1;
             if (ok) {
               s1 += t0 + t1;
               s2 = __builtin_fmaf(t0, t0, __builtin_fmaf(t1, t1, s2));
@@ -522,9 +518,10 @@ struct ApplyDma {
         s1 += pp[0];
         s2 += pp[1];
       }
-      mu = s1 * (1.0f / (float)(W * D));                       // mean of t - pivot, which is what tv holds
+      const float mu = s1 * (1.0f / (float)(W * D));           // mean of t - pivot
       const float var = fmaxf(__builtin_fmaf(-mu, mu, s2 * (1.0f / (float)(W * D))), 0.0f);
       rstd = __builtin_amdgcn_rsqf(var + ln_eps);
+      cn = -(pivot + mu) * rstd;
     }
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -537,8 +534,10 @@ struct ApplyDma {
         float x0, x1;
         unpack2<T>(raw[w], x0, x1);
         if constexpr (MLP) {
-          float y0 = __builtin_fmaf(gam[s * 8 + 2 * w] * rstd, tv[s * 8 + 2 * w] - mu, bet[s * 8 + 2 * w]);
-          float y1 = __builtin_fmaf(gam[s * 8 + 2 * w + 1] * rstd, tv[s * 8 + 2 * w + 1] - mu, bet[s * 8 + 2 * w + 1]);
+          float t0, t1;
+          unpack2<T>(traw[s][w], t0, t1);
+          const float y0 = __builtin_fmaf(gam[s * 8 + 2 * w], __builtin_fmaf(t0, rstd, cn), bet[s * 8 + 2 * w]);
+          const float y1 = __builtin_fmaf(gam[s * 8 + 2 * w + 1], __builtin_fmaf(t1, rstd, cn), bet[s * 8 + 2 * w + 1]);
           x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
           x1 += fmaxf(y1, slope * y1);
         }

@@ -16,7 +16,7 @@ template <typename T, int D, int W> struct ReduceMlpCfg {
   using Base = ReduceRowsCfg<T, D, W>;
   static constexpr int kPartOffset = Base::kLdsBytes;                     // (mean, M2) of every 8-channel chunk
   static constexpr int kPartBytes = kTile * Base::kPiece * 8;
-  static constexpr int kRowOffset = kPartOffset + kPartBytes;             // (mean, rstd) of every token row
+  static constexpr int kRowOffset = kPartOffset + kPartBytes;             // (rstd, -mean * rstd) of every token row
   static constexpr int kAffineOffset = kRowOffset + kTile * 8;             // gamma[C] then beta[C], fp32
   static constexpr int kLdsBytes = kAffineOffset + 2 * W * D * 4;
   static constexpr int kTPR = Base::kThreadsW / kTile;                    // threads that reduce one row
@@ -189,7 +189,10 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
       }
 #pragma unroll
       for (int o = TPR / 2; o > 0; o >>= 1) m2 += __shfl_xor(m2, o);
-      if (ssub == 0) rowstat[srow] = f32x2{mu, __builtin_amdgcn_rsqf(m2 * (1.0f / (float)(8 * PC)) + ln_eps)};
+      if (ssub == 0) {
+        const float rstd = __builtin_amdgcn_rsqf(m2 * (1.0f / (float)(8 * PC)) + ln_eps);
+        rowstat[srow] = f32x2{rstd, -mu * rstd};
+      }
     }
     lds_barrier();
     // ---- k = a + LeakyReLU(LayerNorm(t)) -> phi -> 16-bit (hi [, lo]) -> the owning head's tiles ; V ----
@@ -197,7 +200,7 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
     for (int u = 0; u < NL; ++u) {
       if (u * NT + tid < Cfg::kChunks) {
         const bool ok = trow[u] < lim;
-        const f32x2 rsd = rowstat[ok ? trow[u] : 0];
+        const f32x2 rsd = rowstat[ok ? trow[u] : 0];   // {rstd, -mean * rstd}: LayerNorm(t) = t * rsd[0] + rsd[1]
         u32x4 ph, pl;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -206,8 +209,8 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
           unpack2<T>(tr[u][w], t0, t1);
           const f32x2 gg = *reinterpret_cast<const f32x2*>(affine + coff[u] + 2 * w);
           const f32x2 bb = *reinterpret_cast<const f32x2*>(affine + W * D + coff[u] + 2 * w);
-          const float y0 = __builtin_fmaf(gg[0] * rsd[1], t0 - rsd[0], bb[0]);
-          const float y1 = __builtin_fmaf(gg[1] * rsd[1], t1 - rsd[0], bb[1]);
+          const float y0 = __builtin_fmaf(gg[0], __builtin_fmaf(t0, rsd[0], rsd[1]), bb[0]);
+          const float y1 = __builtin_fmaf(gg[1], __builtin_fmaf(t1, rsd[0], rsd[1]), bb[1]);
           x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
           x1 += fmaxf(y1, slope * y1);
           float p0 = ok ? phi<FM>(x0) : 0.0f;
