@@ -173,8 +173,15 @@ struct ApplyDma {
         const int r = P / PC;
         int c = P % PC - rot(r);
         if (c < 0) c += PC;
-        trow[u] = (u * 64 + lane < Cfg::kChunks) ? r : kTile;   // lanes past the region: never a valid row
-        qoff[u] = r * rs_q + c;
+        // lanes past the region's chunks copy what the lane 32 below copies (same cache lines, no extra request:
+        // re-reading one fixed chunk instead measured 5 % slower) and deposit it in the padding; never stored
+        static_assert(Cfg::kChunks % 32 == 0, "a region is whole half-waves of chunks");
+        const int Pc = (u * 64 + lane < Cfg::kChunks) ? P : P - 32;
+        const int rc = Pc / PC;
+        int cc = Pc % PC - rot(rc);
+        if (cc < 0) cc += PC;
+        trow[u] = rc;
+        qoff[u] = rc * rs_q + cc;
         const int cs = P % PC;               // store side: this lane takes chunk cs of row r ...
         int pos = cs + rot(r);               // ... which sits at this rotated position of the row piece
         if (pos >= PC) pos -= PC;

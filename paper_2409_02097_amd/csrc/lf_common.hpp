@@ -187,6 +187,14 @@ template <typename T> struct NSplit;                 // operand levels needed to
 template <> struct NSplit<F16> { static constexpr int value = 1; };
 template <> struct NSplit<BF16> { static constexpr int value = 2; };
 
+// Bit pattern of the most negative finite value of the storage type.  Rows past the end of a head are given this
+// value instead of a per-element mask: elu(x)+1 and relu map it to exactly 0 (exp underflows), so such rows add
+// nothing to the state; only the identity map (a test aid) still needs the mask.
+template <typename T> struct LowestBits;
+template <> struct LowestBits<F16> { static constexpr uint32_t value = 0xFBFFFBFFu; };    // -65504
+template <> struct LowestBits<BF16> { static constexpr uint32_t value = 0xFF7FFF7Fu; };   // -3.39e38
+template <int FM> constexpr bool kPhiKillsLowest = FM != kPhiIdentity;
+
 template <typename T> struct OneBits;                // bit pattern of 1.0 in the storage type
 template <> struct OneBits<F16> { static constexpr uint16_t value = 0x3C00; };
 template <> struct OneBits<BF16> { static constexpr uint16_t value = 0x3F80; };

@@ -102,7 +102,7 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
         tr[u] = ld_stream(Tg + at);
         vr[u] = ld_stream(Vg + at);
       } else {
-        ar[u] = u32x4{0, 0, 0, 0};
+        ar[u] = u32x4{LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value};   // stays hugely negative after the branch sum: phi maps it to 0
         tr[u] = u32x4{0, 0, 0, 0};
         vr[u] = u32x4{0, 0, 0, 0};
       }
@@ -213,8 +213,11 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
           const float y1 = __builtin_fmaf(gg[1], __builtin_fmaf(t1, rsd[0], rsd[1]), bb[1]);
           x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
           x1 += fmaxf(y1, slope * y1);
-          float p0 = ok ? phi<FM>(x0) : 0.0f;
-          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          float p0 = phi<FM>(x0), p1 = phi<FM>(x1);
+          if constexpr (!kPhiKillsLowest<FM>) {
+            p0 = ok ? p0 : 0.0f;
+            p1 = ok ? p1 : 0.0f;
+          }
           if constexpr (NS == 1) {
             ph[w] = pack2<T>(p0, p1);
           } else {

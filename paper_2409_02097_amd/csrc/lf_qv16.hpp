@@ -83,7 +83,8 @@ state_reduce16_qv(const u32x4* __restrict__ K, const u32x4* __restrict__ V, floa
     const u32x4* vp = Vh + tile * kTile * CPRV;
 #pragma unroll
     for (int u = 0; u < NLK; ++u)
-      kr[u] = (u * 64 + lane < CK::kChunks && rowk[u] < lim) ? ld_stream(kp + u * 64 + lane) : u32x4{0, 0, 0, 0};
+      kr[u] = (u * 64 + lane < CK::kChunks && rowk[u] < lim) ? ld_stream(kp + u * 64 + lane)
+                                                             : u32x4{LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value};   // phi maps it to 0
 #pragma unroll
     for (int u = 0; u < NLV; ++u)
       vr[u] = (u * 64 + lane < CV::kChunks && rowv[u] < lim) ? ld_stream(vp + u * 64 + lane) : u32x4{0, 0, 0, 0};
@@ -111,8 +112,11 @@ state_reduce16_qv(const u32x4* __restrict__ K, const u32x4* __restrict__ V, floa
         for (int w = 0; w < 4; ++w) {
           float x0, x1;
           unpack2<T>(kr[u][w], x0, x1);
-          float p0 = ok ? phi<FM>(x0) : 0.0f;
-          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          float p0 = phi<FM>(x0), p1 = phi<FM>(x1);
+          if constexpr (!kPhiKillsLowest<FM>) {
+            p0 = ok ? p0 : 0.0f;
+            p1 = ok ? p1 : 0.0f;
+          }
           if constexpr (NS == 1) {
             ph[w] = pack2<T>(p0, p1);
           } else {

@@ -102,7 +102,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
         kr[u] = ld_stream(kp + goff[u]);
         vr[u] = ld_stream(vp + goff[u]);
       } else {
-        kr[u] = u32x4{0, 0, 0, 0};
+        kr[u] = u32x4{LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value};   // phi maps it to 0
         vr[u] = u32x4{0, 0, 0, 0};
       }
     }
@@ -132,8 +132,11 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
         for (int w = 0; w < 4; ++w) {
           float x0, x1;
           unpack2<T>(kr[u][w], x0, x1);
-          float p0 = ok ? phi<FM>(x0) : 0.0f;
-          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          float p0 = phi<FM>(x0), p1 = phi<FM>(x1);
+          if constexpr (!kPhiKillsLowest<FM>) {
+            p0 = ok ? p0 : 0.0f;
+            p1 = ok ? p1 : 0.0f;
+          }
           if constexpr (NS == 1) {
             ph[w] = pack2<T>(p0, p1);
           } else {
@@ -315,7 +318,7 @@ state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
         kr[u] = ld_stream(kp + goff[u]);
         vr[u] = ld_stream(vp + goff[u]);
       } else {
-        kr[u] = u32x4{0, 0, 0, 0};
+        kr[u] = u32x4{LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value};   // phi maps it to 0
         vr[u] = u32x4{0, 0, 0, 0};
       }
     }
@@ -346,8 +349,11 @@ state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
         for (int w = 0; w < 4; ++w) {
           float x0, x1;
           unpack2<T>(kr[u][w], x0, x1);
-          float p0 = ok ? phi<FM>(x0) : 0.0f;
-          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          float p0 = phi<FM>(x0), p1 = phi<FM>(x1);
+          if constexpr (!kPhiKillsLowest<FM>) {
+            p0 = ok ? p0 : 0.0f;
+            p1 = ok ? p1 : 0.0f;
+          }
           if constexpr (NS == 1) {
             ph[w] = pack2<T>(p0, p1);
           } else {

@@ -118,7 +118,7 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
         kr[u] = ld_stream(kp + goff[u]);
         vr[u] = ld_stream(vp + goff[u]);
       } else {
-        kr[u] = u32x4{0, 0, 0, 0};
+        kr[u] = u32x4{LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value};   // phi maps it to 0
         vr[u] = u32x4{0, 0, 0, 0};
       }
     }
@@ -142,8 +142,11 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
         for (int w = 0; w < 4; ++w) {
           float x0, x1;
           unpack2<T>(kr[u][w], x0, x1);
-          float p0 = ok ? phi<FM>(x0) : 0.0f;
-          float p1 = ok ? phi<FM>(x1) : 0.0f;
+          float p0 = phi<FM>(x0), p1 = phi<FM>(x1);
+          if constexpr (!kPhiKillsLowest<FM>) {
+            p0 = ok ? p0 : 0.0f;
+            p1 = ok ? p1 : 0.0f;
+          }
           if constexpr (NS == 1) {
             ph[w] = pack2<T>(p0, p1);
           } else {
@@ -346,12 +349,18 @@ struct ApplyWide {
     for (int u = 0; u < NL; ++u) {
       const int P = wave * Sw::kRegionChunks + u * 64 + lane;   // position in the tile
       const int r = P / CPR, pos = P % CPR;
-      int c = pos - Sw::rot(r);                // copy side: position pos of row r receives chunk c
-      if (c < 0) c += CPR;
       int spos = pos + Sw::rot(r);             // store side: this lane sends chunk pos, found at spos
       if (spos >= CPR) spos -= CPR;
-      trow[u] = (u * 64 + lane < Sw::kRegionChunks) ? r : kTile;   // lanes past the region: never a valid row
-      qoff[u] = r * rs_q + c;
+      // copy side: position pos of row r receives chunk c; lanes past the region's chunks copy what the lane 32
+      // below copies (same cache lines) and deposit it in the padding
+      const int li = u * 64 + lane;            // chunk index inside the region; past its end: a valid stand-in
+      const int lc = li < Sw::kRegionChunks ? li : (li - 32 < Sw::kRegionChunks ? li - 32 : li % Sw::kRegionChunks);
+      const int Pc = wave * Sw::kRegionChunks + lc;
+      const int rc = Pc / CPR;
+      int c = Pc % CPR - Sw::rot(rc);
+      if (c < 0) c += CPR;
+      trow[u] = rc;
+      qoff[u] = rc * rs_q + c;
       ooff[u] = r * rs_o + pos;
       soff[u] = ((r % RPR) * CPR + spos) * 16;
     }
