@@ -243,6 +243,28 @@ int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, co
                            int dtype, int feature_map, float eps, float ln_eps, float slope, unsigned flags,
                            void* workspace, size_t workspace_bytes, void* stream, void* events[4]);
 
+/*
+ * linfusion_attn_fwd_mlp on strided token rows (Sec. 4.1: the five branch results are usually column blocks of
+ * one projection's output, [B, N, 5 C] say, and need no copy to become dense).
+ *   in_strides      HOST array {batch, token}: element strides shared by a_q, t_q, a_k, t_k and v, whose
+ *                   [b][n] row is C = H * d contiguous elements at base + b * batch + n * token.
+ *   out_strides     HOST array {batch, token} of out; rows must not intersect (token >= C, batch >=
+ *                   (N - 1) * token + C, else LINFUSION_ERR_OVERLAP).
+ * Strides are multiples of 8 elements (16 bytes; else LINFUSION_ERR_MISALIGNED), non-negative, token >= C for
+ * the inputs, token < 2^27 and the spanned extent below 2^45 elements (else LINFUSION_ERR_INVALID).  The inputs
+ * may interleave in one buffer; the extent out spans must not overlap the extent any input spans.  Either
+ * array NULL = dense [B, N, C].  Everything else, the workspace size included, as linfusion_attn_fwd_mlp, whose
+ * results this call reproduces bit for bit on the same values.
+ */
+int linfusion_attn_fwd_mlp_strided(const void* a_q, const void* t_q, const void* a_k, const void* t_k, const void* v,
+                                   void* out,
+                                   const float* gamma_q, const float* beta_q, const float* gamma_k,
+                                   const float* beta_k,
+                                   int B, int H, long long N, int d,
+                                   int dtype, int feature_map, float eps, float ln_eps, float slope, unsigned flags,
+                                   const long long in_strides[2], const long long out_strides[2],
+                                   void* workspace, size_t workspace_bytes, void* stream, void* events[4]);
+
 /* Bytes of device scratch linfusion_attn_fwd_mlp needs; pure host function; 0 for rejected arguments. */
 size_t linfusion_attn_mlp_workspace_bytes(int B, int H, long long N, int d, int dtype);
 

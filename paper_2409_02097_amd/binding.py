@@ -62,6 +62,11 @@ def library() -> ctypes.CDLL:
     lib.linfusion_attn_fwd_mlp.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32,
                                            f32, f32, u32, vp, sz, vp, ctypes.POINTER(ctypes.c_void_p * 4)]
     lib.linfusion_attn_fwd_mlp.restype = i32
+    st2 = ctypes.POINTER(ctypes.c_longlong * 2)
+    lib.linfusion_attn_fwd_mlp_strided.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i64, i32, i32, i32,
+                                                   f32, f32, f32, u32, st2, st2, vp, sz, vp,
+                                                   ctypes.POINTER(ctypes.c_void_p * 4)]
+    lib.linfusion_attn_fwd_mlp_strided.restype = i32
     lib.linfusion_attn_mlp_workspace_bytes.argtypes = [i32, i32, i64, i32, i32]
     lib.linfusion_attn_mlp_workspace_bytes.restype = sz
     lib.linfusion_attn_fwd_qv.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, i32, f32, u32, vp, sz, vp,
@@ -222,6 +227,42 @@ def linfusion_attn_fwd_mlp(a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k,
                                           if events is not None else None)
     if check and rc != 0:
         raise LinFusionError(rc, "linfusion_attn_fwd_mlp")
+    return rc
+
+
+def linfusion_attn_fwd_mlp_strided(a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, H: int,
+                                   feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6, ln_eps: float = 1e-5,
+                                   slope: float = 0.01, flags: int = FLAG_NONE, workspace=None, stream=None,
+                                   events=None, check: bool = True) -> int:
+    """linfusion_attn_fwd_mlp on [B, N, H*d] views with contiguous channels, e.g. column blocks of one wider
+    [B, N, 5 H d] tensor; the five inputs must share their strides."""
+    import torch
+    ins = (a_q, t_q, a_k, t_k, v)
+    for t in ins + (out,):
+        if (t.dim() != 3 or t.shape != a_q.shape or t.dtype != a_q.dtype or t.device != a_q.device
+                or (t.shape[2] > 1 and t.stride(2) != 1)):
+            raise ValueError("a_q, t_q, a_k, t_k, v, out must be [B, N, H*d] views of one dtype and device with "
+                             "contiguous channels")
+    if any(t.stride() != a_q.stride() for t in ins):
+        raise ValueError("a_q, t_q, a_k, t_k and v must share their strides")
+    B, N, C = a_q.shape
+    if C % H:
+        raise ValueError("the channel count must be a multiple of H")
+    for g in (gamma_q, beta_q, gamma_k, beta_k):
+        if g.dtype != torch.float32 or g.numel() != C or not g.is_contiguous() or g.device != a_q.device:
+            raise ValueError("gamma / beta must be contiguous fp32 vectors of H*d values on the tensors' device")
+    sin = (ctypes.c_longlong * 2)(a_q.stride(0), a_q.stride(1))
+    sout = (ctypes.c_longlong * 2)(out.stride(0), out.stride(1))
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = library().linfusion_attn_fwd_mlp_strided(
+        a_q.data_ptr(), t_q.data_ptr(), a_k.data_ptr(), t_k.data_ptr(), v.data_ptr(), out.data_ptr(),
+        gamma_q.data_ptr(), beta_q.data_ptr(), gamma_k.data_ptr(), beta_k.data_ptr(), B, H, N, C // H,
+        _dtype_code(a_q), feature_map, eps, ln_eps, slope, flags, ctypes.byref(sin), ctypes.byref(sout), ws_ptr,
+        ws_bytes, _stream_ptr(stream),
+        ctypes.byref((ctypes.c_void_p * 4)(*[ctypes.c_void_p(int(e)) for e in events])) if events is not None else None)
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_fwd_mlp_strided")
     return rc
 
 

@@ -82,6 +82,7 @@ struct MlpArgs {
   unsigned char* ws;
   hipStream_t st;
   hipEvent_t* ev;
+  long long in_batch, in_row, out_batch, out_row;   // strides in 16-byte units: the five inputs; out
 };
 
 template <typename T, int D, int W, int FM, bool NORM>
@@ -90,8 +91,8 @@ int run_mlp(const MlpArgs& a) {
   const MlpPlan& p = *a.p;
   constexpr int NE = D * D + D;
   static_assert(W * D % 8 == 0, "rows are whole 16-byte chunks");
-  const int row = W * D / 8;                               // token stride in 16-byte units
-  const long long batch = a.N * row;
+  const int row = (int)a.in_row, row_o = (int)a.out_row;   // token strides in 16-byte units (W D / 8 when dense)
+  const long long batch = a.in_batch, batch_o = a.out_batch;
   float* partials = reinterpret_cast<float*>(a.ws);
   float* state = reinterpret_cast<float*>(a.ws + p.ws_partials);
   unsigned char* packed = a.ws + p.ws_partials + p.ws_state;
@@ -115,7 +116,7 @@ int run_mlp(const MlpArgs& a) {
   pack_state16<T, D, NORM><<<dim3((unsigned)(a.B * W)), dim3(kThreads), lds_p, st>>>(state, packed);
   if (a.ev) (void)hipEventRecord(a.ev[2], st);
   apply16_mlp<T, D, FM, NORM, W><<<dim3(p.apply_wgs, (unsigned)a.B), dim3(64 * W), lds_a, st>>>(
-      (const u32x4*)a.a_q, (const u32x4*)a.t_q, batch, row, (u32x4*)a.out, batch, row, a.gamma_q, a.beta_q, a.ln_eps,
+      (const u32x4*)a.a_q, (const u32x4*)a.t_q, batch, row, (u32x4*)a.out, batch_o, row_o, a.gamma_q, a.beta_q, a.ln_eps,
       a.slope, packed, a.eps, a.N, p.blk_apply);
   if (a.ev) (void)hipEventRecord(a.ev[3], st);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
@@ -164,10 +165,12 @@ size_t linfusion_attn_mlp_workspace_bytes(int B, int H, long long N, int d, int 
   return p.ws_total;
 }
 
-int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, const void* t_k, const void* v, void* out,
-                           const float* gamma_q, const float* beta_q, const float* gamma_k, const float* beta_k, int B,
-                           int H, long long N, int d, int dtype, int feature_map, float eps, float ln_eps, float slope,
-                           unsigned flags, void* workspace, size_t workspace_bytes, void* stream, void* events[4]) {
+// `sin`, `sout`: element strides {batch, token} of the five inputs (shared) and of out; null = dense [B, N, H*d]
+static int mlp_impl(const void* a_q, const void* t_q, const void* a_k, const void* t_k, const void* v, void* out,
+                    const float* gamma_q, const float* beta_q, const float* gamma_k, const float* beta_k, int B, int H,
+                    long long N, int d, int dtype, int feature_map, float eps, float ln_eps, float slope, unsigned flags,
+                    const long long* sin, const long long* sout, void* workspace, size_t workspace_bytes, void* stream,
+                    void* events[4]) {
   if (!a_q || !t_q || !a_k || !t_k || !v || !out || !gamma_q || !beta_q || !gamma_k || !beta_k)
     return LINFUSION_ERR_INVALID;
   if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
@@ -185,11 +188,27 @@ int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, co
   const float* vecs[4] = {gamma_q, beta_q, gamma_k, beta_k};
   for (const float* x : vecs)
     if ((uintptr_t)x & 3) return LINFUSION_ERR_MISALIGNED;
-  const size_t tbytes = (size_t)B * H * (size_t)N * d * 2, vbytes = (size_t)H * d * sizeof(float);
+  const long long C = (long long)H * d;
+  const long long dense[2] = {N * C, C};
+  const long long* si = sin ? sin : dense;
+  const long long* so = sout ? sout : dense;
+  for (const long long* st2 : {si, so}) {
+    if (st2[0] < 0 || st2[1] < 0) return LINFUSION_ERR_INVALID;
+    if (st2[0] % 8 || st2[1] % 8) return LINFUSION_ERR_MISALIGNED;          // 16-byte aligned rows
+    if (st2[1] / 8 >= (1LL << 24)) return LINFUSION_ERR_INVALID;            // 32 rows * stride stays in int
+    if ((long double)(B - 1) * st2[0] + (long double)(N - 1) * st2[1] + C >= (long double)(1LL << 45))
+      return LINFUSION_ERR_INVALID;
+  }
+  if (si[1] < C && N > 1) return LINFUSION_ERR_INVALID;                     // a token row must hold all heads
+  if (so[1] < C && N > 1) return LINFUSION_ERR_OVERLAP;                     // written rows must be disjoint
+  if (B > 1 && so[0] < (N - 1) * so[1] + C) return LINFUSION_ERR_OVERLAP;
+  const size_t tbytes = (size_t)((B - 1) * si[0] + (N - 1) * si[1] + C) * 2;
+  const size_t obytes = (size_t)((B - 1) * so[0] + (N - 1) * so[1] + C) * 2;
+  const size_t vbytes = (size_t)C * sizeof(float);
   for (const void* x : ins)
-    if (overlaps(out, tbytes, x, tbytes)) return LINFUSION_ERR_OVERLAP;
+    if (overlaps(out, obytes, x, tbytes)) return LINFUSION_ERR_OVERLAP;
   for (const float* x : vecs)
-    if (overlaps(out, tbytes, x, vbytes)) return LINFUSION_ERR_OVERLAP;
+    if (overlaps(out, obytes, x, vbytes)) return LINFUSION_ERR_OVERLAP;
   if (!workspace) return LINFUSION_ERR_WORKSPACE;
   if ((uintptr_t)workspace & 15) return LINFUSION_ERR_MISALIGNED;
   if (workspace_bytes < p.ws_total) return LINFUSION_ERR_WORKSPACE;
@@ -197,13 +216,31 @@ int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, co
     if (overlaps(workspace, p.ws_total, x, tbytes)) return LINFUSION_ERR_OVERLAP;
   for (const float* x : vecs)
     if (overlaps(workspace, p.ws_total, x, vbytes)) return LINFUSION_ERR_OVERLAP;
-  if (overlaps(workspace, p.ws_total, out, tbytes)) return LINFUSION_ERR_OVERLAP;
+  if (overlaps(workspace, p.ws_total, out, obytes)) return LINFUSION_ERR_OVERLAP;
   rc = lfh::check_device();
   if (rc != LINFUSION_OK) return rc;
   MlpArgs a{a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, B, N, feature_map, eps, ln_eps, slope,
             (flags & LINFUSION_FLAG_UNNORMALIZED) != 0, &p, (unsigned char*)workspace, (hipStream_t)stream,
-            reinterpret_cast<hipEvent_t*>(events)};
+            reinterpret_cast<hipEvent_t*>(events), si[0] / 8, si[1] / 8, so[0] / 8, so[1] / 8};
   return dispatch_mlp(H, d, dtype, a);
+}
+
+int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, const void* t_k, const void* v, void* out,
+                           const float* gamma_q, const float* beta_q, const float* gamma_k, const float* beta_k, int B,
+                           int H, long long N, int d, int dtype, int feature_map, float eps, float ln_eps, float slope,
+                           unsigned flags, void* workspace, size_t workspace_bytes, void* stream, void* events[4]) {
+  return mlp_impl(a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, B, H, N, d, dtype, feature_map, eps,
+                  ln_eps, slope, flags, nullptr, nullptr, workspace, workspace_bytes, stream, events);
+}
+
+int linfusion_attn_fwd_mlp_strided(const void* a_q, const void* t_q, const void* a_k, const void* t_k, const void* v,
+                                   void* out, const float* gamma_q, const float* beta_q, const float* gamma_k,
+                                   const float* beta_k, int B, int H, long long N, int d, int dtype, int feature_map,
+                                   float eps, float ln_eps, float slope, unsigned flags, const long long in_strides[2],
+                                   const long long out_strides[2], void* workspace, size_t workspace_bytes,
+                                   void* stream, void* events[4]) {
+  return mlp_impl(a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, B, H, N, d, dtype, feature_map, eps,
+                  ln_eps, slope, flags, in_strides, out_strides, workspace, workspace_bytes, stream, events);
 }
 
 }  // extern "C"

@@ -12,6 +12,18 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "linfusion.h")
 
 
+def _device_present():
+    import torch
+    return torch.cuda.is_available()
+
+
+# The validation tests hand the library made-up device addresses.  Nothing dereferences them as long as every
+# call ends in an error code, which without a device even a valid call does (no device); on a machine that has
+# one a valid call would launch kernels on those addresses, so there these tests do not run at all.
+fake_addresses = pytest.mark.skipif(_device_present(), reason="passes made-up device addresses: only where no "
+                                                              "GPU could be handed them")
+
+
 def _declared_symbols():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
@@ -73,6 +85,7 @@ def _call(q=4096, k=1 << 20, v=2 << 20, out=3 << 20, B=1, H=2, N=64, d=40, dtype
     return lf.library().linfusion_attn_fwd_ex(q, k, v, out, B, H, N, d, dtype, fm, eps, flags, ws, ws_bytes, None)
 
 
+@fake_addresses
 def test_argument_validation_happens_on_the_host():
     assert _call(q=None) == -1 and _call(k=None) == -1 and _call(v=None) == -1 and _call(out=None) == -1
     assert _call(B=0) == -1 and _call(H=-1) == -1 and _call(N=0) == -1 and _call(d=0) == -1
@@ -96,6 +109,7 @@ def _strided(sq=None, skv=None, so=None, q=4096, k=1 << 20, v=2 << 20, out=3 << 
                                                    arr(so), ws, ws_bytes, None)
 
 
+@fake_addresses
 def test_stride_validation_happens_on_the_host():
     import torch
     ok = -6 if not torch.cuda.is_available() else None      # valid arguments reach the device check
@@ -122,6 +136,7 @@ def test_stride_validation_happens_on_the_host():
     assert _strided(skv=(64 * 4 * 80, 80, 4 * 80), k=(3 << 20) - 4 * 64 * 80 * 2 * 2 + 4096) == -7
 
 
+@fake_addresses
 def test_backward_argument_validation_happens_on_the_host():
     lib = lf.library()
 
@@ -139,6 +154,7 @@ def test_backward_argument_validation_happens_on_the_host():
     assert lf.linfusion_attn_bwd_workspace_bytes(1, 2, 64, 40, 0) == 0
 
 
+@fake_addresses
 def test_valid_call_without_a_gfx950_device_fails_loudly():
     import torch
     if torch.cuda.is_available():
@@ -166,6 +182,7 @@ def _mlp(B=1, H=8, N=64, d=40, dtype=1, fm=0, eps=1e-6, ln_eps=1e-5, slope=0.01,
                                                None, None)
 
 
+@fake_addresses
 def test_mlp_fed_entry_validates_on_the_host():
     import torch
     ok = -6 if not torch.cuda.is_available() else None
@@ -182,12 +199,47 @@ def test_mlp_fed_entry_validates_on_the_host():
     assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 64, 56, 1) == 0
 
 
+def _mlps(sin=None, sout=None, B=2, N=64, out=40 << 20, **kw):
+    """Raw C call of linfusion_attn_fwd_mlp_strided; the five inputs interleave in one [B, N, 5 C] buffer."""
+    C = 320
+    arr = lambda s: None if s is None else ctypes.byref((ctypes.c_longlong * 2)(*s))
+    base = 1 << 20
+    a = dict(H=8, d=40, dtype=1, fm=0, eps=1e-6, ln_eps=1e-5, slope=0.01, flags=0)
+    a.update(kw)
+    return lf.library().linfusion_attn_fwd_mlp_strided(
+        base, base + 2 * C, base + 4 * C, base + 6 * C, base + 8 * C, out, 48 << 20, 49 << 20, 50 << 20, 51 << 20, B,
+        a["H"], N, a["d"], a["dtype"], a["fm"], a["eps"], a["ln_eps"], a["slope"], a["flags"], arr(sin), arr(sout),
+        64 << 20, 4 << 20, None, None)
+
+
+@fake_addresses
+def test_strided_mlp_entry_validates_on_the_host():
+    import torch
+    ok = -6 if not torch.cuda.is_available() else None
+    C, N = 320, 64
+    inter = (N * 5 * C, 5 * C)
+    if ok is not None:
+        assert _mlps(inter, None) == ok and _mlps(inter, (N * 2 * C, 2 * C)) == ok
+        assert _mlps(inter, None, B=1, N=1) == ok
+    assert _mlps((N * 5 * C, 5 * C + 4), None) == -3 and _mlps(inter, (N * C + 4, C)) == -3     # 16-byte rows
+    assert _mlps((N * 5 * C, -8), None) == -1 and _mlps((N * 5 * C, C - 8), None) == -1         # rows too short
+    assert _mlps(inter, (N * C, C - 8)) == -7 and _mlps(inter, (N * C - 8, C)) == -7            # out rows intersect
+    assert _mlps(inter, (0, C)) == -7
+    assert _mlps((N * 5 * C, 8 << 27), None) == -1 and _mlps((1 << 46, 5 * C), None) == -1      # index ranges
+    # the inputs' extent is that of the wide buffer: an out inside it is caught, one behind it is not
+    assert _mlps(inter, None, out=(1 << 20) + 2 * (2 * N * 5 * C) - 64) == -7
+    if ok is not None:
+        assert _mlps(inter, None, out=(1 << 20) + 2 * (2 * N * 5 * C) + 8 * C * 2) == ok
+    assert _mlps(inter, None, flags=2) == -1 and _mlps(inter, None, H=8, d=64) == -2
+
+
 def _qv(B=1, H=2, N=64, dk=80, dv=40, dtype=1, fm=0, eps=1e-6, flags=0, q=1 << 20, out=4 << 20, ws=64 << 20,
         ws_bytes=4 << 20):
     return lf.library().linfusion_attn_fwd_qv(q, 2 << 20, 3 << 20, out, B, H, N, dk, dv, dtype, fm, eps, flags, ws,
                                               ws_bytes, None, None)
 
 
+@fake_addresses
 def test_unequal_width_entry_validates_on_the_host():
     import torch
     ok = -6 if not torch.cuda.is_available() else None
@@ -210,6 +262,7 @@ def _bwds(strides=(None,) * 5, B=1, H=2, N=64, d=40, dq=5 << 20, dk=6 << 20, dv=
                                                    1e-6, 0, *[arr(s) for s in strides], ws, ws_bytes, None)
 
 
+@fake_addresses
 def test_strided_backward_validates_on_the_host():
     import torch
     ok = -6 if not torch.cuda.is_available() else None

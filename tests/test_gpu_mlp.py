@@ -177,3 +177,50 @@ def test_recorded_into_a_graph_replays_correctly():
         lf.linfusion_attn_fwd_mlp(*dev[:5], eager, *dev[5:], H, 0, 1e-6, LN_EPS, SLOPE, 0, _ws(B, H, N, d, dtype))
         torch.cuda.synchronize()
         assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", [(2, 8, 1000, 40, "f16"), (1, 8, 4099, 40, "bf16"), (2, 4, 333, 80, "f16"),
+                                           (3, 4, 77, 64, "bf16"), (1, 8, 1, 16, "f16")])
+def test_strided_rows_of_one_wide_projection(B, H, N, d, dtype):
+    """The five branch results as column blocks of one [B, N, 5 C] tensor, out as a block of a [B, N, 2 C] one:
+    same bits as the dense call, and the oracle's values; the rest of the output buffer stays untouched."""
+    print(f"mlp strided B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=86)
+    C = H * d
+    dense = _run(ins, H)
+    wide = torch.cat([t.cuda() for t in ins[:5]], dim=2).contiguous()               # [B, N, 5 C]
+    views = [wide[:, :, i * C:(i + 1) * C] for i in range(5)]
+    vecs = [t.cuda() for t in ins[5:]]
+    obuf = torch.full((B, N, 2 * C), 7.0, dtype=wide.dtype, device="cuda")
+    out = obuf[:, :, C:]
+    lf.linfusion_attn_fwd_mlp_strided(*views, out, *vecs, H, 0, 1e-6, LN_EPS, SLOPE, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(out.contiguous().view(torch.int16), dense.view(torch.int16))
+    assert bool((obuf[:, :, :C] == 7.0).all())
+    _check(out.contiguous(), _oracle(ins, H, dtype), H, dtype, f"mlp strided {B}x{H}x{N}x{d} {dtype}")
+
+
+def test_strided_entry_with_padded_batches_and_dense_arrays_absent():
+    """Batch stride larger than N rows (padding between batches) on both sides; NULL stride arrays = dense."""
+    B, H, N, d, dtype = 2, 8, 515, 40, "f16"
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=87)
+    C = H * d
+    dense = _run(ins, H)
+    dev = [t.cuda() for t in ins]
+    pad = [torch.zeros(B, N + 5, C, dtype=dev[0].dtype, device="cuda") for _ in range(5)]
+    for p, t in zip(pad, dev[:5]):
+        p[:, :N].copy_(t)
+    # the five views must share strides, not a buffer
+    obuf = torch.full((B, N + 3, C), 7.0, dtype=dev[0].dtype, device="cuda")
+    lf.linfusion_attn_fwd_mlp_strided(*[p[:, :N] for p in pad], obuf[:, :N], *dev[5:], H, 0, 1e-6, LN_EPS, SLOPE, 0,
+                                      _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(obuf[:, :N].contiguous().view(torch.int16), dense.view(torch.int16))
+    assert bool((obuf[:, N:] == 7.0).all())
+    out2 = torch.empty_like(dense)
+    ws = _ws(B, H, N, d, dtype)
+    rc = lf.library().linfusion_attn_fwd_mlp_strided(
+        *[t.data_ptr() for t in dev[:5]], out2.data_ptr(), *[t.data_ptr() for t in dev[5:]], B, H, N, d, 1, 0, 1e-6,
+        LN_EPS, SLOPE, 0, None, None, ws.data_ptr(), ws.numel(), None, None)
+    torch.cuda.synchronize()
+    assert rc == 0 and torch.equal(out2.view(torch.int16), dense.view(torch.int16))
