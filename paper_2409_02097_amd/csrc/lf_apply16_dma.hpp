@@ -107,10 +107,14 @@ template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :
 // statistics come from the tile in LDS: every lane reduces the channels it holds of its token (mean and
 // centred sum of squares, exact in two passes over registers), the 2 W pieces per token meet in LDS and are
 // merged with the pairwise-variance formula -- one more workgroup barrier per tile, no extra memory pass.
-template <typename T, int D, int FM, bool NORM, int ROWS_W = 0, bool MLP = false, int DV = D>
+// MLP with PRE (per-head mode, for shapes whose token rows do not fit one workgroup): the row statistics were
+// computed by an earlier kernel, {rstd, -mean rstd} per token; a tile's 32 pairs travel with its copies as one
+// more deposit (256 bytes used) into a third ring.
+template <typename T, int D, int FM, bool NORM, int ROWS_W = 0, bool MLP = false, int DV = D, bool PRE = false>
 struct ApplyDma {
   static constexpr bool ROWS = ROWS_W > 0;
-  static_assert(!MLP || ROWS, "the two-branch input needs whole token rows in one workgroup");
+  static_assert(!MLP || ROWS || PRE, "the two-branch input needs whole token rows in one workgroup, or their statistics");
+  static_assert(!PRE || (MLP && !ROWS && DV == D), "precomputed row statistics serve the per-head two-branch kernel");
   static_assert(DV == D || !ROWS, "unequal query and value widths run on the per-head kernel only");
   static constexpr int W = ROWS ? ROWS_W : kWavesPerWG;   // waves per workgroup
   static constexpr int NT = 64 * W;
@@ -128,9 +132,10 @@ struct ApplyDma {
   static constexpr int RPR = kTile / W;   // token rows per wave region
   static_assert(!ROWS || (PC % 4 == 0 && RPR * G >= 16 && kTile % W == 0), "rotation classes must fit a region");
   static constexpr int kStageOffset = (R - 1) * W * Cfg::kSlotBytes;
-  static constexpr int NLC = MLP ? 2 * NL : NL;                  // copy instructions per tile
+  static constexpr int NLC = MLP ? 2 * NL + (PRE ? 1 : 0) : NL;  // copy instructions per tile
   static constexpr int kTOffset = R * W * Cfg::kSlotBytes;        // MLP: ring of the LayerNorm branch's tiles
   static constexpr int kPartOffset = 2 * R * W * Cfg::kSlotBytes; // MLP: (mean, M2) per (wave, half, token)
+  static constexpr int kStatOffset = 2 * R * W * Cfg::kSlotBytes; // PRE: ring of 1 KiB deposits, {rstd, cn} per token
   static __device__ __forceinline__ int rot(int r) { return ((r * G) >> 4) & (G - 1); }
 
   const u32x4* Qh;
@@ -152,6 +157,7 @@ struct ApplyDma {
   float c1, eps_s, c1_az;   // c1_az: alpha_z, kept for save_packed
   // MLP: the LayerNorm branch's tensor, the affine of this lane's channels, and the two scalars
   const u32x4* Th;
+  const u32x4* St;   // PRE: the batch's row statistics, two tokens per 16 bytes (readable up to a whole last tile)
   float gam[MLP ? Shape16<D>::kKS * 8 : 1], bet[MLP ? Shape16<D>::kKS * 8 : 1];
   float ln_eps, slope;
 
@@ -224,12 +230,14 @@ struct ApplyDma {
       const int chunk = kg * KS + s;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const int ch = wave * D + chunk * 8 + e;
+        const int ch = (ROWS ? wave * D : 0) + chunk * 8 + e;
         gam[s * 8 + e] = chunk < CPR ? gamma[ch] : 0.0f;
         bet[s * 8 + e] = chunk < CPR ? beta[ch] : 0.0f;
       }
     }
   }
+
+  LF_DEV void set_stats(const void* stats) { St = reinterpret_cast<const u32x4*>(stats); }
 
   // this wave's region of ring slot `slot`: what it copies in and stores from
   LF_DEV unsigned char* slot_ptr(int slot) const { return smem + (slot * W + wave) * Cfg::kSlotBytes; }
@@ -274,6 +282,12 @@ struct ApplyDma {
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tp + c),
                                          (LF_LDS void*)(sl + kTOffset + u * 1024), 16, 0, 2 /* nt */);
       }
+    }
+    if constexpr (PRE) {
+      // lanes 0..15 bring the tile's 32 pairs, the others repeat them into the deposit's unused part
+      const u32x4* sp = St + tile * (kTile / 2) + (lane & 15);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sp,
+                                       (LF_LDS void*)(smem + kStatOffset + (slot * W + wave) * 1024), 16, 0, 0);
     }
   }
 
@@ -407,11 +421,11 @@ struct ApplyDma {
       if (aslot >= R) aslot -= R;
       if (ahead.valid()) {
         issue_copy(ahead.t, aslot);
-        // issue order is  C0 C1 | C2 W0 S0 | C3 W1 S1 | C4 W2 S2 | ...  (C copies of NL, S stores of NLO
+        // issue order is  C0 C1 | C2 W0 S0 | C3 W1 S1 | C4 W2 S2 | ...  (C copies of NLC, S stores of NLO
         // instructions, W wait): after tile j's copies come C(j+1), C(j+2) and the stores S(j-2), S(j-1)
-        if (iter == 0) wait_vmcnt<2 * NL>();
-        else if (iter == 1) wait_vmcnt<2 * NL + NLO>();
-        else wait_vmcnt<2 * NL + 2 * NLO>();
+        if (iter == 0) wait_vmcnt<2 * NLC>();
+        else if (iter == 1) wait_vmcnt<2 * NLC + NLO>();
+        else wait_vmcnt<2 * NLC + 2 * NLO>();
       } else {
         wait_vmcnt<0>();
       }
@@ -471,7 +485,16 @@ struct ApplyDma {
     u32x4 Bh[KS], Bl[KS];
     u32x4 traw[MLP ? KS : 1];      // MLP: this lane's chunks of t, raw
     float rstd = 0.0f, cn = 0.0f;   // MLP: LayerNorm(t) = t * rstd + cn
-    if constexpr (MLP) {
+    if constexpr (PRE) {
+      const f32x2 rc = *reinterpret_cast<const f32x2*>(smem + kStatOffset + (slot * W + wave) * 1024 + tok * 8);
+      rstd = rc[0];
+      cn = rc[1];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        traw[s] = u32x4{0, 0, 0, 0};
+        if (kg * KS + s < CPR) traw[s] = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, kg * KS + s) + kTOffset);
+      }
+    } else if constexpr (MLP) {
       // ---- LayerNorm statistics of this lane's token over all W D channels: sums of (t - pivot) and of its
       //      square, the pivot being the token's channel 0 (the same for all lanes of the token, so the
       //      pieces simply add; deviations are small next to a large common offset, so nothing cancels) ----

@@ -7,21 +7,27 @@
 
 #include "lf_host_api.hpp"
 #include "lf_mlp16.hpp"
+#include "lf_mlp_api.hpp"
 
 namespace {
 
 constexpr int kNumCU = 256;
 
 struct MlpPlan {
+  int route;                      // 0: whole token rows in one workgroup; 1: per-head kernels + statistics pass
+  long long n_pad;                // route 1: tokens rounded up to whole tiles
+  int stats_wgs;
+  size_t ws_stats;
   int W;                          // heads = waves per workgroup
   int splits, blk_reduce;         // state reduction: workgroups per batch, tiles per block
   int apply_wgs, blk_apply;
   size_t ne, ws_partials, ws_state, ws_pack, ws_total;
 };
 
-// Which shapes have kernels: the workgroup must cover whole token rows (H = W in {4, 8}) and both rings of
-// the apply kernel must fit the 160 KiB of LDS (eight heads: d <= 48; four heads: d <= 80).
-bool mlp_supported(int H, int d) {
+// Which shapes the kernels for whole token rows take: the workgroup must cover a row (H = W in {4, 8}) and both
+// rings of the apply kernel must fit the 160 KiB of LDS (eight heads: d <= 48; four heads: d <= 80).  Every other
+// shape with a per-head kernel width goes the per-head way.
+bool rows_supported(int H, int d) {
   if (d < 8 || d % 8 != 0) return false;
   if (H == 8) return d <= 48;
   if (H == 4) return d <= 64 || d == 80;
@@ -38,10 +44,46 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
   if (B > 65535) return LINFUSION_ERR_INVALID;   // grid.y limit
   if (dtype != LINFUSION_DTYPE_F16 && dtype != LINFUSION_DTYPE_BF16) return LINFUSION_ERR_UNSUPPORTED;
-  if (!mlp_supported(H, d)) return LINFUSION_ERR_UNSUPPORTED;
+  if (d < 8 || d % 8 != 0 || !lfm::heads_supported(d)) return LINFUSION_ERR_UNSUPPORTED;
   if (N > (1LL << 40) / ((long long)H * d)) return LINFUSION_ERR_INVALID;
-  p->W = H;
   const long long n_tiles = (N + lf::kTile - 1) / lf::kTile;
+  p->ne = (size_t)d * d + d;
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  // LINFUSION_MLP_ROUTE=1 sends the shapes of the whole-row kernels the per-head way too (a test aid)
+  p->route = (rows_supported(H, d) && lfh::env_int("LINFUSION_MLP_ROUTE", 0) != 1) ? 0 : 1;
+  if (p->route == 1) {
+    if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;   // grid.y limit
+    p->W = 0;
+    p->n_pad = n_tiles * lf::kTile;
+    const long long units = (long long)B * H;
+    auto per_head = [&](int want_total, int blk_dflt, int* blk) {
+      long long s = want_total / units;
+      if (s > (n_tiles + 3) / 4) s = (n_tiles + 3) / 4;          // four waves, a tile each at least
+      if (s < 1) s = 1;
+      long long t = (n_tiles + s - 1) / s;
+      t = ((blk_dflt < t ? blk_dflt : t) + 3) / 4 * 4;            // a block is whole rounds of the four waves
+      *blk = (int)t;
+      const long long g = (n_tiles + t - 1) / t;                  // blocks are dealt round-robin to the workgroups
+      return (int)(g < s ? g : s);
+    };
+    p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 4 * kNumCU), lfh::env_int("LINFUSION_MLPH_REDUCE_BLK", 8),
+                         &p->blk_reduce);
+    p->apply_wgs = per_head(lfh::env_int("LINFUSION_MLPH_APPLY_WGS", 8 * kNumCU), lfh::env_int("LINFUSION_MLPH_APPLY_BLK", 8),
+                            &p->blk_apply);
+    long long sw = (N + 15) / 16, cap = lfh::env_int("LINFUSION_MLPH_STATS_WGS", 8 * kNumCU) / (2 * B);
+    if (cap < 1) cap = 1;
+    p->stats_wgs = (int)(sw < cap ? sw : cap);
+    p->ws_partials = up((size_t)units * p->splits * p->ne * sizeof(float));
+    p->ws_state = up((size_t)units * p->ne * sizeof(float));
+    p->ws_pack = up((size_t)units * pack_bytes(d, dtype));
+    p->ws_stats = up((size_t)2 * B * p->n_pad * 2 * sizeof(float));
+    p->ws_total = p->ws_partials + p->ws_state + p->ws_pack + p->ws_stats;
+    return LINFUSION_OK;
+  }
+  p->W = H;
+  p->n_pad = 0;
+  p->stats_wgs = 0;
+  p->ws_stats = 0;
   auto per_batch = [&](int want_total, int blk_dflt, int* blk) {
     long long s = want_total / B;
     if (s > n_tiles) s = n_tiles;
@@ -58,8 +100,6 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
                         lfh::env_int("LINFUSION_MLP_REDUCE_BLK", 2), &p->blk_reduce);
   p->apply_wgs = per_batch(lfh::env_int("LINFUSION_MLP_APPLY_WGS", 2 * kNumCU) / unit,
                            lfh::env_int("LINFUSION_MLP_APPLY_BLK", H == 8 ? 1 : 2), &p->blk_apply);
-  p->ne = (size_t)d * d + d;
-  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   p->ws_partials = up((size_t)B * H * p->splits * p->ne * sizeof(float));
   p->ws_state = up((size_t)B * H * p->ne * sizeof(float));
   p->ws_pack = up((size_t)B * H * pack_bytes(d, dtype));
@@ -219,6 +259,16 @@ static int mlp_impl(const void* a_q, const void* t_q, const void* a_k, const voi
   if (overlaps(workspace, p.ws_total, out, obytes)) return LINFUSION_ERR_OVERLAP;
   rc = lfh::check_device();
   if (rc != LINFUSION_OK) return rc;
+  if (p.route == 1) {
+    unsigned char* ws = (unsigned char*)workspace;
+    lfm::HeadsArgs h{a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, B, H, N, d, dtype, feature_map, eps,
+                     ln_eps, slope, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0, si[0] / 8, si[1] / 8, so[0] / 8,
+                     so[1] / 8, reinterpret_cast<float*>(ws), reinterpret_cast<float*>(ws + p.ws_partials),
+                     ws + p.ws_partials + p.ws_state, ws + p.ws_partials + p.ws_state + p.ws_pack, p.n_pad,
+                     p.stats_wgs, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, (hipStream_t)stream,
+                     reinterpret_cast<hipEvent_t*>(events)};
+    return lfm::run_heads(h);
+  }
   MlpArgs a{a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, B, N, feature_map, eps, ln_eps, slope,
             (flags & LINFUSION_FLAG_UNNORMALIZED) != 0, &p, (unsigned char*)workspace, (hipStream_t)stream,
             reinterpret_cast<hipEvent_t*>(events), si[0] / 8, si[1] / 8, so[0] / 8, so[1] / 8};

@@ -191,12 +191,15 @@ def test_mlp_fed_entry_validates_on_the_host():
     assert _mlp(a_q=None) == -1 and _mlp(gamma_q=None) == -1 and _mlp(out=None) == -1
     assert _mlp(ln_eps=0.0) == -1 and _mlp(ln_eps=float("inf")) == -1 and _mlp(slope=-0.1) == -1 and _mlp(slope=2.0) == -1
     assert _mlp(eps=-1.0) == -1 and _mlp(flags=2) == -1 and _mlp(B=0) == -1
-    assert _mlp(H=8, d=64) == -2 and _mlp(H=5) == -2 and _mlp(H=16) == -2 and _mlp(dtype=0) == -2 and _mlp(fm=9) == -2
+    if ok is not None:   # head counts and widths beyond the whole-row kernels go the per-head way
+        assert _mlp(H=8, d=64) == ok and _mlp(H=5) == ok and _mlp(H=20, d=64, ws_bytes=16 << 20) == ok
+    assert _mlp(d=72) == -2 and _mlp(d=96) == -2 and _mlp(d=12) == -2 and _mlp(dtype=0) == -2 and _mlp(fm=9) == -2
     assert _mlp(a_q=(1 << 20) + 8) == -3 and _mlp(gamma_q=(48 << 20) + 2) == -3
     assert _mlp(ws=None) == -4 and _mlp(ws_bytes=1024) == -4
     assert _mlp(out=1 << 20) == -7 and _mlp(ws=5 << 20) == -7
     assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 2097152, 40, 1) > 0
-    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 64, 56, 1) == 0
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 64, 56, 1) > 0       # per-head kernels + statistics
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 64, 72, 1) == 0
 
 
 def _mlps(sin=None, sout=None, B=2, N=64, out=40 << 20, **kw):
@@ -230,7 +233,7 @@ def test_strided_mlp_entry_validates_on_the_host():
     assert _mlps(inter, None, out=(1 << 20) + 2 * (2 * N * 5 * C) - 64) == -7
     if ok is not None:
         assert _mlps(inter, None, out=(1 << 20) + 2 * (2 * N * 5 * C) + 8 * C * 2) == ok
-    assert _mlps(inter, None, flags=2) == -1 and _mlps(inter, None, H=8, d=64) == -2
+    assert _mlps(inter, None, flags=2) == -1 and _mlps(inter, None, H=8, d=72) == -2
 
 
 def _qv(B=1, H=2, N=64, dk=80, dv=40, dtype=1, fm=0, eps=1e-6, flags=0, q=1 << 20, out=4 << 20, ws=64 << 20,

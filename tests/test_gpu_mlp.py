@@ -224,3 +224,77 @@ def test_strided_entry_with_padded_batches_and_dense_arrays_absent():
         LN_EPS, SLOPE, 0, None, None, ws.data_ptr(), ws.numel(), None, None)
     torch.cuda.synchronize()
     assert rc == 0 and torch.equal(out2.view(torch.int16), dense.view(torch.int16))
+
+
+# ---- shapes whose token rows do not fit one workgroup: per-head kernels with a statistics pass ------------------
+HEAD_SHAPES = [
+    (1, 10, 1000, 64, "f16"), (2, 20, 333, 64, "bf16"), (1, 8, 777, 80, "f16"), (1, 5, 515, 64, "f16"),
+    (1, 8, 300, 64, "f16"), (1, 2, 100, 40, "f16"), (1, 3, 2051, 24, "bf16"), (1, 1, 33, 8, "f16"),
+    (2, 16, 64, 56, "f16"), (1, 8, 1, 80, "bf16"), (1, 10, 4099, 64, "bf16"), (3, 6, 31, 16, "f16"),
+    (1, 12, 130, 32, "bf16"), (1, 16, 257, 48, "f16"),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", HEAD_SHAPES)
+def test_per_head_route_matches_oracle(B, H, N, d, dtype):
+    print(f"mlp heads B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=88)
+    out = _run(ins, H)
+    _check(out, _oracle(ins, H, dtype), H, dtype, f"mlp heads {B}x{H}x{N}x{d} {dtype}")
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", [(2, 8, 1000, 40, "f16"), (1, 8, 4099, 40, "bf16"), (1, 4, 333, 80, "f16"),
+                                           (2, 4, 77, 64, "bf16"), (1, 8, 33, 8, "f16")])
+def test_per_head_route_on_whole_row_shapes(B, H, N, d, dtype, monkeypatch):
+    """Both routes on one shape: each within tolerance of the oracle (their bits may differ: the statistics are
+    summed in another order)."""
+    print(f"mlp heads forced B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=89)
+    ref = _oracle(ins, H, dtype)
+    rows = _run(ins, H)
+    monkeypatch.setenv("LINFUSION_MLP_ROUTE", "1")
+    heads = _run(ins, H)
+    monkeypatch.delenv("LINFUSION_MLP_ROUTE")
+    _check(rows, ref, H, dtype, "whole rows")
+    _check(heads, ref, H, dtype, "per head")
+
+
+@pytest.mark.parametrize("fm", [0, 1, 2])
+@pytest.mark.parametrize("unnorm", [False, True])
+def test_per_head_route_feature_maps_and_unnormalized(fm, unnorm):
+    B, H, N, d, dtype = 2, 10, 700, 64, "f16"
+    print(f"mlp heads fm={fm} unnorm={unnorm}", flush=True)
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=90))
+    if fm != 0:   # identity / relu: keep the denominators away from zero
+        ins[0] = (ins[0].float().abs() + 0.5).to(ins[0].dtype)
+        ins[2] = (ins[2].float().abs() + 0.5).to(ins[2].dtype)
+    out = _run(ins, H, fm=fm, flags=lf.FLAG_UNNORMALIZED if unnorm else 0)
+    _check(out, _oracle(ins, H, dtype, fm=fm, normalize=not unnorm), H, dtype, f"mlp heads fm={fm} unnorm={unnorm}")
+
+
+@pytest.mark.parametrize("H,d,dtype", [(10, 64, "f16"), (8, 80, "bf16"), (3, 8, "f16")])
+def test_per_head_route_layer_norm_input_far_from_zero_mean(H, d, dtype):
+    B, N = 1, 500
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=92))
+    for i in (1, 3):
+        ins[i] = (ins[i].float() * 0.5 + 40.0).to(ins[i].dtype)
+    out = _run(ins, H)
+    _check(out, _oracle(ins, H, dtype), H, dtype, "offset LayerNorm input, per head")
+
+
+def test_per_head_route_strided_and_repeatable():
+    """Column blocks of one wide buffer on the per-head route: same bits as its dense call, twice."""
+    B, H, N, d, dtype = 2, 10, 515, 64, "bf16"
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=91)
+    C = H * d
+    dense = _run(ins, H)
+    assert torch.equal(_run(ins, H).view(torch.int16), dense.view(torch.int16))
+    wide = torch.cat([t.cuda() for t in ins[:5]], dim=2).contiguous()
+    views = [wide[:, :, i * C:(i + 1) * C] for i in range(5)]
+    obuf = torch.full((B, N, 2 * C), 7.0, dtype=wide.dtype, device="cuda")
+    lf.linfusion_attn_fwd_mlp_strided(*views, obuf[:, :, C:], *[t.cuda() for t in ins[5:]], H, 0, 1e-6, LN_EPS, SLOPE, 0,
+                                      _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(obuf[:, :, C:].contiguous().view(torch.int16), dense.view(torch.int16))
+    assert bool((obuf[:, :, :C] == 7.0).all())
+    _check(dense, _oracle(ins, H, dtype), H, dtype, "mlp heads strided")
