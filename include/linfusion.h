@@ -215,15 +215,16 @@ size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int 
  * a_* is the result of the linear branch and t_* the result of the second branch's Linear for the same
  * tokens (both GEMMs are the caller's); mean_i and var_i (mean squared deviation) run over all C = H*d
  * channels of token i.  q and k are formed inside the state-reduction and apply kernels and never exist in
- * memory: the call reads five tensors and writes one.
+ * memory: where one workgroup can hold whole token rows (H = 8 with d <= 48, H = 4 with d <= 64 or 80) the
+ * call reads five tensors and writes one; for every other shape a pass over t_q and t_k first leaves the
+ * rows' LayerNorm statistics (8 bytes per token and branch) in the workspace, two tensor reads more.
  *
  *   a_q, t_q, a_k, t_k, v   DEVICE pointers, token-major contiguous [B, N, H*d] (head h owns channels
  *                           h*d .. h*d+d-1 of a token), fp16 or bf16, 16-byte aligned.
  *   out                     DEVICE pointer, same layout and type; must not overlap any input.
  *   gamma_*, beta_*         DEVICE pointers to H*d fp32 values each (the LayerNorms' affine).
- *   H, d                    H = 8 with d in {8, ..., 48 step 8}, or H = 4 with d in {8, ..., 64 step 8, 80}
- *                           (a workgroup must hold whole token rows); LINFUSION_DTYPE_F32 and every
- *                           other shape -> LINFUSION_ERR_UNSUPPORTED.
+ *   H, d                    any H >= 1 with B*H <= 65535; d in {8, ..., 64 step 8, 80}; LINFUSION_DTYPE_F32
+ *                           and every other width -> LINFUSION_ERR_UNSUPPORTED.
  *   eps                     as linfusion_attn_fwd_ex.  ln_eps > 0 (finite), 0 <= slope <= 1: the LayerNorm's
  *                           epsilon (inside the square root) and the LeakyReLU's negative slope; the paper
  *                           names neither, the common defaults are 1e-5 and 0.01.
@@ -231,9 +232,9 @@ size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int 
  *   workspace               DEVICE scratch of at least linfusion_attn_mlp_workspace_bytes(...) bytes,
  *                           16-byte aligned, caller-owned, contents undefined before and after.
  *   events                  NULL, or four hipEvent_t created by the caller (passed as void*), recorded on
- *                           `stream` before the state reduction, after it, after combine + operand
- *                           packing, and after apply.
- * Enqueues four kernels on `stream`; never allocates, never synchronises; run-to-run identical results.
+ *                           `stream` before the first kernel, after the state reduction, after combine +
+ *                           operand packing, and after apply.
+ * Enqueues four kernels (five with the statistics pass) on `stream`; never allocates, never synchronises; run-to-run identical results.
  * Errors as linfusion_attn_fwd_ex (first failing check wins; nothing is enqueued on an error).
  */
 int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, const void* t_k, const void* v,

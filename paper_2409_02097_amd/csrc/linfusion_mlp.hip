@@ -66,10 +66,15 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
       const long long g = (n_tiles + t - 1) / t;                  // blocks are dealt round-robin to the workgroups
       return (int)(g < s ? g : s);
     };
-    p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 4 * kNumCU), lfh::env_int("LINFUSION_MLPH_REDUCE_BLK", 8),
+    // apply: one resident round (two rings of three slots and the statistics deposits per wave decide how many
+    // workgroups a CU holds); measured at 1 M tokens, 10 heads of 64: 0.725 ms with 256 workgroups, 0.77 with 2048
+    const int slot = (lf::kTile * d * 2 + 1023) / 1024 * 1024;
+    const int lds_apply = (2 * 3 * slot + 3 * 1024) * lf::kWavesPerWG;
+    const int resident = 160 * 1024 / lds_apply > 0 ? 160 * 1024 / lds_apply : 1;
+    p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_MLPH_REDUCE_BLK", 8),
                          &p->blk_reduce);
-    p->apply_wgs = per_head(lfh::env_int("LINFUSION_MLPH_APPLY_WGS", 8 * kNumCU), lfh::env_int("LINFUSION_MLPH_APPLY_BLK", 8),
-                            &p->blk_apply);
+    p->apply_wgs = per_head(lfh::env_int("LINFUSION_MLPH_APPLY_WGS", resident * kNumCU),
+                            lfh::env_int("LINFUSION_MLPH_APPLY_BLK", 8), &p->blk_apply);
     long long sw = (N + 15) / 16, cap = lfh::env_int("LINFUSION_MLPH_STATS_WGS", 8 * kNumCU) / (2 * B);
     if (cap < 1) cap = 1;
     p->stats_wgs = (int)(sw < cap ? sw : cap);

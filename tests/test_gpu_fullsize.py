@@ -166,9 +166,17 @@ def test_16k_image_workload_mlp_fed_sampled_rows():
     and evaluates sampled output rows; finiteness and the range of V are checked over every element."""
     name = "sd15_16k_f16"
     c = wl.CONFIGS[name]
-    B, H, N, d, dtype = c["B"], c["H"], c["N"], c["d"], c["dtype"]
-    C = H * d
-    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=c["idx"], device="cuda")
+    _mlp_fed_sampled_rows(name, c["B"], c["H"], c["N"], c["d"], c["dtype"], c["idx"], (0, 5, 7))
+
+
+def test_large_mlp_fed_case_on_per_head_kernels_sampled_rows():
+    """The same check where token rows do not fit one workgroup (ten heads of 64 channels, as in the SD-XL
+    levels): statistics pass + per-head kernels at 2^20 tokens."""
+    _mlp_fed_sampled_rows("10 heads of 64, bf16", 1, 10, 1 << 20, 64, "bf16", 77, (0, 4, 9))
+
+
+def _mlp_fed_sampled_rows(name, B, H, N, d, dtype, idx_, heads):
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=idx_, device="cuda")
     a_q, t_q, a_k, t_k, v = ins[:5]
     gq, bq, gk, bk = (t.cpu().numpy().astype(np.float64) for t in ins[5:])
     out = torch.empty_like(a_q)
@@ -181,7 +189,6 @@ def test_16k_image_workload_mlp_fed_sampled_rows():
     vmax = v.amax(dim=1, keepdim=True).float()
     assert bool((out.float() >= vmin - 1e-3).all()) and bool((out.float() <= vmax + 1e-3).all())
 
-    heads = (0, 5, 7)
     S = {h: np.zeros((d, d)) for h in heads}
     z = {h: np.zeros(d) for h in heads}
     step = 1 << 18

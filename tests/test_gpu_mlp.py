@@ -133,8 +133,9 @@ def test_run_to_run_identical():
 
 def test_rejected_arguments():
     code = wl.DTYPE_CODE
-    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 64, code["f16"]) == 0      # eight heads: d <= 48
-    assert lf.linfusion_attn_mlp_workspace_bytes(1, 5, 100, 40, code["f16"]) == 0      # rows must fit a workgroup
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 72, code["f16"]) == 0      # no kernel of that width
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 5, 100, 96, code["f16"]) == 0
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 64, code["f16"]) > 0       # per-head kernels
     assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 40, code["f32"]) == 0
     ins = [t.cuda() for t in wl.make_mlp_inputs(1, 8, 64, 40, "f16", idx=86)]
     out = torch.empty_like(ins[0])
