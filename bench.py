@@ -341,14 +341,23 @@ def main():
         torch.cuda.synchronize()
         sdt = (time.perf_counter() - ts0) / msteps
         del wide, views
+        # shapes whose token rows fit one workgroup run two big kernels; the others a statistics pass (reads t_q and
+        # t_k once more) and per-head kernels: the first timed interval then covers statistics + reduction
+        whole_rows = ((H == 8 and d <= 48) or (H == 4 and (d <= 64 or d == 80))) and \
+            os.environ.get("LINFUSION_MLP_ROUTE", "0") != "1"
+        rname = "state_reduce16_mlp" if whole_rows else "mlp_rowstats16 + state_reduce16_mlph"
+        aname = "apply16_mlp" if whole_rows else "apply16_mlph"
+        rpasses = 3 if whole_rows else 5
         result["mlp"] = {
+            "route": "whole token rows per workgroup" if whole_rows else "statistics pass + per-head kernels",
+            "kernel_tensor_passes": 6 if whole_rows else 8,
             "ms_per_step": mdt * 1e3, "interleaved_ms_per_step": sdt * 1e3, "tokens_per_s": B * N / mdt, "alg_bytes": 6 * tensor_bytes,
             "hbm_gbps": 6 * tensor_bytes / mdt / 1e9, "hbm_frac_of_peak": 6 * tensor_bytes / mdt / 1e9 / HBM_PEAK_GBPS,
             "kernels": [
-                {"name": "state_reduce16_mlp", "ms": mk[0], "alg_bytes": 3 * tensor_bytes,
-                 "gbps": 3 * tensor_bytes / (mk[0] * 1e-3) / 1e9 if mk[0] > 0 else None},
+                {"name": rname, "ms": mk[0], "alg_bytes": rpasses * tensor_bytes,
+                 "gbps": rpasses * tensor_bytes / (mk[0] * 1e-3) / 1e9 if mk[0] > 0 else None},
                 {"name": "combine_state + pack_state16", "ms": mk[1], "alg_bytes": 0, "gbps": 0.0},
-                {"name": "apply16_mlp", "ms": mk[2], "alg_bytes": 3 * tensor_bytes,
+                {"name": aname, "ms": mk[2], "alg_bytes": 3 * tensor_bytes,
                  "gbps": 3 * tensor_bytes / (mk[2] * 1e-3) / 1e9 if mk[2] > 0 else None}],
             "unfused_ms_per_step": udt * 1e3,
             "unfused": "q, k formed by torch layer_norm + leaky_relu + add (16-bit), then linfusion_attn_fwd_strided",
