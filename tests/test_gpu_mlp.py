@@ -150,10 +150,10 @@ def test_rejected_arguments():
     assert call(*ins[:5], out, *ins[5:], 8, 7, 1e-6, 1e-5, 0.01, 0, ws) == -2          # unknown feature map
 
 
-def test_recorded_into_a_graph_replays_correctly():
-    """The MLP-fed call enqueues kernels only, so it can be captured; every replay (new inputs in the same buffers,
-    eager work in between) must equal the eager result bit for bit."""
-    B, H, N, d, dtype = 1, 8, 2000, 40, "f16"
+@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 8, 2000, 40, "f16"), (2, 10, 1500, 64, "bf16")])
+def test_recorded_into_a_graph_replays_correctly(B, H, N, d, dtype):
+    """The MLP-fed call enqueues kernels only (on either route), so it can be captured; every replay (new inputs in
+    the same buffers, eager work in between) must equal the eager result bit for bit."""
     dev = [t.cuda() for t in wl.make_mlp_inputs(B, H, N, d, dtype, idx=87)]
     out = torch.zeros_like(dev[0])
     ws = _ws(B, H, N, d, dtype)
