@@ -18,7 +18,7 @@ struct HeadsArgs {
   bool unnorm;
   long long in_batch, in_row, out_batch, out_row;   // strides in 16-byte units
   float *partials, *state;                           // [B*H][splits][d*d + d] and [B*H][d*d + d], fp32
-  unsigned char* packed;                             // heads_packed_bytes(d, dtype) per head
+  unsigned char* packed;                             // the heads' operand-ready states
   void* stats;                                       // [2][B][n_pad] pairs of floats
   long long n_pad;                                   // N rounded up to whole 32-token tiles
   int stats_wgs, splits, blk_reduce, apply_wgs, blk_apply;
@@ -27,8 +27,10 @@ struct HeadsArgs {
                               // combine + packing, after apply
 };
 
-// head widths the per-head kernels are built for
+// head widths the per-head kernels are built for; those of them that run on the wide kernels (the packed state
+// then has lfw::wide_packed_bytes per head and a tile block need not be whole rounds of four waves)
 bool heads_supported(int d);
+bool heads_wide(int d);
 // enqueues statistics, state reduction, combine, pack and apply; returns LINFUSION_OK or a LINFUSION_ERR_* code
 int run_heads(const HeadsArgs& a);
 

@@ -315,8 +315,13 @@ pack_state_wide(const float* __restrict__ state, unsigned char* __restrict__ pac
 // j+2, read tile j, barrier, compute and write back, wait for own rows of tile j+1 and apply phi to them,
 // barrier.
 // The state arrives operand-ready from pack_state_wide: the prologue is a handful of coalesced loads.
+// MLP: the query is formed in that same pass over a wave's rows as  a + LeakyReLU(LayerNorm(t))  (the two-branch
+// f' of Sec. 4.1) from the tile of `a` in the ring, the tile of `t` in a second ring behind it (and behind the LO
+// buffer), the rows' {rstd, -mean rstd} from an earlier kernel, which travel with each tile as one more 1 KiB
+// deposit (256 bytes used; every wave brings the same 32 pairs to the same place and reads its own rows'), and
+// the head's gamma, beta from a table in LDS.
 // ==========================================================================================
-template <typename T, int D, int FM, bool NORM, int W>
+template <typename T, int D, int FM, bool NORM, int W, bool MLP = false>
 struct ApplyWide {
   using Sw = ApplyWideShape<D, W>;
   static constexpr int kWavesPerWG = W;   // this kernel's own workgroup shape
@@ -324,6 +329,11 @@ struct ApplyWide {
   static constexpr int CPR = Sw::kCPR, KS = Sw::kKS, MT2 = Sw::kMT2, HALF = Sw::kHalf, DQ = Sw::kDQ;
   static constexpr int NL = Sw::kNLA, NE = D * D + D, R = Sw::kRing, RPR = Sw::kRPR;
   static_assert(R == 3, "the wait counts below are written for a ring of three slots");
+  static constexpr int NLC = MLP ? 2 * NL + 1 : NL;                              // copy instructions per tile
+  static constexpr int kTOffset = (R + (NS == 2 ? 1 : 0)) * Sw::kSlotBytes;      // MLP: ring of the t tiles
+  static constexpr int kStatOffset = kTOffset + R * Sw::kSlotBytes;              // MLP: R deposits of statistics
+  static constexpr int kAffOffset = kStatOffset + R * 1024;                      // MLP: gamma[D] then beta[D], fp32
+  static constexpr int kLdsBytes = MLP ? kAffOffset + 2 * D * 4 : kTOffset;
 
   const u32x4* Qh;
   u32x4* Oh;
@@ -332,6 +342,12 @@ struct ApplyWide {
   int rs_q, rs_o;
   int lane, wave, tok, kg, row_byte, trot;
   int trow[NL], qoff[NL], ooff[NL], soff[NL];
+  // MLP: the t tensor, the statistics (two tokens per 16 bytes), the slope; and for the chunk this lane
+  // transforms at deposit u of its wave's region: its token row in the tile and its first channel
+  const u32x4* Th;
+  const u32x4* St;
+  float slope;
+  int prow[MLP ? NL : 1], pch[MLP ? NL : 1];
   TileIter it, ahead;
   u32x4 A[NS][MT2][KS];
   float c1, eps_s;
@@ -363,7 +379,22 @@ struct ApplyWide {
       qoff[u] = rc * rs_q + c;
       ooff[u] = r * rs_o + pos;
       soff[u] = ((r % RPR) * CPR + spos) * 16;
+      if constexpr (MLP) {
+        prow[u] = rc;
+        pch[u] = c * 8;
+      }
     }
+  }
+
+  // MLP: `Th_` addresses t like Qh addresses a; `stats`: the batch's pairs, readable up to a whole last tile;
+  // gamma, beta: this head's D values.  Whole workgroup; call before prefetch() (ends with a barrier).
+  LF_DEV void set_mlp(const u32x4* Th_, const void* stats, const float* gamma, const float* beta, float slope_) {
+    Th = Th_;
+    St = reinterpret_cast<const u32x4*>(stats);
+    slope = slope_;
+    float* aff = reinterpret_cast<float*>(smem + kAffOffset);
+    for (int i = threadIdx.x; i < 2 * D; i += 64 * W) aff[i] = i < D ? gamma[i] : beta[i - D];
+    __syncthreads();
   }
 
   LF_DEV unsigned char* region_ptr(int slot) const { return smem + slot * Sw::kSlotBytes + wave * Sw::kRegionBytes; }
@@ -387,6 +418,18 @@ struct ApplyWide {
       const int c = trow[u] < lim ? qoff[u] : 0;   // rows past N re-read chunk 0; never stored
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
                                        (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
+    }
+    if constexpr (MLP) {
+      const u32x4* tp = Th + tile * kTile * rs_q;
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        const int c = trow[u] < lim ? qoff[u] : 0;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tp + c),
+                                         (LF_LDS void*)(sl + kTOffset + u * 1024), 16, 0, 2 /* nt */);
+      }
+      const u32x4* sp = St + tile * (kTile / 2) + (lane & 15);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sp,
+                                       (LF_LDS void*)(smem + kStatOffset + slot * 1024), 16, 0, 0);
     }
   }
 
@@ -420,11 +463,38 @@ struct ApplyWide {
     for (int u = 0; u < NL; ++u) {
       const int at = u * 1024 + lane * 16;
       const u32x4 raw = *reinterpret_cast<const u32x4*>(sl + at);
+      u32x4 traw;
+      f32x2 rc;
+      float gg[8], bb[8];
+      if constexpr (MLP) {
+        traw = *reinterpret_cast<const u32x4*>(sl + kTOffset + at);
+        rc = *reinterpret_cast<const f32x2*>(smem + kStatOffset + slot * 1024 + prow[u] * 8);
+        const float* aff = reinterpret_cast<const float*>(smem + kAffOffset);
+        const f32x4 g0 = *reinterpret_cast<const f32x4*>(aff + pch[u]);
+        const f32x4 g1 = *reinterpret_cast<const f32x4*>(aff + pch[u] + 4);
+        const f32x4 b0 = *reinterpret_cast<const f32x4*>(aff + D + pch[u]);
+        const f32x4 b1 = *reinterpret_cast<const f32x4*>(aff + D + pch[u] + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          gg[e] = g0[e];
+          gg[4 + e] = g1[e];
+          bb[e] = b0[e];
+          bb[4 + e] = b1[e];
+        }
+      }
       u32x4 h4, l4;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         float x0, x1;
         unpack2<T>(raw[w], x0, x1);
+        if constexpr (MLP) {
+          float t0, t1;
+          unpack2<T>(traw[w], t0, t1);
+          const float y0 = __builtin_fmaf(gg[2 * w], __builtin_fmaf(t0, rc[0], rc[1]), bb[2 * w]);
+          const float y1 = __builtin_fmaf(gg[2 * w + 1], __builtin_fmaf(t1, rc[0], rc[1]), bb[2 * w + 1]);
+          x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
+          x1 += fmaxf(y1, slope * y1);
+        }
         const float r0 = phi<FM>(x0), r1 = phi<FM>(x1);
         if constexpr (NS == 1) {
           h4[w] = pack2<T>(r0, r1);
@@ -458,7 +528,7 @@ struct ApplyWide {
     {
       TileIter second = it;
       second.next();
-      if (second.valid()) wait_vmcnt<NL>();
+      if (second.valid()) wait_vmcnt<NLC>();
       else wait_vmcnt<0>();
     }
     if (it.valid()) phi_pass(0);
@@ -522,8 +592,9 @@ struct ApplyWide {
       it.next();
       ahead.next();
       if (it.valid()) {
-        if (have_prev && copied) wait_vmcnt<2 * NL>();
-        else if (have_prev || copied) wait_vmcnt<NL>();
+        if (have_prev && copied) wait_vmcnt<NL + NLC>();
+        else if (copied) wait_vmcnt<NLC>();
+        else if (have_prev) wait_vmcnt<NL>();
         else wait_vmcnt<0>();
         phi_pass(slot + 1 == R ? 0 : slot + 1);
       }

@@ -8,6 +8,7 @@
 #include "lf_host_api.hpp"
 #include "lf_mlp16.hpp"
 #include "lf_mlp_api.hpp"
+#include "lf_wide_api.hpp"
 
 namespace {
 
@@ -56,12 +57,15 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     p->W = 0;
     p->n_pad = n_tiles * lf::kTile;
     const long long units = (long long)B * H;
+    const bool wide = lfm::heads_wide(d);   // there every wave of a workgroup visits every tile of its blocks
     auto per_head = [&](int want_total, int blk_dflt, int* blk) {
       long long s = want_total / units;
-      if (s > (n_tiles + 3) / 4) s = (n_tiles + 3) / 4;          // four waves, a tile each at least
+      const long long most = wide ? n_tiles : (n_tiles + 3) / 4;  // four waves, a tile each at least
+      if (s > most) s = most;
       if (s < 1) s = 1;
       long long t = (n_tiles + s - 1) / s;
-      t = ((blk_dflt < t ? blk_dflt : t) + 3) / 4 * 4;            // a block is whole rounds of the four waves
+      t = blk_dflt < t ? blk_dflt : t;
+      if (!wide) t = (t + 3) / 4 * 4;                             // a block is whole rounds of the four waves
       *blk = (int)t;
       const long long g = (n_tiles + t - 1) / t;                  // blocks are dealt round-robin to the workgroups
       return (int)(g < s ? g : s);
@@ -70,17 +74,17 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     // workgroups a CU holds); measured at 1 M tokens, 10 heads of 64: 0.725 ms with 256 workgroups, 0.77 with 2048
     const int slot = (lf::kTile * d * 2 + 1023) / 1024 * 1024;
     const int lds_apply = (2 * 3 * slot + 3 * 1024) * lf::kWavesPerWG;
-    const int resident = 160 * 1024 / lds_apply > 0 ? 160 * 1024 / lds_apply : 1;
-    p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_MLPH_REDUCE_BLK", 8),
-                         &p->blk_reduce);
+    const int resident = (!wide && 160 * 1024 / lds_apply > 0) ? 160 * 1024 / lds_apply : 1;
+    p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 2 * kNumCU),
+                         lfh::env_int("LINFUSION_MLPH_REDUCE_BLK", wide ? 4 : 8), &p->blk_reduce);
     p->apply_wgs = per_head(lfh::env_int("LINFUSION_MLPH_APPLY_WGS", resident * kNumCU),
-                            lfh::env_int("LINFUSION_MLPH_APPLY_BLK", 8), &p->blk_apply);
+                            lfh::env_int("LINFUSION_MLPH_APPLY_BLK", wide ? 1 : 8), &p->blk_apply);
     long long sw = (N + 15) / 16, cap = lfh::env_int("LINFUSION_MLPH_STATS_WGS", 8 * kNumCU) / (2 * B);
     if (cap < 1) cap = 1;
     p->stats_wgs = (int)(sw < cap ? sw : cap);
     p->ws_partials = up((size_t)units * p->splits * p->ne * sizeof(float));
     p->ws_state = up((size_t)units * p->ne * sizeof(float));
-    p->ws_pack = up((size_t)units * pack_bytes(d, dtype));
+    p->ws_pack = up((size_t)units * (wide ? lfw::wide_packed_bytes(d, dtype) : pack_bytes(d, dtype)));
     p->ws_stats = up((size_t)2 * B * p->n_pad * 2 * sizeof(float));
     p->ws_total = p->ws_partials + p->ws_state + p->ws_pack + p->ws_stats;
     return LINFUSION_OK;

@@ -134,7 +134,7 @@ def test_run_to_run_identical():
 def test_rejected_arguments():
     code = wl.DTYPE_CODE
     assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 72, code["f16"]) == 0      # no kernel of that width
-    assert lf.linfusion_attn_mlp_workspace_bytes(1, 5, 100, 96, code["f16"]) == 0
+    assert lf.linfusion_attn_mlp_workspace_bytes(1, 5, 100, 112, code["f16"]) == 0
     assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 64, code["f16"]) > 0       # per-head kernels
     assert lf.linfusion_attn_mlp_workspace_bytes(1, 8, 100, 40, code["f32"]) == 0
     ins = [t.cuda() for t in wl.make_mlp_inputs(1, 8, 64, 40, "f16", idx=86)]
@@ -299,3 +299,52 @@ def test_per_head_route_strided_and_repeatable():
     assert torch.equal(obuf[:, :, C:].contiguous().view(torch.int16), dense.view(torch.int16))
     assert bool((obuf[:, :, :C] == 7.0).all())
     _check(dense, _oracle(ins, H, dtype), H, dtype, "mlp heads strided")
+
+
+# ---- head widths above 64 (SD-v1.5's third level: 8 heads of 160): statistics pass + the wide kernels ------------
+WIDE_SHAPES = [
+    (1, 8, 1000, 160, "f16"), (2, 8, 333, 160, "bf16"), (1, 4, 515, 128, "f16"), (1, 5, 2051, 96, "bf16"),
+    (1, 2, 1, 160, "f16"), (2, 3, 33, 96, "f16"), (1, 8, 4099, 160, "bf16"), (1, 1, 64, 128, "bf16"),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", WIDE_SHAPES)
+def test_wide_heads_match_oracle(B, H, N, d, dtype):
+    print(f"mlp wide B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=93)
+    out = _run(ins, H)
+    _check(out, _oracle(ins, H, dtype), H, dtype, f"mlp wide {B}x{H}x{N}x{d} {dtype}")
+
+
+@pytest.mark.parametrize("fm", [0, 1, 2])
+@pytest.mark.parametrize("unnorm", [False, True])
+def test_wide_heads_feature_maps_and_unnormalized(fm, unnorm):
+    B, H, N, d, dtype = 2, 8, 300, 160, "f16"
+    print(f"mlp wide fm={fm} unnorm={unnorm}", flush=True)
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=94))
+    if fm != 0:   # identity / relu: keep the denominators away from zero
+        ins[0] = (ins[0].float().abs() + 0.5).to(ins[0].dtype)
+        ins[2] = (ins[2].float().abs() + 0.5).to(ins[2].dtype)
+    if unnorm:
+        ins[4] = (ins[4].float() * 0.0625).to(ins[4].dtype)
+    out = _run(ins, H, fm=fm, flags=lf.FLAG_UNNORMALIZED if unnorm else 0)
+    _check(out, _oracle(ins, H, dtype, fm=fm, normalize=not unnorm), H, dtype, f"mlp wide fm={fm} unnorm={unnorm}")
+
+
+def test_wide_heads_strided_repeatable_and_far_from_zero_mean():
+    B, H, N, d, dtype = 2, 8, 515, 160, "bf16"
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=95))
+    for i in (1, 3):
+        ins[i] = (ins[i].float() * 0.5 + 40.0).to(ins[i].dtype)
+    C = H * d
+    dense = _run(ins, H)
+    assert torch.equal(_run(ins, H).view(torch.int16), dense.view(torch.int16))
+    _check(dense, _oracle(ins, H, dtype), H, dtype, "mlp wide, offset LayerNorm input")
+    wide = torch.cat([t.cuda() for t in ins[:5]], dim=2).contiguous()
+    views = [wide[:, :, i * C:(i + 1) * C] for i in range(5)]
+    obuf = torch.full((B, N, 2 * C), 7.0, dtype=wide.dtype, device="cuda")
+    lf.linfusion_attn_fwd_mlp_strided(*views, obuf[:, :, C:], *[t.cuda() for t in ins[5:]], H, 0, 1e-6, LN_EPS, SLOPE, 0,
+                                      _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    assert torch.equal(obuf[:, :, C:].contiguous().view(torch.int16), dense.view(torch.int16))
+    assert bool((obuf[:, :, :C] == 7.0).all())
