@@ -83,7 +83,7 @@ def test_random_mlp_fed_case_on_per_head_kernels_matches_oracle(seed):
     rng = np.random.default_rng(5500 + seed)
     dtype = ["f16", "bf16"][int(rng.integers(0, 2))]
     H = int(rng.choice([1, 2, 3, 5, 6, 8, 10, 12, 16, 20]))
-    d = int(rng.choice([56, 64, 80] if H == 8 else [8, 16, 24, 32, 40, 48, 56, 64, 80]))
+    d = int(rng.choice([56, 64, 80, 96, 128, 160] if H == 8 else [8, 16, 24, 32, 40, 48, 56, 64, 80, 96, 128, 160]))
     _random_mlp_case(500 + seed, rng, dtype, H, d)
 
 
