@@ -107,14 +107,15 @@ template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :
 // statistics come from the tile in LDS: every lane reduces the channels it holds of its token (mean and
 // centred sum of squares, exact in two passes over registers), the 2 W pieces per token meet in LDS and are
 // merged with the pairwise-variance formula -- one more workgroup barrier per tile, no extra memory pass.
-// MLP with PRE (per-head mode, for shapes whose token rows do not fit one workgroup): the row statistics were
-// computed by an earlier kernel, {rstd, -mean rstd} per token; a tile's 32 pairs travel with its copies as one
-// more deposit (256 bytes used) into a third ring.
+// MLP with PRE (for shapes whose token rows do not fit one workgroup; per-head mode, or row-piece mode on a group of
+// W of the row's heads): the row statistics were computed by an earlier kernel, {rstd, -mean rstd} per token; a
+// tile's 32 pairs travel with its copies as one more deposit (256 bytes used) into a third ring (row-piece mode:
+// every wave brings the same pairs to the same place, one deposit per slot).
 template <typename T, int D, int FM, bool NORM, int ROWS_W = 0, bool MLP = false, int DV = D, bool PRE = false>
 struct ApplyDma {
   static constexpr bool ROWS = ROWS_W > 0;
   static_assert(!MLP || ROWS || PRE, "the two-branch input needs whole token rows in one workgroup, or their statistics");
-  static_assert(!PRE || (MLP && !ROWS && DV == D), "precomputed row statistics serve the per-head two-branch kernel");
+  static_assert(!PRE || (MLP && DV == D), "precomputed row statistics serve the two-branch kernels");
   static_assert(DV == D || !ROWS, "unequal query and value widths run on the per-head kernel only");
   static constexpr int W = ROWS ? ROWS_W : kWavesPerWG;   // waves per workgroup
   static constexpr int NT = 64 * W;
@@ -287,7 +288,7 @@ struct ApplyDma {
       // lanes 0..15 bring the tile's 32 pairs, the others repeat them into the deposit's unused part
       const u32x4* sp = St + tile * (kTile / 2) + (lane & 15);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sp,
-                                       (LF_LDS void*)(smem + kStatOffset + (slot * W + wave) * 1024), 16, 0, 0);
+                                       (LF_LDS void*)(smem + kStatOffset + (ROWS ? slot : slot * W + wave) * 1024), 16, 0, 0);
     }
   }
 
@@ -486,7 +487,8 @@ struct ApplyDma {
     u32x4 traw[MLP ? KS : 1];      // MLP: this lane's chunks of t, raw
     float rstd = 0.0f, cn = 0.0f;   // MLP: LayerNorm(t) = t * rstd + cn
     if constexpr (PRE) {
-      const f32x2 rc = *reinterpret_cast<const f32x2*>(smem + kStatOffset + (slot * W + wave) * 1024 + tok * 8);
+      const f32x2 rc =
+          *reinterpret_cast<const f32x2*>(smem + kStatOffset + (ROWS ? slot : slot * W + wave) * 1024 + tok * 8);
       rstd = rc[0];
       cn = rc[1];
 #pragma unroll

@@ -22,8 +22,11 @@ template <typename T, int D, int W> struct ReduceMlpCfg {
   static constexpr int kTPR = Base::kThreadsW / kTile;                    // threads that reduce one row
   static_assert(kTPR == 8 || kTPR == 16, "a row's partials are reduced inside one wave by shuffles");
   // fp16 up to d = 40 fits 128 registers, so two 8-wave workgroups share a CU and cover each other's barrier
-  // waits (0.85 -> 0.67 ms at 2 M tokens); the other shapes would spill and keep one workgroup
-  static constexpr int kWavesPerSimd = (W == 8 && NSplit<T>::value == 1 && D <= 40) ? 4 : W / 4;
+  // waits (0.85 -> 0.67 ms at 2 M tokens); four heads of 80 in fp16 fit 256 (two 4-wave workgroups); the other
+  // shapes would spill and keep one workgroup
+  static constexpr int kWavesPerSimd = (W == 8 && NSplit<T>::value == 1 && D <= 40)
+                                           ? 4
+                                           : ((W == 4 && D == 80 && NSplit<T>::value == 1) ? 2 : W / 4);
 };
 
 // State reduction from the branch results of g'.  grid = (splits, B), block = 64 W, H = W heads.
@@ -31,11 +34,16 @@ template <typename T, int D, int W> struct ReduceMlpCfg {
 // row -> LDS -> barrier -> k = a + LeakyReLU(gamma (t - mean) rstd + beta), phi(k) and v into the heads' LDS tiles
 // -> barrier -> each wave its head's matrix-core products.  `row`: token stride in 16-byte units (= W D / 8 for
 // dense rows); a_k, t_k and v share it.
-template <typename T, int D, int FM, int W>
+// PRE (rows of gpb groups of W heads, too wide for one workgroup): grid = (splits, B * gpb), workgroup (x, y) takes
+// heads W (y % gpb) .. + W - 1 of batch y / gpb; the rows' {rstd, -mean rstd} come from an earlier kernel
+// (`stats`: [B][n_pad] pairs), loaded with the tile by the first 32 threads, and the two statistics levels are
+// skipped.  gamma, beta: all channels of a row.
+template <typename T, int D, int FM, int W, bool PRE = false>
 __global__ void __launch_bounds__(64 * W, (ReduceMlpCfg<T, D, W>::kWavesPerSimd))
 state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, const u32x4* __restrict__ V,
                    long long batch_stride, int row, const float* __restrict__ gamma, const float* __restrict__ beta,
-                   float ln_eps, float slope, float* __restrict__ partials, long long N, int tiles_per_block) {
+                   float ln_eps, float slope, float* __restrict__ partials, long long N, int tiles_per_block,
+                   int gpb = 1, const f32x2* __restrict__ stats = nullptr, long long n_pad = 0) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   using Sh = Shape16<D>;
   using RC = Reduce16Cfg<D>;
@@ -47,10 +55,15 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const long long b = blockIdx.y;
-  const u32x4* Ag = Ak + b * batch_stride;
-  const u32x4* Tg = Tk + b * batch_stride;
-  const u32x4* Vg = V + b * batch_stride;
+  const long long b = PRE ? blockIdx.y / gpb : blockIdx.y;
+  const int grp = PRE ? (int)(blockIdx.y % gpb) : 0;
+  const long long goff = b * batch_stride + (long long)grp * (W * D / 8);
+  const u32x4* Ag = Ak + goff;
+  const u32x4* Tg = Tk + goff;
+  const u32x4* Vg = V + goff;
+  const f32x2* sb = stats + b * n_pad;
+  gamma += grp * (W * D);
+  beta += grp * (W * D);
   uint16_t* lds = reinterpret_cast<uint16_t*>(smem);
   f32x2* part = reinterpret_cast<f32x2*>(smem + MC::kPartOffset);
   f32x2* rowstat = reinterpret_cast<f32x2*>(smem + MC::kRowOffset);
@@ -90,10 +103,15 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
   const u32x4 ones = {one2, one2, one2, one2};
 
   u32x4 ar[NL], tr[NL], vr[NL];
+  f32x2 srow_next = f32x2{0.0f, 0.0f};   // PRE: thread r < 32 carries row r's pair of the tile on its way
   auto issue_loads = [&](long long tile) {
     long long rem = N - tile * kTile;
     int lim = rem < kTile ? (int)rem : kTile;
     const long long base = tile * kTile * row;
+    if constexpr (PRE) {
+      srow_next = f32x2{0.0f, 0.0f};
+      if (tid < lim) srow_next = sb[tile * kTile + tid];
+    }
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
       if (trow[u] < lim) {
@@ -124,6 +142,10 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
   int buf = 0;
   while (it.valid()) {
     uint16_t* bufp = lds + buf * Cfg::kBufElems;
+    if constexpr (PRE) {
+      if (tid < kTile) rowstat[tid] = srow_next;
+      lds_barrier();
+    } else {
     // ---- LayerNorm statistics, level 1: mean and centred sum of squares of every 8-channel chunk ----
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
@@ -195,6 +217,7 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
       }
     }
     lds_barrier();
+    }
     // ---- k = a + LeakyReLU(LayerNorm(t)) -> phi -> 16-bit (hi [, lo]) -> the owning head's tiles ; V ----
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
@@ -264,7 +287,8 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
   }
 
   // ---- each wave owns a whole partial (lane: rows 4 (l / 16) + i, column l % 16 of each 16 x 16 block) ----
-  float* dst = partials + (((b * W + wave) * gridDim.x) + blockIdx.x) * (long long)(D * D + D);
+  const long long head = PRE ? (b * gpb + grp) * W + wave : b * W + wave;   // (b * H + first head of the group + wave)
+  float* dst = partials + ((head * gridDim.x) + blockIdx.x) * (long long)(D * D + D);
 #pragma unroll
   for (int a = 0; a < MT; ++a) {
 #pragma unroll
@@ -283,6 +307,13 @@ state_reduce16_mlp(const u32x4* __restrict__ Ak, const u32x4* __restrict__ Tk, c
       }
     }
   }
+}
+
+// Apply on a group of W of a row's heads with the rows' statistics from an earlier kernel.  grid = (wgs, B * gpb),
+// block = 64 W; `packed`: all heads' operand-ready states; `stats`: this branch's [B][n_pad] pairs.
+template <typename T, int D>
+constexpr int apply16_mlpg_lds_bytes(int waves) {
+  return 2 * ApplyDmaCfg<D>::kRing * ApplyDmaCfg<D>::kSlotBytes * waves + ApplyDmaCfg<D>::kRing * 1024;
 }
 
 template <typename T, int D>
@@ -306,6 +337,26 @@ apply16_mlp(const u32x4* __restrict__ Aq, const u32x4* __restrict__ Tq, long lon
   ap.set_mlp(Tq + b * batch_q, gamma, beta, ln_eps, slope);
   ap.prefetch();
   ap.load_packed(packed + (b * W + wave) * Pack16<T, D>::kHeadBytes, eps);
+  ap.stream();
+}
+
+template <typename T, int D, int FM, bool NORM, int W>
+__global__ void __launch_bounds__(64 * W)
+apply16_mlpg(const u32x4* __restrict__ Aq, const u32x4* __restrict__ Tq, long long batch_q, int row_q,
+             u32x4* __restrict__ O, long long batch_o, int row_o, int gpb, const f32x2* __restrict__ stats,
+             long long n_pad, const float* __restrict__ gamma, const float* __restrict__ beta, float slope,
+             const unsigned char* __restrict__ packed, float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const long long b = blockIdx.y / gpb;
+  const int grp = (int)(blockIdx.y % gpb);
+  const long long in_row = (long long)grp * (W * D / 8);   // the group's place inside a token row, 16-byte units
+  ApplyDma<T, D, FM, NORM, W, true, D, true> ap(Aq + b * batch_q + in_row, row_q, O + b * batch_o + in_row, row_o, N,
+                                               tiles_per_block, blockIdx.x, gridDim.x, smem);
+  ap.set_mlp(Tq + b * batch_q + in_row, gamma + grp * (W * D), beta + grp * (W * D), 0.0f, slope);
+  ap.set_stats(stats + b * n_pad);
+  ap.prefetch();
+  ap.load_packed(packed + ((b * gpb + grp) * W + wave) * Pack16<T, D>::kHeadBytes, eps);
   ap.stream();
 }
 

@@ -22,6 +22,8 @@ struct HeadsArgs {
   void* stats;                                       // [2][B][n_pad] pairs of floats
   long long n_pad;                                   // N rounded up to whole 32-token tiles
   int stats_wgs, splits, blk_reduce, apply_wgs, blk_apply;
+  bool apply_wide;                                   // d = 80: per-head reduction, wide apply (four waves)
+  bool grouped;                                      // row-piece kernels on groups of four heads (heads_grouped)
   hipStream_t st;
   hipEvent_t* ev;             // null, or four events: before the first kernel, after the reduction, after
                               // combine + packing, after apply
@@ -31,6 +33,11 @@ struct HeadsArgs {
 // then has lfw::wide_packed_bytes per head and a tile block need not be whole rounds of four waves)
 bool heads_supported(int d);
 bool heads_wide(int d);
+// shapes the row-piece kernels on groups of four neighbouring heads take: head rows that are no whole 128-byte
+// lines (the per-head kernels would fetch every line twice) in rows of whole groups
+bool heads_grouped(int H, int d);
+// d = 80 with the wide apply: bytes per head of its operand-ready state
+size_t heads_packed_bytes(int d, int dtype);
 // enqueues statistics, state reduction, combine, pack and apply; returns LINFUSION_OK or a LINFUSION_ERR_* code
 int run_heads(const HeadsArgs& a);
 

@@ -15,9 +15,11 @@ namespace {
 constexpr int kNumCU = 256;
 
 struct MlpPlan {
-  int route;                      // 0: whole token rows in one workgroup; 1: per-head kernels + statistics pass
+  int route;                      // 0: whole token rows in one workgroup; 1: per-head kernels + statistics pass;
+                                  // 2: statistics pass + row-piece kernels on groups of four heads
   long long n_pad;                // route 1: tokens rounded up to whole tiles
   int stats_wgs;
+  bool apply_wide;                // route 1, d = 80: the wide apply kernel behind the per-head reduction
   size_t ws_stats;
   int W;                          // heads = waves per workgroup
   int splits, blk_reduce;         // state reduction: workgroups per batch, tiles per block
@@ -50,8 +52,44 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
   const long long n_tiles = (N + lf::kTile - 1) / lf::kTile;
   p->ne = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-  // LINFUSION_MLP_ROUTE=1 sends the shapes of the whole-row kernels the per-head way too (a test aid)
-  p->route = (rows_supported(H, d) && lfh::env_int("LINFUSION_MLP_ROUTE", 0) != 1) ? 0 : 1;
+  // LINFUSION_MLP_ROUTE=1 sends every shape the per-head way, =2 every shape with whole groups of four heads
+  // through the group kernels (test aids)
+  const int forced = lfh::env_int("LINFUSION_MLP_ROUTE", 0);
+  const bool groupable = lfm::heads_grouped(H, d);
+  p->route = forced == 1 ? 1 : ((forced == 2 && groupable) ? 2 : (rows_supported(H, d) ? 0 : (groupable ? 2 : 1)));
+  if (p->route == 2) {
+    // as the whole-row plan below with B * (H / 4) units of four heads; the apply kernel's rings leave room for
+    // one workgroup per CU from d = 40 on
+    if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;
+    p->W = 4;
+    p->apply_wide = false;
+    p->n_pad = n_tiles * lf::kTile;
+    const long long units = (long long)B * (H / 4);
+    auto per_group = [&](int want_total, int blk_dflt, int* blk) {
+      long long s = want_total / units;
+      if (s > n_tiles) s = n_tiles;
+      if (s < 1) s = 1;
+      long long t = (n_tiles + s - 1) / s;
+      *blk = (int)(blk_dflt < t ? blk_dflt : t);
+      return (int)((n_tiles + t - 1) / t);
+    };
+    const int slot = (lf::kTile * d * 2 + 1023) / 1024 * 1024;
+    const int lds_apply = 2 * 3 * slot * 4 + 3 * 1024;
+    const int resident = 160 * 1024 / lds_apply > 0 ? 160 * 1024 / lds_apply : 1;
+    p->splits = per_group(lfh::env_int("LINFUSION_MLPG_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_MLPG_REDUCE_BLK", 2),
+                          &p->blk_reduce);
+    p->apply_wgs = per_group(lfh::env_int("LINFUSION_MLPG_APPLY_WGS", resident * kNumCU),
+                             lfh::env_int("LINFUSION_MLPG_APPLY_BLK", 2), &p->blk_apply);
+    long long sw = (N + 15) / 16, cap = lfh::env_int("LINFUSION_MLPH_STATS_WGS", 8 * kNumCU) / (2 * B);
+    if (cap < 1) cap = 1;
+    p->stats_wgs = (int)(sw < cap ? sw : cap);
+    p->ws_partials = up((size_t)B * H * p->splits * p->ne * sizeof(float));
+    p->ws_state = up((size_t)B * H * p->ne * sizeof(float));
+    p->ws_pack = up((size_t)B * H * pack_bytes(d, dtype));
+    p->ws_stats = up((size_t)2 * B * p->n_pad * 2 * sizeof(float));
+    p->ws_total = p->ws_partials + p->ws_state + p->ws_pack + p->ws_stats;
+    return LINFUSION_OK;
+  }
   if (p->route == 1) {
     if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;   // grid.y limit
     p->W = 0;
@@ -74,7 +112,8 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     // workgroups a CU holds); measured at 1 M tokens, 10 heads of 64: 0.725 ms with 256 workgroups, 0.77 with 2048
     const int slot = (lf::kTile * d * 2 + 1023) / 1024 * 1024;
     const int lds_apply = (2 * 3 * slot + 3 * 1024) * lf::kWavesPerWG;
-    const int resident = (!wide && 160 * 1024 / lds_apply > 0) ? 160 * 1024 / lds_apply : 1;
+    p->apply_wide = d == 80 && lfh::env_int("LINFUSION_MLPH_D80_WIDE_APPLY", 1) == 1;
+    const int resident = p->apply_wide ? 2 : ((!wide && 160 * 1024 / lds_apply > 0) ? 160 * 1024 / lds_apply : 1);
     p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 2 * kNumCU),
                          lfh::env_int("LINFUSION_MLPH_REDUCE_BLK", wide ? 4 : 8), &p->blk_reduce);
     p->apply_wgs = per_head(lfh::env_int("LINFUSION_MLPH_APPLY_WGS", resident * kNumCU),
@@ -84,7 +123,9 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     p->stats_wgs = (int)(sw < cap ? sw : cap);
     p->ws_partials = up((size_t)units * p->splits * p->ne * sizeof(float));
     p->ws_state = up((size_t)units * p->ne * sizeof(float));
-    p->ws_pack = up((size_t)units * (wide ? lfw::wide_packed_bytes(d, dtype) : pack_bytes(d, dtype)));
+    size_t per_head_pack = wide ? lfw::wide_packed_bytes(d, dtype) : pack_bytes(d, dtype);
+    if (lfm::heads_packed_bytes(d, dtype) > per_head_pack) per_head_pack = lfm::heads_packed_bytes(d, dtype);
+    p->ws_pack = up((size_t)units * per_head_pack);
     p->ws_stats = up((size_t)2 * B * p->n_pad * 2 * sizeof(float));
     p->ws_total = p->ws_partials + p->ws_state + p->ws_pack + p->ws_stats;
     return LINFUSION_OK;
@@ -92,6 +133,7 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
   p->W = H;
   p->n_pad = 0;
   p->stats_wgs = 0;
+  p->apply_wide = false;
   p->ws_stats = 0;
   auto per_batch = [&](int want_total, int blk_dflt, int* blk) {
     long long s = want_total / B;
@@ -268,13 +310,13 @@ static int mlp_impl(const void* a_q, const void* t_q, const void* a_k, const voi
   if (overlaps(workspace, p.ws_total, out, obytes)) return LINFUSION_ERR_OVERLAP;
   rc = lfh::check_device();
   if (rc != LINFUSION_OK) return rc;
-  if (p.route == 1) {
+  if (p.route != 0) {
     unsigned char* ws = (unsigned char*)workspace;
     lfm::HeadsArgs h{a_q, t_q, a_k, t_k, v, out, gamma_q, beta_q, gamma_k, beta_k, B, H, N, d, dtype, feature_map, eps,
                      ln_eps, slope, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0, si[0] / 8, si[1] / 8, so[0] / 8,
                      so[1] / 8, reinterpret_cast<float*>(ws), reinterpret_cast<float*>(ws + p.ws_partials),
                      ws + p.ws_partials + p.ws_state, ws + p.ws_partials + p.ws_state + p.ws_pack, p.n_pad,
-                     p.stats_wgs, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, (hipStream_t)stream,
+                     p.stats_wgs, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, p.apply_wide, p.route == 2, (hipStream_t)stream,
                      reinterpret_cast<hipEvent_t*>(events)};
     return lfm::run_heads(h);
   }

@@ -6,6 +6,7 @@
 
 #include "lf_host_api.hpp"
 #include "lf_mlp_api.hpp"
+#include "lf_mlp16.hpp"
 #include "lf_mlph16.hpp"
 #include "lf_mlpw16.hpp"
 
@@ -50,16 +51,22 @@ int run_heads_t(const HeadsArgs& a) {
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
-// head widths above 64: the wide kernels, eight waves per apply workgroup
-template <typename T, int D, int FM, bool NORM>
+// head widths above 64: the wide kernels, eight waves per apply workgroup.  d = 80 (WA = 4): its state still fits
+// one wave's accumulators, so the reduction is the per-head one; the apply is the wide one, whose workgroup-wide
+// slots leave room for two workgroups per CU where the per-head kernel's three rings per wave leave room for one.
+template <typename T, int D, int FM, bool NORM, int WA = 8>
 int run_wide_t(const HeadsArgs& a) {
   using namespace lf;
-  constexpr int NE = D * D + D, WA = 8;
-  constexpr int lds_r = reduce16_wide_mlp_lds_bytes<T, D>();
+  constexpr int NE = D * D + D;
+  constexpr bool kWideReduce = D > 80;
   constexpr int lds_a = ApplyWide<T, D, FM, NORM, WA, true>::kLdsBytes;
-  static_assert(lds_r <= 160 * 1024 && lds_a <= 160 * 1024, "workgroup LDS limit of the device");
-  if (!allow_lds(state_reduce16_wide_mlp<T, D, FM>, lds_r) || !allow_lds(apply16_wide_mlp<T, D, FM, NORM, WA>, lds_a))
-    return LINFUSION_ERR_HIP;
+  static_assert(lds_a <= 160 * 1024, "workgroup LDS limit of the device");
+  if (!allow_lds(apply16_wide_mlp<T, D, FM, NORM, WA>, lds_a)) return LINFUSION_ERR_HIP;
+  if constexpr (kWideReduce) {
+    if (!allow_lds(state_reduce16_wide_mlp<T, D, FM>, reduce16_wide_mlp_lds_bytes<T, D>())) return LINFUSION_ERR_HIP;
+  } else {
+    if (!allow_lds(state_reduce16_mlph<T, D, FM>, reduce16_mlph_lds_bytes<T, D>())) return LINFUSION_ERR_HIP;
+  }
   hipStream_t st = a.st;
   const int row = (int)a.in_row, row_o = (int)a.out_row;
   const unsigned heads = (unsigned)(a.B * a.H);
@@ -68,9 +75,15 @@ int run_wide_t(const HeadsArgs& a) {
   if (a.ev) (void)hipEventRecord(a.ev[0], st);
   mlp_rowstats16<T><<<dim3(a.stats_wgs, 2u * a.B), dim3(kThreads), 0, st>>>(
       (const u32x4*)a.t_q, (const u32x4*)a.t_k, a.in_batch, row, a.H * D / 8, a.ln_eps, a.N, a.n_pad, stats_q);
-  state_reduce16_wide_mlp<T, D, FM><<<dim3(a.splits, heads), dim3(kThreads), lds_r, st>>>(
-      (const u32x4*)a.a_k, (const u32x4*)a.t_k, (const u32x4*)a.v, a.in_batch, row, a.H, stats_k, a.n_pad, a.gamma_k,
-      a.beta_k, a.slope, a.partials, a.N, a.blk_reduce);
+  if constexpr (kWideReduce) {
+    state_reduce16_wide_mlp<T, D, FM><<<dim3(a.splits, heads), dim3(kThreads), reduce16_wide_mlp_lds_bytes<T, D>(), st>>>(
+        (const u32x4*)a.a_k, (const u32x4*)a.t_k, (const u32x4*)a.v, a.in_batch, row, a.H, stats_k, a.n_pad, a.gamma_k,
+        a.beta_k, a.slope, a.partials, a.N, a.blk_reduce);
+  } else {
+    state_reduce16_mlph<T, D, FM><<<dim3(a.splits, heads), dim3(kThreads), reduce16_mlph_lds_bytes<T, D>(), st>>>(
+        (const u32x4*)a.a_k, (const u32x4*)a.t_k, (const u32x4*)a.v, a.in_batch, row, a.H, stats_k, a.n_pad, a.gamma_k,
+        a.beta_k, a.slope, a.partials, a.N, a.blk_reduce);
+  }
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
   combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, heads), dim3(kCombineThreads), 0, st>>>(
       a.partials, a.splits, NE, a.state);
@@ -84,12 +97,58 @@ int run_wide_t(const HeadsArgs& a) {
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
-template <typename T, int D>
+template <typename T, int D, int WA = 8>
 int run_wide_fm(const HeadsArgs& a) {
   switch (a.fm) {
-    case 0: return a.unnorm ? run_wide_t<T, D, 0, false>(a) : run_wide_t<T, D, 0, true>(a);
-    case 1: return a.unnorm ? run_wide_t<T, D, 1, false>(a) : run_wide_t<T, D, 1, true>(a);
-    default: return a.unnorm ? run_wide_t<T, D, 2, false>(a) : run_wide_t<T, D, 2, true>(a);
+    case 0: return a.unnorm ? run_wide_t<T, D, 0, false, WA>(a) : run_wide_t<T, D, 0, true, WA>(a);
+    case 1: return a.unnorm ? run_wide_t<T, D, 1, false, WA>(a) : run_wide_t<T, D, 1, true, WA>(a);
+    default: return a.unnorm ? run_wide_t<T, D, 2, false, WA>(a) : run_wide_t<T, D, 2, true, WA>(a);
+  }
+}
+
+// groups of four neighbouring heads (row-piece kernels): for head rows that are no whole 128-byte lines
+template <typename T, int D, int FM, bool NORM>
+int run_groups_t(const HeadsArgs& a) {
+  using namespace lf;
+  constexpr int NE = D * D + D, W = 4;
+  constexpr int lds_r = ReduceMlpCfg<T, D, W>::kLdsBytes;
+  constexpr int lds_p = apply16_dma_lds_bytes<T, D>();
+  constexpr int lds_a = apply16_mlpg_lds_bytes<T, D>(W);
+  static_assert(lds_r <= 160 * 1024 && lds_a <= 160 * 1024, "workgroup LDS limit of the device");
+  static_assert(Pack16<T, D>::kFrags == NSplit<T>::value * ((D / 2 + 2 + 15) / 16) * ((D / 8 + 1) / 2),
+                "the planner's workspace size formula must match the packed layout");
+  if (!allow_lds(state_reduce16_mlp<T, D, FM, W, true>, lds_r) || !allow_lds(pack_state16<T, D, NORM>, lds_p) ||
+      !allow_lds(apply16_mlpg<T, D, FM, NORM, W>, lds_a))
+    return LINFUSION_ERR_HIP;
+  hipStream_t st = a.st;
+  const int row = (int)a.in_row, row_o = (int)a.out_row, gpb = a.H / W;
+  const unsigned heads = (unsigned)(a.B * a.H), groups = (unsigned)(a.B * gpb);
+  f32x2* stats_q = reinterpret_cast<f32x2*>(a.stats);
+  f32x2* stats_k = stats_q + (long long)a.B * a.n_pad;
+  if (a.ev) (void)hipEventRecord(a.ev[0], st);
+  mlp_rowstats16<T><<<dim3(a.stats_wgs, 2u * a.B), dim3(kThreads), 0, st>>>(
+      (const u32x4*)a.t_q, (const u32x4*)a.t_k, a.in_batch, row, a.H * D / 8, a.ln_eps, a.N, a.n_pad, stats_q);
+  state_reduce16_mlp<T, D, FM, W, true><<<dim3(a.splits, groups), dim3(64 * W), lds_r, st>>>(
+      (const u32x4*)a.a_k, (const u32x4*)a.t_k, (const u32x4*)a.v, a.in_batch, row, a.gamma_k, a.beta_k, a.ln_eps, a.slope,
+      a.partials, a.N, a.blk_reduce, gpb, stats_k, a.n_pad);
+  if (a.ev) (void)hipEventRecord(a.ev[1], st);
+  combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, heads), dim3(kCombineThreads), 0, st>>>(
+      a.partials, a.splits, NE, a.state);
+  pack_state16<T, D, NORM><<<dim3(heads), dim3(kThreads), lds_p, st>>>(a.state, a.packed);
+  if (a.ev) (void)hipEventRecord(a.ev[2], st);
+  apply16_mlpg<T, D, FM, NORM, W><<<dim3(a.apply_wgs, groups), dim3(64 * W), lds_a, st>>>(
+      (const u32x4*)a.a_q, (const u32x4*)a.t_q, a.in_batch, row, (u32x4*)a.out, a.out_batch, row_o, gpb, stats_q, a.n_pad,
+      a.gamma_q, a.beta_q, a.slope, a.packed, a.eps, a.N, a.blk_apply);
+  if (a.ev) (void)hipEventRecord(a.ev[3], st);
+  return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+}
+
+template <typename T, int D>
+int run_groups_fm(const HeadsArgs& a) {
+  switch (a.fm) {
+    case 0: return a.unnorm ? run_groups_t<T, D, 0, false>(a) : run_groups_t<T, D, 0, true>(a);
+    case 1: return a.unnorm ? run_groups_t<T, D, 1, false>(a) : run_groups_t<T, D, 1, true>(a);
+    default: return a.unnorm ? run_groups_t<T, D, 2, false>(a) : run_groups_t<T, D, 2, true>(a);
   }
 }
 
@@ -108,9 +167,25 @@ namespace lfm {
 
 bool heads_supported(int d) { return d >= 8 && d % 8 == 0 && (d <= 64 || d == 80 || heads_wide(d)); }
 bool heads_wide(int d) { return d == 96 || d == 128 || d == 160; }
+bool heads_grouped(int H, int d) { return H % 4 == 0 && d >= 8 && d % 8 == 0 && (d <= 56 || d == 80); }
+
+size_t heads_packed_bytes(int d, int dtype) {
+  if (d == 80)
+    return dtype == LINFUSION_DTYPE_F16 ? lf::PackWide<lf::F16, 80, 4>::kHeadBytes : lf::PackWide<lf::BF16, 80, 4>::kHeadBytes;
+  return 0;
+}
 
 int run_heads(const HeadsArgs& a) {
   const bool f16 = a.dtype == LINFUSION_DTYPE_F16;
+  if (a.grouped) {
+    switch (a.d) {
+#define X(DD) case DD: return f16 ? run_groups_fm<lf::F16, DD>(a) : run_groups_fm<lf::BF16, DD>(a);
+      X(8) X(16) X(24) X(32) X(40) X(48) X(56) X(80)
+#undef X
+    }
+    return LINFUSION_ERR_UNSUPPORTED;
+  }
+  if (a.d == 80 && a.apply_wide) return f16 ? run_wide_fm<lf::F16, 80, 4>(a) : run_wide_fm<lf::BF16, 80, 4>(a);
   switch (a.d) {
 #define X(DD) case DD: return f16 ? run_heads_fm<lf::F16, DD>(a) : run_heads_fm<lf::BF16, DD>(a);
     X(8) X(16) X(24) X(32) X(40) X(48) X(56) X(64) X(80)

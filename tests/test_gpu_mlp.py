@@ -255,8 +255,27 @@ def test_per_head_route_on_whole_row_shapes(B, H, N, d, dtype, monkeypatch):
     rows = _run(ins, H)
     monkeypatch.setenv("LINFUSION_MLP_ROUTE", "1")
     heads = _run(ins, H)
+    monkeypatch.setenv("LINFUSION_MLP_ROUTE", "2")     # statistics pass + row-piece kernels on groups of four heads
+    groups = _run(ins, H)
     monkeypatch.delenv("LINFUSION_MLP_ROUTE")
     _check(rows, ref, H, dtype, "whole rows")
+    _check(heads, ref, H, dtype, "per head")
+    _check(groups, ref, H, dtype, "groups of four heads")
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 8, 777, 80, "f16"), (2, 8, 2051, 80, "bf16"), (1, 16, 257, 48, "f16"),
+                                           (1, 12, 130, 32, "bf16"), (1, 8, 1000, 56, "f16")])
+def test_group_shapes_on_the_per_head_kernels(B, H, N, d, dtype, monkeypatch):
+    """Rows of whole groups of four heads whose head rows are no whole cache lines go through the group kernels by
+    default (covered by the per-head shape list above); the per-head kernels must serve them too."""
+    print(f"mlp group shape forced per head B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=97)
+    ref = _oracle(ins, H, dtype)
+    groups = _run(ins, H)
+    monkeypatch.setenv("LINFUSION_MLP_ROUTE", "1")
+    heads = _run(ins, H)
+    monkeypatch.delenv("LINFUSION_MLP_ROUTE")
+    _check(groups, ref, H, dtype, "groups of four heads")
     _check(heads, ref, H, dtype, "per head")
 
 
