@@ -345,11 +345,22 @@ def main():
         # t_k once more) and per-head kernels: the first timed interval then covers statistics + reduction
         whole_rows = ((H == 8 and d <= 48) or (H == 4 and (d <= 64 or d == 80))) and \
             os.environ.get("LINFUSION_MLP_ROUTE", "0") != "1"
-        rname = "state_reduce16_mlp" if whole_rows else "mlp_rowstats16 + state_reduce16_mlph"
-        aname = "apply16_mlp" if whole_rows else "apply16_mlph"
+        forced = os.environ.get("LINFUSION_MLP_ROUTE", "0")
+        if whole_rows and forced != "2":
+            route, rname, aname = "whole token rows per workgroup", "state_reduce16_mlp", "apply16_mlp"
+        elif forced != "1" and H % 4 == 0 and (d <= 56 or d == 80):
+            route = "statistics pass + row-piece kernels on groups of four heads"
+            rname, aname = "mlp_rowstats16 + state_reduce16_mlp<PRE>", "apply16_mlpg"
+            whole_rows = False
+        elif d > 80:
+            route = "statistics pass + wide kernels"
+            rname, aname = "mlp_rowstats16 + state_reduce16_wide_mlp", "apply16_wide_mlp"
+        else:
+            route = "statistics pass + per-head kernels"
+            rname, aname = "mlp_rowstats16 + state_reduce16_mlph", "apply16_mlph"
         rpasses = 3 if whole_rows else 5
         result["mlp"] = {
-            "route": "whole token rows per workgroup" if whole_rows else "statistics pass + per-head kernels",
+            "route": route,
             "kernel_tensor_passes": 6 if whole_rows else 8,
             "ms_per_step": mdt * 1e3, "interleaved_ms_per_step": sdt * 1e3, "tokens_per_s": B * N / mdt, "alg_bytes": 6 * tensor_bytes,
             "hbm_gbps": 6 * tensor_bytes / mdt / 1e9, "hbm_frac_of_peak": 6 * tensor_bytes / mdt / 1e9 / HBM_PEAK_GBPS,

@@ -217,7 +217,8 @@ size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int 
  * channels of token i.  q and k are formed inside the state-reduction and apply kernels and never exist in
  * memory: where one workgroup can hold whole token rows (H = 8 with d <= 48, H = 4 with d <= 64 or 80) the
  * call reads five tensors and writes one; for every other shape a pass over t_q and t_k first leaves the
- * rows' LayerNorm statistics (8 bytes per token and branch) in the workspace, two tensor reads more.
+ * rows' LayerNorm statistics (8 bytes per token and branch) in the workspace, two tensor reads more, and the
+ * reduction and apply kernels work on groups of four heads, on single heads, or (d > 80) on the wide kernels.
  *
  *   a_q, t_q, a_k, t_k, v   DEVICE pointers, token-major contiguous [B, N, H*d] (head h owns channels
  *                           h*d .. h*d+d-1 of a token), fp16 or bf16, 16-byte aligned.

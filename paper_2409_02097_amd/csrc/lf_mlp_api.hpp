@@ -1,5 +1,5 @@
 // Host-side interface between linfusion_mlp.hip (boundary and planning of the MLP-fed mixer, kernels for whole
-// token rows in one workgroup) and linfusion_mlph.hip (the per-head kernels with a statistics pass).
+// token rows in one workgroup) and linfusion_mlph.hip (the routes that start with a statistics pass).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -22,7 +22,6 @@ struct HeadsArgs {
   void* stats;                                       // [2][B][n_pad] pairs of floats
   long long n_pad;                                   // N rounded up to whole 32-token tiles
   int stats_wgs, splits, blk_reduce, apply_wgs, blk_apply;
-  bool apply_wide;                                   // d = 80: per-head reduction, wide apply (four waves)
   bool grouped;                                      // row-piece kernels on groups of four heads (heads_grouped)
   hipStream_t st;
   hipEvent_t* ev;             // null, or four events: before the first kernel, after the reduction, after
@@ -36,8 +35,6 @@ bool heads_wide(int d);
 // shapes the row-piece kernels on groups of four neighbouring heads take: head rows that are no whole 128-byte
 // lines (the per-head kernels would fetch every line twice) in rows of whole groups
 bool heads_grouped(int H, int d);
-// d = 80 with the wide apply: bytes per head of its operand-ready state
-size_t heads_packed_bytes(int d, int dtype);
 // enqueues statistics, state reduction, combine, pack and apply; returns LINFUSION_OK or a LINFUSION_ERR_* code
 int run_heads(const HeadsArgs& a);
 

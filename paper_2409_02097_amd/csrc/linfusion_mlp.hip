@@ -19,7 +19,6 @@ struct MlpPlan {
                                   // 2: statistics pass + row-piece kernels on groups of four heads
   long long n_pad;                // route 1: tokens rounded up to whole tiles
   int stats_wgs;
-  bool apply_wide;                // route 1, d = 80: the wide apply kernel behind the per-head reduction
   size_t ws_stats;
   int W;                          // heads = waves per workgroup
   int splits, blk_reduce;         // state reduction: workgroups per batch, tiles per block
@@ -62,7 +61,6 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     // one workgroup per CU from d = 40 on
     if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;
     p->W = 4;
-    p->apply_wide = false;
     p->n_pad = n_tiles * lf::kTile;
     const long long units = (long long)B * (H / 4);
     auto per_group = [&](int want_total, int blk_dflt, int* blk) {
@@ -112,8 +110,7 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     // workgroups a CU holds); measured at 1 M tokens, 10 heads of 64: 0.725 ms with 256 workgroups, 0.77 with 2048
     const int slot = (lf::kTile * d * 2 + 1023) / 1024 * 1024;
     const int lds_apply = (2 * 3 * slot + 3 * 1024) * lf::kWavesPerWG;
-    p->apply_wide = d == 80 && lfh::env_int("LINFUSION_MLPH_D80_WIDE_APPLY", 1) == 1;
-    const int resident = p->apply_wide ? 2 : ((!wide && 160 * 1024 / lds_apply > 0) ? 160 * 1024 / lds_apply : 1);
+    const int resident = (!wide && 160 * 1024 / lds_apply > 0) ? 160 * 1024 / lds_apply : 1;
     p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 2 * kNumCU),
                          lfh::env_int("LINFUSION_MLPH_REDUCE_BLK", wide ? 4 : 8), &p->blk_reduce);
     p->apply_wgs = per_head(lfh::env_int("LINFUSION_MLPH_APPLY_WGS", resident * kNumCU),
@@ -123,9 +120,7 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     p->stats_wgs = (int)(sw < cap ? sw : cap);
     p->ws_partials = up((size_t)units * p->splits * p->ne * sizeof(float));
     p->ws_state = up((size_t)units * p->ne * sizeof(float));
-    size_t per_head_pack = wide ? lfw::wide_packed_bytes(d, dtype) : pack_bytes(d, dtype);
-    if (lfm::heads_packed_bytes(d, dtype) > per_head_pack) per_head_pack = lfm::heads_packed_bytes(d, dtype);
-    p->ws_pack = up((size_t)units * per_head_pack);
+    p->ws_pack = up((size_t)units * (wide ? lfw::wide_packed_bytes(d, dtype) : pack_bytes(d, dtype)));
     p->ws_stats = up((size_t)2 * B * p->n_pad * 2 * sizeof(float));
     p->ws_total = p->ws_partials + p->ws_state + p->ws_pack + p->ws_stats;
     return LINFUSION_OK;
@@ -133,7 +128,6 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
   p->W = H;
   p->n_pad = 0;
   p->stats_wgs = 0;
-  p->apply_wide = false;
   p->ws_stats = 0;
   auto per_batch = [&](int want_total, int blk_dflt, int* blk) {
     long long s = want_total / B;
@@ -316,7 +310,7 @@ static int mlp_impl(const void* a_q, const void* t_q, const void* a_k, const voi
                      ln_eps, slope, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0, si[0] / 8, si[1] / 8, so[0] / 8,
                      so[1] / 8, reinterpret_cast<float*>(ws), reinterpret_cast<float*>(ws + p.ws_partials),
                      ws + p.ws_partials + p.ws_state, ws + p.ws_partials + p.ws_state + p.ws_pack, p.n_pad,
-                     p.stats_wgs, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, p.apply_wide, p.route == 2, (hipStream_t)stream,
+                     p.stats_wgs, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply, p.route == 2, (hipStream_t)stream,
                      reinterpret_cast<hipEvent_t*>(events)};
     return lfm::run_heads(h);
   }

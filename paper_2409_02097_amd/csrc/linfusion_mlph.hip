@@ -1,5 +1,6 @@
-// Sixth translation unit of the library: the MLP-fed mixer on per-head kernels (lf_mlph16.hpp), for the shapes
-// whose token rows do not fit one workgroup.
+// Sixth translation unit of the library: the MLP-fed mixer for the shapes whose token rows do not fit one
+// workgroup.  A statistics pass (mlp_rowstats16), then per shape: row-piece kernels on groups of four heads
+// (lf_mlp16.hpp), per-head kernels (lf_mlph16.hpp), or the wide kernels for widths above 64 (lf_mlpw16.hpp).
 #include "../../include/linfusion.h"
 
 #include <stdint.h>
@@ -51,22 +52,16 @@ int run_heads_t(const HeadsArgs& a) {
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
-// head widths above 64: the wide kernels, eight waves per apply workgroup.  d = 80 (WA = 4): its state still fits
-// one wave's accumulators, so the reduction is the per-head one; the apply is the wide one, whose workgroup-wide
-// slots leave room for two workgroups per CU where the per-head kernel's three rings per wave leave room for one.
-template <typename T, int D, int FM, bool NORM, int WA = 8>
+// head widths above 64: the wide kernels, eight waves per apply workgroup
+template <typename T, int D, int FM, bool NORM>
 int run_wide_t(const HeadsArgs& a) {
   using namespace lf;
-  constexpr int NE = D * D + D;
-  constexpr bool kWideReduce = D > 80;
+  constexpr int NE = D * D + D, WA = 8;
+  constexpr int lds_r = reduce16_wide_mlp_lds_bytes<T, D>();
   constexpr int lds_a = ApplyWide<T, D, FM, NORM, WA, true>::kLdsBytes;
-  static_assert(lds_a <= 160 * 1024, "workgroup LDS limit of the device");
-  if (!allow_lds(apply16_wide_mlp<T, D, FM, NORM, WA>, lds_a)) return LINFUSION_ERR_HIP;
-  if constexpr (kWideReduce) {
-    if (!allow_lds(state_reduce16_wide_mlp<T, D, FM>, reduce16_wide_mlp_lds_bytes<T, D>())) return LINFUSION_ERR_HIP;
-  } else {
-    if (!allow_lds(state_reduce16_mlph<T, D, FM>, reduce16_mlph_lds_bytes<T, D>())) return LINFUSION_ERR_HIP;
-  }
+  static_assert(lds_r <= 160 * 1024 && lds_a <= 160 * 1024, "workgroup LDS limit of the device");
+  if (!allow_lds(state_reduce16_wide_mlp<T, D, FM>, lds_r) || !allow_lds(apply16_wide_mlp<T, D, FM, NORM, WA>, lds_a))
+    return LINFUSION_ERR_HIP;
   hipStream_t st = a.st;
   const int row = (int)a.in_row, row_o = (int)a.out_row;
   const unsigned heads = (unsigned)(a.B * a.H);
@@ -75,15 +70,9 @@ int run_wide_t(const HeadsArgs& a) {
   if (a.ev) (void)hipEventRecord(a.ev[0], st);
   mlp_rowstats16<T><<<dim3(a.stats_wgs, 2u * a.B), dim3(kThreads), 0, st>>>(
       (const u32x4*)a.t_q, (const u32x4*)a.t_k, a.in_batch, row, a.H * D / 8, a.ln_eps, a.N, a.n_pad, stats_q);
-  if constexpr (kWideReduce) {
-    state_reduce16_wide_mlp<T, D, FM><<<dim3(a.splits, heads), dim3(kThreads), reduce16_wide_mlp_lds_bytes<T, D>(), st>>>(
-        (const u32x4*)a.a_k, (const u32x4*)a.t_k, (const u32x4*)a.v, a.in_batch, row, a.H, stats_k, a.n_pad, a.gamma_k,
-        a.beta_k, a.slope, a.partials, a.N, a.blk_reduce);
-  } else {
-    state_reduce16_mlph<T, D, FM><<<dim3(a.splits, heads), dim3(kThreads), reduce16_mlph_lds_bytes<T, D>(), st>>>(
-        (const u32x4*)a.a_k, (const u32x4*)a.t_k, (const u32x4*)a.v, a.in_batch, row, a.H, stats_k, a.n_pad, a.gamma_k,
-        a.beta_k, a.slope, a.partials, a.N, a.blk_reduce);
-  }
+  state_reduce16_wide_mlp<T, D, FM><<<dim3(a.splits, heads), dim3(kThreads), lds_r, st>>>(
+      (const u32x4*)a.a_k, (const u32x4*)a.t_k, (const u32x4*)a.v, a.in_batch, row, a.H, stats_k, a.n_pad, a.gamma_k,
+      a.beta_k, a.slope, a.partials, a.N, a.blk_reduce);
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
   combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, heads), dim3(kCombineThreads), 0, st>>>(
       a.partials, a.splits, NE, a.state);
@@ -97,12 +86,12 @@ int run_wide_t(const HeadsArgs& a) {
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
-template <typename T, int D, int WA = 8>
+template <typename T, int D>
 int run_wide_fm(const HeadsArgs& a) {
   switch (a.fm) {
-    case 0: return a.unnorm ? run_wide_t<T, D, 0, false, WA>(a) : run_wide_t<T, D, 0, true, WA>(a);
-    case 1: return a.unnorm ? run_wide_t<T, D, 1, false, WA>(a) : run_wide_t<T, D, 1, true, WA>(a);
-    default: return a.unnorm ? run_wide_t<T, D, 2, false, WA>(a) : run_wide_t<T, D, 2, true, WA>(a);
+    case 0: return a.unnorm ? run_wide_t<T, D, 0, false>(a) : run_wide_t<T, D, 0, true>(a);
+    case 1: return a.unnorm ? run_wide_t<T, D, 1, false>(a) : run_wide_t<T, D, 1, true>(a);
+    default: return a.unnorm ? run_wide_t<T, D, 2, false>(a) : run_wide_t<T, D, 2, true>(a);
   }
 }
 
@@ -169,12 +158,6 @@ bool heads_supported(int d) { return d >= 8 && d % 8 == 0 && (d <= 64 || d == 80
 bool heads_wide(int d) { return d == 96 || d == 128 || d == 160; }
 bool heads_grouped(int H, int d) { return H % 4 == 0 && d >= 8 && d % 8 == 0 && (d <= 56 || d == 80); }
 
-size_t heads_packed_bytes(int d, int dtype) {
-  if (d == 80)
-    return dtype == LINFUSION_DTYPE_F16 ? lf::PackWide<lf::F16, 80, 4>::kHeadBytes : lf::PackWide<lf::BF16, 80, 4>::kHeadBytes;
-  return 0;
-}
-
 int run_heads(const HeadsArgs& a) {
   const bool f16 = a.dtype == LINFUSION_DTYPE_F16;
   if (a.grouped) {
@@ -185,7 +168,6 @@ int run_heads(const HeadsArgs& a) {
     }
     return LINFUSION_ERR_UNSUPPORTED;
   }
-  if (a.d == 80 && a.apply_wide) return f16 ? run_wide_fm<lf::F16, 80, 4>(a) : run_wide_fm<lf::BF16, 80, 4>(a);
   switch (a.d) {
 #define X(DD) case DD: return f16 ? run_heads_fm<lf::F16, DD>(a) : run_heads_fm<lf::BF16, DD>(a);
     X(8) X(16) X(24) X(32) X(40) X(48) X(56) X(64) X(80)
