@@ -22,11 +22,11 @@ template <typename T, int D, int W> struct ReduceMlpCfg {
   static constexpr int kTPR = Base::kThreadsW / kTile;                    // threads that reduce one row
   static_assert(kTPR == 8 || kTPR == 16, "a row's partials are reduced inside one wave by shuffles");
   // fp16 up to d = 40 fits 128 registers, so two 8-wave workgroups share a CU and cover each other's barrier
-  // waits (0.85 -> 0.67 ms at 2 M tokens); four heads of 80 in fp16 fit 256 (two 4-wave workgroups); the other
-  // shapes would spill and keep one workgroup
+  // waits (0.85 -> 0.67 ms at 2 M tokens); four heads of 80 fit 256 (two 4-wave workgroups; bf16 with four spilled
+  // registers, still 0.72 -> 0.58 ms at 2^19 tokens); the other shapes would spill much more and keep one workgroup
   static constexpr int kWavesPerSimd = (W == 8 && NSplit<T>::value == 1 && D <= 40)
                                            ? 4
-                                           : ((W == 4 && D == 80 && NSplit<T>::value == 1) ? 2 : W / 4);
+                                           : ((W == 4 && D == 80) ? 2 : W / 4);
 };
 
 // State reduction from the branch results of g'.  grid = (splits, B), block = 64 W, H = W heads.

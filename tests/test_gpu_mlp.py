@@ -302,9 +302,10 @@ def test_per_head_route_layer_norm_input_far_from_zero_mean(H, d, dtype):
     _check(out, _oracle(ins, H, dtype), H, dtype, "offset LayerNorm input, per head")
 
 
-def test_per_head_route_strided_and_repeatable():
-    """Column blocks of one wide buffer on the per-head route: same bits as its dense call, twice."""
-    B, H, N, d, dtype = 2, 10, 515, 64, "bf16"
+@pytest.mark.parametrize("B,H,N,d,dtype", [(2, 10, 515, 64, "bf16"), (2, 8, 515, 80, "f16"), (1, 16, 1000, 40, "bf16")])
+def test_per_head_route_strided_and_repeatable(B, H, N, d, dtype):
+    """Column blocks of one wide buffer on the routes that start with the statistics pass (per-head kernels; groups of
+    four heads): same bits as the dense call, twice."""
     ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=91)
     C = H * d
     dense = _run(ins, H)
