@@ -6,7 +6,9 @@
 // the kernels read a_k, t_k, v and a_q, t_q and write out -- six tensor passes where forming q and k first
 // costs ten.  Both kernels are the row-piece kernels (lf_reduce16.hpp, lf_apply16_dma.hpp) with the
 // workgroup covering whole token rows (H = W heads, one wave per head), which is what lets the LayerNorm
-// statistics be found without a pass of their own.
+// statistics be found without a pass of their own.  For rows of several groups of four heads the same kernels
+// take the statistics from an earlier pass instead (PRE; mlp_rowstats16 in lf_mlph16.hpp): state_reduce16_mlp<PRE>
+// and apply16_mlpg, eight tensor passes.
 #pragma once
 #include "lf_apply16_dma.hpp"
 
