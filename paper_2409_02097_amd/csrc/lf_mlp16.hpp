@@ -23,10 +23,11 @@ template <typename T, int D, int W> struct ReduceMlpCfg {
   static constexpr int kLdsBytes = kAffineOffset + 2 * W * D * 4;
   static constexpr int kTPR = Base::kThreadsW / kTile;                    // threads that reduce one row
   static_assert(kTPR == 8 || kTPR == 16, "a row's partials are reduced inside one wave by shuffles");
-  // fp16 up to d = 40 fits 128 registers, so two 8-wave workgroups share a CU and cover each other's barrier
+  // fp16 up to d = 40 (bf16 up to 32) fits 128 registers, so two 8-wave workgroups share a CU and cover each other's barrier
   // waits (0.85 -> 0.67 ms at 2 M tokens); four heads of 80 fit 256 (two 4-wave workgroups; bf16 with four spilled
-  // registers, still 0.72 -> 0.58 ms at 2^19 tokens); the other shapes would spill much more and keep one workgroup
-  static constexpr int kWavesPerSimd = (W == 8 && NSplit<T>::value == 1 && D <= 40)
+  // registers, still 0.72 -> 0.58 ms at 2^19 tokens); the other shapes would spill 34 to 52 registers (measured
+  // with that: bf16 d = 40 0.88 -> 1.41 ms, fp16 d = 48 0.92 -> 1.15 ms) and keep one workgroup
+  static constexpr int kWavesPerSimd = (W == 8 && (D <= 32 || (NSplit<T>::value == 1 && D <= 40)))
                                            ? 4
                                            : ((W == 4 && D == 80) ? 2 : W / 4);
 };

@@ -139,8 +139,9 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
   };
   // (defaults in 256-thread units, as for the row-piece kernels: a workgroup of eight waves counts twice)
   const int unit = H / lf::kWavesPerWG;
-  // fp16 up to d = 40 on eight heads: the reduction fits two workgroups per CU (ReduceMlpCfg::kWavesPerSimd)
-  const int rounds = (H == 8 && dtype == LINFUSION_DTYPE_F16 && d <= 40) ? 2 : 1;
+  // fp16 up to d = 40 (bf16 up to 32) on eight heads: the reduction fits two workgroups per CU
+  // (ReduceMlpCfg::kWavesPerSimd)
+  const int rounds = (H == 8 && (d <= 32 || (dtype == LINFUSION_DTYPE_F16 && d <= 40))) ? 2 : 1;
   p->splits = per_batch(lfh::env_int("LINFUSION_MLP_REDUCE_WGS", 2 * kNumCU * rounds) / unit,
                         lfh::env_int("LINFUSION_MLP_REDUCE_BLK", 2), &p->blk_reduce);
   p->apply_wgs = per_batch(lfh::env_int("LINFUSION_MLP_APPLY_WGS", 2 * kNumCU) / unit,
