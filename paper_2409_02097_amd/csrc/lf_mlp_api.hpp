@@ -33,7 +33,7 @@ struct HeadsArgs {
 bool heads_supported(int d);
 bool heads_wide(int d);
 // shapes the row-piece kernels on groups of four neighbouring heads take: head rows that are no whole 128-byte
-// lines (the per-head kernels would fetch every line twice) in rows of whole groups
+// lines (the per-head kernels would read and write partial lines) in rows of whole groups
 bool heads_grouped(int H, int d);
 // enqueues statistics, state reduction, combine, pack and apply; returns LINFUSION_OK or a LINFUSION_ERR_* code
 int run_heads(const HeadsArgs& a);
