@@ -150,7 +150,8 @@ def test_rejected_arguments():
     assert call(*ins[:5], out, *ins[5:], 8, 7, 1e-6, 1e-5, 0.01, 0, ws) == -2          # unknown feature map
 
 
-@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 8, 2000, 40, "f16"), (2, 10, 1500, 64, "bf16")])
+@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 8, 2000, 40, "f16"), (2, 10, 1500, 64, "bf16"), (1, 8, 700, 80, "f16"),
+                                           (1, 8, 300, 160, "bf16")])
 def test_recorded_into_a_graph_replays_correctly(B, H, N, d, dtype):
     """The MLP-fed call enqueues kernels only (on either route), so it can be captured; every replay (new inputs in
     the same buffers, eager work in between) must equal the eager result bit for bit."""
