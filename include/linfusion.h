@@ -224,7 +224,7 @@ size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int 
  *                           h*d .. h*d+d-1 of a token), fp16 or bf16, 16-byte aligned.
  *   out                     DEVICE pointer, same layout and type; must not overlap any input.
  *   gamma_*, beta_*         DEVICE pointers to H*d fp32 values each (the LayerNorms' affine).
- *   H, d                    any H >= 1 with B*H <= 65535; d in {8, ..., 64 step 8, 80, 96, 128, 160};
+ *   H, d                    any H >= 1 with B*H <= 65535 and B <= 32767; d in {8, ..., 64 step 8, 80, 96, 128, 160};
  *                           LINFUSION_DTYPE_F32 and every other width -> LINFUSION_ERR_UNSUPPORTED.
  *   eps                     as linfusion_attn_fwd_ex.  ln_eps > 0 (finite), 0 <= slope <= 1: the LayerNorm's
  *                           epsilon (inside the square root) and the LeakyReLU's negative slope; the paper

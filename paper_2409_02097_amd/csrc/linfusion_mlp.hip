@@ -59,7 +59,7 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
   if (p->route == 2) {
     // as the whole-row plan below with B * (H / 4) units of four heads; the apply kernel's rings leave room for
     // one workgroup per CU from d = 40 on
-    if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;
+    if ((long long)B * H > 65535 || 2LL * B > 65535) return LINFUSION_ERR_INVALID;   // grid.y limits
     p->W = 4;
     p->n_pad = n_tiles * lf::kTile;
     const long long units = (long long)B * (H / 4);
@@ -89,7 +89,7 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     return LINFUSION_OK;
   }
   if (p->route == 1) {
-    if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;   // grid.y limit
+    if ((long long)B * H > 65535 || 2LL * B > 65535) return LINFUSION_ERR_INVALID;   // grid.y limits
     p->W = 0;
     p->n_pad = n_tiles * lf::kTile;
     const long long units = (long long)B * H;

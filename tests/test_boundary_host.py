@@ -194,6 +194,7 @@ def test_mlp_fed_entry_validates_on_the_host():
     if ok is not None:   # head counts and widths beyond the whole-row kernels go the per-head way
         assert _mlp(H=8, d=64) == ok and _mlp(H=5) == ok and _mlp(H=20, d=64, ws_bytes=16 << 20) == ok
         assert _mlp(H=8, d=160, ws_bytes=16 << 20) == ok and _mlp(H=2, d=96, ws_bytes=16 << 20) == ok
+    assert _mlp(B=40000, H=1, d=64) == -1 and _mlp(B=9000, H=8, d=64) == -1       # launch grid limits
     assert _mlp(d=72) == -2 and _mlp(d=112) == -2 and _mlp(d=12) == -2 and _mlp(dtype=0) == -2 and _mlp(fm=9) == -2
     assert _mlp(a_q=(1 << 20) + 8) == -3 and _mlp(gamma_q=(48 << 20) + 2) == -3
     assert _mlp(ws=None) == -4 and _mlp(ws_bytes=1024) == -4
