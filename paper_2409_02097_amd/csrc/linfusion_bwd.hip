@@ -6,6 +6,7 @@
 #include <cmath>
 
 #include "lf_backward16.hpp"
+#include "lf_backward16_rows.hpp"
 #include "lf_host_api.hpp"
 
 namespace {
@@ -74,6 +75,48 @@ struct BwdArgs {
   lf::Layout lq, lkv, lg, ldq, ldkv;   // q; k and v; dout; dq; dk and dv
 };
 
+// dK, dV: the row-piece kernel on groups of W heads where the heads of a token are neighbours in memory (k, v and
+// dk, dv alike), a head's row is no whole 128-byte line and the heads make whole groups; else the per-head kernel.
+template <typename T, int D, int FM, int W>
+int launch_kv_rows(const BwdArgs& a, const float* stateD) {
+  using namespace lf;
+  constexpr int lds = BwdRowsCfg<D, W>::lds_bytes();
+  static_assert(lds <= 160 * 1024, "workgroup LDS limit of the device");
+  if (!allow_lds(bwd_kv16_rows<T, D, FM, W>, lds)) return LINFUSION_ERR_HIP;
+  const int gpb = a.H / W;
+  const long long groups = (long long)a.B * gpb;
+  const long long n_tiles = (a.N + kTile - 1) / kTile;
+  const int resident = 160 * 1024 / lds > 0 ? 160 * 1024 / lds : 1;
+  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * kNumCU) / groups;
+  if (wgs > n_tiles) wgs = n_tiles;
+  if (wgs < 1) wgs = 1;
+  long long blk = lfh::env_int("LINFUSION_BWD_ROWS_BLK", 1);
+  const long long share = (n_tiles + wgs - 1) / wgs;
+  if (blk > share) blk = share;
+  bwd_kv16_rows<T, D, FM, W><<<dim3((unsigned)wgs, (unsigned)groups), dim3(64 * W), lds, a.st>>>(
+      (const u32x4*)a.k, (const u32x4*)a.v, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, gpb, stateD, a.N, (int)blk);
+  return LINFUSION_OK;
+}
+
+template <int D> constexpr bool kRowsW8 = D <= 48;                       // three slots of eight regions fit the LDS
+template <int D> constexpr bool kRowsW4 = D <= 56 || D == 80;
+
+// returns true (and sets *rc) when the row-piece kernel took the launch
+template <typename T, int D, int FM>
+bool kv_rows(const BwdArgs& a, const float* stateD, int* rc) {
+  constexpr int CPR = D / 8;
+  if constexpr ((D * 2) % 128 == 0) return false;
+  if (a.lkv.head != CPR || a.ldkv.head != CPR) return false;
+  if (lfh::env_int("LINFUSION_BWD_ROWS", 1) != 1) return false;
+  if constexpr (kRowsW8<D>) {
+    if (a.H % 8 == 0) { *rc = launch_kv_rows<T, D, FM, 8>(a, stateD); return true; }
+  }
+  if constexpr (kRowsW4<D>) {
+    if (a.H % 4 == 0) { *rc = launch_kv_rows<T, D, FM, 4>(a, stateD); return true; }
+  }
+  return false;
+}
+
 template <typename T, int D, int FM, bool NORM>
 int run_bwd(const BwdArgs& a) {
   using namespace lf;
@@ -115,8 +158,11 @@ int run_bwd(const BwdArgs& a) {
       bwd_qs16<T, D, FM, NORM><<<ga, blk, lds_a + 256, st>>>(Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, partials,
                                                              a.eps, a.N, p.blk_apply);
       combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.apply_wgs, NE, stateD);
-      bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N,
-                                                 p.blk_apply);
+      int rck = LINFUSION_OK;
+      if (!kv_rows<T, D, FM>(a, stateD, &rck))
+        bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N,
+                                                   p.blk_apply);
+      if (rck != LINFUSION_OK) return rck;
       return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
     }
   }
@@ -125,7 +171,10 @@ int run_bwd(const BwdArgs& a) {
   bwd_state16<T, D, FM, NORM><<<dim3(p.gsplits, (unsigned)BH), blk, lds_s, st>>>(Q, a.lq, G, a.lg, scal, stateS,
                                                                                   partials, a.N, p.gblk_reduce);
   combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.gsplits, NE, stateD);
-  bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N, p.blk_apply);
+  int rck = LINFUSION_OK;
+  if (!kv_rows<T, D, FM>(a, stateD, &rck))
+    bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N, p.blk_apply);
+  if (rck != LINFUSION_OK) return rck;
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 

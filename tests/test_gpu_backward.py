@@ -163,7 +163,12 @@ def test_backward_argument_checks():
 
 
 @pytest.mark.parametrize("B,H,N,d,dtype", [(2, 3, 33, 40, "f16"), (1, 8, 1000, 40, "f16"), (2, 5, 700, 64, "bf16"),
-                                            (1, 4, 515, 80, "f16"), (1, 2, 300, 24, "bf16"), (1, 10, 2049, 64, "f16")])
+                                            (1, 4, 515, 80, "f16"), (1, 2, 300, 24, "bf16"), (1, 10, 2049, 64, "f16"),
+                                            # groups of eight / four heads on the row-piece dK, dV kernel
+                                            (2, 8, 2051, 40, "bf16"), (3, 4, 100, 40, "f16"), (1, 16, 257, 24, "f16"),
+                                            (1, 12, 130, 56, "bf16"), (1, 8, 1, 40, "f16"), (2, 8, 33, 80, "bf16"),
+                                            (1, 8, 300, 8, "f16"), (1, 4, 700, 16, "bf16"), (1, 8, 515, 48, "f16"),
+                                            (1, 8, 96, 32, "bf16")])
 def test_backward_on_token_major_views(B, H, N, d, dtype):
     """All seven tensors in the UNet's [B, N, H*d] layout, handed over as strided [B, H, N, d] views: the oracle's
     gradients, and bit for bit what the contiguous entry point gives on the same values."""
