@@ -88,6 +88,14 @@ struct Ring2Rows {
   LF_DEV unsigned char* byte_ptr(int slot, int which, int byte) const {
     return chunk_ptr(slot, which, byte >> 4) + (byte & 15);
   }
+  // address of the four 16-bit elements (row, col .. col + 3) of this wave's head in tile part `which`, col a
+  // multiple of 4: what one lane names in a transposing LDS read
+  LF_DEV const uint16_t* tr_ptr(int slot, int which, int row, int col) const {
+    int x = wave * CPR + C::rot(row) + (col >> 3);
+    if (x >= PC) x -= PC;
+    return reinterpret_cast<const uint16_t*>(tile_ptr(slot, which) + (row / RPR) * C::kRegionBytes +
+                                             (row % RPR) * PC * 16 + (x << 4) + (col & 7) * 2);
+  }
 
   // this wave's rows of tile `tile` of both tensors into ring slot `slot`: always 2 NL vector memory instructions,
   // issued by every lane as straight-line code (see ApplyDma::issue_copy)
@@ -345,6 +353,197 @@ bwd_kv16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout l
   if (prev_tile >= 0) {
     rg.store_tile(prev_tile, prev_slot, 0, dKg, ldkv.row);
     rg.store_tile(prev_tile, prev_slot, 1, dVg, ldkv.row);
+  }
+}
+
+// ==========================================================================================
+// bwd_qs16_rows (fp16): bwd_qs16 on a group of W neighbouring heads -- dQ, and the group's share of the state
+// gradient.  grid = (wgs, B * gpb), block = 64 W.  Wave w works on head w of the group for every token of the
+// workgroup's tiles, so its accumulators are that head's whole partial: written (divided by beta) without a sum
+// across waves, as [B*H][gridDim.x][D*D + D] for combine_state.  (The order in which tiles enter a partial differs
+// from the per-head kernel's, so dS, dz and what follows from them -- dK, dV -- agree with it up to fp32 summation
+// order, not bit for bit; dQ does not depend on them.)  LDS: BwdRowsCfg<D, W>::lds_bytes() + 64 W.
+// ==========================================================================================
+template <typename T, int D, int FM, bool NORM, int W>
+__global__ void __launch_bounds__(64 * W)
+bwd_qs16_rows(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Layout lg, u32x4* __restrict__ dQ,
+              Layout ldq, int gpb, const float* __restrict__ state, float* __restrict__ partials, float eps,
+              long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using RG = Ring2Rows<T, D, W>;
+  using Sh = Shape16<D>;
+  using C = BwdRowsCfg<D, W>;
+  static_assert(NSplit<T>::value == 1, "single-level operands only (fp16)");
+  constexpr int NS = 1, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
+  constexpr int MT = Sh::kMT, NE = D * D + D;
+  const long long b = blockIdx.y / gpb;
+  const long long h0 = (long long)(blockIdx.y % gpb) * W;
+  RG rg(Q + (b * lq.batch + h0 * lq.head), lq.row, G + (b * lg.batch + h0 * lg.head), lg.row, N, tiles_per_block,
+        blockIdx.x, gridDim.x, smem);
+  u32x4* dQg = dQ + (b * ldq.batch + h0 * ldq.head);
+  uint16_t* ecol = reinterpret_cast<uint16_t*>(smem + C::lds_bytes()) + rg.wave * 32;
+  rg.prefetch();
+
+  // every wave its own head's operands: the heads' states pass through the staging area one after the other
+  u32x4 A[NS][MTB][KS];
+  float zo[HALF];
+  float inv_aS = 1.0f, beta = 1.0f, inv_beta = 1.0f;
+  for (int h = 0; h < W; ++h) {
+    const float aS = rg.stage_state(state + (b * lq.H + h0 + h) * NE);
+    if (rg.wave == h) {
+      rg.template build_A<false>(aS, A);
+      rg.load_vec(zo);
+      inv_aS = 1.0f / aS;
+      if constexpr (NORM) {   // power of two near the typical denominator (see bwd_state16)
+        const float* z = reinterpret_cast<const float*>(smem + C::kStageOffset) + D * D;
+        float zs = 0.0f;
+        for (int i = 0; i < D; ++i) zs += z[i];
+        if (zs > 0.0f && zs < 3.0e38f) {
+          int ex;
+          (void)__builtin_frexpf(zs, &ex);
+          ex = ex > 100 ? 100 : (ex < -100 ? -100 : ex);
+          beta = __builtin_ldexpf(1.0f, ex);
+          inv_beta = __builtin_ldexpf(1.0f, -ex);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  f32x4 accS[MT][MT], accZ[MT];
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    accZ[a] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int bb = 0; bb < MT; ++bb) accS[a][bb] = f32x4{0, 0, 0, 0};
+  }
+  const int j16 = rg.lane & 15, g4 = rg.lane >> 4;
+  const int tr_row = 8 * g4 + (j16 >> 2), tr_col = 4 * (j16 & 3);
+
+  {   // this wave's rows of the first tile: only the second tile's copies were issued after them
+    TileIter second = rg.it;
+    second.next();
+    if (second.valid()) wait_vmcnt<2 * NL>();
+    else wait_vmcnt<0>();
+  }
+  lds_barrier();
+  int slot = 0, prev_slot = 0;
+  long long prev_tile = -1;
+  while (rg.it.valid()) {
+    const long long tile = rg.it.t;
+    const bool have_prev = prev_tile >= 0;
+    if (have_prev) rg.store_tile(prev_tile, prev_slot, 0, dQg, ldq.row);
+    const bool copied = rg.ahead.valid();
+    if (copied) rg.issue_copy(rg.ahead.t, have_prev ? prev_slot : R - 1);
+    long long rem = N - tile * kTile;
+    const bool ok = rg.tok < (rem < kTile ? (int)rem : kTile);
+
+    u32x4 Bg[KS];
+    rg.read_B_raw(slot, 1, Bg);
+    f32x16 acc[MTB];
+    rg.products(A, Bg, nullptr, acc);
+    float x[HALF], dr[HALF], rr[HALF];
+    rg.read_half_row(slot, 0, x);
+    float denp = 0.0f, rup = 0.0f;
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const float r = phi<FM>(x[i]);
+      const float u = acc[i / 16][i % 16] * inv_aS;
+      denp = __builtin_fmaf(r, zo[i], denp);
+      rup = __builtin_fmaf(r, u, rup);
+      dr[i] = u;
+      rr[i] = ok ? r : 0.0f;
+      x[i] = phi_prime_from<FM>(x[i], r);
+    }
+    float gsc = ok ? 1.0f : 0.0f, e = 0.0f;
+    if constexpr (NORM) {
+      const float den = denp + __shfl_xor(denp, 32) + eps;
+      const float ru = rup + __shfl_xor(rup, 32);
+      const float invden = 1.0f / den;
+      const float go = ru * invden;
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) dr[i] = (dr[i] - go * zo[i]) * invden * x[i];
+      gsc = ok ? invden * beta : 0.0f;
+      e = ok ? -go * invden * beta : 0.0f;
+    } else {
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) dr[i] *= x[i];
+    }
+    // ---- phi(q), g beta / den and e beta take the places of this head's columns ----------------------
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.write_half_row(slot, 0, rr);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int chunk = rg.kg * KS + s;
+      if (chunk < CPR) {
+        u32x4 w;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          float g0, g1;
+          unpack2<T>(Bg[s][c], g0, g1);
+          w[c] = pack2<T>(g0 * gsc, g1 * gsc);
+        }
+        *reinterpret_cast<u32x4*>(rg.chunk_ptr(slot, 1, chunk)) = w;
+      }
+    }
+    if (rg.kg == 0) ecol[rg.tok] = (uint16_t)pack2<T>(e, 0.0f);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    // ---- dS, dz: token-major operands by transposing reads --------------------------------------------
+    {
+      u32x4 bfrag[MT], bfe = u32x4{0, 0, 0, 0};
+      if (j16 == 0) bfe = *reinterpret_cast<const u32x4*>(ecol + 8 * g4);
+#pragma unroll
+      for (int bb = 0; bb < MT; ++bb) {
+        const u32x2 r0 = lds_read_tr16(rg.tr_ptr(slot, 1, tr_row, 16 * bb + tr_col));
+        const u32x2 r1 = lds_read_tr16(rg.tr_ptr(slot, 1, tr_row + 4, 16 * bb + tr_col));
+        bfrag[bb] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+      }
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        const u32x2 r0 = lds_read_tr16(rg.tr_ptr(slot, 0, tr_row, 16 * a + tr_col));
+        const u32x2 r1 = lds_read_tr16(rg.tr_ptr(slot, 0, tr_row + 4, 16 * a + tr_col));
+        const u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+        for (int bb = 0; bb < MT; ++bb) accS[a][bb] = mfma_16x16x32<T>(afrag, bfrag[bb], accS[a][bb]);
+        accZ[a] = mfma_16x16x32<T>(afrag, bfe, accZ[a]);
+      }
+    }
+    // ---- dq takes the place of this head's columns of the Q tile --------------------------------------
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    rg.write_half_row(slot, 0, dr);
+
+    rg.it.next();
+    rg.ahead.next();
+    if (rg.it.valid()) {
+      // after the copies of tile j+1 came the stores of tile j-1 (dq only) and the copies of tile j+2
+      if (have_prev && copied) wait_vmcnt<3 * NL>();
+      else if (copied) wait_vmcnt<2 * NL>();
+      else if (have_prev) wait_vmcnt<NL>();
+      else wait_vmcnt<0>();
+    }
+    lds_barrier();   // tile j is finished by all waves; tile j+1 has landed for all
+    prev_tile = tile;
+    prev_slot = slot;
+    slot = slot + 1 == R ? 0 : slot + 1;
+  }
+  if (prev_tile >= 0) rg.store_tile(prev_tile, prev_slot, 0, dQg, ldq.row);
+
+  // ---- this wave's accumulators are its head's partial ----------------------------------------------------
+  float* dst = partials + (((b * lq.H + h0 + rg.wave) * gridDim.x) + blockIdx.x) * (long long)NE;
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = a * 16 + 4 * g4 + i;
+      if (row < D) {
+#pragma unroll
+        for (int bb = 0; bb < MT; ++bb) {
+          const int col = bb * 16 + j16;
+          if (col < D) dst[row * D + col] = accS[a][bb][i] * inv_beta;
+        }
+        if (j16 == 0) dst[D * D + row] = accZ[a][i] * inv_beta;
+      }
+    }
   }
 }
 

@@ -16,6 +16,7 @@ constexpr int kNumCU = 256;
 struct BwdPlan {
   int splits, blk_reduce, apply_wgs, blk_apply;
   int gsplits, gblk_reduce;   // the state-gradient reduction's own launch shape
+  int most;                   // partial states per head the workspace has room for
   size_t ne, ws_partials, ws_state, ws_scal, ws_total;
 };
 
@@ -52,6 +53,7 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   int most = p->splits > p->gsplits ? p->splits : p->gsplits;
   if (p->apply_wgs > most) most = p->apply_wgs;   // the merged dQ + state-gradient kernel writes one partial each
+  p->most = most;
   p->ws_partials = up((size_t)BH * most * p->ne * sizeof(float));
   p->ws_state = up((size_t)BH * p->ne * sizeof(float));
   p->ws_scal = up((size_t)BH * (size_t)N * 2 * sizeof(float));
@@ -74,6 +76,12 @@ struct BwdArgs {
   hipStream_t st;
   lf::Layout lq, lkv, lg, ldq, ldkv;   // q; k and v; dout; dq; dk and dv
 };
+
+// The row-piece kernels build their W heads' operands one head after the other (some 30 us per launch), which only
+// tensors from a few tens of MB up repay: B=2, H=8, N=16384, d=40 (21 MB) 105 -> 134 us, 201 MB 1.48 -> 0.51 ms.
+inline bool rows_pay(const BwdArgs& a, int d) {
+  return (double)a.B * a.H * (double)a.N * d * 2.0 >= (double)lfh::env_int("LINFUSION_BWD_ROWS_MIN_MB", 48) * 1048576.0;
+}
 
 // dK, dV: the row-piece kernel on groups of W heads where the heads of a token are neighbours in memory (k, v and
 // dk, dv alike), a head's row is no whole 128-byte line and the heads make whole groups; else the per-head kernel.
@@ -98,6 +106,47 @@ int launch_kv_rows(const BwdArgs& a, const float* stateD) {
   return LINFUSION_OK;
 }
 
+// dQ and the state gradient in one pass (fp16, d <= 48) on groups of heads: as launch_kv_rows; *wgs_used = partial
+// states per head written for combine_state
+template <typename T, int D, int FM, bool NORM, int W>
+int launch_qs_rows(const BwdArgs& a, const float* stateS, float* partials, int* wgs_used) {
+  using namespace lf;
+  constexpr int lds = BwdRowsCfg<D, W>::lds_bytes() + 64 * W;
+  static_assert(lds <= 160 * 1024, "workgroup LDS limit of the device");
+  if (!allow_lds(bwd_qs16_rows<T, D, FM, NORM, W>, lds)) return LINFUSION_ERR_HIP;
+  const int gpb = a.H / W;
+  const long long groups = (long long)a.B * gpb;
+  const long long n_tiles = (a.N + kTile - 1) / kTile;
+  const int resident = 160 * 1024 / lds > 0 ? 160 * 1024 / lds : 1;
+  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * kNumCU) / groups;
+  if (wgs > a.p->most) wgs = a.p->most;   // room for the partial states
+  if (wgs > n_tiles) wgs = n_tiles;
+  if (wgs < 1) wgs = 1;
+  long long blk = lfh::env_int("LINFUSION_BWD_ROWS_BLK", 1);
+  const long long share = (n_tiles + wgs - 1) / wgs;
+  if (blk > share) blk = share;
+  bwd_qs16_rows<T, D, FM, NORM, W><<<dim3((unsigned)wgs, (unsigned)groups), dim3(64 * W), lds, a.st>>>(
+      (const u32x4*)a.q, a.lq, (const u32x4*)a.g, a.lg, (u32x4*)a.dq, a.ldq, gpb, stateS, partials, a.eps, a.N,
+      (int)blk);
+  *wgs_used = (int)wgs;
+  return LINFUSION_OK;
+}
+
+template <typename T, int D, int FM, bool NORM>
+bool qs_rows(const BwdArgs& a, const float* stateS, float* partials, int* wgs_used, int* rc) {
+  constexpr int CPR = D / 8;
+  if constexpr ((D * 2) % 128 == 0 || lf::NSplit<T>::value != 1 || D > 48) {
+    return false;
+  } else {
+    if (a.lq.head != CPR || a.lg.head != CPR || a.ldq.head != CPR) return false;
+    const int mode = lfh::env_int("LINFUSION_BWD_ROWS", 1);   // 1: by size, 2: never, 3: always (a test aid)
+    if (mode == 2 || (mode != 3 && !rows_pay(a, D))) return false;
+    if (a.H % 8 == 0) { *rc = launch_qs_rows<T, D, FM, NORM, 8>(a, stateS, partials, wgs_used); return true; }
+    if (a.H % 4 == 0) { *rc = launch_qs_rows<T, D, FM, NORM, 4>(a, stateS, partials, wgs_used); return true; }
+    return false;
+  }
+}
+
 template <int D> constexpr bool kRowsW8 = D <= 48;                       // three slots of eight regions fit the LDS
 template <int D> constexpr bool kRowsW4 = D <= 56 || D == 80;
 
@@ -107,7 +156,8 @@ bool kv_rows(const BwdArgs& a, const float* stateD, int* rc) {
   constexpr int CPR = D / 8;
   if constexpr ((D * 2) % 128 == 0) return false;
   if (a.lkv.head != CPR || a.ldkv.head != CPR) return false;
-  if (lfh::env_int("LINFUSION_BWD_ROWS", 1) != 1) return false;
+  const int mode = lfh::env_int("LINFUSION_BWD_ROWS", 1);   // 1: by size, 2: never, 3: always (a test aid)
+  if (mode == 2 || (mode != 3 && !rows_pay(a, D))) return false;
   if constexpr (kRowsW8<D>) {
     if (a.H % 8 == 0) { *rc = launch_kv_rows<T, D, FM, 8>(a, stateD); return true; }
   }
@@ -155,9 +205,12 @@ int run_bwd(const BwdArgs& a) {
   if constexpr (kMerged) {
     if (lfh::env_int("LINFUSION_BWD_MERGED", 1) == 1) {
       if (!allow_lds(bwd_qs16<T, D, FM, NORM>, lds_a + 256)) return LINFUSION_ERR_HIP;
-      bwd_qs16<T, D, FM, NORM><<<ga, blk, lds_a + 256, st>>>(Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, partials,
-                                                             a.eps, a.N, p.blk_apply);
-      combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.apply_wgs, NE, stateD);
+      int nparts = p.apply_wgs, rcq = LINFUSION_OK;
+      if (!qs_rows<T, D, FM, NORM>(a, stateS, partials, &nparts, &rcq))
+        bwd_qs16<T, D, FM, NORM><<<ga, blk, lds_a + 256, st>>>(Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, partials,
+                                                               a.eps, a.N, p.blk_apply);
+      if (rcq != LINFUSION_OK) return rcq;
+      combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, nparts, NE, stateD);
       int rck = LINFUSION_OK;
       if (!kv_rows<T, D, FM>(a, stateD, &rck))
         bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N,

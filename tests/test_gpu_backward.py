@@ -169,10 +169,12 @@ def test_backward_argument_checks():
                                             (1, 12, 130, 56, "bf16"), (1, 8, 1, 40, "f16"), (2, 8, 33, 80, "bf16"),
                                             (1, 8, 300, 8, "f16"), (1, 4, 700, 16, "bf16"), (1, 8, 515, 48, "f16"),
                                             (1, 8, 96, 32, "bf16")])
-def test_backward_on_token_major_views(B, H, N, d, dtype):
+def test_backward_on_token_major_views(B, H, N, d, dtype, monkeypatch):
     """All seven tensors in the UNet's [B, N, H*d] layout, handed over as strided [B, H, N, d] views: the oracle's
-    gradients, and bit for bit what the contiguous entry point gives on the same values."""
+    gradients, and what the contiguous entry point gives on the same values.  The row-piece gradient kernels, which
+    the library picks from a few tens of MB up, are switched on for every size here."""
     print(f"bwd token-major B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    monkeypatch.setenv("LINFUSION_BWD_ROWS", "3")
     q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=70, device="cpu")
     g = wl.draw((B, H, N, d), wl.BASE_SEED + 70707, dtype, "cpu")
     tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)   # [B, N, H, d] in memory
@@ -183,9 +185,20 @@ def test_backward_on_token_major_views(B, H, N, d, dtype):
     lf.linfusion_attn_bwd_strided(*views, *outs, 0, 1e-6, 0, ws)
     torch.cuda.synchronize()
     dense = _run(q, k, v, g)
-    for got, want in zip(outs, dense):
-        assert torch.equal(got.contiguous().view(torch.int16), want.view(torch.int16))
+    # dq: the same bits as the contiguous call.  dk, dv: the same bits too unless the row-piece kernels took the
+    # state gradient, whose partial sums then run over the tiles in another order (fp32 rounding only)
+    assert torch.equal(outs[0].contiguous().view(torch.int16), dense[0].view(torch.int16))
+    for got, want in zip(outs[1:], dense[1:]):
+        diff = (got.contiguous().float() - want.float()).abs().max().item()
+        assert diff <= 2e-3 * want.float().abs().max().item(), f"token-major vs contiguous: {diff}"
     _check([o.contiguous() for o in outs], q, k, v, g, dtype, 0, 1e-6, True, "token-major")
+    # and with the per-head kernels only: every gradient bit for bit as the contiguous call
+    monkeypatch.setenv("LINFUSION_BWD_ROWS", "2")
+    outs2 = [torch.full((B, N, H, d), float("nan"), dtype=q.dtype, device="cuda").permute(0, 2, 1, 3) for _ in range(3)]
+    lf.linfusion_attn_bwd_strided(*views, *outs2, 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    for got, want in zip(outs2, dense):
+        assert torch.equal(got.contiguous().view(torch.int16), want.view(torch.int16))
 
 
 def test_backward_on_padded_and_mixed_layouts():
