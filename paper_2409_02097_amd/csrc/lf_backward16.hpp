@@ -13,7 +13,8 @@
 //     bwd_kv16                          reads K, V: writes dK, dV
 // The two apply-shaped kernels use the LDS-DMA ring of apply16_dma with two tensors per slot; the
 // reduction is state_reduce16 with phi(Q) in the place of phi(K), g / den in the place of V and e_i in the
-// place of the ones column.  Contiguous [B, H, N, d] tensors only.
+// place of the ones column.  Every tensor is addressed through a Layout (contiguous or strided views); the
+// row-piece forms of the two apply-shaped kernels for token-major tensors are in lf_backward16_rows.hpp.
 #pragma once
 #include "lf_apply16_dma.hpp"
 
