@@ -191,7 +191,7 @@ int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* 
  * accepted).  Same arithmetic and order as the contiguous call: dense strides give bit-identical results.
  * Speed: where the heads of a token are neighbours in memory (head stride == d, the UNet's [B, N, H*d]), a head's
  * row is no whole number of 128-byte lines (d * 2 % 128 != 0: d = 40, 80, ...), H is a multiple of 4 and a tensor
- * has 48 MB or more, the gradients come from kernels that move whole row pieces of four or eight neighbouring
+ * has 24 MB or more, the gradients come from kernels that move whole row pieces of four or eight neighbouring
  * heads: dK and dV for every width up to 56 and 80, dQ and the state gradient too for fp16 up to d = 48 (token-major
  * 8 x 40 fp16 at 2 M tokens: 2.6 ms, against 7.0 ms on the per-head kernels and 2.3 ms contiguous).  With those,
  * dq keeps the contiguous call's bits; dk and dv may differ from it in the last bits when the state gradient was

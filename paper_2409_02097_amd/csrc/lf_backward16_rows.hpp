@@ -26,6 +26,10 @@ template <int D, int W> struct BwdRowsCfg {
   static_assert(kTile % W == 0 && kPC % 4 == 0 && kRPR * kG >= 16, "rotation classes must fit a region");
   static_assert(kRegionChunks % 32 == 0, "a region is whole half-waves of chunks");
   static_assert(kStageBytes <= kSlotBytes, "the state is staged in the third slot");
+  // every wave its own head's state at once (behind the first slot, before the second tile is requested), where W
+  // states fit the second and third slot; else one head after the other through the third slot
+  static constexpr int kOwnBytes = (kStageBytes + 255) / 256 * 256;
+  static constexpr bool kOwnStage = W * kOwnBytes <= 2 * kSlotBytes;
   static constexpr int kMTB = (Sh::kHalf + 15) / 16;
   static constexpr int lds_bytes() { return kRing * kSlotBytes; }
   static __device__ __forceinline__ int rot(int r) { return ((r * kG) >> 4) & (kG - 1); }
@@ -48,12 +52,14 @@ struct Ring2Rows {
   int trow[NL], xoff[NL], yoff[NL];     // copy side: token row and offsets of the chunk this lane brings
   int trow_o[NL], ooff[NL], soff[NL];   // store side: token row, chunk inside the row piece, byte in the region
   TileIter it, ahead;
+  const float* stage;                    // where the state this wave builds its operands from is staged
 
   LF_DEV Ring2Rows(const u32x4* Xh_, int rsx_, const u32x4* Yh_, int rsy_, long long N_, int tiles_per_block, int wg,
                    int nwg, unsigned char* smem_)
       : Xh(Xh_), Yh(Yh_), rsx(rsx_), rsy(rsy_), N(N_), smem(smem_), lane(threadIdx.x & 63),
         wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
-        it(wg, nwg, 0, tiles_per_block, (N_ + kTile - 1) / kTile, 1), ahead(it) {
+        it(wg, nwg, 0, tiles_per_block, (N_ + kTile - 1) / kTile, 1), ahead(it),
+        stage(reinterpret_cast<const float*>(smem_ + C::kStageOffset)) {
     tok = lane & 31;
     kg = lane >> 5;
     row_byte = (tok / RPR) * C::kRegionBytes + (tok % RPR) * PC * 16;
@@ -114,11 +120,30 @@ struct Ring2Rows {
       }
     }
   }
-  LF_DEV void prefetch() {
+  // the first two tiles; in two steps where the states are staged behind the first slot (kOwnStage)
+  LF_DEV void prefetch_first() {
     if (ahead.valid()) issue_copy(ahead.t, 0);
     ahead.next();
+  }
+  LF_DEV void prefetch_second() {
     if (ahead.valid()) issue_copy(ahead.t, 1);
     ahead.next();
+  }
+  // This wave alone: stages its head's fp32 state in its own piece of LDS (kOwnStage) and returns the power-of-two
+  // scale for the matrix.  A workgroup barrier must follow before prefetch_second().
+  LF_DEV float stage_state_own(const float* state) {
+    float* st = reinterpret_cast<float*>(smem + C::kSlotBytes + wave * C::kOwnBytes);
+    float mS = 0.0f;
+    for (int e = lane; e < NE / 4; e += 64) {
+      const f32x4 x = reinterpret_cast<const f32x4*>(state)[e];
+      reinterpret_cast<f32x4*>(st)[e] = x;
+      if (e < D * D / 4) mS = fmaxf(mS, fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3]))));
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mS = fmaxf(mS, __shfl_xor(mS, o));
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the wave's LDS writes before its reads of them
+    stage = st;
+    return pow2_scale_for(mS);
   }
   // this wave's rows of tile part `which` of slot `slot`, in memory order, to the group's row pieces of `Oh`
   LF_DEV void store_tile(long long tile, int slot, int which, u32x4* Oh, int rso) {
@@ -156,7 +181,7 @@ struct Ring2Rows {
   // A operands of the staged matrix (see Ring2::build_A)
   template <bool TRANSPOSED>
   LF_DEV void build_A(float aS, u32x4 (&A)[NS][MTB][KS]) const {
-    const float* st = reinterpret_cast<const float*>(smem + C::kStageOffset);
+    const float* st = stage;
     const int m = lane & 31;
     const int hv = (m >> 2) & 1;
 #pragma unroll
@@ -186,7 +211,7 @@ struct Ring2Rows {
     }
   }
   LF_DEV void load_vec(float (&v)[HALF]) const {
-    const float* st = reinterpret_cast<const float*>(smem + C::kStageOffset) + D * D;
+    const float* st = stage + D * D;
 #pragma unroll
     for (int i = 0; i < HALF; ++i) v[i] = st[kg * HALF + i];
   }
@@ -264,21 +289,32 @@ bwd_kv16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout l
   RG rg(K + in_off, lkv.row, V + in_off, lkv.row, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
   u32x4* dKg = dK + out_off;
   u32x4* dVg = dV + out_off;
-  rg.prefetch();
+  rg.prefetch_first();
 
-  // every wave its own head's operands: the heads' states pass through the staging area one after the other
+  // every wave its own head's operands
   u32x4 A1[NS][MTB][KS], A2[NS][MTB][KS];
   float dzo[HALF];
   float inv_aS = 1.0f;
-  for (int h = 0; h < W; ++h) {
-    const float aS = rg.stage_state(dstate + (b * lkv.H + h0 + h) * (D * D + D));
-    if (rg.wave == h) {
-      rg.template build_A<true>(aS, A1);    // dv = dS^T p
-      rg.template build_A<false>(aS, A2);   // dp = dS v (+ dz)
-      rg.load_vec(dzo);
-      inv_aS = 1.0f / aS;
+  if constexpr (BwdRowsCfg<D, W>::kOwnStage) {
+    const float aS = rg.stage_state_own(dstate + (b * lkv.H + h0 + rg.wave) * (D * D + D));
+    rg.template build_A<true>(aS, A1);    // dv = dS^T p
+    rg.template build_A<false>(aS, A2);   // dp = dS v (+ dz)
+    rg.load_vec(dzo);
+    inv_aS = 1.0f / aS;
+    __syncthreads();   // the staged states are dead: the second slot may be filled
+    rg.prefetch_second();
+  } else {
+    rg.prefetch_second();
+    for (int h = 0; h < W; ++h) {   // the heads' states pass through the third slot one after the other
+      const float aS = rg.stage_state(dstate + (b * lkv.H + h0 + h) * (D * D + D));
+      if (rg.wave == h) {
+        rg.template build_A<true>(aS, A1);
+        rg.template build_A<false>(aS, A2);
+        rg.load_vec(dzo);
+        inv_aS = 1.0f / aS;
+      }
+      __syncthreads();
     }
-    __syncthreads();
   }
 
   {   // this wave's rows of the first tile: only the second tile's copies were issued after them
@@ -382,32 +418,40 @@ bwd_qs16_rows(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ 
         blockIdx.x, gridDim.x, smem);
   u32x4* dQg = dQ + (b * ldq.batch + h0 * ldq.head);
   uint16_t* ecol = reinterpret_cast<uint16_t*>(smem + C::lds_bytes()) + rg.wave * 32;
-  rg.prefetch();
+  rg.prefetch_first();
 
-  // every wave its own head's operands: the heads' states pass through the staging area one after the other
+  // every wave its own head's operands
   u32x4 A[NS][MTB][KS];
   float zo[HALF];
   float inv_aS = 1.0f, beta = 1.0f, inv_beta = 1.0f;
-  for (int h = 0; h < W; ++h) {
-    const float aS = rg.stage_state(state + (b * lq.H + h0 + h) * NE);
-    if (rg.wave == h) {
-      rg.template build_A<false>(aS, A);
-      rg.load_vec(zo);
-      inv_aS = 1.0f / aS;
-      if constexpr (NORM) {   // power of two near the typical denominator (see bwd_state16)
-        const float* z = reinterpret_cast<const float*>(smem + C::kStageOffset) + D * D;
-        float zs = 0.0f;
-        for (int i = 0; i < D; ++i) zs += z[i];
-        if (zs > 0.0f && zs < 3.0e38f) {
-          int ex;
-          (void)__builtin_frexpf(zs, &ex);
-          ex = ex > 100 ? 100 : (ex < -100 ? -100 : ex);
-          beta = __builtin_ldexpf(1.0f, ex);
-          inv_beta = __builtin_ldexpf(1.0f, -ex);
-        }
+  auto build = [&](float aS) {
+    rg.template build_A<false>(aS, A);
+    rg.load_vec(zo);
+    inv_aS = 1.0f / aS;
+    if constexpr (NORM) {   // power of two near the typical denominator (see bwd_state16)
+      const float* z = rg.stage + D * D;
+      float zs = 0.0f;
+      for (int i = 0; i < D; ++i) zs += z[i];
+      if (zs > 0.0f && zs < 3.0e38f) {
+        int ex;
+        (void)__builtin_frexpf(zs, &ex);
+        ex = ex > 100 ? 100 : (ex < -100 ? -100 : ex);
+        beta = __builtin_ldexpf(1.0f, ex);
+        inv_beta = __builtin_ldexpf(1.0f, -ex);
       }
     }
-    __syncthreads();
+  };
+  if constexpr (C::kOwnStage) {
+    build(rg.stage_state_own(state + (b * lq.H + h0 + rg.wave) * NE));
+    __syncthreads();   // the staged states are dead: the second slot may be filled
+    rg.prefetch_second();
+  } else {
+    rg.prefetch_second();
+    for (int h = 0; h < W; ++h) {   // the heads' states pass through the third slot one after the other
+      const float aS = rg.stage_state(state + (b * lq.H + h0 + h) * NE);
+      if (rg.wave == h) build(aS);
+      __syncthreads();
+    }
   }
 
   f32x4 accS[MT][MT], accZ[MT];

@@ -77,10 +77,11 @@ struct BwdArgs {
   lf::Layout lq, lkv, lg, ldq, ldkv;   // q; k and v; dout; dq; dk and dv
 };
 
-// The row-piece kernels build their W heads' operands one head after the other (some 30 us per launch), which only
-// tensors from a few tens of MB up repay: B=2, H=8, N=16384, d=40 (21 MB) 105 -> 134 us, 201 MB 1.48 -> 0.51 ms.
+// The row-piece kernels run one workgroup of W waves per group and tile, with a longer prologue than the per-head
+// kernels: measured token-major, fp16 8 x 40, per-head / row-piece: 5 MB per tensor 43 / 50 us, 21 MB 106 / 102 us,
+// 84 MB 408 / 322 us, 1.3 GB 7.0 / 2.6 ms.  They are picked from 24 MB up.
 inline bool rows_pay(const BwdArgs& a, int d) {
-  return (double)a.B * a.H * (double)a.N * d * 2.0 >= (double)lfh::env_int("LINFUSION_BWD_ROWS_MIN_MB", 48) * 1048576.0;
+  return (double)a.B * a.H * (double)a.N * d * 2.0 >= (double)lfh::env_int("LINFUSION_BWD_ROWS_MIN_MB", 24) * 1048576.0;
 }
 
 // dK, dV: the row-piece kernel on groups of W heads where the heads of a token are neighbours in memory (k, v and
