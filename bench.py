@@ -261,12 +261,13 @@ def main():
         # gradient tensors resident in HBM; minimal traffic = q, k, v, dout read + dq, dk, dv written (7 tensors);
         # the kernels read k, v twice (9 tensor passes); bf16 and d > 48 also read q and dout twice (11 passes
         # plus 16 bytes per token-head of scalars written and read)
-        g = torch.randn_like(q)
-        grads = [torch.empty_like(q) for _ in range(3)]
+        # (--layout token_major: all seven tensors as strided views of [B, N, H*d] memory)
+        g = torch.empty_like(qd).copy_(torch.randn_like(q))   # keeps the strides of qd
+        grads = [torch.empty_like(qd) for _ in range(3)]
         bws = torch.empty(lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, code), dtype=torch.uint8, device="cuda")
 
         def bstep():
-            lf.linfusion_attn_bwd(q, k, v, g, *grads, lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, bws)   # state recomputed
+            lf.linfusion_attn_bwd_strided(qd, kd, vd, g, *grads, lf.PHI_ELU_PLUS_ONE, wl.EPS, 0, bws)   # state recomputed
         for _ in range(max(args.warmup // 2, 2)):
             bstep()
         torch.cuda.synchronize()
@@ -279,7 +280,7 @@ def main():
         tensor_bytes = alg_bytes / 4
         merged = dtype == "f16" and d <= 48
         kbytes = 9 * tensor_bytes if merged else 11 * tensor_bytes + 16.0 * B * H * N
-        result["backward"] = {"ms_per_step": bdt * 1e3, "tokens_per_s": B * N / bdt,
+        result["backward"] = {"layout": args.layout, "ms_per_step": bdt * 1e3, "tokens_per_s": B * N / bdt,
                               "min_traffic_gbps": 7 * tensor_bytes / bdt / 1e9,
                               "kernel_traffic_gbps": kbytes / bdt / 1e9,
                               "frac_of_peak_kernel_traffic": kbytes / bdt / 1e9 / HBM_PEAK_GBPS}

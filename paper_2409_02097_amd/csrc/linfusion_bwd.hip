@@ -148,6 +148,43 @@ bool qs_rows(const BwdArgs& a, const float* stateS, float* partials, int* wgs_us
   }
 }
 
+// the forward state of token-major k, v by the row-piece reduction (as the forward pass does); *nparts = partial
+// states per head written for combine_state
+template <typename T, int D, int FM, int W>
+int launch_state_rows(const BwdArgs& a, float* partials, int* nparts) {
+  using namespace lf;
+  constexpr int lds = ReduceRowsCfg<T, D, W>::kLdsBytes;
+  if (!allow_lds(state_reduce16_rows<T, D, FM, W>, lds)) return LINFUSION_ERR_HIP;
+  const int gpb = a.H / W;
+  const long long groups = (long long)a.B * gpb;
+  const long long n_tiles = (a.N + kTile - 1) / kTile;
+  long long s = lfh::env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * kNumCU) / (W / kWavesPerWG) / groups;
+  if (s > a.p->most) s = a.p->most;   // room for the partial states
+  if (s > n_tiles) s = n_tiles;
+  if (s < 1) s = 1;
+  long long blk = lfh::env_int("LINFUSION_GROUP_REDUCE_BLK", 2);
+  const long long share = (n_tiles + s - 1) / s;
+  if (blk > share) blk = share;
+  state_reduce16_rows<T, D, FM, W><<<dim3((unsigned)s, (unsigned)groups), dim3(64 * W), lds, a.st>>>(
+      (const u32x4*)a.k, (const u32x4*)a.v, a.lkv, gpb, partials, a.N, (int)blk);
+  *nparts = (int)s;
+  return LINFUSION_OK;
+}
+
+template <typename T, int D, int FM>
+bool state_rows(const BwdArgs& a, float* partials, int* nparts, int* rc) {
+  constexpr int CPR = D / 8;
+  if constexpr ((D * 2) % 128 == 0) return false;
+  if (a.lkv.head != CPR) return false;
+  const int mode = lfh::env_int("LINFUSION_BWD_ROWS", 1);   // 1: by size, 2: never, 3: always (a test aid)
+  if (mode == 2 || (mode != 3 && !rows_pay(a, D))) return false;
+  if constexpr (D <= 64) {
+    if (a.H % 8 == 0) { *rc = launch_state_rows<T, D, FM, 8>(a, partials, nparts); return true; }
+  }
+  if (a.H % 4 == 0) { *rc = launch_state_rows<T, D, FM, 4>(a, partials, nparts); return true; }
+  return false;
+}
+
 template <int D> constexpr bool kRowsW8 = D <= 48;                       // three slots of eight regions fit the LDS
 template <int D> constexpr bool kRowsW4 = D <= 56 || D == 80;
 
@@ -198,8 +235,11 @@ int run_bwd(const BwdArgs& a) {
   if (a.saved_state) {
     stateS = const_cast<float*>(a.saved_state);   // only read below
   } else {
-    state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, a.lkv, all, partials, a.N, p.blk_reduce);
-    combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.splits, NE, stateS);
+    int nparts = p.splits, rcs = LINFUSION_OK;
+    if (!state_rows<T, D, FM>(a, partials, &nparts, &rcs))
+      state_reduce16<T, D, FM><<<gr, blk, lds_r, st>>>(K, V, a.lkv, all, partials, a.N, p.blk_reduce);
+    if (rcs != LINFUSION_OK) return rcs;
+    combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, nparts, NE, stateS);
   }
   // fp16 up to d = 48: dQ and the state gradient in one pass over Q and dout (registers allow it there)
   constexpr bool kMerged = NSplit<T>::value == 1 && D <= 48;

@@ -185,12 +185,13 @@ def test_backward_on_token_major_views(B, H, N, d, dtype, monkeypatch):
     lf.linfusion_attn_bwd_strided(*views, *outs, 0, 1e-6, 0, ws)
     torch.cuda.synchronize()
     dense = _run(q, k, v, g)
-    # dq: the same bits as the contiguous call.  dk, dv: the same bits too unless the row-piece kernels took the
-    # state gradient, whose partial sums then run over the tiles in another order (fp32 rounding only)
-    assert torch.equal(outs[0].contiguous().view(torch.int16), dense[0].view(torch.int16))
-    for got, want in zip(outs[1:], dense[1:]):
+    # the row-piece kernels sum the state and the state gradient over the tiles in another order than the per-head
+    # kernels: the gradients agree with the contiguous call's up to that fp32 rounding
+    # (two units in the last place of the 16-bit results at most; the oracle check below is the measure of accuracy)
+    ulp2 = 2.0 ** -7 if dtype == "bf16" else 2.0 ** -10
+    for got, want in zip(outs, dense):
         diff = (got.contiguous().float() - want.float()).abs().max().item()
-        assert diff <= 2e-3 * want.float().abs().max().item(), f"token-major vs contiguous: {diff}"
+        assert diff <= ulp2 * want.float().abs().max().item(), f"token-major vs contiguous: {diff}"
     _check([o.contiguous() for o in outs], q, k, v, g, dtype, 0, 1e-6, True, "token-major")
     # and with the per-head kernels only: every gradient bit for bit as the contiguous call
     monkeypatch.setenv("LINFUSION_BWD_ROWS", "2")
