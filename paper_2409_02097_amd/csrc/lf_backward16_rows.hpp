@@ -1,9 +1,11 @@
-// Row-piece form of the dK / dV kernel of the backward pass (lf_backward16.hpp), for layouts in which the heads of
-// a token are neighbours in memory (token-major [B, N, H*d]) and a head's row is no whole cache line: a workgroup
-// of W waves takes a group of W heads, moves every tile as whole row pieces of W*d elements (both tensors, in and
-// out) through a workgroup-wide LDS-DMA ring, and wave w computes head w exactly as bwd_kv16 does -- same
-// products, same operands, same bits.  The ring, its rotation against bank conflicts and the pipeline with one
-// workgroup barrier per tile are those of ApplyDma's row-piece mode (lf_apply16_dma.hpp), with two tensors per slot.
+// Row-piece forms of the two apply-shaped kernels of the backward pass (lf_backward16.hpp), for layouts in which
+// the heads of a token are neighbours in memory (token-major [B, N, H*d]) and a head's row is no whole cache line:
+// a workgroup of W waves takes a group of W heads, moves every tile as whole row pieces of W*d elements (both
+// tensors, in and out) through a workgroup-wide LDS-DMA ring, and wave w computes head w exactly as the per-head
+// kernel does -- same products, same operands.  bwd_kv16_rows (dK, dV) gives the per-head kernel's bits;
+// bwd_qs16_rows (dQ and the state gradient, fp16) sums a head's partial in one wave instead of four.  The ring, its
+// rotation against bank conflicts and the pipeline with one workgroup barrier per tile are those of ApplyDma's
+// row-piece mode (lf_apply16_dma.hpp), with two tensors per slot.
 #pragma once
 #include "lf_backward16.hpp"
 
