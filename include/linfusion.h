@@ -192,12 +192,11 @@ int linfusion_attn_bwd(const void* q, const void* k, const void* v, const void* 
  * Speed: where the heads of a token are neighbours in memory (head stride == d, the UNet's [B, N, H*d]), a head's
  * row is no whole number of 128-byte lines (d * 2 % 128 != 0: d = 40, 80, ...), H is a multiple of 4 and a tensor
  * has 24 MB or more, the gradients come from kernels that move whole row pieces of four or eight neighbouring
- * heads: the forward state (when not handed in), dK and dV for every width up to 56 and 80, dQ and the state
- * gradient too for fp16 up to d = 48 (token-major 8 x 40 fp16 at 2 M tokens: 2.2 ms, against 7.0 ms on the per-head
- * kernels and 2.3 ms contiguous).  These kernels sum the state and its gradient over the tiles in another order
+ * heads: the forward state (when not handed in), dQ, dK and dV for every width up to 56 and 80, the state gradient
+ * too for fp16 up to d = 48 (token-major 8 x 40 at 2 M tokens: fp16 2.2 ms, against 7.0 ms on the per-head kernels
+ * and 2.3 ms contiguous; bf16 3.5 against 8.2 and 3.2 ms).  These kernels sum the state and its gradient over the tiles in another order
  * than the per-head kernels, so the gradients may differ from the contiguous call's in the last bit; they stay
- * run-to-run identical.  Other such layouts (bf16 or
- * d = 56, 80 for dQ; head counts that are no multiple of 4) run the per-head kernels on partial lines, at a
+ * run-to-run identical.  Head counts that are no multiple of 4 run the per-head kernels on partial lines, at a
  * fraction of the contiguous speed; d = 64 token-major does not suffer.
  */
 int linfusion_attn_bwd_strided(const void* q, const void* k, const void* v, const void* dout, const float* state,

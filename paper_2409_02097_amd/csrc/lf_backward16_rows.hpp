@@ -2,8 +2,9 @@
 // the heads of a token are neighbours in memory (token-major [B, N, H*d]) and a head's row is no whole cache line:
 // a workgroup of W waves takes a group of W heads, moves every tile as whole row pieces of W*d elements (both
 // tensors, in and out) through a workgroup-wide LDS-DMA ring, and wave w computes head w exactly as the per-head
-// kernel does -- same products, same operands.  bwd_kv16_rows (dK, dV) gives the per-head kernel's bits;
-// bwd_qs16_rows (dQ and the state gradient, fp16) sums a head's partial in one wave instead of four.  The ring, its
+// kernel does -- same products, same operands.  bwd_kv16_rows (dK, dV) and bwd_q16_rows (dQ, per-token scalars)
+// give the per-head kernels' bits; bwd_qs16_rows (dQ and the state gradient, fp16) sums a head's partial in one
+// wave instead of four.  The ring, its
 // rotation against bank conflicts and the pipeline with one workgroup barrier per tile are those of ApplyDma's
 // row-piece mode (lf_apply16_dma.hpp), with two tensors per slot.
 #pragma once
@@ -591,6 +592,119 @@ bwd_qs16_rows(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ 
       }
     }
   }
+}
+
+// ==========================================================================================
+// bwd_q16_rows: bwd_q16 (dQ and the per-token scalars {1 / den, e} for bwd_state16) on a group of W neighbouring
+// heads.  grid = (wgs, B * gpb), block = 64 W.  `scal`: [B*H][N] pairs.  Same values as the per-head kernel.
+// ==========================================================================================
+template <typename T, int D, int FM, bool NORM, int W>
+__global__ void __launch_bounds__(64 * W)
+bwd_q16_rows(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Layout lg, u32x4* __restrict__ dQ,
+             Layout ldq, int gpb, const float* __restrict__ state, f32x2* __restrict__ scal, float eps, long long N,
+             int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using RG = Ring2Rows<T, D, W>;
+  using C = BwdRowsCfg<D, W>;
+  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R;
+  constexpr int NE = D * D + D;
+  const long long b = blockIdx.y / gpb;
+  const long long h0 = (long long)(blockIdx.y % gpb) * W;
+  RG rg(Q + (b * lq.batch + h0 * lq.head), lq.row, G + (b * lg.batch + h0 * lg.head), lg.row, N, tiles_per_block,
+        blockIdx.x, gridDim.x, smem);
+  u32x4* dQg = dQ + (b * ldq.batch + h0 * ldq.head);
+  f32x2* sh = scal + (b * lq.H + h0 + rg.wave) * N;
+  rg.prefetch_first();
+
+  u32x4 A[NS][MTB][KS];
+  float zo[HALF];
+  float inv_aS = 1.0f;
+  if constexpr (C::kOwnStage) {
+    const float aS = rg.stage_state_own(state + (b * lq.H + h0 + rg.wave) * NE);
+    rg.template build_A<false>(aS, A);       // u = S g
+    rg.load_vec(zo);
+    inv_aS = 1.0f / aS;
+    __syncthreads();   // the staged states are dead: the second slot may be filled
+    rg.prefetch_second();
+  } else {
+    rg.prefetch_second();
+    for (int h = 0; h < W; ++h) {   // the heads' states pass through the third slot one after the other
+      const float aS = rg.stage_state(state + (b * lq.H + h0 + h) * NE);
+      if (rg.wave == h) {
+        rg.template build_A<false>(aS, A);
+        rg.load_vec(zo);
+        inv_aS = 1.0f / aS;
+      }
+      __syncthreads();
+    }
+  }
+
+  {   // this wave's rows of the first tile: only the second tile's copies were issued after them
+    TileIter second = rg.it;
+    second.next();
+    if (second.valid()) wait_vmcnt<2 * NL>();
+    else wait_vmcnt<0>();
+  }
+  lds_barrier();
+  int slot = 0, prev_slot = 0;
+  long long prev_tile = -1;
+  while (rg.it.valid()) {
+    const long long tile = rg.it.t;
+    const bool have_prev = prev_tile >= 0;
+    if (have_prev) rg.store_tile(prev_tile, prev_slot, 0, dQg, ldq.row);
+    const bool copied = rg.ahead.valid();
+    if (copied) rg.issue_copy(rg.ahead.t, have_prev ? prev_slot : R - 1);
+
+    u32x4 Bg[KS];
+    rg.read_B_raw(slot, 1, Bg);
+    f32x16 acc[MTB];
+    rg.products(A, Bg, nullptr, acc);
+    float x[HALF];
+    rg.read_half_row(slot, 0, x);             // q at this lane's output channels
+    float denp = 0.0f, rup = 0.0f;
+    float dr[HALF];
+#pragma unroll
+    for (int i = 0; i < HALF; ++i) {
+      const float r = phi<FM>(x[i]);
+      const float u = acc[i / 16][i % 16] * inv_aS;
+      denp = __builtin_fmaf(r, zo[i], denp);
+      rup = __builtin_fmaf(r, u, rup);
+      dr[i] = u;
+      x[i] = phi_prime_from<FM>(x[i], r);     // x now holds phi'(q)
+    }
+    if constexpr (NORM) {
+      const float den = denp + __shfl_xor(denp, 32) + eps;
+      const float ru = rup + __shfl_xor(rup, 32);
+      const float invden = 1.0f / den;
+      const float go = ru * invden;
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) dr[i] = (dr[i] - go * zo[i]) * invden * x[i];
+      long long rem = N - tile * kTile;
+      const int lim = rem < kTile ? (int)rem : kTile;
+      if (rg.kg == 0 && rg.tok < lim) sh[tile * kTile + rg.tok] = f32x2{invden, -go * invden};
+    } else {
+#pragma unroll
+      for (int i = 0; i < HALF; ++i) dr[i] *= x[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // both half-waves have read the row before it changes
+    rg.write_half_row(slot, 0, dr);
+
+    rg.it.next();
+    rg.ahead.next();
+    if (rg.it.valid()) {
+      // after the copies of tile j+1 came the stores of tile j-1 and the copies of tile j+2 (and up to two stores of
+      // scalars, which these counts leave out: a stricter wait, never a laxer one)
+      if (have_prev && copied) wait_vmcnt<3 * NL>();
+      else if (copied) wait_vmcnt<2 * NL>();
+      else if (have_prev) wait_vmcnt<NL>();
+      else wait_vmcnt<0>();
+    }
+    lds_barrier();   // tile j is finished by all waves; tile j+1 has landed for all
+    prev_tile = tile;
+    prev_slot = slot;
+    slot = slot + 1 == R ? 0 : slot + 1;
+  }
+  if (prev_tile >= 0) rg.store_tile(prev_tile, prev_slot, 0, dQg, ldq.row);
 }
 
 }  // namespace lf

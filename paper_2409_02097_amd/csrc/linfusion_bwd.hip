@@ -133,6 +133,47 @@ int launch_qs_rows(const BwdArgs& a, const float* stateS, float* partials, int* 
   return LINFUSION_OK;
 }
 
+// dQ and the per-token scalars (the separate-kernel path: bf16, d > 48) on groups of heads
+template <typename T, int D, int FM, bool NORM, int W>
+int launch_q_rows(const BwdArgs& a, const float* stateS, lf::f32x2* scal) {
+  using namespace lf;
+  constexpr int lds = BwdRowsCfg<D, W>::lds_bytes();
+  static_assert(lds <= 160 * 1024, "workgroup LDS limit of the device");
+  if (!allow_lds(bwd_q16_rows<T, D, FM, NORM, W>, lds)) return LINFUSION_ERR_HIP;
+  const int gpb = a.H / W;
+  const long long groups = (long long)a.B * gpb;
+  const long long n_tiles = (a.N + kTile - 1) / kTile;
+  const int resident = 160 * 1024 / lds > 0 ? 160 * 1024 / lds : 1;
+  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * kNumCU) / groups;
+  if (wgs > n_tiles) wgs = n_tiles;
+  if (wgs < 1) wgs = 1;
+  long long blk = lfh::env_int("LINFUSION_BWD_ROWS_BLK", 1);
+  const long long share = (n_tiles + wgs - 1) / wgs;
+  if (blk > share) blk = share;
+  bwd_q16_rows<T, D, FM, NORM, W><<<dim3((unsigned)wgs, (unsigned)groups), dim3(64 * W), lds, a.st>>>(
+      (const u32x4*)a.q, a.lq, (const u32x4*)a.g, a.lg, (u32x4*)a.dq, a.ldq, gpb, stateS, scal, a.eps, a.N, (int)blk);
+  return LINFUSION_OK;
+}
+
+template <typename T, int D, int FM, bool NORM>
+bool q_rows(const BwdArgs& a, const float* stateS, lf::f32x2* scal, int* rc) {
+  constexpr int CPR = D / 8;
+  if constexpr ((D * 2) % 128 == 0) {
+    return false;
+  } else {
+    if (a.lq.head != CPR || a.lg.head != CPR || a.ldq.head != CPR) return false;
+    const int mode = lfh::env_int("LINFUSION_BWD_ROWS", 1);   // 1: by size, 2: never, 3: always (a test aid)
+    if (mode == 2 || (mode != 3 && !rows_pay(a, D))) return false;
+    if constexpr (D <= 48) {
+      if (a.H % 8 == 0) { *rc = launch_q_rows<T, D, FM, NORM, 8>(a, stateS, scal); return true; }
+    }
+    if constexpr (D <= 56 || D == 80) {
+      if (a.H % 4 == 0) { *rc = launch_q_rows<T, D, FM, NORM, 4>(a, stateS, scal); return true; }
+    }
+    return false;
+  }
+}
+
 template <typename T, int D, int FM, bool NORM>
 bool qs_rows(const BwdArgs& a, const float* stateS, float* partials, int* wgs_used, int* rc) {
   constexpr int CPR = D / 8;
@@ -260,8 +301,11 @@ int run_bwd(const BwdArgs& a) {
       return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
     }
   }
-  bwd_q16<T, D, FM, NORM><<<ga, blk, lds_a, st>>>(Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, scal, a.eps, a.N,
-                                                  p.blk_apply);
+  int rcq = LINFUSION_OK;
+  if (!q_rows<T, D, FM, NORM>(a, stateS, scal, &rcq))
+    bwd_q16<T, D, FM, NORM><<<ga, blk, lds_a, st>>>(Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, scal, a.eps, a.N,
+                                                    p.blk_apply);
+  if (rcq != LINFUSION_OK) return rcq;
   bwd_state16<T, D, FM, NORM><<<dim3(p.gsplits, (unsigned)BH), blk, lds_s, st>>>(Q, a.lq, G, a.lg, scal, stateS,
                                                                                   partials, a.N, p.gblk_reduce);
   combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.gsplits, NE, stateD);
