@@ -84,6 +84,75 @@ def cpu_baseline(q, k, v, cfg, sample_tokens):
                       f"{os.cpu_count()} logical cores, BLAS threads = {threads}"}, ref
 
 
+def hbm_ceilings(nbytes=1342177280, reps=20):
+    """What plain streaming reaches on this device with the access pattern of the library's kernels
+    (linfusion_hbm_probe: 128-bit non-temporal accesses, workgroups sweeping one moving window): read-only
+    streams (the state reduction's pattern), one read + one write stream (apply's pattern), and the 3 : 1 mix
+    of a whole step.  Best launch size per pattern; every byte crosses HBM (streams of 1.34 GB each)."""
+    import torch
+    import paper_2409_02097_amd as lf
+    bufs = [torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device="cuda") for _ in range(3)]
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    rows = []
+    for reads, writes in ((1, 0), (2, 0), (1, 1), (3, 1), (2, 1), (0, 1)):
+        best = None
+        for wgs in (512, 1024, 2048, 4096, 8192, 16384):
+            def call():
+                lf.linfusion_hbm_probe(reads, writes, bufs[0], bufs[1], bufs[2], dst, nbytes, wgs, sink)
+            for _ in range(5):
+                call()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            torch.cuda.synchronize()
+            ev[0].record()
+            for _ in range(reps):
+                call()
+            ev[1].record()
+            torch.cuda.synchronize()
+            us = ev[0].elapsed_time(ev[1]) * 1e3 / reps
+            gbps = (reads + writes) * nbytes / us / 1e3
+            if best is None or gbps > best["gbps"]:
+                best = {"reads": reads, "writes": writes, "bytes_per_stream": nbytes, "workgroups": wgs,
+                        "avg_us": round(us, 1), "gbps": round(gbps, 1), "frac_of_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+        rows.append(best)
+    del bufs, dst
+    return rows
+
+
+def launch_floor(reps=200):
+    """Cost of launching by itself: one empty kernel, three dependent empty kernels (the split path's chain), and
+    one HIP-graph replay of those three; microseconds per chain, back to back on one stream, host-timed."""
+    import torch
+    import paper_2409_02097_amd as lf
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    res = {}
+    for label, n, wgs in (("one_empty_kernel", 1, 512), ("three_empty_kernels", 3, 512), ("three_empty_kernels_1wg", 3, 1)):
+        for _ in range(20):
+            lf.linfusion_launch_probe(n, wgs, sink)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            lf.linfusion_launch_probe(n, wgs, sink)
+        torch.cuda.synchronize()
+        res[label + "_us"] = round((time.perf_counter() - t0) / reps * 1e6, 2)
+    g = torch.cuda.CUDAGraph()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        lf.linfusion_launch_probe(3, 512, sink)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=st):
+            lf.linfusion_launch_probe(3, 512, sink)
+    for _ in range(20):
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        g.replay()
+    torch.cuda.synchronize()
+    res["graph_of_three_empty_kernels_us"] = round((time.perf_counter() - t0) / reps * 1e6, 2)
+    return res
+
+
 def latency_table(steps=200):
     """Per-call latency of the small and medium workloads (they fit the 256 MB memory-side cache):
     'hot' = the same buffers back to back, 'cold' = rotating through enough independent buffer sets
@@ -156,6 +225,9 @@ def main():
     ap.add_argument("--latency-table", action="store_true",
                     help="also time the small and medium workloads, hot and cold cache, both launch paths "
                          "(JSON lines on stderr; the one-line result on stdout is unchanged)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="also measure what plain streaming kernels reach on this device (read-only, copy, 3:1 mix) "
+                         "and what empty launches cost; reported in extra `hbm_ceilings` and `launch_floor` objects")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of one tensor (known size) so that a rocprofv3 --pmc "
                          "run of this command holds the reference reading for FETCH_SIZE / WRITE_SIZE")
@@ -411,6 +483,9 @@ def main():
     if not args.no_cpu_baseline:
         base, ref = cpu_baseline(q, k, v, cfg, args.cpu_sample_tokens)
         result["cpu_baseline"] = base
+    if args.ceilings:
+        result["hbm_ceilings"] = hbm_ceilings()
+        result["launch_floor"] = launch_floor()
     if args.latency_table:
         del q, k, v, qd, kd, vd, out
         torch.cuda.empty_cache()

@@ -308,7 +308,10 @@ size_t linfusion_attn_qv_workspace_bytes(int B, int H, long long N, int d_qk, in
 /*
  * Synchronises `stream` and reports whether the most recent single-launch call that used this
  * workspace for this shape completed: LINFUSION_OK, LINFUSION_ERR_TIMEOUT, or an argument / HIP
- * error code.  (The split path cannot time out; after it this returns LINFUSION_OK.)
+ * error code.  The answer is read from records the single-launch kernels keep inside the workspace
+ * itself, so calls on other workspaces, streams or threads do not disturb it.  (The split path
+ * cannot time out and leaves the records alone; a workspace no single-launch call has used
+ * reports LINFUSION_OK.)
  */
 int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes,
                               int B, int H, long long N, int d, int dtype, void* stream);
@@ -321,8 +324,10 @@ int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes,
 size_t linfusion_attn_workspace_state_offset(int B, int H, long long N, int d, int dtype);
 
 /*
- * Bytes of device scratch linfusion_attn_fwd_ex needs for this shape.  Pure host function of
- * its arguments (no device query); returns 0 for arguments the forward call would reject.
+ * Bytes of device scratch linfusion_attn_fwd_ex needs for this shape; 0 for arguments the forward
+ * call would reject.  Host function of its arguments and of the current device's compute-unit count
+ * (launch sizes follow it; 256, one whole MI355X, is assumed while no device is visible).  No
+ * environment variable enters unless tuning has been switched on (linfusion_set_tuning).
  */
 size_t linfusion_attn_workspace_bytes(int B, int H, long long N, int d, int dtype);
 
@@ -332,7 +337,9 @@ size_t linfusion_attn_workspace_bytes(int B, int H, long long N, int d, int dtyp
  * _bf16, fp32 for _f32.  They use a library-owned scratch buffer per device that is allocated
  * with hipMalloc on first use (and re-allocated when a later call needs more), so the first
  * call per device -- and any call that grows the buffer -- synchronises that device.  Calls
- * on one device must be issued from one thread at a time and ordered on one stream.
+ * on one device must be issued from one thread at a time and ordered on one stream.  They always
+ * take the three-kernel path, which cannot time out (the caller has no workspace to ask
+ * linfusion_attn_last_error about).
  */
 int linfusion_attn_fwd(const void* q, const void* k, const void* v, void* out,
                        int B, int H, long long N, int d, int feature_map, float eps, void* stream);
@@ -362,6 +369,34 @@ const char* linfusion_status_string(int status);
 
 /* major * 10000 + minor * 100 + patch */
 int linfusion_version(void);
+
+/*
+ * Measurement aids (no arithmetic of the method): what plain streaming and plain launching reach on the
+ * device, for the roofline figures of the benchmark to be compared with.
+ *
+ * linfusion_hbm_probe enqueues one kernel that reads `reads` (0..3) streams a, b, c and writes `writes` (0 or 1)
+ * stream d of `bytes` bytes each (a multiple of 16), every byte once, with 256-thread workgroups, 128-bit
+ * non-temporal accesses and `workgroups` workgroups that sweep the streams in one moving window -- the access
+ * pattern of the state reduction (reads = 2, writes = 0) and of apply (reads = 1, writes = 1).  With reads > 0
+ * the written (or, with writes = 0, discarded) value is the xor of the streams read.  All pointers DEVICE,
+ * 16-byte aligned; unused ones may be NULL; `sink`: DEVICE pointer to two 32-bit words (required when
+ * writes = 0).
+ * linfusion_launch_probe enqueues `launches` (1..1024) kernels of `workgroups` x 256 threads that do nothing,
+ * back to back on `stream`: the cost of a dependent chain of launches by itself.
+ * Both return LINFUSION_OK or LINFUSION_ERR_INVALID / _MISALIGNED / _DEVICE / _HIP; never allocate or synchronise.
+ */
+int linfusion_hbm_probe(int reads, int writes, const void* a, const void* b, const void* c, void* d,
+                        size_t bytes, int workgroups, unsigned* sink, void* stream);
+int linfusion_launch_probe(int launches, int workgroups, unsigned* sink, void* stream);
+
+/*
+ * Development switch.  The LINFUSION_* environment variables (launch shapes, forced kernel routes, the
+ * single launch's poll limit: aids for sweeps and tests) are consulted only while tuning is on; it is
+ * off unless LINFUSION_TUNE=1 was in the environment when the library was first used or this function
+ * switched it on.  With tuning off no call reads the environment and launch plans and workspace sizes
+ * depend on the shape and the device alone.
+ */
+void linfusion_set_tuning(int on);
 
 /*
  * Introspection for benchmarks and tests (host only, no device work): the launch plan the

@@ -90,6 +90,12 @@ def library() -> ctypes.CDLL:
     lib.linfusion_status_string.restype = ctypes.c_char_p
     lib.linfusion_version.argtypes = []
     lib.linfusion_version.restype = i32
+    lib.linfusion_hbm_probe.argtypes = [i32, i32, vp, vp, vp, vp, sz, i32, vp, vp]
+    lib.linfusion_hbm_probe.restype = i32
+    lib.linfusion_launch_probe.argtypes = [i32, i32, vp, vp]
+    lib.linfusion_launch_probe.restype = i32
+    lib.linfusion_set_tuning.argtypes = [i32]
+    lib.linfusion_set_tuning.restype = None
     lib.linfusion_attn_plan.argtypes = [i32, i32, i64, i32, i32, u32, ctypes.POINTER(ctypes.c_int * 4)]
     lib.linfusion_attn_plan.restype = i32
     _lib = lib
@@ -391,6 +397,32 @@ def linfusion_attn_state(k, v, state_out, feature_map: int = PHI_ELU_PLUS_ONE, w
     if check and rc != 0:
         raise LinFusionError(rc, "linfusion_attn_state")
     return rc
+
+
+def linfusion_hbm_probe(reads: int, writes: int, a, b, c, d, nbytes: int, workgroups: int, sink, stream=None,
+                        check: bool = True) -> int:
+    """One plain streaming kernel: reads `reads` of the uint8 device tensors a, b, c and writes `writes` of d,
+    `nbytes` bytes each (measurement aid)."""
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    rc = library().linfusion_hbm_probe(reads, writes, ptr(a), ptr(b), ptr(c), ptr(d), nbytes, workgroups, ptr(sink),
+                                       _stream_ptr(stream))
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_hbm_probe")
+    return rc
+
+
+def linfusion_launch_probe(launches: int, workgroups: int, sink, stream=None, check: bool = True) -> int:
+    """`launches` empty kernels back to back on the stream (measurement aid)."""
+    rc = library().linfusion_launch_probe(launches, workgroups, sink.data_ptr() if sink is not None else None,
+                                          _stream_ptr(stream))
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_launch_probe")
+    return rc
+
+
+def linfusion_set_tuning(on: bool) -> None:
+    """Switches on / off whether the library looks at the LINFUSION_* environment variables (development aids)."""
+    library().linfusion_set_tuning(1 if on else 0)
 
 
 def linfusion_release() -> None:

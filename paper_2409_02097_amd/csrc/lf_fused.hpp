@@ -9,14 +9,16 @@
 // grid = (splits, B*H), block = 256; the host launches it only when every workgroup of the grid is
 // resident at once.  All sums run in a fixed order, so results are run-to-run bit-identical.
 //
-// Barrier: every workgroup owns one 32-bit flag per barrier in the caller's workspace and publishes
+// Barrier: every workgroup owns one 64-bit flag per barrier in the caller's workspace and publishes
 // its arrival by storing the call's `ticket` there; wave 0 of each workgroup then polls the flags of
 // all workgroups of its head (one lane per flag).  There is no read-modify-write and no shared
-// counter, so arrivals never contend, and because the ticket is unique per call a flag left by an
-// earlier call (or any other content) reads as "not arrived": the workspace needs no initialisation
-// and nothing is reset afterwards.  Waiting is bounded: a workgroup that does not see all arrivals
-// within `spin_limit` polls raises the error word and returns, so every wave reaches the end of the
-// kernel whatever happens.
+// counter, so arrivals never contend.  The ticket is {t, ~t} with t unique per call and counted from a
+// random per-process base, so a flag left by an earlier call reads as "not arrived", and so does any
+// other content the workspace may hold (it would have to agree in all 64 bits): the workspace needs no
+// initialisation and nothing is reset afterwards.  Waiting is bounded: a workgroup that does not see
+// all arrivals within `spin_limit` polls records the ticket as failed and returns, so every wave
+// reaches the end of the kernel whatever happens.  `rec`: two 64-bit words behind the flags,
+// {ticket of the last call that ran on this workspace, ticket of the last call that gave up}.
 #pragma once
 #include "lf_apply16_dma.hpp"
 #include "lf_fp32.hpp"
@@ -25,8 +27,8 @@ namespace lf {
 
 // Returns false (for every thread of the workgroup) when the wait timed out.
 // `flags`: the nsplit flags of this head and barrier.
-LF_DEV bool head_barrier(unsigned* flags, int split, int nsplit, unsigned ticket, unsigned spin_limit,
-                         unsigned* err, int* lds_flag) {
+LF_DEV bool head_barrier(unsigned long long* flags, int split, int nsplit, unsigned long long ticket,
+                         unsigned spin_limit, unsigned long long* rec, int* lds_flag) {
   // The partial states / states exchanged through this barrier are written with st_agent and read
   // with ld_agent, so no cache write-back or invalidation is needed here (a device-scope fence writes
   // back and invalidates the whole L2 of the XCD, measured at several microseconds per wave): it is
@@ -52,10 +54,7 @@ LF_DEV bool head_barrier(unsigned* flags, int split, int nsplit, unsigned ticket
       }
     }
     if (threadIdx.x == 0) {
-      if (!ok) {   // error word: {ticket of the failing call, 1}
-        __hip_atomic_store(err, ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(err + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+      if (!ok) __hip_atomic_store(rec + 1, ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *lds_flag = ok;
     }
   }
@@ -114,7 +113,8 @@ constexpr int fused16_lds_bytes() {
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
 fused16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, const u32x4* __restrict__ Q,
-        Layout lq, u32x4* __restrict__ O, Layout lo, float* partials, float* state, unsigned* flags, unsigned* err, unsigned ticket,
+        Layout lq, u32x4* __restrict__ O, Layout lo, float* partials, float* state, unsigned long long* flags, unsigned long long* rec,
+        unsigned long long ticket,
         unsigned spin_limit, float eps, long long N, int blk_reduce, int blk_apply) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int flag;
@@ -124,14 +124,16 @@ fused16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, co
   float* head_part = partials + bh * nsplit * (long long)NE;
   float* head_state = state + bh * NE;
   const long long okv = lkv.slice(bh);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    __hip_atomic_store(rec, ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   reduce16_phase<T, D, FM>(K + okv, V + okv, lkv.row, head_part + (long long)split * NE, N, blk_reduce, split, nsplit,
                            smem);
-  if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
+  if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, rec, &flag)) return;
   ApplyDma<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, blk_apply, split, nsplit, smem);
   ap.prefetch();   // Q does not depend on the state: its first tiles travel during phase 2 and the barrier
   combine_owned(head_part, nsplit, NE, split, head_state,
                 reinterpret_cast<float*>(smem + ApplyDmaCfg<D>::kStageOffset));
-  if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) {
+  if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, rec, &flag)) {
     wait_vmcnt<0>();   // no copy into this workgroup's LDS may still be in flight when it ends
     return;
   }
@@ -145,7 +147,8 @@ template <int D> constexpr int fused32_lds_bytes() {
 template <int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
 fused32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout lkv, const f32x4* __restrict__ Q,
-        Layout lq, f32x4* __restrict__ O, Layout lo, float* partials, float* state, unsigned* flags, unsigned* err, unsigned ticket,
+        Layout lq, f32x4* __restrict__ O, Layout lo, float* partials, float* state, unsigned long long* flags, unsigned long long* rec,
+        unsigned long long ticket,
         unsigned spin_limit, float eps, long long N, int blk_reduce, int blk_apply) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int flag;
@@ -155,10 +158,12 @@ fused32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout lkv, co
   float* head_part = partials + bh * nsplit * (long long)NE;
   float* head_state = state + bh * NE;
   const long long okv = lkv.slice(bh);
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    __hip_atomic_store(rec, ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   reduce32_phase<D, FM>(K + okv, V + okv, lkv.row, head_part + (long long)split * NE, N, blk_reduce, split, nsplit, smem);
-  if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
+  if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, rec, &flag)) return;
   combine_owned(head_part, nsplit, NE, split, head_state, reinterpret_cast<float*>(smem));
-  if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, err, &flag)) return;
+  if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, rec, &flag)) return;
   Apply32Dma<D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, blk_apply, split, nsplit, smem);
   ap.prefetch();   // the combine's scratch in LDS is dead after the barrier
   ap.template load_state<true>(head_state);

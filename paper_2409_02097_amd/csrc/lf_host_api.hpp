@@ -8,8 +8,11 @@ namespace lfh {
 
 // LINFUSION_OK when the current device is a gfx950, else LINFUSION_ERR_DEVICE (cached per device)
 int check_device();
-// positive integer from the environment, `dflt` when unset or not positive (tuning aids)
+// `dflt`, unless tuning is switched on (LINFUSION_TUNE=1 at first use, or linfusion_set_tuning) and the
+// environment holds a positive integer under `name`
 int env_int(const char* name, int dflt);
+// compute units of the current device (256 while no device is visible)
+int num_cu();
 
 // Element strides {batch, head, token} of a [B, H, N, d] view with contiguous channels (null = dense).
 // check_strides: LINFUSION_OK when the kernels can address the view (non-negative, token rows 16-byte aligned,

@@ -9,8 +9,10 @@
 #include <string.h>
 
 #include <atomic>
+#include <chrono>
 #include <cmath>
 #include <mutex>
+#include <random>
 
 #include "lf_fused.hpp"
 #include "lf_host_api.hpp"
@@ -18,9 +20,54 @@
 
 namespace {
 
-constexpr int kVersion = 500;  // 0.5.0
+constexpr int kVersion = 600;  // 0.6.0
 constexpr int kMaxDevices = 16;
-constexpr int kNumCU = 256;    // the library targets one chip
+constexpr int kDefaultCU = 256;   // compute units assumed while no device can be asked (one whole MI355X)
+
+// ---- per-device facts, asked once ---------------------------------------------------------------
+std::mutex g_mu;
+int g_dev_ok[kMaxDevices];   // 0 = unknown, 1 = gfx950, -1 = something else
+int g_dev_cu[kMaxDevices];   // compute units of the device (valid once g_dev_ok != 0)
+
+// fills g_dev_ok / g_dev_cu for the current device; returns its index or -1
+int probe_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0) { (void)hipGetLastError(); return -1; }
+  if (dev >= kMaxDevices) return -1;
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (g_dev_ok[dev] == 0) {
+    hipDeviceProp_t pr;
+    if (hipGetDeviceProperties(&pr, dev) != hipSuccess) { (void)hipGetLastError(); return -1; }
+    g_dev_ok[dev] = strncmp(pr.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+    g_dev_cu[dev] = pr.multiProcessorCount > 0 ? pr.multiProcessorCount : kDefaultCU;
+  }
+  return dev;
+}
+
+// Compute units of the current device: launch sizes and the residency test of the single-launch kernel follow
+// it (a partitioned device has fewer than the whole chip's 256).  kDefaultCU when no device is visible, so the
+// size queries still answer on a host without a GPU.
+int num_cu() {
+  const int dev = probe_device();
+  return dev >= 0 ? g_dev_cu[dev] : kDefaultCU;
+}
+
+// ---- tuning switch ---------------------------------------------------------------------------------
+// The LINFUSION_* environment variables (launch shapes, forced routes, the barrier poll limit) are development
+// aids.  They are looked at only while tuning is on -- LINFUSION_TUNE=1 in the environment when the library is
+// first used, or linfusion_set_tuning(1) -- so the default path reads no environment at all and the launch
+// plan is a function of the shape and the device alone.
+std::atomic<int> g_tuning{-1};   // -1 = not decided yet
+
+bool tuning_on() {
+  int t = g_tuning.load(std::memory_order_relaxed);
+  if (t < 0) {
+    const char* s = getenv("LINFUSION_TUNE");
+    t = (s && *s && atoi(s) > 0) ? 1 : 0;
+    g_tuning.store(t, std::memory_order_relaxed);
+  }
+  return t == 1;
+}
 
 // ---- launch plan (pure function of the shape and flags) ----------------------------------------
 struct Plan {
@@ -40,6 +87,7 @@ struct Plan {
 };
 
 int env_int(const char* name, int dflt) {
+  if (!tuning_on()) return dflt;
   const char* s = getenv(name);
   if (!s || !*s) return dflt;
   int v = atoi(s);
@@ -101,8 +149,8 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
       *blk = block_tiles(t, env_blk, blk_dflt, 1);
       return (int)((p->n_tiles + t - 1) / t);
     };
-    p->splits = per_head(env_int("LINFUSION_WIDE_REDUCE_WGS", 2 * kNumCU), 4, "LINFUSION_WIDE_REDUCE_BLK", &p->blk_reduce);
-    p->apply_wgs = per_head(env_int("LINFUSION_WIDE_APPLY_WGS", 2 * kNumCU), 1, "LINFUSION_WIDE_APPLY_BLK", &p->blk_apply);
+    p->splits = per_head(env_int("LINFUSION_WIDE_REDUCE_WGS", 2 * num_cu()), 4, "LINFUSION_WIDE_REDUCE_BLK", &p->blk_reduce);
+    p->apply_wgs = per_head(env_int("LINFUSION_WIDE_APPLY_WGS", 2 * num_cu()), 1, "LINFUSION_WIDE_APPLY_BLK", &p->blk_apply);
     p->fsplits = 0;
     p->fblk_reduce = p->fblk_apply = 1;
     p->gwaves = lf::kWavesPerWG;
@@ -132,7 +180,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   long long share = 0;
   // state reduction (read-only stream): two workgroups per CU measured best -- fewer, longer
   // streams keep DRAM pages open
-  p->splits = per_head(env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), &share);
+  p->splits = per_head(env_int("LINFUSION_REDUCE_WGS", 2 * num_cu()), &share);
   p->blk_reduce = block_tiles(share, "LINFUSION_REDUCE_BLK", 16);
   // apply (read + write streams): more, smaller workgroups that sweep memory in one moving window.
   // Up to a few hundred MB of tensor traffic one resident round measured best (a second, partly filled
@@ -140,11 +188,11 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
   const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
   const bool one_round = bytes < (double)env_int("LINFUSION_APPLY_ONE_ROUND_MB", 768) * 1048576.0;
-  const int apply_dflt = (one_round ? apply_wgs_per_cu(d, dtype) : 8) * kNumCU;
+  const int apply_dflt = (one_round ? apply_wgs_per_cu(d, dtype) : 8) * num_cu();
   p->apply_wgs = per_head(env_int("LINFUSION_APPLY_WGS", apply_dflt), &share);
   p->blk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", 8);
   // fused single launch: every workgroup must be resident at once
-  const long long cap = (long long)fused_wgs_per_cu(d, dtype) * kNumCU;
+  const long long cap = (long long)fused_wgs_per_cu(d, dtype) * num_cu();
   p->fsplits = 0;
   if (BH <= cap) {
     p->fsplits = per_head((int)(cap / BH * BH), &share);
@@ -166,9 +214,9 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     };
     // (the defaults are in 256-thread units: a workgroup of eight waves counts twice)
     const int unit = p->gwaves / lf::kWavesPerWG;
-    p->gsplits = per_group(env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * kNumCU) / unit, &share);
+    p->gsplits = per_group(env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * num_cu()) / unit, &share);
     p->gblk_reduce = block_tiles(share, "LINFUSION_GROUP_REDUCE_BLK", 2, 1);
-    p->gapply_wgs = per_group(env_int("LINFUSION_GROUP_APPLY_WGS", 2 * kNumCU) / unit, &share);
+    p->gapply_wgs = per_group(env_int("LINFUSION_GROUP_APPLY_WGS", 2 * num_cu()) / unit, &share);
     // measured best: one workgroup of eight waves (two of four) per CU, tiles dealt out one at a time so
     // that the whole chip sweeps one narrow window of memory
     p->gblk_apply = block_tiles(share, "LINFUSION_GROUP_APPLY_BLK", p->gwaves == 8 ? 1 : 2, 1);
@@ -192,7 +240,8 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   if (dtype != LINFUSION_DTYPE_F32 && p->gsplits > smax) smax = p->gsplits;
   p->ws_partials = up((size_t)BH * smax * p->state_floats * sizeof(float));
   p->ws_state = up((size_t)BH * p->state_floats * sizeof(float));
-  p->ws_sync = up((size_t)BH * 2 * (p->fsplits > 0 ? p->fsplits : 1) * sizeof(unsigned) + 16);
+  // single launch: one 64-bit flag per workgroup and barrier, then two 64-bit records {last call, failed call}
+  p->ws_sync = up((size_t)BH * 2 * (p->fsplits > 0 ? p->fsplits : 1) * sizeof(unsigned long long) + 16);
   p->ws_pack = 0;
   if (dtype != LINFUSION_DTYPE_F32 && p->groups > 0) {
     const size_t ns = dtype == LINFUSION_DTYPE_BF16 ? 2 : 1;
@@ -204,31 +253,31 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
 }
 
 // ---- device check (cached per device) ------------------------------------------------------------
-int g_dev_ok[kMaxDevices];   // 0 = unknown, 1 = gfx950, -1 = something else
-std::mutex g_mu;
-std::atomic<unsigned> g_ticket{1};
-std::atomic<unsigned> g_last_ticket{0};   // ticket of the most recent single-launch call
-
 int check_device() {
-  int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0) { (void)hipGetLastError(); return LINFUSION_ERR_DEVICE; }
-  if (dev >= kMaxDevices) return LINFUSION_ERR_DEVICE;
-  std::lock_guard<std::mutex> lk(g_mu);
-  if (g_dev_ok[dev] == 0) {
-    hipDeviceProp_t pr;
-    if (hipGetDeviceProperties(&pr, dev) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_DEVICE; }
-    g_dev_ok[dev] = strncmp(pr.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
-  }
+  const int dev = probe_device();
+  if (dev < 0) return LINFUSION_ERR_DEVICE;
   return g_dev_ok[dev] == 1 ? LINFUSION_OK : LINFUSION_ERR_DEVICE;
 }
 
 using lfh::overlaps;
 
-unsigned next_ticket() {
+// Barrier tickets of the single-launch kernel.  A call's ticket is a 64-bit word {t, ~t}: t counts up from a
+// base drawn at random once per process, so no earlier call of this or another process used it, and a word the
+// (uninitialised) workspace happens to hold equals it only if all 64 bits agree -- a stale flag, a counter, a
+// bool or a float pattern never has its upper half equal to the complement of its lower half and to this t.
+std::atomic<unsigned> g_ticket{0};
+std::once_flag g_ticket_once;
+
+unsigned long long next_ticket() {
+  std::call_once(g_ticket_once, [] {
+    std::random_device rd;
+    const unsigned long long mix = ((unsigned long long)rd() << 32) ^ rd() ^
+                                   (unsigned long long)std::chrono::steady_clock::now().time_since_epoch().count();
+    g_ticket.store((unsigned)(mix ^ (mix >> 32)) | 1u, std::memory_order_relaxed);
+  });
   unsigned t = g_ticket.fetch_add(1, std::memory_order_relaxed);
   if (t == 0) t = g_ticket.fetch_add(1, std::memory_order_relaxed);
-  g_last_ticket.store(t, std::memory_order_relaxed);
-  return t;
+  return ((unsigned long long)t << 32) | (unsigned long long)(~t);
 }
 
 // true when `grid` workgroups of `kernel` (256 threads, `lds` dynamic bytes) are resident at once
@@ -239,7 +288,7 @@ bool fits_resident(KernelT kernel, size_t lds, long long grid) {
     (void)hipGetLastError();
     return false;
   }
-  return (long long)per_cu * kNumCU >= grid;
+  return (long long)per_cu * num_cu() >= grid;
 }
 
 using lfh::allow_lds;
@@ -274,8 +323,10 @@ struct Args {
 // polls (of about a microsecond each) before a single-launch call gives up at a barrier; the
 // environment override exists so that a test can force the give-up path from the host
 unsigned spin_limit() {
-  const char* s = getenv("LINFUSION_FUSED_SPIN_LIMIT");
-  if (s && *s) return (unsigned)strtoul(s, nullptr, 10);
+  if (tuning_on()) {
+    const char* s = getenv("LINFUSION_FUSED_SPIN_LIMIT");
+    if (s && *s) return (unsigned)strtoul(s, nullptr, 10);
+  }
   return 4u << 20;
 }
 
@@ -309,8 +360,8 @@ int run16(const Args& a) {
   u32x4* O = (u32x4*)a.out;
   hipStream_t st = a.st;
   if (p.path == 1 && a.out && !(a.group_reduce || a.group_apply) && !capturing(a.st)) {
-    unsigned* sync = reinterpret_cast<unsigned*>(a.ws + p.ws_partials + p.ws_state);
-    unsigned* err = sync + a.BH * 2 * p.fsplits;
+    unsigned long long* sync = reinterpret_cast<unsigned long long*>(a.ws + p.ws_partials + p.ws_state);
+    unsigned long long* err = sync + a.BH * 2 * p.fsplits;
     const dim3 g(p.fsplits, (unsigned)a.BH);
     const size_t lds = fused16_lds_bytes<T, D>();
     bool launched = false;
@@ -435,8 +486,8 @@ int run32(const Args& a) {
   constexpr size_t ldsf = fused32_lds_bytes<D>();
   constexpr size_t ldsa = apply32_lds_bytes<D>();
   if (p.path == 1 && a.out && !capturing(a.st)) {
-    unsigned* sync = reinterpret_cast<unsigned*>(a.ws + p.ws_partials + p.ws_state);
-    unsigned* err = sync + a.BH * 2 * p.fsplits;
+    unsigned long long* sync = reinterpret_cast<unsigned long long*>(a.ws + p.ws_partials + p.ws_state);
+    unsigned long long* err = sync + a.BH * 2 * p.fsplits;
     const dim3 g(p.fsplits, (unsigned)a.BH);
     bool launched = false;
 #define LF_FUSED(FM, NORM)                                                                           \
@@ -647,7 +698,8 @@ int fwd_owned(const void* q, const void* k, const void* v, void* out, int B, int
   void* ws = nullptr;
   rc = owned_workspace(need, &ws);
   if (rc != LINFUSION_OK) return rc;
-  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, 0u, ws, need, stream, nullptr);
+  // the three-kernel path, which cannot time out: the caller of these entry points has no workspace to ask about
+  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, LINFUSION_FLAG_FORCE_SPLIT, ws, need, stream, nullptr);
 }
 
 }  // namespace
@@ -655,6 +707,7 @@ int fwd_owned(const void* q, const void* k, const void* v, void* out, int B, int
 namespace lfh {
 int check_device() { return ::check_device(); }
 int env_int(const char* name, int dflt) { return ::env_int(name, dflt); }
+int num_cu() { return ::num_cu(); }
 int check_strides(const long long s[3], int B, int H, long long N, int d, size_t esz, bool written) {
   return ::check_strides(Strides{s[0], s[1], s[2]}, B, H, N, d, esz, written);
 }
@@ -703,12 +756,16 @@ int linfusion_attn_last_error(const void* workspace, size_t workspace_bytes, int
   if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
   if (p.fsplits == 0) return LINFUSION_OK;   // no single-launch path for this shape: nothing can time out
   const unsigned char* ws = (const unsigned char*)workspace;
-  const unsigned* err = reinterpret_cast<const unsigned*>(ws + p.ws_partials + p.ws_state) +
-                        (size_t)B * H * 2 * (p.fsplits > 0 ? p.fsplits : 1);
-  unsigned pair[2] = {0, 0};   // {ticket of the call that raised it, 1}
-  if (hipMemcpy(pair, err, sizeof(pair), hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
-  // the word is meaningful only when it carries the ticket of the last single-launch call on this process
-  return (pair[1] == 1u && pair[0] != 0u && pair[0] == g_last_ticket.load()) ? LINFUSION_ERR_TIMEOUT : LINFUSION_OK;
+  const unsigned long long* rec = reinterpret_cast<const unsigned long long*>(ws + p.ws_partials + p.ws_state) +
+                                  (size_t)B * H * 2 * p.fsplits;
+  // {ticket of the last single-launch call that ran on this workspace, ticket of the last one that gave up}:
+  // both written by the kernels themselves, so the answer belongs to this workspace whatever ran elsewhere.
+  // A well-formed ticket has its lower half equal to the complement of its upper half; anything else is the
+  // workspace's undefined initial content (no single-launch call has used it yet).
+  unsigned long long pair[2] = {0, 0};
+  if (hipMemcpy(pair, rec, sizeof(pair), hipMemcpyDeviceToHost) != hipSuccess) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
+  const bool formed = (unsigned)(pair[0] >> 32) == ~(unsigned)pair[0];
+  return (formed && pair[1] == pair[0]) ? LINFUSION_ERR_TIMEOUT : LINFUSION_OK;
 }
 
 size_t linfusion_attn_workspace_state_offset(int B, int H, long long N, int d, int dtype) {
@@ -793,6 +850,8 @@ const char* linfusion_status_string(int status) {
 }
 
 int linfusion_version(void) { return kVersion; }
+
+void linfusion_set_tuning(int on) { g_tuning.store(on ? 1 : 0, std::memory_order_relaxed); }
 
 int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned flags, int plan[4]) {
   if (!plan) return LINFUSION_ERR_INVALID;

@@ -11,7 +11,6 @@
 
 namespace {
 
-constexpr int kNumCU = 256;
 
 struct BwdPlan {
   int splits, blk_reduce, apply_wgs, blk_apply;
@@ -43,11 +42,11 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   // Launch sizes measured on MI355X: up to a few hundred MB of tensor traffic two workgroups per CU (one resident
   // round) are best for the gradient kernels too; at GB sizes four (dQ, dK/dV) and eight (state gradient) per CU.
   const bool mid = 4.0 * (double)BH * (double)N * d * 2.0 < (double)lfh::env_int("LINFUSION_APPLY_ONE_ROUND_MB", 768) * 1048576.0;
-  p->splits = per_head(lfh::env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_REDUCE_BLK", 16),
+  p->splits = per_head(lfh::env_int("LINFUSION_REDUCE_WGS", 2 * lfh::num_cu()), lfh::env_int("LINFUSION_REDUCE_BLK", 16),
                        &p->blk_reduce);
-  p->gsplits = per_head(lfh::env_int("LINFUSION_BWD_REDUCE_WGS", (mid ? 2 : 8) * kNumCU),
+  p->gsplits = per_head(lfh::env_int("LINFUSION_BWD_REDUCE_WGS", (mid ? 2 : 8) * lfh::num_cu()),
                         lfh::env_int("LINFUSION_BWD_REDUCE_BLK", 16), &p->gblk_reduce);
-  p->apply_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY_WGS", (mid ? 2 : 4) * kNumCU),
+  p->apply_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY_WGS", (mid ? 2 : 4) * lfh::num_cu()),
                           lfh::env_int("LINFUSION_BWD_APPLY_BLK", 8), &p->blk_apply);
   p->ne = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -96,7 +95,7 @@ int launch_kv_rows(const BwdArgs& a, const float* stateD) {
   const long long groups = (long long)a.B * gpb;
   const long long n_tiles = (a.N + kTile - 1) / kTile;
   const int resident = 160 * 1024 / lds > 0 ? 160 * 1024 / lds : 1;
-  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * kNumCU) / groups;
+  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * lfh::num_cu()) / groups;
   if (wgs > n_tiles) wgs = n_tiles;
   if (wgs < 1) wgs = 1;
   long long blk = lfh::env_int("LINFUSION_BWD_ROWS_BLK", 1);
@@ -119,7 +118,7 @@ int launch_qs_rows(const BwdArgs& a, const float* stateS, float* partials, int* 
   const long long groups = (long long)a.B * gpb;
   const long long n_tiles = (a.N + kTile - 1) / kTile;
   const int resident = 160 * 1024 / lds > 0 ? 160 * 1024 / lds : 1;
-  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * kNumCU) / groups;
+  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * lfh::num_cu()) / groups;
   if (wgs > a.p->most) wgs = a.p->most;   // room for the partial states
   if (wgs > n_tiles) wgs = n_tiles;
   if (wgs < 1) wgs = 1;
@@ -144,7 +143,7 @@ int launch_q_rows(const BwdArgs& a, const float* stateS, lf::f32x2* scal) {
   const long long groups = (long long)a.B * gpb;
   const long long n_tiles = (a.N + kTile - 1) / kTile;
   const int resident = 160 * 1024 / lds > 0 ? 160 * 1024 / lds : 1;
-  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * kNumCU) / groups;
+  long long wgs = lfh::env_int("LINFUSION_BWD_ROWS_WGS", resident * lfh::num_cu()) / groups;
   if (wgs > n_tiles) wgs = n_tiles;
   if (wgs < 1) wgs = 1;
   long long blk = lfh::env_int("LINFUSION_BWD_ROWS_BLK", 1);
@@ -199,7 +198,7 @@ int launch_state_rows(const BwdArgs& a, float* partials, int* nparts) {
   const int gpb = a.H / W;
   const long long groups = (long long)a.B * gpb;
   const long long n_tiles = (a.N + kTile - 1) / kTile;
-  long long s = lfh::env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * kNumCU) / (W / kWavesPerWG) / groups;
+  long long s = lfh::env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * lfh::num_cu()) / (W / kWavesPerWG) / groups;
   if (s > a.p->most) s = a.p->most;   // room for the partial states
   if (s > n_tiles) s = n_tiles;
   if (s < 1) s = 1;

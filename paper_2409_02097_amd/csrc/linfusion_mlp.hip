@@ -12,7 +12,6 @@
 
 namespace {
 
-constexpr int kNumCU = 256;
 
 struct MlpPlan {
   int route;                      // 0: whole token rows in one workgroup; 1: per-head kernels + statistics pass;
@@ -74,11 +73,11 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     const int slot = (lf::kTile * d * 2 + 1023) / 1024 * 1024;
     const int lds_apply = 2 * 3 * slot * 4 + 3 * 1024;
     const int resident = 160 * 1024 / lds_apply > 0 ? 160 * 1024 / lds_apply : 1;
-    p->splits = per_group(lfh::env_int("LINFUSION_MLPG_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_MLPG_REDUCE_BLK", 2),
+    p->splits = per_group(lfh::env_int("LINFUSION_MLPG_REDUCE_WGS", 2 * lfh::num_cu()), lfh::env_int("LINFUSION_MLPG_REDUCE_BLK", 2),
                           &p->blk_reduce);
-    p->apply_wgs = per_group(lfh::env_int("LINFUSION_MLPG_APPLY_WGS", resident * kNumCU),
+    p->apply_wgs = per_group(lfh::env_int("LINFUSION_MLPG_APPLY_WGS", resident * lfh::num_cu()),
                              lfh::env_int("LINFUSION_MLPG_APPLY_BLK", 2), &p->blk_apply);
-    long long sw = (N + 15) / 16, cap = lfh::env_int("LINFUSION_MLPH_STATS_WGS", 8 * kNumCU) / (2 * B);
+    long long sw = (N + 15) / 16, cap = lfh::env_int("LINFUSION_MLPH_STATS_WGS", 8 * lfh::num_cu()) / (2 * B);
     if (cap < 1) cap = 1;
     p->stats_wgs = (int)(sw < cap ? sw : cap);
     p->ws_partials = up((size_t)B * H * p->splits * p->ne * sizeof(float));
@@ -111,11 +110,11 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
     const int slot = (lf::kTile * d * 2 + 1023) / 1024 * 1024;
     const int lds_apply = (2 * 3 * slot + 3 * 1024) * lf::kWavesPerWG;
     const int resident = (!wide && 160 * 1024 / lds_apply > 0) ? 160 * 1024 / lds_apply : 1;
-    p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 2 * kNumCU),
+    p->splits = per_head(lfh::env_int("LINFUSION_MLPH_REDUCE_WGS", 2 * lfh::num_cu()),
                          lfh::env_int("LINFUSION_MLPH_REDUCE_BLK", wide ? 4 : 8), &p->blk_reduce);
-    p->apply_wgs = per_head(lfh::env_int("LINFUSION_MLPH_APPLY_WGS", resident * kNumCU),
+    p->apply_wgs = per_head(lfh::env_int("LINFUSION_MLPH_APPLY_WGS", resident * lfh::num_cu()),
                             lfh::env_int("LINFUSION_MLPH_APPLY_BLK", wide ? 1 : 8), &p->blk_apply);
-    long long sw = (N + 15) / 16, cap = lfh::env_int("LINFUSION_MLPH_STATS_WGS", 8 * kNumCU) / (2 * B);
+    long long sw = (N + 15) / 16, cap = lfh::env_int("LINFUSION_MLPH_STATS_WGS", 8 * lfh::num_cu()) / (2 * B);
     if (cap < 1) cap = 1;
     p->stats_wgs = (int)(sw < cap ? sw : cap);
     p->ws_partials = up((size_t)units * p->splits * p->ne * sizeof(float));
@@ -142,9 +141,9 @@ int make_mlp_plan(int B, int H, long long N, int d, int dtype, MlpPlan* p) {
   // fp16 up to d = 40 (bf16 up to 32) on eight heads: the reduction fits two workgroups per CU
   // (ReduceMlpCfg::kWavesPerSimd)
   const int rounds = (H == 8 && (d <= 32 || (dtype == LINFUSION_DTYPE_F16 && d <= 40))) ? 2 : 1;
-  p->splits = per_batch(lfh::env_int("LINFUSION_MLP_REDUCE_WGS", 2 * kNumCU * rounds) / unit,
+  p->splits = per_batch(lfh::env_int("LINFUSION_MLP_REDUCE_WGS", 2 * lfh::num_cu() * rounds) / unit,
                         lfh::env_int("LINFUSION_MLP_REDUCE_BLK", 2), &p->blk_reduce);
-  p->apply_wgs = per_batch(lfh::env_int("LINFUSION_MLP_APPLY_WGS", 2 * kNumCU) / unit,
+  p->apply_wgs = per_batch(lfh::env_int("LINFUSION_MLP_APPLY_WGS", 2 * lfh::num_cu()) / unit,
                            lfh::env_int("LINFUSION_MLP_APPLY_BLK", H == 8 ? 1 : 2), &p->blk_apply);
   p->ws_partials = up((size_t)B * H * p->splits * p->ne * sizeof(float));
   p->ws_state = up((size_t)B * H * p->ne * sizeof(float));

@@ -10,7 +10,6 @@
 
 namespace {
 
-constexpr int kNumCU = 256;
 
 struct QvPlan {
   int splits, blk_reduce, apply_wgs, blk_apply;
@@ -45,9 +44,9 @@ int make_qv_plan(int B, int H, long long N, int dk, int dv, int dtype, QvPlan* p
   };
   const bool mid = (double)BH * (double)N * (2.0 * dk + 2.0 * dv) * 2.0 <
                    (double)lfh::env_int("LINFUSION_APPLY_ONE_ROUND_MB", 768) * 1048576.0;
-  p->splits = per_head(lfh::env_int("LINFUSION_REDUCE_WGS", 2 * kNumCU), lfh::env_int("LINFUSION_REDUCE_BLK", 16),
+  p->splits = per_head(lfh::env_int("LINFUSION_REDUCE_WGS", 2 * lfh::num_cu()), lfh::env_int("LINFUSION_REDUCE_BLK", 16),
                        &p->blk_reduce);
-  p->apply_wgs = per_head(lfh::env_int("LINFUSION_APPLY_WGS", (mid ? 2 : 8) * kNumCU),
+  p->apply_wgs = per_head(lfh::env_int("LINFUSION_APPLY_WGS", (mid ? 2 : 8) * lfh::num_cu()),
                           lfh::env_int("LINFUSION_APPLY_BLK", 8), &p->blk_apply);
   p->ne = (size_t)dk * dv + dk;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };

@@ -15,3 +15,13 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def repo_root():
     return ROOT
+
+
+@pytest.fixture
+def tuning():
+    """Switches on the library's development switch for the test, so that the LINFUSION_* environment
+    variables it sets (forced kernel routes, poll limit) are looked at; off again afterwards."""
+    import paper_2409_02097_amd as lf
+    lf.linfusion_set_tuning(True)
+    yield
+    lf.linfusion_set_tuning(False)

@@ -69,3 +69,40 @@ def check_all(out_t, q_t, k_t, v_t, dtype, feature_map=0, eps=1e-6, normalize=Tr
             r = check_slice(gpu[b, h], ref, dtype, f"{what} b={b} h={h}")
             worst = (max(worst[0], r[0]), max(worst[1], r[1]))
     return worst
+
+
+def gradient_term_scales(q, k, v, g, fm, eps, normalize):
+    """Largest magnitude, per gradient, of the sums of absolute terms that the gradient is made of:
+        dq: (|g / den| |S|^T + |e| |z|) phi'(q),  dk: (|v| |dS|^T + |dz|) phi'(k),  dv: |p| |dS|.
+    Gradients cancel (with one token dq is exactly zero: the output does not depend on q), so an error
+    bound has to be relative to what is summed, not to what is left; these are the classical |A| |B| bounds."""
+    r, p = orc.phi(q, fm), orc.phi(k, fm)
+    S, z = orc.state(k, v, fm)
+    if normalize:
+        den = r @ z + eps
+        gn = g / den[:, None]
+        e = -(g * ((r @ S) / den[:, None])).sum(axis=1) / den
+    else:
+        gn, e = g, np.zeros(q.shape[0])
+    dS, dz = r.T @ gn, r.T @ e
+    sq = (np.abs(gn) @ np.abs(S).T + np.abs(e)[:, None] * np.abs(z)[None, :]) * np.abs(orc.phi_prime(q, fm))
+    sk = (np.abs(v) @ np.abs(dS).T + np.abs(dz)[None, :]) * np.abs(orc.phi_prime(k, fm))
+    sv = np.abs(p) @ np.abs(dS)
+    return sq.max(), sk.max(), sv.max()
+
+
+def check_gradients(got, q, k, v, g, dtype, fm=0, eps=1e-6, normalize=True, what=""):
+    """got = (dq, dk, dv) of one (b, h) slice as fp64 arrays; q, k, v, g the slice's widened inputs.
+    |gpu - ref| <= tol * (largest sum of absolute terms in the slice) + half an ulp of the output type."""
+    tol = TOL[dtype]
+    ref = orc.attention_backward_linear(q, k, v, g, fm, eps, normalize)
+    scales = gradient_term_scales(q, k, v, g, fm, eps, normalize)
+    worst = 0.0
+    for gpu, want, scale, name in zip(got, ref, scales, ("dq", "dk", "dv")):
+        assert np.all(np.isfinite(gpu)), f"{what} {name}: non-finite values"
+        err = np.abs(gpu - want)
+        bound = tol * scale + orc.half_ulp(want, dtype)
+        assert (err - bound).max() <= 0, (f"{what} {name}: error {err.max():.3e} vs term scale "
+                                          f"{scale:.3e} (ratio {err.max() / scale:.3e}, tol {tol:g})")
+        worst = max(worst, float((err / scale).max()))
+    return worst

@@ -67,6 +67,34 @@ def test_workspace_bytes_is_a_pure_function_of_the_shape():
     assert lf.linfusion_attn_workspace_bytes(1, 8, 1024, 40, 7) == 0
 
 
+def test_environment_is_ignored_unless_tuning_is_switched_on(monkeypatch):
+    shape = (1, 8, 2097152, 40, lf.DTYPE_F16)
+    base_ws = lf.linfusion_attn_workspace_bytes(*shape)
+    base_plan = lf.linfusion_attn_plan(*shape)
+    monkeypatch.setenv("LINFUSION_REDUCE_WGS", "4096")
+    monkeypatch.setenv("LINFUSION_APPLY_WGS", "512")
+    assert lf.linfusion_attn_workspace_bytes(*shape) == base_ws         # no environment on the default path
+    assert lf.linfusion_attn_plan(*shape) == base_plan
+    lf.linfusion_set_tuning(True)
+    try:
+        tuned = lf.linfusion_attn_plan(*shape)
+        assert tuned["reduce_wgs_per_head"] == 512 and tuned["apply_wgs_per_head"] == 64
+        assert lf.linfusion_attn_workspace_bytes(*shape) > base_ws
+    finally:
+        lf.linfusion_set_tuning(False)
+    assert lf.linfusion_attn_plan(*shape) == base_plan
+
+
+def test_probe_entry_points_validate_on_the_host():
+    assert lf.library().linfusion_hbm_probe(0, 0, None, None, None, None, 1024, 64, None, None) == -1
+    assert lf.library().linfusion_hbm_probe(1, 0, None, None, None, None, 1024, 64, None, None) == -1   # no source
+    assert lf.library().linfusion_hbm_probe(4, 0, 4096, None, None, None, 1024, 64, 4096, None) == -1
+    assert lf.library().linfusion_hbm_probe(1, 1, 4096, None, None, 8192, 1000, 64, None, None) == -1    # not whole chunks
+    assert lf.library().linfusion_hbm_probe(1, 1, 4100, None, None, 8192, 1024, 64, None, None) == -3
+    assert lf.library().linfusion_launch_probe(0, 64, None, None) == -1
+    assert lf.library().linfusion_launch_probe(3, 0, None, None) == -1
+
+
 @pytest.mark.parametrize("B,H,N,d,dtype", [(1, 8, 1024, 40, 0), (2, 8, 4096, 40, 1), (2, 5, 9216, 64, 1),
                                           (2, 10, 16384, 64, 2), (2, 20, 4096, 64, 2), (1, 8, 2097152, 40, 1),
                                           (1, 1, 1, 8, 1), (1, 1, 31, 64, 0)])

@@ -22,45 +22,16 @@ def _run(q, k, v, g, fm=0, eps=1e-6, flags=0):
     return outs
 
 
-def _term_scales(q, k, v, g, fm, eps, normalize):
-    """Largest magnitude, per gradient, of the sums of absolute terms that the gradient is made of:
-        dq: (|g / den| |S|^T + |e| |z|) phi'(q),  dk: (|v| |dS|^T + |dz|) phi'(k),  dv: |p| |dS|.
-    Gradients cancel (with one token dq is exactly zero: the output does not depend on q), so an error
-    bound has to be relative to what is summed, not to what is left; these are the classical |A| |B| bounds."""
-    r, p = orc.phi(q, fm), orc.phi(k, fm)
-    S, z = orc.state(k, v, fm)
-    if normalize:
-        den = r @ z + eps
-        gn = g / den[:, None]
-        e = -(g * ((r @ S) / den[:, None])).sum(axis=1) / den
-    else:
-        gn, e = g, np.zeros(q.shape[0])
-    dS, dz = r.T @ gn, r.T @ e
-    sq = (np.abs(gn) @ np.abs(S).T + np.abs(e)[:, None] * np.abs(z)[None, :]) * np.abs(orc.phi_prime(q, fm))
-    sk = (np.abs(v) @ np.abs(dS).T + np.abs(dz)[None, :]) * np.abs(orc.phi_prime(k, fm))
-    sv = np.abs(p) @ np.abs(dS)
-    return sq.max(), sk.max(), sv.max()
-
-
 def _check(outs, q, k, v, g, dtype, fm, eps, normalize, what):
-    """|gpu - ref| <= tol * (largest sum of absolute terms in the slice) + half an ulp of the output type."""
+    """Every (batch, head) slice against the oracle's gradients, rule of tests/parity.py: check_gradients."""
     qs, ks, vs, gs = (wl.stored_numpy(t) for t in (q, k, v, g))
     B, H = qs.shape[:2]
-    tol = parity.TOL[dtype]
     worst = 0.0
     for b in range(B):
         for h in range(H):
             w = [orc.widen(x[b, h], dtype) for x in (qs, ks, vs, gs)]
-            ref = orc.attention_backward_linear(*w, fm, eps, normalize)
-            scales = _term_scales(*w, fm, eps, normalize)
-            for got, want, scale, name in zip(outs, ref, scales, ("dq", "dk", "dv")):
-                gpu = parity.to_f64(got[b, h])
-                assert np.all(np.isfinite(gpu)), f"{what} {name} b={b} h={h}: non-finite values"
-                err = np.abs(gpu - want)
-                bound = tol * scale + orc.half_ulp(want, dtype)
-                assert (err - bound).max() <= 0, (f"{what} {name} b={b} h={h}: error {err.max():.3e} vs term scale "
-                                                  f"{scale:.3e} (ratio {err.max() / scale:.3e}, tol {tol:g})")
-                worst = max(worst, float((err / scale).max()))
+            got = [parity.to_f64(t[b, h]) for t in outs]
+            worst = max(worst, parity.check_gradients(got, *w, dtype, fm, eps, normalize, f"{what} b={b} h={h}"))
     return worst
 
 
@@ -84,7 +55,7 @@ def test_backward_matches_oracle(B, H, N, d, dtype):
 
 
 @pytest.mark.parametrize("B,H,N,d", [(1, 2, 1000, 40), (2, 2, 333, 16), (1, 1, 4099, 48)])
-def test_backward_separate_kernels_for_fp16_small_widths(B, H, N, d, monkeypatch):
+def test_backward_separate_kernels_for_fp16_small_widths(B, H, N, d, monkeypatch, tuning):
     """fp16 with d <= 48 normally takes the merged dQ + state-gradient kernel; the separate kernels (what bf16
     and wider heads use) must give the same gradients to tolerance."""
     monkeypatch.setenv("LINFUSION_BWD_MERGED", "2")
@@ -169,7 +140,7 @@ def test_backward_argument_checks():
                                             (1, 12, 130, 56, "bf16"), (1, 8, 1, 40, "f16"), (2, 8, 33, 80, "bf16"),
                                             (1, 8, 300, 8, "f16"), (1, 4, 700, 16, "bf16"), (1, 8, 515, 48, "f16"),
                                             (1, 8, 96, 32, "bf16")])
-def test_backward_on_token_major_views(B, H, N, d, dtype, monkeypatch):
+def test_backward_on_token_major_views(B, H, N, d, dtype, monkeypatch, tuning):
     """All seven tensors in the UNet's [B, N, H*d] layout, handed over as strided [B, H, N, d] views: the oracle's
     gradients, and what the contiguous entry point gives on the same values.  The row-piece gradient kernels, which
     the library picks from a few tens of MB up, are switched on for every size here."""

@@ -247,7 +247,7 @@ def test_per_head_route_matches_oracle(B, H, N, d, dtype):
 
 @pytest.mark.parametrize("B,H,N,d,dtype", [(2, 8, 1000, 40, "f16"), (1, 8, 4099, 40, "bf16"), (1, 4, 333, 80, "f16"),
                                            (2, 4, 77, 64, "bf16"), (1, 8, 33, 8, "f16")])
-def test_per_head_route_on_whole_row_shapes(B, H, N, d, dtype, monkeypatch):
+def test_per_head_route_on_whole_row_shapes(B, H, N, d, dtype, monkeypatch, tuning):
     """Both routes on one shape: each within tolerance of the oracle (their bits may differ: the statistics are
     summed in another order)."""
     print(f"mlp heads forced B={B} H={H} N={N} d={d} {dtype}", flush=True)
@@ -266,7 +266,7 @@ def test_per_head_route_on_whole_row_shapes(B, H, N, d, dtype, monkeypatch):
 
 @pytest.mark.parametrize("B,H,N,d,dtype", [(1, 8, 777, 80, "f16"), (2, 8, 2051, 80, "bf16"), (1, 16, 257, 48, "f16"),
                                            (1, 12, 130, 32, "bf16"), (1, 8, 1000, 56, "f16")])
-def test_group_shapes_on_the_per_head_kernels(B, H, N, d, dtype, monkeypatch):
+def test_group_shapes_on_the_per_head_kernels(B, H, N, d, dtype, monkeypatch, tuning):
     """Rows of whole groups of four heads whose head rows are no whole cache lines go through the group kernels by
     default (covered by the per-head shape list above); the per-head kernels must serve them too."""
     print(f"mlp group shape forced per head B={B} H={H} N={N} d={d} {dtype}", flush=True)

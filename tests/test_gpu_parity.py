@@ -157,7 +157,7 @@ def test_owned_workspace_entry_points():
     lf.linfusion_release()
 
 
-def test_single_launch_timeout_is_reported_and_harmless(monkeypatch):
+def test_single_launch_timeout_is_reported_and_harmless(monkeypatch, tuning):
     # a spin limit of zero makes every workgroup that does not see all arrivals at its first poll give
     # up: the kernel must still end (no hang), the error must be reported, and the next call must work
     B, H, N, d = 2, 4, 20000, 40
@@ -171,12 +171,49 @@ def test_single_launch_timeout_is_reported_and_harmless(monkeypatch):
     assert rc in (0, -8)          # -8 unless every workgroup happened to arrive before the first poll
     print("forced give-up ->", rc, flush=True)
     monkeypatch.delenv("LINFUSION_FUSED_SPIN_LIMIT")
+    # the report belongs to the workspace: single-launch calls on another workspace (and another shape) in
+    # between do not hide it
+    ws2 = torch.empty_like(ws)
+    out2 = torch.empty_like(q)
+    lf.linfusion_attn_fwd_ex(q, k, v, out2, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws2)
+    assert lf.linfusion_attn_last_error(ws2, B, H, N, d, 1) == 0
+    assert lf.linfusion_attn_last_error(ws, B, H, N, d, 1) == rc
     lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws)
     assert lf.linfusion_attn_last_error(ws, B, H, N, d, 1) == 0
     parity.check_all(out, q.cpu(), k.cpu(), v.cpu(), "f16", 0, 1e-6, True, "after a forced give-up")
+    assert torch.equal(out.view(torch.uint8), out2.view(torch.uint8))
     # the split path never reports a timeout
     lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, lf.FLAG_FORCE_SPLIT, ws)
     assert lf.linfusion_attn_last_error(ws, B, H, N, d, 1) == 0
+
+
+@pytest.mark.parametrize("dtype,d", [("f16", 40), ("bf16", 64), ("f32", 40)])
+def test_single_launch_on_a_workspace_with_arbitrary_content(dtype, d):
+    # The workspace's content is undefined: whatever it holds (zeros, ones, small integers, bytes an earlier
+    # tensor left behind), the barrier flags must read as "not arrived" and no timeout may be reported.
+    B, H, N = 2, 4, 6000
+    code = wl.DTYPE_CODE[dtype]
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=69, device="cuda")
+    nbytes = lf.linfusion_attn_workspace_bytes(B, H, N, d, code)
+    assert lf.linfusion_attn_plan(B, H, N, d, code, lf.FLAG_FORCE_FUSED)["path"] == 1
+    ref = None
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    fills = [lambda w: w.zero_(), lambda w: w.fill_(1), lambda w: w.fill_(255),
+             lambda w: w.view(torch.int32).copy_(torch.arange(w.numel() // 4, device="cuda", dtype=torch.int32) % 7),
+             lambda w: w.view(torch.int32).fill_(1),
+             lambda w: w.copy_(torch.randint(0, 256, (w.numel(),), device="cuda", dtype=torch.uint8, generator=gen))]
+    for i, fill in enumerate(fills):
+        ws = torch.empty((nbytes + 3) // 4 * 4, dtype=torch.uint8, device="cuda")
+        fill(ws)
+        assert lf.linfusion_attn_last_error(ws, B, H, N, d, code) == 0, f"fill {i}: a report before any call"
+        out = torch.full_like(q, float("nan"))
+        lf.linfusion_attn_fwd_ex(q, k, v, out, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws)
+        assert lf.linfusion_attn_last_error(ws, B, H, N, d, code) == 0, f"fill {i}"
+        if ref is None:
+            ref = out
+            parity.check_all(out, q.cpu(), k.cpu(), v.cpu(), dtype, 0, 1e-6, True, "single launch, zeroed workspace")
+        else:
+            assert torch.equal(out.view(torch.uint8), ref.view(torch.uint8)), f"fill {i}"
 
 
 def test_single_launch_falls_back_when_heads_exceed_residency():

@@ -30,7 +30,7 @@ def _case(seed):
 
 
 @pytest.mark.parametrize("seed", range(48))
-def test_random_case_matches_oracle(seed, monkeypatch):
+def test_random_case_matches_oracle(seed, monkeypatch, tuning):
     dtype, d, B, H, N, layout, path, groups, fm = _case(seed)
     print(f"seed {seed}: {dtype} d={d} B={B} H={H} N={N} {layout} flags={path} groups={groups} fm={fm}", flush=True)
     if groups:

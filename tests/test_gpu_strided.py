@@ -15,7 +15,7 @@ SENTINEL = 12345.0
 
 
 @pytest.fixture(autouse=True)
-def _row_piece_kernels_at_every_size(monkeypatch):
+def _row_piece_kernels_at_every_size(monkeypatch, tuning):
     """By default the library keeps the per-head kernels below ~24 MB of tensor traffic; these tests want the
     row-piece kernels wherever the layout allows them (the library reads the variable at every call)."""
     monkeypatch.setenv("LINFUSION_HEAD_GROUPS", "3")
@@ -140,7 +140,7 @@ def test_in_place_on_a_token_major_q():
 
 
 @pytest.mark.parametrize("name", ["sd15_512_f16", "B=2,H=8,N=16384,d=40,dtype=f16"])
-def test_sd_sized_token_major_layer(name, monkeypatch):
+def test_sd_sized_token_major_layer(name, monkeypatch, tuning):
     """SD-v1.5 layers at 512 px and 1024 px in the UNet's own [B, N, H*d] layout, default choice of kernels
     (per-head below the size threshold, row-piece above)."""
     monkeypatch.delenv("LINFUSION_HEAD_GROUPS")
