@@ -178,7 +178,20 @@ def test_recorded_into_a_graph_replays_correctly(B, H, N, d, dtype):
         eager = torch.empty_like(out)
         lf.linfusion_attn_fwd_mlp(*dev[:5], eager, *dev[5:], H, 0, 1e-6, LN_EPS, SLOPE, 0, _ws(B, H, N, d, dtype))
         torch.cuda.synchronize()
-        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep}"
+        if not torch.equal(out.view(torch.int16), eager.view(torch.int16)):
+            # say what differs before failing: which rows, whether the eager call repeats itself, whether the replay does
+            ne = (out.view(torch.int16) != eager.view(torch.int16)).nonzero()
+            rows = sorted(set((ne[:, 0] * N + ne[:, 1]).tolist()))
+            eager2 = torch.empty_like(out)
+            lf.linfusion_attn_fwd_mlp(*dev[:5], eager2, *dev[5:], H, 0, 1e-6, LN_EPS, SLOPE, 0, _ws(B, H, N, d, dtype))
+            first = out.clone()
+            graph.replay()
+            torch.cuda.synchronize()
+            raise AssertionError(
+                f"replay {rep}: {ne.shape[0]} elements in {len(rows)} rows differ from the eager call (rows {rows[:8]} .. "
+                f"{rows[-3:]}); eager repeats itself: {torch.equal(eager.view(torch.int16), eager2.view(torch.int16))}; "
+                f"replay repeats itself: {torch.equal(first.view(torch.int16), out.view(torch.int16))}; "
+                f"second replay equals eager: {torch.equal(out.view(torch.int16), eager.view(torch.int16))}")
 
 
 @pytest.mark.parametrize("B,H,N,d,dtype", [(2, 8, 1000, 40, "f16"), (1, 8, 4099, 40, "bf16"), (2, 4, 333, 80, "f16"),
