@@ -351,6 +351,34 @@ int linfusion_attn_fwd_f32(const void* q, const void* k, const void* v, void* ou
                            int B, int H, long long N, int d, int feature_map, float eps, void* stream);
 
 /*
+ * linfusion_attn_fwd_ex for callers that cannot allocate and have no workspace to hand over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch the kernels need (the
+ * partial states of the split-N reduction, the combined states, the apply operands of the row-piece kernels)
+ * lives in a fixed array inside the library's device image, linfusion_attn_static_scratch_bytes() = 16 MiB per
+ * device, held until the process ends.  The call allocates nothing, frees nothing and synchronises nothing.
+ *
+ *   q, k, v, out, B, H, N, d, dtype, feature_map, eps, stream: as linfusion_attn_fwd_ex (contiguous [B, H, N, d]).
+ *   flags        LINFUSION_FLAG_NONE or LINFUSION_FLAG_UNNORMALIZED; the three-kernel path always runs
+ *                (LINFUSION_FLAG_FORCE_FUSED -> LINFUSION_ERR_INVALID), so results equal those of
+ *                linfusion_attn_fwd_ex with LINFUSION_FLAG_FORCE_SPLIT bit for bit.
+ * Shapes whose three-kernel scratch exceeds the array are rejected with LINFUSION_ERR_WORKSPACE before anything
+ * is enqueued (the need is that of the three-kernel path alone, well below linfusion_attn_workspace_bytes, which
+ * also covers the single launch).  On a whole MI355X: widths up to 64 fit for B*H up to a few hundred, d = 80
+ * for B*H up to about 64; the wide widths (96, 128, 160) exceed it for all but tiny shapes -- for those use
+ * linfusion_attn_fwd_ex.  Every call on a device uses that device's one array: calls on one device
+ * must be ordered on one stream (or otherwise not overlap in time); overlapping calls race on the scratch.
+ * Nothing in the array has to start at zero -- every word a kernel reads was written earlier in the same call
+ * -- so contents left by an earlier call, of whatever shape, are harmless.
+ * linfusion_init (optional) resolves the array's device address for the current device ahead of time, so that
+ * the first linfusion_attn_fwd_static call does not; it allocates nothing either.
+ */
+int linfusion_attn_fwd_static(const void* q, const void* k, const void* v, void* out,
+                              int B, int H, long long N, int d,
+                              int dtype, int feature_map, float eps, unsigned flags, void* stream);
+size_t linfusion_attn_static_scratch_bytes(void);
+int linfusion_init(void);
+
+/*
  * State-only entry point (the reduction half of Prop. 2; also what an N-sharded deployment
  * exchanges between devices, Sec. 3.3 "constant communication cost"): writes, per (b, h),
  * the fp32 state S as [d][d] row-major (row = feature index of phi(K), column = value

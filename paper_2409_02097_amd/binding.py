@@ -90,6 +90,12 @@ def library() -> ctypes.CDLL:
     lib.linfusion_status_string.restype = ctypes.c_char_p
     lib.linfusion_version.argtypes = []
     lib.linfusion_version.restype = i32
+    lib.linfusion_attn_fwd_static.argtypes = [vp, vp, vp, vp, i32, i32, i64, i32, i32, i32, f32, u32, vp]
+    lib.linfusion_attn_fwd_static.restype = i32
+    lib.linfusion_attn_static_scratch_bytes.argtypes = []
+    lib.linfusion_attn_static_scratch_bytes.restype = sz
+    lib.linfusion_init.argtypes = []
+    lib.linfusion_init.restype = i32
     lib.linfusion_hbm_probe.argtypes = [i32, i32, vp, vp, vp, vp, sz, i32, vp, vp]
     lib.linfusion_hbm_probe.restype = i32
     lib.linfusion_launch_probe.argtypes = [i32, i32, vp, vp]
@@ -322,6 +328,28 @@ def linfusion_attn_fwd_ex(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps
                                          _stream_ptr(stream))
     if check and rc != 0:
         raise LinFusionError(rc, "linfusion_attn_fwd_ex")
+    return rc
+
+
+def linfusion_attn_fwd_static(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6,
+                              flags: int = FLAG_NONE, stream=None, check: bool = True) -> int:
+    """out <- mixer(q, k, v) with the library's fixed scratch array: no workspace argument, no allocation."""
+    B, H, N, d = _check_layout(q, k, v, out)
+    rc = library().linfusion_attn_fwd_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d,
+                                             _dtype_code(q), feature_map, eps, flags, _stream_ptr(stream))
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_attn_fwd_static")
+    return rc
+
+
+def linfusion_attn_static_scratch_bytes() -> int:
+    return int(library().linfusion_attn_static_scratch_bytes())
+
+
+def linfusion_init(check: bool = True) -> int:
+    rc = library().linfusion_init()
+    if check and rc != 0:
+        raise LinFusionError(rc, "linfusion_init")
     return rc
 
 

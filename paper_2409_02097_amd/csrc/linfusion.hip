@@ -127,7 +127,9 @@ int apply_wgs_per_cu(int d, int dtype) {
   return fused_wgs_per_cu(d, dtype);
 }
 
-int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan* p) {
+// `compact`: size the scratch for the three-kernel path alone (no room for the single launch's partials and
+// flags, which take most of the general workspace) -- the plan of the entry point with the fixed scratch array.
+int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan* p, bool compact = false) {
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
   if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;   // grid.y limit
   if (flags & ~(LINFUSION_FLAG_UNNORMALIZED | LINFUSION_FLAG_FORCE_SPLIT | LINFUSION_FLAG_FORCE_FUSED))
@@ -194,7 +196,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   // fused single launch: every workgroup must be resident at once
   const long long cap = (long long)fused_wgs_per_cu(d, dtype) * num_cu();
   p->fsplits = 0;
-  if (BH <= cap) {
+  if (BH <= cap && !compact) {
     p->fsplits = per_head((int)(cap / BH * BH), &share);
     if ((long long)p->fsplits * BH > cap) p->fsplits = 0;
     p->fblk_reduce = block_tiles(share, "LINFUSION_REDUCE_BLK", 16);
@@ -202,7 +204,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   }
   // row-piece kernels: a workgroup covers a whole group of four heads, every wave walks all of its tiles
   p->gwaves = (H % 8 == 0 && d <= 64 && env_int("LINFUSION_GROUP_WAVES", 8) == 8) ? 8 : 4;   // d = 80: registers
-  p->groups = B * (H / p->gwaves);
+  p->groups = compact ? 0 : B * (H / p->gwaves);   // (compact: contiguous tensors only, whose heads are never neighbours)
   if (p->groups > 0) {
     auto per_group = [&](int want_total, long long* sh) {
       long long s = want_total / p->groups;
@@ -561,9 +563,9 @@ int dispatch(int d, int dtype, const Args& a) {
 }
 
 int validate_common(const void* k, const void* v, int B, int H, long long N, int d, int dtype, int feature_map,
-                    unsigned flags, Plan* p) {
+                    unsigned flags, Plan* p, bool compact = false) {
   if (!k || !v) return LINFUSION_ERR_INVALID;
-  int rc = make_plan(B, H, N, d, dtype, flags, p);
+  int rc = make_plan(B, H, N, d, dtype, flags, p, compact);
   if (rc != LINFUSION_OK) return rc;
   if (feature_map < 0 || feature_map > 2) return LINFUSION_ERR_UNSUPPORTED;
   if (((uintptr_t)k | (uintptr_t)v) & 15) return LINFUSION_ERR_MISALIGNED;
@@ -638,11 +640,11 @@ lf::Layout device_layout(const Strides& s, int H, size_t esz) {
 int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d, int dtype,
              int feature_map, float eps, unsigned flags, void* workspace, size_t workspace_bytes, void* stream,
              hipEvent_t* ev, const long long* sq = nullptr, const long long* skv = nullptr,
-             const long long* so = nullptr) {
+             const long long* so = nullptr, bool compact = false) {
   if (!q || !out) return LINFUSION_ERR_INVALID;
   if (!(eps >= 0.0f) || std::isinf(eps)) return LINFUSION_ERR_INVALID;
   Plan p;
-  int rc = validate_common(k, v, B, H, N, d, dtype, feature_map, flags, &p);
+  int rc = validate_common(k, v, B, H, N, d, dtype, feature_map, flags, &p, compact);
   if (rc != LINFUSION_OK) return rc;
   if (((uintptr_t)q | (uintptr_t)out) & 15) return LINFUSION_ERR_MISALIGNED;
   const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
@@ -700,6 +702,29 @@ int fwd_owned(const void* q, const void* k, const void* v, void* out, int B, int
   if (rc != LINFUSION_OK) return rc;
   // the three-kernel path, which cannot time out: the caller of these entry points has no workspace to ask about
   return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, LINFUSION_FLAG_FORCE_SPLIT, ws, need, stream, nullptr);
+}
+
+// ---- scratch that no call has to allocate ------------------------------------------------------------
+// One fixed array per device, part of the library's device image (each GPU the library runs on holds its
+// own copy at its own address until the process ends).  In host code the array's name is only a stand-in
+// for the symbol, not a device address: the address is asked once per device with hipGetSymbolAddress and
+// only that pointer is ever handed to kernels.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices];
+
+// device address of `scratch` on the current device (asked on first use, with that device current)
+int static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return LINFUSION_ERR_DEVICE; }
+  std::lock_guard<std::mutex> lk(g_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return LINFUSION_ERR_HIP; }
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return LINFUSION_OK;
 }
 
 }  // namespace
@@ -815,6 +840,34 @@ int linfusion_attn_fwd_bf16(const void* q, const void* k, const void* v, void* o
 int linfusion_attn_fwd_f32(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d,
                            int feature_map, float eps, void* stream) {
   return fwd_owned(q, k, v, out, B, H, N, d, LINFUSION_DTYPE_F32, feature_map, eps, stream);
+}
+
+size_t linfusion_attn_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int linfusion_init(void) {
+  int rc = check_device();
+  if (rc != LINFUSION_OK) return rc;
+  void* p = nullptr;
+  return static_scratch(&p);
+}
+
+int linfusion_attn_fwd_static(const void* q, const void* k, const void* v, void* out, int B, int H, long long N, int d,
+                              int dtype, int feature_map, float eps, unsigned flags, void* stream) {
+  // the three-kernel path only: its scratch needs no initial content, and nothing in it can time out
+  if (flags & LINFUSION_FLAG_FORCE_FUSED) return LINFUSION_ERR_INVALID;
+  const unsigned f = flags | LINFUSION_FLAG_FORCE_SPLIT;
+  Plan p;
+  int rc = make_plan(B, H, N, d, dtype, f, &p, true);
+  if (rc != LINFUSION_OK)   // let the general entry point name the error in its own order of checks
+    return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, f, nullptr, 0, stream, nullptr);
+  if (p.ws_total > kStaticScratchBytes) return LINFUSION_ERR_WORKSPACE;
+  rc = check_device();
+  if (rc != LINFUSION_OK) return rc;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != LINFUSION_OK) return rc;
+  return fwd_impl(q, k, v, out, B, H, N, d, dtype, feature_map, eps, f, ws, kStaticScratchBytes, stream, nullptr,
+                  nullptr, nullptr, nullptr, true);
 }
 
 void linfusion_release(void) {
