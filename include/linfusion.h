@@ -435,6 +435,13 @@ void linfusion_set_tuning(int on);
  */
 int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned flags, int plan[4]);
 
+/*
+ * Name of the kernel that will run the apply step for this shape on contiguous tensors ("apply16_dma",
+ * "apply16_packed", "apply32", "apply16_wide", or "fused16" / "fused32" when the single launch is chosen);
+ * an empty string for rejected arguments.  Static storage.  For benchmarks and profile summaries.
+ */
+const char* linfusion_attn_apply_kernel(int B, int H, long long N, int d, int dtype, unsigned flags);
+
 #ifdef __cplusplus
 }
 #endif

@@ -102,6 +102,8 @@ def library() -> ctypes.CDLL:
     lib.linfusion_launch_probe.restype = i32
     lib.linfusion_set_tuning.argtypes = [i32]
     lib.linfusion_set_tuning.restype = None
+    lib.linfusion_attn_apply_kernel.argtypes = [i32, i32, i64, i32, i32, u32]
+    lib.linfusion_attn_apply_kernel.restype = ctypes.c_char_p
     lib.linfusion_attn_plan.argtypes = [i32, i32, i64, i32, i32, u32, ctypes.POINTER(ctypes.c_int * 4)]
     lib.linfusion_attn_plan.restype = i32
     _lib = lib
@@ -306,6 +308,10 @@ def linfusion_attn_last_error(workspace, B: int, H: int, N: int, d: int, dtype: 
     """Synchronises the stream; 0, or LINFUSION_ERR_TIMEOUT (-8) if the last single-launch call gave up."""
     return int(library().linfusion_attn_last_error(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                                    B, H, N, d, dtype, _stream_ptr(stream)))
+
+
+def linfusion_attn_apply_kernel(B: int, H: int, N: int, d: int, dtype: int, flags: int = 0) -> str:
+    return library().linfusion_attn_apply_kernel(B, H, N, d, dtype, flags).decode()
 
 
 def linfusion_attn_plan(B: int, H: int, N: int, d: int, dtype: int, flags: int = 0):

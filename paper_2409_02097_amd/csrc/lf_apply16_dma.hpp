@@ -111,13 +111,16 @@ template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :
 // W of the row's heads): the row statistics were computed by an earlier kernel, {rstd, -mean rstd} per token; a
 // tile's 32 pairs travel with its copies as one more deposit (256 bytes used) into a third ring (row-piece mode:
 // every wave brings the same pairs to the same place, one deposit per slot).
-template <typename T, int D, int FM, bool NORM, int ROWS_W = 0, bool MLP = false, int DV = D, bool PRE = false>
+// WPW: waves per workgroup in per-head mode (each wave streams on its own, so any count works; 4 where the
+// workgroup stages the fp32 state together, fewer for the short-lived workgroups of apply16_packed).
+template <typename T, int D, int FM, bool NORM, int ROWS_W = 0, bool MLP = false, int DV = D, bool PRE = false,
+          int WPW = kWavesPerWG>
 struct ApplyDma {
   static constexpr bool ROWS = ROWS_W > 0;
   static_assert(!MLP || ROWS || PRE, "the two-branch input needs whole token rows in one workgroup, or their statistics");
   static_assert(!PRE || (MLP && DV == D), "precomputed row statistics serve the two-branch kernels");
   static_assert(DV == D || !ROWS, "unequal query and value widths run on the per-head kernel only");
-  static constexpr int W = ROWS ? ROWS_W : kWavesPerWG;   // waves per workgroup
+  static constexpr int W = ROWS ? ROWS_W : WPW;   // waves per workgroup
   static constexpr int NT = 64 * W;
   using Sh = Shape16<D>;
   using Cfg = ApplyDmaCfg<D, DV>;
@@ -167,7 +170,7 @@ struct ApplyDma {
                   int nwg, unsigned char* smem_)
       : Qh(Qh_), Oh(Oh_), N(N_), smem(smem_), rs_q(rs_q_), rs_o(rs_o_),
         lane(threadIdx.x & 63), wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
-        it(wg, nwg, ROWS ? 0 : wave, tiles_per_block, (N_ + kTile - 1) / kTile, ROWS ? 1 : kWavesPerWG),
+        it(wg, nwg, ROWS ? 0 : wave, tiles_per_block, (N_ + kTile - 1) / kTile, ROWS ? 1 : WPW),
         ahead(it) {
     tok = lane & 31;
     kg = lane >> 5;
@@ -662,6 +665,23 @@ apply16_dma(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layou
                               gridDim.x, smem);
   ap.prefetch();
   ap.run(state + bh * (D * D + D), eps);
+}
+
+// apply16_dma with the head's operands prepared by pack_state16: a workgroup's start-up is a few coalesced
+// loads instead of staging and packing the fp32 state, so a launch can use many short-lived workgroups
+// (each a few tiles), which the hardware deals out in order: the chip then reads and writes one narrow
+// moving window of memory, which the write stream in particular rewards.
+template <typename T, int D, int FM, bool NORM, int WPW>
+__global__ void __launch_bounds__(64 * WPW)
+apply16_packed(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, HeadSubset hs,
+               const unsigned char* __restrict__ packed, float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const long long bh = hs.bh(blockIdx.y, lq.H);
+  ApplyDma<T, D, FM, NORM, 0, false, D, false, WPW> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N,
+                                                       tiles_per_block, blockIdx.x, gridDim.x, smem);
+  ap.prefetch();
+  ap.load_packed(packed + bh * Pack16<T, D>::kHeadBytes, eps);
+  ap.stream();
 }
 
 // Apply on groups of W (4 or 8) neighbouring heads (see ROWS_W above).  grid = (wgs, B * groups_per_batch),

@@ -81,6 +81,8 @@ struct Plan {
   // row-piece kernels (heads adjacent in memory): whole groups of gwaves (8 if H % 8 == 0, else 4)
   // heads, one wave per head; workgroups per group
   int gwaves, groups, gsplits, gblk_reduce, gapply_wgs, gblk_apply;
+  int apply_waves;      // waves per workgroup of the packed per-head apply (1, 2 or 4)
+  bool apply_packed;    // per-head apply from operands prepared by pack_state16 (many short-lived workgroups)
   long long n_tiles;
   size_t state_floats;  // d*d + d: one partial, and one head's state
   size_t ws_partials, ws_state, ws_sync, ws_pack, ws_total;   // ws_pack: operand-ready state (row-piece apply)
@@ -158,6 +160,8 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     p->gwaves = lf::kWavesPerWG;
     p->groups = p->gsplits = p->gapply_wgs = 0;
     p->gblk_reduce = p->gblk_apply = 1;
+    p->apply_packed = false;
+    p->apply_waves = lf::kWavesPerWG;
     p->path = 0;
     if (flags & LINFUSION_FLAG_FORCE_FUSED) return LINFUSION_ERR_UNSUPPORTED;
     p->state_floats = (size_t)d * d + d;
@@ -191,8 +195,31 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
   const bool one_round = bytes < (double)env_int("LINFUSION_APPLY_ONE_ROUND_MB", 768) * 1048576.0;
   const int apply_dflt = (one_round ? apply_wgs_per_cu(d, dtype) : 8) * num_cu();
-  p->apply_wgs = per_head(env_int("LINFUSION_APPLY_WGS", apply_dflt), &share);
-  p->blk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", 8);
+  // Large 16-bit problems: the head's operands are packed once (pack_state16) and apply runs as many short-lived
+  // workgroups of about 16 tiles each, dealt out by the hardware in order, so that the chip reads and writes one
+  // narrow moving window (measured on the 2 M-token workload: 443 us against 488 us for 2048 long-lived
+  // workgroups that each stage and pack the fp32 state themselves).
+  const int packed_mode = env_int("LINFUSION_APPLY_PACKED", 1);   // 1 = by size, 2 = never, 3 = always
+  p->apply_packed = dtype != LINFUSION_DTYPE_F32 && (packed_mode == 3 || (packed_mode == 1 && !one_round));
+  p->apply_waves = lf::kWavesPerWG;
+  int apply_want = apply_dflt, blk_dflt = 8;
+  if (p->apply_packed) {
+    const int w = env_int("LINFUSION_APPLY_WAVES", lf::kWavesPerWG);
+    p->apply_waves = (w == 1 || w == 2) ? w : lf::kWavesPerWG;
+    const long long by_tiles = BH * p->n_tiles / (4 * p->apply_waves);   // four tiles per wave
+    if (!one_round && by_tiles > apply_want) apply_want = by_tiles > (1 << 24) ? (1 << 24) : (int)by_tiles;
+    blk_dflt = p->apply_waves;                                           // one tile per wave and round
+  }
+  {
+    // every wave gets at least one tile
+    const long long max_a = (p->n_tiles + p->apply_waves - 1) / p->apply_waves;
+    long long s = env_int("LINFUSION_APPLY_WGS", apply_want) / BH;
+    if (s > max_a) s = max_a;
+    if (s < 1) s = 1;
+    share = (p->n_tiles + s - 1) / s;
+    p->apply_wgs = (int)((p->n_tiles + share - 1) / share);
+  }
+  p->blk_apply = block_tiles(share, "LINFUSION_APPLY_BLK", blk_dflt, p->apply_waves);
   // fused single launch: every workgroup must be resident at once
   const long long cap = (long long)fused_wgs_per_cu(d, dtype) * num_cu();
   p->fsplits = 0;
@@ -245,7 +272,7 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   // single launch: one 64-bit flag per workgroup and barrier, then two 64-bit records {last call, failed call}
   p->ws_sync = up((size_t)BH * 2 * (p->fsplits > 0 ? p->fsplits : 1) * sizeof(unsigned long long) + 16);
   p->ws_pack = 0;
-  if (dtype != LINFUSION_DTYPE_F32 && p->groups > 0) {
+  if (dtype != LINFUSION_DTYPE_F32 && (p->groups > 0 || p->apply_packed)) {
     const size_t ns = dtype == LINFUSION_DTYPE_BF16 ? 2 : 1;
     const size_t frags = ns * (size_t)((d / 2 + 2 + 15) / 16) * (size_t)((d / 8 + 1) / 2);   // Pack16<T, D>::kFrags
     p->ws_pack = up((size_t)BH * (256 + frags * 1024));
@@ -423,7 +450,7 @@ int run16(const Args& a) {
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
   combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)a.BH), dim3(kCombineThreads), 0, st>>>(
       partials, a.group_reduce ? p.gsplits : p.splits, NE, state);
-  if (a.ev && !(a.out && a.group_apply)) (void)hipEventRecord(a.ev[2], st);
+  if (a.ev && !(a.out && (a.group_apply || p.apply_packed))) (void)hipEventRecord(a.ev[2], st);
   if (a.out) {
     const size_t lds2 = apply16_dma_lds_bytes<T, D>();
     if (a.group_apply) {
@@ -458,6 +485,26 @@ int run16(const Args& a) {
         LF_SWITCH_FM_NORM(LF_APPLY)
 #undef LF_APPLY
       }
+    } else if (p.apply_packed) {
+      const dim3 g2(p.apply_wgs, (unsigned)a.BH);
+      unsigned char* packed = a.ws + p.ws_partials + p.ws_state + p.ws_sync;
+      if (!allow_lds(pack_state16<T, D, true>, (int)lds2) || !allow_lds(pack_state16<T, D, false>, (int)lds2))
+        return LINFUSION_ERR_HIP;
+      if (a.unnorm) pack_state16<T, D, false><<<dim3((unsigned)a.BH), blk, lds2, st>>>(state, packed);
+      else pack_state16<T, D, true><<<dim3((unsigned)a.BH), blk, lds2, st>>>(state, packed);
+      if (a.ev) (void)hipEventRecord(a.ev[2], st);   // the operand packing counts with the combine
+#define LF_APPLY_W(FM, NORM, WW)                                                                          \
+  {                                                                                                       \
+    constexpr size_t lds3 = (size_t)ApplyDmaCfg<D>::kRing * ApplyDmaCfg<D>::kSlotBytes * WW;              \
+    if (!allow_lds(apply16_packed<T, D, FM, NORM, WW>, (int)lds3)) return LINFUSION_ERR_HIP;             \
+    apply16_packed<T, D, FM, NORM, WW><<<g2, dim3(64 * WW), lds3, st>>>(Q, a.lq, O, a.lo, all, packed, a.eps, a.N, \
+                                                                        p.blk_apply);                    \
+  }
+#define LF_APPLY(FM, NORM)                                                        \
+  if (p.apply_waves == 1) LF_APPLY_W(FM, NORM, 1) else if (p.apply_waves == 2) LF_APPLY_W(FM, NORM, 2) else LF_APPLY_W(FM, NORM, 4)
+      LF_SWITCH_FM_NORM(LF_APPLY)
+#undef LF_APPLY
+#undef LF_APPLY_W
     } else {
       const dim3 g2(p.apply_wgs, (unsigned)a.BH);
 #define LF_APPLY(FM, NORM)                                                               \
@@ -905,6 +952,15 @@ const char* linfusion_status_string(int status) {
 int linfusion_version(void) { return kVersion; }
 
 void linfusion_set_tuning(int on) { g_tuning.store(on ? 1 : 0, std::memory_order_relaxed); }
+
+const char* linfusion_attn_apply_kernel(int B, int H, long long N, int d, int dtype, unsigned flags) {
+  Plan p;
+  if (make_plan(B, H, N, d, dtype, flags, &p) != LINFUSION_OK) return "";
+  if (is_wide(d)) return "apply16_wide";
+  if (p.path == 1) return dtype == LINFUSION_DTYPE_F32 ? "fused32" : "fused16";
+  if (dtype == LINFUSION_DTYPE_F32) return "apply32";
+  return p.apply_packed ? "apply16_packed" : "apply16_dma";
+}
 
 int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned flags, int plan[4]) {
   if (!plan) return LINFUSION_ERR_INVALID;

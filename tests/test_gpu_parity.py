@@ -50,6 +50,29 @@ def test_small_shapes_match_oracle(B, H, N, d, dtype, path):
     print(f"  worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("waves", [4, 2, 1])
+@pytest.mark.parametrize("B,H,N,d,dtype", [c for c in SMALL if c[4] != "f32"])
+def test_packed_operand_apply_on_small_shapes(B, H, N, d, dtype, waves, monkeypatch, tuning):
+    """The apply kernel of the large workloads (operands packed once per head, many short-lived workgroups),
+    forced onto small shapes: the oracle's values, and the bits of the kernel that packs per workgroup."""
+    print(f"packed apply B={B} H={H} N={N} d={d} {dtype} waves={waves}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=51, device="cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    monkeypatch.setenv("LINFUSION_APPLY_PACKED", "2")
+    ref = _run(qd, kd, vd, flags=lf.FLAG_FORCE_SPLIT)
+    monkeypatch.setenv("LINFUSION_APPLY_PACKED", "3")
+    monkeypatch.setenv("LINFUSION_APPLY_WAVES", str(waves))
+    monkeypatch.setenv("LINFUSION_APPLY_WGS", str(7 * B * H))      # several workgroups per head, tiles dealt cyclically
+    out = _run(qd, kd, vd, flags=lf.FLAG_FORCE_SPLIT)
+    parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"packed apply N={N} d={d} {dtype}")
+    assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
+    if N >= 1000:      # feature maps and the un-normalized arm on the same kernel
+        for fm, flags in ((1, 0), (2, 0), (0, lf.FLAG_UNNORMALIZED)):
+            qq, kk = (qd.abs(), kd.abs()) if fm == 2 else (qd, kd)
+            out = _run(qq, kk, vd, fm, 1e-6, flags | lf.FLAG_FORCE_SPLIT)
+            parity.check_all(out, qq.cpu(), kk.cpu(), v, dtype, fm, 1e-6, not flags, f"packed apply fm={fm} flags={flags}")
+
+
 @pytest.mark.parametrize("path", list(PATHS))
 @pytest.mark.parametrize("name", ["sd15_256_f32", "sd15_512_f16", "sd21_768_f16", "sd21_768_f16_peaky",
                                   "sdxl_2048_A_bf16", "sdxl_2048_B_bf16"])
