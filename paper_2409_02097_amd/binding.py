@@ -26,7 +26,8 @@ class LinFusionError(RuntimeError):
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, _LIB_NAME)
+    """The in-tree library; LINFUSION_LIBRARY names another build of it (for A/B timing of two builds)."""
+    return os.environ.get("LINFUSION_LIBRARY") or os.path.join(_HERE, _LIB_NAME)
 
 
 def library() -> ctypes.CDLL:

@@ -125,6 +125,9 @@ struct ApplyDma {
   using Sh = Shape16<D>;
   using Cfg = ApplyDmaCfg<D, DV>;
   static constexpr int NS = NSplit<T>::value;
+  // fp16 + elu+1 on stored queries: rows whose channels are all very negative are shifted (see compute_tile)
+  static constexpr bool kShiftRows = NSplit<T>::value == 1 && FM == kPhiEluPlusOne && !MLP;
+  static constexpr float kSmallDen = 64.0f * D;   // see compute_tile
   // k-steps and chunks follow the query width D, output tiles and channels per half-wave the value width DV
   static constexpr int KS = Sh::kKS, MT2 = Shape16<DV>::kMT2, CPR = Sh::kChunksPerRow, HALF = Shape16<DV>::kHalf;
   static constexpr int NL = Cfg::kNL, NLO = Cfg::kNLO, NE = D * DV + D, R = Cfg::kRing;
@@ -558,55 +561,104 @@ struct ApplyDma {
       rstd = __builtin_amdgcn_rsqf(var + ln_eps);
       cn = -(pivot + mu) * rstd;
     }
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      const int chunk = kg * KS + s;
-      const bool ok = chunk < CPR;
-      u32x4 raw = u32x4{0, 0, 0, 0};
-      if (ok) raw = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, chunk));
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        float x0, x1;
-        unpack2<T>(raw[w], x0, x1);
-        if constexpr (MLP) {
-          float t0, t1;
-          unpack2<T>(traw[s][w], t0, t1);
-          const float y0 = __builtin_fmaf(gam[s * 8 + 2 * w], __builtin_fmaf(t0, rstd, cn), bet[s * 8 + 2 * w]);
-          const float y1 = __builtin_fmaf(gam[s * 8 + 2 * w + 1], __builtin_fmaf(t1, rstd, cn), bet[s * 8 + 2 * w + 1]);
-          x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
-          x1 += fmaxf(y1, slope * y1);
-        }
-        float r0 = ok ? phi<FM>(x0) : 0.0f;
-        float r1 = ok ? phi<FM>(x1) : 0.0f;
-        if constexpr (NS == 1) {
-          Bh[s][w] = pack2<T>(r0, r1);
-        } else {
-          uint32_t h, l;
-          pack2_split<T>(r0, r1, h, l);
-          Bh[s][w] = h;
-          Bl[s][w] = l;
-        }
-      }
-    }
-
-    f32x16 acc[MT2];
-#pragma unroll
-    for (int t = 0; t < MT2; ++t) {
-      acc[t] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    // fp16, elu+1: a token whose channels are all far below zero has phi(q) = exp(q) below fp16's normal range
+    // (bits are lost below -10, everything below -17), although only the ratios between its channels matter.
+    // Such a token shows in its (scaled) denominator, which is then tiny: z' is scaled to about 2^14, so every row
+    // whose largest phi(q) is below 2^-8 has den' < 64 d.  Where a tile holds such a row the wave goes through the
+    // tile a second time and evaluates those rows as exp(q - m), m = the row's largest channel: the factor exp(-m)
+    // cancels between numerator and denominator once eps carries it too.  Ordinary tiles take one round and pay a
+    // compare.  (Without the normalizer nothing signals the case, so there every row is treated that way and the
+    // factor is taken out again at the end.)
+    float qc = 0.0f;   // this lane's row is evaluated times 2^qc
+    auto row_shift = [&](const u32x4* raw) {      // -log2(e) * min(largest channel of the lane's token, 0)
+      f16x2 m2 = __builtin_bit_cast(f16x2, LowestBits<F16>::value);
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        acc[t] = mfma_32x32x16<T>(A[0][t][s], Bh[s], acc[t]);
-        if constexpr (NS == 2) {
-          acc[t] = mfma_32x32x16<T>(A[0][t][s], Bl[s], acc[t]);
-          if (16 * t < HALF) acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);   // lo rows are zero beyond S'
+        if (kg * KS + s < CPR) {
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const uint32_t word = raw[s][w];
+            m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(f16x2, word));
+          }
         }
       }
+      float m = fmaxf((float)m2[0], (float)m2[1]);
+      m = fmaxf(m, __shfl_xor(m, 32));          // the token's other half of the channels
+      return fminf(m, 0.0f) * -1.44269504088896340736f;
+    };
+    f32x16 acc[MT2];
+    float den = 0.0f;
+    // B operands of the lane's token (each row times 2^c) and the products with the state operands
+    auto products = [&](const bool shift, const bool only_small) {
+      u32x4 qraw[KS];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        qraw[s] = u32x4{0, 0, 0, 0};
+        if (kg * KS + s < CPR) qraw[s] = *reinterpret_cast<const u32x4*>(chunk_ptr(slot, kg * KS + s));
+      }
+      if (shift) {
+        const float sh = row_shift(qraw);      // (all lanes take part: it exchanges values between them)
+        qc = (!only_small || den < kSmallDen) ? sh : 0.0f;
+      }
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const int chunk = kg * KS + s;
+        const bool ok = chunk < CPR;
+        const u32x4 raw = qraw[s];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float x0, x1;
+          unpack2<T>(raw[w], x0, x1);
+          if constexpr (MLP) {
+            float t0, t1;
+            unpack2<T>(traw[s][w], t0, t1);
+            const float y0 = __builtin_fmaf(gam[s * 8 + 2 * w], __builtin_fmaf(t0, rstd, cn), bet[s * 8 + 2 * w]);
+            const float y1 = __builtin_fmaf(gam[s * 8 + 2 * w + 1], __builtin_fmaf(t1, rstd, cn), bet[s * 8 + 2 * w + 1]);
+            x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
+            x1 += fmaxf(y1, slope * y1);
+          }
+          float r0 = ok ? (shift ? phi_scaled<FM>(x0, qc) : phi<FM>(x0)) : 0.0f;
+          float r1 = ok ? (shift ? phi_scaled<FM>(x1, qc) : phi<FM>(x1)) : 0.0f;
+          if constexpr (NS == 1) {
+            Bh[s][w] = pack2<T>(r0, r1);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(r0, r1, h, l);
+            Bh[s][w] = h;
+            Bl[s][w] = l;
+          }
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < MT2; ++t) {
+        acc[t] = f32x16{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          acc[t] = mfma_32x32x16<T>(A[0][t][s], Bh[s], acc[t]);
+          if constexpr (NS == 2) {
+            acc[t] = mfma_32x32x16<T>(A[0][t][s], Bl[s], acc[t]);
+            if (16 * t < HALF) acc[t] = mfma_32x32x16<T>(A[1][t][s], Bh[s], acc[t]);   // lo rows are zero beyond S'
+          }
+        }
+      }
+      // normalizer: slots HALF (z' rounded) and HALF+1 (its remainder) of this lane's accumulators
+      if constexpr (NORM) den = acc[HALF / 16][HALF % 16] + acc[(HALF + 1) / 16][(HALF + 1) % 16];
+    };
+    if constexpr (kShiftRows && !NORM) {
+      products(true, false);
+    } else {
+      products(false, false);
+      if constexpr (kShiftRows) {
+        if (__builtin_amdgcn_ballot_w64(den < kSmallDen) != 0) products(true, true);   // rare: a second round
+      }
     }
-    // normalizer: slots HALF (z' rounded) and HALF+1 (its remainder) of this lane's accumulators
     float scale = c1;
     if constexpr (NORM) {
-      const float den = acc[HALF / 16][HALF % 16] + acc[(HALF + 1) / 16][(HALF + 1) % 16] + eps_s;
-      scale = c1 * __builtin_amdgcn_rcpf(den);
+      float eps_row = eps_s;
+      if constexpr (kShiftRows) eps_row = eps_s * __builtin_amdgcn_exp2f(qc);   // (inf for a row of -65504s: out = 0)
+      scale = c1 * __builtin_amdgcn_rcpf(den + eps_row);
+    } else if constexpr (kShiftRows) {
+      scale = c1 * __builtin_amdgcn_exp2f(-qc);   // nothing cancels without the normalizer: take the factor out again
     }
 
     // ---- d/2 channels of this lane's token -> 16-bit -> back into the slot -------------------------

@@ -51,6 +51,20 @@ LF_DEV float phi(float x) {
   }
 }
 
+// elu(x)+1 of a value whose exponential branch is evaluated as exp(x + c / log2 e), i.e. scaled by 2^c: used
+// where a whole row (or a whole stream) of inputs is negative and so small that exp(x) itself would leave the
+// normal range of fp16; the caller divides the factor out again (or it cancels in a ratio).  c = 0: phi itself.
+template <int FM>
+LF_DEV float phi_scaled(float x, float c) {
+  if constexpr (FM == kPhiEluPlusOne) {
+    constexpr float kLog2e = 1.44269504088896340736f;
+    const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(x, kLog2e, c));
+    return x > 0.0f ? x + 1.0f : e;
+  } else {
+    return phi<FM>(x);
+  }
+}
+
 // ---- 16-bit storage <-> fp32 ----------------------------------------------------------------
 template <typename T> LF_DEV void unpack2(uint32_t w, float& lo, float& hi);
 template <> LF_DEV void unpack2<F16>(uint32_t w, float& lo, float& hi) {

@@ -76,16 +76,9 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
   const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
 
   const long long n_tiles = (N + kTile - 1) / kTile;
-  TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
 
   f32x4 acc[MT][MT];
   f32x4 accz[MT];
-#pragma unroll
-  for (int a = 0; a < MT; ++a) {
-    accz[a] = f32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int b = 0; b < MT; ++b) acc[a][b] = f32x4{0, 0, 0, 0};
-  }
   const uint32_t one2 = (uint32_t)OneBits<T>::value * 0x10001u;
   const u32x4 ones = {one2, one2, one2, one2};
 
@@ -109,76 +102,153 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
     return lim;
   };
 
-  int lim = 0;
-  if (it.valid()) lim = issue_loads(it.t);
+  // fp16 with elu+1: phi(k) = exp(k) of keys far below zero leaves fp16's normal range (bits are lost below -10,
+  // everything below -17), which matters when ALL keys a wave sees are that small: nothing larger dominates its
+  // sums then.  Such a stream shows in the wave's normalizer sums: z_c >= every phi(k_jc) that went into it, so if
+  // all z_c stay below 2^-11 per token summed, no single phi(k) can have been above 2^-11 either... and conversely a
+  // stream whose largest phi(k) is below 2^-11 always has every z_c below (tokens) * 2^-11.  Only then (never for
+  // ordinary data) the wave goes through its tiles again: once to find its largest key m, and, if m is below
+  // kRescanBelow, once more with phi(k) evaluated as exp(k - m) (m not below kShiftFloor, so that the rows past
+  // the end of a head, which are loaded as the most negative fp16 value, still map to 0); the factor exp(m) is
+  // taken out of the fp32 sums afterwards.
+  constexpr bool kRescan = NS == 1 && FM == kPhiEluPlusOne;
+  constexpr float kRescanBelow = -5.0f, kShiftFloor = -64.0f, kLog2e = 1.44269504088896340736f;
 
-  // (while the first tile is on its way) one-time fill of the wave's tiles: phi(K) pad columns zero; V pad columns zero except the
-  // ones column at index D (when a spare column exists) which makes z fall out of the products
+  // (one-time fill of the wave's tiles: phi(K) pad columns zero; V pad columns zero except the ones column at
+  // index D (when a spare column exists) which makes z fall out of the products)
   for (int i = lane; i < Cfg::kTileElems; i += 64) {
 #pragma unroll
     for (int s = 0; s < NS; ++s) ldsP[s][i] = 0;
     ldsV[i] = (Sh::kSpareCol && (i % RS) == D) ? OneBits<T>::value : (uint16_t)0;
   }
 
-  while (it.valid()) {
-    // ---- phi(K) -> 16-bit (hi [, lo]) -> LDS ; V -> LDS --------------------------------------
+  // the wave's whole stream: sums of phi(k) 2^kc (x) v into acc / accz; returns the token rows summed
+  auto run_stream = [&](const float kc) {
+    TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
 #pragma unroll
-    for (int u = 0; u < NL; ++u) {
-      int c = u * 64 + lane;
-      if (c < Cfg::kChunks) {
-        const bool ok = trow[u] < lim;
-        u32x4 ph, pl;
+    for (int a = 0; a < MT; ++a) {
+      accz[a] = f32x4{0, 0, 0, 0};
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          float x0, x1;
-          unpack2<T>(kr[u][w], x0, x1);
-          float p0 = phi<FM>(x0), p1 = phi<FM>(x1);
-          if constexpr (!kPhiKillsLowest<FM>) {
-            p0 = ok ? p0 : 0.0f;
-            p1 = ok ? p1 : 0.0f;
+      for (int b = 0; b < MT; ++b) acc[a][b] = f32x4{0, 0, 0, 0};
+    }
+    int lim = 0;
+    long long tokens = 0;
+    if (it.valid()) lim = issue_loads(it.t);
+    while (it.valid()) {
+      tokens += lim;
+      // ---- phi(K) -> 16-bit (hi [, lo]) -> LDS ; V -> LDS --------------------------------------
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        int c = u * 64 + lane;
+        if (c < Cfg::kChunks) {
+          const bool ok = trow[u] < lim;
+          u32x4 ph, pl;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            float x0, x1;
+            unpack2<T>(kr[u][w], x0, x1);
+            float p0 = kRescan ? phi_scaled<FM>(x0, kc) : phi<FM>(x0);
+            float p1 = kRescan ? phi_scaled<FM>(x1, kc) : phi<FM>(x1);
+            if constexpr (!kPhiKillsLowest<FM>) {
+              p0 = ok ? p0 : 0.0f;
+              p1 = ok ? p1 : 0.0f;
+            }
+            if constexpr (NS == 1) {
+              ph[w] = pack2<T>(p0, p1);
+            } else {
+              uint32_t h, l;
+              pack2_split<T>(p0, p1, h, l);
+              ph[w] = h;
+              pl[w] = l;
+            }
           }
-          if constexpr (NS == 1) {
-            ph[w] = pack2<T>(p0, p1);
-          } else {
-            uint32_t h, l;
-            pack2_split<T>(p0, p1, h, l);
-            ph[w] = h;
-            pl[w] = l;
-          }
+          *reinterpret_cast<u32x4*>(ldsP[0] + lds_off[u]) = ph;
+          if constexpr (NS == 2) *reinterpret_cast<u32x4*>(ldsP[1] + lds_off[u]) = pl;
+          *reinterpret_cast<u32x4*>(ldsV + lds_off[u]) = vr[u];
         }
-        *reinterpret_cast<u32x4*>(ldsP[0] + lds_off[u]) = ph;
-        if constexpr (NS == 2) *reinterpret_cast<u32x4*>(ldsP[1] + lds_off[u]) = pl;
-        *reinterpret_cast<u32x4*>(ldsV + lds_off[u]) = vr[u];
       }
-    }
-    // ---- prefetch the wave's next tile while this one is multiplied -------------------------
-    it.next();
-    int next_lim = 0;
-    if (it.valid()) next_lim = issue_loads(it.t);
+      // ---- prefetch the wave's next tile while this one is multiplied -------------------------
+      it.next();
+      int next_lim = 0;
+      if (it.valid()) next_lim = issue_loads(it.t);
 
-    // ---- token-major operands by transposing LDS reads, then the outer products -------------
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    u32x4 bfrag[MT];
+      // ---- token-major operands by transposing LDS reads, then the outer products -------------
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      u32x4 bfrag[MT];
 #pragma unroll
-    for (int b = 0; b < MT; ++b) {
-      u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * b);
-      u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * b);
-      bfrag[b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+      for (int b = 0; b < MT; ++b) {
+        u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * b);
+        u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * b);
+        bfrag[b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+      }
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+#pragma unroll
+        for (int a = 0; a < MT; ++a) {
+          u32x2 r0 = lds_read_tr16(ldsP[s] + tr_base + 16 * a);
+          u32x2 r1 = lds_read_tr16(ldsP[s] + tr_base + 4 * RS + 16 * a);
+          u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+          for (int b = 0; b < MT; ++b) acc[a][b] = mfma_16x16x32<T>(afrag, bfrag[b], acc[a][b]);
+          if constexpr (!Sh::kSpareCol) accz[a] = mfma_16x16x32<T>(afrag, ones, accz[a]);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      lim = next_lim;
     }
+    return tokens;
+  };
+
+  const long long tokens = run_stream(0.0f);
+
+  if constexpr (kRescan) {
+    // largest normalizer sum of the wave (spare column: column D of the last block row holds z; else accz, whose
+    // columns all hold it)
+    float zm = 0.0f;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
+    for (int a = 0; a < MT; ++a) {
 #pragma unroll
-      for (int a = 0; a < MT; ++a) {
-        u32x2 r0 = lds_read_tr16(ldsP[s] + tr_base + 16 * a);
-        u32x2 r1 = lds_read_tr16(ldsP[s] + tr_base + 4 * RS + 16 * a);
-        u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
-#pragma unroll
-        for (int b = 0; b < MT; ++b) acc[a][b] = mfma_16x16x32<T>(afrag, bfrag[b], acc[a][b]);
-        if constexpr (!Sh::kSpareCol) accz[a] = mfma_16x16x32<T>(afrag, ones, accz[a]);
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (Sh::kSpareCol) zm = fmaxf(zm, j16 == D % 16 ? acc[a][D / 16][i] : 0.0f);
+        else zm = fmaxf(zm, accz[a][i]);
       }
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    lim = next_lim;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) zm = fmaxf(zm, __shfl_xor(zm, o));
+    if (zm < (float)tokens * 0x1p-11f) {      // never for ordinary data, a wave without tiles (0 < 0) or NaNs
+      // the stream's largest key
+      f16x2 kmax2 = __builtin_bit_cast(f16x2, LowestBits<F16>::value);
+      {
+        TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
+        while (it.valid()) {
+          (void)issue_loads(it.t);
+#pragma unroll
+          for (int u = 0; u < NL; ++u) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              const uint32_t word = kr[u][w];
+              kmax2 = __builtin_elementwise_max(kmax2, __builtin_bit_cast(f16x2, word));
+            }
+          }
+          it.next();
+        }
+      }
+      float m = fmaxf((float)kmax2[0], (float)kmax2[1]);
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      // (not small after all -- many tokens of middling keys -- or nothing but the most negative value: keep the sums)
+      if (m < kRescanBelow && m > -65504.0f) {
+        const float kc = fmaxf(m, kShiftFloor) * -kLog2e;
+        (void)run_stream(kc);
+        const float back = __builtin_amdgcn_exp2f(-kc);      // the rescanned sums carry 2^kc
+#pragma unroll
+        for (int a = 0; a < MT; ++a) {
+          accz[a] *= back;
+#pragma unroll
+          for (int b = 0; b < MT; ++b) acc[a][b] *= back;
+        }
+      }
+    }
   }
 
   // ---- cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3): waves 0 and 1 park their accumulators
@@ -293,16 +363,9 @@ state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
   const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
 
   const long long n_tiles = (N + kTile - 1) / kTile;
-  TileIter it(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);   // every wave walks every tile
 
   f32x4 acc[MT][MT];
   f32x4 accz[MT];
-#pragma unroll
-  for (int a = 0; a < MT; ++a) {
-    accz[a] = f32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int bb = 0; bb < MT; ++bb) acc[a][bb] = f32x4{0, 0, 0, 0};
-  }
   const uint32_t one2 = (uint32_t)OneBits<T>::value * 0x10001u;
   const u32x4 ones = {one2, one2, one2, one2};
 
@@ -325,9 +388,6 @@ state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
     return lim;
   };
 
-  int lim = 0;
-  if (it.valid()) lim = issue_loads(it.t);
-
   // one-time fill: pad columns zero, ones column (index D, where a spare column exists) in the V tiles
   for (int i = tid; i < (Cfg::kDouble ? 2 : 1) * Cfg::kBufElems; i += NT) {
     const int tile_idx = i / TE, within = i % TE;
@@ -336,68 +396,162 @@ state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
   }
   __syncthreads();
 
-  int buf = 0;
-  while (it.valid()) {
-    uint16_t* bufp = lds + buf * Cfg::kBufElems;
-    // ---- phi(K) -> 16-bit (hi [, lo]) -> the owning head's tiles ; V likewise ------------------
+  // fp16 with elu+1: a head whose keys are all far below zero is summed a second time relative to its largest
+  // key (see reduce16_phase).  Here the waves of a workgroup move in step, so the workgroup decides together;
+  // `hshift`: per head of the group, first the largest key (as an ordered integer), then the shift 2^kc.
+  constexpr bool kRescan = NS == 1 && FM == kPhiEluPlusOne;
+  constexpr float kRescanBelow = -5.0f, kShiftFloor = -64.0f, kLog2e = 1.44269504088896340736f;
+  __shared__ int hmax[8];
+  __shared__ float hshift[8];
+  int head_of[NL];
 #pragma unroll
-    for (int u = 0; u < NL; ++u) {
-      if (u * NT + tid < Cfg::kChunks) {
-        const bool ok = trow[u] < lim;
-        u32x4 ph, pl;
+  for (int u = 0; u < NL; ++u) head_of[u] = ((u * NT + tid) % PC) / CPR;
+
+  // the workgroup's whole stream; `shifted`: chunk u's phi(k) carries 2^hshift[its head]; returns token rows summed
+  auto run_stream = [&](const bool shifted) {
+    TileIter it(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);   // every wave walks every tile
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          float x0, x1;
-          unpack2<T>(kr[u][w], x0, x1);
-          float p0 = phi<FM>(x0), p1 = phi<FM>(x1);
-          if constexpr (!kPhiKillsLowest<FM>) {
-            p0 = ok ? p0 : 0.0f;
-            p1 = ok ? p1 : 0.0f;
+    for (int a = 0; a < MT; ++a) {
+      accz[a] = f32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int bb = 0; bb < MT; ++bb) acc[a][bb] = f32x4{0, 0, 0, 0};
+    }
+    float kcu[NL];
+#pragma unroll
+    for (int u = 0; u < NL; ++u) kcu[u] = shifted ? hshift[head_of[u]] : 0.0f;
+    int lim = 0;
+    long long tokens = 0;
+    if (it.valid()) lim = issue_loads(it.t);
+    int buf = 0;
+    while (it.valid()) {
+      tokens += lim;
+      uint16_t* bufp = lds + buf * Cfg::kBufElems;
+      // ---- phi(K) -> 16-bit (hi [, lo]) -> the owning head's tiles ; V likewise ------------------
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        if (u * NT + tid < Cfg::kChunks) {
+          const bool ok = trow[u] < lim;
+          u32x4 ph, pl;
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            float x0, x1;
+            unpack2<T>(kr[u][w], x0, x1);
+            float p0 = (kRescan && shifted) ? phi_scaled<FM>(x0, kcu[u]) : phi<FM>(x0);
+            float p1 = (kRescan && shifted) ? phi_scaled<FM>(x1, kcu[u]) : phi<FM>(x1);
+            if constexpr (!kPhiKillsLowest<FM>) {
+              p0 = ok ? p0 : 0.0f;
+              p1 = ok ? p1 : 0.0f;
+            }
+            if constexpr (NS == 1) {
+              ph[w] = pack2<T>(p0, p1);
+            } else {
+              uint32_t h, l;
+              pack2_split<T>(p0, p1, h, l);
+              ph[w] = h;
+              pl[w] = l;
+            }
           }
-          if constexpr (NS == 1) {
-            ph[w] = pack2<T>(p0, p1);
-          } else {
-            uint32_t h, l;
-            pack2_split<T>(p0, p1, h, l);
-            ph[w] = h;
-            pl[w] = l;
-          }
+          *reinterpret_cast<u32x4*>(bufp + loff[u]) = ph;
+          if constexpr (NS == 2) *reinterpret_cast<u32x4*>(bufp + TE + loff[u]) = pl;
+          *reinterpret_cast<u32x4*>(bufp + NS * TE + loff[u]) = vr[u];
         }
-        *reinterpret_cast<u32x4*>(bufp + loff[u]) = ph;
-        if constexpr (NS == 2) *reinterpret_cast<u32x4*>(bufp + TE + loff[u]) = pl;
-        *reinterpret_cast<u32x4*>(bufp + NS * TE + loff[u]) = vr[u];
+      }
+      it.next();
+      int next_lim = 0;
+      if (it.valid()) next_lim = issue_loads(it.t);
+      lds_barrier();   // the tile is complete in LDS
+
+      // ---- wave w: head w's outer products ----------------------------------------------------
+      const uint16_t* hp = bufp + wave * Cfg::kHeadElems;
+      const uint16_t* ldsV = hp + NS * TE;
+      u32x4 bfrag[MT];
+#pragma unroll
+      for (int bb = 0; bb < MT; ++bb) {
+        u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * bb);
+        u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * bb);
+        bfrag[bb] = u32x4{r0[0], r0[1], r1[0], r1[1]};
+      }
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+#pragma unroll
+        for (int a = 0; a < MT; ++a) {
+          u32x2 r0 = lds_read_tr16(hp + s * TE + tr_base + 16 * a);
+          u32x2 r1 = lds_read_tr16(hp + s * TE + tr_base + 4 * RS + 16 * a);
+          u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+#pragma unroll
+          for (int bb = 0; bb < MT; ++bb) acc[a][bb] = mfma_16x16x32<T>(afrag, bfrag[bb], acc[a][bb]);
+          if constexpr (!Sh::kSpareCol) accz[a] = mfma_16x16x32<T>(afrag, ones, accz[a]);
+        }
+      }
+      if constexpr (Cfg::kDouble) buf ^= 1;
+      else lds_barrier();   // single buffer: everyone is done reading before the next tile is written
+      lim = next_lim;
+    }
+    return tokens;
+  };
+
+  const long long tokens = run_stream(false);
+
+  if constexpr (kRescan) {
+    float zm = 0.0f;      // largest normalizer sum of this wave's head
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (Sh::kSpareCol) zm = fmaxf(zm, j16 == D % 16 ? acc[a][D / 16][i] : 0.0f);
+        else zm = fmaxf(zm, accz[a][i]);
       }
     }
-    it.next();
-    int next_lim = 0;
-    if (it.valid()) next_lim = issue_loads(it.t);
-    lds_barrier();   // the tile is complete in LDS
-
-    // ---- wave w: head w's outer products ----------------------------------------------------
-    const uint16_t* hp = bufp + wave * Cfg::kHeadElems;
-    const uint16_t* ldsV = hp + NS * TE;
-    u32x4 bfrag[MT];
 #pragma unroll
-    for (int bb = 0; bb < MT; ++bb) {
-      u32x2 r0 = lds_read_tr16(ldsV + tr_base + 16 * bb);
-      u32x2 r1 = lds_read_tr16(ldsV + tr_base + 4 * RS + 16 * bb);
-      bfrag[bb] = u32x4{r0[0], r0[1], r1[0], r1[1]};
-    }
+    for (int o = 32; o > 0; o >>= 1) zm = fmaxf(zm, __shfl_xor(zm, o));
+    const bool suspicious = zm < (float)tokens * 0x1p-11f;     // never for ordinary data
+    if (__syncthreads_or(suspicious ? 1 : 0)) {
+      // rare: every head's largest key (an ordered integer image of the float, so that an integer maximum does it)
+      if (tid < 8) hmax[tid] = (int)0x80000000;
+      __syncthreads();
+      f16x2 kmax2[NL];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
+      for (int u = 0; u < NL; ++u) kmax2[u] = __builtin_bit_cast(f16x2, LowestBits<F16>::value);
+      {
+        TileIter it(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);
+        while (it.valid()) {
+          (void)issue_loads(it.t);
+#pragma unroll
+          for (int u = 0; u < NL; ++u) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+              const uint32_t word = kr[u][w];
+              kmax2[u] = __builtin_elementwise_max(kmax2[u], __builtin_bit_cast(f16x2, word));
+            }
+          }
+          it.next();
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        if (u * NT + tid < Cfg::kChunks) {
+          const float m = fmaxf((float)kmax2[u][0], (float)kmax2[u][1]);
+          const int bits = __builtin_bit_cast(int, m);
+          atomicMax(&hmax[head_of[u]], bits >= 0 ? bits : bits ^ 0x7fffffff);
+        }
+      }
+      __syncthreads();
+      if (lane == 0) {      // wave w decides for head w (its own `suspicious` is wave-uniform)
+        const int key = hmax[wave];
+        const float m = __builtin_bit_cast(float, key >= 0 ? key : key ^ 0x7fffffff);
+        const bool shift = suspicious && m < kRescanBelow && m > -65504.0f;
+        hshift[wave] = shift ? fmaxf(m, kShiftFloor) * -kLog2e : 0.0f;
+      }
+      __syncthreads();
+      (void)run_stream(true);      // (heads without a shift come out as before)
+      const float back = __builtin_amdgcn_exp2f(-hshift[wave]);
 #pragma unroll
       for (int a = 0; a < MT; ++a) {
-        u32x2 r0 = lds_read_tr16(hp + s * TE + tr_base + 16 * a);
-        u32x2 r1 = lds_read_tr16(hp + s * TE + tr_base + 4 * RS + 16 * a);
-        u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+        accz[a] *= back;
 #pragma unroll
-        for (int bb = 0; bb < MT; ++bb) acc[a][bb] = mfma_16x16x32<T>(afrag, bfrag[bb], acc[a][bb]);
-        if constexpr (!Sh::kSpareCol) accz[a] = mfma_16x16x32<T>(afrag, ones, accz[a]);
+        for (int bb = 0; bb < MT; ++bb) acc[a][bb] *= back;
       }
     }
-    if constexpr (Cfg::kDouble) buf ^= 1;
-    else lds_barrier();   // single buffer: everyone is done reading before the next tile is written
-    lim = next_lim;
   }
 
   // ---- each wave owns a whole partial: straight from the accumulator layout (lane: rows 4 (l / 16) + i,

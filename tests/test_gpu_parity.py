@@ -269,6 +269,44 @@ def test_extreme_values_match_oracle(dtype, case, path):
     parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"{case} {dtype}")
 
 
+@pytest.mark.parametrize("path", ["split", "fused", "packed"])
+@pytest.mark.parametrize("d", [40, 64])
+@pytest.mark.parametrize("case", ["q-20", "q-12", "k-12", "k-20", "q-20_k-20", "some_rows_q-25", "some_tokens_k-25",
+                                  "q-60000"])
+def test_fp16_inputs_far_below_zero(case, d, path, monkeypatch, tuning):
+    """exp(x) of fp16 inputs far below zero leaves the normal range of an fp16 operand (subnormal below -10, zero
+    below -17), but the definition gives a proper weighted mean as long as the denominator stays above eps: query
+    rows are evaluated relative to their largest channel, key streams relative to their largest key.  Shifts are
+    applied to q or k alone (shifting both only makes eps dominate on both sides, which hides the case)."""
+    B, H, N = 1, 2, 777
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=70, device="cpu")
+    if case == "q-20" or case == "q-20_k-20":
+        q = q - 20.0
+    if case == "q-12":
+        q = q - 12.0
+    if case == "q-60000":
+        q = q * 100.0 - 60000.0
+    if case == "k-12":
+        k = k - 12.0
+    if case == "k-20" or case == "q-20_k-20":
+        k = k - 20.0
+    if case == "some_rows_q-25":
+        q[:, :, ::3] -= 25.0
+    if case == "some_tokens_k-25":
+        k[:, :, ::2] -= 25.0
+    q, k, v = q.half(), k.half(), v.half()
+    flags = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED, "packed": lf.FLAG_FORCE_SPLIT}[path]
+    monkeypatch.setenv("LINFUSION_APPLY_PACKED", "3" if path == "packed" else "2")
+    # (exp(-60000) is zero in every arithmetic: the definition gives 0 / eps = 0 there, and nothing without eps)
+    for eps in ((1e-6,) if case == "q-60000" else (1e-6, 0.0)):
+        out = _run(q.cuda(), k.cuda(), v.cuda(), 0, eps, flags)
+        worst = parity.check_all(out, q, k, v, "f16", 0, eps, True, f"{case} d={d} {path} eps={eps}")
+        print(f"{case} d={d} {path} eps={eps}: worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
+    if case in ("q-12", "some_rows_q-25"):      # the un-normalized arm takes the row's factor out again
+        out = _run(q.cuda(), k.cuda(), v.cuda(), 0, 1e-6, flags | lf.FLAG_UNNORMALIZED)
+        parity.check_all(out, q, k, v, "f16", 0, 1e-6, False, f"{case} d={d} {path} unnormalized")
+
+
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
 def test_a_nan_stays_inside_its_head(dtype):
     B, H, N, d = 1, 3, 500, 40

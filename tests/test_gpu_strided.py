@@ -155,3 +155,34 @@ def test_sd_sized_token_major_layer(name, monkeypatch, tuning):
                                   _ws(B, H, N, d, c["dtype"], qt.device))
     torch.cuda.synchronize()
     parity.check_all(view(ot).contiguous(), q, k, v, c["dtype"], 0, wl.EPS, True, name + " token-major")
+
+
+@pytest.mark.parametrize("H,d", [(8, 40), (4, 40), (12, 24), (4, 80)])
+@pytest.mark.parametrize("case", ["q-20", "k-12", "k-20", "one_head_k-20", "some_tokens_k-25"])
+def test_token_major_fp16_inputs_far_below_zero(case, H, d):
+    """The row-piece kernels on inputs whose exp() leaves fp16's normal range (see the test of the same name for
+    the per-head kernels): queries per row, keys per head -- a workgroup here sums several heads at once, and one
+    of them may need the second pass while its neighbours do not."""
+    B, N = 1, 777
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=71, device="cpu")
+    if case == "q-20":
+        q = q - 20.0
+    if case == "k-12":
+        k = k - 12.0
+    if case == "k-20":
+        k = k - 20.0
+    if case == "one_head_k-20":
+        k[:, 1] -= 20.0
+    if case == "some_tokens_k-25":
+        k[:, :, ::2] -= 25.0
+    q, k, v = q.half(), k.half(), v.half()
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda()          # [B, N, H, d] in memory
+    qt, kt, vt = tm(q), tm(k), tm(v)
+    view = lambda t: t.permute(0, 2, 1, 3)
+    for eps in (1e-6, 0.0):
+        ot = torch.full_like(qt, float("nan"))
+        lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(ot), 0, eps, lf.FLAG_FORCE_SPLIT,
+                                      _ws(B, H, N, d, "f16", "cuda"))
+        torch.cuda.synchronize()
+        worst = parity.check_all(view(ot).contiguous(), q, k, v, "f16", 0, eps, True, f"token-major {case} H={H} d={d} eps={eps}")
+        print(f"token-major {case} H={H} d={d} eps={eps}: worst max-norm ratio {worst[0]:.2e}", flush=True)
