@@ -11,6 +11,10 @@
  *     z     = sum_j phi(k_j)                (normalizer state, non-causal Z of Eq. 5)
  *     out_i = phi(q_i) S / (phi(q_i) . z + eps)
  *
+ * (Sections of the paper are cited by position: 2.1 Preliminary, 2.2 Overview, 2.3 Normalization-Aware
+ * Mamba, 2.4 Non-Causal Mamba, 2.5 Training Objectives, 3.1 Implementation Details, 3.2 Main Results,
+ * 3.3 Empirical Extensions.)
+ *
  * Every step (feature map, state reduction, combine, apply, normalize) runs in this
  * library's own HIP kernels.  There is no CPU fallback: on a machine without a gfx950
  * device every compute entry point returns LINFUSION_ERR_DEVICE.
@@ -102,7 +106,7 @@ int linfusion_attn_fwd_ex(const void* q, const void* k, const void* v, void* out
 
 /*
  * linfusion_attn_fwd_ex on tensors that are views into larger buffers, so that the layer around
- * the mixer needs no permute or copy: the UNet's token-major activations [B, N, H*d] (Sec. 3:
+ * the mixer needs no permute or copy: the UNet's token-major activations [B, N, H*d] (Sec. 2.2, Overview:
  * the module replaces self-attention inside each transformer block, whose q/k/v projections emit
  * that layout), or q, k, v sliced out of one fused projection output.
  *
@@ -152,7 +156,7 @@ int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void
 
 /*
  * Backward pass of the mixer: gradients of a scalar loss with respect to q, k and v, given
- * dout = d loss / d out.  (Training by distillation, Sec. 3.4, Eq. 8, differentiates through every
+ * dout = d loss / d out.  (Training by distillation, Sec. 2.5 (Training Objectives), Eq. 8, differentiates through every
  * LinFusion module; the paper gives no formula, so the operation is defined as the derivative of the
  * forward definition above.)  With P = phi(K), R = phi(Q), S = P^T V, z = P^T 1, den_i = r_i . z + eps:
  *
@@ -212,7 +216,7 @@ int linfusion_attn_bwd_strided(const void* q, const void* k, const void* v, cons
 size_t linfusion_attn_bwd_workspace_bytes(int B, int H, long long N, int d, int dtype);
 
 /*
- * The mixer fed directly by the two-branch MLPs f' and g' that produce its queries and keys (Sec. 4.1,
+ * The mixer fed directly by the two-branch MLPs f' and g' that produce its queries and keys (Sec. 3.1 (Implementation Details),
  * implementation details: a linear branch, started from the softmax layer's W_Q / W_K, plus one
  * Linear-LayerNorm-LeakyReLU block, started at zero, the two results added; Prop. 2 names the functions):
  *
@@ -253,7 +257,7 @@ int linfusion_attn_fwd_mlp(const void* a_q, const void* t_q, const void* a_k, co
                            void* workspace, size_t workspace_bytes, void* stream, void* events[4]);
 
 /*
- * linfusion_attn_fwd_mlp on strided token rows (Sec. 4.1: the five branch results are usually column blocks of
+ * linfusion_attn_fwd_mlp on strided token rows (Sec. 3.1 (Implementation Details): the five branch results are usually column blocks of
  * one projection's output, [B, N, 5 C] say, and need no copy to become dense).
  *   in_strides      HOST array {batch, token}: element strides shared by a_q, t_q, a_k, t_k and v, whose
  *                   [b][n] row is C = H * d contiguous elements at base + b * batch + n * token.
@@ -380,7 +384,7 @@ int linfusion_init(void);
 
 /*
  * State-only entry point (the reduction half of Prop. 2; also what an N-sharded deployment
- * exchanges between devices, Sec. 3.3 "constant communication cost"): writes, per (b, h),
+ * exchanges between devices, Sec. 3.3 (Empirical Extensions, distributed parallel inference: "constant communication cost")): writes, per (b, h),
  * the fp32 state S as [d][d] row-major (row = feature index of phi(K), column = value
  * channel) followed by z as [d], i.e. state_out is a DEVICE buffer of B*H*(d*d+d) floats.
  * Same workspace contract as linfusion_attn_fwd_ex.

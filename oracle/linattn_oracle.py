@@ -35,13 +35,13 @@ equal to one, row-stochastic weights, Prop. 1 (constant V), joint K/V permutatio
 token-tiling invariance, the Kronecker identity from the proof of Prop. 2, affine
 equivariance, the d = 1 weighted mean, all-equal K = plain mean, IDENTITY phi = two library
 GEMMs, and a mutant check showing that planted mistakes are caught.
-Backward pass (needed by the distillation of Sec. 3.4, Eq. 8; the paper gives no formula, so the
+Backward pass (needed by the distillation of Sec. 2.5 (Training Objectives), Eq. 8; the paper gives no formula, so the
 definition is the derivative of the forward definition): `attention_backward_quadratic` differentiates
 the quadratic form with the n x n weights written out, `attention_backward_linear` is the same gradient
 reordered through the d x d states (S, z, dS, dz) and is what large-N parity tests call.  Pins
 (tests/test_oracle_backward.py): central differences of `attention_quadratic`, agreement of the two
 forms, dV column sums, orthogonality of d phi(q) to phi(q) at eps = 0, linearity in the upstream gradient.
-Upstream of the mixer (Sec. 4.1, implementation details): f' and g' are two-branch MLPs, a plain
+Upstream of the mixer (Sec. 3.1 (Implementation Details), implementation details): f' and g' are two-branch MLPs, a plain
 linear branch plus one Linear-LayerNorm-LeakyReLU block, the two results added; the linear branch starts
 from the softmax layer's W_Q / W_K and the other branch starts at zero.  `mlp_branch_sum` is that sum given
 the two Linear outputs, `module_mixer` feeds it to the mixer over all heads of a token-major tensor.
@@ -204,7 +204,7 @@ def attention_linear_stored(q, k, v, dtype: str, feature_map: int = ELU_PLUS_ONE
 
 
 # ----------------------------------------------------------------------------------------
-# The two-branch MLPs f', g' in front of the mixer (Sec. 4.1): what they add after their Linears.
+# The two-branch MLPs f', g' in front of the mixer (Sec. 3.1 (Implementation Details)): what they add after their Linears.
 # ----------------------------------------------------------------------------------------
 def layer_norm_rows(t, gamma, beta, ln_eps: float = 1e-5) -> np.ndarray:
     """LayerNorm over the last axis (all C channels of a token): (t - mean) / sqrt(var + ln_eps),

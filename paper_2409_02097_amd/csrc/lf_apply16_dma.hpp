@@ -102,7 +102,7 @@ template <int N> LF_DEV void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :
 // prefetch(), load_packed() with the wave's own head (operands prepared by pack_state16), stream().
 //
 // MLP (row-piece mode with the workgroup covering whole token rows, C = W D channels): the query is not read
-// but formed per element as  a + LeakyReLU(LayerNorm_C(t)),  the sum of the two branches of f' (Sec. 4.1), from
+// but formed per element as  a + LeakyReLU(LayerNorm_C(t)),  the sum of the two branches of f' (Sec. 3.1 (Implementation Details)), from
 // the branch results `a` (through the ring at offset 0) and `t` (through a second ring behind it).  The row
 // statistics come from the tile in LDS: every lane reduces the channels it holds of its token (mean and
 // centred sum of squares, exact in two passes over registers), the 2 W pieces per token meet in LDS and are

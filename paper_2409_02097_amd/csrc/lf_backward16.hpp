@@ -1,4 +1,4 @@
-// Backward pass of the token mixer for fp16 / bf16, head widths up to 80 (training by distillation, Sec. 3.4,
+// Backward pass of the token mixer for fp16 / bf16, head widths up to 80 (training by distillation, Sec. 2.5 (Training Objectives),
 // Eq. 8, needs it; the paper gives no formula -- these are the derivatives of Eq. 5 on Prop. 2's form).
 // With P = phi(K), R = phi(Q), S = P^T V, z = P^T 1, den = R z + eps, out = R S / den and g = dL/d out:
 //     u_i  = S g_i                      (d-vector per token)

@@ -1,4 +1,4 @@
-// The mixer fed straight from the two-branch MLPs f', g' of Sec. 4.1 (fp16 / bf16, token-major rows):
+// The mixer fed straight from the two-branch MLPs f', g' of Sec. 3.1 (Implementation Details) (fp16 / bf16, token-major rows):
 //   q = a_q + LeakyReLU(LayerNorm_C(t_q)),   k = a_k + LeakyReLU(LayerNorm_C(t_k)),   C = H d,
 // where a_* is the result of the linear branch and t_* the result of the second branch's Linear.  The sum,
 // the LayerNorm over all channels of a token and the activation happen inside the state-reduction and the

@@ -316,7 +316,7 @@ pack_state_wide(const float* __restrict__ state, unsigned char* __restrict__ pac
 // barrier.
 // The state arrives operand-ready from pack_state_wide: the prologue is a handful of coalesced loads.
 // MLP: the query is formed in that same pass over a wave's rows as  a + LeakyReLU(LayerNorm(t))  (the two-branch
-// f' of Sec. 4.1) from the tile of `a` in the ring, the tile of `t` in a second ring behind it (and behind the LO
+// f' of Sec. 3.1 (Implementation Details)) from the tile of `a` in the ring, the tile of `t` in a second ring behind it (and behind the LO
 // buffer), the rows' {rstd, -mean rstd} from an earlier kernel, which travel with each tile as one more 1 KiB
 // deposit (256 bytes used; every wave brings the same 32 pairs to the same place and reads its own rows'), and
 // the head's gamma, beta from a table in LDS.

@@ -245,9 +245,16 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     const int unit = p->gwaves / lf::kWavesPerWG;
     p->gsplits = per_group(env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * num_cu()) / unit, &share);
     p->gblk_reduce = block_tiles(share, "LINFUSION_GROUP_REDUCE_BLK", 2, 1);
-    p->gapply_wgs = per_group(env_int("LINFUSION_GROUP_APPLY_WGS", 2 * num_cu()) / unit, &share);
-    // measured best: one workgroup of eight waves (two of four) per CU, tiles dealt out one at a time so
-    // that the whole chip sweeps one narrow window of memory
+    // up to a few hundred MB one workgroup of eight waves (two of four) per CU; large problems as many short-lived
+    // workgroups of about `kGroupTilesPerWG` tiles each (the hardware deals them out in order: one narrow moving
+    // window of memory, as for the per-head apply; 2 M tokens of 8 x 40: 472 -> 445 us); tiles dealt out one at
+    // a time
+    constexpr long long kGroupTilesPerWG = 8;
+    long long gwant = 2 * num_cu();
+    if (!one_round && p->groups * p->n_tiles / kGroupTilesPerWG * unit > gwant)
+      gwant = p->groups * p->n_tiles / kGroupTilesPerWG * unit;
+    if (gwant > (1 << 24)) gwant = 1 << 24;
+    p->gapply_wgs = per_group(env_int("LINFUSION_GROUP_APPLY_WGS", (int)gwant) / unit, &share);
     p->gblk_apply = block_tiles(share, "LINFUSION_GROUP_APPLY_BLK", p->gwaves == 8 ? 1 : 2, 1);
   } else {
     p->gsplits = p->gapply_wgs = 0;

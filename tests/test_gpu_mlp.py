@@ -1,4 +1,4 @@
-"""GPU parity of linfusion_attn_fwd_mlp (the mixer fed by the two-branch MLPs f', g' of Sec. 4.1) against the
+"""GPU parity of linfusion_attn_fwd_mlp (the mixer fed by the two-branch MLPs f', g' of Sec. 3.1 (Implementation Details)) against the
 fp64 oracle's module_mixer on the same stored inputs, element by element."""
 import numpy as np
 import pytest
@@ -87,7 +87,7 @@ def test_feature_maps_and_unnormalized(H, d, dtype, fm, unnorm):
 
 @pytest.mark.parametrize("H,d,dtype", [(8, 40, "f16"), (8, 48, "bf16"), (4, 80, "f16")])
 def test_zero_start_is_the_plain_mixer(H, d, dtype):
-    """Sec. 4.1: with the second branch at its initial value zero, q and k are the linear-branch results."""
+    """Sec. 3.1 (Implementation Details): with the second branch at its initial value zero, q and k are the linear-branch results."""
     B, N = 2, 1500
     ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=82, zero_start=True)
     out = _run(ins, H)

@@ -1,4 +1,4 @@
-"""Pins for the oracle's upstream part: the two-branch MLPs f', g' of Sec. 4.1 (a linear branch plus one
+"""Pins for the oracle's upstream part: the two-branch MLPs f', g' of Sec. 3.1 (Implementation Details) (a linear branch plus one
 Linear-LayerNorm-LeakyReLU block, results added) in front of the mixer.  CPU only."""
 import numpy as np
 import pytest
@@ -66,7 +66,7 @@ def test_leaky_relu_slope():
 
 
 def test_zero_start_reduces_the_module_to_the_plain_mixer():
-    """Sec. 4.1: the second branch starts at zero, so at initialisation q = X W_Q and k = X W_K exactly."""
+    """Sec. 3.1 (Implementation Details): the second branch starts at zero, so at initialisation q = X W_Q and k = X W_K exactly."""
     r = _rng(5)
     B, N, H, d = 2, 33, 4, 8
     C = H * d

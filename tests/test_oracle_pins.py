@@ -207,7 +207,7 @@ def test_non_causal_permutation_invariance():
 
 
 def test_token_tiling_invariance():
-    # the normalizer keeps the total impact the same at any number of tokens (Sec. 1 / 2.3)
+    # the normalizer keeps the total impact the same at any number of tokens (Sec. 1, Introduction; Sec. 2.3)
     rng = np.random.default_rng(6)
     q, k, v = rng.normal(size=(3, 17, 4))
     base = orc.attention_linear(q, k, v, 0, 0.0)
