@@ -173,6 +173,7 @@ def test_recorded_into_a_graph_replays_correctly(B, H, N, d, dtype):
         for dst, src in zip(dev, fresh):
             dst.copy_(src)
         out.fill_(float("nan"))
+        torch.cuda.synchronize()      # the program's own eager work is complete before the replay starts
         graph.replay()
         torch.cuda.synchronize()
         eager = torch.empty_like(out)
