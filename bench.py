@@ -166,6 +166,7 @@ def launch_floor(reps=200):
     return res
 
 
+PATH_NAMES = {0: "three kernels", 1: "single launch with barriers", 2: "replicated-state single launch"}
 PAPER_CONFIGS = ["sd15_256_f32", "sd15_512_f16", "sd21_768_f16", "sd21_768_f16_peaky", "sdxl_2048_A_bf16",
                  "sdxl_2048_B_bf16"]
 
@@ -213,7 +214,7 @@ def latency_rows(names, paths=(("auto", 0),), steps=200):
                 row[f"{pre}{mode}_tokens_per_s"] = round(B * N / us * 1e6)
                 row[f"{pre}{mode}_gbps"] = round(nbytes / us / 1e3, 1)
                 row[f"{pre}{mode}_frac_of_peak"] = round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)
-            row[("" if label == "auto" else label + "_") + "path"] = "single launch" if plan["path"] == 1 else "three kernels"
+            row[("" if label == "auto" else label + "_") + "path"] = PATH_NAMES[plan["path"]]
         rows.append(row)
         del sets
     return rows
@@ -226,7 +227,7 @@ def latency_table(steps=200):
     from paper_2409_02097_amd import workloads as wl
     names = [n for n, c in wl.CONFIGS.items()
              if n != DEFAULT_WORKLOAD and wl.algorithmic_bytes(c["B"], c["H"], c["N"], c["d"], c["dtype"]) <= 512e6]
-    for row in latency_rows(names, (("auto", 0), ("split", lf.FLAG_FORCE_SPLIT), ("fused", lf.FLAG_FORCE_FUSED)), steps):
+    for row in latency_rows(names, (("auto", 0), ("split", lf.FLAG_FORCE_SPLIT), ("fused", lf.FLAG_FORCE_FUSED), ("solo", lf.FLAG_FORCE_SOLO)), steps):
         print(json.dumps(row), file=sys.stderr, flush=True)
 
 
@@ -553,7 +554,7 @@ def main():
                      "cold_us": round(ms_per_step * 1e3, 2), "cold_tokens_per_s": round(tokens_per_s),
                      "cold_gbps": round(alg_bytes / (dt / args.steps) / 1e9, 1),
                      "cold_frac_of_peak": round(alg_bytes / (dt / args.steps) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "path": "single launch" if plan["path"] == 1 else "three kernels",
+                     "path": PATH_NAMES[plan["path"]],
                      "note": "5.4 GB per call: every call streams from HBM"})
         result["configs"] = rows
     if args.ceilings:

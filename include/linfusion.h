@@ -60,6 +60,7 @@ extern "C" {
 #define LINFUSION_FLAG_UNNORMALIZED 1u /* out_i = phi(q_i) S, the un-normalized arm of Tab. 2 */
 #define LINFUSION_FLAG_FORCE_SPLIT 2u  /* always take the three-kernel split-N path */
 #define LINFUSION_FLAG_FORCE_FUSED 4u  /* take the single-launch path whenever the shape allows it */
+#define LINFUSION_FLAG_FORCE_SOLO 8u   /* take the replicated-state launch whenever the shape allows it */
 
 #define LINFUSION_OK 0
 #define LINFUSION_ERR_INVALID (-1)     /* NULL pointer, B/H/N/d <= 0, eps < 0 or NaN, bad flags */
@@ -75,7 +76,13 @@ extern "C" {
  * General entry point: the whole hot path (feature map -> split-N state reduction ->
  * deterministic combine -> apply + normalize) for one [B, H, N, d] problem.
  *
- * Two launch shapes compute it.  The split path enqueues three kernels (state reduction,
+ * Three launch shapes compute it.  The replicated-state launch is one kernel without any exchange between
+ * workgroups: every workgroup reduces the whole state of its head by itself and applies it to its share
+ * of the queries; no workspace is touched, nothing can time out, and it may be captured into a HIP graph.
+ * It is taken only when LINFUSION_FLAG_FORCE_SOLO asks for it (d <= 64): on MI355X the repeated reduction,
+ * bound by one compute unit's vector rate, made it slower than three launches at every measured size
+ * (36 against 22 us at 4096 tokens of 8 x 40 fp16; a tie below 256 tokens).
+ * The split path enqueues three kernels (state reduction,
  * combine, apply).  The single-launch path runs the same three phases in one kernel whose
  * workgroups meet at two per-head barriers; it is chosen automatically where it measured
  * faster (16-bit heads of 56 or 64 channels with about 128 MB to 1 GB of tensor traffic, where
@@ -433,15 +440,16 @@ void linfusion_set_tuning(int on);
 /*
  * Introspection for benchmarks and tests (host only, no device work): the launch plan the
  * forward call will use for this shape.  plan[0] = path (0 = split-N three-kernel path,
- * 1 = single launch), plan[1] = state-reduction workgroups per head, plan[2] = apply
- * workgroups per head (on the single-launch path both are its workgroups per head),
+ * 1 = single launch with barriers, 2 = replicated-state launch), plan[1] = state-reduction workgroups per
+ * head, plan[2] = apply workgroups per head (on the single-launch paths both are its workgroups per head),
  * plan[3] = tokens per tile.  Returns LINFUSION_OK or an error code.
  */
 int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned flags, int plan[4]);
 
 /*
  * Name of the kernel that will run the apply step for this shape on contiguous tensors ("apply16_dma",
- * "apply16_packed", "apply32", "apply16_wide", or "fused16" / "fused32" when the single launch is chosen);
+ * "apply16_packed", "apply32", "apply16_wide", or "fused16" / "fused32" / "solo16" / "solo32" when a single
+ * launch is chosen);
  * an empty string for rejected arguments.  Static storage.  For benchmarks and profile summaries.
  */
 const char* linfusion_attn_apply_kernel(int B, int H, long long N, int d, int dtype, unsigned flags);

@@ -14,7 +14,7 @@ _LIB_NAME = "liblinfusion.so"
 
 DTYPE_F32, DTYPE_F16, DTYPE_BF16 = 0, 1, 2
 PHI_ELU_PLUS_ONE, PHI_RELU, PHI_IDENTITY = 0, 1, 2
-FLAG_NONE, FLAG_UNNORMALIZED, FLAG_FORCE_SPLIT, FLAG_FORCE_FUSED = 0, 1, 2, 4
+FLAG_NONE, FLAG_UNNORMALIZED, FLAG_FORCE_SPLIT, FLAG_FORCE_FUSED, FLAG_FORCE_SOLO = 0, 1, 2, 4, 8
 
 _lib = None
 

@@ -59,7 +59,7 @@ template <int D, int DV = D> struct ApplyDmaCfg {
   static constexpr int kSlotBytes = (kNL > kNLO ? kNL : kNLO) * 1024;   // whole 1 KiB deposits; >= either tile's bytes
   static constexpr int kRing = 3;
   static constexpr int kStageOffset = (kRing - 1) * kWavesPerWG * kSlotBytes;
-  static constexpr int kStageBytes = (D * DV + D) * 4 + 64;
+  static constexpr int kStageBytes = (D * DV + D) * 4 + 256;   // the state and two maxima per wave
   // XOR swizzle of the chunk position with the row index where rows are 64 or 128 bytes
   static constexpr int kSwzMask = (kCPR == 8) ? 7 : (kCPR == 4 ? 3 : 0);
   static constexpr int kSwzShift = (kCPR == 4) ? 2 : 0;
@@ -347,7 +347,8 @@ struct ApplyDma {
   }
 
   // Whole workgroup: stages one head's state in LDS; the waves with `keep` build their operands from it.
-  template <bool COHERENT = false>
+  // STAGED: the state already lies in the staging area (the workgroup computed it itself); `state` is not read.
+  template <bool COHERENT = false, bool STAGED = false>
   LF_DEV void load_state(const float* state, float eps, bool keep) {
     // ---- prologue: state -> LDS, maxima, power-of-two scales, A fragments -------------------------
     float* st = reinterpret_cast<float*>(smem + kStageOffset);
@@ -356,13 +357,15 @@ struct ApplyDma {
     static_assert(NE % 4 == 0 && (D * DV) % 4 == 0, "the state is moved four floats at a time");
     for (int e = threadIdx.x; e < NE / 4; e += NT) {
       f32x4 x;
-      if constexpr (COHERENT) {
+      if constexpr (STAGED) {
+        x = reinterpret_cast<const f32x4*>(st)[e];
+      } else if constexpr (COHERENT) {
         x = f32x4{ld_agent(state + 4 * e), ld_agent(state + 4 * e + 1), ld_agent(state + 4 * e + 2),
                   ld_agent(state + 4 * e + 3)};
       } else {
         x = reinterpret_cast<const f32x4*>(state)[e];
       }
-      reinterpret_cast<f32x4*>(st)[e] = x;
+      if constexpr (!STAGED) reinterpret_cast<f32x4*>(st)[e] = x;
       const float m4 = fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3])));
       if (e < D * DV / 4) mS = fmaxf(mS, m4); else mz = fmaxf(mz, m4);
     }

@@ -21,7 +21,7 @@ template <int D> struct Shape32 {
   static constexpr int kMT = (kQuarter + 1 + 3) / 4;        // 16-row output tiles incl. normalizer row
 };
 
-template <int D> constexpr int reduce32_lds_bytes() { return 2 * (D * D + D) * 4; }
+template <int D> constexpr int reduce32_lds_bytes(int waves = kWavesPerWG) { return reduce_copies(waves, D) * (D * D + D) * 4; }
 
 LF_DEV f32x4 mfma_16x16x4(float a, float b, f32x4 c) { return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0); }
 
@@ -29,10 +29,10 @@ LF_DEV f32x4 mfma_16x16x4(float a, float b, f32x4 c) { return __builtin_amdgcn_m
 // Lane (m = lane % 16, kq = lane / 16) holds channels 4m..4m+3 of token 4u + kq of the tile;
 // element i of its K chunk (after phi) is the A operand and element j of its V chunk the B
 // operand of product (i, j), whose accumulator tile is S[4*row + i][4*col + j].  z is summed
-// on the vector ALU.  `smem`: reduce32_lds_bytes<D>() bytes; `dst`: this workgroup's partial;
-// `Kh`, `Vh`: first token row of this head; `rs`: row stride in 16-byte units.
+// on the vector ALU.  `smem`: reduce32_lds_bytes<D>(WAVES) bytes; `dst`: this workgroup's partial;
+// `Kh`, `Vh`: first token row of this head; `rs`: row stride in 16-byte units.  WAVES, TO_LDS: as reduce16_phase.
 // ------------------------------------------------------------------------------------------
-template <int D, int FM>
+template <int D, int FM, int WAVES = kWavesPerWG, bool TO_LDS = false>
 LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict__ Vh, int rs,
                            float* __restrict__ dst, long long N, int tiles_per_block, int split, int nsplit,
                            unsigned char* smem) {
@@ -45,7 +45,7 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict
   const bool lane_on = m < CH;
 
   const long long n_tiles = (N + kTile32 - 1) / kTile32;
-  TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
+  TileIter it(split, nsplit, wave, tiles_per_block, n_tiles, WAVES);
   f32x4 acc[4][4];
   float zacc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -61,8 +61,13 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict
       const long long t = tile * kTile32 + 4 * u + kq;
       okr[u] = lane_on && t < N;
       if (okr[u]) {
-        kr[u] = __builtin_nontemporal_load(Kh + t * rs + m);
-        vr[u] = __builtin_nontemporal_load(Vh + t * rs + m);
+        if constexpr (TO_LDS) {      // every workgroup of the head reads these rows: keep them in the L2
+          kr[u] = Kh[t * rs + m];
+          vr[u] = Vh[t * rs + m];
+        } else {
+          kr[u] = __builtin_nontemporal_load(Kh + t * rs + m);
+          vr[u] = __builtin_nontemporal_load(Vh + t * rs + m);
+        }
       } else {
         kr[u] = f32x4{0, 0, 0, 0};
         vr[u] = f32x4{0, 0, 0, 0};
@@ -92,14 +97,16 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict
     }
   }
 
-  // cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3): waves 0 and 1 park their accumulators in
-  // two LDS copies, waves 2 and 3 add theirs on top (inside a wave the four token groups kq = 0..3 add
-  // their z in order), then all threads add the two copies and write the partial
+  // cross-wave sum in a fixed order: wave w adds into LDS copy w % COPIES in round w / COPIES (round 0 stores;
+  // inside a wave the four token groups kq = 0..3 add their z in order), then all threads add the copies in order
+  // and write the partial.  Four waves, two copies: (w0 + w2) + (w1 + w3).
   constexpr int NE = D * D + D;
-  float* mine = red + (wave & 1) * NE;
+  constexpr int COPIES = reduce_copies(WAVES, D);
+  static_assert(WAVES % COPIES == 0, "whole rounds");
+  float* mine = red + (wave % COPIES) * NE;
 #pragma unroll
-  for (int round = 0; round < 2; ++round) {
-    if ((wave >> 1) == round) {
+  for (int round = 0; round < WAVES / COPIES; ++round) {
+    if (wave / COPIES == round) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -129,7 +136,12 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict
     }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < NE; i += kThreads) st_agent(dst + i, red[i] + red[NE + i]);
+  for (int i = threadIdx.x; i < NE; i += 64 * WAVES) {
+    float v = red[i] + red[NE + i];
+    if constexpr (COPIES == 4) v = (v + red[2 * NE + i]) + red[3 * NE + i];
+    if constexpr (TO_LDS) dst[i] = v;
+    else st_agent(dst + i, v);
+  }
 }
 
 // grid = (splits, B*H), block = 256
@@ -169,11 +181,12 @@ template <int D> struct Apply32Cfg {
   static_assert(kCH % 2 == 0, "d is a multiple of 8");
   static __device__ __forceinline__ int rot(int r) { return ((r * kG) >> 4) & (kG - 1); }
 };
-template <int D> constexpr int apply32_lds_bytes() { return Apply32Cfg<D>::kRing * kWavesPerWG * Apply32Cfg<D>::kSlotBytes; }
+template <int D> constexpr int apply32_lds_bytes(int waves = kWavesPerWG) { return Apply32Cfg<D>::kRing * waves * Apply32Cfg<D>::kSlotBytes; }
 
 template <int N> LF_DEV void wait_vmcnt32() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int D, int FM, bool NORM>
+// WPW: waves per workgroup (each wave streams on its own)
+template <int D, int FM, bool NORM, int WPW = kWavesPerWG>
 struct Apply32Dma {
   using Sh = Shape32<D>;
   using Cfg = Apply32Cfg<D>;
@@ -195,7 +208,7 @@ struct Apply32Dma {
                     int nwg, unsigned char* smem_)
       : Qh(Qh_), Oh(Oh_), N(N_), smem(smem_), rs_q(rs_q_), rs_o(rs_o_), lane(threadIdx.x & 63),
         wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
-        it(wg, nwg, wave, tiles_per_block, (N_ + kTile32 - 1) / kTile32), ahead(it) {
+        it(wg, nwg, wave, tiles_per_block, (N_ + kTile32 - 1) / kTile32, WPW), ahead(it) {
     tok = lane & 15;
     kq = lane >> 4;
     row_byte = tok * CH * 16;
@@ -215,7 +228,7 @@ struct Apply32Dma {
     }
   }
 
-  LF_DEV unsigned char* slot_ptr(int slot) const { return smem + (slot * kWavesPerWG + wave) * Cfg::kSlotBytes; }
+  LF_DEV unsigned char* slot_ptr(int slot) const { return smem + (slot * WPW + wave) * Cfg::kSlotBytes; }
   LF_DEV unsigned char* chunk_ptr(int slot, int chunk) const {
     int x = chunk + trot;
     if (x >= CH) x -= CH;

@@ -31,19 +31,25 @@ template <int D> struct Reduce16Cfg {
   static constexpr int kNL = (kChunks + 63) / 64;              // loads per lane per tensor
 };
 
+// copies of the accumulators in the cross-wave sum: two for the four waves of the separate kernels; workgroups of
+// more waves (the replicated-state kernel) take four where they fit below the apply phase's staging area
+constexpr int reduce_copies(int waves, int d) { return (waves > 4 && d <= 48) ? 4 : 2; }
+
 template <typename T, int D>
-constexpr int reduce16_lds_bytes() {
-  // per wave: NSplit tiles of phi(K) + one of V; reused by the cross-wave reduction (two copies of the
-  // accumulators)
-  int tiles = (NSplit<T>::value + 1) * Reduce16Cfg<D>::kTileElems * 2 * kWavesPerWG;
-  int red = 2 * (D * D + D) * 4;
+constexpr int reduce16_lds_bytes(int waves = kWavesPerWG) {
+  // per wave: NSplit tiles of phi(K) + one of V; reused by the cross-wave reduction (copies of the accumulators)
+  int tiles = (NSplit<T>::value + 1) * Reduce16Cfg<D>::kTileElems * 2 * waves;
+  int red = reduce_copies(waves, D) * (D * D + D) * 4;
   return tiles > red ? tiles : red;
 }
 
-// `dst`: where this workgroup's partial goes ([D*D + D] floats).  `smem`: reduce16_lds_bytes<T,D>()
+// `dst`: where this workgroup's partial goes ([D*D + D] floats).  `smem`: reduce16_lds_bytes<T,D>(WAVES)
 // bytes of LDS.  Ends with every thread having written its share of `dst` (no trailing barrier).
 // `Kh`, `Vh`: first token row of this head; `rs`: row stride in 16-byte units.
-template <typename T, int D, int FM>
+// WAVES: waves of the workgroup.  TO_LDS: `dst` lies in the workgroup's own LDS (beyond the first
+// reduce_copies(WAVES, D) * (D*D + D) floats of `smem`) and takes plain stores; else it is global memory that other
+// workgroups read.
+template <typename T, int D, int FM, int WAVES = kWavesPerWG, bool TO_LDS = false>
 LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict__ Vh, int rs,
                            float* __restrict__ dst, long long N, int tiles_per_block, int split, int nsplit,
                            unsigned char* smem) {
@@ -92,8 +98,13 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
       if (u * 64 + lane < Cfg::kChunks && trow[u] < lim) {
-        kr[u] = ld_stream(kp + goff[u]);
-        vr[u] = ld_stream(vp + goff[u]);
+        if constexpr (TO_LDS) {      // every workgroup of the head reads these rows: keep them in the L2
+          kr[u] = kp[goff[u]];
+          vr[u] = vp[goff[u]];
+        } else {
+          kr[u] = ld_stream(kp + goff[u]);
+          vr[u] = ld_stream(vp + goff[u]);
+        }
       } else {
         kr[u] = u32x4{LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value};   // phi maps it to 0
         vr[u] = u32x4{0, 0, 0, 0};
@@ -124,7 +135,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
 
   // the wave's whole stream: sums of phi(k) 2^kc (x) v into acc / accz; returns the token rows summed
   auto run_stream = [&](const float kc) {
-    TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
+    TileIter it(split, nsplit, wave, tiles_per_block, n_tiles, WAVES);
 #pragma unroll
     for (int a = 0; a < MT; ++a) {
       accz[a] = f32x4{0, 0, 0, 0};
@@ -219,7 +230,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
       // the stream's largest key
       f16x2 kmax2 = __builtin_bit_cast(f16x2, LowestBits<F16>::value);
       {
-        TileIter it(split, nsplit, wave, tiles_per_block, n_tiles);
+        TileIter it(split, nsplit, wave, tiles_per_block, n_tiles, WAVES);
         while (it.valid()) {
           (void)issue_loads(it.t);
 #pragma unroll
@@ -251,16 +262,18 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
     }
   }
 
-  // ---- cross-wave sum in a fixed order, (w0 + w2) + (w1 + w3): waves 0 and 1 park their accumulators
-  //      in two LDS copies ([D*D] S then [D] z), waves 2 and 3 add theirs on top, then all threads add
-  //      the two copies and write the partial --------------------------------------------------------
+  // ---- cross-wave sum in a fixed order: wave w adds into LDS copy w % COPIES ([D*D] S then [D] z) in round
+  //      w / COPIES (round 0 stores), so copy c = w_c + w_(c+COPIES) + ...; then all threads add the copies in
+  //      order and write the partial.  Four waves, two copies: (w0 + w2) + (w1 + w3). -----------------------
   __syncthreads();
   constexpr int NE = D * D + D;
+  constexpr int COPIES = reduce_copies(WAVES, D);
+  static_assert(WAVES % COPIES == 0, "whole rounds");
   float* red = reinterpret_cast<float*>(smem);
-  float* mine = red + (wave & 1) * NE;
+  float* mine = red + (wave % COPIES) * NE;
 #pragma unroll
-  for (int round = 0; round < 2; ++round) {
-    if ((wave >> 1) == round) {
+  for (int round = 0; round < WAVES / COPIES; ++round) {
+    if (wave / COPIES == round) {
 #pragma unroll
       for (int a = 0; a < MT; ++a) {
 #pragma unroll
@@ -287,7 +300,12 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
     }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < NE; i += kThreads) st_agent(dst + i, red[i] + red[NE + i]);
+  for (int i = threadIdx.x; i < NE; i += 64 * WAVES) {
+    float v = red[i] + red[NE + i];
+    if constexpr (COPIES == 4) v = (v + red[2 * NE + i]) + red[3 * NE + i];
+    if constexpr (TO_LDS) dst[i] = v;
+    else st_agent(dst + i, v);
+  }
 }
 
 template <typename T, int D, int FM>

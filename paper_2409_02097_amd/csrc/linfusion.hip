@@ -15,6 +15,7 @@
 #include <random>
 
 #include "lf_fused.hpp"
+#include "lf_solo_api.hpp"
 #include "lf_host_api.hpp"
 #include "lf_wide_api.hpp"
 
@@ -71,7 +72,8 @@ bool tuning_on() {
 
 // ---- launch plan (pure function of the shape and flags) ----------------------------------------
 struct Plan {
-  int path;             // 0 = split-N three-kernel path, 1 = fused single launch
+  int path;             // 0 = split-N three-kernel path, 1 = fused single launch, 2 = replicated-state launch
+  int solo_g;           // replicated-state launch: workgroups per head (0 = the shape cannot use it)
   int splits;           // split path: state-reduction workgroups per head
   int blk_reduce;       //   tiles per contiguous block of a reduction workgroup
   int apply_wgs;        //   apply workgroups per head
@@ -134,9 +136,13 @@ int apply_wgs_per_cu(int d, int dtype) {
 int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan* p, bool compact = false) {
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
   if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;   // grid.y limit
-  if (flags & ~(LINFUSION_FLAG_UNNORMALIZED | LINFUSION_FLAG_FORCE_SPLIT | LINFUSION_FLAG_FORCE_FUSED))
+  if (flags & ~(LINFUSION_FLAG_UNNORMALIZED | LINFUSION_FLAG_FORCE_SPLIT | LINFUSION_FLAG_FORCE_FUSED |
+                LINFUSION_FLAG_FORCE_SOLO))
     return LINFUSION_ERR_INVALID;
-  if ((flags & LINFUSION_FLAG_FORCE_SPLIT) && (flags & LINFUSION_FLAG_FORCE_FUSED)) return LINFUSION_ERR_INVALID;
+  {
+    const unsigned forced = flags & (LINFUSION_FLAG_FORCE_SPLIT | LINFUSION_FLAG_FORCE_FUSED | LINFUSION_FLAG_FORCE_SOLO);
+    if (forced & (forced - 1)) return LINFUSION_ERR_INVALID;   // at most one path may be forced
+  }
   if (dtype < 0 || dtype > 2) return LINFUSION_ERR_UNSUPPORTED;
   if (!supported_d(d, dtype)) return LINFUSION_ERR_UNSUPPORTED;
   if (N > (1LL << 40) / d) return LINFUSION_ERR_INVALID;
@@ -163,7 +169,8 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     p->apply_packed = false;
     p->apply_waves = lf::kWavesPerWG;
     p->path = 0;
-    if (flags & LINFUSION_FLAG_FORCE_FUSED) return LINFUSION_ERR_UNSUPPORTED;
+    p->solo_g = 0;
+    if (flags & (LINFUSION_FLAG_FORCE_FUSED | LINFUSION_FLAG_FORCE_SOLO)) return LINFUSION_ERR_UNSUPPORTED;
     p->state_floats = (size_t)d * d + d;
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     p->ws_partials = up((size_t)BH * p->splits * p->state_floats * sizeof(float));
@@ -268,8 +275,33 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   const double fused_max = (double)env_int("LINFUSION_FUSED_MAX_MB", 1024) * 1048576.0;
   const bool fused_pays = dtype != LINFUSION_DTYPE_F32 && d > 48 && d <= 64 && bytes >= fused_min && bytes <= fused_max;
   p->path = 0;
-  if (p->fsplits > 0 && !(flags & LINFUSION_FLAG_FORCE_SPLIT) && ((flags & LINFUSION_FLAG_FORCE_FUSED) || fused_pays))
+  if (p->fsplits > 0 && !(flags & (LINFUSION_FLAG_FORCE_SPLIT | LINFUSION_FLAG_FORCE_SOLO)) &&
+      ((flags & LINFUSION_FLAG_FORCE_FUSED) || fused_pays))
     p->path = 1;
+  // Replicated-state launch (lf_solo.hpp): one kernel, every workgroup reduces its head's whole state itself.
+  // Workgroups per head: one workgroup per CU, but no more than there are blocks of apply tiles.
+  p->solo_g = 0;
+  if (d <= 64 && !compact && BH <= 32768) {
+    const int waves = lfs::solo_waves(d, dtype);
+    long long g = num_cu() / BH;
+    const long long blocks = (p->n_tiles + waves - 1) / waves;
+    if (g > blocks) g = blocks;
+    if (g < 1) g = 1;
+    if (g * BH <= (1 << 20)) p->solo_g = (int)g;
+    // Measured on MI355X it never beat three launches: the repeated reduction runs on ONE compute unit per workgroup
+    // and is bound by that unit's vector rate (phi, conversions: about 0.6 us per 32-token tile and SIMD), so it costs
+    // 36 us at 4096 tokens of 8 x 40 fp16 (three kernels: 22 us), 51 us at 1024 fp32 tokens (16 us), and only ties
+    // below 256 tokens, where the host's call overhead hides everything.  It is therefore taken only when asked for
+    // (LINFUSION_FLAG_FORCE_SOLO; LINFUSION_SOLO_MAX_KB under the tuning switch): a launch that needs no workspace
+    // content, no barrier and no ticket, e.g. for capture into a graph of very small layers.
+    const double kv_head = 2.0 * (double)N * d * (double)esz;
+    const bool solo_pays = kv_head <= (double)env_int("LINFUSION_SOLO_MAX_KB", 0) * 1024.0 && BH <= num_cu() &&
+                           env_int("LINFUSION_SOLO_MAX_KB", 0) > 0;
+    if (p->solo_g > 0 && !(flags & (LINFUSION_FLAG_FORCE_SPLIT | LINFUSION_FLAG_FORCE_FUSED)) &&
+        ((flags & LINFUSION_FLAG_FORCE_SOLO) || solo_pays))
+      p->path = 2;
+  }
+  if ((flags & LINFUSION_FLAG_FORCE_SOLO) && p->path != 2) return LINFUSION_ERR_UNSUPPORTED;
   p->state_floats = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   int smax = p->splits > p->fsplits ? p->splits : p->fsplits;
@@ -581,6 +613,14 @@ int run32(const Args& a) {
 }
 
 int dispatch(int d, int dtype, const Args& a) {
+  if (a.p->path == 2 && a.out) {      // replicated-state single launch: no workspace, one kernel
+    if (a.ev) (void)hipEventRecord(a.ev[0], a.st);
+    const lfs::SoloArgs s{a.q, a.k, a.v, a.out, a.BH, a.N, d, dtype, a.fm, a.eps, a.unnorm, a.lq, a.lkv, a.lo,
+                          a.p->solo_g, a.st};
+    const int rc = lfs::run_solo(s);
+    if (a.ev) { (void)hipEventRecord(a.ev[1], a.st); (void)hipEventRecord(a.ev[2], a.st); (void)hipEventRecord(a.ev[3], a.st); }
+    return rc;
+  }
   if (is_wide(d)) {
     const Plan& p = *a.p;
     lfw::WideArgs w{a.q, a.k, a.v, a.out, (int)(a.BH / a.lkv.H), a.lkv.H, a.N, d, dtype, a.fm, a.eps, a.unnorm,
@@ -738,6 +778,9 @@ int fwd_impl(const void* q, const void* k, const void* v, void* out, int B, int 
                     (d * esz) % 128 != 0 && !(flags & LINFUSION_FLAG_FORCE_FUSED);
   const bool group_reduce = frag && heads_adjacent(lkv);
   const bool group_apply = frag && heads_adjacent(lo) && heads_adjacent(lq);
+  // (where the row-piece kernels are due -- large token-major tensors -- they go before the replicated-state launch,
+  // whose per-head accesses would touch the rows as fragments)
+  if (p.path == 2 && (group_reduce || group_apply) && !(flags & LINFUSION_FLAG_FORCE_SOLO)) p.path = 0;
   Args a{q, k, v, out, (long long)B * H, N, feature_map, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
          &p, (unsigned char*)workspace, nullptr, (hipStream_t)stream, ev,
          device_layout(lq, H, esz), device_layout(lkv, H, esz), device_layout(lo, H, esz), group_reduce, group_apply};
@@ -964,6 +1007,7 @@ const char* linfusion_attn_apply_kernel(int B, int H, long long N, int d, int dt
   Plan p;
   if (make_plan(B, H, N, d, dtype, flags, &p) != LINFUSION_OK) return "";
   if (is_wide(d)) return "apply16_wide";
+  if (p.path == 2) return dtype == LINFUSION_DTYPE_F32 ? "solo32" : "solo16";
   if (p.path == 1) return dtype == LINFUSION_DTYPE_F32 ? "fused32" : "fused16";
   if (dtype == LINFUSION_DTYPE_F32) return "apply32";
   return p.apply_packed ? "apply16_packed" : "apply16_dma";
@@ -975,8 +1019,8 @@ int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned fl
   int rc = make_plan(B, H, N, d, dtype, flags, &p);
   if (rc != LINFUSION_OK) return rc;
   plan[0] = p.path;
-  plan[1] = p.path == 1 ? p.fsplits : p.splits;
-  plan[2] = p.path == 1 ? p.fsplits : p.apply_wgs;
+  plan[1] = p.path == 2 ? p.solo_g : (p.path == 1 ? p.fsplits : p.splits);
+  plan[2] = p.path == 2 ? p.solo_g : (p.path == 1 ? p.fsplits : p.apply_wgs);
   plan[3] = dtype == LINFUSION_DTYPE_F32 ? lf::kTile32 : lf::kTile;
   return LINFUSION_OK;
 }

@@ -104,7 +104,7 @@ def test_plan_covers_every_token_tile(B, H, N, d, dtype):
     n_tiles = -(-N // tile)
     assert 1 <= plan["reduce_wgs_per_head"] <= n_tiles
     assert 1 <= plan["apply_wgs_per_head"] <= n_tiles
-    assert plan["path"] in (0, 1)
+    assert plan["path"] in (0, 1, 2)
 
 
 def _call(q=4096, k=1 << 20, v=2 << 20, out=3 << 20, B=1, H=2, N=64, d=40, dtype=1, fm=0, eps=1e-6, flags=0,

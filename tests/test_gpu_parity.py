@@ -36,7 +36,8 @@ SMALL = [
 ]
 
 
-PATHS = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED}
+PATHS = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED, "solo": lf.FLAG_FORCE_SOLO}
+PATH_CODE = {"split": 0, "fused": 1, "solo": 2}
 
 
 @pytest.mark.parametrize("path", list(PATHS))
@@ -44,7 +45,11 @@ PATHS = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED}
 def test_small_shapes_match_oracle(B, H, N, d, dtype, path):
     print(f"case B={B} H={H} N={N} d={d} {dtype} {path}", flush=True)
     q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=50, device="cpu")
-    assert lf.linfusion_attn_plan(B, H, N, d, wl.DTYPE_CODE[dtype], PATHS[path])["path"] == (path == "fused")
+    if path == "solo" and d > 64:
+        with pytest.raises(lf.LinFusionError):       # the replicated-state launch covers head widths up to 64
+            lf.linfusion_attn_plan(B, H, N, d, wl.DTYPE_CODE[dtype], PATHS[path])
+        return
+    assert lf.linfusion_attn_plan(B, H, N, d, wl.DTYPE_CODE[dtype], PATHS[path])["path"] == PATH_CODE[path]
     out = _run(q.cuda(), k.cuda(), v.cuda(), flags=PATHS[path])
     worst = parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"N={N} d={d} {dtype}")
     print(f"  worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
@@ -176,7 +181,8 @@ def test_owned_workspace_entry_points():
         out = torch.empty_like(q)
         fn(q, k, v, out, 0, 1e-6)
         torch.cuda.synchronize()
-        assert torch.equal(out.view(torch.uint8), _run(q, k, v).view(torch.uint8))
+        # (these entry points always take the three-kernel path)
+        assert torch.equal(out.view(torch.uint8), _run(q, k, v, flags=lf.FLAG_FORCE_SPLIT).view(torch.uint8))
     lf.linfusion_release()
 
 
@@ -269,7 +275,7 @@ def test_extreme_values_match_oracle(dtype, case, path):
     parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"{case} {dtype}")
 
 
-@pytest.mark.parametrize("path", ["split", "fused", "packed"])
+@pytest.mark.parametrize("path", ["split", "fused", "packed", "solo"])
 @pytest.mark.parametrize("d", [40, 64])
 @pytest.mark.parametrize("case", ["q-20", "q-12", "k-12", "k-20", "q-20_k-20", "some_rows_q-25", "some_tokens_k-25",
                                   "q-60000"])
@@ -295,7 +301,8 @@ def test_fp16_inputs_far_below_zero(case, d, path, monkeypatch, tuning):
     if case == "some_tokens_k-25":
         k[:, :, ::2] -= 25.0
     q, k, v = q.half(), k.half(), v.half()
-    flags = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED, "packed": lf.FLAG_FORCE_SPLIT}[path]
+    flags = {"split": lf.FLAG_FORCE_SPLIT, "fused": lf.FLAG_FORCE_FUSED, "packed": lf.FLAG_FORCE_SPLIT,
+             "solo": lf.FLAG_FORCE_SOLO}[path]
     monkeypatch.setenv("LINFUSION_APPLY_PACKED", "3" if path == "packed" else "2")
     # (exp(-60000) is zero in every arithmetic: the definition gives 0 / eps = 0 there, and nothing without eps)
     for eps in ((1e-6,) if case == "q-60000" else (1e-6, 0.0)):
@@ -305,6 +312,25 @@ def test_fp16_inputs_far_below_zero(case, d, path, monkeypatch, tuning):
     if case in ("q-12", "some_rows_q-25"):      # the un-normalized arm takes the row's factor out again
         out = _run(q.cuda(), k.cuda(), v.cuda(), 0, 1e-6, flags | lf.FLAG_UNNORMALIZED)
         parity.check_all(out, q, k, v, "f16", 0, 1e-6, False, f"{case} d={d} {path} unnormalized")
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype", [(2, 150, 70, 40, "f16"), (1, 3, 20000, 40, "f16"), (1, 2, 9000, 64, "bf16"),
+                                           (1, 2, 5000, 56, "f32"), (3, 100, 33, 16, "f32"), (1, 1, 3000, 48, "bf16")])
+def test_replicated_state_launch_on_other_shapes(B, H, N, d, dtype):
+    """More heads than compute units (one workgroup per head, several rounds), many tiles per workgroup, the other
+    feature maps and the un-normalized arm; the single launch needs no workspace content and repeats itself."""
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=72, device="cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    assert lf.linfusion_attn_plan(B, H, N, d, wl.DTYPE_CODE[dtype], lf.FLAG_FORCE_SOLO)["path"] == 2
+    out = _run(qd, kd, vd, flags=lf.FLAG_FORCE_SOLO)
+    parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"solo B={B} H={H} N={N} d={d} {dtype}")
+    again = _run(qd, kd, vd, flags=lf.FLAG_FORCE_SOLO)
+    assert torch.equal(out.view(torch.uint8), again.view(torch.uint8))
+    if H <= 3:
+        for fm, flags in ((1, 0), (2, 0), (0, lf.FLAG_UNNORMALIZED)):
+            qq, kk = (qd.abs(), kd.abs()) if fm == 2 else (qd, kd)
+            out = _run(qq, kk, vd, fm, 1e-6, flags | lf.FLAG_FORCE_SOLO)
+            parity.check_all(out, qq.cpu(), kk.cpu(), v, dtype, fm, 1e-6, not flags, f"solo fm={fm} flags={flags} {dtype}")
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
