@@ -448,7 +448,7 @@ int linfusion_attn_plan(int B, int H, long long N, int d, int dtype, unsigned fl
 
 /*
  * Name of the kernel that will run the apply step for this shape on contiguous tensors ("apply16_dma",
- * "apply16_packed", "apply32", "apply16_wide", or "fused16" / "fused32" / "solo16" / "solo32" when a single
+ * "apply16_packed", "apply32", "apply16_wide", "apply16_wave", or "fused16" / "fused32" / "solo16" / "solo32" when a single
  * launch is chosen);
  * an empty string for rejected arguments.  Static storage.  For benchmarks and profile summaries.
  */

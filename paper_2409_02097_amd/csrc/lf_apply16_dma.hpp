@@ -620,6 +620,11 @@ struct ApplyDma {
             x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
             x1 += fmaxf(y1, slope * y1);
           }
+          if constexpr (NS == 1 && !MLP) {
+            const uint32_t r = shift ? phi_pack2_scaled<T, FM>(raw[w], qc) : phi_pack2<T, FM>(raw[w]);
+            Bh[s][w] = ok ? r : 0u;
+            continue;
+          }
           float r0 = ok ? (shift ? phi_scaled<FM>(x0, qc) : phi<FM>(x0)) : 0.0f;
           float r1 = ok ? (shift ? phi_scaled<FM>(x1, qc) : phi<FM>(x1)) : 0.0f;
           if constexpr (NS == 1) {

@@ -88,6 +88,46 @@ template <> LF_DEV uint32_t pack2<BF16>(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
+// phi of a stored pair, rounded to the storage type again: the word a matrix-core operand takes; the _scaled form
+// is phi_scaled on both halves.  fp16 elu(x)+1 goes a shorter way to the same bits: x + 1 in packed fp16 arithmetic
+// (the exact sum rounded once, as the fp32 sum rounded to fp16 is: it is exact in fp32 wherever it is not 1 anyway),
+// the exponential through fp32 as in phi(), and the choice between them by the sign bit (both give 1 at +-0, and
+// callers scale by 2^c only rows or streams without a non-negative element; a NaN stays a NaN on either side) --
+// 6 + 2 instructions per pair instead of 11 + 2.
+template <typename T, int FM> struct PhiPack2 {
+  static LF_DEV uint32_t run(uint32_t w) {
+    float x0, x1;
+    unpack2<T>(w, x0, x1);
+    return pack2<T>(phi<FM>(x0), phi<FM>(x1));
+  }
+  static LF_DEV uint32_t run_scaled(uint32_t w, float c) {
+    float x0, x1;
+    unpack2<T>(w, x0, x1);
+    return pack2<T>(phi_scaled<FM>(x0, c), phi_scaled<FM>(x1, c));
+  }
+};
+template <> struct PhiPack2<F16, kPhiEluPlusOne> {
+  static LF_DEV uint32_t run_scaled(uint32_t w, float c) {
+    const float kLog2e = 1.44269504088896340736f;
+    const f16x2 x = __builtin_bit_cast(f16x2, w);
+    const f16x2 one = {(_Float16)1.0f, (_Float16)1.0f};
+    const uint32_t lin = __builtin_bit_cast(uint32_t, x + one);
+    // (written out: left to itself the compiler turns the mask into two compares and selects, and converts before
+    //  it multiplies)  t = fma(half, log2 e, c) in one rounding, as the fp32 fma of the converted half is
+    float t0, t1;
+    uint32_t neg;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel_hi:[1,0,0]" : "=v"(t0) : "v"(w), "v"(kLog2e), "v"(c));
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(t1) : "v"(w), "v"(kLog2e), "v"(c));
+    // 0xffff in every negative half (op_sel_hi: the upper half takes its shift count from the constant's lower half too)
+    asm("v_pk_ashrrev_i16 %0, 15, %1 op_sel_hi:[0,1]" : "=v"(neg) : "v"(w));
+    const uint32_t e = pack2<F16>(__builtin_amdgcn_exp2f(t0), __builtin_amdgcn_exp2f(t1));
+    return (e & neg) | (lin & ~neg);
+  }
+  static LF_DEV uint32_t run(uint32_t w) { return run_scaled(w, 0.0f); }
+};
+template <typename T, int FM> LF_DEV uint32_t phi_pack2(uint32_t w) { return PhiPack2<T, FM>::run(w); }
+template <typename T, int FM> LF_DEV uint32_t phi_pack2_scaled(uint32_t w, float c) { return PhiPack2<T, FM>::run_scaled(w, c); }
+
 // value of a packed pair after rounding, back in fp32 (for hi/lo operand splitting)
 template <typename T> LF_DEV void pack2_split(float lo, float hi, uint32_t& w_hi, uint32_t& w_lo) {
   w_hi = pack2<T>(lo, hi);

@@ -110,6 +110,10 @@ state_reduce16_qv(const u32x4* __restrict__ K, const u32x4* __restrict__ V, floa
         u32x4 ph, pl;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
+          if constexpr (NS == 1 && kPhiKillsLowest<FM>) {
+            ph[w] = phi_pack2<T, FM>(kr[u][w]);
+            continue;
+          }
           float x0, x1;
           unpack2<T>(kr[u][w], x0, x1);
           float p0 = phi<FM>(x0), p1 = phi<FM>(x1);

@@ -156,6 +156,10 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
           u32x4 ph, pl;
 #pragma unroll
           for (int w = 0; w < 4; ++w) {
+            if constexpr (NS == 1 && kPhiKillsLowest<FM>) {
+              ph[w] = kRescan ? phi_pack2_scaled<T, FM>(kr[u][w], kc) : phi_pack2<T, FM>(kr[u][w]);
+              continue;
+            }
             float x0, x1;
             unpack2<T>(kr[u][w], x0, x1);
             float p0 = kRescan ? phi_scaled<FM>(x0, kc) : phi<FM>(x0);
@@ -452,6 +456,10 @@ state_reduce16_rows(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
           u32x4 ph, pl;
 #pragma unroll
           for (int w = 0; w < 4; ++w) {
+            if constexpr (NS == 1 && kPhiKillsLowest<FM>) {
+              ph[w] = (kRescan && shifted) ? phi_pack2_scaled<T, FM>(kr[u][w], kcu[u]) : phi_pack2<T, FM>(kr[u][w]);
+              continue;
+            }
             float x0, x1;
             unpack2<T>(kr[u][w], x0, x1);
             float p0 = (kRescan && shifted) ? phi_scaled<FM>(x0, kcu[u]) : phi<FM>(x0);

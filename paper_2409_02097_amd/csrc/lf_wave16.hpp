@@ -1,0 +1,399 @@
+// Apply + normalize for head widths above 80 with one wave per tile (Eq. 5 applied to Prop. 2's state).
+//
+// The workgroup-shared apply of lf_wide16.hpp splits the output channels of every tile over the waves of a
+// workgroup: all waves read the whole tile, so two workgroup barriers per tile separate "tile carries phi" ->
+// "everyone holds its operands" -> "outputs are back", and with two workgroups per CU the barriers' bubbles
+// bound the kernel well below the memory rate.  Here a wave keeps the WHOLE operand-ready state of its head in
+// registers ((d + 2) x d 16-bit values: 220 registers at d = 160 fp16 -- one wave per SIMD, the 512-register file
+// of a lone wave is what makes it fit) and streams tiles of its own through a ring of its own in LDS, exactly
+// as the narrow per-head kernel does: copy in by LDS-DMA, phi in place, read the tile as matrix-core B operands,
+// multiply, write the outputs over the tile, store.  No barrier anywhere; a wave waits only for its own copies.
+//
+// Products: v_mfma_f32_16x16x32 with A = S'^T row blocks (16 output channels, or the two normalizer rows, by 32
+// contraction channels), B = phi(q) of 16 tokens.  Per tile and wave 2 token blocks x (d/16 + 1) row blocks x
+// d/32 steps (110 at d = 160, 162 of 176 rows useful).  Lane l of a product: token l % 16, contraction channels
+// 32 s + 8 (l / 16) .. + 7; afterwards it holds output channels 16 b + 4 (l / 16) .. + 3 of its token, four
+// neighbours = one 8-byte piece of the output row.
+//
+// LDS: slot (ring position) of wave w at (slot * 4 + w) * kSlotBytes; a tile lies there row after row, the
+// 16-byte chunks of row r swizzled (see ApplyWaveShape) so that token-per-lane accesses are bank-conflict free.
+// bf16 keeps the low halves of phi(q) (hi + lo operands) in one more slot per wave behind the ring.
+#pragma once
+#include "lf_wide16.hpp"
+
+namespace lf {
+
+template <int D> struct ApplyWaveShape {
+  static_assert(D % 32 == 0 && D > 64 && D <= 160, "one-wave-per-tile apply: head width a multiple of 32 in (64, 160]");
+  static constexpr int kCPR = D / 8;                  // 16-byte chunks per token row
+  static constexpr int kKS = D / 32;                  // contraction steps of 32 channels
+  static constexpr int kCB = D / 16;                  // 16-row output blocks that hold channels
+  static constexpr int kRB = kCB + 1;                 // ... and the block with the two normalizer rows
+  static constexpr int kNL = kTile * kCPR / 64;       // 1 KiB deposits per tile (copies / stores per wave and tile)
+  static constexpr int kSlotBytes = kNL * 1024;
+  static constexpr int kWaves = 4;
+  // Swizzle of the 16-byte chunks inside a token row: position p of row r holds chunk p ^ swz(r).  Token-per-lane
+  // accesses to one chunk index then hit sixteen different groups of four banks (row starts are 16 r dwords apart
+  // mod 64 where the row is not a multiple of 256 bytes: r % 4 picks the group of sixteen banks, (r / 4) % 4 the four
+  // inside it; rows of 256 bytes all start at bank 0, so r % 16 picks), while every aligned group of four lanes of a
+  // copy still reads one aligned 64-byte piece of memory (a rotation by single chunks would straddle two).
+  static_assert(kCPR % 4 == 0, "four chunks per contraction step; the swizzle permutes inside aligned groups of four");
+  static constexpr int kSwzMask = (kCPR % 16 == 0) ? 15 : 3;
+  static constexpr int kSwzShift = (kCPR % 16 == 0) ? 0 : 2;
+  static __device__ __forceinline__ int swz(int r) { return (r >> kSwzShift) & kSwzMask; }
+};
+
+// Ring slots per wave: the tile being worked on and two on their way (bf16: and the LO slot).
+template <typename T> constexpr int apply16_wave_ring() { return 3; }
+template <typename T, int D>
+constexpr int apply16_wave_lds_bytes() {
+  return ApplyWaveShape<D>::kWaves * (apply16_wave_ring<T>() + (NSplit<T>::value == 2 ? 1 : 0)) *
+         ApplyWaveShape<D>::kSlotBytes;
+}
+
+// The operand-ready state of one head for apply16_wave: {c1 = alpha_z / alpha_S, alpha_z} then
+// frag[level][b][s][lane], 16 bytes each.  Lane l of fragment (b, s), element j:  output row m = 16 b + l % 16,
+// contraction channel ch = 32 s + 8 (l / 16) + j;  m < d -> S'[ch][m] = alpha_S S[ch][m];  m == d -> z'[ch]
+// = alpha_z z[ch] rounded to 16 bits;  m == d + 1 -> what that rounding left;  else 0.  Level 1 (bf16 only) holds
+// what rounding S' to 16 bits left.
+template <typename T, int D> struct PackWave {
+  using Sw = ApplyWaveShape<D>;
+  static constexpr int kHeaderBytes = 256;
+  static constexpr int kFrags = NSplit<T>::value * Sw::kRB * Sw::kKS;   // per lane
+  static constexpr int kHeadBytes = kHeaderBytes + kFrags * 64 * 16;
+};
+
+// grid = (d / 32, heads), block = 256.  Every workgroup finds the maxima (power-of-two scales, as
+// pack_state_wide); workgroup s writes the fragments of contraction step s, wave w those of row blocks w, w + 4, ..
+template <typename T, int D>
+__global__ void __launch_bounds__(kThreads)
+pack_state_wave(const float* __restrict__ state, unsigned char* __restrict__ packed, int normalize) {
+  using Sw = ApplyWaveShape<D>;
+  constexpr int NS = NSplit<T>::value, KS = Sw::kKS, RB = Sw::kRB, NE = D * D + D;
+  __shared__ float redmax[2 * kWavesPerWG];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int s = blockIdx.x;
+  const long long bh = blockIdx.y;
+  const float* st = state + bh * NE;
+  unsigned char* out = packed + bh * PackWave<T, D>::kHeadBytes;
+
+  float mS = 0.0f, mz = 0.0f;
+  const f32x4* st4 = reinterpret_cast<const f32x4*>(st);
+  for (int e = tid; e < NE / 4; e += kThreads) {     // D*D and D are multiples of 4
+    const f32x4 x = st4[e];
+    const float m = fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3])));
+    if (e < D * D / 4) mS = fmaxf(mS, m); else mz = fmaxf(mz, m);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    mS = fmaxf(mS, __shfl_xor(mS, o));
+    mz = fmaxf(mz, __shfl_xor(mz, o));
+  }
+  if (lane == 0) { redmax[wave] = mS; redmax[kWavesPerWG + wave] = mz; }
+  __syncthreads();
+  mS = 0.0f; mz = 0.0f;
+#pragma unroll
+  for (int w = 0; w < kWavesPerWG; ++w) { mS = fmaxf(mS, redmax[w]); mz = fmaxf(mz, redmax[kWavesPerWG + w]); }
+  const float aS = pow2_scale_for(mS);
+  const float az = normalize ? pow2_scale_for(mz) : 1.0f;
+  if (s == 0 && tid == 0) {
+    float* scales = reinterpret_cast<float*>(out);
+    scales[0] = az / aS;
+    scales[1] = az;
+  }
+
+  u32x4* frag = reinterpret_cast<u32x4*>(out + PackWave<T, D>::kHeaderBytes);
+  const int g = lane >> 4;
+  for (int b = wave; b < RB; b += kWavesPerWG) {
+    const int m = 16 * b + (lane & 15);
+    u32x4 hi4, lo4;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      float hi2[2], lo2[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const int ch = 32 * s + 8 * g + 2 * w + q;
+        float x = 0.0f;
+        bool zrem = false;
+        if (m < D) x = st[ch * D + m] * aS;
+        else if (normalize && m == D) x = st[D * D + ch] * az;
+        else if (normalize && m == D + 1) { x = st[D * D + ch] * az; zrem = true; }
+        float r0, r1;
+        unpack2<T>(pack2<T>(x, 0.0f), r0, r1);   // x rounded once to 16 bits
+        hi2[q] = zrem ? x - r0 : x;
+        lo2[q] = (m < D) ? x - r0 : 0.0f;
+      }
+      hi4[w] = pack2<T>(hi2[0], hi2[1]);
+      lo4[w] = pack2<T>(lo2[0], lo2[1]);
+    }
+    frag[((0 * RB + b) * KS + s) * 64 + lane] = hi4;
+    if constexpr (NS == 2) frag[((1 * RB + b) * KS + s) * 64 + lane] = lo4;
+  }
+}
+
+// One wave's apply work on one head: construct, prefetch(), load_packed(), stream().
+template <typename T, int D, int FM, bool NORM>
+struct ApplyWave {
+  using Sw = ApplyWaveShape<D>;
+  static constexpr int NS = NSplit<T>::value;
+  static constexpr int CPR = Sw::kCPR, KS = Sw::kKS, RB = Sw::kRB, CB = Sw::kCB, NL = Sw::kNL;
+  static constexpr int R = apply16_wave_ring<T>();
+  static constexpr int W = Sw::kWaves;
+  static_assert(R == 3, "the wait counts below are written for a ring of three slots");
+  static_assert(4 * NL <= 63, "the vector-memory counter has six bits");
+
+  const u32x4* Qh;
+  u32x4* Oh;
+  long long N;
+  unsigned char* smem;
+  int rs_q, rs_o;
+  int lane, wave, g;
+  int trow[NL], qoff[NL], ooff[NL], soff[NL];
+  int rowb[2], x0[2];        // per token block: byte offset of this lane's token row in a slot, its swizzle
+  TileIter it, ahead;
+  u32x4 A[NS][RB][KS];
+  float c1, eps_s;
+
+  LF_DEV ApplyWave(const u32x4* Qh_, int rs_q_, u32x4* Oh_, int rs_o_, long long N_, int tiles_per_block, int wg,
+                   int nwg, unsigned char* smem_)
+      : Qh(Qh_), Oh(Oh_), N(N_), smem(smem_), rs_q(rs_q_), rs_o(rs_o_),
+        lane(threadIdx.x & 63), wave(__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)),
+        it(wg, nwg, wave, tiles_per_block, (N_ + kTile - 1) / kTile, W), ahead(it) {
+    g = lane >> 4;
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const int P = u * 64 + lane;             // position in the tile
+      const int r = P / CPR, pos = P % CPR;
+      const int c = pos ^ Sw::swz(r);          // copy side: position pos of row r receives chunk c
+      const int spos = pos ^ Sw::swz(r);       // store side: this lane sends chunk pos, found at spos
+      trow[u] = r;
+      qoff[u] = r * rs_q + c;
+      ooff[u] = r * rs_o + pos;
+      soff[u] = (r * CPR + spos) * 16;
+    }
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      const int r = 16 * tb + (lane & 15);
+      rowb[tb] = r * CPR * 16;
+      x0[tb] = Sw::swz(r);
+    }
+  }
+
+  LF_DEV unsigned char* slot_ptr(int slot) const { return smem + (slot * W + wave) * Sw::kSlotBytes; }
+  // where chunk `chunk` of this lane's token of block tb lies inside a slot
+  LF_DEV int chunk_off(int tb, int chunk) const {
+    return rowb[tb] + ((chunk ^ x0[tb]) << 4);
+  }
+
+  // always issues exactly NL vector memory instructions
+  LF_DEV void issue_copy(long long tile, int slot) {
+    long long rem = N - tile * kTile;
+    const int lim = rem < kTile ? (int)rem : kTile;
+    const u32x4* qp = Qh + tile * kTile * rs_q;
+    unsigned char* sl = slot_ptr(slot);
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const int c = trow[u] < lim ? qoff[u] : 0;   // rows past N re-read chunk 0; never stored
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(qp + c),
+                                       (LF_LDS void*)(sl + u * 1024), 16, 0, 2 /* nt */);
+    }
+  }
+
+  LF_DEV void prefetch() {
+#pragma unroll
+    for (int i = 0; i < R - 1; ++i) {
+      if (ahead.valid()) issue_copy(ahead.t, i);
+      ahead.next();
+    }
+  }
+
+  // `packed`: this head's operands as pack_state_wave wrote them
+  LF_DEV void load_packed(const unsigned char* packed, float eps) {
+    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + PackWave<T, D>::kHeaderBytes);
+#pragma unroll
+    for (int l = 0; l < NS; ++l)
+#pragma unroll
+      for (int b = 0; b < RB; ++b)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) A[l][b][s] = frag[((l * RB + b) * KS + s) * 64 + lane];
+    const float* scales = reinterpret_cast<const float*>(packed);
+    c1 = scales[0];
+    eps_s = eps * scales[1];
+  }
+
+  // phi on the tile in ring slot `slot` (it has landed), in place; bf16: low halves to the LO slot
+  LF_DEV void phi_pass(int slot) {
+    unsigned char* sl = slot_ptr(slot);
+    unsigned char* lo = slot_ptr(R);
+    // all reads first: a lone wave per SIMD has nobody to hide one LDS round trip per deposit behind
+    u32x4 raw[NL];
+#pragma unroll
+    for (int u = 0; u < NL; ++u) raw[u] = *reinterpret_cast<const u32x4*>(sl + u * 1024 + lane * 16);
+    __builtin_amdgcn_sched_barrier(0);   // (the scheduler would pull each read down to its use again)
+#pragma unroll
+    for (int u = 0; u < NL; ++u) {
+      const int at = u * 1024 + lane * 16;
+      u32x4 h4, l4;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        if constexpr (NS == 1) {
+          h4[w] = phi_pack2<T, FM>(raw[u][w]);
+        } else {
+          float x0_, x1_;
+          unpack2<T>(raw[u][w], x0_, x1_);
+          const float r0 = phi<FM>(x0_), r1 = phi<FM>(x1_);
+          uint32_t h, l;
+          pack2_split<T>(r0, r1, h, l);
+          h4[w] = h;
+          l4[w] = l;
+        }
+      }
+      *reinterpret_cast<u32x4*>(sl + at) = h4;
+      if constexpr (NS == 2) *reinterpret_cast<u32x4*>(lo + at) = l4;
+    }
+  }
+
+  // the finished tile in `slot` goes out; always NL vector memory instructions for a full tile (only the very
+  // last tile of a head can be ragged, and nothing is counted after it)
+  LF_DEV void store_tile(long long tile, int slot) {
+    const unsigned char* sl = slot_ptr(slot);
+    long long rem = N - tile * kTile;
+    const int lim = rem < kTile ? (int)rem : kTile;
+    u32x4* op = Oh + tile * kTile * rs_o;
+    u32x4 w[NL];
+#pragma unroll
+    for (int u = 0; u < NL; ++u) w[u] = *reinterpret_cast<const u32x4*>(sl + soff[u]);
+    if (lim == kTile) {   // (a branch per store would pull each read behind it, one LDS round trip each)
+#pragma unroll
+      for (int u = 0; u < NL; ++u) st_stream(op + ooff[u], w[u]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < NL; ++u)
+        if (trow[u] < lim) st_stream(op + ooff[u], w[u]);
+    }
+  }
+
+  // at most k * NL vector memory instructions outstanding
+  LF_DEV void wait_groups(int k) {
+    switch (k) {
+      case 0: wait_vmcnt<0>(); break;
+      case 1: wait_vmcnt<NL>(); break;
+      case 2: wait_vmcnt<2 * NL>(); break;
+      case 3: wait_vmcnt<3 * NL>(); break;
+      default: wait_vmcnt<4 * NL>(); break;
+    }
+  }
+
+  // this lane's B operands of token block tb of the tile in `slot`
+  LF_DEV void read_block(const unsigned char* sl, int slot, int tb, u32x4 (&Bh)[KS], u32x4 (&Bl)[NS == 2 ? KS : 1]) {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int o = chunk_off(tb, 4 * s + g);
+      Bh[s] = *reinterpret_cast<const u32x4*>(sl + o);
+      if constexpr (NS == 2) Bl[s] = *reinterpret_cast<const u32x4*>(sl + (R - slot) * W * Sw::kSlotBytes + o);
+    }
+  }
+
+  // multiply one block of 16 tokens and write its outputs over its rows of the tile at `sl`
+  LF_DEV void multiply_block(unsigned char* sl, int tb, const u32x4 (&Bh)[KS], const u32x4 (&Bl)[NS == 2 ? KS : 1]) {
+    f32x4 acc[RB];
+#pragma unroll
+    for (int b = 0; b < RB; ++b) acc[b] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+#pragma unroll
+      for (int b = 0; b < RB; ++b) {
+        acc[b] = mfma_16x16x32<T>(A[0][b][s], Bh[s], acc[b]);
+        if constexpr (NS == 2) {
+          acc[b] = mfma_16x16x32<T>(A[0][b][s], Bl[s], acc[b]);
+          if (b < CB) acc[b] = mfma_16x16x32<T>(A[1][b][s], Bh[s], acc[b]);
+        }
+      }
+    }
+    float scale = c1;
+    if constexpr (NORM) {
+      // rows d and d + 1 (the normalizer and what its rounding left) are rows 0 and 1 of the last block: lanes
+      // 0-15 hold them for their tokens
+      const float part = acc[RB - 1][0] + acc[RB - 1][1];
+      const float den = __shfl(part, lane & 15) + eps_s;
+      scale = c1 * __builtin_amdgcn_rcpf(den);
+    }
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+      const u32x2 w = {pack2<T>(acc[b][0] * scale, acc[b][1] * scale), pack2<T>(acc[b][2] * scale, acc[b][3] * scale)};
+      // channels 16 b + 4 g .. + 3: chunk 2 b + g / 2, its first or second half
+      *reinterpret_cast<u32x2*>(sl + chunk_off(tb, 2 * b + (g >> 1)) + 8 * (g & 1)) = w;
+    }
+  }
+
+  // The tile in `slot` (it carries phi) -> its outputs, in place.  All LDS reads of a stretch are issued before its
+  // first product: a lone wave per SIMD has nobody to hide an LDS round trip per contraction step behind.
+  LF_DEV void compute_tile(int slot) {
+    unsigned char* sl = slot_ptr(slot);
+    if constexpr (NS == 1) {
+      u32x4 B0[KS], B1[KS], none[1];
+      read_block(sl, slot, 0, B0, none);
+      read_block(sl, slot, 1, B1, none);   // block 0's outputs land in other rows
+      __builtin_amdgcn_sched_barrier(0);
+      multiply_block(sl, 0, B0, none);
+      multiply_block(sl, 1, B1, none);
+    } else {
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) {
+        u32x4 Bh[KS], Bl[KS];
+        read_block(sl, slot, tb, Bh, Bl);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply_block(sl, tb, Bh, Bl);
+      }
+    }
+  }
+
+  // Issue order per wave:  C0 C1 [state] | C2 K0 | S0 C3 K1 | S1 C4 K2 | ...  Before tile j is touched its copies
+  // must have landed: vector memory instructions issued after them are S(j-2), C(j+1) (previous round) and
+  // S(j-1), C(j+2) (this round), where they exist.
+  LF_DEV void stream() {
+    int slot = 0, prev_slot = 0, j = 0;
+    long long prev_tile = -1;
+    bool next_copied = false;   // C(j+1) exists
+    {
+      TileIter second = it;
+      second.next();
+      next_copied = second.valid();
+    }
+    while (it.valid()) {
+      const long long tile = it.t;
+      const bool have_prev = prev_tile >= 0;
+      if (have_prev) store_tile(prev_tile, prev_slot);
+      const bool copied = ahead.valid();
+      if (copied) issue_copy(ahead.t, have_prev ? prev_slot : R - 1);
+      wait_groups((j >= 2 ? 2 : j) + (next_copied ? 1 : 0) + (copied ? 1 : 0));
+      phi_pass(slot);
+      compute_tile(slot);
+      it.next();
+      ahead.next();
+      next_copied = copied;
+      prev_tile = tile;
+      prev_slot = slot;
+      slot = slot + 1 == R ? 0 : slot + 1;
+      ++j;
+    }
+    if (prev_tile >= 0) store_tile(prev_tile, prev_slot);
+  }
+};
+
+// grid = (wgs, heads), block = 256 (four waves that share nothing but the workgroup)
+template <typename T, int D, int FM, bool NORM>
+__global__ void __launch_bounds__(kThreads)
+apply16_wave(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, HeadSubset hs,
+             const unsigned char* __restrict__ packed, float eps, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const long long bh = hs.bh(blockIdx.y, lq.H);
+  ApplyWave<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
+                               gridDim.x, smem);
+  ap.prefetch();
+  ap.load_packed(packed + bh * PackWave<T, D>::kHeadBytes, eps);
+  ap.stream();
+}
+
+}  // namespace lf

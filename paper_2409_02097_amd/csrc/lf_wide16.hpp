@@ -140,6 +140,10 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
         u32x4 ph, pl;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
+          if constexpr (NS == 1 && kPhiKillsLowest<FM>) {
+            ph[w] = phi_pack2<T, FM>(kr[u][w]);
+            continue;
+          }
           float x0, x1;
           unpack2<T>(kr[u][w], x0, x1);
           float p0 = phi<FM>(x0), p1 = phi<FM>(x1);
@@ -494,6 +498,10 @@ struct ApplyWide {
           const float y1 = __builtin_fmaf(gg[2 * w + 1], __builtin_fmaf(t1, rc[0], rc[1]), bb[2 * w + 1]);
           x0 += fmaxf(y0, slope * y0);   // LeakyReLU for slopes up to one
           x1 += fmaxf(y1, slope * y1);
+        }
+        if constexpr (NS == 1 && !MLP) {
+          h4[w] = phi_pack2<T, FM>(raw[w]);
+          continue;
         }
         const float r0 = phi<FM>(x0), r1 = phi<FM>(x1);
         if constexpr (NS == 1) {

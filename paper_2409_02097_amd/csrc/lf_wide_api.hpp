@@ -19,13 +19,16 @@ struct WideArgs {
   float *partials, *state;    // [B*H][splits][d*d + d] and [B*H][d*d + d], fp32
   unsigned char* packed;      // wide_packed_bytes(d, dtype) per head: the state as apply operands
   int splits, blk_reduce, apply_wgs, blk_apply;
-  int apply_waves;            // waves per apply workgroup: 4 or 8
+  int apply_waves;            // waves per apply workgroup: 4 or 8 (apply16_wide)
+  bool wave_apply;            // apply16_wave (a wave per tile, the whole state in its registers) instead
   hipStream_t st;
   hipEvent_t* ev;             // null, or four events: before reduce, after it, after combine, after apply
 };
 
 // head widths the wide kernels are built for
 bool wide_supported(int d);
+// whether apply16_wave is built for this width and dtype (its state operands must fit one wave's registers)
+bool wave_apply_supported(int d, int dtype);
 // bytes per head of the operand-ready state between the pack and apply kernels (0 if unsupported)
 size_t wide_packed_bytes(int d, int dtype);
 // enqueues state reduction, combine and (if out) pack and apply; returns LINFUSION_OK or a LINFUSION_ERR_* code

@@ -84,6 +84,7 @@ struct Plan {
   // heads, one wave per head; workgroups per group
   int gwaves, groups, gsplits, gblk_reduce, gapply_wgs, gblk_apply;
   int apply_waves;      // waves per workgroup of the packed per-head apply (1, 2 or 4)
+  bool wave_apply;      // widths above 80: apply16_wave (a wave per tile) instead of apply16_wide
   bool apply_packed;    // per-head apply from operands prepared by pack_state16 (many short-lived workgroups)
   long long n_tiles;
   size_t state_floats;  // d*d + d: one partial, and one head's state
@@ -160,7 +161,20 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
       return (int)((p->n_tiles + t - 1) / t);
     };
     p->splits = per_head(env_int("LINFUSION_WIDE_REDUCE_WGS", 2 * num_cu()), 4, "LINFUSION_WIDE_REDUCE_BLK", &p->blk_reduce);
-    p->apply_wgs = per_head(env_int("LINFUSION_WIDE_APPLY_WGS", 2 * num_cu()), 1, "LINFUSION_WIDE_APPLY_BLK", &p->blk_apply);
+    // apply: a wave per tile with the head's whole state in its registers where that fits (one workgroup
+    // per CU, long-lived: its prologue loads the (d + 2) x d operands), else the workgroup-shared tiles
+    p->wave_apply = lfw::wave_apply_supported(d, dtype) && env_int("LINFUSION_WIDE_WAVE_APPLY", 1) == 1;   // 2: never
+    if (p->wave_apply) {
+      const long long max_a = (p->n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;   // every wave gets a tile
+      long long s = env_int("LINFUSION_WIDE_APPLY_WGS", num_cu()) / BH;
+      if (s > max_a) s = max_a;
+      if (s < 1) s = 1;
+      const long long t = (p->n_tiles + s - 1) / s;
+      p->apply_wgs = (int)((p->n_tiles + t - 1) / t);
+      p->blk_apply = block_tiles(t, "LINFUSION_WIDE_APPLY_BLK", lf::kWavesPerWG);
+    } else {
+      p->apply_wgs = per_head(env_int("LINFUSION_WIDE_APPLY_WGS", 2 * num_cu()), 1, "LINFUSION_WIDE_APPLY_BLK", &p->blk_apply);
+    }
     p->fsplits = 0;
     p->fblk_reduce = p->fblk_apply = 1;
     p->gwaves = lf::kWavesPerWG;
@@ -209,12 +223,17 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   const int packed_mode = env_int("LINFUSION_APPLY_PACKED", 1);   // 1 = by size, 2 = never, 3 = always
   p->apply_packed = dtype != LINFUSION_DTYPE_F32 && (packed_mode == 3 || (packed_mode == 1 && !one_round));
   p->apply_waves = lf::kWavesPerWG;
+  p->wave_apply = false;
   int apply_want = apply_dflt, blk_dflt = 8;
   if (p->apply_packed) {
     const int w = env_int("LINFUSION_APPLY_WAVES", lf::kWavesPerWG);
     p->apply_waves = (w == 1 || w == 2) ? w : lf::kWavesPerWG;
     const long long by_tiles = BH * p->n_tiles / (4 * p->apply_waves);   // four tiles per wave
-    if (!one_round && by_tiles > apply_want) apply_want = by_tiles > (1 << 24) ? (1 << 24) : (int)by_tiles;
+    // bf16 operands are twice as large (high and low halves), and at these widths the resident grid of
+    // eight long-lived workgroups per CU measured 9-14 % faster than the short-lived ones (d = 32 and 48
+    // measured 3-9 % slower that way, fp16 within 1 % either way)
+    const bool resident = dtype == LINFUSION_DTYPE_BF16 && (d == 40 || d >= 64);
+    if (!one_round && !resident && by_tiles > apply_want) apply_want = by_tiles > (1 << 24) ? (1 << 24) : (int)by_tiles;
     blk_dflt = p->apply_waves;                                           // one tile per wave and round
   }
   {
@@ -627,7 +646,8 @@ int dispatch(int d, int dtype, const Args& a) {
                     a.lq, a.lkv, a.lo, reinterpret_cast<float*>(a.ws),
                     a.state_out ? a.state_out : reinterpret_cast<float*>(a.ws + p.ws_partials),
                     a.ws + p.ws_partials + p.ws_state, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply,
-                    env_int("LINFUSION_WIDE_APPLY_WAVES", dtype == LINFUSION_DTYPE_BF16 ? 8 : 4) == 8 ? 8 : 4, a.st, a.ev};
+                    env_int("LINFUSION_WIDE_APPLY_WAVES", dtype == LINFUSION_DTYPE_BF16 ? 8 : 4) == 8 ? 8 : 4,
+                    p.wave_apply, a.st, a.ev};
     return lfw::run_wide(w);
   }
   switch (dtype) {
@@ -1006,7 +1026,7 @@ void linfusion_set_tuning(int on) { g_tuning.store(on ? 1 : 0, std::memory_order
 const char* linfusion_attn_apply_kernel(int B, int H, long long N, int d, int dtype, unsigned flags) {
   Plan p;
   if (make_plan(B, H, N, d, dtype, flags, &p) != LINFUSION_OK) return "";
-  if (is_wide(d)) return "apply16_wide";
+  if (is_wide(d)) return p.wave_apply ? "apply16_wave" : "apply16_wide";
   if (p.path == 2) return dtype == LINFUSION_DTYPE_F32 ? "solo32" : "solo16";
   if (p.path == 1) return dtype == LINFUSION_DTYPE_F32 ? "fused32" : "fused16";
   if (dtype == LINFUSION_DTYPE_F32) return "apply32";

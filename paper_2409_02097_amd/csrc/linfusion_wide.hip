@@ -2,7 +2,7 @@
 // (lf_wide16.hpp).  Kept apart from linfusion.hip so that the two compile side by side.
 #include "../../include/linfusion.h"
 
-#include "lf_wide16.hpp"
+#include "lf_wave16.hpp"
 #include "lf_host_api.hpp"
 #include "lf_wide_api.hpp"
 
@@ -11,6 +11,9 @@ namespace lfw {
 namespace {
 
 using lfh::allow_lds;
+
+// apply16_wave holds (d + 2) x d operands per level in registers: every fp16 width, bf16 up to 128
+template <typename T, int D> constexpr bool wave_ok() { return lf::NSplit<T>::value == 1 || D <= 128; }
 
 template <typename T, int D>
 int run(const WideArgs& a) {
@@ -53,14 +56,27 @@ int run(const WideArgs& a) {
     apply16_wide<T, D, FM, NORM, WW><<<g2, dim3(64 * WW), lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, \
                                                                       a.N, a.blk_apply);                     \
   }
-#define LFW_APPLY(FM, NORM) \
-  if (a.apply_waves == 8) LFW_APPLY_W(FM, NORM, 8) else LFW_APPLY_W(FM, NORM, 4)
+#define LFW_APPLY_WAVE(FM, NORM)                                                                             \
+  if constexpr (wave_ok<T, D>()) {                                                                          \
+    constexpr int lds2 = apply16_wave_lds_bytes<T, D>();                                                     \
+    if (!allow_lds(apply16_wave<T, D, FM, NORM>, lds2)) return LINFUSION_ERR_HIP;                            \
+    pack_state_wave<T, D><<<dim3(ApplyWaveShape<D>::kKS, (unsigned)BH), blk, 0, st>>>(a.state, a.packed,     \
+                                                                                     NORM ? 1 : 0);          \
+    apply16_wave<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, a.N,         \
+                                                        a.blk_apply);                                        \
+  } else {                                                                                                   \
+    return LINFUSION_ERR_UNSUPPORTED;                                                                        \
+  }
+#define LFW_APPLY(FM, NORM)                                        \
+  if (a.wave_apply) { LFW_APPLY_WAVE(FM, NORM) }                   \
+  else if (a.apply_waves == 8) LFW_APPLY_W(FM, NORM, 8) else LFW_APPLY_W(FM, NORM, 4)
     switch (a.fm) {
       case 0: if (a.unnorm) { LFW_APPLY(0, false) } else { LFW_APPLY(0, true) } break;
       case 1: if (a.unnorm) { LFW_APPLY(1, false) } else { LFW_APPLY(1, true) } break;
       default: if (a.unnorm) { LFW_APPLY(2, false) } else { LFW_APPLY(2, true) } break;
     }
 #undef LFW_APPLY
+#undef LFW_APPLY_WAVE
 #undef LFW_APPLY_W
   }
   if (a.ev) (void)hipEventRecord(a.ev[3], st);
@@ -71,11 +87,13 @@ int run(const WideArgs& a) {
 
 #define LFW_FOR_D(X) X(96) X(128) X(160)
 
-// room for either workgroup shape of the apply kernel
+// room for the operands of any of the apply kernels
 template <typename T, int D>
 constexpr size_t pack_bytes() {
-  return lf::PackWide<T, D, 4>::kHeadBytes > lf::PackWide<T, D, 8>::kHeadBytes ? lf::PackWide<T, D, 4>::kHeadBytes
-                                                                               : lf::PackWide<T, D, 8>::kHeadBytes;
+  size_t b = lf::PackWide<T, D, 4>::kHeadBytes > lf::PackWide<T, D, 8>::kHeadBytes ? lf::PackWide<T, D, 4>::kHeadBytes
+                                                                                   : lf::PackWide<T, D, 8>::kHeadBytes;
+  if (wave_ok<T, D>() && (size_t)lf::PackWave<T, D>::kHeadBytes > b) b = lf::PackWave<T, D>::kHeadBytes;
+  return b;
 }
 
 bool wide_supported(int d) {
@@ -84,6 +102,16 @@ bool wide_supported(int d) {
     LFW_FOR_D(X)
 #undef X
     return true;
+  }
+  return false;
+}
+
+bool wave_apply_supported(int d, int dtype) {
+  switch (d) {
+#define X(DD) \
+  case DD: return dtype == LINFUSION_DTYPE_F16 ? wave_ok<lf::F16, DD>() : wave_ok<lf::BF16, DD>();
+    LFW_FOR_D(X)
+#undef X
   }
   return false;
 }

@@ -41,6 +41,51 @@ def test_wide_heads_match_oracle(B, H, N, d, dtype):
     assert torch.equal(out.view(torch.uint8), out2.view(torch.uint8)), "not run-to-run identical"
 
 
+@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 3, 33, 160, "f16"), (1, 1, 4099, 160, "f16"), (2, 2, 333, 128, "f16"),
+                                           (1, 3, 1030, 128, "bf16"), (1, 2, 700, 96, "f16"), (1, 2, 65, 96, "bf16")])
+def test_workgroup_shared_apply_where_the_wave_apply_is_the_default(B, H, N, d, dtype, waves, monkeypatch, tuning):
+    """These shapes run apply16_wave (a wave per tile) by default; the workgroup-shared apply16_wide, which the widths
+    and dtypes whose operands exceed one wave's registers still use, is checked on them as well."""
+    print(f"shared-tile apply B={B} H={H} N={N} d={d} {dtype} waves={waves}", flush=True)
+    code = wl.DTYPE_CODE[dtype]
+    assert lf.linfusion_attn_apply_kernel(B, H, N, d, code) == "apply16_wave"
+    monkeypatch.setenv("LINFUSION_WIDE_WAVE_APPLY", "2")
+    monkeypatch.setenv("LINFUSION_WIDE_APPLY_WAVES", str(waves))
+    assert lf.linfusion_attn_apply_kernel(B, H, N, d, code) == "apply16_wide"
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=74, device="cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    out = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, 1e-6, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"shared-tile apply N={N} d={d} {dtype} waves={waves}")
+
+
+@pytest.mark.parametrize("wgs,blk", [(4, 4), (6, 8), (2, 64)])
+@pytest.mark.parametrize("N,d,dtype", [(20011, 160, "f16"), (9000, 128, "bf16"), (6000, 96, "bf16")])
+def test_wave_apply_with_many_tiles_per_wave(N, d, dtype, wgs, blk, monkeypatch, tuning):
+    """Few long-lived workgroups: every wave walks dozens of tiles through its ring (steady state of the copy /
+    store pipeline, block changes, a ragged last tile), which the small shapes never reach."""
+    B, H = 1, 2
+    print(f"wave apply N={N} d={d} {dtype} wgs={wgs} blk={blk}", flush=True)
+    monkeypatch.setenv("LINFUSION_WIDE_APPLY_WGS", str(wgs))
+    monkeypatch.setenv("LINFUSION_WIDE_APPLY_BLK", str(blk))
+    assert lf.linfusion_attn_apply_kernel(B, H, N, d, wl.DTYPE_CODE[dtype]) == "apply16_wave"
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=75, device="cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    out = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, 1e-6, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"wave apply N={N} d={d} {dtype} wgs={wgs} blk={blk}")
+
+
+def test_wave_apply_is_chosen_where_its_operands_fit():
+    names = {(d, t): lf.linfusion_attn_apply_kernel(1, 8, 4096, d, wl.DTYPE_CODE[t])
+             for d in (96, 128, 160) for t in ("f16", "bf16")}
+    assert names[(160, "bf16")] == "apply16_wide"
+    assert all(v == "apply16_wave" for key, v in names.items() if key != (160, "bf16")), names
+
+
 @pytest.mark.parametrize("d,dtype", [(80, "f16"), (160, "f16"), (80, "bf16"), (160, "bf16"), (96, "f16"), (128, "bf16")])
 def test_wide_heads_token_major_and_in_place(d, dtype):
     B, H, N = 2, 4, 700
