@@ -11,7 +11,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRCS = [os.path.join(HERE, "csrc", name) for name in ("linfusion.hip", "linfusion_wide.hip", "linfusion_bwd.hip", "linfusion_mlp.hip", "linfusion_mlph.hip", "linfusion_qv.hip", "linfusion_solo.hip", "lf_probe.hip")]
+SRCS = [os.path.join(HERE, "csrc", name) for name in ("linfusion.hip", "linfusion_wide.hip", "linfusion_bwd.hip", "linfusion_mlp.hip", "linfusion_mlph.hip", "linfusion_qv.hip", "linfusion_solo.hip", "linfusion_bwdw.hip", "lf_probe.hip")]
 LIB = os.path.join(HERE, "liblinfusion.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 

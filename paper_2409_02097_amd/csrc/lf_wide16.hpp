@@ -63,7 +63,7 @@ constexpr int apply16_wide_lds_bytes() {
 // ==========================================================================================
 template <typename T, int D, int FM>
 __global__ void __launch_bounds__(kThreads, 2)   // two workgroups per CU: one multiplies while the other loads
-state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout kv, HeadSubset hs,
+state_reduce16_wide(const u32x4* __restrict__ K, Layout kl, const u32x4* __restrict__ V, Layout vl, HeadSubset hs,
                     float* __restrict__ partials, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   using Sw = ShapeWide<D>;
@@ -72,14 +72,13 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const long long bh = hs.bh(blockIdx.y, kv.H);
-  const long long off = kv.slice(bh);
-  const u32x4* Kh = K + off;
-  const u32x4* Vh = V + off;
-  const int rs = kv.row;
+  const long long bh = hs.bh(blockIdx.y, kl.H);
+  const u32x4* Kh = K + kl.slice(bh);
+  const u32x4* Vh = V + vl.slice(bh);
+  const int rs = kl.row, rsv = vl.row;   // the two tensors may be laid out differently (the backward pass pairs q with a dense temporary)
   uint16_t* lds = reinterpret_cast<uint16_t*>(smem);
 
-  int goff[NL], loff[NL], trow[NL];
+  int goff[NL], goffv[NL], loff[NL], trow[NL];
 #pragma unroll
   for (int u = 0; u < NL; ++u) {
     const int p = u * kThreads + tid;
@@ -87,6 +86,7 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
     const bool in = p < Sw::kChunks;
     trow[u] = in ? r : kTile;              // kTile: never below the row limit
     goff[u] = r * rs + c;
+    goffv[u] = r * rsv + c;
     loff[u] = in ? r * RS + c * 8 : 0;
   }
   const int j16 = lane & 15, g4 = lane >> 4;
@@ -111,12 +111,12 @@ state_reduce16_wide(const u32x4* __restrict__ K, const u32x4* __restrict__ V, La
     long long rem = N - tile * kTile;
     int lim = rem < kTile ? (int)rem : kTile;
     const u32x4* kp = Kh + tile * kTile * rs;
-    const u32x4* vp = Vh + tile * kTile * rs;
+    const u32x4* vp = Vh + tile * kTile * rsv;
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
       if (trow[u] < lim) {
         kr[u] = ld_stream(kp + goff[u]);
-        vr[u] = ld_stream(vp + goff[u]);
+        vr[u] = ld_stream(vp + goffv[u]);
       } else {
         kr[u] = u32x4{LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value, LowestBits<T>::value};   // phi maps it to 0
         vr[u] = u32x4{0, 0, 0, 0};

@@ -132,6 +132,13 @@ int apply_wgs_per_cu(int d, int dtype) {
   return fused_wgs_per_cu(d, dtype);
 }
 
+// the wide kernels' share of a plan
+lfw::WidePlan wide_plan_of(const Plan& p, int dtype) {
+  return lfw::WidePlan{p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply,
+                       env_int("LINFUSION_WIDE_APPLY_WAVES", dtype == LINFUSION_DTYPE_BF16 ? 8 : 4) == 8 ? 8 : 4,
+                       p.wave_apply};
+}
+
 // `compact`: size the scratch for the three-kernel path alone (no room for the single launch's partials and
 // flags, which take most of the general workspace) -- the plan of the entry point with the fixed scratch array.
 int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan* p, bool compact = false) {
@@ -645,9 +652,7 @@ int dispatch(int d, int dtype, const Args& a) {
     lfw::WideArgs w{a.q, a.k, a.v, a.out, (int)(a.BH / a.lkv.H), a.lkv.H, a.N, d, dtype, a.fm, a.eps, a.unnorm,
                     a.lq, a.lkv, a.lo, reinterpret_cast<float*>(a.ws),
                     a.state_out ? a.state_out : reinterpret_cast<float*>(a.ws + p.ws_partials),
-                    a.ws + p.ws_partials + p.ws_state, p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply,
-                    env_int("LINFUSION_WIDE_APPLY_WAVES", dtype == LINFUSION_DTYPE_BF16 ? 8 : 4) == 8 ? 8 : 4,
-                    p.wave_apply, a.st, a.ev};
+                    a.ws + p.ws_partials + p.ws_state, wide_plan_of(p, dtype), a.st, a.ev};
     return lfw::run_wide(w);
   }
   switch (dtype) {
@@ -845,6 +850,18 @@ int static_scratch(void** ptr) {
 }
 
 }  // namespace
+
+namespace lfw {
+int wide_launch_plan(int B, int H, long long N, int d, int dtype, WidePlan* wp, size_t* partial_bytes) {
+  Plan p;
+  const int rc = make_plan(B, H, N, d, dtype, 0, &p);
+  if (rc != LINFUSION_OK) return rc;
+  if (!is_wide(d)) return LINFUSION_ERR_UNSUPPORTED;
+  *wp = wide_plan_of(p, dtype);
+  *partial_bytes = p.ws_partials;
+  return LINFUSION_OK;
+}
+}  // namespace lfw
 
 namespace lfh {
 int check_device() { return ::check_device(); }

@@ -7,6 +7,7 @@
 
 #include "lf_backward16.hpp"
 #include "lf_backward16_rows.hpp"
+#include "lf_bwdw_api.hpp"
 #include "lf_host_api.hpp"
 
 namespace {
@@ -16,6 +17,7 @@ struct BwdPlan {
   int splits, blk_reduce, apply_wgs, blk_apply;
   int gsplits, gblk_reduce;   // the state-gradient reduction's own launch shape
   int most;                   // partial states per head the workspace has room for
+  bool wide;                  // widths above 80: the composed pass of linfusion_bwdw.hip (its own workspace layout)
   size_t ne, ws_partials, ws_state, ws_scal, ws_total;
 };
 
@@ -25,8 +27,14 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
   if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;
   if (dtype != LINFUSION_DTYPE_F16 && dtype != LINFUSION_DTYPE_BF16) return LINFUSION_ERR_UNSUPPORTED;
-  if (!bwd_supported_d(d)) return LINFUSION_ERR_UNSUPPORTED;
+  p->wide = lfbw::bwd_wide_supported(d, dtype);
+  if (!bwd_supported_d(d) && !p->wide) return LINFUSION_ERR_UNSUPPORTED;
   if (N > (1LL << 40) / d) return LINFUSION_ERR_INVALID;
+  if (p->wide) {
+    p->ne = (size_t)d * d + d;
+    p->ws_total = lfbw::bwd_wide_workspace_bytes(B, H, N, d, dtype);
+    return p->ws_total ? LINFUSION_OK : LINFUSION_ERR_UNSUPPORTED;
+  }
   const long long BH = (long long)B * H;
   const long long n_tiles = (N + lf::kTile - 1) / lf::kTile;
   const long long max_s = (n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;
@@ -399,6 +407,12 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* dou
   rc = lfh::check_device();
   if (rc != LINFUSION_OK) return rc;
   auto lay = [&](const long long* s) { return lf::Layout{s[0] / 8, s[1] / 8, (int)(s[2] / 8), H}; };   // 16-byte units
+  if (p.wide) {
+    const lfbw::BwdWideArgs w{state, q, k, v, dout, dq, dk, dv, B, H, N, d, dtype, feature_map, eps,
+                              (flags & LINFUSION_FLAG_UNNORMALIZED) != 0, (unsigned char*)workspace,
+                              (hipStream_t)stream, lay(st5[0]), lay(st5[1]), lay(st5[2]), lay(st5[3]), lay(st5[4])};
+    return lfbw::run_bwd_wide(w);
+  }
   BwdArgs a{state, q, k, v, dout, dq, dk, dv, B, H, N, eps, (flags & LINFUSION_FLAG_UNNORMALIZED) != 0,
             &p, (unsigned char*)workspace, (hipStream_t)stream,
             lay(st5[0]), lay(st5[1]), lay(st5[2]), lay(st5[3]), lay(st5[4])};

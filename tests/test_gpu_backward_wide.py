@@ -1,0 +1,111 @@
+"""GPU parity of the backward pass at head widths above 80 (fp16; the d = 160 level of the SD-v1.5 UNet and the
+other widths of the wide kernels) against the fp64 oracle's gradients, rule of tests/parity.py: check_gradients."""
+import pytest
+import torch
+
+import paper_2409_02097_amd as lf
+from oracle import linattn_oracle as orc
+from paper_2409_02097_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def _ws(B, H, N, d):
+    n = lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, lf.DTYPE_F16)
+    assert n > 0
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    return ws
+
+
+def _run(q, k, v, g, fm=0, eps=1e-6, flags=0, state=None):
+    B, H, N, d = q.shape
+    outs = [torch.full_like(q, float("nan")).cuda() for _ in range(3)]
+    lf.linfusion_attn_bwd(q.cuda(), k.cuda(), v.cuda(), g.cuda(), *outs, fm, eps, flags, _ws(B, H, N, d), state=state)
+    torch.cuda.synchronize()
+    return outs
+
+
+def _check(outs, q, k, v, g, fm, eps, normalize, what):
+    qs, ks, vs, gs = (wl.stored_numpy(t) for t in (q, k, v, g))
+    B, H = qs.shape[:2]
+    worst = 0.0
+    for b in range(B):
+        for h in range(H):
+            w = [orc.widen(x[b, h], "f16") for x in (qs, ks, vs, gs)]
+            got = [parity.to_f64(t[b, h]) for t in outs]
+            worst = max(worst, parity.check_gradients(got, *w, "f16", fm, eps, normalize, f"{what} b={b} h={h}"))
+    return worst
+
+
+SHAPES = [
+    # SD-v1.5 at 512 px has (2, 8, 256 / 64, 160)
+    (2, 8, 256, 160), (2, 8, 64, 160), (1, 2, 1, 160), (1, 3, 33, 160), (1, 1, 4099, 160), (1, 2, 700, 96),
+    (2, 2, 333, 128), (1, 2, 1, 96), (1, 1, 20011, 160),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d", SHAPES)
+def test_wide_backward_matches_oracle(B, H, N, d):
+    print(f"wide bwd B={B} H={H} N={N} d={d}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=90, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 90777, "f16", "cpu")
+    outs = _run(q, k, v, g)
+    worst = _check(outs, q, k, v, g, 0, 1e-6, True, f"wide bwd N={N} d={d}")
+    print(f"  worst error / term scale {worst:.2e}", flush=True)
+    again = _run(q, k, v, g)
+    for a, b in zip(outs, again):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "not run-to-run identical"
+
+
+@pytest.mark.parametrize("fm,normalize", [(1, True), (2, True), (0, False), (1, False)])
+def test_wide_backward_other_feature_maps_and_unnormalized(fm, normalize):
+    B, H, N, d = 1, 2, 300, 160
+    q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=91, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 91777, "f16", "cpu")
+    if fm == 2:
+        q, k = q.abs(), k.abs()
+    if not normalize:
+        v, g = v * 0.02, g * 0.02      # keeps the un-normalized sums inside fp16's range
+    outs = _run(q, k, v, g, fm, 1e-6, 0 if normalize else lf.FLAG_UNNORMALIZED)
+    _check(outs, q, k, v, g, fm, 1e-6, normalize, f"wide bwd fm={fm} norm={normalize}")
+
+
+def test_wide_backward_with_the_forward_state_handed_in():
+    """A forward call leaves the fp32 state in its workspace; handing it to the backward call skips the first
+    reduction and must not change a bit."""
+    B, H, N, d = 2, 4, 515, 160
+    q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=92, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 92777, "f16", "cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    fws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, lf.DTYPE_F16), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(qd)
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, 1e-6, 0, fws)
+    off = lf.linfusion_attn_workspace_state_offset(B, H, N, d, lf.DTYPE_F16)
+    state = fws[off:off + B * H * (d * d + d) * 4].view(torch.float32)
+    with_state = _run(q, k, v, g, state=state)
+    without = _run(q, k, v, g)
+    for a, b in zip(with_state, without):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    _check(with_state, q, k, v, g, 0, 1e-6, True, "wide bwd with saved state")
+
+
+def test_wide_backward_token_major_views():
+    B, H, N, d = 2, 4, 300, 160
+    q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=93, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 93777, "f16", "cpu")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)   # [B, N, H, d] in memory
+    outs = [tm(torch.full_like(q, float("nan"))) for _ in range(3)]
+    lf.linfusion_attn_bwd_strided(tm(q), tm(k), tm(v), tm(g), *outs, 0, 1e-6, 0, _ws(B, H, N, d))
+    torch.cuda.synchronize()
+    dense = _run(q, k, v, g)
+    for a, b in zip(outs, dense):
+        assert torch.equal(a.contiguous().view(torch.int16), b.view(torch.int16)), "token-major differs from contiguous"
+
+
+def test_wide_backward_rejects_bf16():
+    x = torch.zeros(1, 1, 64, 160, dtype=torch.bfloat16, device="cuda")
+    assert lf.linfusion_attn_bwd_workspace_bytes(1, 1, 64, 160, lf.DTYPE_BF16) == 0
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    assert lf.linfusion_attn_bwd(x, x, x, x, *[torch.empty_like(x) for _ in range(3)], 0, 1e-6, 0, ws, check=False) == -2
