@@ -179,11 +179,11 @@ int linfusion_attn_fwd_profile(const void* q, const void* k, const void* v, void
  *                   row-major then z, as linfusion_attn_state writes it and as a forward call leaves it in
  *                   its workspace at linfusion_attn_workspace_state_offset(...)): saves the pass over k, v.
  *                   16-byte aligned; must not overlap dq, dk, dv or `workspace`.
- *   q, k, v, dout   DEVICE pointers, contiguous [B, H, N, d], fp16 or bf16 (LINFUSION_DTYPE_F32 ->
- *                   LINFUSION_ERR_UNSUPPORTED), d in {8, ..., 64 step 8, 80}; fp16 also d in {96, 128, 160}
- *                   (bf16 there -> LINFUSION_ERR_UNSUPPORTED).  At those widths the pass is composed of the
- *                   forward's kernels and 16-bit temporaries in the workspace (three tensors more than the
- *                   narrow widths need), sixteen launches: made for the few tokens these widths have in training.
+ *   q, k, v, dout   DEVICE pointers, contiguous [B, H, N, d].  fp16, bf16: d in {8, ..., 64 step 8, 80}; fp16 also
+ *                   d in {96, 128, 160} (bf16 there -> LINFUSION_ERR_UNSUPPORTED); fp32: d in {8, ..., 64 step 8}.
+ *                   fp16 above 80 and fp32 run a pass composed of the forward's kernels with three temporaries of
+ *                   the tensors' type in the workspace, sixteen launches: there so that every level of the UNet
+ *                   and every type has a gradient, not for speed.
  *   dq, dk, dv      DEVICE pointers, same shape and type; must not overlap any input or each other.
  *   flags           LINFUSION_FLAG_NONE or LINFUSION_FLAG_UNNORMALIZED (anything else -> ERR_INVALID).
  *   workspace       DEVICE scratch of at least linfusion_attn_bwd_workspace_bytes(...) bytes, 16-byte

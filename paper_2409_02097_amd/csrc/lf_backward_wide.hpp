@@ -1,5 +1,5 @@
-// Backward pass for head widths above 80 (fp16), composed of the forward's wide kernels and the small kernels
-// below.  Same derivative as lf_backward16.hpp (of Eq. 5 applied to Prop. 2's state; Sec. 2.5 (Training Objectives)
+// Backward pass composed of the forward's state reduction and apply kernels and the small kernels below: fp16 at
+// head widths above 80 (on the wide kernels) and fp32 at every width it has (on the fp32 kernels).  Same derivative as lf_backward16.hpp (of Eq. 5 applied to Prop. 2's state; Sec. 2.5 (Training Objectives)
 // differentiates through every module), evaluated in units of a power of two beta near sum(z) so that every 16-bit
 // intermediate is of order one whatever N is:
 //   S' = S / beta, z' = z / beta, eps' = eps / beta            (fp32, exact)
@@ -12,18 +12,69 @@
 //   dv_j = dS^T phi(k_j)                                       apply(state dS, input k, phi, no normalizer)
 //   t_j  = dS v_j                                              apply(state dS^T, input v, identity map, no normalizer)
 //   dk_j = (t_j + dz) * phi'(k_j)                              (bwdw_k_finish)
-// Without the normalizer: den' = 1, go = e' = 0, beta = 1.  At the sizes these widths occur in training (the
-// innermost UNet levels: tens to a few thousand tokens) the pass is bound by its sixteen launches, not by its
-// fourteen tensor passes; it is there so that every level of the UNet has a gradient, not for speed.
+// Without the normalizer: den' = 1, go = e' = 0, beta = 1.  The temporaries u', gp, t have the tensors' type (fp32
+// needs no beta for range, but takes the same route).  At the sizes the wide widths occur in training (the innermost
+// UNet levels: tens to a few thousand tokens) the pass is bound by its sixteen launches, not by its fourteen tensor
+// passes; it is there so that every level of the UNet, and the fp32 type, has a gradient, not for speed.
 #pragma once
+#include <type_traits>
+
 #include "lf_backward16.hpp"
 
 namespace lf {
 
 constexpr int kBwdWideThreads = 256;
 
-// grid = (D / 16, heads), block = 256.  st: {S [D][D], z [D]} fp32 of the head.  Workgroup x writes rows 16 x ..
-// 16 x + 15 of tS = {S^T / beta, z / beta} (x = 0: z and aux[bh] = {beta, 1 / beta} too); every workgroup finds beta.
+struct F32 {};   // tag: fp32 storage
+
+// A 16-byte chunk of a token row as floats
+template <typename T> struct RowChunk {
+  static constexpr int kPer = 8;   // elements per chunk
+  using Elem = uint16_t;
+  static LF_DEV void load(const u32x4* p, float (&x)[8]) {
+    const u32x4 w = *p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) unpack2<T>(w[i], x[2 * i], x[2 * i + 1]);
+  }
+  static LF_DEV void store(u32x4* p, const float (&x)[8]) {
+    u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = pack2<T>(x[2 * i], x[2 * i + 1]);
+    *p = w;
+  }
+  static LF_DEV float elem(Elem e) {
+    float x, unused;
+    unpack2<T>((uint32_t)e, x, unused);
+    return x;
+  }
+};
+template <> struct RowChunk<F32> {
+  static constexpr int kPer = 4;
+  using Elem = float;
+  static LF_DEV void load(const u32x4* p, float (&x)[4]) {
+    const u32x4 w = *p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t e = w[i];   // (a bit cast applied to the vector element itself read element 0 four times)
+      x[i] = __builtin_bit_cast(float, e);
+    }
+  }
+  static LF_DEV void store(u32x4* p, const float (&x)[4]) {
+    u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = __builtin_bit_cast(uint32_t, x[i]);
+    *p = w;
+  }
+  static LF_DEV float elem(Elem e) { return e; }
+};
+template <typename T, int FM> LF_DEV float bw_phi(float x) {
+  if constexpr (std::is_same<T, F32>::value) return phi<FM, true>(x);
+  else return phi<FM>(x);
+}
+constexpr int kBwdStrip = 8;   // rows of the state per workgroup of the two state kernels
+
+// grid = (D / 8, heads), block = 256.  st: {S [D][D], z [D]} fp32 of the head.  Workgroup x writes rows 8 x ..
+// 8 x + 7 of tS = {S^T / beta, z / beta} (x = 0: z and aux[bh] = {beta, 1 / beta} too); every workgroup finds beta.
 template <int D, bool NORM>
 __global__ void __launch_bounds__(kBwdWideThreads)
 bwdw_prep_state(const float* __restrict__ state, float* __restrict__ tstate, float* __restrict__ aux) {
@@ -51,9 +102,9 @@ bwdw_prep_state(const float* __restrict__ state, float* __restrict__ tstate, flo
       inv_beta = __builtin_ldexpf(1.0f, -ex);
     }
   }
-  const int a0 = 16 * blockIdx.x;
-  for (int e = threadIdx.x; e < 16 * D; e += kBwdWideThreads) {
-    const int a = a0 + e % 16, b = e / 16;   // ts[a][b] = S[b][a] / beta: sixteen neighbours of a row of S per read
+  const int a0 = kBwdStrip * blockIdx.x;
+  for (int e = threadIdx.x; e < kBwdStrip * D; e += kBwdWideThreads) {
+    const int a = a0 + e % kBwdStrip, b = e / kBwdStrip;   // ts[a][b] = S[b][a] / beta: eight neighbours of a row of S per read
     ts[a * D + b] = st[b * D + a] * inv_beta;
   }
   if (blockIdx.x == 0) {
@@ -65,16 +116,17 @@ bwdw_prep_state(const float* __restrict__ state, float* __restrict__ tstate, flo
   }
 }
 
-// One wave per token, lane l < D / 8 holds channels 8 l .. 8 l + 7.  grid = (ceil(N / 4), heads), block = 256.
-// q, g: the call's tensors; u: S' g (dense [B, H, N, D]); tstate: its z' is read.  Writes dq, gp (dense) and
-// scal[bh][token] = e'.
+// One wave per token, lane l < (chunks per row) holds the channels of chunk l.  grid = (ceil(N / 4), heads),
+// block = 256.  q, g: the call's tensors; u: S' g (dense [B, H, N, D]); tstate: its z' is read.  Writes dq, gp
+// (dense) and scal[bh][token] = e'.
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kBwdWideThreads)
 bwdw_q_finish(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Layout lg,
               const u32x4* __restrict__ U, const float* __restrict__ tstate, const float* __restrict__ aux,
               u32x4* __restrict__ DQ, Layout ldq, u32x4* __restrict__ GP, float* __restrict__ scal, float eps,
               long long N) {
-  constexpr int CPR = D / 8, NE = D * D + D;
+  using RC = RowChunk<T>;
+  constexpr int PER = RC::kPer, CPR = D / PER, NE = D * D + D;
   static_assert(CPR <= 32, "a token row fits half a wave");
   const int lane = threadIdx.x & 63;
   const long long bh = blockIdx.y;
@@ -83,21 +135,15 @@ bwdw_q_finish(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ 
   const bool on = lane < CPR;
   const int c = on ? lane : 0;
   const long long dense = (bh * N + t) * CPR + c;
-  const u32x4 qw = Q[lq.slice(bh) + t * lq.row + c];
-  const u32x4 gw = G[lg.slice(bh) + t * lg.row + c];
-  const u32x4 uw = U[dense];
-  const float* zp = tstate + bh * NE + D * D + 8 * c;
-  float x[8], gg[8], uu[8], r[8], z[8];
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    unpack2<T>(qw[w], x[2 * w], x[2 * w + 1]);
-    unpack2<T>(gw[w], gg[2 * w], gg[2 * w + 1]);
-    unpack2<T>(uw[w], uu[2 * w], uu[2 * w + 1]);
-  }
+  float x[PER], gg[PER], uu[PER], r[PER], z[PER];
+  RC::load(Q + lq.slice(bh) + t * lq.row + c, x);
+  RC::load(G + lg.slice(bh) + t * lg.row + c, gg);
+  RC::load(U + dense, uu);
+  const float* zp = tstate + bh * NE + D * D + PER * c;
   float s_rz = 0.0f, s_ru = 0.0f;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    r[i] = phi<FM>(x[i]);
+  for (int i = 0; i < PER; ++i) {
+    r[i] = bw_phi<T, FM>(x[i]);
     z[i] = NORM ? zp[i] : 0.0f;
     if (on) {
       s_rz = __builtin_fmaf(r[i], z[i], s_rz);
@@ -116,63 +162,51 @@ bwdw_q_finish(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ 
   }
   if (lane == 0) scal[bh * N + t] = -go * invden;
   if (!on) return;
-  u32x4 dqw, gpw;
+  float o2[PER], p2[PER];
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    float o2[2], p2[2];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int i = 2 * w + h;
-      o2[h] = (uu[i] - go * z[i]) * invden * phi_prime_from<FM>(x[i], r[i]);
-      p2[h] = gg[i] * invden;
-    }
-    dqw[w] = pack2<T>(o2[0], o2[1]);
-    gpw[w] = pack2<T>(p2[0], p2[1]);
+  for (int i = 0; i < PER; ++i) {
+    o2[i] = (uu[i] - go * z[i]) * invden * phi_prime_from<FM>(x[i], r[i]);
+    p2[i] = gg[i] * invden;
   }
-  DQ[ldq.slice(bh) + t * ldq.row + c] = dqw;
-  GP[dense] = gpw;
+  RC::store(DQ + ldq.slice(bh) + t * ldq.row + c, o2);
+  RC::store(GP + dense, p2);
 }
 
 // dz' partials: grid = (splits, heads), block = 256; thread c < D sums phi(q_t[c]) e'_t over the split's tokens in
 // token order.  part[bh][split][c].
 template <typename T, int D, int FM>
 __global__ void __launch_bounds__(kBwdWideThreads)
-bwdw_dz(const uint16_t* __restrict__ Q, Layout lq, const float* __restrict__ scal, float* __restrict__ part,
-        long long N) {
+bwdw_dz(const typename RowChunk<T>::Elem* __restrict__ Q, Layout lq, const float* __restrict__ scal,
+        float* __restrict__ part, long long N) {
+  using RC = RowChunk<T>;
+  using Elem = typename RC::Elem;
+  constexpr int PER = RC::kPer;
   const long long bh = blockIdx.y;
   const int c = threadIdx.x;
   const long long per = (N + gridDim.x - 1) / gridDim.x;
   const long long t0 = blockIdx.x * per, t1 = t0 + per < N ? t0 + per : N;
   float acc = 0.0f;
   if (c < D) {
-    const uint16_t* qh = Q + lq.slice(bh) * 8;     // Layout counts 16-byte units
+    const Elem* qh = Q + lq.slice(bh) * PER;     // Layout counts 16-byte units
     long long t = t0;
     for (; t + 4 <= t1; t += 4) {   // four independent loads in flight; summed in token order all the same
-      uint16_t w[4];
+      Elem w[4];
       float e[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        w[i] = qh[(t + i) * lq.row * 8 + c];
+        w[i] = qh[(t + i) * lq.row * PER + c];
         e[i] = scal[bh * N + t + i];
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float x, unused;
-        unpack2<T>((uint32_t)w[i], x, unused);
-        acc = __builtin_fmaf(phi<FM>(x), e[i], acc);
-      }
+      for (int i = 0; i < 4; ++i) acc = __builtin_fmaf(bw_phi<T, FM>(RC::elem(w[i])), e[i], acc);
     }
-    for (; t < t1; ++t) {
-      float x, unused;
-      unpack2<T>((uint32_t)qh[t * lq.row * 8 + c], x, unused);
-      acc = __builtin_fmaf(phi<FM>(x), scal[bh * N + t], acc);
-    }
+    for (; t < t1; ++t) acc = __builtin_fmaf(bw_phi<T, FM>(RC::elem(qh[t * lq.row * PER + c])), scal[bh * N + t], acc);
     part[(bh * gridDim.x + blockIdx.x) * D + c] = acc;
   }
 }
 
-// grid = (D / 16, heads), block = 256.  raw: {dS' [D][D], (unused) [D]} as the reduction left it; part: dz' partials.
-// Workgroup x writes rows 16 x .. 16 x + 15 of dstate = {dS, dz} and of tdstate = {dS^T, 0} (x = 0: the vectors too),
+// grid = (D / 8, heads), block = 256.  raw: {dS' [D][D], (unused) [D]} as the reduction left it; part: dz' partials.
+// Workgroup x writes rows 8 x .. 8 x + 7 of dstate = {dS, dz} and of tdstate = {dS^T, 0} (x = 0: the vectors too),
 // all divided by beta.
 template <int D>
 __global__ void __launch_bounds__(kBwdWideThreads)
@@ -184,10 +218,10 @@ bwdw_finish_state(const float* __restrict__ raw, float* __restrict__ dstate, flo
   float* ds = dstate + bh * NE;
   float* td = tdstate + bh * NE;
   const float inv_beta = aux[2 * bh + 1];
-  const int a0 = 16 * blockIdx.x;
-  for (int e = threadIdx.x; e < 16 * D; e += kBwdWideThreads) ds[a0 * D + e] = rw[a0 * D + e] * inv_beta;
-  for (int e = threadIdx.x; e < 16 * D; e += kBwdWideThreads) {
-    const int a = a0 + e % 16, b = e / 16;
+  const int a0 = kBwdStrip * blockIdx.x;
+  for (int e = threadIdx.x; e < kBwdStrip * D; e += kBwdWideThreads) ds[a0 * D + e] = rw[a0 * D + e] * inv_beta;
+  for (int e = threadIdx.x; e < kBwdStrip * D; e += kBwdWideThreads) {
+    const int a = a0 + e % kBwdStrip, b = e / kBwdStrip;
     td[a * D + b] = rw[b * D + a] * inv_beta;
   }
   if (blockIdx.x == 0) {
@@ -205,25 +239,19 @@ template <typename T, int D, int FM>
 __global__ void __launch_bounds__(kBwdWideThreads)
 bwdw_k_finish(const u32x4* __restrict__ K, Layout lk, const u32x4* __restrict__ Tk, const float* __restrict__ dstate,
               u32x4* __restrict__ DK, Layout ldk, long long N) {
-  constexpr int CPR = D / 8, NE = D * D + D;
+  using RC = RowChunk<T>;
+  constexpr int PER = RC::kPer, CPR = D / PER, NE = D * D + D;
   const int lane = threadIdx.x & 63;
   const long long bh = blockIdx.y;
   const long long t = (long long)blockIdx.x * (kBwdWideThreads / 64) + (threadIdx.x >> 6);
   if (t >= N || lane >= CPR) return;
-  const u32x4 kw = K[lk.slice(bh) + t * lk.row + lane];
-  const u32x4 tw = Tk[(bh * N + t) * CPR + lane];
-  const float* dz = dstate + bh * NE + D * D + 8 * lane;
-  u32x4 o;
+  float x[PER], tt[PER], o[PER];
+  RC::load(K + lk.slice(bh) + t * lk.row + lane, x);
+  RC::load(Tk + (bh * N + t) * CPR + lane, tt);
+  const float* dz = dstate + bh * NE + D * D + PER * lane;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    float x[2], tt[2], r[2];
-    unpack2<T>(kw[w], x[0], x[1]);
-    unpack2<T>(tw[w], tt[0], tt[1]);
-#pragma unroll
-    for (int h = 0; h < 2; ++h) r[h] = (tt[h] + dz[2 * w + h]) * phi_prime_from<FM>(x[h], phi<FM>(x[h]));
-    o[w] = pack2<T>(r[0], r[1]);
-  }
-  DK[ldk.slice(bh) + t * ldk.row + lane] = o;
+  for (int i = 0; i < PER; ++i) o[i] = (tt[i] + dz[i]) * phi_prime_from<FM>(x[i], bw_phi<T, FM>(x[i]));
+  RC::store(DK + ldk.slice(bh) + t * ldk.row + lane, o);
 }
 
 }  // namespace lf

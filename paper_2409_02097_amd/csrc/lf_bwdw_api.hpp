@@ -1,5 +1,5 @@
 // Host-side interface between linfusion_bwd.hip (the backward entry points) and linfusion_bwdw.hip (the backward
-// pass for head widths above 80, composed of the forward's wide kernels).
+// pass composed of the forward's kernels: fp16 at head widths above 80, fp32 at every width it has).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -21,7 +21,7 @@ struct BwdWideArgs {
   lf::Layout lq, lkv, lg, ldq, ldkv;   // q; k and v; dout; dq; dk and dv
 };
 
-// fp16 at the wide kernels' widths
+// fp16 at the wide kernels' widths; fp32 at 8 .. 64 in steps of 8
 bool bwd_wide_supported(int d, int dtype);
 // 0 for unsupported shapes
 size_t bwd_wide_workspace_bytes(int B, int H, long long N, int d, int dtype);

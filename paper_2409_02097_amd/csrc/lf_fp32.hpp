@@ -30,10 +30,10 @@ LF_DEV f32x4 mfma_16x16x4(float a, float b, f32x4 c) { return __builtin_amdgcn_m
 // element i of its K chunk (after phi) is the A operand and element j of its V chunk the B
 // operand of product (i, j), whose accumulator tile is S[4*row + i][4*col + j].  z is summed
 // on the vector ALU.  `smem`: reduce32_lds_bytes<D>(WAVES) bytes; `dst`: this workgroup's partial;
-// `Kh`, `Vh`: first token row of this head; `rs`: row stride in 16-byte units.  WAVES, TO_LDS: as reduce16_phase.
+// `Kh`, `Vh`: first token row of this head; `rs`, `rsv`: their row strides in 16-byte units.  WAVES, TO_LDS: as reduce16_phase.
 // ------------------------------------------------------------------------------------------
 template <int D, int FM, int WAVES = kWavesPerWG, bool TO_LDS = false>
-LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict__ Vh, int rs,
+LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict__ Vh, int rs, int rsv,
                            float* __restrict__ dst, long long N, int tiles_per_block, int split, int nsplit,
                            unsigned char* smem) {
   constexpr int CH = Shape32<D>::kChunks;
@@ -63,10 +63,10 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict
       if (okr[u]) {
         if constexpr (TO_LDS) {      // every workgroup of the head reads these rows: keep them in the L2
           kr[u] = Kh[t * rs + m];
-          vr[u] = Vh[t * rs + m];
+          vr[u] = Vh[t * rsv + m];
         } else {
           kr[u] = __builtin_nontemporal_load(Kh + t * rs + m);
-          vr[u] = __builtin_nontemporal_load(Vh + t * rs + m);
+          vr[u] = __builtin_nontemporal_load(Vh + t * rsv + m);
         }
       } else {
         kr[u] = f32x4{0, 0, 0, 0};
@@ -147,13 +147,13 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict
 // grid = (splits, B*H), block = 256
 template <int D, int FM>
 __global__ void __launch_bounds__(kThreads)
-state_reduce32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout kv, float* __restrict__ partials,
-               long long N, int tiles_per_block) {
+state_reduce32(const f32x4* __restrict__ K, Layout kl, const f32x4* __restrict__ V, Layout vl,
+               float* __restrict__ partials, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const long long bh = blockIdx.y;
   float* dst = partials + (bh * gridDim.x + blockIdx.x) * (long long)(D * D + D);
-  const long long off = kv.slice(bh);
-  reduce32_phase<D, FM>(K + off, V + off, kv.row, dst, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  reduce32_phase<D, FM>(K + kl.slice(bh), V + vl.slice(bh), kl.row, vl.row, dst, N, tiles_per_block, blockIdx.x,
+                        gridDim.x, smem);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -160,7 +160,7 @@ fused32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout lkv, co
   const long long okv = lkv.slice(bh);
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
     __hip_atomic_store(rec, ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  reduce32_phase<D, FM>(K + okv, V + okv, lkv.row, head_part + (long long)split * NE, N, blk_reduce, split, nsplit, smem);
+  reduce32_phase<D, FM>(K + okv, V + okv, lkv.row, lkv.row, head_part + (long long)split * NE, N, blk_reduce, split, nsplit, smem);
   if (!head_barrier(flags + (2 * bh) * nsplit, split, nsplit, ticket, spin_limit, rec, &flag)) return;
   combine_owned(head_part, nsplit, NE, split, head_state, reinterpret_cast<float*>(smem));
   if (!head_barrier(flags + (2 * bh + 1) * nsplit, split, nsplit, ticket, spin_limit, rec, &flag)) return;

@@ -97,7 +97,7 @@ solo32(const f32x4* __restrict__ K, const f32x4* __restrict__ V, Layout lkv, con
   const long long n_tiles = (N + kTile32 - 1) / kTile32;
   const int blk_all = (int)((n_tiles + W - 1) / W * W);
   float* st = reinterpret_cast<float*>(smem + Cfg::kStateOffset);
-  reduce32_phase<D, FM, W, true>(K + okv, V + okv, lkv.row, st, N, blk_all, 0, 1, smem);
+  reduce32_phase<D, FM, W, true>(K + okv, V + okv, lkv.row, lkv.row, st, N, blk_all, 0, 1, smem);
   __syncthreads();
   Apply32Dma<D, FM, NORM, W> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, blk_apply, part, G, smem);
   ap.prefetch();                           // slots 0 and 1: the cross-wave copies there are dead

@@ -17,6 +17,7 @@
 #include "lf_fused.hpp"
 #include "lf_solo_api.hpp"
 #include "lf_host_api.hpp"
+#include "lf_f32_api.hpp"
 #include "lf_wide_api.hpp"
 
 namespace {
@@ -621,7 +622,7 @@ int run32(const Args& a) {
   }
   const dim3 g1(p.splits, (unsigned)a.BH);
   if (a.ev) (void)hipEventRecord(a.ev[0], st);
-#define LF_REDUCE(FM) state_reduce32<D, FM><<<g1, blk, lds, st>>>(K, V, a.lkv, partials, a.N, p.blk_reduce);
+#define LF_REDUCE(FM) state_reduce32<D, FM><<<g1, blk, lds, st>>>(K, a.lkv, V, a.lkv, partials, a.N, p.blk_reduce);
   LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
@@ -850,6 +851,73 @@ int static_scratch(void** ptr) {
 }
 
 }  // namespace
+
+namespace lf32 {
+
+int launch_plan32(int B, int H, long long N, int d, Plan32* out, size_t* partial_bytes) {
+  Plan p;
+  const int rc = make_plan(B, H, N, d, LINFUSION_DTYPE_F32, LINFUSION_FLAG_FORCE_SPLIT, &p);
+  if (rc != LINFUSION_OK) return rc;
+  *out = Plan32{p.splits, p.blk_reduce, p.apply_wgs, p.blk_apply};
+  *partial_bytes = p.ws_partials;
+  return LINFUSION_OK;
+}
+
+namespace {
+template <int D>
+int reduce32(const Reduce32Args& a) {
+  using namespace lf;
+  constexpr int NE = D * D + D;
+  constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
+  const long long BH = (long long)a.B * a.H;
+  const dim3 g1(a.plan.splits, (unsigned)BH), blk(kThreads);
+  const f32x4* K = (const f32x4*)a.k;
+  const f32x4* V = (const f32x4*)a.v;
+  switch (a.fm) {
+    case 0: state_reduce32<D, 0><<<g1, blk, lds, a.st>>>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.blk_reduce); break;
+    case 1: state_reduce32<D, 1><<<g1, blk, lds, a.st>>>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.blk_reduce); break;
+    default: state_reduce32<D, 2><<<g1, blk, lds, a.st>>>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.blk_reduce); break;
+  }
+  combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, a.st>>>(
+      a.partials, a.plan.splits, NE, a.state);
+  return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+}
+
+template <int D>
+int apply32(const Apply32Args& a) {
+  using namespace lf;
+  constexpr size_t ldsa = apply32_lds_bytes<D>();
+  const long long BH = (long long)a.B * a.H;
+  const dim3 g2(a.plan.apply_wgs, (unsigned)BH), blk(kThreads);
+  const f32x4* Q = (const f32x4*)a.q;
+  f32x4* O = (f32x4*)a.out;
+#define LF_APPLY(FM, NORM) \
+  lf::apply32<D, FM, NORM><<<g2, blk, ldsa, a.st>>>(Q, a.lq, O, a.lo, a.state, a.eps, a.N, a.plan.blk_apply);
+  LF_SWITCH_FM_NORM(LF_APPLY)
+#undef LF_APPLY
+  return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+}
+}  // namespace
+
+int run_reduce32(const Reduce32Args& a) {
+  switch (a.d) {
+#define X(DD) case DD: return reduce32<DD>(a);
+    LF_FOR_D(X)
+#undef X
+  }
+  return LINFUSION_ERR_UNSUPPORTED;
+}
+
+int run_apply32(const Apply32Args& a) {
+  switch (a.d) {
+#define X(DD) case DD: return apply32<DD>(a);
+    LF_FOR_D(X)
+#undef X
+  }
+  return LINFUSION_ERR_UNSUPPORTED;
+}
+
+}  // namespace lf32
 
 namespace lfw {
 int wide_launch_plan(int B, int H, long long N, int d, int dtype, WidePlan* wp, size_t* partial_bytes) {

@@ -26,8 +26,8 @@ bool bwd_supported_d(int d) { return (d >= 8 && d <= 64 && d % 8 == 0) || d == 8
 int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return LINFUSION_ERR_INVALID;
   if ((long long)B * H > 65535) return LINFUSION_ERR_INVALID;
-  if (dtype != LINFUSION_DTYPE_F16 && dtype != LINFUSION_DTYPE_BF16) return LINFUSION_ERR_UNSUPPORTED;
-  p->wide = lfbw::bwd_wide_supported(d, dtype);
+  p->wide = lfbw::bwd_wide_supported(d, dtype);   // the composed pass: fp16 above 80, fp32
+  if (dtype != LINFUSION_DTYPE_F16 && dtype != LINFUSION_DTYPE_BF16 && !p->wide) return LINFUSION_ERR_UNSUPPORTED;
   if (!bwd_supported_d(d) && !p->wide) return LINFUSION_ERR_UNSUPPORTED;
   if (N > (1LL << 40) / d) return LINFUSION_ERR_INVALID;
   if (p->wide) {
@@ -374,16 +374,17 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* dou
     if ((uintptr_t)x & 15) return LINFUSION_ERR_MISALIGNED;
   for (void* x : outs)
     if ((uintptr_t)x & 15) return LINFUSION_ERR_MISALIGNED;
+  const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
   const long long dense[3] = {(long long)H * N * d, N * d, (long long)d};
   const long long* st5[5];
   for (int i = 0; i < 5; ++i) st5[i] = (strides && strides[i]) ? strides[i] : dense;
   for (int i = 0; i < 5; ++i)
-    if ((rc = lfh::check_strides(st5[i], B, H, N, d, 2, i >= 3)) != LINFUSION_OK) return rc;
+    if ((rc = lfh::check_strides(st5[i], B, H, N, d, esz, i >= 3)) != LINFUSION_OK) return rc;
   // spans of q, k, v, dout and of dq, dk, dv
-  const size_t in_span[4] = {lfh::span_bytes(st5[0], B, H, N, d, 2), lfh::span_bytes(st5[1], B, H, N, d, 2),
-                             lfh::span_bytes(st5[1], B, H, N, d, 2), lfh::span_bytes(st5[2], B, H, N, d, 2)};
-  const size_t out_span[3] = {lfh::span_bytes(st5[3], B, H, N, d, 2), lfh::span_bytes(st5[4], B, H, N, d, 2),
-                              lfh::span_bytes(st5[4], B, H, N, d, 2)};
+  const size_t in_span[4] = {lfh::span_bytes(st5[0], B, H, N, d, esz), lfh::span_bytes(st5[1], B, H, N, d, esz),
+                             lfh::span_bytes(st5[1], B, H, N, d, esz), lfh::span_bytes(st5[2], B, H, N, d, esz)};
+  const size_t out_span[3] = {lfh::span_bytes(st5[3], B, H, N, d, esz), lfh::span_bytes(st5[4], B, H, N, d, esz),
+                              lfh::span_bytes(st5[4], B, H, N, d, esz)};
   for (int i = 0; i < 3; ++i) {
     for (int j = 0; j < 4; ++j)
       if (overlaps(outs[i], out_span[i], ins[j], in_span[j])) return LINFUSION_ERR_OVERLAP;
@@ -406,7 +407,8 @@ static int bwd_impl(const void* q, const void* k, const void* v, const void* dou
     if (overlaps(workspace, p.ws_total, outs[i], out_span[i])) return LINFUSION_ERR_OVERLAP;
   rc = lfh::check_device();
   if (rc != LINFUSION_OK) return rc;
-  auto lay = [&](const long long* s) { return lf::Layout{s[0] / 8, s[1] / 8, (int)(s[2] / 8), H}; };   // 16-byte units
+  const int per = 16 / (int)esz;   // elements per 16-byte unit
+  auto lay = [&](const long long* s) { return lf::Layout{s[0] / per, s[1] / per, (int)(s[2] / per), H}; };   // 16-byte units
   if (p.wide) {
     const lfbw::BwdWideArgs w{state, q, k, v, dout, dq, dk, dv, B, H, N, d, dtype, feature_map, eps,
                               (flags & LINFUSION_FLAG_UNNORMALIZED) != 0, (unsigned char*)workspace,

@@ -172,15 +172,17 @@ def test_backward_argument_validation_happens_on_the_host():
              flags=0, ws=64 << 20, ws_bytes=8 << 20):
         return lib.linfusion_attn_bwd(q, k, v, g, state, dq, dk, dv, 1, 2, 64, d, dtype, fm, eps, flags, ws, ws_bytes, None)
     assert call(g=None) == -1 and call(dk=None) == -1 and call(eps=-1.0) == -1 and call(flags=2) == -1
-    assert call(dtype=0) == -2 and call(d=160, dtype=2) == -2 and call(d=12) == -2 and call(fm=3) == -2
-    assert call(d=160, dtype=1) == -6       # fp16 at the wide widths is supported (this workspace is too small for it)
+    assert call(d=160, dtype=2) == -2 and call(d=12) == -2 and call(fm=3) == -2 and call(d=80, dtype=0) == -2
+    # fp16 at the wide widths and fp32 are supported (the composed pass): validation goes on to the workspace size
+    # (-4) and, past it, to the device check (-6: there is none here)
+    assert call(d=160, dtype=1) == -6 and call(dtype=0) == -6 and call(dtype=0, ws_bytes=1 << 10) == -4
     assert call(dq=(4 << 20) + 8) == -3 and call(ws=(64 << 20) + 4) == -3
     assert call(ws=None) == -4 and call(ws_bytes=64) == -4
     assert call(dq=4096) == -7 and call(dk=4 << 20) == -7 and call(dv=(2 << 20) + 256) == -7 and call(ws=6 << 20) == -7
     assert call(state=(7 << 20) + 4) == -3 and call(state=4 << 20) == -7 and call(state=64 << 20) == -7
     assert lf.linfusion_attn_bwd_workspace_bytes(1, 2, 64, 40, 1) > 0
     assert 0 < lf.linfusion_attn_workspace_state_offset(1, 2, 64, 40, 1) < lf.linfusion_attn_workspace_bytes(1, 2, 64, 40, 1)
-    assert lf.linfusion_attn_bwd_workspace_bytes(1, 2, 64, 40, 0) == 0
+    assert lf.linfusion_attn_bwd_workspace_bytes(1, 2, 64, 40, 0) > 0 and lf.linfusion_attn_bwd_workspace_bytes(1, 2, 64, 80, 0) == 0
 
 
 @fake_addresses

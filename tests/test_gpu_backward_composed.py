@@ -1,5 +1,6 @@
-"""GPU parity of the backward pass at head widths above 80 (fp16; the d = 160 level of the SD-v1.5 UNet and the
-other widths of the wide kernels) against the fp64 oracle's gradients, rule of tests/parity.py: check_gradients."""
+"""GPU parity of the composed backward pass -- fp16 at head widths above 80 (the d = 160 level of the SD-v1.5 UNet
+and the other widths of the wide kernels) and fp32 at every width -- against the fp64 oracle's gradients, rule of
+tests/parity.py: check_gradients."""
 import pytest
 import torch
 
@@ -11,8 +12,8 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 
-def _ws(B, H, N, d):
-    n = lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, lf.DTYPE_F16)
+def _ws(B, H, N, d, code=lf.DTYPE_F16):
+    n = lf.linfusion_attn_bwd_workspace_bytes(B, H, N, d, code)
     assert n > 0
     ws = torch.empty(n, dtype=torch.uint8, device="cuda")
     ws.fill_(0xFF)
@@ -22,20 +23,21 @@ def _ws(B, H, N, d):
 def _run(q, k, v, g, fm=0, eps=1e-6, flags=0, state=None):
     B, H, N, d = q.shape
     outs = [torch.full_like(q, float("nan")).cuda() for _ in range(3)]
-    lf.linfusion_attn_bwd(q.cuda(), k.cuda(), v.cuda(), g.cuda(), *outs, fm, eps, flags, _ws(B, H, N, d), state=state)
+    code = lf.DTYPE_F32 if q.dtype == torch.float32 else lf.DTYPE_F16
+    lf.linfusion_attn_bwd(q.cuda(), k.cuda(), v.cuda(), g.cuda(), *outs, fm, eps, flags, _ws(B, H, N, d, code), state=state)
     torch.cuda.synchronize()
     return outs
 
 
-def _check(outs, q, k, v, g, fm, eps, normalize, what):
+def _check(outs, q, k, v, g, fm, eps, normalize, what, dtype="f16"):
     qs, ks, vs, gs = (wl.stored_numpy(t) for t in (q, k, v, g))
     B, H = qs.shape[:2]
     worst = 0.0
     for b in range(B):
         for h in range(H):
-            w = [orc.widen(x[b, h], "f16") for x in (qs, ks, vs, gs)]
+            w = [orc.widen(x[b, h], dtype) for x in (qs, ks, vs, gs)]
             got = [parity.to_f64(t[b, h]) for t in outs]
-            worst = max(worst, parity.check_gradients(got, *w, "f16", fm, eps, normalize, f"{what} b={b} h={h}"))
+            worst = max(worst, parity.check_gradients(got, *w, dtype, fm, eps, normalize, f"{what} b={b} h={h}"))
     return worst
 
 
@@ -109,3 +111,52 @@ def test_wide_backward_rejects_bf16():
     assert lf.linfusion_attn_bwd_workspace_bytes(1, 1, 64, 160, lf.DTYPE_BF16) == 0
     ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
     assert lf.linfusion_attn_bwd(x, x, x, x, *[torch.empty_like(x) for _ in range(3)], 0, 1e-6, 0, ws, check=False) == -2
+
+
+F32_SHAPES = [
+    # SD-v1.5 at 256 px in fp32 is (2, 8, 1024, 40)
+    (2, 8, 1024, 40), (1, 2, 1, 40), (2, 3, 33, 40), (1, 1, 4099, 64), (1, 2, 300, 8), (1, 2, 515, 24), (1, 2, 300, 16),
+    (1, 2, 300, 32), (1, 1, 200, 48), (1, 1, 130, 56), (1, 2, 20011, 40),
+]
+
+
+@pytest.mark.parametrize("B,H,N,d", F32_SHAPES)
+def test_fp32_backward_matches_oracle(B, H, N, d):
+    print(f"fp32 bwd B={B} H={H} N={N} d={d}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=94, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 94777, "f32", "cpu")
+    outs = _run(q, k, v, g)
+    worst = _check(outs, q, k, v, g, 0, 1e-6, True, f"fp32 bwd N={N} d={d}", "f32")
+    print(f"  worst error / term scale {worst:.2e}", flush=True)
+    again = _run(q, k, v, g)
+    for a, b in zip(outs, again):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32)), "not run-to-run identical"
+
+
+@pytest.mark.parametrize("fm,normalize", [(1, True), (2, True), (0, False), (1, False)])
+def test_fp32_backward_other_feature_maps_and_unnormalized(fm, normalize):
+    B, H, N, d = 1, 2, 500, 40
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=95, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 95777, "f32", "cpu")
+    if fm == 2:
+        q, k = q.abs(), k.abs()
+    outs = _run(q, k, v, g, fm, 1e-6, 0 if normalize else lf.FLAG_UNNORMALIZED)
+    _check(outs, q, k, v, g, fm, 1e-6, normalize, f"fp32 bwd fm={fm} norm={normalize}", "f32")
+
+
+def test_fp32_backward_token_major_views_and_saved_state():
+    B, H, N, d = 2, 4, 300, 40
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=96, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 96777, "f32", "cpu")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)   # [B, N, H, d] in memory
+    outs = [tm(torch.full_like(q, float("nan"))) for _ in range(3)]
+    lf.linfusion_attn_bwd_strided(tm(q), tm(k), tm(v), tm(g), *outs, 0, 1e-6, 0, _ws(B, H, N, d, lf.DTYPE_F32))
+    torch.cuda.synchronize()
+    dense = _run(q, k, v, g)
+    for a, b in zip(outs, dense):
+        assert torch.equal(a.contiguous().view(torch.int32), b.view(torch.int32)), "token-major differs from contiguous"
+    st = torch.full((B, H, d * d + d), float("nan"), dtype=torch.float32, device="cuda")
+    fws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, lf.DTYPE_F32), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_state(k.cuda(), v.cuda(), st, 0, fws)
+    with_state = _run(q, k, v, g, state=st)
+    _check(with_state, q, k, v, g, 0, 1e-6, True, "fp32 bwd with saved state", "f32")
