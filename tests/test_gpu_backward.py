@@ -127,10 +127,13 @@ def test_backward_argument_checks():
     assert lf.linfusion_attn_bwd(x, x, x, x, outs[0], outs[0], outs[2], 0, 1e-6, 0, ws, check=False) == -7
     assert lf.linfusion_attn_bwd(x, x, x, x, *outs, 0, 1e-6, lf.FLAG_FORCE_FUSED, ws, check=False) == -1
     assert lf.linfusion_attn_bwd(x, x, x, x, *outs, 0, 1e-6, 0, ws[:64], check=False) == -4
-    f = torch.zeros(1, 1, 64, 40, dtype=torch.float32, device="cuda")
+    f = torch.zeros(1, 1, 64, 80, dtype=torch.float32, device="cuda")      # fp32 stops at d = 64, as its forward does
     fo = [torch.empty_like(f) for _ in range(3)]
     assert lf.linfusion_attn_bwd(f, f, f, f, *fo, 0, 1e-6, 0, ws, check=False) == -2
-    assert lf.linfusion_attn_bwd_workspace_bytes(1, 1, 64, 40, 0) == 0
+    assert lf.linfusion_attn_bwd_workspace_bytes(1, 1, 64, 80, 0) == 0
+    b = torch.zeros(1, 1, 64, 160, dtype=torch.bfloat16, device="cuda")    # bf16 stops at d = 80
+    bo = [torch.empty_like(b) for _ in range(3)]
+    assert lf.linfusion_attn_bwd(b, b, b, b, *bo, 0, 1e-6, 0, ws, check=False) == -2
 
 
 @pytest.mark.parametrize("B,H,N,d,dtype", [(2, 3, 33, 40, "f16"), (1, 8, 1000, 40, "f16"), (2, 5, 700, 64, "bf16"),
