@@ -15,6 +15,7 @@
 #include <random>
 
 #include "lf_fused.hpp"
+#include "lf_reduce32s.hpp"
 #include "lf_solo_api.hpp"
 #include "lf_host_api.hpp"
 #include "lf_f32_api.hpp"
@@ -584,6 +585,31 @@ int run16(const Args& a) {
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }
 
+// fp32 state reduction of the split path: on the 16-bit matrix cores through three bf16 terms per value
+// (state_reduce32_split), or on the fp32 instruction (state_reduce32).  Measured on MI355X, B=1, H=8, whole step:
+// d = 8: 249 against 942 us at 2^20 tokens, d = 16: 393 / 939, d = 24: 306 / 531 at 2^19, d = 32: 738 / 1138 at
+// 2^20, d = 40: 502 / 632 at 2^19, d = 48: 344 / 355 at 2^18; d = 56: 434 / 422 and d = 64: 495 / 459 the other way
+// (its six 16-bit tiles per wave leave one workgroup per CU there); below about 8192 tokens per head the fp32
+// instruction's shorter prologue wins (d = 40, N = 2048: 24.8 / 20.6 us, N = 8192: 36.7 / 37.2).
+template <int D, int FM>
+int launch_reduce32(const lf::f32x4* K, lf::Layout lk, const lf::f32x4* V, lf::Layout lv, float* partials, long long N,
+                    int splits, int blk, long long BH, hipStream_t st) {
+  using namespace lf;
+  const dim3 g1(splits, (unsigned)BH), b(kThreads);
+  const int mode = env_int("LINFUSION_F32_SPLIT", 1);   // 1 = by shape, 2 = never, 3 = always
+  if (mode == 3 || (mode == 1 && D <= 48 && N >= 8192)) {
+    constexpr int lds = reduce32s_lds_bytes<D>();
+    if (!lfh::allow_lds(state_reduce32_split<D, FM>, lds)) return LINFUSION_ERR_HIP;
+    // the plan counts 16-token tiles; this kernel's are 32 tokens
+    const int blk32 = ((blk / 2 + kWavesPerWG - 1) / kWavesPerWG) * kWavesPerWG;
+    state_reduce32_split<D, FM><<<g1, b, lds, st>>>(K, lk, V, lv, partials, N, blk32 < kWavesPerWG ? kWavesPerWG : blk32);
+  } else {
+    constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
+    state_reduce32<D, FM><<<g1, b, lds, st>>>(K, lk, V, lv, partials, N, blk);
+  }
+  return LINFUSION_OK;
+}
+
 template <int D>
 int run32(const Args& a) {
   using namespace lf;
@@ -597,7 +623,6 @@ int run32(const Args& a) {
   const f32x4* Q = (const f32x4*)a.q;
   f32x4* O = (f32x4*)a.out;
   hipStream_t st = a.st;
-  constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
   constexpr size_t ldsf = fused32_lds_bytes<D>();
   constexpr size_t ldsa = apply32_lds_bytes<D>();
   if (p.path == 1 && a.out && !capturing(a.st)) {
@@ -620,9 +645,9 @@ int run32(const Args& a) {
       return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
     }
   }
-  const dim3 g1(p.splits, (unsigned)a.BH);
   if (a.ev) (void)hipEventRecord(a.ev[0], st);
-#define LF_REDUCE(FM) state_reduce32<D, FM><<<g1, blk, lds, st>>>(K, a.lkv, V, a.lkv, partials, a.N, p.blk_reduce);
+#define LF_REDUCE(FM)                                                                                              \
+  if (int rc = launch_reduce32<D, FM>(K, a.lkv, V, a.lkv, partials, a.N, p.splits, p.blk_reduce, a.BH, st)) return rc;
   LF_SWITCH_FM(LF_REDUCE)
 #undef LF_REDUCE
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
@@ -868,16 +893,16 @@ template <int D>
 int reduce32(const Reduce32Args& a) {
   using namespace lf;
   constexpr int NE = D * D + D;
-  constexpr size_t lds = reduce32_lds_bytes<D>() > 1024 ? reduce32_lds_bytes<D>() : 1024;
   const long long BH = (long long)a.B * a.H;
-  const dim3 g1(a.plan.splits, (unsigned)BH), blk(kThreads);
   const f32x4* K = (const f32x4*)a.k;
   const f32x4* V = (const f32x4*)a.v;
+  int rc;
   switch (a.fm) {
-    case 0: state_reduce32<D, 0><<<g1, blk, lds, a.st>>>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.blk_reduce); break;
-    case 1: state_reduce32<D, 1><<<g1, blk, lds, a.st>>>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.blk_reduce); break;
-    default: state_reduce32<D, 2><<<g1, blk, lds, a.st>>>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.blk_reduce); break;
+    case 0: rc = launch_reduce32<D, 0>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.splits, a.plan.blk_reduce, BH, a.st); break;
+    case 1: rc = launch_reduce32<D, 1>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.splits, a.plan.blk_reduce, BH, a.st); break;
+    default: rc = launch_reduce32<D, 2>(K, a.lk, V, a.lv, a.partials, a.N, a.plan.splits, a.plan.blk_reduce, BH, a.st); break;
   }
+  if (rc != LINFUSION_OK) return rc;
   combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, a.st>>>(
       a.partials, a.plan.splits, NE, a.state);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;

@@ -380,3 +380,33 @@ def test_forward_recorded_into_a_graph_replays_correctly():
         torch.cuda.synchronize()
         assert torch.equal(out.view(torch.uint8), eager.view(torch.uint8)), f"replay {rep} differs from the eager call"
     worst = parity.check_all(out[:, :2], q[:, :2].cpu(), k[:, :2].cpu(), v[:, :2].cpu(), dtype, 0, 1e-6, True, "graph replay")
+
+
+@pytest.mark.parametrize("mode", [3, 2])
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 1, 40), (1, 2, 17, 64), (2, 2, 1000, 40), (1, 3, 2051, 64), (1, 2, 100, 8),
+                                     (1, 2, 515, 24), (1, 1, 300, 56), (1, 1, 333, 32), (1, 2, 300, 16), (1, 1, 200, 48),
+                                     (1, 2, 9001, 40)])
+def test_fp32_state_reduction_on_either_matrix_instruction(B, H, N, d, mode, monkeypatch, tuning):
+    """fp32 runs its state reduction through three bf16 terms per value on the 16-bit matrix cores (narrow heads at
+    large N) or on the fp32 instruction (the rest); both kernels on every width and on ragged sizes, each against the
+    oracle at the fp32 tolerance, split path forced so that the choice is the reduction's alone."""
+    print(f"fp32 reduction mode {mode} B={B} H={H} N={N} d={d}", flush=True)
+    monkeypatch.setenv("LINFUSION_F32_SPLIT", str(mode))
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=45, device="cpu")
+    out = _run(q.cuda(), k.cuda(), v.cuda(), flags=lf.FLAG_FORCE_SPLIT)
+    worst = parity.check_all(out, q, k, v, "f32", 0, 1e-6, True, f"fp32 reduction mode {mode} N={N} d={d}")
+    print(f"  worst max-norm ratio {worst[0]:.2e}", flush=True)
+
+
+def test_fp32_split_reduction_is_the_default_for_narrow_heads_at_large_n():
+    """Default choice (no environment): N = 20,011 tokens of width 40 take the 16-bit route; token-major views too."""
+    B, H, N, d = 1, 4, 20011, 40
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=46, device="cpu")
+    out = _run(q.cuda(), k.cuda(), v.cuda())
+    parity.check_all(out, q, k, v, "f32", 0, 1e-6, True, "fp32 default at large N")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda().permute(0, 2, 1, 3)
+    o = tm(torch.full_like(q, float("nan")))
+    ws = torch.empty(lf.linfusion_attn_workspace_bytes(B, H, N, d, lf.DTYPE_F32), dtype=torch.uint8, device="cuda")
+    lf.linfusion_attn_fwd_strided(tm(q), tm(k), tm(v), o, 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o.contiguous().view(torch.int32), out.view(torch.int32)), "token-major differs from contiguous"
