@@ -395,8 +395,8 @@ def main():
     }
     if args.backward:
         # gradient tensors resident in HBM; minimal traffic = q, k, v, dout read + dq, dk, dv written (7 tensors);
-        # the kernels read k, v twice (9 tensor passes); bf16 and d > 48 also read q and dout twice (11 passes
-        # plus 16 bytes per token-head of scalars written and read)
+        # the kernels read k, v twice when they recompute the forward state (9 tensor passes); token-major bf16 and
+        # token-major d = 56 / 80 also read q and dout twice (11 passes plus 16 bytes per token-head of scalars)
         # (--layout token_major: all seven tensors as strided views of [B, N, H*d] memory)
         g = torch.empty_like(qd).copy_(torch.randn_like(q))   # keeps the strides of qd
         grads = [torch.empty_like(qd) for _ in range(3)]
@@ -410,7 +410,9 @@ def main():
         nstate = B * H * (d * d + d)
         saved = ws[off:off + 4 * nstate].view(torch.float32).clone()
         tensor_bytes = alg_bytes / 4
-        merged = dtype == "f16" and d <= 48
+        # dQ and the state gradient in one kernel: always on contiguous heads; on token-major tensors whose head
+        # rows are no whole cache lines only where its row-piece form exists (fp16, d <= 48)
+        merged = args.layout == "head_major" or (d * 2) % 128 == 0 or (dtype == "f16" and d <= 48)
         timings = {}
         for label, state in (("with_state", saved), ("recomputed", None)):
             def bstep():
@@ -426,8 +428,8 @@ def main():
             timings[label] = (time.perf_counter() - tb) / bsteps
         bdt = timings["with_state"]
         # tensor passes of the kernels with the state handed over: the minimum of 7 (q, k, v, dout read; dq, dk, dv
-        # written) for fp16 up to d = 48; bf16 and d > 48 read q and dout twice and move 16 bytes of scalars per
-        # token-head; recomputing the state reads k and v once more
+        # written) with the merged kernel; the separate kernels read q and dout twice and move 16 bytes of scalars
+        # per token-head; recomputing the state reads k and v once more
         passes = (7 if merged else 9)
         kbytes = passes * tensor_bytes + (0 if merged else 16.0 * B * H * N)
         result["backward"] = {"layout": args.layout, "ms_per_step": bdt * 1e3, "tokens_per_s": B * N / bdt,

@@ -27,13 +27,14 @@ LF_DEV float phi_prime_from(float x, float phi_x) {   // d phi / dx given x and 
   else return 1.0f;
 }
 
-template <int D> struct BwdCfg {
+// RING: slots of the per-wave ring (RING - 1 tiles in flight); three where two workgroups share a CU
+template <int D, int RING = 3> struct BwdCfg {
   using Sh = Shape16<D>;
   using AC = ApplyDmaCfg<D>;
   static constexpr int kNL = AC::kNL;
   static constexpr int kTileBytes = AC::kSlotBytes;              // one tensor's tile (whole 1 KiB deposits)
   static constexpr int kSlotBytes = 2 * kTileBytes;              // two tensors per ring slot
-  static constexpr int kRing = 3;
+  static constexpr int kRing = RING;
   static constexpr int kStageOffset = (kRing - 1) * kWavesPerWG * kSlotBytes;
   static constexpr int kStageBytes = (D * D + D) * 4 + 64;
   static constexpr int kMTB = (Sh::kHalf + 15) / 16;            // 32-row output tiles (no normalizer rows)
@@ -44,15 +45,15 @@ template <int D> struct BwdCfg {
 };
 
 // ---- two-tensor LDS-DMA ring, one wave per tile (see apply16_dma for the mechanism) -----------------
-template <typename T, int D>
+template <typename T, int D, int RING = 3>
 struct Ring2 {
   using Sh = Shape16<D>;
   using AC = ApplyDmaCfg<D>;
-  using BC = BwdCfg<D>;
+  using BC = BwdCfg<D, RING>;
   static constexpr int NS = NSplit<T>::value;
   static constexpr int KS = Sh::kKS, CPR = Sh::kChunksPerRow, HALF = Sh::kHalf, MTB = BC::kMTB;
   static constexpr int NL = BC::kNL, NE = D * D + D, R = BC::kRing, TB = BC::kTileBytes;
-  static_assert(R == 3, "the wait counts are written for a ring of three slots");
+  static_assert(R >= 3 && R <= 5, "ring depths the wait counts are written out for");
 
   const u32x4 *Xh, *Yh;
   int rsx, rsy;   // token strides of the two tensors, in 16-byte units (CPR when the rows are dense)
@@ -117,10 +118,11 @@ struct Ring2 {
     }
   }
   LF_DEV void prefetch() {
-    if (ahead.valid()) issue_copy(ahead.t, 0);
-    ahead.next();
-    if (ahead.valid()) issue_copy(ahead.t, 1);
-    ahead.next();
+#pragma unroll
+    for (int s = 0; s < R - 1; ++s) {
+      if (ahead.valid()) issue_copy(ahead.t, s);
+      ahead.next();
+    }
   }
   // coalesced stores of tile part `which` of slot `slot` to head tensor `Oh` (token stride `rso`): always NL
   // instructions
@@ -136,13 +138,20 @@ struct Ring2 {
     }
   }
   // waits until the copies of the tile that is about to be used have landed; `iter` = tiles done so far
-  // (0, 1, 2 = two or more), `more` = a copy was issued this iteration, SN = store instructions per tile
+  // (0 ... R - 1 = that many or more), `more` = a copy was issued this iteration, SN = store instructions per
+  // tile.  Issued after the wanted tile's copies: those of the R - 1 tiles behind it and the stores of the up to
+  // R - 1 tiles finished since.
   template <int SN>
   LF_DEV void wait_tile(int iter, bool more) {
+    constexpr int C = (R - 1) * 2 * NL;
+    static_assert(C + (R - 1) * SN <= 63, "the counter of outstanding vector memory operations has six bits");
     if (!more) { wait_vmcnt<0>(); return; }
-    if (iter == 0) wait_vmcnt<4 * NL>();
-    else if (iter == 1) wait_vmcnt<4 * NL + SN>();
-    else wait_vmcnt<4 * NL + 2 * SN>();
+    constexpr int M = R - 1;   // `iter` never exceeds it
+    if (iter == 0) wait_vmcnt<C>();
+    else if (iter == 1) wait_vmcnt<C + SN>();
+    else if (iter == 2) wait_vmcnt<C + 2 * SN>();
+    else if (iter == 3) wait_vmcnt<C + (M < 3 ? M : 3) * SN>();
+    else wait_vmcnt<C + (M < 4 ? M : 4) * SN>();
   }
 
   // Stages one head's fp32 state ([D*D] matrix then [D] vector) in LDS and returns the power-of-two scale
@@ -233,6 +242,16 @@ struct Ring2 {
       for (int e = 0; e < PB / 4; ++e) w[e] = pack2<T>(x[c * (PB / 2) + 2 * e], x[c * (PB / 2) + 2 * e + 1]);
       if constexpr (PB == 16) *reinterpret_cast<u32x4*>(p) = u32x4{w[0], w[1], w[2], w[3]};
       else *reinterpret_cast<u32x2*>(p) = u32x2{w[0], w[1]};
+    }
+  }
+  // the same from words already packed (element 2 i in the low half of word i)
+  LF_DEV void write_half_row_words(int slot, int which, const uint32_t (&w)[HALF / 2]) const {
+    constexpr int PB = (HALF % 8 == 0) ? 16 : 8;
+#pragma unroll
+    for (int c = 0; c < HALF * 2 / PB; ++c) {
+      unsigned char* p = byte_ptr(slot, which, kg * HALF * 2 + c * PB);
+      if constexpr (PB == 16) *reinterpret_cast<u32x4*>(p) = u32x4{w[4 * c], w[4 * c + 1], w[4 * c + 2], w[4 * c + 3]};
+      else *reinterpret_cast<u32x2*>(p) = u32x2{w[2 * c], w[2 * c + 1]};
     }
   }
   // B operands: this lane's input chunks of its token's row, raw 16-bit values
@@ -347,34 +366,55 @@ bwd_q16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Lay
 // transposing LDS reads exactly as the reductions do; then dq takes the Q tile's place and leaves.
 // At the end the four waves' accumulators are summed in a fixed order and written (divided by beta) as
 // this workgroup's partial: [B*H][gridDim.x][D*D + D], for combine_state.  No per-token scalars in memory,
-// two tensor passes fewer.  LDS: BwdCfg<D>::lds_bytes() + 256.
+// two tensor passes fewer.  LDS: qs_lds_bytes<T, D>().
 // ==========================================================================================
+// Ring depth of the merged kernel: three slots and two workgroups per CU where the kernel fits 256 registers;
+// beyond that a lone workgroup per CU (512 registers per lane) with a deeper ring, as LDS allows.
+template <typename T, int D> constexpr bool qs_two_per_cu() { return NSplit<T>::value == 1 ? D <= 48 : D <= 32; }
+template <typename T, int D> constexpr int qs_ring() {
+  if (qs_two_per_cu<T, D>()) return 3;
+  return D <= 48 ? 5 : (D <= 64 ? 4 : 3);
+}
+template <typename T, int D> constexpr int qs_lds_bytes() { return BwdCfg<D, qs_ring<T, D>()>::lds_bytes() + 512; }
+
 template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
 bwd_qs16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Layout lg, u32x4* __restrict__ dQ,
          Layout ldq, const float* __restrict__ state, float* __restrict__ partials, float eps, long long N,
          int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  using RG = Ring2<T, D>;
+  using RG = Ring2<T, D, qs_ring<T, D>()>;
+  using BC = typename RG::BC;
   using Sh = Shape16<D>;
-  static_assert(NSplit<T>::value == 1, "single-level operands only (fp16)");
-  constexpr int NS = 1, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
+  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
   constexpr int MT = Sh::kMT, NE = D * D + D;
   const long long bh = blockIdx.y;
   RG rg(Q + lq.slice(bh), lq.row, G + lg.slice(bh), lg.row, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
   u32x4* dQh = dQ + ldq.slice(bh);
-  uint16_t* ecol = reinterpret_cast<uint16_t*>(smem + BwdCfg<D>::lds_bytes()) + rg.wave * 32;
+  uint16_t* ecol = reinterpret_cast<uint16_t*>(smem + BC::lds_bytes()) + rg.wave * 32;
   rg.prefetch();
 
   const float aS = rg.stage_state(state + bh * NE);
   u32x4 A[NS][MTB][KS];
   rg.template build_A<false>(aS, A);
-  float zo[HALF];
-  rg.load_vec(zo);
+  // z at this lane-half's output channels: in registers (fp16) or, where registers are short (bf16), in a copy
+  // of its own in LDS behind the e column, read per use
+  float zo[NS == 1 ? HALF : 1];
+  float* zlds = reinterpret_cast<float*>(smem + BC::lds_bytes() + 256);
+  if constexpr (NS == 1) {
+    rg.load_vec(zo);
+  } else {
+    const float* z = reinterpret_cast<const float*>(smem + BC::kStageOffset) + D * D;
+    for (int i = threadIdx.x; i < D; i += kThreads) zlds[i] = z[i];
+  }
+  auto zv = [&](int i) -> float {
+    if constexpr (NS == 1) return zo[i];
+    else return zlds[rg.kg * HALF + i];
+  };
   const float inv_aS = 1.0f / aS;
   float beta = 1.0f, inv_beta = 1.0f;
   if constexpr (NORM) {   // power of two near the typical denominator (see bwd_state16)
-    const float* z = reinterpret_cast<const float*>(smem + BwdCfg<D>::kStageOffset) + D * D;
+    const float* z = reinterpret_cast<const float*>(smem + BC::kStageOffset) + D * D;
     float zs = 0.0f;
     for (int i = 0; i < D; ++i) zs += z[i];
     if (zs > 0.0f && zs < 3.0e38f) {
@@ -405,7 +445,7 @@ bwd_qs16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, La
     const bool more = rg.ahead.valid();
     if (more) rg.issue_copy(rg.ahead.t, aslot);
     rg.template wait_tile<NL>(iter, more);
-    iter = iter < 2 ? iter + 1 : 2;
+    iter = iter < R - 1 ? iter + 1 : R - 1;
     long long rem = N - tile * kTile;
     const bool ok = rg.tok < (rem < kTile ? (int)rem : kTile);
 
@@ -413,36 +453,70 @@ bwd_qs16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, La
     rg.read_B_raw(slot, 1, Bg);
     f32x16 acc[MTB];
     rg.products(A, Bg, nullptr, acc);
-    float x[HALF], dr[HALF], rr[HALF];
-    rg.read_half_row(slot, 0, x);
-    float denp = 0.0f, rup = 0.0f;
-#pragma unroll
-    for (int i = 0; i < HALF; ++i) {
-      const float r = phi<FM>(x[i]);
-      const float u = acc[i / 16][i % 16] * inv_aS;
-      denp = __builtin_fmaf(r, zo[i], denp);
-      rup = __builtin_fmaf(r, u, rup);
-      dr[i] = u;
-      rr[i] = ok ? r : 0.0f;
-      x[i] = phi_prime_from<FM>(x[i], r);
-    }
+    // dq and phi(q) leave this block as the 16-bit words that go to LDS (bf16: phi(q) as a rounded value plus the
+    // remainder).  bf16 is short of registers: it keeps phi'(q) as one sign bit per element and takes the value
+    // back from the two levels of phi(q) (16 significant bits; elu + 1 and relu have phi' = 1 where q > 0, else phi
+    // resp. 0, the identity map 1 everywhere).
+    uint32_t dqw[HALF / 2], rw[NS][HALF / 2];
     float gsc = ok ? 1.0f : 0.0f, e = 0.0f;
-    if constexpr (NORM) {
-      const float den = denp + __shfl_xor(denp, 32) + eps;
-      const float ru = rup + __shfl_xor(rup, 32);
-      const float invden = 1.0f / den;
-      const float go = ru * invden;
+    {
+      float x[HALF], dr[HALF];
+      rg.read_half_row(slot, 0, x);
+      float denp = 0.0f, rup = 0.0f;
+      uint64_t pos = 0;   // bit i: q at output channel i is positive
 #pragma unroll
-      for (int i = 0; i < HALF; ++i) dr[i] = (dr[i] - go * zo[i]) * invden * x[i];
-      gsc = ok ? invden * beta : 0.0f;
-      e = ok ? -go * invden * beta : 0.0f;
-    } else {
+      for (int i = 0; i < HALF; i += 2) {
+        float r[2];
 #pragma unroll
-      for (int i = 0; i < HALF; ++i) dr[i] *= x[i];
+        for (int q = 0; q < 2; ++q) {
+          r[q] = phi<FM>(x[i + q]);
+          const float u = acc[(i + q) / 16][(i + q) % 16] * inv_aS;
+          denp = __builtin_fmaf(r[q], zv(i + q), denp);
+          rup = __builtin_fmaf(r[q], u, rup);
+          dr[i + q] = u;
+          if constexpr (NS == 1) x[i + q] = phi_prime_from<FM>(x[i + q], r[q]);
+          else pos |= (uint64_t)(x[i + q] > 0.0f ? 1u : 0u) << (i + q);
+          r[q] = ok ? r[q] : 0.0f;
+        }
+        if constexpr (NS == 1) rw[0][i / 2] = pack2<T>(r[0], r[1]);
+        else pack2_split<T>(r[0], r[1], rw[0][i / 2], rw[1][i / 2]);
+      }
+      auto phi_prime = [&](int i) -> float {
+        if constexpr (NS == 1) {
+          return x[i];
+        } else if constexpr (FM == kPhiIdentity) {
+          return 1.0f;
+        } else {
+          float h[2], l[2];
+          unpack2<T>(rw[0][i / 2], h[0], h[1]);
+          unpack2<T>(rw[1][i / 2], l[0], l[1]);
+          const float below = FM == kPhiRelu ? 0.0f : h[i & 1] + l[i & 1];
+          return (pos >> i) & 1u ? 1.0f : below;
+        }
+      };
+      if constexpr (NORM) {
+        const float den = denp + __shfl_xor(denp, 32) + eps;
+        const float ru = rup + __shfl_xor(rup, 32);
+        const float invden = 1.0f / den;
+        const float go = ru * invden;
+#pragma unroll
+        for (int i = 0; i < HALF; ++i) dr[i] = (dr[i] - go * zv(i)) * invden * phi_prime(i);
+        gsc = ok ? invden * beta : 0.0f;
+        e = ok ? -go * invden * beta : 0.0f;
+      } else {
+#pragma unroll
+        for (int i = 0; i < HALF; ++i) dr[i] *= phi_prime(i);
+      }
+#pragma unroll
+      for (int i = 0; i < HALF / 2; ++i) dqw[i] = pack2<T>(dr[2 * i], dr[2 * i + 1]);
     }
     // ---- phi(q), g beta / den and e beta take the tiles' places --------------------------------------
+    // bf16 carries each as two 8-bit levels.  The remainders take the same places once the rounded values have
+    // been read into operands (a wave's LDS operations retire in order), so no LDS beyond the ring is needed.
+    u32x4 glo[NS == 2 ? KS : 1];
+    uint32_t elo = 0;
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    rg.write_half_row(slot, 0, rr);
+    rg.write_half_row_words(slot, 0, rw[0]);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       const int chunk = rg.kg * KS + s;
@@ -452,36 +526,97 @@ bwd_qs16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, La
         for (int c = 0; c < 4; ++c) {
           float g0, g1;
           unpack2<T>(Bg[s][c], g0, g1);
-          w[c] = pack2<T>(g0 * gsc, g1 * gsc);
+          if constexpr (NS == 1) {
+            w[c] = pack2<T>(g0 * gsc, g1 * gsc);
+          } else {
+            uint32_t h, l;
+            pack2_split<T>(g0 * gsc, g1 * gsc, h, l);
+            w[c] = h;
+            glo[s][c] = l;
+          }
         }
         *reinterpret_cast<u32x4*>(rg.chunk_ptr(slot, 1, chunk)) = w;
       }
     }
-    if (rg.kg == 0) ecol[rg.tok] = (uint16_t)pack2<T>(e, 0.0f);
+    if constexpr (NS == 1) {
+      if (rg.kg == 0) ecol[rg.tok] = (uint16_t)pack2<T>(e, 0.0f);
+    } else {
+      uint32_t eh;
+      pack2_split<T>(e, 0.0f, eh, elo);
+      if (rg.kg == 0) ecol[rg.tok] = (uint16_t)eh;
+    }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     // ---- dS, dz: token-major operands by transposing reads --------------------------------------------
-    {
-      u32x4 bfrag[MT], bfe = u32x4{0, 0, 0, 0};
-      if (j16 == 0) bfe = *reinterpret_cast<const u32x4*>(ecol + 8 * g4);
+    auto read_a = [&](int a) {
+      const u32x2 r0 = lds_read_tr16(rg.tr_ptr(slot, 0, tr_row, 16 * a + tr_col));
+      const u32x2 r1 = lds_read_tr16(rg.tr_ptr(slot, 0, tr_row + 4, 16 * a + tr_col));
+      return u32x4{r0[0], r0[1], r1[0], r1[1]};
+    };
+    auto read_b = [&](int b) {
+      const u32x2 r0 = lds_read_tr16(rg.tr_ptr(slot, 1, tr_row, 16 * b + tr_col));
+      const u32x2 r1 = lds_read_tr16(rg.tr_ptr(slot, 1, tr_row + 4, 16 * b + tr_col));
+      return u32x4{r0[0], r0[1], r1[0], r1[1]};
+    };
+    auto read_e = [&]() {
+      u32x4 w = u32x4{0, 0, 0, 0};
+      if (j16 == 0) w = *reinterpret_cast<const u32x4*>(ecol + 8 * g4);
+      return w;
+    };
+    if constexpr (NS == 1) {
+      u32x4 bfrag[MT];
+      const u32x4 bfe = read_e();
 #pragma unroll
-      for (int b = 0; b < MT; ++b) {
-        const u32x2 r0 = lds_read_tr16(rg.tr_ptr(slot, 1, tr_row, 16 * b + tr_col));
-        const u32x2 r1 = lds_read_tr16(rg.tr_ptr(slot, 1, tr_row + 4, 16 * b + tr_col));
-        bfrag[b] = u32x4{r0[0], r0[1], r1[0], r1[1]};
-      }
+      for (int b = 0; b < MT; ++b) bfrag[b] = read_b(b);
 #pragma unroll
       for (int a = 0; a < MT; ++a) {
-        const u32x2 r0 = lds_read_tr16(rg.tr_ptr(slot, 0, tr_row, 16 * a + tr_col));
-        const u32x2 r1 = lds_read_tr16(rg.tr_ptr(slot, 0, tr_row + 4, 16 * a + tr_col));
-        const u32x4 afrag = u32x4{r0[0], r0[1], r1[0], r1[1]};
+        const u32x4 afrag = read_a(a);
 #pragma unroll
         for (int b = 0; b < MT; ++b) accS[a][b] = mfma_16x16x32<T>(afrag, bfrag[b], accS[a][b]);
         accZ[a] = mfma_16x16x32<T>(afrag, bfe, accZ[a]);
       }
+    } else {
+      // rounded x rounded, remainder x rounded, rounded x remainder; the remainders' operands live one at a time
+      u32x4 ah[MT], bh[MT];
+      const u32x4 beh = read_e();
+#pragma unroll
+      for (int b = 0; b < MT; ++b) bh[b] = read_b(b);
+#pragma unroll
+      for (int a = 0; a < MT; ++a) ah[a] = read_a(a);
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      rg.write_half_row_words(slot, 0, rw[NS - 1]);
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const int chunk = rg.kg * KS + s;
+        if (chunk < CPR) *reinterpret_cast<u32x4*>(rg.chunk_ptr(slot, 1, chunk)) = glo[s];
+      }
+      if (rg.kg == 0) ecol[rg.tok] = (uint16_t)elo;
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+#pragma unroll
+        for (int b = 0; b < MT; ++b) accS[a][b] = mfma_16x16x32<T>(ah[a], bh[b], accS[a][b]);
+        accZ[a] = mfma_16x16x32<T>(ah[a], beh, accZ[a]);
+      }
+#pragma unroll
+      for (int a = 0; a < MT; ++a) {
+        const u32x4 al = read_a(a);
+#pragma unroll
+        for (int b = 0; b < MT; ++b) accS[a][b] = mfma_16x16x32<T>(al, bh[b], accS[a][b]);
+        accZ[a] = mfma_16x16x32<T>(al, beh, accZ[a]);
+      }
+#pragma unroll
+      for (int b = 0; b < MT; ++b) {
+        const u32x4 bl = read_b(b);
+#pragma unroll
+        for (int a = 0; a < MT; ++a) accS[a][b] = mfma_16x16x32<T>(ah[a], bl, accS[a][b]);
+      }
+      const u32x4 bel = read_e();
+#pragma unroll
+      for (int a = 0; a < MT; ++a) accZ[a] = mfma_16x16x32<T>(ah[a], bel, accZ[a]);
     }
     // ---- dq takes the Q tile's place and leaves -----------------------------------------------------------
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    rg.write_half_row(slot, 0, dr);
+    rg.write_half_row_words(slot, 0, dqw);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     rg.store_tile(tile, slot, 0, dQh, ldq.row);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");

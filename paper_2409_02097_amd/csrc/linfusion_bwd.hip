@@ -15,6 +15,7 @@ namespace {
 
 struct BwdPlan {
   int splits, blk_reduce, apply_wgs, blk_apply;
+  int apply1_wgs, blk_apply1;   // launch shape of the gradient kernels of which one workgroup fills a CU
   int gsplits, gblk_reduce;   // the state-gradient reduction's own launch shape
   int most;                   // partial states per head the workspace has room for
   bool wide;                  // widths above 80: the composed pass of linfusion_bwdw.hip (its own workspace layout)
@@ -56,10 +57,13 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
                         lfh::env_int("LINFUSION_BWD_REDUCE_BLK", 16), &p->gblk_reduce);
   p->apply_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY_WGS", (mid ? 2 : 4) * lfh::num_cu()),
                           lfh::env_int("LINFUSION_BWD_APPLY_BLK", 8), &p->blk_apply);
+  p->apply1_wgs = per_head(lfh::env_int("LINFUSION_BWD_APPLY1_WGS", lfh::num_cu()),
+                           lfh::env_int("LINFUSION_BWD_APPLY1_BLK", 8), &p->blk_apply1);
   p->ne = (size_t)d * d + d;
   auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
   int most = p->splits > p->gsplits ? p->splits : p->gsplits;
   if (p->apply_wgs > most) most = p->apply_wgs;   // the merged dQ + state-gradient kernel writes one partial each
+  if (p->apply1_wgs > most) most = p->apply1_wgs;
   p->most = most;
   p->ws_partials = up((size_t)BH * most * p->ne * sizeof(float));
   p->ws_state = up((size_t)BH * p->ne * sizeof(float));
@@ -160,6 +164,27 @@ int launch_q_rows(const BwdArgs& a, const float* stateS, lf::f32x2* scal) {
   bwd_q16_rows<T, D, FM, NORM, W><<<dim3((unsigned)wgs, (unsigned)groups), dim3(64 * W), lds, a.st>>>(
       (const u32x4*)a.q, a.lq, (const u32x4*)a.g, a.lg, (u32x4*)a.dq, a.ldq, gpb, stateS, scal, a.eps, a.N, (int)blk);
   return LINFUSION_OK;
+}
+
+// whether q_rows below takes the dQ launch (bf16 has no row-piece form of the merged kernel and keeps the separate
+// row-piece kernels wherever they would be picked)
+template <int D>
+bool q_rows_wanted(const BwdArgs& a) {
+  constexpr int CPR = D / 8;
+  if constexpr ((D * 2) % 128 == 0) {
+    return false;
+  } else {
+    if (a.lq.head != CPR || a.lg.head != CPR || a.ldq.head != CPR) return false;
+    const int mode = lfh::env_int("LINFUSION_BWD_ROWS", 1);
+    if (mode == 2 || (mode != 3 && !rows_pay(a, D))) return false;
+    if constexpr (D <= 48) {
+      if (a.H % 8 == 0) return true;
+    }
+    if constexpr (D <= 56 || D == 80) {
+      if (a.H % 4 == 0) return true;
+    }
+    return false;
+  }
 }
 
 template <typename T, int D, int FM, bool NORM>
@@ -289,15 +314,24 @@ int run_bwd(const BwdArgs& a) {
     if (rcs != LINFUSION_OK) return rcs;
     combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, nparts, NE, stateS);
   }
-  // fp16 up to d = 48: dQ and the state gradient in one pass over Q and dout (registers allow it there)
-  constexpr bool kMerged = NSplit<T>::value == 1 && D <= 48;
+  // dQ and the state gradient in one pass over Q and dout.  Its row-piece form exists for fp16 up to d = 48; where
+  // the layout asks for row-piece kernels and that form is missing, the separate row-piece kernels are kept.
+  constexpr bool kMerged = !(NSplit<T>::value == 2 && D == 80);   // bf16 at d = 80: measured slower than the separate kernels
+  constexpr bool kQsRows = NSplit<T>::value == 1 && D <= 48;
   if constexpr (kMerged) {
-    if (lfh::env_int("LINFUSION_BWD_MERGED", 1) == 1) {
-      if (!allow_lds(bwd_qs16<T, D, FM, NORM>, lds_a + 256)) return LINFUSION_ERR_HIP;
-      int nparts = p.apply_wgs, rcq = LINFUSION_OK;
+    bool merged = lfh::env_int("LINFUSION_BWD_MERGED", 1) == 1;
+    if (!kQsRows && q_rows_wanted<D>(a)) merged = false;
+    if (merged) {
+      constexpr int lds_qs = qs_lds_bytes<T, D>();
+      static_assert(lds_qs <= 160 * 1024, "workgroup LDS limit of the device");
+      if (!allow_lds(bwd_qs16<T, D, FM, NORM>, lds_qs)) return LINFUSION_ERR_HIP;
+      const bool two = qs_two_per_cu<T, D>();
+      const int qs_wgs = two ? p.apply_wgs : p.apply1_wgs, qs_blk = two ? p.blk_apply : p.blk_apply1;
+      if (qs_wgs > p.most) return LINFUSION_ERR_WORKSPACE;   // one partial state per workgroup must fit
+      int nparts = qs_wgs, rcq = LINFUSION_OK;
       if (!qs_rows<T, D, FM, NORM>(a, stateS, partials, &nparts, &rcq))
-        bwd_qs16<T, D, FM, NORM><<<ga, blk, lds_a + 256, st>>>(Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, partials,
-                                                               a.eps, a.N, p.blk_apply);
+        bwd_qs16<T, D, FM, NORM><<<dim3(qs_wgs, (unsigned)BH), blk, lds_qs, st>>>(
+            Q, a.lq, G, a.lg, (u32x4*)a.dq, a.ldq, stateS, partials, a.eps, a.N, qs_blk);
       if (rcq != LINFUSION_OK) return rcq;
       combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, nparts, NE, stateD);
       int rck = LINFUSION_OK;

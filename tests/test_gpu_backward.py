@@ -41,6 +41,8 @@ SHAPES = [
     (1, 2, 300, 32, "f16"), (1, 2, 300, 48, "f16"), (1, 1, 300, 56, "f16"), (1, 2, 700, 80, "f16"),
     (1, 2, 1, 64, "bf16"), (2, 2, 33, 40, "bf16"), (1, 2, 1000, 64, "bf16"), (1, 3, 4099, 40, "bf16"),
     (1, 2, 300, 24, "bf16"), (1, 1, 200, 48, "bf16"), (1, 2, 600, 80, "bf16"), (2, 8, 4096, 40, "f16"),
+    (1, 2, 515, 8, "bf16"), (1, 2, 130, 16, "bf16"), (1, 2, 300, 32, "bf16"), (2, 8, 4096, 40, "bf16"),
+    (1, 1, 2100, 48, "bf16"), (1, 2, 300, 56, "bf16"),
 ]
 
 
@@ -54,15 +56,16 @@ def test_backward_matches_oracle(B, H, N, d, dtype):
     print(f"  worst max-norm ratio {worst:.2e}", flush=True)
 
 
-@pytest.mark.parametrize("B,H,N,d", [(1, 2, 1000, 40), (2, 2, 333, 16), (1, 1, 4099, 48)])
-def test_backward_separate_kernels_for_fp16_small_widths(B, H, N, d, monkeypatch, tuning):
-    """fp16 with d <= 48 normally takes the merged dQ + state-gradient kernel; the separate kernels (what bf16
-    and wider heads use) must give the same gradients to tolerance."""
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,H,N,d", [(1, 2, 1000, 40), (2, 2, 333, 16), (1, 1, 4099, 48), (1, 2, 700, 64), (1, 1, 300, 80)])
+def test_backward_separate_kernels(B, H, N, d, dtype, monkeypatch, tuning):
+    """Contiguous heads normally take the merged dQ + state-gradient kernel; the separate kernels (kept for the
+    token-major layouts without a row-piece form of the merged one) must give the same gradients to tolerance."""
     monkeypatch.setenv("LINFUSION_BWD_MERGED", "2")
-    q, k, v = wl.make_qkv(B, H, N, d, "f16", idx=84, device="cpu")
-    g = wl.draw((B, H, N, d), wl.BASE_SEED + 84777, "f16", "cpu")
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=84, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 84777, dtype, "cpu")
     outs = _run(q, k, v, g)
-    _check(outs, q, k, v, g, "f16", 0, 1e-6, True, f"bwd separate kernels N={N} d={d}")
+    _check(outs, q, k, v, g, dtype, 0, 1e-6, True, f"bwd separate kernels N={N} d={d} {dtype}")
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
