@@ -6,11 +6,16 @@
 //     dr_i = (u_i - go_i z) / den_i ,   dq = dr * phi'(q)
 //     e_i  = -go_i / den_i ,            dS = R^T (g / den) ,  dz = R^T e
 //     dp_j = dS v_j + dz ,              dk = dp * phi'(k) ,   dv_j = dS^T p_j
-// (un-normalized: den = 1, go = e = 0).  Launches (fp16 with d <= 48 merges the second and third: bwd_qs16):
-//     state_reduce16 + combine_state    S, z                         (the forward kernels)
+// (un-normalized: den = 1, go = e = 0).  Launches:
+//     state_reduce16 + combine_state    S, z                         (the forward kernels; skipped when the
+//                                                                      forward pass's state is handed in)
+//     bwd_qs16 + combine_state          reads Q, g: writes dQ, and dS, dz as split partials
+//     bwd_kv16                          reads K, V: writes dK, dV    (large fp16 problems: bwd_pack_kv16 +
+//                                                                      bwd_kv16_packed, short-lived workgroups)
+// The merged bwd_qs16 has no row-piece form for bf16 and d > 48; token-major tensors whose head rows are no whole
+// cache lines take two kernels in its place there (and bf16 at d = 80 everywhere, where that measured faster):
 //     bwd_q16                           reads Q, g: writes dQ and per token {1 / den_i, e_i}
 //     bwd_state16 + combine_state       reads Q, g and those scalars: dS, dz
-//     bwd_kv16                          reads K, V: writes dK, dV
 // The two apply-shaped kernels use the LDS-DMA ring of apply16_dma with two tensors per slot; the
 // reduction is state_reduce16 with phi(Q) in the place of phi(K), g / den in the place of V and e_i in the
 // place of the ones column.  Every tensor is addressed through a Layout (contiguous or strided views); the
@@ -360,10 +365,13 @@ bwd_q16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, Lay
 }
 
 // ==========================================================================================
-// bwd_qs16 (fp16): bwd_q16 and bwd_state16 in one pass over Q and g.  After a tile's dq is known, the wave
+// bwd_qs16: bwd_q16 and bwd_state16 in one pass over Q and g.  After a tile's dq is known, the wave
 // overwrites the Q tile in its LDS slot with phi(q) and the g tile with g beta / den (16-bit), keeps
 // e_i beta in a 32-entry column, and accumulates dS += phi(q)^T (g beta / den), dz += phi(q)^T (e beta) with
 // transposing LDS reads exactly as the reductions do; then dq takes the Q tile's place and leaves.
+// bf16 needs two 8-bit levels of each of the three: the rounded values go first and are read into operands,
+// then the remainders take the same places (no LDS beyond the ring), and three products per block follow
+// (rounded x rounded, remainder x rounded, rounded x remainder).
 // At the end the four waves' accumulators are summed in a fixed order and written (divided by beta) as
 // this workgroup's partial: [B*H][gridDim.x][D*D + D], for combine_state.  No per-token scalars in memory,
 // two tensor passes fewer.  LDS: qs_lds_bytes<T, D>().
@@ -662,30 +670,26 @@ bwd_qs16(const u32x4* __restrict__ Q, Layout lq, const u32x4* __restrict__ G, La
 
 // ==========================================================================================
 // bwd_kv16: dK and dV.  grid = (wgs, B*H), block = 256.  `dstate`: [B*H][D*D + D], dS row-major then dz.
+// bwd_kv16_packed: the same stream from operands that bwd_pack_kv16 prepared once per head, so that a
+// workgroup's start-up is a few coalesced loads and a launch can use many short-lived workgroups (see
+// apply16_packed: the chip then reads and writes one narrow moving window of memory).
 // ==========================================================================================
+// What bwd_pack_kv16 leaves per head: {1 / scale} and dz in a 1 KiB header, then the lanes' operands of dS^T and dS
+template <typename T, int D> struct PackKV16 {
+  static constexpr int kHeaderBytes = 1024;
+  static constexpr int kDzOffset = 256;   // bytes; D floats
+  static constexpr int kFrags = NSplit<T>::value * BwdCfg<D>::kMTB * Shape16<D>::kKS;   // per lane and matrix
+  static constexpr int kHeadBytes = kHeaderBytes + 2 * kFrags * 64 * 16;
+  static_assert(kDzOffset + D * 4 <= kHeaderBytes, "dz fits the header");
+};
+
 template <typename T, int D, int FM>
-__global__ void __launch_bounds__(kThreads)
-bwd_kv16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, u32x4* __restrict__ dK,
-         u32x4* __restrict__ dV, Layout ldkv, const float* __restrict__ dstate, long long N, int tiles_per_block) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+LF_DEV void bwd_kv_stream(Ring2<T, D>& rg, const u32x4 (&A1)[NSplit<T>::value][BwdCfg<D>::kMTB][Shape16<D>::kKS],
+                          const u32x4 (&A2)[NSplit<T>::value][BwdCfg<D>::kMTB][Shape16<D>::kKS],
+                          const float (&dzo)[Shape16<D>::kHalf], float inv_aS, u32x4* dKh, u32x4* dVh, int rso) {
   using RG = Ring2<T, D>;
   constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF, NL = RG::NL, R = RG::R, CPR = RG::CPR;
   constexpr int SN = 2 * NL;
-  const long long bh = blockIdx.y;
-  RG rg(K + lkv.slice(bh), lkv.row, V + lkv.slice(bh), lkv.row, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
-  u32x4* dKh = dK + ldkv.slice(bh);
-  u32x4* dVh = dV + ldkv.slice(bh);
-  rg.prefetch();
-
-  const float aS = rg.stage_state(dstate + bh * (D * D + D));
-  u32x4 A1[NS][MTB][KS], A2[NS][MTB][KS];
-  rg.template build_A<true>(aS, A1);        // dv = dS^T p
-  rg.template build_A<false>(aS, A2);       // dp = dS v (+ dz)
-  float dzo[HALF];
-  rg.load_vec(dzo);
-  const float inv_aS = 1.0f / aS;
-  __syncthreads();
-
   int slot = 0, iter = 0;
   while (rg.it.valid()) {
     const long long tile = rg.it.t;
@@ -733,13 +737,101 @@ bwd_kv16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, u
     rg.write_half_row(slot, 0, x);
     rg.write_half_row(slot, 1, o);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    rg.store_tile(tile, slot, 0, dKh, ldkv.row);
-    rg.store_tile(tile, slot, 1, dVh, ldkv.row);
+    rg.store_tile(tile, slot, 0, dKh, rso);
+    rg.store_tile(tile, slot, 1, dVh, rso);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     rg.it.next();
     rg.ahead.next();
     slot = slot + 1 == R ? 0 : slot + 1;
   }
+}
+
+template <typename T, int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+bwd_kv16(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, u32x4* __restrict__ dK,
+         u32x4* __restrict__ dV, Layout ldkv, const float* __restrict__ dstate, long long N, int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using RG = Ring2<T, D>;
+  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF;
+  const long long bh = blockIdx.y;
+  RG rg(K + lkv.slice(bh), lkv.row, V + lkv.slice(bh), lkv.row, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  rg.prefetch();
+
+  const float aS = rg.stage_state(dstate + bh * (D * D + D));
+  u32x4 A1[NS][MTB][KS], A2[NS][MTB][KS];
+  rg.template build_A<true>(aS, A1);        // dv = dS^T p
+  rg.template build_A<false>(aS, A2);       // dp = dS v (+ dz)
+  float dzo[HALF];
+  rg.load_vec(dzo);
+  __syncthreads();
+  bwd_kv_stream<T, D, FM>(rg, A1, A2, dzo, 1.0f / aS, dK + ldkv.slice(bh), dV + ldkv.slice(bh), ldkv.row);
+}
+
+// grid = (B*H), block = 256, dynamic LDS BwdCfg<D>::lds_bytes(): the operands of bwd_kv16 for one head, built with
+// that kernel's own prologue and written by wave 0 in lane order.
+template <typename T, int D>
+__global__ void __launch_bounds__(kThreads)
+bwd_pack_kv16(const float* __restrict__ dstate, unsigned char* __restrict__ packed) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using RG = Ring2<T, D>;
+  using PK = PackKV16<T, D>;
+  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB;
+  const long long bh = blockIdx.x;
+  RG rg(nullptr, 0, nullptr, 0, 0, kWavesPerWG, 0, 1, smem);
+  const float aS = rg.stage_state(dstate + bh * (D * D + D));
+  u32x4 A1[NS][MTB][KS], A2[NS][MTB][KS];
+  rg.template build_A<true>(aS, A1);
+  rg.template build_A<false>(aS, A2);
+  unsigned char* dst = packed + bh * PK::kHeadBytes;
+  if (rg.wave == 0) {
+    u32x4* frag = reinterpret_cast<u32x4*>(dst + PK::kHeaderBytes);
+#pragma unroll
+    for (int l = 0; l < NS; ++l)
+#pragma unroll
+      for (int t = 0; t < MTB; ++t)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          frag[((l * MTB + t) * KS + s) * 64 + rg.lane] = A1[l][t][s];
+          frag[(PK::kFrags + (l * MTB + t) * KS + s) * 64 + rg.lane] = A2[l][t][s];
+        }
+    const float* st = reinterpret_cast<const float*>(smem + BwdCfg<D>::kStageOffset) + D * D;
+    float* dz = reinterpret_cast<float*>(dst + PK::kDzOffset);
+    for (int i = rg.lane; i < D; i += 64) dz[i] = st[i];
+    if (rg.lane == 0) *reinterpret_cast<float*>(dst) = 1.0f / aS;
+  }
+}
+
+// grid = (wgs, B*H), block = 256, dynamic LDS = the ring (BwdCfg<D>::kRing slots); no staging, no workgroup barrier
+template <typename T, int D, int FM>
+__global__ void __launch_bounds__(kThreads)
+bwd_kv16_packed(const u32x4* __restrict__ K, const u32x4* __restrict__ V, Layout lkv, u32x4* __restrict__ dK,
+                u32x4* __restrict__ dV, Layout ldkv, const unsigned char* __restrict__ packed, long long N,
+                int tiles_per_block) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using RG = Ring2<T, D>;
+  using PK = PackKV16<T, D>;
+  constexpr int NS = RG::NS, KS = RG::KS, MTB = RG::MTB, HALF = RG::HALF;
+  const long long bh = blockIdx.y;
+  RG rg(K + lkv.slice(bh), lkv.row, V + lkv.slice(bh), lkv.row, N, tiles_per_block, blockIdx.x, gridDim.x, smem);
+  rg.prefetch();
+  const unsigned char* src = packed + bh * PK::kHeadBytes;
+  const u32x4* frag = reinterpret_cast<const u32x4*>(src + PK::kHeaderBytes);
+  u32x4 A1[NS][MTB][KS], A2[NS][MTB][KS];
+#pragma unroll
+  for (int l = 0; l < NS; ++l)
+#pragma unroll
+    for (int t = 0; t < MTB; ++t)
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        A1[l][t][s] = frag[((l * MTB + t) * KS + s) * 64 + rg.lane];
+        A2[l][t][s] = frag[(PK::kFrags + (l * MTB + t) * KS + s) * 64 + rg.lane];
+      }
+  const float* dz = reinterpret_cast<const float*>(src + PK::kDzOffset);
+  float dzo[HALF];
+#pragma unroll
+  for (int i = 0; i < HALF; ++i) dzo[i] = dz[rg.kg * HALF + i];
+  const float inv_aS = *reinterpret_cast<const float*>(src);
+  bwd_kv_stream<T, D, FM>(rg, A1, A2, dzo, inv_aS, dK + ldkv.slice(bh), dV + ldkv.slice(bh), ldkv.row);
 }
 
 // ==========================================================================================

@@ -19,8 +19,17 @@ struct BwdPlan {
   int gsplits, gblk_reduce;   // the state-gradient reduction's own launch shape
   int most;                   // partial states per head the workspace has room for
   bool wide;                  // widths above 80: the composed pass of linfusion_bwdw.hip (its own workspace layout)
-  size_t ne, ws_partials, ws_state, ws_scal, ws_total;
+  size_t ne, ws_partials, ws_state, ws_scal, ws_pack, ws_total;
+  bool kv_packed;             // dK / dV from operands packed once per head, many short-lived workgroups
+  int kvp_wgs, kvp_blk;
 };
+
+// bytes per head of bwd_pack_kv16's output (PackKV16<T, D>::kHeadBytes, kept in step by a static_assert at the launch)
+size_t kv_pack_head_bytes(int d, int dtype) {
+  const int ns = dtype == LINFUSION_DTYPE_BF16 ? 2 : 1;
+  const int mtb = (d / 2 + 15) / 16, ks = (d / 8 + 1) / 2;
+  return 1024 + (size_t)2 * ns * mtb * ks * 64 * 16;
+}
 
 bool bwd_supported_d(int d) { return (d >= 8 && d <= 64 && d % 8 == 0) || d == 80; }
 
@@ -68,7 +77,19 @@ int make_bwd_plan(int B, int H, long long N, int d, int dtype, BwdPlan* p) {
   p->ws_partials = up((size_t)BH * most * p->ne * sizeof(float));
   p->ws_state = up((size_t)BH * p->ne * sizeof(float));
   p->ws_scal = up((size_t)BH * (size_t)N * 2 * sizeof(float));
-  p->ws_total = p->ws_partials + 2 * p->ws_state + p->ws_scal;
+  p->ws_pack = up((size_t)BH * kv_pack_head_bytes(d, dtype));
+  p->ws_total = p->ws_partials + 2 * p->ws_state + p->ws_scal + p->ws_pack;
+  // Large fp16 problems: dK / dV as many short-lived workgroups of a few tiles each (the hardware deals them out in
+  // order, so the chip reads and writes one narrow moving window of memory), which needs a start-up of a few loads:
+  // the head's operands are packed once.  Measured at 1.3 GB per tensor, long-lived / 32 tiles per short-lived
+  // workgroup: fp16 d = 40 1.92 / 1.88 ms per backward call; d = 64 2.02 / 2.03, d = 80 1.11 / 1.12, bf16 d = 40
+  // 2.58 / 2.56 (operands two to four times as large): taken for fp16 up to d = 48.
+  const int pk = lfh::env_int("LINFUSION_BWD_KV_PACKED", 1);   // 1: by size and type, 2: never, 3: always
+  p->kv_packed = pk == 3 || (pk == 1 && !mid && dtype == LINFUSION_DTYPE_F16 && d <= 48);
+  p->kvp_blk = (lfh::env_int("LINFUSION_BWD_KVP_BLK", 32) + lf::kWavesPerWG - 1) / lf::kWavesPerWG * lf::kWavesPerWG;
+  if (p->kvp_blk < lf::kWavesPerWG) p->kvp_blk = lf::kWavesPerWG;
+  const long long kw = (n_tiles + p->kvp_blk - 1) / p->kvp_blk;
+  p->kvp_wgs = (int)(kw < 1048576 ? kw : 1048576);   // blocks beyond that are taken cyclically
   return LINFUSION_OK;
 }
 
@@ -278,6 +299,34 @@ bool kv_rows(const BwdArgs& a, const float* stateD, int* rc) {
   return false;
 }
 
+// dK, dV by the per-head kernel: long-lived workgroups that stage the state gradient themselves, or (large fp16
+// problems) operands packed once per head and many short-lived workgroups
+template <typename T, int D, int FM>
+int launch_kv(const BwdArgs& a, const float* stateD) {
+  using namespace lf;
+  const BwdPlan& p = *a.p;
+  const long long BH = (long long)a.B * a.H;
+  constexpr int lds_a = BwdCfg<D>::lds_bytes();
+  const u32x4* K = (const u32x4*)a.k;
+  const u32x4* V = (const u32x4*)a.v;
+  if (p.kv_packed) {
+    using PK = PackKV16<T, D>;
+    unsigned char* packed = a.ws + p.ws_partials + 2 * p.ws_state + p.ws_scal;
+    if ((size_t)PK::kHeadBytes != kv_pack_head_bytes(D, NSplit<T>::value == 2 ? LINFUSION_DTYPE_BF16 : LINFUSION_DTYPE_F16))
+      return LINFUSION_ERR_WORKSPACE;
+    constexpr int lds_ring = BwdCfg<D>::kRing * kWavesPerWG * BwdCfg<D>::kSlotBytes;
+    if (!allow_lds(bwd_pack_kv16<T, D>, lds_a) || !allow_lds(bwd_kv16_packed<T, D, FM>, lds_ring)) return LINFUSION_ERR_HIP;
+    bwd_pack_kv16<T, D><<<dim3((unsigned)BH), dim3(kThreads), lds_a, a.st>>>(stateD, packed);
+    bwd_kv16_packed<T, D, FM><<<dim3((unsigned)p.kvp_wgs, (unsigned)BH), dim3(kThreads), lds_ring, a.st>>>(
+        K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, packed, a.N, p.kvp_blk);
+    return LINFUSION_OK;
+  }
+  if (!allow_lds(bwd_kv16<T, D, FM>, lds_a)) return LINFUSION_ERR_HIP;
+  bwd_kv16<T, D, FM><<<dim3(p.apply_wgs, (unsigned)BH), dim3(kThreads), lds_a, a.st>>>(
+      K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N, p.blk_apply);
+  return LINFUSION_OK;
+}
+
 template <typename T, int D, int FM, bool NORM>
 int run_bwd(const BwdArgs& a) {
   using namespace lf;
@@ -335,9 +384,7 @@ int run_bwd(const BwdArgs& a) {
       if (rcq != LINFUSION_OK) return rcq;
       combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, nparts, NE, stateD);
       int rck = LINFUSION_OK;
-      if (!kv_rows<T, D, FM>(a, stateD, &rck))
-        bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N,
-                                                   p.blk_apply);
+      if (!kv_rows<T, D, FM>(a, stateD, &rck)) rck = launch_kv<T, D, FM>(a, stateD);
       if (rck != LINFUSION_OK) return rck;
       return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
     }
@@ -351,8 +398,7 @@ int run_bwd(const BwdArgs& a) {
                                                                                   partials, a.N, p.gblk_reduce);
   combine_state<0><<<gc, dim3(kCombineThreads), 0, st>>>(partials, p.gsplits, NE, stateD);
   int rck = LINFUSION_OK;
-  if (!kv_rows<T, D, FM>(a, stateD, &rck))
-    bwd_kv16<T, D, FM><<<ga, blk, lds_a, st>>>(K, V, a.lkv, (u32x4*)a.dk, (u32x4*)a.dv, a.ldkv, stateD, a.N, p.blk_apply);
+  if (!kv_rows<T, D, FM>(a, stateD, &rck)) rck = launch_kv<T, D, FM>(a, stateD);
   if (rck != LINFUSION_OK) return rck;
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }

@@ -68,6 +68,24 @@ def test_backward_separate_kernels(B, H, N, d, dtype, monkeypatch, tuning):
     _check(outs, q, k, v, g, dtype, 0, 1e-6, True, f"bwd separate kernels N={N} d={d} {dtype}")
 
 
+@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 2, 1000, 40, "f16"), (2, 3, 4099, 40, "f16"), (1, 2, 33, 64, "f16"),
+                                            (1, 1, 2100, 80, "f16"), (1, 2, 777, 8, "f16"), (1, 2, 1000, 40, "bf16"),
+                                            (1, 2, 515, 64, "bf16"), (1, 1, 1, 48, "f16"), (1, 2, 5000, 56, "bf16")])
+def test_backward_kv_from_packed_operands(B, H, N, d, dtype, monkeypatch, tuning):
+    """Large fp16 problems compute dK, dV with many short-lived workgroups from operands packed once per head; forced
+    here at small sizes: the oracle's gradients, and bit for bit what the long-lived workgroups give."""
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=85, device="cpu")
+    g = wl.draw((B, H, N, d), wl.BASE_SEED + 85777, dtype, "cpu")
+    monkeypatch.setenv("LINFUSION_BWD_KV_PACKED", "2")
+    plain = _run(q, k, v, g)
+    monkeypatch.setenv("LINFUSION_BWD_KV_PACKED", "3")
+    monkeypatch.setenv("LINFUSION_BWD_KVP_BLK", "8")
+    outs = _run(q, k, v, g)
+    _check(outs, q, k, v, g, dtype, 0, 1e-6, True, f"bwd packed kv N={N} d={d} {dtype}")
+    for got, want in zip(outs, plain):
+        assert torch.equal(got.view(torch.int16), want.view(torch.int16))
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("fm,normalize", [(1, True), (2, True), (0, False), (1, False)])
 def test_backward_other_feature_maps_and_unnormalized(dtype, fm, normalize):
