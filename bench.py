@@ -199,16 +199,22 @@ def latency_rows(names, paths=(("auto", 0),), steps=200):
                 continue
             for mode in ("hot", "cold"):
                 use = sets[:1] if mode == "hot" else sets
+                # arguments marshalled once per buffer set (the binding's per-call checks cost the host ~5 us,
+                # more than the difference between the paths at these sizes); the status of every call is checked
+                calls = [lf.linfusion_attn_fwd_ex_bound(q, k, v, o, lf.PHI_ELU_PLUS_ONE, wl.EPS, flags, ws)
+                         for q, k, v, o in use]
                 for i in range(20):
-                    q, k, v, o = use[i % len(use)]
-                    lf.linfusion_attn_fwd_ex(q, k, v, o, lf.PHI_ELU_PLUS_ONE, wl.EPS, flags, ws)
+                    if calls[i % len(calls)]() != 0:
+                        raise RuntimeError(f"{name}: the library returned an error")
                 torch.cuda.synchronize()
+                bad = 0
                 t0 = time.perf_counter()
                 for i in range(steps):
-                    q, k, v, o = use[i % len(use)]
-                    lf.linfusion_attn_fwd_ex(q, k, v, o, lf.PHI_ELU_PLUS_ONE, wl.EPS, flags, ws)
+                    bad |= calls[i % len(calls)]()
                 torch.cuda.synchronize()
                 us = (time.perf_counter() - t0) / steps * 1e6
+                if bad:
+                    raise RuntimeError(f"{name}: the library returned an error")
                 pre = "" if label == "auto" else label + "_"
                 row[f"{pre}{mode}_us"] = round(us, 2)
                 row[f"{pre}{mode}_tokens_per_s"] = round(B * N / us * 1e6)

@@ -338,6 +338,25 @@ def linfusion_attn_fwd_ex(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps
     return rc
 
 
+def linfusion_attn_fwd_ex_bound(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6,
+                                flags: int = FLAG_NONE, workspace=None, stream=None):
+    """The same call as linfusion_attn_fwd_ex with the marshalling done once: returns a function of no arguments
+    that enqueues the call on the stream current now (or `stream`) and returns the status.  For loops that repeat
+    one call on the same buffers: checking four tensors and looking up the stream costs this binding about 5 us a
+    call, as much as two of the library's three kernel launches, which matters where a whole call takes 15 us.
+    The tensors and the workspace must stay alive as long as the function is used."""
+    B, H, N, d = _check_layout(q, k, v, out)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    fn = library().linfusion_attn_fwd_ex
+    args = (q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, N, d, _dtype_code(q), feature_map, eps,
+            flags, ws_ptr, ws_bytes, _stream_ptr(stream))
+
+    def call() -> int:
+        return fn(*args)
+    return call
+
+
 def linfusion_attn_fwd_static(q, k, v, out, feature_map: int = PHI_ELU_PLUS_ONE, eps: float = 1e-6,
                               flags: int = FLAG_NONE, stream=None, check: bool = True) -> int:
     """out <- mixer(q, k, v) with the library's fixed scratch array: no workspace argument, no allocation."""

@@ -347,14 +347,18 @@ struct ApplyDma {
   }
 
   // Whole workgroup: stages one head's state in LDS; the waves with `keep` build their operands from it.
-  // STAGED: the state already lies in the staging area (the workgroup computed it itself); `state` is not read.
+  // STAGED: the state already lies in the staging area (the workgroup computed it itself), S row-major as in
+  // memory; `state` is not read.  Otherwise S is staged transposed -- st[col * D + ch], then z[ch] -- so that the
+  // eight consecutive feature channels of one output column that make up a lane's operand are two 16-byte LDS
+  // reads, all of them issued before the first is used (read one by one, row-major, with the slot tests around
+  // each read, the operand build took 3-5 us per workgroup: a fifth of a small call).
   template <bool COHERENT = false, bool STAGED = false>
   LF_DEV void load_state(const float* state, float eps, bool keep) {
     // ---- prologue: state -> LDS, maxima, power-of-two scales, A fragments -------------------------
     float* st = reinterpret_cast<float*>(smem + kStageOffset);
     float* redmax = st + NE;
     float mS = 0.0f, mz = 0.0f;
-    static_assert(NE % 4 == 0 && (D * DV) % 4 == 0, "the state is moved four floats at a time");
+    static_assert(NE % 4 == 0 && (D * DV) % 4 == 0 && DV % 4 == 0, "the state is moved four floats of one row at a time");
     for (int e = threadIdx.x; e < NE / 4; e += NT) {
       f32x4 x;
       if constexpr (STAGED) {
@@ -365,7 +369,15 @@ struct ApplyDma {
       } else {
         x = reinterpret_cast<const f32x4*>(state)[e];
       }
-      if constexpr (!STAGED) reinterpret_cast<f32x4*>(st)[e] = x;
+      if constexpr (!STAGED) {
+        if (e < D * DV / 4) {
+          const int ch = (4 * e) / DV, col = (4 * e) % DV;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) st[(col + i) * D + ch] = x[i];
+        } else {
+          reinterpret_cast<f32x4*>(st)[e] = x;
+        }
+      }
       const float m4 = fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3])));
       if (e < D * DV / 4) mS = fmaxf(mS, m4); else mz = fmaxf(mz, m4);
     }
@@ -387,29 +399,44 @@ struct ApplyDma {
       c1_az = az;
       const int m = lane & 31;
       const int hv = (m >> 2) & 1;
+      // per output tile: the raw fp32 values of its fragments first (unconditional reads from clamped, valid
+      // places), then the arithmetic
 #pragma unroll
       for (int t = 0; t < MT2; ++t) {
         const int slot = 16 * t + 4 * (m >> 3) + (m & 3);
+        const bool isS = slot < HALF;
+        const bool isZ = NORM && slot == HALF, zrem = NORM && slot == HALF + 1;
+        const int col = isS ? hv * HALF + slot : 0;
+        const float sc = isS ? aS : az;
+        float raw[KS][8];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
           const int chunk = kg * KS + s;
+          const int ch0 = (chunk < CPR ? chunk : 0) * 8;
+          if constexpr (STAGED) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) raw[s][j] = isS ? st[(ch0 + j) * DV + col] : st[D * DV + ch0 + j];
+          } else {
+            const float* src = isS ? st + col * D + ch0 : st + D * DV + ch0;
+            const f32x4 lo4 = *reinterpret_cast<const f32x4*>(src);
+            const f32x4 hi4 = *reinterpret_cast<const f32x4*>(src + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { raw[s][j] = lo4[j]; raw[s][4 + j] = hi4[j]; }
+          }
+        }
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          const bool used = (kg * KS + s < CPR) && (isS || isZ || zrem);
 #pragma unroll
           for (int w = 0; w < 4; ++w) {
             float hi2[2], lo2[2];
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-              const int ch = chunk * 8 + 2 * w + q;
-              float x = 0.0f;
-              bool zrem = false;
-              if (chunk < CPR) {
-                if (slot < HALF) x = st[ch * DV + hv * HALF + slot] * aS;
-                else if (NORM && slot == HALF) x = st[D * DV + ch] * az;
-                else if (NORM && slot == HALF + 1) { x = st[D * DV + ch] * az; zrem = true; }
-              }
+              const float x = used ? raw[s][2 * w + q] * sc : 0.0f;
               float r0, r1;
               unpack2<T>(pack2<T>(x, 0.0f), r0, r1);   // x rounded once to 16 bits
               hi2[q] = zrem ? x - r0 : x;
-              lo2[q] = (slot < HALF) ? x - r0 : 0.0f;  // S' remainder -> lo fragment (bf16 only)
+              lo2[q] = isS ? x - r0 : 0.0f;            // S' remainder -> lo fragment (bf16 only)
             }
             A[0][t][s][w] = pack2<T>(hi2[0], hi2[1]);
             if constexpr (NS == 2) A[1][t][s][w] = pack2<T>(lo2[0], lo2[1]);

@@ -98,12 +98,23 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict
   }
 
   // cross-wave sum in a fixed order: wave w adds into LDS copy w % COPIES in round w / COPIES (round 0 stores;
-  // inside a wave the four token groups kq = 0..3 add their z in order), then all threads add the copies in order
-  // and write the partial.  Four waves, two copies: (w0 + w2) + (w1 + w3).
+  // inside a wave the four token groups kq = 0..3 add their z in order, by lane exchanges), then all threads add
+  // the copies in order and write the partial.  Four waves: (w0 + w2) + (w1 + w3), with two copies or four (four:
+  // every wave stores at once and no read-add-write round is needed).  A lane's four columns of a row leave as one
+  // 16-byte store.
   constexpr int NE = D * D + D;
   constexpr int COPIES = reduce_copies(WAVES, D);
   static_assert(WAVES % COPIES == 0, "whole rounds");
+  static_assert(D % 4 == 0, "rows of the state are moved four columns at a time");
   float* mine = red + (wave % COPIES) * NE;
+  float zsum[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float t = __shfl(zacc[i], m);
+#pragma unroll
+    for (int s = 1; s < 4; ++s) t += __shfl(zacc[i], m + 16 * s);
+    zsum[i] = t;
+  }
 #pragma unroll
   for (int round = 0; round < WAVES / COPIES; ++round) {
     if (wave / COPIES == round) {
@@ -112,33 +123,27 @@ LF_DEV void reduce32_phase(const f32x4* __restrict__ Kh, const f32x4* __restrict
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int row = 4 * (4 * kq + r) + i;
-          if (row < D) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              const int col = 4 * m + j;
-              if (col < D) {
-                float* q = mine + row * D + col;
-                *q = (round == 0) ? acc[i][j][r] : *q + acc[i][j][r];
-              }
-            }
+          if (row < D && lane_on) {
+            f32x4* q = reinterpret_cast<f32x4*>(mine + row * D + 4 * m);
+            f32x4 x = f32x4{acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]};
+            if (round != 0) x += *q;
+            *q = x;
           }
         }
-      for (int s = 0; s < 4; ++s) {
-        if (kq == s && lane_on) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            float* q = mine + D * D + 4 * m + i;
-            *q = (round == 0 && s == 0) ? zacc[i] : *q + zacc[i];
-          }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      if (kq == 0 && lane_on) {
+        f32x4* q = reinterpret_cast<f32x4*>(mine + D * D + 4 * m);
+        f32x4 x = f32x4{zsum[0], zsum[1], zsum[2], zsum[3]};
+        if (round != 0) x += *q;
+        *q = x;
       }
     }
     __syncthreads();
   }
   for (int i = threadIdx.x; i < NE; i += 64 * WAVES) {
-    float v = red[i] + red[NE + i];
-    if constexpr (COPIES == 4) v = (v + red[2 * NE + i]) + red[3 * NE + i];
+    float v;
+    if constexpr (COPIES == 4 && WAVES == 4) v = (red[i] + red[2 * NE + i]) + (red[NE + i] + red[3 * NE + i]);   // (w0 + w2) + (w1 + w3)
+    else if constexpr (COPIES == 4) v = ((red[i] + red[NE + i]) + red[2 * NE + i]) + red[3 * NE + i];
+    else v = red[i] + red[NE + i];
     if constexpr (TO_LDS) dst[i] = v;
     else st_agent(dst + i, v);
   }
@@ -257,24 +262,31 @@ struct Apply32Dma {
   }
 
   // COHERENT: the state was written by other workgroups of the same launch (single-launch kernel)
+  // Every lane loads all its operands from clamped, valid places first (the loads are independent and issued
+  // back to back) and zeroes the unused ones afterwards; a test around each load would serialise them.
   template <bool COHERENT>
   LF_DEV void load_state(const float* state) {
     const int mrow = lane & 15, g = mrow >> 2;
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
       const int slot = 4 * t + (mrow & 3);
+      const bool isS = slot < QT;
 #pragma unroll
       for (int ks = 0; ks < KST; ++ks) {
         const int chunk = kq * CS + (ks >> 2);
-        const int ch = 4 * chunk + (ks & 3);
-        float x = 0.0f;
-        if (chunk < CH) {
-          const float* p = nullptr;
-          if (slot < QT) p = state + ch * D + g * QT + slot;
-          else if (NORM && slot == QT) p = state + D * D + ch;
-          if (p) x = COHERENT ? ld_agent(p) : *p;
-        }
-        A[t][ks] = x;
+        const int ch = 4 * (chunk < CH ? chunk : 0) + (ks & 3);
+        const float* p = isS ? state + ch * D + g * QT + slot : state + D * D + ch;
+        A[t][ks] = COHERENT ? ld_agent(p) : *p;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      const int slot = 4 * t + (mrow & 3);
+      const bool isS = slot < QT, isZ = NORM && slot == QT;
+#pragma unroll
+      for (int ks = 0; ks < KST; ++ks) {
+        const bool used = (kq * CS + (ks >> 2) < CH) && (isS || isZ);
+        A[t][ks] = used ? A[t][ks] : 0.0f;
       }
     }
   }

@@ -31,9 +31,11 @@ template <int D> struct Reduce16Cfg {
   static constexpr int kNL = (kChunks + 63) / 64;              // loads per lane per tensor
 };
 
-// copies of the accumulators in the cross-wave sum: two for the four waves of the separate kernels; workgroups of
+// copies of the accumulators in the cross-wave sum: one per wave for the four waves of the separate kernels up to
+// d = 64 (every wave stores at once: one barrier, no read-add-write round, whose 40 dependent LDS round trips per
+// lane cost 1.5 us of a small launch), two beyond (the copies would take a second workgroup's LDS); workgroups of
 // more waves (the replicated-state kernel) take four where they fit below the apply phase's staging area
-constexpr int reduce_copies(int waves, int d) { return (waves > 4 && d <= 48) ? 4 : 2; }
+constexpr int reduce_copies(int waves, int d) { return waves > 4 ? (d <= 48 ? 4 : 2) : (d <= 64 ? 4 : 2); }
 
 template <typename T, int D>
 constexpr int reduce16_lds_bytes(int waves = kWavesPerWG) {
@@ -125,13 +127,18 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
   constexpr bool kRescan = NS == 1 && FM == kPhiEluPlusOne;
   constexpr float kRescanBelow = -5.0f, kShiftFloor = -64.0f, kLog2e = 1.44269504088896340736f;
 
-  // (one-time fill of the wave's tiles: phi(K) pad columns zero; V pad columns zero except the ones column at
-  // index D (when a spare column exists) which makes z fall out of the products)
-  for (int i = lane; i < Cfg::kTileElems; i += 64) {
-#pragma unroll
-    for (int s = 0; s < NS; ++s) ldsP[s][i] = 0;
-    ldsV[i] = (Sh::kSpareCol && (i % RS) == D) ? OneBits<T>::value : (uint16_t)0;
-  }
+  // Fill of the wave's tiles (after the stream's first loads have been issued, so that it runs under their
+  // latency): phi(K) pad columns zero; V pad columns zero except the ones column at index D (when a spare column
+  // exists) which makes z fall out of the products.  16 bytes per lane and store; LDS operations of a wave
+  // complete in order, so the ones land on the zeros.
+  auto fill_tiles = [&]() {
+    static_assert(((NS + 1) * Cfg::kTileElems * 2) % 16 == 0, "whole 16-byte pieces");
+    u32x4* w16 = reinterpret_cast<u32x4*>(wbase);
+    for (int i = lane; i < (NS + 1) * Cfg::kTileElems / 8; i += 64) w16[i] = u32x4{0, 0, 0, 0};
+    if constexpr (Sh::kSpareCol) {
+      if (lane < kTile) ldsV[lane * RS + D] = OneBits<T>::value;
+    }
+  };
 
   // the wave's whole stream: sums of phi(k) 2^kc (x) v into acc / accz; returns the token rows summed
   auto run_stream = [&](const float kc) {
@@ -145,6 +152,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
     int lim = 0;
     long long tokens = 0;
     if (it.valid()) lim = issue_loads(it.t);
+    fill_tiles();
     while (it.valid()) {
       tokens += lim;
       // ---- phi(K) -> 16-bit (hi [, lo]) -> LDS ; V -> LDS --------------------------------------
@@ -268,7 +276,7 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
 
   // ---- cross-wave sum in a fixed order: wave w adds into LDS copy w % COPIES ([D*D] S then [D] z) in round
   //      w / COPIES (round 0 stores), so copy c = w_c + w_(c+COPIES) + ...; then all threads add the copies in
-  //      order and write the partial.  Four waves, two copies: (w0 + w2) + (w1 + w3). -----------------------
+  //      order and write the partial.  Four waves: (w0 + w2) + (w1 + w3), with two copies or four. ----------
   __syncthreads();
   constexpr int NE = D * D + D;
   constexpr int COPIES = reduce_copies(WAVES, D);
@@ -305,8 +313,10 @@ LF_DEV void reduce16_phase(const u32x4* __restrict__ Kh, const u32x4* __restrict
     __syncthreads();
   }
   for (int i = threadIdx.x; i < NE; i += 64 * WAVES) {
-    float v = red[i] + red[NE + i];
-    if constexpr (COPIES == 4) v = (v + red[2 * NE + i]) + red[3 * NE + i];
+    float v;
+    if constexpr (COPIES == 4 && WAVES == 4) v = (red[i] + red[2 * NE + i]) + (red[NE + i] + red[3 * NE + i]);   // (w0 + w2) + (w1 + w3)
+    else if constexpr (COPIES == 4) v = ((red[i] + red[NE + i]) + red[2 * NE + i]) + red[3 * NE + i];
+    else v = red[i] + red[NE + i];
     if constexpr (TO_LDS) dst[i] = v;
     else st_agent(dst + i, v);
   }
