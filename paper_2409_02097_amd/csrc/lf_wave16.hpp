@@ -18,6 +18,14 @@
 // LDS: slot (ring position) of wave w at (slot * 4 + w) * kSlotBytes; a tile lies there row after row, the
 // 16-byte chunks of row r swizzled (see ApplyWaveShape) so that token-per-lane accesses are bank-conflict free.
 // bf16 keeps the low halves of phi(q) (hi + lo operands) in one more slot per wave behind the ring.
+//
+// Operand type TA other than the storage type T (bf16 tensors, fp16 operands): two levels of bf16 operands do not
+// fit the registers at d = 160 and triple the products at every width, while the state scaled by a power of two and a
+// query row scaled to [1, 2) lose nothing in fp16's 11 bits that the bf16 output would keep.  phi is then applied
+// when a lane reads its token's channels as B operands (no pass over the tile in place, no LO slot): the row's
+// largest channel m gives  phi~ = phi(q) 2^c / 2^e  with  2^c = exp(-m) for a row of negative channels (1 otherwise)
+// and 2^e the power of two at or below the row's largest phi, so any bf16 row -- far below zero or huge -- fills
+// fp16's range; the factor cancels between numerator and denominator once eps carries it too.
 #pragma once
 #include "lf_wide16.hpp"
 
@@ -133,12 +141,14 @@ pack_state_wave(const float* __restrict__ state, unsigned char* __restrict__ pac
 }
 
 // One wave's apply work on one head: construct, prefetch(), load_packed(), stream().
-template <typename T, int D, int FM, bool NORM>
+template <typename T, int D, int FM, bool NORM, typename TA = T>
 struct ApplyWave {
   using Sw = ApplyWaveShape<D>;
-  static constexpr int NS = NSplit<T>::value;
+  static constexpr bool kMixed = !__is_same(T, TA);   // operands of another type than the stored tensors
+  static_assert(!kMixed || (__is_same(T, BF16) && __is_same(TA, F16)), "mixed form: bf16 tensors, fp16 operands");
+  static constexpr int NS = NSplit<TA>::value;
   static constexpr int CPR = Sw::kCPR, KS = Sw::kKS, RB = Sw::kRB, CB = Sw::kCB, NL = Sw::kNL;
-  static constexpr int R = apply16_wave_ring<T>();
+  static constexpr int R = apply16_wave_ring<TA>();
   static constexpr int W = Sw::kWaves;
   static_assert(R == 3, "the wait counts below are written for a ring of three slots");
   static_assert(4 * NL <= 63, "the vector-memory counter has six bits");
@@ -210,7 +220,7 @@ struct ApplyWave {
 
   // `packed`: this head's operands as pack_state_wave wrote them
   LF_DEV void load_packed(const unsigned char* packed, float eps) {
-    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + PackWave<T, D>::kHeaderBytes);
+    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + PackWave<TA, D>::kHeaderBytes);
 #pragma unroll
     for (int l = 0; l < NS; ++l)
 #pragma unroll
@@ -295,8 +305,11 @@ struct ApplyWave {
     }
   }
 
-  // multiply one block of 16 tokens and write its outputs over its rows of the tile at `sl`
-  LF_DEV void multiply_block(unsigned char* sl, int tb, const u32x4 (&Bh)[KS], const u32x4 (&Bl)[NS == 2 ? KS : 1]) {
+  // multiply one block of 16 tokens and write its outputs over its rows of the tile at `sl`; `eps_tok`: eps in the
+  // units of this lane's token's denominator, `post`: factor on its un-normalized outputs (mixed form: the row's
+  // scale taken out again)
+  LF_DEV void multiply_block(unsigned char* sl, int tb, const u32x4 (&Bh)[KS], const u32x4 (&Bl)[NS == 2 ? KS : 1],
+                             float eps_tok, float post = 1.0f) {
     f32x4 acc[RB];
 #pragma unroll
     for (int b = 0; b < RB; ++b) acc[b] = f32x4{0, 0, 0, 0};
@@ -304,19 +317,19 @@ struct ApplyWave {
     for (int s = 0; s < KS; ++s) {
 #pragma unroll
       for (int b = 0; b < RB; ++b) {
-        acc[b] = mfma_16x16x32<T>(A[0][b][s], Bh[s], acc[b]);
+        acc[b] = mfma_16x16x32<TA>(A[0][b][s], Bh[s], acc[b]);
         if constexpr (NS == 2) {
-          acc[b] = mfma_16x16x32<T>(A[0][b][s], Bl[s], acc[b]);
-          if (b < CB) acc[b] = mfma_16x16x32<T>(A[1][b][s], Bh[s], acc[b]);
+          acc[b] = mfma_16x16x32<TA>(A[0][b][s], Bl[s], acc[b]);
+          if (b < CB) acc[b] = mfma_16x16x32<TA>(A[1][b][s], Bh[s], acc[b]);
         }
       }
     }
-    float scale = c1;
+    float scale = c1 * post;
     if constexpr (NORM) {
       // rows d and d + 1 (the normalizer and what its rounding left) are rows 0 and 1 of the last block: lanes
       // 0-15 hold them for their tokens
       const float part = acc[RB - 1][0] + acc[RB - 1][1];
-      const float den = __shfl(part, lane & 15) + eps_s;
+      const float den = __shfl(part, lane & 15) + eps_tok;
       scale = c1 * __builtin_amdgcn_rcpf(den);
     }
 #pragma unroll
@@ -331,22 +344,77 @@ struct ApplyWave {
   // first product: a lone wave per SIMD has nobody to hide an LDS round trip per contraction step behind.
   LF_DEV void compute_tile(int slot) {
     unsigned char* sl = slot_ptr(slot);
-    if constexpr (NS == 1) {
+    if constexpr (kMixed) {
+      u32x4 R0[KS], R1[KS], none[1];
+      read_block(sl, slot, 0, R0, none);
+      read_block(sl, slot, 1, R1, none);   // block 0's outputs land in other rows
+      __builtin_amdgcn_sched_barrier(0);
+      float eps_tok, post;
+      make_operands(R0, eps_tok, post);
+      multiply_block(sl, 0, R0, none, eps_tok, post);
+      make_operands(R1, eps_tok, post);
+      multiply_block(sl, 1, R1, none, eps_tok, post);
+    } else if constexpr (NS == 1) {
       u32x4 B0[KS], B1[KS], none[1];
       read_block(sl, slot, 0, B0, none);
       read_block(sl, slot, 1, B1, none);   // block 0's outputs land in other rows
       __builtin_amdgcn_sched_barrier(0);
-      multiply_block(sl, 0, B0, none);
-      multiply_block(sl, 1, B1, none);
+      multiply_block(sl, 0, B0, none, eps_s);
+      multiply_block(sl, 1, B1, none, eps_s);
     } else {
 #pragma unroll
       for (int tb = 0; tb < 2; ++tb) {
         u32x4 Bh[KS], Bl[KS];
         read_block(sl, slot, tb, Bh, Bl);
         __builtin_amdgcn_sched_barrier(0);
-        multiply_block(sl, tb, Bh, Bl);
+        multiply_block(sl, tb, Bh, Bl, eps_s);
       }
     }
+  }
+
+  // Mixed form.  `B`: this lane's 8 KS stored channels of its token (lanes l, l + 16, l + 32, l + 48 hold one token
+  // between them) -> the fp16 operands phi~ = phi(q) 2^c 2^-e, where 2^c = exp(-m) if the row's largest channel m is
+  // negative under elu + 1 (else 1) and 2^e is the power of two at or below the row's largest phi 2^c, so the
+  // row's largest operand lies in [1, 2) whatever the bf16 inputs' magnitude.  eps_tok = eps' 2^c 2^-e is what eps
+  // becomes in that row's units (the factor cancels in Eq. 5's ratio), post = its inverse for the un-normalized form.
+  // A row without a positive phi (relu of non-positive channels) keeps operands 0 and gives 0, as the definition does;
+  // a NaN stays in its own token's outputs (the row maximum skips it).
+  LF_DEV void make_operands(u32x4 (&B)[KS], float& eps_tok, float& post) {
+    constexpr float kLog2e = 1.44269504088896340736f;
+    float x[8 * KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) unpack2<T>(B[s][w], x[8 * s + 2 * w], x[8 * s + 2 * w + 1]);
+    float m = FM == kPhiIdentity ? fabsf(x[0]) : x[0];
+#pragma unroll
+    for (int i = 1; i < 8 * KS; ++i) m = fmaxf(m, FM == kPhiIdentity ? fabsf(x[i]) : x[i]);
+    m = fmaxf(m, __shfl_xor(m, 16));
+    m = fmaxf(m, __shfl_xor(m, 32));
+    float c = 0.0f, top;   // top: the row's largest |phi 2^c|
+    if constexpr (FM == kPhiEluPlusOne) {
+      c = m < 0.0f ? fminf(-m * kLog2e, 3.0e38f) : 0.0f;   // (finite: a row of -inf gives phi = 0, not inf - inf)
+      top = m < 0.0f ? 1.0f : m + 1.0f;
+    } else if constexpr (FM == kPhiRelu) {
+      top = fmaxf(m, 0.0f);
+    } else {
+      top = m;
+    }
+    // 2^-e from top's exponent field f: (254 - f) as the field of the factor; f is kept inside [1, 253] so that the
+    // factor is a normal number (top = 0: the operands are 0 whatever it is)
+    uint32_t f = (__builtin_bit_cast(uint32_t, top) >> 23) & 0xffu;
+    f = f < 1u ? 1u : (f > 253u ? 253u : f);
+    const float mult = __builtin_bit_cast(float, (254u - f) << 23);
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        B[s][w] = pack2<TA>(phi_scaled<FM>(x[8 * s + 2 * w], c) * mult, phi_scaled<FM>(x[8 * s + 2 * w + 1], c) * mult);
+    // eps' 2^c 2^-e in two finite factors (2^c alone leaves fp32's range from m = -88.7 on; the clamp only keeps
+    // 0 * 2^c = 0 for eps = 0: beyond it the product is infinite anyway and the row's outputs are 0, as their true
+    // size, below e^-131 / eps of the values', rounds to)
+    eps_tok = __builtin_amdgcn_exp2f(fminf(c, 190.0f) - 64.0f) * (eps_s * mult * 0x1p64f);
+    post = __builtin_amdgcn_exp2f(-c) * __builtin_bit_cast(float, f << 23);   // 2^-c 2^e
   }
 
   // Issue order per wave:  C0 C1 [state] | C2 K0 | S0 C3 K1 | S1 C4 K2 | ...  Before tile j is touched its copies
@@ -368,7 +436,7 @@ struct ApplyWave {
       const bool copied = ahead.valid();
       if (copied) issue_copy(ahead.t, have_prev ? prev_slot : R - 1);
       wait_groups((j >= 2 ? 2 : j) + (next_copied ? 1 : 0) + (copied ? 1 : 0));
-      phi_pass(slot);
+      if constexpr (!kMixed) phi_pass(slot);   // (mixed form: phi where the operands are read)
       compute_tile(slot);
       it.next();
       ahead.next();
@@ -383,16 +451,17 @@ struct ApplyWave {
 };
 
 // grid = (wgs, heads), block = 256 (four waves that share nothing but the workgroup)
-template <typename T, int D, int FM, bool NORM>
+// (TA: the operands' type; `packed` comes from pack_state_wave<TA, D>)
+template <typename T, int D, int FM, bool NORM, typename TA = T>
 __global__ void __launch_bounds__(kThreads)
 apply16_wave(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, HeadSubset hs,
              const unsigned char* __restrict__ packed, float eps, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const long long bh = hs.bh(blockIdx.y, lq.H);
-  ApplyWave<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
-                               gridDim.x, smem);
+  ApplyWave<T, D, FM, NORM, TA> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
+                                   gridDim.x, smem);
   ap.prefetch();
-  ap.load_packed(packed + bh * PackWave<T, D>::kHeadBytes, eps);
+  ap.load_packed(packed + bh * PackWave<TA, D>::kHeadBytes, eps);
   ap.stream();
 }
 

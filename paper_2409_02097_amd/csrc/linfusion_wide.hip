@@ -12,8 +12,11 @@ namespace {
 
 using lfh::allow_lds;
 
-// apply16_wave holds (d + 2) x d operands per level in registers: every fp16 width, bf16 up to 128
-template <typename T, int D> constexpr bool wave_ok() { return lf::NSplit<T>::value == 1 || D <= 128; }
+// apply16_wave holds the (d + 2) x d operands of a head in one wave's registers.  They are fp16 for both storage
+// types: bf16 tensors take the mixed form (query rows scaled into fp16's range as they are read), since two levels
+// of bf16 operands do not fit at d = 160 and triple the products everywhere.
+using WaveOperand = lf::F16;
+template <typename T, int D> constexpr bool wave_ok() { return true; }
 
 template <typename T, int D>
 int reduce(const WideReduceArgs& a, hipEvent_t* ev) {
@@ -67,12 +70,12 @@ int apply(const WideApplyArgs& a) {
   }
 #define LFW_APPLY_WAVE(FM, NORM)                                                                             \
   if constexpr (wave_ok<T, D>()) {                                                                          \
-    constexpr int lds2 = apply16_wave_lds_bytes<T, D>();                                                     \
-    if (!allow_lds(apply16_wave<T, D, FM, NORM>, lds2)) return LINFUSION_ERR_HIP;                            \
-    pack_state_wave<T, D><<<dim3(ApplyWaveShape<D>::kKS, (unsigned)BH), blk, 0, st>>>(a.state, a.packed,     \
-                                                                                     NORM ? 1 : 0);          \
-    apply16_wave<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, a.N,         \
-                                                        a.plan.blk_apply);                                   \
+    constexpr int lds2 = apply16_wave_lds_bytes<WaveOperand, D>();                                           \
+    if (!allow_lds(apply16_wave<T, D, FM, NORM, WaveOperand>, lds2)) return LINFUSION_ERR_HIP;               \
+    pack_state_wave<WaveOperand, D><<<dim3(ApplyWaveShape<D>::kKS, (unsigned)BH), blk, 0, st>>>(             \
+        a.state, a.packed, NORM ? 1 : 0);                                                                    \
+    apply16_wave<T, D, FM, NORM, WaveOperand><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, \
+                                                                     a.N, a.plan.blk_apply);                 \
   } else {                                                                                                   \
     return LINFUSION_ERR_UNSUPPORTED;                                                                        \
   }
@@ -113,7 +116,7 @@ template <typename T, int D>
 constexpr size_t pack_bytes() {
   size_t b = lf::PackWide<T, D, 4>::kHeadBytes > lf::PackWide<T, D, 8>::kHeadBytes ? lf::PackWide<T, D, 4>::kHeadBytes
                                                                                    : lf::PackWide<T, D, 8>::kHeadBytes;
-  if (wave_ok<T, D>() && (size_t)lf::PackWave<T, D>::kHeadBytes > b) b = lf::PackWave<T, D>::kHeadBytes;
+  if (wave_ok<T, D>() && (size_t)lf::PackWave<WaveOperand, D>::kHeadBytes > b) b = lf::PackWave<WaveOperand, D>::kHeadBytes;
   return b;
 }
 

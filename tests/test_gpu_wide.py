@@ -43,10 +43,11 @@ def test_wide_heads_match_oracle(B, H, N, d, dtype):
 
 @pytest.mark.parametrize("waves", [4, 8])
 @pytest.mark.parametrize("B,H,N,d,dtype", [(1, 3, 33, 160, "f16"), (1, 1, 4099, 160, "f16"), (2, 2, 333, 128, "f16"),
-                                           (1, 3, 1030, 128, "bf16"), (1, 2, 700, 96, "f16"), (1, 2, 65, 96, "bf16")])
+                                           (1, 3, 1030, 128, "bf16"), (1, 2, 700, 96, "f16"), (1, 2, 65, 96, "bf16"),
+                                           (2, 2, 515, 160, "bf16")])
 def test_workgroup_shared_apply_where_the_wave_apply_is_the_default(B, H, N, d, dtype, waves, monkeypatch, tuning):
-    """These shapes run apply16_wave (a wave per tile) by default; the workgroup-shared apply16_wide, which the widths
-    and dtypes whose operands exceed one wave's registers still use, is checked on them as well."""
+    """These shapes run apply16_wave (a wave per tile) by default; the workgroup-shared apply16_wide, which the
+    MLP-fed call at these widths is built on, is checked on them as well."""
     print(f"shared-tile apply B={B} H={H} N={N} d={d} {dtype} waves={waves}", flush=True)
     code = wl.DTYPE_CODE[dtype]
     assert lf.linfusion_attn_apply_kernel(B, H, N, d, code) == "apply16_wave"
@@ -62,7 +63,7 @@ def test_workgroup_shared_apply_where_the_wave_apply_is_the_default(B, H, N, d, 
 
 
 @pytest.mark.parametrize("wgs,blk", [(4, 4), (6, 8), (2, 64)])
-@pytest.mark.parametrize("N,d,dtype", [(20011, 160, "f16"), (9000, 128, "bf16"), (6000, 96, "bf16")])
+@pytest.mark.parametrize("N,d,dtype", [(20011, 160, "f16"), (9000, 128, "bf16"), (6000, 96, "bf16"), (20011, 160, "bf16")])
 def test_wave_apply_with_many_tiles_per_wave(N, d, dtype, wgs, blk, monkeypatch, tuning):
     """Few long-lived workgroups: every wave walks dozens of tiles through its ring (steady state of the copy /
     store pipeline, block changes, a ragged last tile), which the small shapes never reach."""
@@ -79,11 +80,52 @@ def test_wave_apply_with_many_tiles_per_wave(N, d, dtype, wgs, blk, monkeypatch,
     parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"wave apply N={N} d={d} {dtype} wgs={wgs} blk={blk}")
 
 
-def test_wave_apply_is_chosen_where_its_operands_fit():
+def test_wave_apply_is_chosen_at_every_wide_width():
+    """fp16 operands for both storage types: (d + 2) x d of them fit one wave's registers up to d = 160."""
     names = {(d, t): lf.linfusion_attn_apply_kernel(1, 8, 4096, d, wl.DTYPE_CODE[t])
              for d in (96, 128, 160) for t in ("f16", "bf16")}
-    assert names[(160, "bf16")] == "apply16_wide"
-    assert all(v == "apply16_wave" for key, v in names.items() if key != (160, "bf16")), names
+    assert all(v == "apply16_wave" for v in names.values()), names
+
+
+@pytest.mark.parametrize("d", [96, 160])
+@pytest.mark.parametrize("case", ["q-20", "q-60", "some_rows_q-300", "q+3000", "some_rows_q*1e30", "q*1e-20",
+                                  "one_channel_up"])
+def test_bf16_query_rows_of_any_magnitude(case, d):
+    """bf16 tensors at the wide widths are multiplied as fp16 operands; every query row is scaled into fp16's range
+    by its own largest channel (the factor cancels in the ratio once eps carries it), so rows far below zero, rows
+    of huge values and rows of tiny ones must come out as the definition gives them."""
+    B, H, N = 1, 2, 777
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=76, device="cpu")
+    if case == "q-20":
+        q = q - 20.0
+    elif case == "q-60":
+        q = q * 3.0 - 60.0
+    elif case == "some_rows_q-300":
+        q[:, :, ::3] -= 300.0
+    elif case == "q+3000":
+        q = q * 500.0 + 3000.0
+    elif case == "some_rows_q*1e30":
+        q[:, :, 1::2] *= 1e30
+    elif case == "q*1e-20":
+        q = q * 1e-20
+    else:
+        q = q - 30.0
+        q[:, :, :, 7] += 25.0 + 10.0 * torch.rand(B, H, N)
+    q, k, v = q.bfloat16(), k.bfloat16(), v.bfloat16()
+    assert lf.linfusion_attn_apply_kernel(B, H, N, d, lf.DTYPE_BF16) == "apply16_wave"
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    for eps in (1e-6, 0.0):
+        out = torch.full_like(qd, float("nan"))
+        lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, eps, 0, _ws(B, H, N, d, "bf16"))
+        torch.cuda.synchronize()
+        worst = parity.check_all(out, q, k, v, "bf16", 0, eps, True, f"{case} d={d} eps={eps}")
+        print(f"{case} d={d} eps={eps}: worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
+    if case in ("q-20", "some_rows_q-300", "q+3000"):      # the un-normalized arm takes the row's factor out again
+        vs = (v.float() * (1e-4 if case == "q+3000" else 0.01)).bfloat16()
+        out = torch.full_like(qd, float("nan"))
+        lf.linfusion_attn_fwd_ex(qd, kd, vs.cuda(), out, 0, 1e-6, lf.FLAG_UNNORMALIZED, _ws(B, H, N, d, "bf16"))
+        torch.cuda.synchronize()
+        parity.check_all(out, q, k, vs, "bf16", 0, 1e-6, False, f"{case} d={d} unnormalized")
 
 
 @pytest.mark.parametrize("d,dtype", [(80, "f16"), (160, "f16"), (80, "bf16"), (160, "bf16"), (96, "f16"), (128, "bf16")])
@@ -102,10 +144,10 @@ def test_wide_heads_token_major_and_in_place(d, dtype):
     assert torch.equal(qt.view(torch.uint8), ot.view(torch.uint8)), "in place differs from out of place"
 
 
-@pytest.mark.parametrize("d", [80, 160])
+@pytest.mark.parametrize("d,dtype", [(80, "f16"), (160, "f16"), (160, "bf16"), (96, "bf16")])
 @pytest.mark.parametrize("fm,normalize", [(1, True), (2, True), (0, False)])
-def test_wide_heads_other_feature_maps_and_unnormalized(d, fm, normalize):
-    B, H, N, dtype = 1, 2, 300, "f16"
+def test_wide_heads_other_feature_maps_and_unnormalized(d, dtype, fm, normalize):
+    B, H, N = 1, 2, 300
     q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=72, device="cpu")
     if fm == 2:
         q, k = q.abs(), k.abs()
