@@ -17,15 +17,16 @@
 //
 // LDS: slot (ring position) of wave w at (slot * 4 + w) * kSlotBytes; a tile lies there row after row, the
 // 16-byte chunks of row r swizzled (see ApplyWaveShape) so that token-per-lane accesses are bank-conflict free.
-// bf16 keeps the low halves of phi(q) (hi + lo operands) in one more slot per wave behind the ring.
 //
-// Operand type TA other than the storage type T (bf16 tensors, fp16 operands): two levels of bf16 operands do not
-// fit the registers at d = 160 and triple the products at every width, while the state scaled by a power of two and a
-// query row scaled to [1, 2) lose nothing in fp16's 11 bits that the bf16 output would keep.  phi is then applied
-// when a lane reads its token's channels as B operands (no pass over the tile in place, no LO slot): the row's
-// largest channel m gives  phi~ = phi(q) 2^c / 2^e  with  2^c = exp(-m) for a row of negative channels (1 otherwise)
-// and 2^e the power of two at or below the row's largest phi, so any bf16 row -- far below zero or huge -- fills
-// fp16's range; the factor cancels between numerator and denominator once eps carries it too.
+// The operands are fp16 for both storage types.  For bf16 tensors two levels of bf16 operands (hi + lo) would not
+// fit the registers at d = 160 and would triple the products at every width, while fp16's 11 bits are what the
+// fp16 path lives on and more than a bf16 output keeps.  What fp16 lacks is range, and that is given back per row:
+// phi is applied when a lane reads its token's channels as B operands (no pass over the tile in place), and the
+// row's largest channel m gives  phi~ = phi(q) 2^c / 2^e  with  2^c = exp(-m) for a row of negative channels under
+// elu + 1 (1 otherwise) and 2^e the power of two at or below the row's largest phi 2^c.  Every row's largest operand
+// then lies in [1, 2) -- a row at -300, at 1e30 or at 1e-20 alike -- and the factor cancels between numerator and
+// denominator once eps carries it too.  fp16 tensors go the same way: a row far below zero (exp(q) subnormal or zero
+// in fp16) or near the top of the range (phi = q + 1 above 65504) comes out as the definition gives it.
 #pragma once
 #include "lf_wide16.hpp"
 
@@ -51,40 +52,36 @@ template <int D> struct ApplyWaveShape {
   static __device__ __forceinline__ int swz(int r) { return (r >> kSwzShift) & kSwzMask; }
 };
 
-// Ring slots per wave: the tile being worked on and two on their way (bf16: and the LO slot).
-template <typename T> constexpr int apply16_wave_ring() { return 3; }
-template <typename T, int D>
-constexpr int apply16_wave_lds_bytes() {
-  return ApplyWaveShape<D>::kWaves * (apply16_wave_ring<T>() + (NSplit<T>::value == 2 ? 1 : 0)) *
-         ApplyWaveShape<D>::kSlotBytes;
-}
+// Ring slots per wave: the tile being worked on and two on their way.
+constexpr int kApplyWaveRing = 3;
+template <int D>
+constexpr int apply16_wave_lds_bytes() { return ApplyWaveShape<D>::kWaves * kApplyWaveRing * ApplyWaveShape<D>::kSlotBytes; }
 
-// The operand-ready state of one head for apply16_wave: {c1 = alpha_z / alpha_S, alpha_z} then
-// frag[level][b][s][lane], 16 bytes each.  Lane l of fragment (b, s), element j:  output row m = 16 b + l % 16,
-// contraction channel ch = 32 s + 8 (l / 16) + j;  m < d -> S'[ch][m] = alpha_S S[ch][m];  m == d -> z'[ch]
-// = alpha_z z[ch] rounded to 16 bits;  m == d + 1 -> what that rounding left;  else 0.  Level 1 (bf16 only) holds
-// what rounding S' to 16 bits left.
-template <typename T, int D> struct PackWave {
+// The operand-ready state of one head for apply16_wave: {c1 = alpha_z / alpha_S, alpha_z} then frag[b][s][lane],
+// 16 bytes each, fp16.  Lane l of fragment (b, s), element j:  output row m = 16 b + l % 16, contraction channel
+// ch = 32 s + 8 (l / 16) + j;  m < d -> S'[ch][m] = alpha_S S[ch][m];  m == d -> z'[ch] = alpha_z z[ch] rounded to
+// fp16;  m == d + 1 -> what that rounding left;  else 0.
+template <int D> struct PackWave {
   using Sw = ApplyWaveShape<D>;
   static constexpr int kHeaderBytes = 256;
-  static constexpr int kFrags = NSplit<T>::value * Sw::kRB * Sw::kKS;   // per lane
+  static constexpr int kFrags = Sw::kRB * Sw::kKS;   // per lane
   static constexpr int kHeadBytes = kHeaderBytes + kFrags * 64 * 16;
 };
 
 // grid = (d / 32, heads), block = 256.  Every workgroup finds the maxima (power-of-two scales, as
 // pack_state_wide); workgroup s writes the fragments of contraction step s, wave w those of row blocks w, w + 4, ..
-template <typename T, int D>
+template <int D>
 __global__ void __launch_bounds__(kThreads)
 pack_state_wave(const float* __restrict__ state, unsigned char* __restrict__ packed, int normalize) {
   using Sw = ApplyWaveShape<D>;
-  constexpr int NS = NSplit<T>::value, KS = Sw::kKS, RB = Sw::kRB, NE = D * D + D;
+  constexpr int KS = Sw::kKS, RB = Sw::kRB, NE = D * D + D;
   __shared__ float redmax[2 * kWavesPerWG];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int s = blockIdx.x;
   const long long bh = blockIdx.y;
   const float* st = state + bh * NE;
-  unsigned char* out = packed + bh * PackWave<T, D>::kHeadBytes;
+  unsigned char* out = packed + bh * PackWave<D>::kHeadBytes;
 
   float mS = 0.0f, mz = 0.0f;
   const f32x4* st4 = reinterpret_cast<const f32x4*>(st);
@@ -111,14 +108,14 @@ pack_state_wave(const float* __restrict__ state, unsigned char* __restrict__ pac
     scales[1] = az;
   }
 
-  u32x4* frag = reinterpret_cast<u32x4*>(out + PackWave<T, D>::kHeaderBytes);
+  u32x4* frag = reinterpret_cast<u32x4*>(out + PackWave<D>::kHeaderBytes);
   const int g = lane >> 4;
   for (int b = wave; b < RB; b += kWavesPerWG) {
     const int m = 16 * b + (lane & 15);
-    u32x4 hi4, lo4;
+    u32x4 w4;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      float hi2[2], lo2[2];
+      float v2[2];
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         const int ch = 32 * s + 8 * g + 2 * w + q;
@@ -128,27 +125,22 @@ pack_state_wave(const float* __restrict__ state, unsigned char* __restrict__ pac
         else if (normalize && m == D) x = st[D * D + ch] * az;
         else if (normalize && m == D + 1) { x = st[D * D + ch] * az; zrem = true; }
         float r0, r1;
-        unpack2<T>(pack2<T>(x, 0.0f), r0, r1);   // x rounded once to 16 bits
-        hi2[q] = zrem ? x - r0 : x;
-        lo2[q] = (m < D) ? x - r0 : 0.0f;
+        unpack2<F16>(pack2<F16>(x, 0.0f), r0, r1);   // x rounded once to fp16
+        v2[q] = zrem ? x - r0 : x;
       }
-      hi4[w] = pack2<T>(hi2[0], hi2[1]);
-      lo4[w] = pack2<T>(lo2[0], lo2[1]);
+      w4[w] = pack2<F16>(v2[0], v2[1]);
     }
-    frag[((0 * RB + b) * KS + s) * 64 + lane] = hi4;
-    if constexpr (NS == 2) frag[((1 * RB + b) * KS + s) * 64 + lane] = lo4;
+    frag[(b * KS + s) * 64 + lane] = w4;
   }
 }
 
-// One wave's apply work on one head: construct, prefetch(), load_packed(), stream().
-template <typename T, int D, int FM, bool NORM, typename TA = T>
+// One wave's apply work on one head: construct, prefetch(), load_packed(), stream().  T: the tensors' storage type.
+template <typename T, int D, int FM, bool NORM>
 struct ApplyWave {
   using Sw = ApplyWaveShape<D>;
-  static constexpr bool kMixed = !__is_same(T, TA);   // operands of another type than the stored tensors
-  static_assert(!kMixed || (__is_same(T, BF16) && __is_same(TA, F16)), "mixed form: bf16 tensors, fp16 operands");
-  static constexpr int NS = NSplit<TA>::value;
+  using TA = F16;   // the operands' type
   static constexpr int CPR = Sw::kCPR, KS = Sw::kKS, RB = Sw::kRB, CB = Sw::kCB, NL = Sw::kNL;
-  static constexpr int R = apply16_wave_ring<TA>();
+  static constexpr int R = kApplyWaveRing;
   static constexpr int W = Sw::kWaves;
   static_assert(R == 3, "the wait counts below are written for a ring of three slots");
   static_assert(4 * NL <= 63, "the vector-memory counter has six bits");
@@ -162,7 +154,7 @@ struct ApplyWave {
   int trow[NL], qoff[NL], ooff[NL], soff[NL];
   int rowb[2], x0[2];        // per token block: byte offset of this lane's token row in a slot, its swizzle
   TileIter it, ahead;
-  u32x4 A[NS][RB][KS];
+  u32x4 A[RB][KS];
   float c1, eps_s;
 
   LF_DEV ApplyWave(const u32x4* Qh_, int rs_q_, u32x4* Oh_, int rs_o_, long long N_, int tiles_per_block, int wg,
@@ -220,48 +212,14 @@ struct ApplyWave {
 
   // `packed`: this head's operands as pack_state_wave wrote them
   LF_DEV void load_packed(const unsigned char* packed, float eps) {
-    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + PackWave<TA, D>::kHeaderBytes);
+    const u32x4* frag = reinterpret_cast<const u32x4*>(packed + PackWave<D>::kHeaderBytes);
 #pragma unroll
-    for (int l = 0; l < NS; ++l)
+    for (int b = 0; b < RB; ++b)
 #pragma unroll
-      for (int b = 0; b < RB; ++b)
-#pragma unroll
-        for (int s = 0; s < KS; ++s) A[l][b][s] = frag[((l * RB + b) * KS + s) * 64 + lane];
+      for (int s = 0; s < KS; ++s) A[b][s] = frag[(b * KS + s) * 64 + lane];
     const float* scales = reinterpret_cast<const float*>(packed);
     c1 = scales[0];
     eps_s = eps * scales[1];
-  }
-
-  // phi on the tile in ring slot `slot` (it has landed), in place; bf16: low halves to the LO slot
-  LF_DEV void phi_pass(int slot) {
-    unsigned char* sl = slot_ptr(slot);
-    unsigned char* lo = slot_ptr(R);
-    // all reads first: a lone wave per SIMD has nobody to hide one LDS round trip per deposit behind
-    u32x4 raw[NL];
-#pragma unroll
-    for (int u = 0; u < NL; ++u) raw[u] = *reinterpret_cast<const u32x4*>(sl + u * 1024 + lane * 16);
-    __builtin_amdgcn_sched_barrier(0);   // (the scheduler would pull each read down to its use again)
-#pragma unroll
-    for (int u = 0; u < NL; ++u) {
-      const int at = u * 1024 + lane * 16;
-      u32x4 h4, l4;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        if constexpr (NS == 1) {
-          h4[w] = phi_pack2<T, FM>(raw[u][w]);
-        } else {
-          float x0_, x1_;
-          unpack2<T>(raw[u][w], x0_, x1_);
-          const float r0 = phi<FM>(x0_), r1 = phi<FM>(x1_);
-          uint32_t h, l;
-          pack2_split<T>(r0, r1, h, l);
-          h4[w] = h;
-          l4[w] = l;
-        }
-      }
-      *reinterpret_cast<u32x4*>(sl + at) = h4;
-      if constexpr (NS == 2) *reinterpret_cast<u32x4*>(lo + at) = l4;
-    }
   }
 
   // the finished tile in `slot` goes out; always NL vector memory instructions for a full tile (only the very
@@ -295,100 +253,32 @@ struct ApplyWave {
     }
   }
 
-  // this lane's B operands of token block tb of the tile in `slot`
-  LF_DEV void read_block(const unsigned char* sl, int slot, int tb, u32x4 (&Bh)[KS], u32x4 (&Bl)[NS == 2 ? KS : 1]) {
+  // this lane's 8 KS stored channels of its token of block tb of the tile at `sl`
+  LF_DEV void read_block(const unsigned char* sl, int tb, u32x4 (&B)[KS]) {
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      const int o = chunk_off(tb, 4 * s + g);
-      Bh[s] = *reinterpret_cast<const u32x4*>(sl + o);
-      if constexpr (NS == 2) Bl[s] = *reinterpret_cast<const u32x4*>(sl + (R - slot) * W * Sw::kSlotBytes + o);
-    }
+    for (int s = 0; s < KS; ++s) B[s] = *reinterpret_cast<const u32x4*>(sl + chunk_off(tb, 4 * s + g));
   }
 
-  // multiply one block of 16 tokens and write its outputs over its rows of the tile at `sl`; `eps_tok`: eps in the
-  // units of this lane's token's denominator, `post`: factor on its un-normalized outputs (mixed form: the row's
-  // scale taken out again)
-  LF_DEV void multiply_block(unsigned char* sl, int tb, const u32x4 (&Bh)[KS], const u32x4 (&Bl)[NS == 2 ? KS : 1],
-                             float eps_tok, float post = 1.0f) {
-    f32x4 acc[RB];
-#pragma unroll
-    for (int b = 0; b < RB; ++b) acc[b] = f32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-#pragma unroll
-      for (int b = 0; b < RB; ++b) {
-        acc[b] = mfma_16x16x32<TA>(A[0][b][s], Bh[s], acc[b]);
-        if constexpr (NS == 2) {
-          acc[b] = mfma_16x16x32<TA>(A[0][b][s], Bl[s], acc[b]);
-          if (b < CB) acc[b] = mfma_16x16x32<TA>(A[1][b][s], Bh[s], acc[b]);
-        }
-      }
-    }
-    float scale = c1 * post;
-    if constexpr (NORM) {
-      // rows d and d + 1 (the normalizer and what its rounding left) are rows 0 and 1 of the last block: lanes
-      // 0-15 hold them for their tokens
-      const float part = acc[RB - 1][0] + acc[RB - 1][1];
-      const float den = __shfl(part, lane & 15) + eps_tok;
-      scale = c1 * __builtin_amdgcn_rcpf(den);
-    }
-#pragma unroll
-    for (int b = 0; b < CB; ++b) {
-      const u32x2 w = {pack2<T>(acc[b][0] * scale, acc[b][1] * scale), pack2<T>(acc[b][2] * scale, acc[b][3] * scale)};
-      // channels 16 b + 4 g .. + 3: chunk 2 b + g / 2, its first or second half
-      *reinterpret_cast<u32x2*>(sl + chunk_off(tb, 2 * b + (g >> 1)) + 8 * (g & 1)) = w;
-    }
-  }
-
-  // The tile in `slot` (it carries phi) -> its outputs, in place.  All LDS reads of a stretch are issued before its
-  // first product: a lone wave per SIMD has nobody to hide an LDS round trip per contraction step behind.
-  LF_DEV void compute_tile(int slot) {
-    unsigned char* sl = slot_ptr(slot);
-    if constexpr (kMixed) {
-      u32x4 R0[KS], R1[KS], none[1];
-      read_block(sl, slot, 0, R0, none);
-      read_block(sl, slot, 1, R1, none);   // block 0's outputs land in other rows
-      __builtin_amdgcn_sched_barrier(0);
-      float eps_tok, post;
-      make_operands(R0, eps_tok, post);
-      multiply_block(sl, 0, R0, none, eps_tok, post);
-      make_operands(R1, eps_tok, post);
-      multiply_block(sl, 1, R1, none, eps_tok, post);
-    } else if constexpr (NS == 1) {
-      u32x4 B0[KS], B1[KS], none[1];
-      read_block(sl, slot, 0, B0, none);
-      read_block(sl, slot, 1, B1, none);   // block 0's outputs land in other rows
-      __builtin_amdgcn_sched_barrier(0);
-      multiply_block(sl, 0, B0, none, eps_s);
-      multiply_block(sl, 1, B1, none, eps_s);
-    } else {
-#pragma unroll
-      for (int tb = 0; tb < 2; ++tb) {
-        u32x4 Bh[KS], Bl[KS];
-        read_block(sl, slot, tb, Bh, Bl);
-        __builtin_amdgcn_sched_barrier(0);
-        multiply_block(sl, tb, Bh, Bl, eps_s);
-      }
-    }
-  }
-
-  // Mixed form.  `B`: this lane's 8 KS stored channels of its token (lanes l, l + 16, l + 32, l + 48 hold one token
-  // between them) -> the fp16 operands phi~ = phi(q) 2^c 2^-e, where 2^c = exp(-m) if the row's largest channel m is
-  // negative under elu + 1 (else 1) and 2^e is the power of two at or below the row's largest phi 2^c, so the
-  // row's largest operand lies in [1, 2) whatever the bf16 inputs' magnitude.  eps_tok = eps' 2^c 2^-e is what eps
-  // becomes in that row's units (the factor cancels in Eq. 5's ratio), post = its inverse for the un-normalized form.
-  // A row without a positive phi (relu of non-positive channels) keeps operands 0 and gives 0, as the definition does;
-  // a NaN stays in its own token's outputs (the row maximum skips it).
+  // `B`: this lane's 8 KS stored channels of its token (lanes l, l + 16, l + 32, l + 48 hold one token between them)
+  // -> the fp16 operands phi~ = phi(q) 2^c 2^-e, where 2^c = exp(-m) if the row's largest channel m is negative
+  // under elu + 1 (else 1) and 2^e is the power of two at or below the row's largest phi 2^c, so the row's largest
+  // operand lies in [1, 2) whatever the inputs' magnitude.  eps_tok = eps' 2^c 2^-e is what eps becomes in that
+  // row's units (the factor cancels in Eq. 5's ratio), post = its inverse for the un-normalized form.  A row without
+  // a positive phi (relu of non-positive channels) keeps operands 0 and gives 0, as the definition does; a NaN stays
+  // in its own token's outputs (the row maximum skips it).
   LF_DEV void make_operands(u32x4 (&B)[KS], float& eps_tok, float& post) {
     constexpr float kLog2e = 1.44269504088896340736f;
-    float x[8 * KS];
+    // (the channels are unpacked twice, for the maximum and for phi, rather than kept: 8 KS more live registers
+    //  would not fit beside the head's operands at d = 160)
+    float m = -__builtin_inff();
 #pragma unroll
     for (int s = 0; s < KS; ++s)
 #pragma unroll
-      for (int w = 0; w < 4; ++w) unpack2<T>(B[s][w], x[8 * s + 2 * w], x[8 * s + 2 * w + 1]);
-    float m = FM == kPhiIdentity ? fabsf(x[0]) : x[0];
-#pragma unroll
-    for (int i = 1; i < 8 * KS; ++i) m = fmaxf(m, FM == kPhiIdentity ? fabsf(x[i]) : x[i]);
+      for (int w = 0; w < 4; ++w) {
+        float a, b;
+        unpack2<T>(B[s][w], a, b);
+        m = fmaxf(m, fmaxf(FM == kPhiIdentity ? fabsf(a) : a, FM == kPhiIdentity ? fabsf(b) : b));
+      }
     m = fmaxf(m, __shfl_xor(m, 16));
     m = fmaxf(m, __shfl_xor(m, 32));
     float c = 0.0f, top;   // top: the row's largest |phi 2^c|
@@ -408,13 +298,58 @@ struct ApplyWave {
 #pragma unroll
     for (int s = 0; s < KS; ++s)
 #pragma unroll
-      for (int w = 0; w < 4; ++w)
-        B[s][w] = pack2<TA>(phi_scaled<FM>(x[8 * s + 2 * w], c) * mult, phi_scaled<FM>(x[8 * s + 2 * w + 1], c) * mult);
+      for (int w = 0; w < 4; ++w) {
+        float a, b;
+        unpack2<T>(B[s][w], a, b);
+        B[s][w] = pack2<TA>(phi_scaled<FM>(a, c) * mult, phi_scaled<FM>(b, c) * mult);
+      }
     // eps' 2^c 2^-e in two finite factors (2^c alone leaves fp32's range from m = -88.7 on; the clamp only keeps
     // 0 * 2^c = 0 for eps = 0: beyond it the product is infinite anyway and the row's outputs are 0, as their true
     // size, below e^-131 / eps of the values', rounds to)
     eps_tok = __builtin_amdgcn_exp2f(fminf(c, 190.0f) - 64.0f) * (eps_s * mult * 0x1p64f);
     post = __builtin_amdgcn_exp2f(-c) * __builtin_bit_cast(float, f << 23);   // 2^-c 2^e
+  }
+
+  // multiply one block of 16 tokens and write its outputs over its rows of the tile at `sl`; `eps_tok`: eps in the
+  // units of this lane's token's denominator, `post`: the row's scale taken out of its un-normalized outputs
+  LF_DEV void multiply_block(unsigned char* sl, int tb, const u32x4 (&B)[KS], float eps_tok, float post) {
+    f32x4 acc[RB];
+#pragma unroll
+    for (int b = 0; b < RB; ++b) acc[b] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+#pragma unroll
+      for (int b = 0; b < RB; ++b) acc[b] = mfma_16x16x32<TA>(A[b][s], B[s], acc[b]);
+    }
+    float scale = c1 * post;
+    if constexpr (NORM) {
+      // rows d and d + 1 (the normalizer and what its rounding left) are rows 0 and 1 of the last block: lanes
+      // 0-15 hold them for their tokens
+      const float part = acc[RB - 1][0] + acc[RB - 1][1];
+      const float den = __shfl(part, lane & 15) + eps_tok;
+      scale = c1 * __builtin_amdgcn_rcpf(den);
+    }
+#pragma unroll
+    for (int b = 0; b < CB; ++b) {
+      const u32x2 w = {pack2<T>(acc[b][0] * scale, acc[b][1] * scale), pack2<T>(acc[b][2] * scale, acc[b][3] * scale)};
+      // channels 16 b + 4 g .. + 3: chunk 2 b + g / 2, its first or second half
+      *reinterpret_cast<u32x2*>(sl + chunk_off(tb, 2 * b + (g >> 1)) + 8 * (g & 1)) = w;
+    }
+  }
+
+  // The tile in `slot` (as stored) -> its outputs, in place.  All LDS reads are issued before the first use: a lone
+  // wave per SIMD has nobody to hide an LDS round trip per contraction step behind.
+  LF_DEV void compute_tile(int slot) {
+    unsigned char* sl = slot_ptr(slot);
+    u32x4 B0[KS], B1[KS];
+    read_block(sl, 0, B0);
+    read_block(sl, 1, B1);   // block 0's outputs land in other rows
+    __builtin_amdgcn_sched_barrier(0);
+    float eps_tok, post;
+    make_operands(B0, eps_tok, post);
+    multiply_block(sl, 0, B0, eps_tok, post);
+    make_operands(B1, eps_tok, post);
+    multiply_block(sl, 1, B1, eps_tok, post);
   }
 
   // Issue order per wave:  C0 C1 [state] | C2 K0 | S0 C3 K1 | S1 C4 K2 | ...  Before tile j is touched its copies
@@ -436,7 +371,6 @@ struct ApplyWave {
       const bool copied = ahead.valid();
       if (copied) issue_copy(ahead.t, have_prev ? prev_slot : R - 1);
       wait_groups((j >= 2 ? 2 : j) + (next_copied ? 1 : 0) + (copied ? 1 : 0));
-      if constexpr (!kMixed) phi_pass(slot);   // (mixed form: phi where the operands are read)
       compute_tile(slot);
       it.next();
       ahead.next();
@@ -450,18 +384,17 @@ struct ApplyWave {
   }
 };
 
-// grid = (wgs, heads), block = 256 (four waves that share nothing but the workgroup)
-// (TA: the operands' type; `packed` comes from pack_state_wave<TA, D>)
-template <typename T, int D, int FM, bool NORM, typename TA = T>
+// grid = (wgs, heads), block = 256 (four waves that share nothing but the workgroup); `packed` from pack_state_wave<D>
+template <typename T, int D, int FM, bool NORM>
 __global__ void __launch_bounds__(kThreads)
 apply16_wave(const u32x4* __restrict__ Q, Layout lq, u32x4* __restrict__ O, Layout lo, HeadSubset hs,
              const unsigned char* __restrict__ packed, float eps, long long N, int tiles_per_block) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const long long bh = hs.bh(blockIdx.y, lq.H);
-  ApplyWave<T, D, FM, NORM, TA> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
-                                   gridDim.x, smem);
+  ApplyWave<T, D, FM, NORM> ap(Q + lq.slice(bh), lq.row, O + lo.slice(bh), lo.row, N, tiles_per_block, blockIdx.x,
+                               gridDim.x, smem);
   ap.prefetch();
-  ap.load_packed(packed + bh * PackWave<TA, D>::kHeadBytes, eps);
+  ap.load_packed(packed + bh * PackWave<D>::kHeadBytes, eps);
   ap.stream();
 }
 

@@ -12,10 +12,8 @@ namespace {
 
 using lfh::allow_lds;
 
-// apply16_wave holds the (d + 2) x d operands of a head in one wave's registers.  They are fp16 for both storage
-// types: bf16 tensors take the mixed form (query rows scaled into fp16's range as they are read), since two levels
-// of bf16 operands do not fit at d = 160 and triple the products everywhere.
-using WaveOperand = lf::F16;
+// apply16_wave holds the (d + 2) x d fp16 operands of a head in one wave's registers, for both storage types
+// (query rows are scaled into fp16's range as they are read): built for every wide width.
 template <typename T, int D> constexpr bool wave_ok() { return true; }
 
 template <typename T, int D>
@@ -70,12 +68,12 @@ int apply(const WideApplyArgs& a) {
   }
 #define LFW_APPLY_WAVE(FM, NORM)                                                                             \
   if constexpr (wave_ok<T, D>()) {                                                                          \
-    constexpr int lds2 = apply16_wave_lds_bytes<WaveOperand, D>();                                           \
-    if (!allow_lds(apply16_wave<T, D, FM, NORM, WaveOperand>, lds2)) return LINFUSION_ERR_HIP;               \
-    pack_state_wave<WaveOperand, D><<<dim3(ApplyWaveShape<D>::kKS, (unsigned)BH), blk, 0, st>>>(             \
-        a.state, a.packed, NORM ? 1 : 0);                                                                    \
-    apply16_wave<T, D, FM, NORM, WaveOperand><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, \
-                                                                     a.N, a.plan.blk_apply);                 \
+    constexpr int lds2 = apply16_wave_lds_bytes<D>();                                                        \
+    if (!allow_lds(apply16_wave<T, D, FM, NORM>, lds2)) return LINFUSION_ERR_HIP;                            \
+    pack_state_wave<D><<<dim3(ApplyWaveShape<D>::kKS, (unsigned)BH), blk, 0, st>>>(a.state, a.packed,        \
+                                                                                  NORM ? 1 : 0);             \
+    apply16_wave<T, D, FM, NORM><<<g2, blk, lds2, st>>>(Q, a.lq, O, a.lo, all, a.packed, a.eps, a.N,         \
+                                                        a.plan.blk_apply);                                   \
   } else {                                                                                                   \
     return LINFUSION_ERR_UNSUPPORTED;                                                                        \
   }
@@ -116,7 +114,7 @@ template <typename T, int D>
 constexpr size_t pack_bytes() {
   size_t b = lf::PackWide<T, D, 4>::kHeadBytes > lf::PackWide<T, D, 8>::kHeadBytes ? lf::PackWide<T, D, 4>::kHeadBytes
                                                                                    : lf::PackWide<T, D, 8>::kHeadBytes;
-  if (wave_ok<T, D>() && (size_t)lf::PackWave<WaveOperand, D>::kHeadBytes > b) b = lf::PackWave<WaveOperand, D>::kHeadBytes;
+  if (wave_ok<T, D>() && (size_t)lf::PackWave<D>::kHeadBytes > b) b = lf::PackWave<D>::kHeadBytes;
   return b;
 }
 

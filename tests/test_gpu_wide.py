@@ -87,13 +87,16 @@ def test_wave_apply_is_chosen_at_every_wide_width():
     assert all(v == "apply16_wave" for v in names.values()), names
 
 
-@pytest.mark.parametrize("d", [96, 160])
-@pytest.mark.parametrize("case", ["q-20", "q-60", "some_rows_q-300", "q+3000", "some_rows_q*1e30", "q*1e-20",
-                                  "one_channel_up"])
-def test_bf16_query_rows_of_any_magnitude(case, d):
-    """bf16 tensors at the wide widths are multiplied as fp16 operands; every query row is scaled into fp16's range
-    by its own largest channel (the factor cancels in the ratio once eps carries it), so rows far below zero, rows
-    of huge values and rows of tiny ones must come out as the definition gives them."""
+@pytest.mark.parametrize("d,dtype", [(96, "bf16"), (160, "bf16"), (160, "f16"), (128, "f16")])
+@pytest.mark.parametrize("case", ["q-20", "q-60", "some_rows_q-300", "q+3000", "q_near_the_top", "some_rows_q*1e30",
+                                  "q*1e-20", "one_channel_up"])
+def test_wide_query_rows_of_any_magnitude(case, d, dtype):
+    """At the wide widths both storage types are multiplied as fp16 operands; every query row is scaled into fp16's
+    range by its own largest channel as it is read (the factor cancels in the ratio once eps carries it), so rows far
+    below zero (exp(q) subnormal or zero in fp16), rows of huge values (q + 1 beyond 65504) and rows of tiny ones
+    must come out as the definition gives them."""
+    if dtype == "f16" and case in ("some_rows_q*1e30", "q*1e-20"):
+        pytest.skip("outside what fp16 storage holds")
     B, H, N = 1, 2, 777
     q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=76, device="cpu")
     if case == "q-20":
@@ -104,6 +107,8 @@ def test_bf16_query_rows_of_any_magnitude(case, d):
         q[:, :, ::3] -= 300.0
     elif case == "q+3000":
         q = q * 500.0 + 3000.0
+    elif case == "q_near_the_top":
+        q = q * 2500.0 + 50000.0
     elif case == "some_rows_q*1e30":
         q[:, :, 1::2] *= 1e30
     elif case == "q*1e-20":
@@ -111,21 +116,22 @@ def test_bf16_query_rows_of_any_magnitude(case, d):
     else:
         q = q - 30.0
         q[:, :, :, 7] += 25.0 + 10.0 * torch.rand(B, H, N)
-    q, k, v = q.bfloat16(), k.bfloat16(), v.bfloat16()
-    assert lf.linfusion_attn_apply_kernel(B, H, N, d, lf.DTYPE_BF16) == "apply16_wave"
+    tt = torch.bfloat16 if dtype == "bf16" else torch.float16
+    q, k, v = q.to(tt), k.to(tt), v.to(tt)
+    assert lf.linfusion_attn_apply_kernel(B, H, N, d, wl.DTYPE_CODE[dtype]) == "apply16_wave"
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     for eps in (1e-6, 0.0):
         out = torch.full_like(qd, float("nan"))
-        lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, eps, 0, _ws(B, H, N, d, "bf16"))
+        lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, eps, 0, _ws(B, H, N, d, dtype))
         torch.cuda.synchronize()
-        worst = parity.check_all(out, q, k, v, "bf16", 0, eps, True, f"{case} d={d} eps={eps}")
-        print(f"{case} d={d} eps={eps}: worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
+        worst = parity.check_all(out, q, k, v, dtype, 0, eps, True, f"{case} d={d} {dtype} eps={eps}")
+        print(f"{case} d={d} {dtype} eps={eps}: worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
     if case in ("q-20", "some_rows_q-300", "q+3000"):      # the un-normalized arm takes the row's factor out again
-        vs = (v.float() * (1e-4 if case == "q+3000" else 0.01)).bfloat16()
+        vs = (v.float() * (1e-4 if case == "q+3000" else 0.01)).to(tt)
         out = torch.full_like(qd, float("nan"))
-        lf.linfusion_attn_fwd_ex(qd, kd, vs.cuda(), out, 0, 1e-6, lf.FLAG_UNNORMALIZED, _ws(B, H, N, d, "bf16"))
+        lf.linfusion_attn_fwd_ex(qd, kd, vs.cuda(), out, 0, 1e-6, lf.FLAG_UNNORMALIZED, _ws(B, H, N, d, dtype))
         torch.cuda.synchronize()
-        parity.check_all(out, q, k, vs, "bf16", 0, 1e-6, False, f"{case} d={d} unnormalized")
+        parity.check_all(out, q, k, vs, dtype, 0, 1e-6, False, f"{case} d={d} {dtype} unnormalized")
 
 
 @pytest.mark.parametrize("d,dtype", [(80, "f16"), (160, "f16"), (80, "bf16"), (160, "bf16"), (96, "f16"), (128, "bf16")])
