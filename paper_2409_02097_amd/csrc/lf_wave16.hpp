@@ -83,13 +83,26 @@ pack_state_wave(const float* __restrict__ state, unsigned char* __restrict__ pac
   const float* st = state + bh * NE;
   unsigned char* out = packed + bh * PackWave<D>::kHeadBytes;
 
-  float mS = 0.0f, mz = 0.0f;
-  const f32x4* st4 = reinterpret_cast<const f32x4*>(st);
-  for (int e = tid; e < NE / 4; e += kThreads) {     // D*D and D are multiples of 4
-    const f32x4 x = st4[e];
-    const float m = fmaxf(fmaxf(fabsf(x[0]), fabsf(x[1])), fmaxf(fabsf(x[2]), fabsf(x[3])));
-    if (e < D * D / 4) mS = fmaxf(mS, m); else mz = fmaxf(mz, m);
+  // this wave's row blocks b = wave, wave + 4, ..: their raw values are requested before the maxima are known, so that
+  // the kernel waits for memory once
+  constexpr int NB = (RB + kWavesPerWG - 1) / kWavesPerWG;
+  const int g = lane >> 4;
+  float raw[NB][8];
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int b = wave + kWavesPerWG * i;
+    const int m = 16 * b + (lane & 15);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int ch = 32 * s + 8 * g + j;
+      int at = ch * D;                                  // (rows past d + 1 and blocks past the end: a valid place, unused)
+      if (m < D) at = ch * D + m;
+      else if (m <= D + 1) at = D * D + ch;
+      raw[i][j] = st[at];
+    }
   }
+  float mS, mz;
+  state_maxima_share<D, kThreads>(st, tid, mS, mz);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     mS = fmaxf(mS, __shfl_xor(mS, o));
@@ -109,28 +122,30 @@ pack_state_wave(const float* __restrict__ state, unsigned char* __restrict__ pac
   }
 
   u32x4* frag = reinterpret_cast<u32x4*>(out + PackWave<D>::kHeaderBytes);
-  const int g = lane >> 4;
-  for (int b = wave; b < RB; b += kWavesPerWG) {
-    const int m = 16 * b + (lane & 15);
-    u32x4 w4;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      float v2[2];
+  for (int i = 0; i < NB; ++i) {
+    const int b = wave + kWavesPerWG * i;
+    if (b < RB) {
+      const int m = 16 * b + (lane & 15);
+      u32x4 w4;
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const int ch = 32 * s + 8 * g + 2 * w + q;
-        float x = 0.0f;
-        bool zrem = false;
-        if (m < D) x = st[ch * D + m] * aS;
-        else if (normalize && m == D) x = st[D * D + ch] * az;
-        else if (normalize && m == D + 1) { x = st[D * D + ch] * az; zrem = true; }
-        float r0, r1;
-        unpack2<F16>(pack2<F16>(x, 0.0f), r0, r1);   // x rounded once to fp16
-        v2[q] = zrem ? x - r0 : x;
+      for (int w = 0; w < 4; ++w) {
+        float v2[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          float x = 0.0f;
+          bool zrem = false;
+          if (m < D) x = raw[i][2 * w + q] * aS;
+          else if (normalize && m == D) x = raw[i][2 * w + q] * az;
+          else if (normalize && m == D + 1) { x = raw[i][2 * w + q] * az; zrem = true; }
+          float r0, r1;
+          unpack2<F16>(pack2<F16>(x, 0.0f), r0, r1);   // x rounded once to fp16
+          v2[q] = zrem ? x - r0 : x;
+        }
+        w4[w] = pack2<F16>(v2[0], v2[1]);
       }
-      w4[w] = pack2<F16>(v2[0], v2[1]);
+      frag[(b * KS + s) * 64 + lane] = w4;
     }
-    frag[(b * KS + s) * 64 + lane] = w4;
   }
 }
 
