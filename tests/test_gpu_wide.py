@@ -134,6 +134,33 @@ def test_wide_query_rows_of_any_magnitude(case, d, dtype):
         parity.check_all(out, q, k, vs, dtype, 0, 1e-6, False, f"{case} d={d} {dtype} unnormalized")
 
 
+@pytest.mark.parametrize("d,dtype", [(160, "f16"), (160, "bf16"), (96, "bf16")])
+def test_wide_nan_stays_where_it_belongs(d, dtype):
+    """A NaN in one query row reaches that token's outputs only (the row's maximum, which scales the row, skips it and
+    the other rows are bit-identical to a clean run); a NaN in a key poisons its own head and no other."""
+    B, H, N = 1, 3, 333
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=77, device="cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    ws = _ws(B, H, N, d, dtype)
+    clean = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, clean, 0, 1e-6, 0, ws)
+    qn = qd.clone()
+    qn[0, 1, 200, 17] = float("nan")
+    out = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qn, kd, vd, out, 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(out[0, 1, 200]).all()), "the poisoned token must not produce numbers"
+    keep = torch.ones(B, H, N, dtype=torch.bool, device="cuda")
+    keep[0, 1, 200] = False
+    assert torch.equal(out[keep].view(torch.uint8), clean[keep].view(torch.uint8)), "other tokens changed"
+    kn = kd.clone()
+    kn[0, 2, 100, 5] = float("nan")
+    lf.linfusion_attn_fwd_ex(qd, kn, vd, out, 0, 1e-6, 0, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(out[0, 2]).all()), "the poisoned head must not produce numbers"
+    assert torch.equal(out[0, :2].view(torch.uint8), clean[0, :2].view(torch.uint8)), "other heads changed"
+
+
 @pytest.mark.parametrize("d,dtype", [(80, "f16"), (160, "f16"), (80, "bf16"), (160, "bf16"), (96, "f16"), (128, "bf16")])
 def test_wide_heads_token_major_and_in_place(d, dtype):
     B, H, N = 2, 4, 700
