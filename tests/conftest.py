@@ -25,3 +25,11 @@ def tuning():
     lf.linfusion_set_tuning(True)
     yield
     lf.linfusion_set_tuning(False)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """The largest result-relative gradient errors the run met (tests/parity.py: check_gradients)."""
+    from tests import parity
+    if parity.REL_L2_SEEN:
+        terminalreporter.write_line("largest relative L2 error of a gradient tensor beyond its half ulp: " + ", ".join(
+            f"{d} {n} {v:.2e}" for (d, n), v in sorted(parity.REL_L2_SEEN.items())))

@@ -96,6 +96,12 @@ def gradient_term_scales(q, k, v, g, fm, eps, normalize):
     return sq.max(), sk.max(), sv.max()
 
 
+# Result-relative bound on a whole gradient tensor (beyond the half ulp of its storage type): ||gpu - ref|| / ||ref||.
+# Gradients cancel, so single elements cannot be held to a relative bound, but the tensor as a whole can.
+GRAD_REL_L2 = {"f16": 2e-3, "bf16": 2e-3, "f32": 1e-5}   # the forward budgets; measured 7e-4, 5e-7, 4e-7
+REL_L2_SEEN = {}
+
+
 def check_gradients(got, q, k, v, g, dtype, fm=0, eps=1e-6, normalize=True, what=""):
     """got = (dq, dk, dv) of one (b, h) slice as fp64 arrays; q, k, v, g the slice's widened inputs.
     |gpu - ref| <= tol * (largest sum of absolute terms in the slice) + half an ulp of the output type."""
@@ -110,4 +116,13 @@ def check_gradients(got, q, k, v, g, dtype, fm=0, eps=1e-6, normalize=True, what
         assert (err - bound).max() <= 0, (f"{what} {name}: error {err.max():.3e} vs term scale "
                                           f"{scale:.3e} (ratio {err.max() / scale:.3e}, tol {tol:g})")
         worst = max(worst, float((err / scale).max()))
+        # result-relative as well: the error of the whole gradient tensor against its own size (half an ulp of every
+        # output allowed for, as above)
+        beyond = np.maximum(err - orc.half_ulp(want, dtype), 0.0)
+        rel = float(np.sqrt((beyond ** 2).sum()) / max(np.sqrt((want ** 2).sum()), 1e-300))
+        # (only where the tensor is not itself a cancellation: with a single token dq is exactly zero, and the measure
+        #  would divide rounding noise by rounding noise)
+        if np.sqrt((want ** 2).mean()) >= 1e-2 * scale:
+            REL_L2_SEEN[(dtype, name)] = max(REL_L2_SEEN.get((dtype, name), 0.0), rel)
+            assert rel <= GRAD_REL_L2[dtype], f"{what} {name}: relative L2 error {rel:.3e} (bound {GRAD_REL_L2[dtype]:g})"
     return worst
