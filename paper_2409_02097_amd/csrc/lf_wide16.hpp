@@ -93,16 +93,9 @@ state_reduce16_wide(const u32x4* __restrict__ K, Layout kl, const u32x4* __restr
   const int tr_base = (8 * g4 + (j16 >> 2)) * RS + 4 * (j16 & 3);
 
   const long long n_tiles = (N + kTile - 1) / kTile;
-  TileIter it(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);
 
   f32x4 acc[MT][NBW];
   f32x4 accz[NBW];
-#pragma unroll
-  for (int i = 0; i < NBW; ++i) {
-    accz[i] = f32x4{0, 0, 0, 0};
-#pragma unroll
-    for (int a = 0; a < MT; ++a) acc[a][i] = f32x4{0, 0, 0, 0};
-  }
   const uint32_t one2 = (uint32_t)OneBits<T>::value * 0x10001u;
   const u32x4 ones = {one2, one2, one2, one2};
 
@@ -125,6 +118,26 @@ state_reduce16_wide(const u32x4* __restrict__ K, Layout kl, const u32x4* __restr
     return lim;
   };
 
+  // fp16 with elu + 1: phi(k) = exp(k) of keys far below zero leaves fp16's normal range (see reduce16_phase: the same
+  // remedy here, decided by the workgroup as a whole since its waves share every tile): a stream whose normalizer sums
+  // all stay below (tokens) 2^-11 is scanned for its largest key m and, if that is far below zero, summed again with
+  // phi(k) = exp(k - m); the factor exp(m) is taken out of the fp32 sums afterwards.  Never taken for ordinary data.
+  constexpr bool kRescan = NS == 1 && FM == kPhiEluPlusOne;
+  constexpr float kRescanBelow = -5.0f, kShiftFloor = -64.0f, kLog2e = 1.44269504088896340736f;
+  __shared__ float wgmax[kWavesPerWG];
+
+  // The workgroup's whole stream, sums of phi(k) 2^kc (x) v into acc / accz; a second pass (fp16, elu + 1 only)
+  // where the first one's normalizer sums call for it.
+  float kc = 0.0f;
+  for (int pass = 0;; ++pass) {
+  TileIter it(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);
+#pragma unroll
+  for (int i = 0; i < NBW; ++i) {
+    accz[i] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int a = 0; a < MT; ++a) acc[a][i] = f32x4{0, 0, 0, 0};
+  }
+  long long tokens = 0;
   int lim = 0;
   if (it.valid()) lim = issue_loads(it.t);
   static_assert(BUF % 8 == 0, "16-byte fill");
@@ -133,6 +146,7 @@ state_reduce16_wide(const u32x4* __restrict__ K, Layout kl, const u32x4* __restr
 
   int buf = 0;
   while (it.valid()) {
+    tokens += lim;
     uint16_t* bufp = lds + buf * BUF;
 #pragma unroll
     for (int u = 0; u < NL; ++u) {
@@ -142,7 +156,7 @@ state_reduce16_wide(const u32x4* __restrict__ K, Layout kl, const u32x4* __restr
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           if constexpr (NS == 1 && kPhiKillsLowest<FM>) {
-            ph[w] = phi_pack2<T, FM>(kr[u][w]);
+            ph[w] = kRescan ? phi_pack2_scaled<T, FM>(kr[u][w], kc) : phi_pack2<T, FM>(kr[u][w]);
             continue;
           }
           float x0, x1;
@@ -198,6 +212,65 @@ state_reduce16_wide(const u32x4* __restrict__ K, Layout kl, const u32x4* __restr
     }
     buf ^= 1;
     lim = next_lim;
+  }
+  if constexpr (!kRescan) {
+    break;
+  } else {
+    if (pass == 1) {
+      const float back = __builtin_amdgcn_exp2f(-kc);      // the rescanned sums carry 2^kc
+#pragma unroll
+      for (int i = 0; i < NBW; ++i) {
+        accz[i] *= back;
+#pragma unroll
+        for (int a = 0; a < MT; ++a) acc[a][i] *= back;
+      }
+      break;
+    }
+    // largest normalizer sum of the workgroup (accz: z of rows a = wave mod 4, every column holds it)
+    float zm = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NBW; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) zm = fmaxf(zm, accz[i][e]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) zm = fmaxf(zm, __shfl_xor(zm, o));
+    __syncthreads();   // (every wave has left the stream's last tile)
+    if (lane == 0) wgmax[wave] = zm;
+    __syncthreads();
+    zm = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerWG; ++w) zm = fmaxf(zm, wgmax[w]);
+    if (!(zm < (float)tokens * 0x1p-11f)) break;   // ordinary data, a workgroup without tiles (0 < 0), NaNs
+    // the stream's largest key
+    f16x2 kmax2 = __builtin_bit_cast(f16x2, LowestBits<F16>::value);
+    {
+      TileIter jt(blockIdx.x, gridDim.x, 0, tiles_per_block, n_tiles, 1);
+      while (jt.valid()) {
+        (void)issue_loads(jt.t);
+#pragma unroll
+        for (int u = 0; u < NL; ++u) {
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            const uint32_t word = kr[u][w];
+            kmax2 = __builtin_elementwise_max(kmax2, __builtin_bit_cast(f16x2, word));
+          }
+        }
+        jt.next();
+      }
+    }
+    float m = fmaxf((float)kmax2[0], (float)kmax2[1]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    __syncthreads();
+    if (lane == 0) wgmax[wave] = m;
+    __syncthreads();
+    m = wgmax[0];
+#pragma unroll
+    for (int w = 1; w < kWavesPerWG; ++w) m = fmaxf(m, wgmax[w]);
+    // (not small after all -- many tokens of middling keys -- or nothing but the most negative value: keep the sums)
+    if (!(m < kRescanBelow && m > -65504.0f)) break;
+    kc = fmaxf(m, kShiftFloor) * -kLog2e;
+  }
   }
 
   // ---- each wave writes its columns of the partial (lane: rows 4 (l / 16) + i, column l % 16 of a block) ----

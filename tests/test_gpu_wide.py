@@ -134,6 +134,33 @@ def test_wide_query_rows_of_any_magnitude(case, d, dtype):
         parity.check_all(out, q, k, vs, dtype, 0, 1e-6, False, f"{case} d={d} {dtype} unnormalized")
 
 
+@pytest.mark.parametrize("d", [96, 160])
+@pytest.mark.parametrize("case", ["k-12", "k-20", "k-20_q-20", "some_tokens_k-25", "k-70"])
+def test_wide_fp16_keys_far_below_zero(case, d):
+    """exp(k) of fp16 keys far below zero is subnormal or zero as an fp16 operand, but the definition still gives a
+    proper weighted mean: a stream whose normalizer sums show it is summed again relative to its largest key."""
+    B, H, N = 1, 2, 777
+    q, k, v = wl.make_qkv(B, H, N, d, "f32", idx=78, device="cpu")
+    if case == "k-12":
+        k = k - 12.0
+    elif case in ("k-20", "k-20_q-20"):
+        k = k - 20.0
+    elif case == "some_tokens_k-25":
+        k[:, :, ::2] -= 25.0
+    else:
+        k = k * 3.0 - 70.0
+    if case == "k-20_q-20":
+        q = q - 20.0
+    q, k, v = q.half(), k.half(), v.half()
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    for eps in (1e-6, 0.0):
+        out = torch.full_like(qd, float("nan"))
+        lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, eps, 0, _ws(B, H, N, d, "f16"))
+        torch.cuda.synchronize()
+        worst = parity.check_all(out, q, k, v, "f16", 0, eps, True, f"{case} d={d} eps={eps}")
+        print(f"{case} d={d} eps={eps}: worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
+
+
 @pytest.mark.parametrize("d,dtype", [(160, "f16"), (160, "bf16"), (96, "bf16")])
 def test_wide_nan_stays_where_it_belongs(d, dtype):
     """A NaN in one query row reaches that token's outputs only (the row's maximum, which scales the row, skips it and
