@@ -35,6 +35,12 @@
  *     d = 80 and d = 160 (the deeper levels of the SD-v1.5 UNet: 640 and 1280 channels over 8 heads) and
  *     d = 96, 128.  Widths above 80 run on the three-kernel path only (LINFUSION_FLAG_FORCE_FUSED ->
  *     LINFUSION_ERR_UNSUPPORTED).
+ *   - Arithmetic: every sum over tokens or channels is accumulated in fp32; the state is rescaled by a power of
+ *     two before it becomes a 16-bit matrix-core operand.  Operands are rounded once to fp16 for fp16 tensors
+ *     (relative 2^-12 each); carried as two bf16 levels (about 16 bits) for bf16 tensors, except in the apply
+ *     kernel of the widths above 80, which multiplies bf16 tensors as fp16 operands after scaling every query
+ *     row into fp16's range (the factor cancels in Eq. 5's ratio); fp32 tensors never pass through 16-bit
+ *     products of fewer than 24 bits.  The result is rounded once, to nearest even, to the tensors' type.
  */
 #ifndef LINFUSION_H_
 #define LINFUSION_H_
