@@ -515,7 +515,8 @@ def main():
             whole_rows = False
         elif d > 80:
             route = "statistics pass + wide kernels"
-            rname, aname = "mlp_rowstats16 + state_reduce16_wide_mlp", "apply16_wide_mlp"
+            rname = "mlp_rowstats16 + state_reduce16_wide_mlp"
+            aname = "apply16_wave_mlp"
         else:
             route = "statistics pass + per-head kernels"
             rname, aname = "mlp_rowstats16 + state_reduce16_mlph", "apply16_mlph"

@@ -76,6 +76,25 @@ int run_wide_t(const HeadsArgs& a) {
   if (a.ev) (void)hipEventRecord(a.ev[1], st);
   combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, heads), dim3(kCombineThreads), 0, st>>>(
       a.partials, a.splits, NE, a.state);
+  // A wave per 16-token tile with the head's whole state in its registers (apply16_wave_mlp), one long-lived
+  // workgroup per CU.  (LINFUSION_MLPW_WAVE_APPLY = 2 under tuning: the workgroup-shared kernel instead)
+  {
+    if (lfh::env_int("LINFUSION_MLPW_WAVE_APPLY", 1) == 1) {
+      constexpr int lds_w = ApplyWaveMlpShape<D>::kLdsBytes;
+      if (!allow_lds(apply16_wave_mlp<T, D, FM, NORM>, lds_w)) return LINFUSION_ERR_HIP;
+      pack_state_wave<D><<<dim3(ApplyWaveShape<D>::kKS, heads), dim3(kThreads), 0, st>>>(a.state, a.packed, NORM ? 1 : 0);
+      if (a.ev) (void)hipEventRecord(a.ev[2], st);
+      const long long tiles = (a.N + ApplyWaveMlpShape<D>::kTok - 1) / ApplyWaveMlpShape<D>::kTok;
+      const long long most = (tiles + kWavesPerWG - 1) / kWavesPerWG;   // every wave gets a tile
+      long long wgs = lfh::env_int("LINFUSION_MLPW_WAVE_WGS", lfh::num_cu()) / (long long)heads;
+      wgs = wgs > most ? most : (wgs < 1 ? 1 : wgs);
+      apply16_wave_mlp<T, D, FM, NORM><<<dim3((unsigned)wgs, heads), dim3(kThreads), lds_w, st>>>(
+          (const u32x4*)a.a_q, (const u32x4*)a.t_q, a.in_batch, row, (u32x4*)a.out, a.out_batch, row_o, a.H, stats_q,
+          a.n_pad, a.gamma_q, a.beta_q, a.slope, a.packed, a.eps, a.N, kWavesPerWG);
+      if (a.ev) (void)hipEventRecord(a.ev[3], st);
+      return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
+    }
+  }
   pack_state_wide<T, D, WA><<<dim3(ApplyWideShape<D, WA>::kKS, heads), dim3(64 * WA), 0, st>>>(a.state, a.packed,
                                                                                              NORM ? 1 : 0);
   if (a.ev) (void)hipEventRecord(a.ev[2], st);

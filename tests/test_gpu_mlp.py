@@ -306,6 +306,38 @@ def test_wide_heads_match_oracle(B, H, N, d, dtype):
     _check(out, _oracle(ins, H, dtype), H, dtype, f"mlp wide {B}x{H}x{N}x{d} {dtype}")
 
 
+@pytest.mark.parametrize("B,H,N,d,dtype", [(1, 8, 1000, 160, "f16"), (2, 8, 333, 160, "bf16"), (1, 5, 2051, 96, "bf16"),
+                                           (1, 4, 515, 128, "f16")])
+def test_wide_heads_on_the_workgroup_shared_apply(B, H, N, d, dtype, monkeypatch, tuning):
+    """By default apply runs a wave per 16-token tile (apply16_wave_mlp); the workgroup-shared kernel that it replaced
+    stays in the library as a tuning aid and is checked against the oracle too."""
+    monkeypatch.setenv("LINFUSION_MLPW_WAVE_APPLY", "2")
+    ins = wl.make_mlp_inputs(B, H, N, d, dtype, idx=93)
+    out = _run(ins, H)
+    _check(out, _oracle(ins, H, dtype), H, dtype, f"mlp wide, shared tiles {B}x{H}x{N}x{d} {dtype}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("case", ["a-20", "a+3000", "some_rows_a-300"])
+def test_wide_heads_query_rows_far_from_one(case, dtype):
+    """The formed query a + LeakyReLU(LayerNorm(t)) far below zero or large: bf16 rows are scaled into fp16's range
+    as they are formed; fp16 rows keep fp16's own range (so -20 stays inside what exp leaves representable)."""
+    if dtype == "f16" and case == "some_rows_a-300":
+        pytest.skip("exp(-300) is zero in an fp16 operand: covered for bf16, whose rows are scaled")
+    B, H, N, d = 1, 8, 333, 160
+    ins = list(wl.make_mlp_inputs(B, H, N, d, dtype, idx=96))
+    a = ins[0].float()
+    if case == "a-20":
+        a = a - (8.0 if dtype == "f16" else 20.0)
+    elif case == "a+3000":
+        a = a * 500.0 + 3000.0
+    else:
+        a[:, ::3] -= 300.0
+    ins[0] = a.to(ins[0].dtype)
+    out = _run(ins, H)
+    _check(out, _oracle(ins, H, dtype), H, dtype, f"mlp wide {case} {dtype}")
+
+
 @pytest.mark.parametrize("fm", [0, 1, 2])
 @pytest.mark.parametrize("unnorm", [False, True])
 def test_wide_heads_feature_maps_and_unnormalized(fm, unnorm):
