@@ -358,6 +358,8 @@ def main():
     mid = "combine_state + pack_state16" if aname.startswith("apply16_packed") else "combine_state"
     if d > 80:
         rname = rname.replace("state_reduce16<", "state_reduce16_wide<")
+        if (N + 31) // 32 <= 2:
+            mid = "(no combine: one workgroup per head wrote the state)"
     elif args.layout == "token_major" and dtype != "f32" and (d * 2) % 128 != 0 and H >= 4:
         # heads adjacent in memory and rows that are not whole 128-byte lines: the row-piece kernels run
         rname = rname.replace("state_reduce16<", "state_reduce16_rows<")

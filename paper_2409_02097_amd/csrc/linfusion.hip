@@ -170,6 +170,12 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
       return (int)((p->n_tiles + t - 1) / t);
     };
     p->splits = per_head(env_int("LINFUSION_WIDE_REDUCE_WGS", 2 * num_cu()), 4, "LINFUSION_WIDE_REDUCE_BLK", &p->blk_reduce);
+    // a head of one or two tiles: one workgroup sums them and writes the state itself (no partials, no combine
+    // launch; from four tiles on a workgroup's tiles in sequence cost more than the launch saved)
+    if (p->n_tiles <= env_int("LINFUSION_WIDE_ONE_SPLIT_TILES", 2)) {
+      p->splits = 1;
+      p->blk_reduce = (int)p->n_tiles;
+    }
     // apply: a wave per tile with the head's whole state in its registers where that fits (one workgroup
     // per CU, long-lived: its prologue loads the (d + 2) x d operands), else the workgroup-shared tiles
     p->wave_apply = lfw::wave_apply_supported(d, dtype) && env_int("LINFUSION_WIDE_WAVE_APPLY", 1) == 1;   // 2: never

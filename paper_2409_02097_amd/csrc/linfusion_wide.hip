@@ -28,11 +28,14 @@ int reduce(const WideReduceArgs& a, hipEvent_t* ev) {
   hipStream_t st = a.st;
   constexpr int lds1 = reduce16_wide_lds_bytes<T, D>();
   const dim3 g1(a.plan.splits, (unsigned)BH);
+  // one workgroup per head: its partial is the state (same layout), and there is nothing to combine
+  const bool direct = a.plan.splits == 1;
+  float* part = direct ? a.state : a.partials;
   if (ev) (void)hipEventRecord(ev[0], st);
 #define LFW_REDUCE(FM)                                                                       \
   {                                                                                          \
     if (!allow_lds(state_reduce16_wide<T, D, FM>, lds1)) return LINFUSION_ERR_HIP;           \
-    state_reduce16_wide<T, D, FM><<<g1, blk, lds1, st>>>(K, a.lk, V, a.lv, all, a.partials, a.N, a.plan.blk_reduce); \
+    state_reduce16_wide<T, D, FM><<<g1, blk, lds1, st>>>(K, a.lk, V, a.lv, all, part, a.N, a.plan.blk_reduce); \
   }
   switch (a.fm) {
     case 0: LFW_REDUCE(0) break;
@@ -41,8 +44,9 @@ int reduce(const WideReduceArgs& a, hipEvent_t* ev) {
   }
 #undef LFW_REDUCE
   if (ev) (void)hipEventRecord(ev[1], st);
-  combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, st>>>(
-      a.partials, a.plan.splits, NE, a.state);
+  if (!direct)
+    combine_state<0><<<dim3((NE + kCombineElems - 1) / kCombineElems, (unsigned)BH), dim3(kCombineThreads), 0, st>>>(
+        a.partials, a.plan.splits, NE, a.state);
   if (ev) (void)hipEventRecord(ev[2], st);
   return hipGetLastError() == hipSuccess ? LINFUSION_OK : LINFUSION_ERR_HIP;
 }

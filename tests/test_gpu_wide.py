@@ -62,6 +62,23 @@ def test_workgroup_shared_apply_where_the_wave_apply_is_the_default(B, H, N, d, 
     parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"shared-tile apply N={N} d={d} {dtype} waves={waves}")
 
 
+@pytest.mark.parametrize("N,d,dtype,limit", [(1000, 160, "f16", 32), (1000, 160, "f16", 1), (33, 96, "bf16", 2),
+                                             (33, 96, "bf16", 1), (420, 128, "bf16", 16)])
+def test_heads_of_few_tiles_with_and_without_partials(N, d, dtype, limit, monkeypatch, tuning):
+    """Heads of one or two tiles are summed by one workgroup that writes the state itself (no partials, no combine
+    launch).  Both routes on the same shapes: the limit raised so that one workgroup walks dozens of tiles to a
+    ragged last one, and lowered so that the partials and the combine kernel run."""
+    B, H = 2, 3
+    print(f"one-workgroup heads N={N} d={d} {dtype} limit={limit}", flush=True)
+    monkeypatch.setenv("LINFUSION_WIDE_ONE_SPLIT_TILES", str(limit))
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=91, device="cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    out = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, 1e-6, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"one-workgroup heads N={N} d={d} {dtype} limit={limit}")
+
+
 @pytest.mark.parametrize("wgs,blk", [(4, 4), (6, 8), (2, 64)])
 @pytest.mark.parametrize("N,d,dtype", [(20011, 160, "f16"), (9000, 128, "bf16"), (6000, 96, "bf16"), (20011, 160, "bf16")])
 def test_wave_apply_with_many_tiles_per_wave(N, d, dtype, wgs, blk, monkeypatch, tuning):
