@@ -169,7 +169,15 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
       *blk = block_tiles(t, env_blk, blk_dflt, 1);
       return (int)((p->n_tiles + t - 1) / t);
     };
-    p->splits = per_head(env_int("LINFUSION_WIDE_REDUCE_WGS", 2 * num_cu()), 4, "LINFUSION_WIDE_REDUCE_BLK", &p->blk_reduce);
+    // reduction workgroups per CU: two; from 768 MB of tensor traffic on, what fits below d = 160 measured faster
+    // (d = 128: three, 3-5 %; d = 96: three for fp16, four for bf16, 6-15 %), while smaller problems lose to the
+    // longer combine
+    int reduce_per_cu = 2;
+    {
+      const double bytes = 4.0 * (double)BH * (double)N * d * 2.0;
+      if (d <= 128 && bytes >= 768.0 * 1048576.0) reduce_per_cu = (d <= 96 && dtype == LINFUSION_DTYPE_BF16) ? 4 : 3;
+    }
+    p->splits = per_head(env_int("LINFUSION_WIDE_REDUCE_WGS", reduce_per_cu * num_cu()), 4, "LINFUSION_WIDE_REDUCE_BLK", &p->blk_reduce);
     // a head of one or two tiles: one workgroup sums them and writes the state itself (no partials, no combine
     // launch; from four tiles on a workgroup's tiles in sequence cost more than the launch saved)
     if (p->n_tiles <= env_int("LINFUSION_WIDE_ONE_SPLIT_TILES", 2)) {

@@ -97,6 +97,27 @@ def test_wave_apply_with_many_tiles_per_wave(N, d, dtype, wgs, blk, monkeypatch,
     parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"wave apply N={N} d={d} {dtype} wgs={wgs} blk={blk}")
 
 
+@pytest.mark.parametrize("N,d,dtype,per_cu", [(200003, 128, "f16", 3), (270001, 96, "bf16", 4), (270001, 96, "f16", 3),
+                                              (150001, 160, "f16", 2)])
+def test_large_wide_heads_every_row(N, d, dtype, per_cu):
+    """From 768 MB of tensor traffic on the widths below 160 run three or four reduction workgroups per CU instead
+    of two (more partials for the combine kernel, longer streams): every row of every head against the oracle at
+    such sizes, with a ragged last tile."""
+    B, H = 1, 4
+    print(f"large wide heads N={N} d={d} {dtype}", flush=True)
+    plan = lf.linfusion_attn_plan(B, H, N, d, wl.DTYPE_CODE[dtype])
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert plan["reduce_wgs_per_head"] * B * H <= per_cu * cus
+    assert plan["reduce_wgs_per_head"] * B * H > (per_cu - 1) * cus, plan
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=93, device="cpu")
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    out = torch.full_like(qd, float("nan"))
+    lf.linfusion_attn_fwd_ex(qd, kd, vd, out, 0, 1e-6, 0, _ws(B, H, N, d, dtype))
+    torch.cuda.synchronize()
+    worst = parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"large wide heads N={N} d={d} {dtype}")
+    print(f"  worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
+
+
 def test_wave_apply_is_chosen_at_every_wide_width():
     """fp16 operands for both storage types: (d + 2) x d of them fit one wave's registers up to d = 160."""
     names = {(d, t): lf.linfusion_attn_apply_kernel(1, 8, 4096, d, wl.DTYPE_CODE[t])
