@@ -230,13 +230,23 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
   long long share = 0;
   // state reduction (read-only stream): two workgroups per CU measured best -- fewer, longer
   // streams keep DRAM pages open
-  p->splits = per_head(env_int("LINFUSION_REDUCE_WGS", 2 * num_cu()), &share);
+  const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
+  const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
+  // From 768 MB of tensor traffic on, the narrow heads whose tiles carry more vector work than bytes run faster with
+  // more, shorter streams (sweeps at 2-4 M tokens of 8 heads: bf16 d = 8 / 16 / 24 / 32 / 40 -30 / -13 / -9 / -3.5 /
+  // -3.5 % per call with eight workgroups per CU, fp16 d = 8 / 16 / 24 -32 / -9 / -3 %, fp32 d = 8 -14 % with four;
+  // the other widths measured equal or slower that way, smaller problems equal).  Not for the entry point with the
+  // fixed scratch array, whose partials are sized for two.
+  int reduce_per_cu = 2;
+  if (!compact && bytes >= 768.0 * 1048576.0) {
+    if (dtype == LINFUSION_DTYPE_F32) reduce_per_cu = d <= 8 ? 4 : 2;
+    else if (d <= 24 || (dtype == LINFUSION_DTYPE_BF16 && d <= 40)) reduce_per_cu = 8;
+  }
+  p->splits = per_head(env_int("LINFUSION_REDUCE_WGS", reduce_per_cu * num_cu()), &share);
   p->blk_reduce = block_tiles(share, "LINFUSION_REDUCE_BLK", 16);
   // apply (read + write streams): more, smaller workgroups that sweep memory in one moving window.
   // Up to a few hundred MB of tensor traffic one resident round measured best (a second, partly filled
   // round costs more than its finer balance gains); beyond that eight workgroups per CU.
-  const size_t esz = dtype == LINFUSION_DTYPE_F32 ? 4 : 2;
-  const double bytes = 4.0 * (double)BH * (double)N * d * (double)esz;
   const bool one_round = bytes < (double)env_int("LINFUSION_APPLY_ONE_ROUND_MB", 768) * 1048576.0;
   const int apply_dflt = (one_round ? apply_wgs_per_cu(d, dtype) : 8) * num_cu();
   // Large 16-bit problems: the head's operands are packed once (pack_state16) and apply runs as many short-lived

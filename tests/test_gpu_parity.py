@@ -410,3 +410,19 @@ def test_fp32_split_reduction_is_the_default_for_narrow_heads_at_large_n():
     lf.linfusion_attn_fwd_strided(tm(q), tm(k), tm(v), o, 0, 1e-6, 0, ws)
     torch.cuda.synchronize()
     assert torch.equal(o.contiguous().view(torch.int32), out.view(torch.int32)), "token-major differs from contiguous"
+
+
+@pytest.mark.parametrize("B,H,N,d,dtype,per_cu", [(1, 4, 3200003, 8, "f16", 8), (1, 4, 1100001, 24, "bf16", 8),
+                                                  (1, 2, 3300001, 8, "f32", 4)])
+def test_narrow_heads_at_large_n_with_more_reduction_workgroups(B, H, N, d, dtype, per_cu):
+    """From 768 MB of tensor traffic on the narrowest heads (and bf16 up to 40 channels, which the full-size bf16 test
+    covers) are reduced by eight workgroups per CU instead of two (four in fp32): every row of every head of such
+    shapes, with a ragged last tile, against the oracle."""
+    print(f"narrow heads at large N: B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    plan = lf.linfusion_attn_plan(B, H, N, d, wl.DTYPE_CODE[dtype])
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert (per_cu - 1) * cus < plan["reduce_wgs_per_head"] * B * H <= per_cu * cus, plan
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=94, device="cpu")
+    out = _run(q.cuda(), k.cuda(), v.cuda())
+    worst = parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"narrow heads at large N d={d} {dtype}")
+    print(f"  worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
