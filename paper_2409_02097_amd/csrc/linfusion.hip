@@ -302,7 +302,10 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     };
     // (the defaults are in 256-thread units: a workgroup of eight waves counts twice)
     const int unit = p->gwaves / lf::kWavesPerWG;
-    p->gsplits = per_group(env_int("LINFUSION_GROUP_REDUCE_WGS", 2 * num_cu()) / unit, &share);
+    // (the widths and sizes that take more reduction workgroups per CU above do here as well: four, eight at d = 8;
+    // token-major bf16 8 x 40 at 2 M tokens 0.999 -> 0.971 ms, d = 24 0.616 -> 0.556, fp16 d = 8 0.577 -> 0.407)
+    const int greduce_per_cu = reduce_per_cu == 8 ? (d <= 8 ? 8 : 4) : 2;
+    p->gsplits = per_group(env_int("LINFUSION_GROUP_REDUCE_WGS", greduce_per_cu * num_cu()) / unit, &share);
     p->gblk_reduce = block_tiles(share, "LINFUSION_GROUP_REDUCE_BLK", 2, 1);
     // up to a few hundred MB one workgroup of eight waves (two of four) per CU; large problems as many short-lived
     // workgroups of about `kGroupTilesPerWG` tiles each (the hardware deals them out in order: one narrow moving

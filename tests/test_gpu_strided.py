@@ -186,3 +186,20 @@ def test_token_major_fp16_inputs_far_below_zero(case, H, d):
         torch.cuda.synchronize()
         worst = parity.check_all(view(ot).contiguous(), q, k, v, "f16", 0, eps, True, f"token-major {case} H={H} d={d} eps={eps}")
         print(f"token-major {case} H={H} d={d} eps={eps}: worst max-norm ratio {worst[0]:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("N,d,dtype", [(530003, 24, "bf16"), (1600003, 8, "f16")])
+def test_token_major_narrow_heads_at_large_n(N, d, dtype):
+    """From 768 MB of tensor traffic on the row-piece reduction of these widths runs four workgroups per CU (eight at
+    d = 8) instead of two: every row of every head of a token-major tensor of that size against the oracle."""
+    B, H = 1, 8
+    print(f"token-major large B={B} H={H} N={N} d={d} {dtype}", flush=True)
+    q, k, v = wl.make_qkv(B, H, N, d, dtype, idx=95, device="cpu")
+    tm = lambda t: t.permute(0, 2, 1, 3).contiguous().cuda()
+    qt, kt, vt = tm(q), tm(k), tm(v)
+    ot = torch.full_like(qt, float("nan"))
+    view = lambda t: t.permute(0, 2, 1, 3)
+    lf.linfusion_attn_fwd_strided(view(qt), view(kt), view(vt), view(ot), 0, 1e-6, 0, _ws(B, H, N, d, dtype, qt.device))
+    torch.cuda.synchronize()
+    worst = parity.check_all(view(ot).contiguous(), q, k, v, dtype, 0, 1e-6, True, f"token-major large N={N} d={d} {dtype}")
+    print(f"  worst max-norm ratio {worst[0]:.2e}, rel L2 {worst[1]:.2e}", flush=True)
