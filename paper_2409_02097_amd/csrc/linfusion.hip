@@ -189,7 +189,10 @@ int make_plan(int B, int H, long long N, int d, int dtype, unsigned flags, Plan*
     p->wave_apply = lfw::wave_apply_supported(d, dtype) && env_int("LINFUSION_WIDE_WAVE_APPLY", 1) == 1;   // 2: never
     if (p->wave_apply) {
       const long long max_a = (p->n_tiles + lf::kWavesPerWG - 1) / lf::kWavesPerWG;   // every wave gets a tile
-      long long s = env_int("LINFUSION_WIDE_APPLY_WGS", num_cu()) / BH;
+      // (d = 96 leaves room for a second workgroup per CU: at 2^18 tokens of 8 heads apply 166 -> 157 us; measured
+      // slower at d = 128 and 160)
+      const bool two_per_cu = d <= 96 && 4.0 * (double)BH * (double)N * d * 2.0 >= 768.0 * 1048576.0;
+      long long s = env_int("LINFUSION_WIDE_APPLY_WGS", (two_per_cu ? 2 : 1) * num_cu()) / BH;
       if (s > max_a) s = max_a;
       if (s < 1) s = 1;
       const long long t = (p->n_tiles + s - 1) / s;
