@@ -412,8 +412,7 @@ def test_fp32_split_reduction_is_the_default_for_narrow_heads_at_large_n():
     assert torch.equal(o.contiguous().view(torch.int32), out.view(torch.int32)), "token-major differs from contiguous"
 
 
-@pytest.mark.parametrize("B,H,N,d,dtype,per_cu", [(1, 4, 3200003, 8, "f16", 8), (1, 4, 1100001, 24, "bf16", 8),
-                                                  (1, 2, 3300001, 8, "f32", 4)])
+@pytest.mark.parametrize("B,H,N,d,dtype,per_cu", [(1, 4, 3200003, 8, "f16", 8), (1, 2, 3300001, 8, "f32", 4)])
 def test_narrow_heads_at_large_n_with_more_reduction_workgroups(B, H, N, d, dtype, per_cu):
     """From 768 MB of tensor traffic on the narrowest heads (and bf16 up to 40 channels, which the full-size bf16 test
     covers) are reduced by eight workgroups per CU instead of two (four in fp32): every row of every head of such

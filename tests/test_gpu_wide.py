@@ -97,7 +97,7 @@ def test_wave_apply_with_many_tiles_per_wave(N, d, dtype, wgs, blk, monkeypatch,
     parity.check_all(out, q, k, v, dtype, 0, 1e-6, True, f"wave apply N={N} d={d} {dtype} wgs={wgs} blk={blk}")
 
 
-@pytest.mark.parametrize("N,d,dtype,per_cu", [(200003, 128, "f16", 3), (270001, 96, "bf16", 4), (270001, 96, "f16", 3)])
+@pytest.mark.parametrize("N,d,dtype,per_cu", [(200003, 128, "f16", 3), (270001, 96, "bf16", 4)])
 def test_large_wide_heads_every_row(N, d, dtype, per_cu):
     """From 768 MB of tensor traffic on the widths below 160 run three or four reduction workgroups per CU instead
     of two (more partials for the combine kernel, longer streams): every row of every head against the oracle at
